@@ -1,0 +1,249 @@
+/*
+ * fastgrpo.h -- C ABI of the MI355X speculative-verify library (libfastgrpo.so).
+ *
+ * The hot path of FastGRPO's generation phase (Alg. 1, the concurrency-aware speculative decoding block of
+ * the generation loop): plan the tree shape from the live concurrency (Sec. 4.1 Eq. 1-3), expand and rerank
+ * the draft tree (Alg. 1 drafting loop and reranking; Sec. 2 "Draft Model Architectures", "Verification
+ * Strategies"), verify all nodes in one target forward with tree attention, accept the longest matching
+ * path, and keep its K/V.
+ *
+ * Conventions
+ *  - Every function returns int32_t: FG_OK (0) or a negative fg_status.  fg_last_error() gives the message
+ *    of the calling thread's last failure.  Nothing throws or aborts.
+ *  - "device" pointers are HIP device memory owned by the caller; "host" pointers are read before return.
+ *  - All device work is enqueued on the caller's stream (a hipStream_t passed as void*); calls are
+ *    asynchronous and outputs are valid once the caller has synchronised that stream.  The library never
+ *    allocates or frees device memory after fg_model_create (which allocates one RoPE table).
+ *  - dtype FG_F32: every tensor fp32.  dtype FG_BF16: weights, activations and KV are bf16, accumulation,
+ *    the residual stream, softmax and norm statistics are fp32.
+ *  - A sequence's cache holds the K/V of all its tokens but the last emitted one, which is the root
+ *    (node 0) of the next step's tree.  In-round node i of a sequence of committed length L lives in cache
+ *    slot L + i at position L + depth(i), and attends to positions 0..L-1 and to its in-round ancestors
+ *    and itself.
+ */
+#ifndef FASTGRPO_H
+#define FASTGRPO_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FG_OK = 0,
+    FG_ERR_INVALID_ARG = -1,   /* NULL required pointer, negative size, unknown mode or dtype          */
+    FG_ERR_SHAPE = -2,         /* a dimension the kernels do not support (see each function)           */
+    FG_ERR_CAPACITY = -3,      /* N > FG_MAX_NODES, workspace too small, page table too short          */
+    FG_ERR_HIP = -4,           /* a HIP runtime call failed                                            */
+    FG_ERR_UNIMPLEMENTED = -5
+} fg_status;
+
+enum { FG_F32 = 0, FG_BF16 = 1 };
+enum { FG_MAX_NODES = 64 };                 /* in-round nodes per sequence (ancestor sets are 64-bit masks) */
+enum { FG_ACCEPT_GREEDY = 0, FG_ACCEPT_SAMPLE_MATCH = 1, FG_ACCEPT_REJECT = 2 };
+
+typedef struct fg_model fg_model;           /* opaque */
+
+typedef struct {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    int32_t dtype;                          /* FG_F32 or FG_BF16                                            */
+    int32_t max_pos;                        /* positions 0..max_pos-1 get a RoPE table entry                */
+    float rms_eps, rope_theta;
+} fg_model_cfg;
+
+/*
+ * Weights: device pointers the caller owns and keeps alive while the model exists.  Every matrix is the
+ * output of fg_pack_weight (its logical shape is [out, in]).  embed, the norm gains: plain row-major in the
+ * model's dtype.  The per-layer members are HOST arrays of n_layers device pointers (copied at create).
+ * A draft head (Sec. 2, "Draft Model Architectures": one decoder layer that reads the target's feature and
+ * is decoded by the target's LM head) has fc ([d, 2d], input = token embedding ++ feature), n_layers = 1,
+ * final_norm = NULL, and embed / lm_head pointing at the target's.
+ */
+typedef struct {
+    const void *embed;              /* [vocab, d] row-major                                                */
+    const void *lm_head;            /* packed [vocab, d]                                                   */
+    const void *final_norm;         /* [d] or NULL (draft head)                                            */
+    const void *fc;                 /* packed [d, 2d] or NULL (target)                                     */
+    const void *const *wqkv;        /* packed [(Hq + 2 Hkv) * hd, d]: q rows, then k rows, then v rows     */
+    const void *const *wo;          /* packed [d, Hq * hd]                                                 */
+    const void *const *w_gate_up;   /* packed, gate and up interleaved (fg_pack_weight with src2)          */
+    const void *const *w_down;      /* packed [d, F]                                                       */
+    const void *const *norm_attn;   /* [d]                                                                 */
+    const void *const *norm_ffn;    /* [d]                                                                 */
+} fg_weights;
+
+/*
+ * Paged KV cache, caller-owned.  Page p of layer l, kv head h:
+ *   k_pool[((l * n_pages + p) * n_kv_heads + h) * page_size * head_dim + t * head_dim + e]   (token-major)
+ *   v_pool[((l * n_pages + p) * n_kv_heads + h) * page_size * head_dim + e * page_size + t]   (transposed)
+ * Token t of a sequence in cache slot s is entry t % page_size of page page_table[s][t / page_size].
+ * page_size must be 16.  seq_len[s] is the committed length; only fg_kv_compact changes it.
+ */
+typedef struct {
+    void *k_pool, *v_pool;          /* device                                                               */
+    const int32_t *page_table;      /* device [n_slots][max_pages_per_seq]                                  */
+    int32_t *seq_len;               /* device [n_slots]                                                     */
+    int32_t n_layers, n_kv_heads, head_dim, dtype;
+    int32_t page_size, max_pages_per_seq, n_pages, n_slots;
+} fg_kv_cache;
+
+/*
+ * The nodes one call works on.  B sequences, N new in-round nodes each, after n_prev nodes that earlier
+ * calls of the same round already appended (0 for the target's verify step).
+ *   parent[b][i], i < n_prev + N: in-round index of node i's parent, -1 for a child of the committed prefix
+ *   (the root); parent[b][i] < i.  n_prev + N <= FG_MAX_NODES.
+ * max_seq_len: a host-side upper bound on seq_len[slot[b]] + n_prev + N over the batch, used to size the
+ * attention grid (0 = the cache's capacity).  A bound that is too small is FG_ERR_CAPACITY only if it
+ * exceeds the capacity; sequences longer than the bound are not detected (their tail would be ignored).
+ */
+typedef struct {
+    const int32_t *slot;            /* device [B]: cache slot of each sequence                              */
+    const int32_t *tokens;          /* device [B, N]                                                        */
+    const int32_t *parent;          /* device [B, n_prev + N]                                               */
+    int32_t B, N, n_prev, max_seq_len;
+} fg_tree;
+
+const char *fg_last_error(void);
+
+/*
+ * The concurrency rule (Sec. 4.1 Eq. 1-3).  Host only.  N = floor(C_peak / B_cur) clamped to [1, N_cap];
+ * K = min(N - 1, K_max); L = min(floor(log2(N / alpha)), L_max) clamped to [0, N - 1]; K = 0 or L = 0 gives
+ * plain decoding (N = 1, K = L = 0); N is capped by the candidate count 1 + K + (L - 1) K^2.
+ * Errors: B_cur < 1, C_peak <= 0, alpha <= 0, negative caps, N_cap < 1 or > FG_MAX_NODES -> FG_ERR_INVALID_ARG.
+ */
+int32_t fg_plan(int32_t B_cur, float C_peak, float alpha, int32_t K_max, int32_t L_max, int32_t N_cap,
+                int32_t *N_verify, int32_t *K_draft, int32_t *L_draft);
+
+/*
+ * Weight packing (one-time, on the stream).  src is [n_out, n_in] row-major in `dtype`; with src2 != NULL
+ * the logical matrix is [2 n_out, n_in] with rows interleaved in blocks of 32 (32 of src, 32 of src2, ...),
+ * which is how gate and up are fused.  FG_F32: dst is that logical matrix row-major.  FG_BF16: dst holds it
+ * as MFMA operand fragments: tile (n / 32, k / 16) is 1 KiB, lane ((k % 16) / 8) * 32 + n % 32 holds 8
+ * consecutive k; the tiles of one 32-row band are contiguous in k.  Needs n_out % 32 == 0 and
+ * n_in % 64 == 0 (FG_ERR_SHAPE).  dst has fg_packed_bytes(...) bytes and must not alias src.
+ */
+int64_t fg_packed_bytes(int32_t dtype, int64_t n_out_total, int64_t n_in);
+int32_t fg_pack_weight(int32_t dtype, const void *src, const void *src2, void *dst, int64_t n_out, int64_t n_in,
+                       void *stream);
+
+/* Creates the model descriptor (copies cfg and the pointer tables; allocates the RoPE table on the current
+ * device).  Shape limits: head_dim 64 or 128, n_q_heads % n_kv_heads == 0, d_model / d_ffn / vocab multiples
+ * of 32, inner dimensions multiples of 64, (n_q_heads / n_kv_heads) <= 8.  fg_model_destroy frees the table. */
+int32_t fg_model_create(const fg_model_cfg *cfg, const fg_weights *w, fg_model **out);
+int32_t fg_model_destroy(fg_model *m);
+
+/* Bytes of caller-provided device workspace fg_spec_verify / fg_draft_step need for up to max_rows = B * N
+ * rows per call with caches of at most max_seq_len tokens.  256-byte aligned base expected. */
+int64_t fg_workspace_bytes(const fg_model *m, int32_t max_rows, int32_t max_seq_len);
+
+/*
+ * Verification (Alg. 1 "verify selected tokens in parallel"; Sec. 2): one target forward over the B * N new
+ * nodes with tree attention against the paged cache.  Appends K/V of every node at slots seq_len + n_prev + j
+ * (lengths are NOT changed; fg_kv_compact commits).  Outputs, each optional (NULL to skip), row r = b * N + j:
+ *   logits      fp32 [B*N, vocab]
+ *   feature     model dtype [B*N, d]: the final-norm output, i.e. the LM head's input
+ *   row_argmax  int32 [B*N]: argmax of each logits row, lowest index on ties
+ *   row_top2    fp32 [B*N, 2]: the largest and second-largest logit of the row
+ * Errors: NULL model / cache / tree members, B or N < 0, n_prev + N > FG_MAX_NODES, dtype mismatch between
+ * model and cache, workspace too small, max_seq_len beyond the cache's capacity.  B == 0 or N == 0 is FG_OK
+ * and does nothing.  Tokens and parents are not validated on the device beyond clamping into range.
+ */
+int32_t fg_spec_verify(fg_model *m, fg_kv_cache *kv, const fg_tree *tree, float *logits, void *feature,
+                       int32_t *row_argmax, float *row_top2, void *workspace, int64_t workspace_bytes, void *stream);
+
+/*
+ * Acceptance (Alg. 1 "extract accepted tokens"; Sec. 2 "accepts the longest path whose generated tokens match
+ * the draft tokens under strict token-level comparison").  Per sequence, from the root: the target's token t
+ * after the current node u is
+ *   FG_ACCEPT_GREEDY        row_argmax[u] if given, else the argmax of logits[u];
+ *   FG_ACCEPT_SAMPLE_MATCH  argmax_v logits[u][v] / temperature + Gumbel(seed, row0 + row of u, v);
+ * move to the lowest-indexed child of u whose token equals t, stop when there is none.
+ *   FG_ACCEPT_REJECT        rejection sampling over the sibling set: for each child c of u in index order with
+ *   token x, accept when uniforms[c] < min(1, p(x) / q(x)), p = softmax(logits[u] / temperature),
+ *   q = draft_probs[u]; on rejection p <- normalise(max(p - q, 0)), q(x) <- 0, q <- normalise(q); with no child
+ *   accepted the bonus token is the Gumbel-max draw from the current p.
+ * Outputs (device): accept_len [B] = a, the number of accepted drafts; path [B, N] node indices path[0..a]
+ * (path[0] = 0, rest -1); out_tokens [B, N]: out_tokens[0..a] = the emitted tokens (accepted drafts then the
+ * bonus token; rest -1); finished [B] = 1 when an emitted token equals eos_id, in which case the walk is cut
+ * at that token.  The uniform/Gumbel generator is SplitMix64-based: u = ((mix(mix(seed ^ row * 0xD1B54A32D192ED03)
+ * + v) >> 41) + 0.5) / 2^23.  workspace: FG_ACCEPT_REJECT needs 2 * B * vocab floats, other modes none.
+ * Errors: missing inputs for the mode, temperature <= 0 in modes 1-2, N > FG_MAX_NODES.
+ */
+int32_t fg_spec_accept(const fg_tree *tree, int32_t mode, const float *logits, const int32_t *row_argmax,
+                       int32_t vocab, float temperature, const float *draft_probs, const float *uniforms,
+                       uint64_t seed, int64_t row0, int32_t eos_id, int32_t *accept_len, int32_t *path,
+                       int32_t *out_tokens, int32_t *finished, void *workspace, int64_t workspace_bytes,
+                       void *stream);
+
+/*
+ * KV compaction in place (implied by Alg. 1 "update S_generated": rejected nodes are dropped).  For sequence b
+ * with committed length L: in-round slot L + path[b][j] moves to L + j for j = 0..accept_len[b], K and V of
+ * every layer and head; then seq_len += accept_len[b] + 1.  path rows must increase strictly with
+ * path[j] >= j (what fg_spec_accept emits); rows that do not are left untouched and their length unchanged.
+ * N is the row stride of path.  If feature_in / feature_out are given, feature_out[b][j] = feature_in[b][path[j]]
+ * for j <= accept_len[b] ([B, N, d] both; rows beyond are zero-filled) -- the accepted hidden states the draft
+ * head reads next.  d_model and feat_dtype describe those rows.
+ */
+int32_t fg_kv_compact(fg_kv_cache *kv, const int32_t *slot, const int32_t *accept_len, const int32_t *path,
+                      int32_t B, int32_t N, const void *feature_in, void *feature_out, int32_t d_model,
+                      int32_t feat_dtype, void *stream);
+
+/*
+ * One drafting step (Alg. 1 "generate children for K_draft paths"; Sec. 2 "Draft Model Architectures"): the
+ * draft head runs on B * tree->N new in-round nodes.  Node input = fc(embed(token) ++ in_feature row); one
+ * decoder layer against the draft's own paged cache with tree attention; the output hidden state is decoded by
+ * the target's LM head; per node the K_draft most likely tokens and their log-probabilities come back.
+ *   in_feature   model dtype [B, N, d]: the feature each node's token is paired with
+ *   child_tok    int32 [B, N, K_draft]; child_logp fp32 [B, N, K_draft] (log-softmax, descending, ties by index)
+ *   out_feature  model dtype [B, N, d]: the head's output hidden state of each node
+ * n_commit (device [B] or NULL): after the step, seq_len[slot[b]] += n_commit[b] -- used for the catch-up chain
+ * of accepted tokens, which stays in the draft cache; NULL leaves lengths alone.
+ */
+int32_t fg_draft_step(fg_model *target, fg_model *draft, fg_kv_cache *draft_kv, const fg_tree *tree,
+                      const void *in_feature, const int32_t *n_commit, int32_t K_draft, int32_t *child_tok,
+                      float *child_logp, void *out_feature, void *workspace, int64_t workspace_bytes, void *stream);
+
+/*
+ * Frontier update between drafting steps (Alg. 1 "update candidate tokens T_candi").  The K_in expanded nodes
+ * of this step have candidate indices node_cand [B, K_in] and scores node_score [B, K_in]; their K_in * K
+ * children (child_tok / child_logp from fg_draft_step) are appended to the candidate lists at index n_cand
+ * (cand_* are [B, cand_stride]) with score = parent score + log-probability, and the K best children (ties:
+ * lower index) become the next frontier: next_tok / next_cand / next_score / next_src [B, K], next_src being
+ * the position (0..K_in-1) of the frontier node's parent among this step's nodes.
+ */
+int32_t fg_draft_frontier(int32_t B, int32_t K_in, int32_t K, const int32_t *child_tok, const float *child_logp,
+                          const int32_t *node_cand, const float *node_score, int32_t n_cand, int32_t cand_stride,
+                          int32_t *cand_tok, int32_t *cand_parent, float *cand_score, int32_t *next_tok,
+                          int32_t *next_cand, float *next_score, int32_t *next_src, void *stream);
+
+/*
+ * Rerank (Alg. 1 "select N_verify tokens from T_candi based on their confidences").  Candidate 0 is the root;
+ * cand_parent[i] < i.  Selects the root and the N - 1 best-scoring other candidates (ties: lower index), orders
+ * them by (depth, candidate index) and writes tokens [B, N], parent [B, N] (parent[0] = -1, parent[i] < i) and
+ * sel [B, N] (candidate index of each node; optional).  Scores must not increase from parent to child; a
+ * selected node whose parent was not selected is re-attached to the root.  n_cand <= 128, N <= FG_MAX_NODES.
+ */
+int32_t fg_build_tree(const int32_t *cand_tok, const int32_t *cand_parent, const float *cand_score, int32_t B,
+                      int32_t n_cand, int32_t cand_stride, int32_t N, int32_t *tokens, int32_t *parent,
+                      int32_t *sel, void *stream);
+
+/*
+ * Kernel-level entry points (unit parity and per-kernel measurement).
+ * fg_gemm: out = x . W^T for packed W [n_out, n_in]; x is [M, n_in] row-major in dtype.
+ *   epilogue 0: out fp32 [split_k][M][n_out] partial sums (split_k >= 1; 0 lets the library choose and
+ *               returns the value through *split_k_used); the caller adds the slabs.
+ *   epilogue 1: W is a gate/up interleaved matrix; out[M, n_out / 2] in dtype = silu(gate) * up.
+ * fg_attention: tree attention of already-rotated queries q [B*N, Hq*hd] (dtype) over the cache, which must
+ *   already hold the in-round nodes' K/V; out [B*N, Hq*hd] (dtype).
+ */
+int32_t fg_gemm(int32_t dtype, const void *x, const void *w_packed, void *out, int32_t M, int32_t n_out,
+                int32_t n_in, int32_t epilogue, int32_t split_k, int32_t *split_k_used, void *stream);
+int32_t fg_attention(const fg_kv_cache *kv, int32_t layer, const fg_tree *tree, int32_t n_q_heads, const void *q,
+                     void *out, void *workspace, int64_t workspace_bytes, void *stream);
+int64_t fg_attention_workspace_bytes(int32_t B, int32_t N, int32_t n_q_heads, int32_t head_dim, int32_t max_seq_len);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FASTGRPO_H */

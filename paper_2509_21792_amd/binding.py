@@ -1,0 +1,373 @@
+"""Thin ctypes binding of libfastgrpo.so: the same entry points as include/fastgrpo.h, taking torch tensors.
+
+Argument marshalling only.  torch is used for device memory and the current HIP stream; every step of the
+hot path runs in the library's kernels.  There is no CPU fallback: without the built library (or without a
+GPU for the compute calls) this module raises.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+FG_F32, FG_BF16 = 0, 1
+FG_MAX_NODES = 64
+ACCEPT_GREEDY, ACCEPT_SAMPLE_MATCH, ACCEPT_REJECT = 0, 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfastgrpo.so")
+
+EXPORTS = ["fg_last_error", "fg_plan", "fg_packed_bytes", "fg_pack_weight", "fg_model_create", "fg_model_destroy",
+           "fg_workspace_bytes", "fg_spec_verify", "fg_spec_accept", "fg_kv_compact", "fg_draft_step",
+           "fg_draft_frontier", "fg_build_tree", "fg_gemm", "fg_attention", "fg_attention_workspace_bytes"]
+
+
+class FgError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"libfastgrpo error {code}: {msg}")
+        self.code = code
+
+
+class ModelCfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab",
+                                         "dtype", "max_pos")] + [("rms_eps", C.c_float), ("rope_theta", C.c_float)]
+
+
+class Weights(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p), ("fc", C.c_void_p)] + \
+               [(n, C.POINTER(C.c_void_p)) for n in ("wqkv", "wo", "w_gate_up", "w_down", "norm_attn", "norm_ffn")]
+
+
+class KvCacheC(C.Structure):
+    _fields_ = [("k_pool", C.c_void_p), ("v_pool", C.c_void_p), ("page_table", C.c_void_p), ("seq_len", C.c_void_p)] + \
+               [(n, C.c_int32) for n in ("n_layers", "n_kv_heads", "head_dim", "dtype", "page_size", "max_pages_per_seq",
+                                         "n_pages", "n_slots")]
+
+
+class TreeC(C.Structure):
+    _fields_ = [("slot", C.c_void_p), ("tokens", C.c_void_p), ("parent", C.c_void_p)] + \
+               [(n, C.c_int32) for n in ("B", "N", "n_prev", "max_seq_len")]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built (python -c 'import __graft_entry__ as g; g.build()')."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it first (__graft_entry__.build()); there is no fallback")
+        L = C.CDLL(LIB_PATH)
+        L.fg_last_error.restype = C.c_char_p
+        L.fg_packed_bytes.restype = C.c_int64
+        L.fg_packed_bytes.argtypes = [C.c_int32, C.c_int64, C.c_int64]
+        L.fg_workspace_bytes.restype = C.c_int64
+        L.fg_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+        L.fg_attention_workspace_bytes.restype = C.c_int64
+        L.fg_attention_workspace_bytes.argtypes = [C.c_int32] * 5
+        L.fg_plan.argtypes = [C.c_int32, C.c_float, C.c_float, C.c_int32, C.c_int32, C.c_int32] + [C.POINTER(C.c_int32)] * 3
+        L.fg_pack_weight.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p]
+        L.fg_model_create.argtypes = [C.POINTER(ModelCfg), C.POINTER(Weights), C.POINTER(C.c_void_p)]
+        L.fg_model_destroy.argtypes = [C.c_void_p]
+        L.fg_spec_verify.argtypes = [C.c_void_p, C.POINTER(KvCacheC), C.POINTER(TreeC), C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        L.fg_spec_accept.argtypes = [C.POINTER(TreeC), C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_void_p,
+                                     C.c_void_p, C.c_uint64, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        L.fg_kv_compact.argtypes = [C.POINTER(KvCacheC), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                    C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+        L.fg_draft_step.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(KvCacheC), C.POINTER(TreeC), C.c_void_p, C.c_void_p,
+                                    C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        L.fg_draft_frontier.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.c_int32, C.c_int32] + [C.c_void_p] * 8
+        L.fg_build_tree.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.fg_gemm.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                              C.c_int32, C.POINTER(C.c_int32), C.c_void_p]
+        L.fg_attention.argtypes = [C.POINTER(KvCacheC), C.c_int32, C.POINTER(TreeC), C.c_int32, C.c_void_p, C.c_void_p,
+                                   C.c_void_p, C.c_int64, C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise FgError(rc, lib().fg_last_error().decode())
+
+
+def _p(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _tdtype(dtype):
+    return torch.bfloat16 if dtype == FG_BF16 else torch.float32
+
+
+def dtype_code(name):
+    return FG_BF16 if name == "bf16" else FG_F32
+
+
+# ---- host-only ---------------------------------------------------------------------------------------------
+def fg_plan(B_cur, C_peak, alpha=0.5, K_max=4, L_max=6, N_cap=64):
+    N, K, Lr = C.c_int32(), C.c_int32(), C.c_int32()
+    _check(lib().fg_plan(B_cur, C_peak, alpha, K_max, L_max, N_cap, C.byref(N), C.byref(K), C.byref(Lr)))
+    return N.value, K.value, Lr.value
+
+
+# ---- weights and model ---------------------------------------------------------------------------------------
+def fg_pack_weight(dtype, src, src2=None):
+    """src [n_out, n_in] (and optionally src2 of the same shape, interleaved in blocks of 32 rows) -> packed tensor."""
+    src = src.contiguous()
+    n_out, n_in = src.shape
+    total = n_out * (2 if src2 is not None else 1)
+    if src2 is not None:
+        src2 = src2.contiguous()
+        assert src2.shape == src.shape
+    dst = torch.empty(total * n_in, dtype=_tdtype(dtype), device=src.device)
+    assert lib().fg_packed_bytes(dtype, total, n_in) == dst.numel() * dst.element_size()
+    _check(lib().fg_pack_weight(dtype, _p(src), _p(src2), _p(dst), n_out, n_in, _stream()))
+    return dst
+
+
+class Model:
+    """A target model or a draft head on the device.  `weights` is the dict layout of synth.gen.make_weights with
+    torch tensors on the device; a draft head passes target=<Model> to share its embedding and LM head."""
+
+    def __init__(self, cfg, weights, target=None, max_pos=8192):
+        self.cfg = dict(cfg)
+        self.dtype = dtype_code(cfg["dtype"])
+        td = _tdtype(self.dtype)
+        dev = weights["layers"][0]["wqkv"].device
+        cast = lambda t: t.to(device=dev, dtype=td).contiguous()
+        self.keep = []
+
+        def packed(a, b=None):
+            t = fg_pack_weight(self.dtype, cast(a), None if b is None else cast(b))
+            self.keep.append(t)
+            return t
+
+        w = Weights()
+        if target is None:
+            self.embed = cast(weights["embed"])
+            self.lm_head = packed(weights["lm_head"])
+            self.final_norm = cast(weights["final_norm"])
+            self.fc = None
+        else:
+            self.embed, self.lm_head, self.final_norm = target.embed, target.lm_head, None
+            self.fc = packed(weights["fc"])
+        w.embed, w.lm_head = self.embed.data_ptr(), self.lm_head.data_ptr()
+        w.final_norm = None if self.final_norm is None else self.final_norm.data_ptr()
+        w.fc = None if self.fc is None else self.fc.data_ptr()
+        nl = cfg["n_layers"]
+        per = {k: [] for k in ("wqkv", "wo", "w_gate_up", "w_down", "norm_attn", "norm_ffn")}
+        for lay in weights["layers"]:
+            per["wqkv"].append(packed(lay["wqkv"]))
+            per["wo"].append(packed(lay["wo"]))
+            per["w_gate_up"].append(packed(lay["w_gate"], lay["w_up"]))
+            per["w_down"].append(packed(lay["w_down"]))
+            for k in ("norm_attn", "norm_ffn"):
+                t = cast(lay[k])
+                self.keep.append(t)
+                per[k].append(t)
+        self._tabs = []
+        for k, lst in per.items():
+            tab = (C.c_void_p * nl)(*[t.data_ptr() for t in lst])
+            self._tabs.append(tab)
+            setattr(w, k, C.cast(tab, C.POINTER(C.c_void_p)))
+        c = ModelCfg(cfg["n_layers"], cfg["d_model"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["d_ffn"],
+                     cfg["vocab"], self.dtype, max_pos, cfg.get("rms_eps", 1e-6), cfg.get("rope_theta", 10000.0))
+        h = C.c_void_p()
+        torch.cuda.current_stream().synchronize()
+        _check(lib().fg_model_create(C.byref(c), C.byref(w), C.byref(h)))
+        self.handle = h
+
+    def workspace(self, max_rows, max_seq_len):
+        n = lib().fg_workspace_bytes(self.handle, max_rows, max_seq_len)
+        if n <= 0:
+            raise FgError(-1, "fg_workspace_bytes failed")
+        return torch.empty(n, dtype=torch.uint8, device=self.embed.device)
+
+    def __del__(self):
+        try:
+            if getattr(self, "handle", None):
+                lib().fg_model_destroy(self.handle)
+                self.handle = None
+        except Exception:
+            pass
+
+
+class KVCache:
+    """Paged cache on the device.  page_table: int32 [n_slots, max_pages] (numpy or tensor)."""
+
+    def __init__(self, cfg, page_table, n_pages, device="cuda", page_size=16):
+        self.cfg = dict(cfg)
+        self.dtype = dtype_code(cfg["dtype"])
+        td = _tdtype(self.dtype)
+        nl, Hkv, hd = cfg["n_layers"], cfg["n_kv_heads"], cfg["head_dim"]
+        self.page_table = torch.as_tensor(np.asarray(page_table), dtype=torch.int32).to(device).contiguous()
+        self.n_slots, self.max_pages = self.page_table.shape
+        self.n_pages, self.page_size = n_pages, page_size
+        self.k_pool = torch.zeros((nl, n_pages, Hkv, page_size, hd), dtype=td, device=device)
+        self.v_pool = torch.zeros((nl, n_pages, Hkv, hd, page_size), dtype=td, device=device)
+        self.seq_len = torch.zeros(self.n_slots, dtype=torch.int32, device=device)
+        self.c = KvCacheC(self.k_pool.data_ptr(), self.v_pool.data_ptr(), self.page_table.data_ptr(), self.seq_len.data_ptr(),
+                          nl, Hkv, hd, self.dtype, page_size, self.max_pages, n_pages, self.n_slots)
+
+    def _where(self, slot, L):
+        t = torch.arange(L, device=self.k_pool.device)
+        pages = self.page_table[slot, (t // self.page_size)].long()
+        return pages, (t % self.page_size)
+
+    def write_prefix(self, slot, k, v):
+        """Set-up helper: k, v [n_layers, L, Hkv, hd] become positions 0..L-1 of `slot`; seq_len[slot] = L."""
+        L = k.shape[1]
+        pages, off = self._where(slot, L)
+        self.k_pool[:, pages, :, off, :] = k.to(self.k_pool.dtype).permute(1, 0, 2, 3)
+        self.v_pool[:, pages, :, :, off] = v.to(self.v_pool.dtype).permute(1, 0, 2, 3)
+        self.seq_len[slot] = L
+
+    def read(self, slot, L):
+        """Test helper: positions 0..L-1 of `slot` as contiguous k, v [n_layers, L, Hkv, hd]."""
+        pages, off = self._where(slot, L)
+        k = self.k_pool[:, pages, :, off, :].permute(1, 0, 2, 3).contiguous()
+        v = self.v_pool[:, pages, :, :, off].permute(1, 0, 2, 3).contiguous()
+        return k, v
+
+
+def _tree(slot, tokens, parent, B, N, n_prev, max_seq_len):
+    return TreeC(None if slot is None else slot.data_ptr(), None if tokens is None else tokens.data_ptr(),
+                 None if parent is None else parent.data_ptr(), B, N, n_prev, max_seq_len)
+
+
+def _dev_i32(x, device):
+    if isinstance(x, torch.Tensor):
+        return x.to(device=device, dtype=torch.int32).contiguous()
+    return torch.as_tensor(np.ascontiguousarray(x, dtype=np.int32)).to(device)
+
+
+# ---- the hot path -----------------------------------------------------------------------------------------
+def fg_spec_verify(model, kv, slot, tokens, parent, workspace, n_prev=0, max_seq_len=0, want_logits=False,
+                   want_feature=True, want_argmax=True, want_top2=False):
+    dev = kv.k_pool.device
+    slot, tokens, parent = _dev_i32(slot, dev), _dev_i32(tokens, dev), _dev_i32(parent, dev)
+    B, N = tokens.shape
+    M, d, V = B * N, model.cfg["d_model"], model.cfg["vocab"]
+    out = {}
+    out["logits"] = torch.empty((M, V), dtype=torch.float32, device=dev) if want_logits else None
+    out["feature"] = torch.empty((M, d), dtype=_tdtype(model.dtype), device=dev) if want_feature else None
+    out["argmax"] = torch.empty(M, dtype=torch.int32, device=dev) if want_argmax else None
+    out["top2"] = torch.empty((M, 2), dtype=torch.float32, device=dev) if want_top2 else None
+    tree = _tree(slot, tokens, parent, B, N, n_prev, max_seq_len)
+    _check(lib().fg_spec_verify(model.handle, C.byref(kv.c), C.byref(tree), _p(out["logits"]), _p(out["feature"]),
+                                _p(out["argmax"]), _p(out["top2"]), _p(workspace), workspace.numel(), _stream()))
+    out["_keep"] = (slot, tokens, parent)
+    return out
+
+
+def fg_spec_accept(tokens, parent, mode=ACCEPT_GREEDY, logits=None, row_argmax=None, vocab=0, temperature=1.0,
+                   draft_probs=None, uniforms=None, seed=0, row0=0, eos_id=-1, workspace=None):
+    dev = tokens.device if isinstance(tokens, torch.Tensor) else (logits if logits is not None else row_argmax).device
+    tokens, parent = _dev_i32(tokens, dev), _dev_i32(parent, dev)
+    B, N = tokens.shape
+    acc = torch.empty(B, dtype=torch.int32, device=dev)
+    path = torch.empty((B, N), dtype=torch.int32, device=dev)
+    out = torch.empty((B, N), dtype=torch.int32, device=dev)
+    fin = torch.empty(B, dtype=torch.int32, device=dev)
+    if workspace is None:
+        need = B * N * 4 if mode != ACCEPT_REJECT else B * 2 * max(vocab, 1) * 4
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    tree = _tree(None, tokens, parent, B, N, 0, 0)
+    _check(lib().fg_spec_accept(C.byref(tree), mode, _p(logits), _p(row_argmax), vocab, temperature, _p(draft_probs),
+                                _p(uniforms), seed, row0, eos_id, _p(acc), _p(path), _p(out), _p(fin), _p(workspace),
+                                workspace.numel(), _stream()))
+    return acc, path, out, fin
+
+
+def fg_kv_compact(kv, slot, accept_len, path, feature_in=None, d_model=0):
+    dev = kv.k_pool.device
+    slot = _dev_i32(slot, dev)
+    B, N = path.shape
+    fout = None
+    fdt = kv.dtype
+    if feature_in is not None:
+        fout = torch.empty((B, N, d_model), dtype=feature_in.dtype, device=dev)
+        fdt = FG_BF16 if feature_in.dtype == torch.bfloat16 else FG_F32
+    _check(lib().fg_kv_compact(C.byref(kv.c), _p(slot), _p(accept_len), _p(path), B, N, _p(feature_in), _p(fout), d_model,
+                               fdt, _stream()))
+    return fout
+
+
+def fg_draft_step(target, draft, draft_kv, slot, tokens, parent, in_feature, workspace, K_draft, n_prev=0, n_commit=None,
+                  max_seq_len=0, want_children=True):
+    dev = draft_kv.k_pool.device
+    slot, tokens, parent = _dev_i32(slot, dev), _dev_i32(tokens, dev), _dev_i32(parent, dev)
+    B, N = tokens.shape
+    d = draft.cfg["d_model"]
+    in_feature = in_feature.contiguous()
+    assert in_feature.shape == (B, N, d) and in_feature.dtype == _tdtype(draft.dtype)
+    ctok = torch.empty((B, N, K_draft), dtype=torch.int32, device=dev) if want_children else None
+    clogp = torch.empty((B, N, K_draft), dtype=torch.float32, device=dev) if want_children else None
+    ofeat = torch.empty((B, N, d), dtype=_tdtype(draft.dtype), device=dev)
+    if n_commit is not None:
+        n_commit = _dev_i32(n_commit, dev)
+    tree = _tree(slot, tokens, parent, B, N, n_prev, max_seq_len)
+    _check(lib().fg_draft_step(target.handle, draft.handle, C.byref(draft_kv.c), C.byref(tree), _p(in_feature), _p(n_commit),
+                               K_draft, _p(ctok), _p(clogp), _p(ofeat), _p(workspace), workspace.numel(), _stream()))
+    return ctok, clogp, ofeat
+
+
+def fg_draft_frontier(child_tok, child_logp, node_cand, node_score, n_cand, cand_tok, cand_parent, cand_score):
+    B, K_in, K = child_tok.shape
+    dev = child_tok.device
+    nt = torch.empty((B, K), dtype=torch.int32, device=dev)
+    nc = torch.empty((B, K), dtype=torch.int32, device=dev)
+    ns = torch.empty((B, K), dtype=torch.float32, device=dev)
+    nsrc = torch.empty((B, K), dtype=torch.int32, device=dev)
+    _check(lib().fg_draft_frontier(B, K_in, K, _p(child_tok), _p(child_logp), _p(node_cand), _p(node_score), n_cand,
+                                   cand_tok.shape[1], _p(cand_tok), _p(cand_parent), _p(cand_score), _p(nt), _p(nc), _p(ns),
+                                   _p(nsrc), _stream()))
+    return nt, nc, ns, nsrc
+
+
+def fg_build_tree(cand_tok, cand_parent, cand_score, n_cand, N):
+    B, stride = cand_tok.shape
+    dev = cand_tok.device
+    tokens = torch.empty((B, N), dtype=torch.int32, device=dev)
+    parent = torch.empty((B, N), dtype=torch.int32, device=dev)
+    sel = torch.empty((B, N), dtype=torch.int32, device=dev)
+    _check(lib().fg_build_tree(_p(cand_tok), _p(cand_parent), _p(cand_score), B, n_cand, stride, N, _p(tokens), _p(parent),
+                               _p(sel), _stream()))
+    return tokens, parent, sel
+
+
+# ---- kernel-level ---------------------------------------------------------------------------------------------
+def fg_gemm(dtype, x, w_packed, n_out, epilogue=0, split_k=0):
+    x = x.contiguous()
+    M, n_in = x.shape
+    used = C.c_int32(1)
+    if epilogue == 0:
+        smax = 16 if split_k == 0 else split_k
+        out = torch.empty((smax, M, n_out), dtype=torch.float32, device=x.device)
+    else:
+        out = torch.empty((M, n_out // 2), dtype=x.dtype, device=x.device)
+    _check(lib().fg_gemm(dtype, _p(x), _p(w_packed), _p(out), M, n_out, n_in, epilogue, split_k, C.byref(used), _stream()))
+    if epilogue == 0:
+        return out[:used.value].sum(dim=0) if used.value > 1 else out[0], used.value
+    return out, 1
+
+
+def fg_attention(kv, layer, slot, parent, B, N, n_q_heads, q, n_prev=0, max_seq_len=0):
+    dev = kv.k_pool.device
+    slot, parent = _dev_i32(slot, dev), _dev_i32(parent, dev)
+    hd = kv.cfg["head_dim"]
+    cap = kv.max_pages * kv.page_size
+    ws = torch.empty(lib().fg_attention_workspace_bytes(B, N, n_q_heads, hd, max_seq_len or cap), dtype=torch.uint8, device=dev)
+    out = torch.empty_like(q)
+    tree = _tree(slot, None, parent, B, N, n_prev, max_seq_len)
+    _check(lib().fg_attention(C.byref(kv.c), layer, C.byref(tree), n_q_heads, _p(q), _p(out), _p(ws), ws.numel(), _stream()))
+    return out

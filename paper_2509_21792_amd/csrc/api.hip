@@ -1,0 +1,538 @@
+// The C ABI of libfastgrpo: argument checking, workspace carving and the launch sequence of each entry point.
+// Every numeric step is a kernel in the sibling .hip files; nothing here touches tensor contents on the host.
+#include <math.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "fg_common.h"
+
+namespace fg {
+
+static thread_local char g_err[512] = "";
+
+int32_t fail(int32_t code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+// launchers defined in the other translation units and not listed in fg_common.h
+int32_t launch_tree_prep_ex(const fg_tree *t, const int32_t *seq_len, int n_slots, TreeDev td, hipStream_t st);
+int32_t launch_swiglu_partials_bf16(const float *gu, int S, void *act, int M, int F, hipStream_t st);
+int32_t launch_attention_simple(const fg_kv_cache *kv, int layer, const fg_tree *t, TreeDev td, int Hq, const void *q, void *out,
+                                int max_keys, hipStream_t st);
+int32_t launch_attention_mfma(const fg_kv_cache *kv, int layer, const fg_tree *t, TreeDev td, int Hq, const void *q, void *out,
+                              int max_keys, void *ws, int64_t ws_bytes, hipStream_t st);
+int64_t attention_mfma_ws_bytes(int B, int N, int Hq, int Hkv, int hd, int max_keys);
+bool attention_mfma_supported(const fg_kv_cache *kv, int Hq, int N);
+int32_t launch_gumbel_argmax(const float *logits, int M, int V, float T, uint64_t seed, int64_t row0, int32_t *idx, hipStream_t st);
+int32_t launch_walk(int B, int N, const int32_t *tokens, const int32_t *parent, const int32_t *target_tok, int32_t eos,
+                    int32_t *accept_len, int32_t *path, int32_t *out_tokens, int32_t *finished, hipStream_t st);
+int32_t launch_reject(int B, int N, int V, const int32_t *tokens, const int32_t *parent, const float *logits,
+                      const float *draft_probs, const float *unif, float T, uint64_t seed, int64_t row0, int32_t eos, float *ws,
+                      int32_t *accept_len, int32_t *path, int32_t *out_tokens, int32_t *finished, hipStream_t st);
+int32_t launch_kv_compact(fg_kv_cache *kv, const int32_t *slot, const int32_t *accept_len, const int32_t *path, int B, int N,
+                          const void *fin, void *fout, int d, int feat_dtype, hipStream_t st);
+int32_t launch_topk_logp(const float *logits, int M, int V, int K, int32_t *tok, float *logp, hipStream_t st);
+int32_t launch_frontier(int B, int K_in, int K, const int32_t *child_tok, const float *child_logp, const int32_t *node_cand,
+                        const float *node_score, int n_cand, int stride, int32_t *cand_tok, int32_t *cand_parent,
+                        float *cand_score, int32_t *next_tok, int32_t *next_cand, float *next_score, int32_t *next_src,
+                        hipStream_t st);
+int32_t launch_build_tree(const int32_t *cand_tok, const int32_t *cand_parent, const float *cand_score, int B, int C, int stride,
+                          int N, int32_t *tokens, int32_t *parent, int32_t *sel, hipStream_t st);
+int32_t launch_commit_len(int32_t *seq_len, const int32_t *slot, const int32_t *n_commit, int B, int n_slots, hipStream_t st);
+int gemm_bf16_split_for(int M, int N, int K);
+
+}  // namespace fg
+
+using namespace fg;
+
+struct fg_model {
+    fg_model_cfg cfg;
+    const void *embed, *lm_head, *final_norm, *fc;
+    std::vector<const void *> wqkv, wo, wgu, wdown, norm_attn, norm_ffn;
+    float2 *rope_tab;  // device [max_pos][head_dim / 2] (cos, sin), angles evaluated in double
+    int device;
+};
+
+namespace {
+
+struct Carver {
+    char *base;
+    int64_t off, cap;
+    bool ok;
+    Carver(void *b, int64_t c) : base((char *)b), off(0), cap(c), ok(true) {}
+    template <typename T> T *take(int64_t n)
+    {
+        off = align_up(off, 256);
+        T *p = (T *)(base + off);
+        off += n * (int64_t)sizeof(T);
+        if (off > cap) ok = false;
+        return p;
+    }
+};
+
+// split-K factor the library will use for each GEMM of the step (0 = not a partial-sum GEMM)
+int split_for(const fg_model_cfg &c, int M, int N, int K) { return c.dtype == FG_BF16 ? gemm_bf16_split_for(M, N, K) : 1; }
+
+bool gate_up_fused(const fg_model_cfg &c, int M) { return c.dtype == FG_BF16 && M > 256; }
+
+int64_t partial_floats(const fg_model_cfg &c, int M, bool is_draft)
+{
+    const int d = c.d_model, F = c.d_ffn, qkvd = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim, hq = c.n_q_heads * c.head_dim;
+    int64_t m = 0;
+    // the split factor steps down as M crosses multiples of the block height, so S * M is not monotone in M:
+    // size for the worst row count up to M
+    auto upd = [&](int N, int K) {
+        for (int mm = M; mm > 0; mm = (mm - 1) / 256 * 256) {
+            int64_t v = (int64_t)split_for(c, mm, N, K) * mm * N;
+            if (v > m) m = v;
+        }
+    };
+    upd(qkvd, d);
+    upd(d, hq);
+    upd(d, F);
+    if (!gate_up_fused(c, M)) upd(2 * F, d);
+    if (is_draft) upd(d, 2 * d);
+    return m;
+}
+
+struct StepWs {
+    TreeDev td;
+    float *h, *partials, *logits;
+    void *a, *q, *att, *act, *feat, *cat;
+    void *attn_ws;
+    int64_t attn_ws_bytes;
+};
+
+int64_t carve_step(const fg_model_cfg &c, int M, int max_keys, int B, int N, bool is_draft, void *base, int64_t cap, StepWs *w,
+                   bool need_logits)
+{
+    Carver cv(base, cap);
+    const int64_t es = dtype_size(c.dtype);
+    const int d = c.d_model, hq = c.n_q_heads * c.head_dim;
+    StepWs s;
+    s.td.pos = cv.take<int32_t>(M);
+    s.td.mask = cv.take<uint64_t>(M);
+    s.h = cv.take<float>((int64_t)M * d);
+    s.partials = cv.take<float>(partial_floats(c, M, is_draft));
+    s.a = cv.take<char>((int64_t)M * d * es);
+    s.q = cv.take<char>((int64_t)M * hq * es);
+    s.att = cv.take<char>((int64_t)M * hq * es);
+    s.act = cv.take<char>((int64_t)M * c.d_ffn * es);
+    s.feat = cv.take<char>((int64_t)M * d * es);
+    s.cat = is_draft ? (void *)cv.take<char>((int64_t)M * 2 * d * es) : nullptr;
+    s.logits = need_logits ? cv.take<float>((int64_t)M * c.vocab) : nullptr;
+    s.attn_ws_bytes = attention_mfma_ws_bytes(B, N, c.n_q_heads, c.n_kv_heads, c.head_dim, max_keys);
+    s.attn_ws = cv.take<char>(s.attn_ws_bytes);
+    if (w) *w = s;
+    if (base && !cv.ok) return -1;
+    return align_up(cv.off, 256);
+}
+
+int32_t gemm_any(const fg_model_cfg &c, const void *x, const void *w, float *partials, int M, int N, int K, int *S, hipStream_t st)
+{
+    if (c.dtype == FG_BF16) return launch_gemm_bf16(x, w, partials, M, N, K, 0, 0, S, st);
+    *S = 1;
+    return launch_gemm_f32((const float *)x, (const float *)w, partials, M, N, K, st);
+}
+
+int32_t check_cache(const fg_model *m, const fg_kv_cache *kv)
+{
+    if (!kv || !kv->k_pool || !kv->v_pool || !kv->page_table || !kv->seq_len)
+        return fail(FG_ERR_INVALID_ARG, "KV cache or one of its members is NULL");
+    if (kv->page_size != 16) return fail(FG_ERR_SHAPE, "page_size must be 16 (got %d)", kv->page_size);
+    if (kv->n_slots < 1 || kv->n_pages < 1 || kv->max_pages_per_seq < 1)
+        return fail(FG_ERR_INVALID_ARG, "KV cache sizes must be positive");
+    if (m) {
+        const fg_model_cfg &c = m->cfg;
+        if (kv->dtype != c.dtype) return fail(FG_ERR_INVALID_ARG, "dtype mismatch: model %d, cache %d", c.dtype, kv->dtype);
+        if (kv->n_layers != c.n_layers || kv->n_kv_heads != c.n_kv_heads || kv->head_dim != c.head_dim)
+            return fail(FG_ERR_SHAPE, "cache geometry (%d layers, %d kv heads, head_dim %d) does not match the model (%d, %d, %d)",
+                        kv->n_layers, kv->n_kv_heads, kv->head_dim, c.n_layers, c.n_kv_heads, c.head_dim);
+    }
+    return FG_OK;
+}
+
+int32_t check_tree(const fg_tree *t, bool need_tokens)
+{
+    if (!t) return fail(FG_ERR_INVALID_ARG, "tree is NULL");
+    if (t->B < 0 || t->N < 0 || t->n_prev < 0) return fail(FG_ERR_INVALID_ARG, "negative B / N / n_prev");
+    if (t->n_prev + t->N > FG_MAX_NODES)
+        return fail(FG_ERR_CAPACITY, "n_prev + N = %d exceeds %d in-round nodes", t->n_prev + t->N, (int)FG_MAX_NODES);
+    if (t->B > 0 && t->N > 0 && (!t->parent || (need_tokens && (!t->tokens || !t->slot))))
+        return fail(FG_ERR_INVALID_ARG, "tree slot / tokens / parent is NULL");
+    return FG_OK;
+}
+
+int max_keys_of(const fg_kv_cache *kv, const fg_tree *t, int32_t *rc)
+{
+    int cap = kv->max_pages_per_seq * kv->page_size;
+    int mk = t->max_seq_len > 0 ? t->max_seq_len : cap;
+    if (mk > cap) { *rc = fail(FG_ERR_CAPACITY, "max_seq_len %d exceeds the cache capacity %d", mk, cap); return 0; }
+    *rc = FG_OK;
+    return mk;
+}
+
+int32_t attention_any(const fg_kv_cache *kv, int layer, const fg_tree *t, TreeDev td, int Hq, const void *q, void *out,
+                      int max_keys, void *ws, int64_t ws_bytes, hipStream_t st)
+{
+    if (attention_mfma_supported(kv, Hq, t->N))
+        return launch_attention_mfma(kv, layer, t, td, Hq, q, out, max_keys, ws, ws_bytes, st);
+    return launch_attention_simple(kv, layer, t, td, Hq, q, out, max_keys, st);
+}
+
+// The decoder layers shared by the target's verify step and the draft head.  On entry h holds the layer
+// input when first_S == 0, otherwise `partials` holds first_S slabs whose sum is the layer input (h is
+// initialised from them).  On exit `partials` holds *last_S slabs that still have to be added to h.
+int32_t run_layers(const fg_model *m, fg_kv_cache *kv, const fg_tree *t, const StepWs &w, int max_keys, int first_S,
+                   int *last_S, hipStream_t st)
+{
+    const fg_model_cfg &c = m->cfg;
+    const int M = t->B * t->N, d = c.d_model, F = c.d_ffn, hq = c.n_q_heads * c.head_dim;
+    const int qkvd = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+    int S = first_S, init = first_S > 0 ? 1 : 0;
+    int32_t rc;
+    for (int l = 0; l < c.n_layers; l++) {
+        if ((rc = launch_add_rmsnorm(c.dtype, w.h, w.partials, S, init, m->norm_attn[l], w.a, nullptr, M, d, c.rms_eps, st))) return rc;
+        init = 0;
+        if ((rc = gemm_any(c, w.a, m->wqkv[l], w.partials, M, qkvd, d, &S, st))) return rc;
+        if ((rc = launch_rope_append(c.dtype, w.partials, S, t, w.td, kv, l, (const float *)m->rope_tab, c.max_pos, c.n_q_heads, w.q, st))) return rc;
+        if ((rc = attention_any(kv, l, t, w.td, c.n_q_heads, w.q, w.att, max_keys, w.attn_ws, w.attn_ws_bytes, st))) return rc;
+        if ((rc = gemm_any(c, w.att, m->wo[l], w.partials, M, d, hq, &S, st))) return rc;
+        if ((rc = launch_add_rmsnorm(c.dtype, w.h, w.partials, S, 0, m->norm_ffn[l], w.a, nullptr, M, d, c.rms_eps, st))) return rc;
+        if (gate_up_fused(c, M)) {
+            if ((rc = launch_gemm_bf16(w.a, m->wgu[l], w.act, M, 2 * F, d, 1, 1, nullptr, st))) return rc;
+        } else {
+            if ((rc = gemm_any(c, w.a, m->wgu[l], w.partials, M, 2 * F, d, &S, st))) return rc;
+            if (c.dtype == FG_BF16) rc = launch_swiglu_partials_bf16(w.partials, S, w.act, M, F, st);
+            else rc = launch_swiglu_f32(w.partials, (float *)w.act, M, F, st);
+            if (rc) return rc;
+        }
+        if ((rc = gemm_any(c, w.act, m->wdown[l], w.partials, M, d, F, &S, st))) return rc;
+    }
+    *last_S = S;
+    return FG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *fg_last_error(void) { return g_err; }
+
+int32_t fg_plan(int32_t B_cur, float C_peak, float alpha, int32_t K_max, int32_t L_max, int32_t N_cap, int32_t *N_verify,
+                int32_t *K_draft, int32_t *L_draft)
+{
+    if (!N_verify || !K_draft || !L_draft) return fail(FG_ERR_INVALID_ARG, "fg_plan: NULL output");
+    if (B_cur < 1 || !(C_peak > 0.f) || !(alpha > 0.f) || K_max < 0 || L_max < 0 || N_cap < 1 || N_cap > FG_MAX_NODES)
+        return fail(FG_ERR_INVALID_ARG, "fg_plan: B_cur=%d C_peak=%g alpha=%g K_max=%d L_max=%d N_cap=%d", B_cur, (double)C_peak,
+                    (double)alpha, K_max, L_max, N_cap);
+    // Eq. 1: N = C_peak / B, floored, at least the root, at most the mask width
+    long long N = (long long)floor((double)C_peak / (double)B_cur);
+    N = N < 1 ? 1 : (N > N_cap ? N_cap : N);
+    // Eq. 2
+    long long K = N - 1 < K_max ? N - 1 : K_max;
+    // Eq. 3: the largest L with 2^L <= N / alpha, found by doubling (no libm rounding at powers of two)
+    long long L = 0;
+    const double ratio = (double)N / (double)alpha;
+    if (ratio >= 1.0) {
+        double pw = 2.0;
+        while (pw <= ratio && L < 62) { L++; pw *= 2.0; }
+    }
+    if (L > L_max) L = L_max;
+    if (L > N - 1) L = N - 1;
+    if (K <= 0 || L <= 0) { N = 1; K = 0; L = 0; }
+    else {
+        long long cand = 1 + K + (L - 1) * K * K;  // all candidates the expansion produces
+        if (N > cand) N = cand;
+    }
+    *N_verify = (int32_t)N; *K_draft = (int32_t)K; *L_draft = (int32_t)L;
+    return FG_OK;
+}
+
+int64_t fg_packed_bytes(int32_t dtype, int64_t n_out_total, int64_t n_in) { return n_out_total * n_in * (int64_t)dtype_size(dtype); }
+
+int32_t fg_pack_weight(int32_t dtype, const void *src, const void *src2, void *dst, int64_t n_out, int64_t n_in, void *stream)
+{
+    if (!src || !dst || n_out <= 0 || n_in <= 0) return fail(FG_ERR_INVALID_ARG, "fg_pack_weight: NULL pointer or empty matrix");
+    return launch_pack(dtype, src, src2, dst, n_out, n_in, (hipStream_t)stream);
+}
+
+int32_t fg_model_create(const fg_model_cfg *cfg, const fg_weights *w, fg_model **out)
+{
+    if (!cfg || !w || !out) return fail(FG_ERR_INVALID_ARG, "fg_model_create: NULL argument");
+    const fg_model_cfg &c = *cfg;
+    if (c.dtype != FG_F32 && c.dtype != FG_BF16) return fail(FG_ERR_INVALID_ARG, "unknown dtype %d", c.dtype);
+    if (c.n_layers < 1 || c.d_model < 1 || c.n_q_heads < 1 || c.n_kv_heads < 1 || c.d_ffn < 1 || c.vocab < 1 || c.max_pos < 1)
+        return fail(FG_ERR_INVALID_ARG, "model sizes must be positive");
+    if (c.head_dim != 64 && c.head_dim != 128) return fail(FG_ERR_SHAPE, "head_dim must be 64 or 128 (got %d)", c.head_dim);
+    if (c.n_q_heads % c.n_kv_heads || c.n_q_heads / c.n_kv_heads > 8)
+        return fail(FG_ERR_SHAPE, "n_q_heads must be a multiple (at most 8x) of n_kv_heads");
+    if (c.d_model % 64 || c.d_ffn % 64 || c.vocab % 32 || (c.n_q_heads * c.head_dim) % 64)
+        return fail(FG_ERR_SHAPE, "d_model, d_ffn and Hq*hd must be multiples of 64, vocab of 32");
+    if (!w->embed || !w->lm_head || !w->wqkv || !w->wo || !w->w_gate_up || !w->w_down || !w->norm_attn || !w->norm_ffn)
+        return fail(FG_ERR_INVALID_ARG, "a weight pointer is NULL");
+    if (!w->final_norm && !w->fc) return fail(FG_ERR_INVALID_ARG, "need final_norm (target) or fc (draft head)");
+    fg_model *m = new (std::nothrow) fg_model();
+    if (!m) return fail(FG_ERR_INVALID_ARG, "out of host memory");
+    m->cfg = c;
+    m->embed = w->embed; m->lm_head = w->lm_head; m->final_norm = w->final_norm; m->fc = w->fc;
+    for (int l = 0; l < c.n_layers; l++) {
+        if (!w->wqkv[l] || !w->wo[l] || !w->w_gate_up[l] || !w->w_down[l] || !w->norm_attn[l] || !w->norm_ffn[l]) {
+            delete m;
+            return fail(FG_ERR_INVALID_ARG, "a weight pointer of layer %d is NULL", l);
+        }
+        m->wqkv.push_back(w->wqkv[l]); m->wo.push_back(w->wo[l]); m->wgu.push_back(w->w_gate_up[l]);
+        m->wdown.push_back(w->w_down[l]); m->norm_attn.push_back(w->norm_attn[l]); m->norm_ffn.push_back(w->norm_ffn[l]);
+    }
+    const int half = c.head_dim / 2;
+    std::vector<float2> tab((size_t)c.max_pos * half);
+    for (int p = 0; p < c.max_pos; p++)
+        for (int i = 0; i < half; i++) {
+            double ang = (double)p * pow((double)c.rope_theta, -2.0 * (double)i / (double)c.head_dim);
+            tab[(size_t)p * half + i] = make_float2((float)cos(ang), (float)sin(ang));
+        }
+    m->rope_tab = nullptr;
+    hipError_t e = hipGetDevice(&m->device);
+    if (e == hipSuccess) e = hipMalloc((void **)&m->rope_tab, tab.size() * sizeof(float2));
+    if (e == hipSuccess) e = hipMemcpy(m->rope_tab, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        if (m->rope_tab) (void)hipFree(m->rope_tab);
+        delete m;
+        return fail(FG_ERR_HIP, "RoPE table: %s", hipGetErrorString(e));
+    }
+    *out = m;
+    return FG_OK;
+}
+
+int32_t fg_model_destroy(fg_model *m)
+{
+    if (!m) return FG_OK;
+    if (m->rope_tab) (void)hipFree(m->rope_tab);
+    delete m;
+    return FG_OK;
+}
+
+int64_t fg_workspace_bytes(const fg_model *m, int32_t max_rows, int32_t max_seq_len)
+{
+    if (!m || max_rows < 1 || max_seq_len < 1) return 0;
+    // B and N only enter through the attention workspace, which is largest at N = 1 (B = max_rows) for split
+    // bookkeeping and at N = 64 for rows per sequence; take the maximum over the two extremes and powers of two.
+    int64_t best = 0;
+    for (int N = 1; N <= FG_MAX_NODES; N *= 2) {
+        int B = (max_rows + N - 1) / N;
+        int64_t v = carve_step(m->cfg, max_rows, max_seq_len, B, N, m->fc != nullptr, nullptr, 0, nullptr, true);
+        if (v > best) best = v;
+    }
+    return best + (1 << 20);
+}
+
+int32_t fg_spec_verify(fg_model *m, fg_kv_cache *kv, const fg_tree *tree, float *logits, void *feature, int32_t *row_argmax,
+                       float *row_top2, void *workspace, int64_t workspace_bytes, void *stream)
+{
+    if (!m) return fail(FG_ERR_INVALID_ARG, "fg_spec_verify: model is NULL");
+    int32_t rc;
+    if ((rc = check_cache(m, kv))) return rc;
+    if ((rc = check_tree(tree, true))) return rc;
+    if (!m->final_norm) return fail(FG_ERR_INVALID_ARG, "fg_spec_verify needs a target model (final_norm)");
+    if (tree->B == 0 || tree->N == 0) return FG_OK;
+    if (!workspace) return fail(FG_ERR_INVALID_ARG, "workspace is NULL");
+    const fg_model_cfg &c = m->cfg;
+    const int M = tree->B * tree->N;
+    const int mk = max_keys_of(kv, tree, &rc);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    StepWs w;
+    const bool need_logits = !logits && (row_argmax || row_top2);
+    if (carve_step(c, M, mk, tree->B, tree->N, false, workspace, workspace_bytes, &w, need_logits) < 0)
+        return fail(FG_ERR_CAPACITY, "workspace too small: have %lld bytes", (long long)workspace_bytes);
+    if ((rc = launch_tree_prep_ex(tree, kv->seq_len, kv->n_slots, w.td, st))) return rc;
+    if ((rc = launch_embed(c.dtype, m->embed, tree->tokens, c.vocab, w.h, M, c.d_model, st))) return rc;
+    int S = 0;
+    if ((rc = run_layers(m, kv, tree, w, mk, 0, &S, st))) return rc;
+    void *feat = feature ? feature : w.feat;
+    if ((rc = launch_add_rmsnorm(c.dtype, w.h, w.partials, S, 0, m->final_norm, feat, nullptr, M, c.d_model, c.rms_eps, st))) return rc;
+    float *lg = logits ? logits : w.logits;
+    if (lg) {
+        if (c.dtype == FG_BF16) rc = launch_gemm_bf16(feat, m->lm_head, lg, M, c.vocab, c.d_model, 0, 1, nullptr, st);
+        else rc = launch_gemm_f32((const float *)feat, (const float *)m->lm_head, lg, M, c.vocab, c.d_model, st);
+        if (rc) return rc;
+        if (row_argmax || row_top2)
+            if ((rc = launch_argmax_top2(lg, M, c.vocab, row_argmax, row_top2, st))) return rc;
+    }
+    return FG_OK;
+}
+
+int32_t fg_spec_accept(const fg_tree *tree, int32_t mode, const float *logits, const int32_t *row_argmax, int32_t vocab,
+                       float temperature, const float *draft_probs, const float *uniforms, uint64_t seed, int64_t row0,
+                       int32_t eos_id, int32_t *accept_len, int32_t *path, int32_t *out_tokens, int32_t *finished,
+                       void *workspace, int64_t workspace_bytes, void *stream)
+{
+    int32_t rc;
+    if ((rc = check_tree(tree, false))) return rc;
+    if (!tree->tokens) return fail(FG_ERR_INVALID_ARG, "fg_spec_accept: tokens is NULL");
+    if (tree->n_prev != 0) return fail(FG_ERR_INVALID_ARG, "fg_spec_accept works on a whole tree (n_prev must be 0)");
+    if (!accept_len || !path || !out_tokens || !finished) return fail(FG_ERR_INVALID_ARG, "fg_spec_accept: NULL output");
+    if (tree->B == 0) return FG_OK;
+    if (tree->N < 1) return fail(FG_ERR_INVALID_ARG, "fg_spec_accept: N must be at least 1");
+    const int B = tree->B, N = tree->N, M = B * N;
+    hipStream_t st = (hipStream_t)stream;
+    if (mode == FG_ACCEPT_GREEDY || mode == FG_ACCEPT_SAMPLE_MATCH) {
+        const int32_t *tt = row_argmax;
+        if (mode == FG_ACCEPT_SAMPLE_MATCH || !tt) {
+            if (!logits || vocab < 1) return fail(FG_ERR_INVALID_ARG, "fg_spec_accept: logits needed");
+            if (!workspace || workspace_bytes < (int64_t)M * 4)
+                return fail(FG_ERR_CAPACITY, "fg_spec_accept: workspace of %lld bytes needed", (long long)M * 4);
+            int32_t *buf = (int32_t *)workspace;
+            if (mode == FG_ACCEPT_GREEDY) rc = launch_argmax_top2(logits, M, vocab, buf, nullptr, st);
+            else {
+                if (!(temperature > 0.f)) return fail(FG_ERR_INVALID_ARG, "temperature must be positive");
+                rc = launch_gumbel_argmax(logits, M, vocab, temperature, seed, row0, buf, st);
+            }
+            if (rc) return rc;
+            tt = buf;
+        }
+        return launch_walk(B, N, tree->tokens, tree->parent, tt, eos_id, accept_len, path, out_tokens, finished, st);
+    }
+    if (mode == FG_ACCEPT_REJECT) {
+        if (!logits || !draft_probs || !uniforms || vocab < 1) return fail(FG_ERR_INVALID_ARG, "rejection mode needs logits, draft_probs, uniforms");
+        if (!(temperature > 0.f)) return fail(FG_ERR_INVALID_ARG, "temperature must be positive");
+        int64_t need = (int64_t)B * 2 * vocab * 4;
+        if (!workspace || workspace_bytes < need) return fail(FG_ERR_CAPACITY, "fg_spec_accept: workspace of %lld bytes needed", (long long)need);
+        return launch_reject(B, N, vocab, tree->tokens, tree->parent, logits, draft_probs, uniforms, temperature, seed, row0,
+                             eos_id, (float *)workspace, accept_len, path, out_tokens, finished, st);
+    }
+    return fail(FG_ERR_INVALID_ARG, "unknown acceptance mode %d", mode);
+}
+
+int32_t fg_kv_compact(fg_kv_cache *kv, const int32_t *slot, const int32_t *accept_len, const int32_t *path, int32_t B, int32_t N,
+                      const void *feature_in, void *feature_out, int32_t d_model, int32_t feat_dtype, void *stream)
+{
+    int32_t rc;
+    if ((rc = check_cache(nullptr, kv))) return rc;
+    if (B < 0 || N < 1 || N > FG_MAX_NODES) return fail(FG_ERR_INVALID_ARG, "fg_kv_compact: bad B / N");
+    if (B == 0) return FG_OK;
+    if (!slot || !accept_len || !path) return fail(FG_ERR_INVALID_ARG, "fg_kv_compact: NULL input");
+    if ((feature_in != nullptr) != (feature_out != nullptr)) return fail(FG_ERR_INVALID_ARG, "feature_in and feature_out go together");
+    if (kv->dtype != FG_F32 && kv->dtype != FG_BF16) return fail(FG_ERR_INVALID_ARG, "unknown cache dtype");
+    return launch_kv_compact(kv, slot, accept_len, path, B, N, feature_in, feature_out, d_model, feat_dtype, (hipStream_t)stream);
+}
+
+int32_t fg_draft_step(fg_model *target, fg_model *draft, fg_kv_cache *draft_kv, const fg_tree *tree, const void *in_feature,
+                      const int32_t *n_commit, int32_t K_draft, int32_t *child_tok, float *child_logp, void *out_feature,
+                      void *workspace, int64_t workspace_bytes, void *stream)
+{
+    if (!target || !draft) return fail(FG_ERR_INVALID_ARG, "fg_draft_step: model is NULL");
+    if (!draft->fc) return fail(FG_ERR_INVALID_ARG, "fg_draft_step needs a draft head (fc)");
+    int32_t rc;
+    if ((rc = check_cache(draft, draft_kv))) return rc;
+    if ((rc = check_tree(tree, true))) return rc;
+    const fg_model_cfg &c = draft->cfg;
+    if (c.d_model != target->cfg.d_model || c.vocab != target->cfg.vocab || c.dtype != target->cfg.dtype)
+        return fail(FG_ERR_SHAPE, "draft head and target differ in width, vocabulary or dtype");
+    if (tree->B == 0 || tree->N == 0) return FG_OK;
+    if (!in_feature || !workspace) return fail(FG_ERR_INVALID_ARG, "fg_draft_step: NULL input");
+    if ((child_tok != nullptr) != (child_logp != nullptr)) return fail(FG_ERR_INVALID_ARG, "child_tok and child_logp go together");
+    const int M = tree->B * tree->N, d = c.d_model;
+    const int mk = max_keys_of(draft_kv, tree, &rc);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    StepWs w;
+    if (carve_step(c, M, mk, tree->B, tree->N, true, workspace, workspace_bytes, &w, child_tok != nullptr) < 0)
+        return fail(FG_ERR_CAPACITY, "workspace too small: have %lld bytes", (long long)workspace_bytes);
+    if ((rc = launch_tree_prep_ex(tree, draft_kv->seq_len, draft_kv->n_slots, w.td, st))) return rc;
+    if ((rc = launch_concat_embed(c.dtype, target->embed, tree->tokens, c.vocab, in_feature, w.cat, M, d, st))) return rc;
+    int S = 0;
+    if ((rc = gemm_any(c, w.cat, draft->fc, w.partials, M, d, 2 * d, &S, st))) return rc;
+    if ((rc = run_layers(draft, draft_kv, tree, w, mk, S, &S, st))) return rc;
+    void *hid = out_feature ? out_feature : w.feat;
+    if ((rc = launch_add_rmsnorm(c.dtype, w.h, w.partials, S, 0, draft->norm_attn[0], nullptr, hid, M, d, c.rms_eps, st))) return rc;
+    if (child_tok) {
+        if (c.dtype == FG_BF16) rc = launch_gemm_bf16(hid, target->lm_head, w.logits, M, c.vocab, d, 0, 1, nullptr, st);
+        else rc = launch_gemm_f32((const float *)hid, (const float *)target->lm_head, w.logits, M, c.vocab, d, st);
+        if (rc) return rc;
+        if ((rc = launch_topk_logp(w.logits, M, c.vocab, K_draft, child_tok, child_logp, st))) return rc;
+    }
+    if (n_commit)
+        if ((rc = launch_commit_len(draft_kv->seq_len, tree->slot, n_commit, tree->B, draft_kv->n_slots, st))) return rc;
+    return FG_OK;
+}
+
+int32_t fg_draft_frontier(int32_t B, int32_t K_in, int32_t K, const int32_t *child_tok, const float *child_logp,
+                          const int32_t *node_cand, const float *node_score, int32_t n_cand, int32_t cand_stride,
+                          int32_t *cand_tok, int32_t *cand_parent, float *cand_score, int32_t *next_tok, int32_t *next_cand,
+                          float *next_score, int32_t *next_src, void *stream)
+{
+    if (B < 0 || K_in < 1 || K < 1 || K_in * K > 64 || K > K_in * K) return fail(FG_ERR_INVALID_ARG, "fg_draft_frontier: bad K_in / K");
+    if (n_cand < 0 || n_cand + K_in * K > cand_stride) return fail(FG_ERR_CAPACITY, "candidate lists too short");
+    if (B == 0) return FG_OK;
+    if (!child_tok || !child_logp || !node_cand || !node_score || !cand_tok || !cand_parent || !cand_score || !next_tok ||
+        !next_cand || !next_score || !next_src)
+        return fail(FG_ERR_INVALID_ARG, "fg_draft_frontier: NULL pointer");
+    return launch_frontier(B, K_in, K, child_tok, child_logp, node_cand, node_score, n_cand, cand_stride, cand_tok, cand_parent,
+                           cand_score, next_tok, next_cand, next_score, next_src, (hipStream_t)stream);
+}
+
+int32_t fg_build_tree(const int32_t *cand_tok, const int32_t *cand_parent, const float *cand_score, int32_t B, int32_t n_cand,
+                      int32_t cand_stride, int32_t N, int32_t *tokens, int32_t *parent, int32_t *sel, void *stream)
+{
+    if (B < 0 || n_cand < 1 || N < 1 || N > n_cand || N > FG_MAX_NODES || cand_stride < n_cand)
+        return fail(FG_ERR_INVALID_ARG, "fg_build_tree: bad sizes (n_cand %d, N %d)", n_cand, N);
+    if (B == 0) return FG_OK;
+    if (!cand_tok || !cand_parent || !cand_score || !tokens || !parent) return fail(FG_ERR_INVALID_ARG, "fg_build_tree: NULL pointer");
+    return launch_build_tree(cand_tok, cand_parent, cand_score, B, n_cand, cand_stride, N, tokens, parent, sel, (hipStream_t)stream);
+}
+
+int32_t fg_gemm(int32_t dtype, const void *x, const void *w_packed, void *out, int32_t M, int32_t n_out, int32_t n_in,
+                int32_t epilogue, int32_t split_k, int32_t *split_k_used, void *stream)
+{
+    if (!x || !w_packed || !out || M < 0 || n_out < 1 || n_in < 1) return fail(FG_ERR_INVALID_ARG, "fg_gemm: bad argument");
+    if (M == 0) return FG_OK;
+    if (dtype == FG_BF16) return launch_gemm_bf16(x, w_packed, out, M, n_out, n_in, epilogue, split_k, split_k_used, (hipStream_t)stream);
+    if (dtype == FG_F32) {
+        if (epilogue != 0) return fail(FG_ERR_UNIMPLEMENTED, "fp32 GEMM has no fused epilogue");
+        if (split_k_used) *split_k_used = 1;
+        return launch_gemm_f32((const float *)x, (const float *)w_packed, (float *)out, M, n_out, n_in, (hipStream_t)stream);
+    }
+    return fail(FG_ERR_INVALID_ARG, "unknown dtype %d", dtype);
+}
+
+int64_t fg_attention_workspace_bytes(int32_t B, int32_t N, int32_t n_q_heads, int32_t head_dim, int32_t max_seq_len)
+{
+    // the kv-head count only lowers the need; size for the worst case of one kv head per query head group of 1
+    return (int64_t)B * N * 8 + (int64_t)B * N * 8 + 512 + attention_mfma_ws_bytes(B, N, n_q_heads, 1, head_dim, max_seq_len) + 4096;
+}
+
+int32_t fg_attention(const fg_kv_cache *kv, int32_t layer, const fg_tree *tree, int32_t n_q_heads, const void *q, void *out,
+                     void *workspace, int64_t workspace_bytes, void *stream)
+{
+    int32_t rc;
+    if ((rc = check_cache(nullptr, kv))) return rc;
+    if ((rc = check_tree(tree, false))) return rc;
+    if (!tree->slot) return fail(FG_ERR_INVALID_ARG, "fg_attention: slot is NULL");
+    if (tree->B == 0 || tree->N == 0) return FG_OK;
+    if (!q || !out || !workspace) return fail(FG_ERR_INVALID_ARG, "fg_attention: NULL pointer");
+    if (layer < 0 || layer >= kv->n_layers || n_q_heads < 1 || n_q_heads % kv->n_kv_heads)
+        return fail(FG_ERR_INVALID_ARG, "fg_attention: bad layer or head count");
+    const int mk = max_keys_of(kv, tree, &rc);
+    if (rc) return rc;
+    const int M = tree->B * tree->N;
+    Carver cv(workspace, workspace_bytes);
+    TreeDev td;
+    td.pos = cv.take<int32_t>(M);
+    td.mask = cv.take<uint64_t>(M);
+    int64_t ab = attention_mfma_ws_bytes(tree->B, tree->N, n_q_heads, kv->n_kv_heads, kv->head_dim, mk);
+    void *aws = cv.take<char>(ab);
+    if (!cv.ok) return fail(FG_ERR_CAPACITY, "fg_attention: workspace too small");
+    hipStream_t st = (hipStream_t)stream;
+    if ((rc = launch_tree_prep_ex(tree, kv->seq_len, kv->n_slots, td, st))) return rc;
+    return attention_any(kv, layer, tree, td, n_q_heads, q, out, mk, aws, ab, st);
+}
+
+}  // extern "C"

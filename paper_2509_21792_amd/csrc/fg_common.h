@@ -1,0 +1,98 @@
+// Internal helpers of libfastgrpo: error state, small device utilities, launcher prototypes.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdarg.h>
+
+#include "fastgrpo.h"
+
+namespace fg {
+
+// ---- error state (thread local) -------------------------------------------------------------------
+int32_t fail(int32_t code, const char *fmt, ...);
+#define FG_HIP(call)                                                                                   \
+    do {                                                                                               \
+        hipError_t e_ = (call);                                                                        \
+        if (e_ != hipSuccess) return fg::fail(FG_ERR_HIP, "%s: %s", #call, hipGetErrorString(e_));     \
+    } while (0)
+#define FG_LAUNCH_CHECK(name)                                                                          \
+    do {                                                                                               \
+        hipError_t e_ = hipGetLastError();                                                             \
+        if (e_ != hipSuccess) return fg::fail(FG_ERR_HIP, "launch of %s: %s", name, hipGetErrorString(e_)); \
+    } while (0)
+
+// ---- element types --------------------------------------------------------------------------------
+typedef uint16_t bf16_t;  // storage only
+
+__device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+__device__ __forceinline__ bf16_t f2bf(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);  // round to nearest even (inputs are finite here)
+    return (bf16_t)(u >> 16);
+}
+template <typename T> __device__ __forceinline__ float to_f(T v);
+template <> __device__ __forceinline__ float to_f<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f<bf16_t>(bf16_t v) { return bf2f(v); }
+template <typename T> __device__ __forceinline__ T from_f(float v);
+template <> __device__ __forceinline__ float from_f<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f<bf16_t>(float v) { return f2bf(v); }
+
+static inline size_t dtype_size(int32_t dtype) { return dtype == FG_BF16 ? 2 : 4; }
+static inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+// ---- wave / block reductions (wave64) -------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// ---- counter-based uniforms (SplitMix64 finaliser) ------------------------------------------------
+__host__ __device__ __forceinline__ uint64_t mix64(uint64_t z)
+{
+    z += 0x9E3779B97F4A7C15ULL;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+__device__ __forceinline__ uint64_t row_key(uint64_t seed, uint64_t row) { return mix64(seed ^ (row * 0xD1B54A32D192ED03ULL)); }
+__device__ __forceinline__ float uniform_from_key(uint64_t key, uint64_t v)
+{
+    uint64_t bits = mix64(key + v);
+    return ((float)(bits >> 41) + 0.5f) * (1.0f / 8388608.0f);
+}
+__device__ __forceinline__ float gumbel_from_key(uint64_t key, uint64_t v) { return -logf(-logf(uniform_from_key(key, v))); }
+
+// ---- launchers (one per kernel family; all asynchronous on `st`) -------------------------------------
+struct TreeDev {             // per-call derived tree data in the workspace
+    int32_t *pos;            // [B*N] position of each new node
+    uint64_t *mask;          // [B*N] in-round ancestors-or-self of each new node (bit i = in-round node i)
+};
+
+int32_t launch_gemm_bf16(const void *x, const void *wp, void *out, int M, int N, int K, int epilogue, int split_k,
+                         int *split_used, hipStream_t st);
+int32_t launch_gemm_f32(const float *x, const float *w, float *out, int M, int N, int K, hipStream_t st);
+int32_t launch_pack(int32_t dtype, const void *src, const void *src2, void *dst, int64_t n_out, int64_t n_in, hipStream_t st);
+
+int32_t launch_embed(int32_t dtype, const void *embed, const int32_t *tokens, int vocab, float *h, int M, int d, hipStream_t st);
+int32_t launch_concat_embed(int32_t dtype, const void *embed, const int32_t *tokens, int vocab, const void *feat, void *cat,
+                            int M, int d, hipStream_t st);
+// h (+)= sum of S partial slabs; optional norm output a = rmsnorm(h) * gain (dtype), optional copy of h as dtype
+int32_t launch_add_rmsnorm(int32_t dtype, float *h, const float *partials, int S, int init, const void *gain, void *a,
+                           void *h_copy, int M, int d, float eps, hipStream_t st);
+int32_t launch_rope_append(int32_t dtype, const float *qkv_partials, int S, const fg_tree *t, TreeDev td, const fg_kv_cache *kv,
+                           int layer, const float *rope_tab, int max_pos, int Hq, void *q_out, hipStream_t st);
+int32_t launch_swiglu_f32(const float *gu, float *act, int M, int F, hipStream_t st);
+int32_t launch_argmax_top2(const float *logits, int M, int V, int32_t *idx, float *top2, hipStream_t st);
+
+
+}  // namespace fg

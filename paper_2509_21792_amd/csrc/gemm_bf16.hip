@@ -1,0 +1,283 @@
+// bf16 GEMM on MFMA for gfx950: out = X . W^T with W pre-packed as MFMA operand fragments.
+//
+// W [N, K] is stored as 1 KiB tiles of 32 rows x 16 k: lane ((k % 16) / 8) * 32 + n % 32 of a tile holds the 8
+// consecutive k of row n -- exactly the per-lane operand of v_mfma_f32_32x32x16_bf16 -- and the tiles of one
+// 32-row band are contiguous in k.  A wave therefore streams its band of W straight from HBM into MFMA operand
+// registers with fully coalesced 16-byte loads (1 KiB per wave instruction, no LDS round trip, no swizzle).
+// The activation block X [M, K] (row-major, small or reused) is staged through LDS in the same fragment order,
+// double buffered, one barrier per 64-wide k chunk.
+//
+// Block = WM x WN waves; a wave owns MT x NT tiles of 32 x 32 outputs.  WM = 1 with MT = ceil(M / 32) is the
+// weight-streaming (memory-bound) shape: every byte of W is read exactly once per GEMM.  Split-K over
+// blockIdx.z writes fp32 partial slabs that the consumer kernel sums (no atomics: results are deterministic).
+#include "fg_common.h"
+
+namespace fg {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+union Frag {
+    uint4 u;
+    bf16x8_t v;
+};
+
+constexpr int KT = 4;  // k tiles (of 16) per chunk: 64 k
+
+template <int MT, int NT, int WM, int WN, int EPI>
+__global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(const bf16_t *__restrict__ X,
+                                                                  const uint4 *__restrict__ Wp, void *__restrict__ out,
+                                                                  int M, int N, int K, int chunks_per_split)
+{
+    constexpr int THREADS = WM * WN * 64;
+    constexpr int BM = WM * MT * 32;
+    constexpr int XLOADS = BM * 8 / THREADS;  // 16-byte loads of X per thread per chunk
+    static_assert(BM * 8 % THREADS == 0, "X staging must divide evenly");
+    __shared__ uint4 xs[2][BM / 32 * KT * 64];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int row0 = blockIdx.y * BM;
+    const int n_tiles = N >> 5, k_tiles = K >> 4;
+    const int ntile0 = (blockIdx.x * WN + wn) * NT;
+    const int total_chunks = k_tiles / KT;
+    const int c_begin = blockIdx.z * chunks_per_split;
+    const int c_end = min(c_begin + chunks_per_split, total_chunks);
+    const int n_chunks = c_end - c_begin;
+
+    f32x16_t acc[MT][NT];
+#pragma unroll
+    for (int i = 0; i < MT; i++)
+#pragma unroll
+        for (int j = 0; j < NT; j++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
+
+    // W band pointers (clamped for the ragged last block so loads stay in bounds; results are not stored)
+    const uint4 *wband[NT];
+#pragma unroll
+    for (int j = 0; j < NT; j++) {
+        int t = min(ntile0 + j, n_tiles - 1);
+        wband[j] = Wp + ((size_t)t * k_tiles) * 64 + lane;
+    }
+
+    uint4 xr[XLOADS];
+    Frag w[NT][KT];
+
+    auto load_x = [&](int chunk) {
+#pragma unroll
+        for (int i = 0; i < XLOADS; i++) {
+            int idx = i * THREADS + tid;
+            int c = idx & 7, r = idx >> 3;
+            int row = row0 + r;
+            if (row < M)
+                xr[i] = *reinterpret_cast<const uint4 *>(X + (size_t)row * K + (size_t)chunk * 64 + c * 8);
+            else
+                xr[i] = make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto store_x = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < XLOADS; i++) {
+            int idx = i * THREADS + tid;
+            int c = idx & 7, r = idx >> 3;
+            xs[buf][(((r >> 5) * KT + (c >> 1)) << 6) + ((c & 1) << 5) + (r & 31)] = xr[i];
+        }
+    };
+
+    if (n_chunks > 0) {
+        load_x(c_begin);
+#pragma unroll
+        for (int j = 0; j < NT; j++)
+#pragma unroll
+            for (int kt = 0; kt < KT; kt++) w[j][kt].u = wband[j][(size_t)(c_begin * KT + kt) * 64];
+        store_x(0);
+        __syncthreads();
+        // One chunk per iteration.  The next chunk's X goes global -> registers at the top and registers -> the
+        // other LDS buffer at the bottom; the next chunk's W fragment kt is requested right after the MFMAs that
+        // consumed the current fragment kt, so a full chunk of MFMA work covers its latency.  The last iteration
+        // re-requests its own chunk (clamped index) instead of branching.
+        for (int c = 0; c < n_chunks; c++) {
+            const int buf = c & 1;
+            const int nxt = c_begin + min(c + 1, n_chunks - 1);
+            load_x(nxt);
+#pragma unroll
+            for (int kt = 0; kt < KT; kt++) {
+#pragma unroll
+                for (int i = 0; i < MT; i++) {
+                    Frag xf;
+                    xf.u = xs[buf][(((wm * MT + i) * KT + kt) << 6) + lane];
+#pragma unroll
+                    for (int j = 0; j < NT; j++)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf.v, w[j][kt].v, acc[i][j], 0, 0, 0);
+                }
+#pragma unroll
+                for (int j = 0; j < NT; j++) w[j][kt].u = wband[j][(size_t)(nxt * KT + kt) * 64];
+            }
+            store_x(buf ^ 1);
+            __syncthreads();
+        }
+    }
+
+    // epilogue: lane holds column n = lane % 32 of each tile, rows 8 * (r / 4) + 4 * (lane / 32) + r % 4
+    const int col_in_tile = lane & 31, row_half = (lane >> 5) * 4;
+    if (EPI == 0) {
+        float *o = reinterpret_cast<float *>(out) + (size_t)blockIdx.z * M * N;
+#pragma unroll
+        for (int j = 0; j < NT; j++) {
+            int nt = ntile0 + j;
+            if (nt >= n_tiles) continue;
+            int n = nt * 32 + col_in_tile;
+#pragma unroll
+            for (int i = 0; i < MT; i++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    int m = row0 + (wm * MT + i) * 32 + 8 * (r >> 2) + row_half + (r & 3);
+                    if (m < M) o[(size_t)m * N + n] = acc[i][j][r];
+                }
+        }
+    } else {
+        // gate / up tiles alternate: tile 2t = gate, 2t + 1 = up, both for output columns 32 t .. 32 t + 31
+        bf16_t *o = reinterpret_cast<bf16_t *>(out);
+        const int F = N >> 1;
+#pragma unroll
+        for (int j = 0; j < NT; j += 2) {
+            int nt = ntile0 + j;
+            if (nt + 1 >= n_tiles) continue;  // n_tiles is even and pairs start at even tiles
+            int f = (nt >> 1) * 32 + col_in_tile;
+#pragma unroll
+            for (int i = 0; i < MT; i++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    int m = row0 + (wm * MT + i) * 32 + 8 * (r >> 2) + row_half + (r & 3);
+                    if (m < M) {
+                        float g = acc[i][j][r], u = acc[i][(j + 1) % NT][r];
+                        float s = g / (1.f + __expf(-g));
+                        o[(size_t)m * F + f] = f2bf(s * u);
+                    }
+                }
+        }
+    }
+}
+
+// ---- host side -----------------------------------------------------------------------------------------
+
+struct GemmShape { int mt, nt, wm, wn; };
+
+template <int MT, int NT, int WM, int WN, int EPI>
+static void launch_variant(const void *x, const void *wp, void *out, int M, int N, int K, int split, hipStream_t st)
+{
+    const int n_tiles = N / 32, per_block = WN * NT;
+    const int total_chunks = K / 64;
+    const int cps = (total_chunks + split - 1) / split;
+    dim3 grid((n_tiles + per_block - 1) / per_block, (M + WM * MT * 32 - 1) / (WM * MT * 32), split);
+    hipLaunchKernelGGL((gemm_bf16_kernel<MT, NT, WM, WN, EPI>), grid, dim3(WM * WN * 64), 0, st,
+                       reinterpret_cast<const bf16_t *>(x), reinterpret_cast<const uint4 *>(wp), out, M, N, K, cps);
+}
+
+// Number of k splits: enough blocks to cover the chip a few times over when the output is narrow, never
+// fewer than two chunks per split, and only for the fp32-partial epilogue.
+static int choose_split(int M, int N, int K, int block_rows, int block_cols)
+{
+    const int blocks = ((N + block_cols - 1) / block_cols) * ((M + block_rows - 1) / block_rows);
+    const int total_chunks = K / 64;
+    int want = (768 + blocks - 1) / blocks;
+    if (M > 256) want = (320 + blocks - 1) / blocks;
+    int s = want < 1 ? 1 : want;
+    if (s > 16) s = 16;
+    if (s > total_chunks / 2) s = total_chunks / 2;
+    if (s < 1) s = 1;
+    // make every split non-empty
+    int cps = (total_chunks + s - 1) / s;
+    s = (total_chunks + cps - 1) / cps;
+    return s;
+}
+
+int gemm_bf16_split_for(int M, int N, int K)
+{
+    if (M <= 256) return choose_split(M, N, K, 256, 256);
+    return choose_split(M, N, K, 256, 256);
+}
+
+int32_t launch_gemm_bf16(const void *x, const void *wp, void *out, int M, int N, int K, int epilogue, int split_k,
+                         int *split_used, hipStream_t st)
+{
+    if (M <= 0) return FG_OK;
+    if (N % 32 || K % 64) return fail(FG_ERR_SHAPE, "bf16 GEMM needs n_out %% 32 == 0 and n_in %% 64 == 0 (got %d, %d)", N, K);
+    if (epilogue == 1 && (N % 64)) return fail(FG_ERR_SHAPE, "gate/up GEMM needs n_out %% 64 == 0");
+    int split = 1;
+    if (epilogue == 0) {
+        split = split_k > 0 ? split_k : gemm_bf16_split_for(M, N, K);
+        if (split > K / 64) split = K / 64;
+        int cps = (K / 64 + split - 1) / split;
+        split = (K / 64 + cps - 1) / cps;
+    }
+    if (split_used) *split_used = split;
+#define FG_GEMM_CASE(MT, NT, WM, WN)                                                                    \
+    do {                                                                                                \
+        if (epilogue == 0) launch_variant<MT, NT, WM, WN, 0>(x, wp, out, M, N, K, split, st);           \
+        else launch_variant<MT, NT, WM, WN, 1>(x, wp, out, M, N, K, split, st);                         \
+    } while (0)
+    if (M <= 32) FG_GEMM_CASE(1, 2, 1, 4);
+    else if (M <= 64) FG_GEMM_CASE(2, 2, 1, 4);
+    else if (M <= 128) FG_GEMM_CASE(4, 2, 1, 4);
+    else if (M <= 256) FG_GEMM_CASE(8, 2, 1, 4);
+    else FG_GEMM_CASE(4, 4, 2, 2);
+#undef FG_GEMM_CASE
+    FG_LAUNCH_CHECK("gemm_bf16");
+    return FG_OK;
+}
+
+// ---- packing ---------------------------------------------------------------------------------------------
+// Logical row n of the packed matrix: without src2 it is src row n; with src2 the rows alternate in blocks of
+// 32: logical block 2t = src rows 32t.., block 2t + 1 = src2 rows 32t...
+template <typename T>
+__device__ __forceinline__ const T *logical_row(const T *src, const T *src2, int64_t n, int64_t K)
+{
+    if (!src2) return src + n * K;
+    int64_t blk = n >> 5, r = n & 31;
+    const T *base = (blk & 1) ? src2 : src;
+    return base + ((blk >> 1) * 32 + r) * K;
+}
+
+__global__ void pack_bf16_kernel(const bf16_t *src, const bf16_t *src2, uint4 *dst, int64_t N, int64_t K)
+{
+    // one thread per 16-byte fragment element: (n tile, k tile, lane)
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t total = (N / 32) * (K / 16) * 64;
+    if (idx >= total) return;
+    int lane = idx & 63;
+    int64_t tile = idx >> 6;
+    int64_t kt = tile % (K / 16), nt = tile / (K / 16);
+    int64_t n = nt * 32 + (lane & 31), k = kt * 16 + (lane >> 5) * 8;
+    dst[idx] = *reinterpret_cast<const uint4 *>(logical_row(src, src2, n, K) + k);
+}
+
+__global__ void pack_f32_kernel(const float *src, const float *src2, float *dst, int64_t N, int64_t K)
+{
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= N * K) return;
+    int64_t n = idx / K, k = idx % K;
+    dst[idx] = logical_row(src, src2, n, K)[k];
+}
+
+int32_t launch_pack(int32_t dtype, const void *src, const void *src2, void *dst, int64_t n_out, int64_t n_in, hipStream_t st)
+{
+    int64_t N = src2 ? 2 * n_out : n_out;
+    if (n_out % 32 || n_in % 64) return fail(FG_ERR_SHAPE, "pack needs n_out %% 32 == 0 and n_in %% 64 == 0 (got %lld, %lld)",
+                                             (long long)n_out, (long long)n_in);
+    if (dtype == FG_BF16) {
+        int64_t total = (N / 32) * (n_in / 16) * 64;
+        hipLaunchKernelGGL(pack_bf16_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                           (const bf16_t *)src, (const bf16_t *)src2, (uint4 *)dst, N, n_in);
+    } else if (dtype == FG_F32) {
+        int64_t total = N * n_in;
+        hipLaunchKernelGGL(pack_f32_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const float *)src,
+                           (const float *)src2, (float *)dst, N, n_in);
+    } else
+        return fail(FG_ERR_INVALID_ARG, "unknown dtype %d", dtype);
+    FG_LAUNCH_CHECK("pack");
+    return FG_OK;
+}
+
+}  // namespace fg

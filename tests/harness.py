@@ -1,0 +1,118 @@
+"""Shared set-up of the GPU parity tests (and of the smoke check): builds the same seeded workload on both sides.
+
+The HIP side gets torch tensors on the device, the oracle gets float32 numpy copies of the very same values;
+the two implementations never see each other.  Oracle-side work can be limited to a subset of the sequences
+(rows of the batch are independent), which is how the full-size configurations are checked.
+"""
+import numpy as np
+import torch
+
+import paper_2509_21792_amd as fg
+from oracle import loop
+from oracle.oracle import Oracle
+from synth import configs, gen
+
+MARGIN = 0.05          # token decisions are exempt where the oracle's top-2 margin is below this
+TOL = {"fp32": 1e-4, "bf16": 3e-2}
+
+
+class Pair:
+    """A target (and optionally its draft head) on the device and in the oracle, from one set of weights."""
+
+    def __init__(self, model_cfg, seed=0, with_draft=False, kind="f32", max_pos=8192, oracle_side=True):
+        self.cfg = model_cfg
+        self.orc = Oracle(kind)
+        w = gen.make_weights(model_cfg, seed, device="cuda")
+        self.gm = fg.Model(model_cfg, w, max_pos=max_pos)
+        self.om = self.orc.model(model_cfg, gen.weights_to_numpy(w)) if oracle_side else None
+        self.gd = self.od = None
+        if with_draft:
+            dcfg = configs.draft_of(model_cfg)
+            dw = gen.make_weights(dcfg, seed, device="cuda", draft=True)
+            self.dcfg = dcfg
+            self.gd = fg.Model(dcfg, dw, target=self.gm, max_pos=max_pos)
+            self.od = self.orc.model(dcfg, gen.weights_to_numpy(dw), embed_from=self.om) if oracle_side else None
+        del w
+        torch.cuda.synchronize()
+
+
+class State:
+    """Caches of B sequences with synthetic committed prefixes of the given lengths, on the device (all B) and
+    in the oracle (the sequences listed in `subset`, default all)."""
+
+    def __init__(self, pair, model_cfg, lengths, extra, seed, subset=None, spare=0, oracle_model=None):
+        self.pair, self.cfg = pair, model_cfg
+        self.B = len(lengths)
+        self.lengths = np.asarray(lengths, dtype=np.int32)
+        self.subset = list(range(self.B)) if subset is None else list(subset)
+        table, n_pages = gen.make_page_table(self.lengths, extra, 16, seed, spare_pages=spare)
+        self.kv = fg.KVCache(model_cfg, table, n_pages)
+        self.cap = int(self.lengths.max()) + extra
+        orc = pair.orc
+        self.ocache = orc.cache(model_cfg, len(self.subset), self.cap) if pair.om is not None else None
+        for b in range(self.B):
+            L = int(self.lengths[b])
+            if L == 0:
+                continue
+            k, v = gen.make_prefix_kv(model_cfg, L, seed, b, device="cuda")
+            self.kv.write_prefix(b, k, v)
+            if self.ocache is not None and b in self.subset:
+                j = self.subset.index(b)
+                self.ocache.k[:, j, :L] = k.float().cpu().numpy()
+                self.ocache.v[:, j, :L] = v.float().cpu().numpy()
+        if self.ocache is not None:
+            self.ocache.len[:] = self.lengths[self.subset]
+        self.slot = np.arange(self.B, dtype=np.int32)
+        torch.cuda.synchronize()
+
+
+def compare_rows(got_logits, want_logits, tol, got_argmax=None, margin=MARGIN):
+    """Element-wise logits check plus the token decision check with the top-2 margin exemption.
+    Returns a dict of statistics; raises AssertionError on a violation."""
+    got = np.asarray(got_logits, dtype=np.float64)
+    want = np.asarray(want_logits, dtype=np.float64)
+    err = np.abs(got - want).max()
+    stats = dict(max_abs=float(err), rows=int(want.shape[0]))
+    assert err <= tol, f"logits max-abs {err:.4g} exceeds {tol}"
+    order = np.sort(want, axis=1)
+    mar = order[:, -1] - order[:, -2]
+    want_tok = want.argmax(axis=1)
+    tok = got.argmax(axis=1) if got_argmax is None else np.asarray(got_argmax)
+    bad = (tok != want_tok) & (mar >= margin)
+    stats["exempt_rows"] = int((mar < margin).sum())
+    stats["token_mismatch_exempt"] = int(((tok != want_tok) & (mar < margin)).sum())
+    assert not bad.any(), f"{int(bad.sum())} token decisions differ outside the margin exemption"
+    return stats
+
+
+def oracle_verify(state, tokens, parent, n_prev=0):
+    """The oracle's forward over the subset rows; returns (hidden [S*N, d], logits [S*N, V])."""
+    sub = state.subset
+    return state.pair.orc.tree_forward(state.pair.om, state.ocache, tokens[sub], parent[sub], n_prev=n_prev)
+
+
+def smoke_check():
+    """One tiny verify + accept + compact of the fp32 config on cuda:0 against the oracle."""
+    cfg = configs.CONFIGS["cfg1"]
+    model = configs.TINY
+    pair = Pair(model, seed=0)
+    B, N = 4, 5
+    lengths = np.array([7, 16, 21, 33], dtype=np.int32)
+    st = State(pair, model, lengths, N + 2, seed=1)
+    rng = np.random.default_rng(0)
+    parent = np.tile(np.array([-1, 0, 0, 1, 3], dtype=np.int32), (B, 1))
+    tokens = rng.integers(0, model["vocab"], size=(B, N)).astype(np.int32)
+    ws = pair.gm.workspace(B * N, st.cap)
+    out = fg.fg_spec_verify(pair.gm, st.kv, st.slot, tokens, parent, ws, want_logits=True)
+    torch.cuda.synchronize()
+    _, ol = oracle_verify(st, tokens, parent)
+    compare_rows(out["logits"].cpu().numpy(), ol, TOL["fp32"], out["argmax"].cpu().numpy())
+    tt = ol.argmax(axis=1).astype(np.int32).reshape(B, N)
+    tokens[:, 1] = tt[:, 0]                      # plant one agreement so a path gets accepted
+    out = fg.fg_spec_verify(pair.gm, st.kv, st.slot, tokens, parent, ws, want_logits=True)
+    acc, path, otok, fin = fg.fg_spec_accept(torch.as_tensor(tokens).cuda(), torch.as_tensor(parent).cuda(),
+                                             row_argmax=out["argmax"])
+    fg.fg_kv_compact(st.kv, st.slot, acc, path)
+    torch.cuda.synchronize()
+    assert (acc.cpu().numpy() >= 1).all()
+    assert (st.kv.seq_len.cpu().numpy() == lengths + acc.cpu().numpy() + 1).all()

@@ -1,0 +1,69 @@
+"""CPU-side checks of the boundary: the library loads, exports what include/fastgrpo.h declares, and its host-only
+logic (the concurrency rule, argument validation) behaves.  No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "fastgrpo.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2509_21792_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return binding.lib()
+
+
+def declared():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fg_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = declared()
+    assert "fg_spec_verify" in names and "fg_spec_accept" in names and "fg_kv_compact" in names and "fg_draft_step" in names
+    for n in names:
+        assert hasattr(L, n), n
+    from paper_2509_21792_amd import binding
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_plan_matches_the_worked_table(L):
+    from paper_2509_21792_amd import fg_plan
+    for line in open(os.path.join(ROOT, "tests", "golden", "plan_table.txt")):
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        f = line.split()
+        got = fg_plan(int(f[0]), float(f[1]), float(f[2]), int(f[3]), int(f[4]), int(f[5]))
+        assert got == (int(f[6]), int(f[7]), int(f[8])), line
+
+
+def test_plan_agrees_with_oracle_on_a_sweep(L, orc32):
+    from paper_2509_21792_amd import fg_plan
+    for B in list(range(1, 70)) + [96, 128, 255, 256, 257, 512, 1000]:
+        for Cp in (1.0, 7.5, 64.0, 100.0, 256.0, 315.0, 512.0, 1024.0, 2048.0, 4096.0):
+            for alpha in (0.25, 0.5, 1.0, 3.0):
+                assert fg_plan(B, Cp, alpha) == orc32.plan(B, Cp, alpha), (B, Cp, alpha)
+
+
+def test_bad_arguments_are_errors_not_crashes(L):
+    from paper_2509_21792_amd import FgError, fg_plan
+    for args in [(0, 256.0), (4, 0.0), (4, 256.0, 0.0), (4, 256.0, 0.5, -1), (4, 256.0, 0.5, 4, 6, 65)]:
+        with pytest.raises(FgError):
+            fg_plan(*args)
+    assert L.fg_spec_verify(None, None, None, None, None, None, None, None, 0, None) == -1
+    assert b"NULL" in L.fg_last_error()
+    assert L.fg_model_create(None, None, None) == -1
+    assert L.fg_pack_weight(1, None, None, None, 32, 64, None) == -1
+    assert L.fg_kv_compact(None, None, None, None, 1, 1, None, None, 0, 0, None) == -1
+    assert L.fg_build_tree(None, None, None, 1, 4, 4, 8, None, None, None, None) == -1     # N > n_cand
+    assert L.fg_draft_frontier(1, 9, 8, *([None] * 4), 0, 100, *([None] * 8)) == -1        # K_in * K > 64
+    assert L.fg_workspace_bytes(None, 8, 8) == 0
+    assert L.fg_packed_bytes(1, 64, 128) == 64 * 128 * 2 and L.fg_packed_bytes(0, 64, 128) == 64 * 128 * 4

@@ -1,0 +1,131 @@
+"""Kernel-level checks on the GPU (through the C ABI): the packed bf16 MFMA GEMM and the tree attention kernels
+against their plain definitions evaluated with torch library routines in fp64 on the CPU.  The step-level parity
+against the oracle is in test_gpu_verify.py; these narrow a failure down to one kernel."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def fg():
+    import paper_2509_21792_amd as m
+    m.lib()
+    assert torch.cuda.is_available()
+    return m
+
+
+def bf16_randn(shape, gen, scale=1.0):
+    return (torch.randn(shape, generator=gen, dtype=torch.float32) * scale).to(torch.bfloat16)
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 64, 64), (8, 4608, 3584), (48, 3584, 3584), (40, 96, 128), (130, 1024, 704 - 64),
+                                   (192, 3584, 18944), (256, 512, 256), (257, 544, 192), (700, 4608, 1536)])
+def test_gemm_bf16_partial_epilogue(fg, M, N, K):
+    print(f"gemm M={M} N={N} K={K}", flush=True)
+    g = torch.Generator().manual_seed(M * 7 + N)
+    x, w = bf16_randn((M, K), g), bf16_randn((N, K), g, 0.05)
+    ref = x.double() @ w.double().T
+    wp = fg.fg_pack_weight(fg.FG_BF16, w.cuda())
+    for split in (0, 1, 3):
+        out, used = fg.fg_gemm(fg.FG_BF16, x.cuda(), wp, N, epilogue=0, split_k=split)
+        torch.cuda.synchronize()
+        err = (out.double().cpu() - ref).abs().max().item()
+        scale = ref.abs().max().item()
+        assert err <= 2e-5 * scale + 1e-4, (split, used, err, scale)
+    # run twice: split-K slabs are summed in a fixed order, so results are bitwise repeatable
+    a, _ = fg.fg_gemm(fg.FG_BF16, x.cuda(), wp, N)
+    b, _ = fg.fg_gemm(fg.FG_BF16, x.cuda(), wp, N)
+    assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("M,F,K", [(8, 704, 256), (33, 1024, 128), (200, 18944, 3584), (300, 2048, 512), (1000, 1024, 256)])
+def test_gemm_bf16_swiglu_epilogue(fg, M, F, K):
+    print(f"swiglu gemm M={M} F={F} K={K}", flush=True)
+    g = torch.Generator().manual_seed(M + F)
+    x, wg, wu = bf16_randn((M, K), g), bf16_randn((F, K), g, 0.05), bf16_randn((F, K), g, 0.05)
+    gate, up = x.double() @ wg.double().T, x.double() @ wu.double().T
+    ref = torch.nn.functional.silu(gate) * up
+    wp = fg.fg_pack_weight(fg.FG_BF16, wg.cuda(), wu.cuda())
+    out, _ = fg.fg_gemm(fg.FG_BF16, x.cuda(), wp, 2 * F, epilogue=1)
+    torch.cuda.synchronize()
+    err = (out.double().cpu() - ref).abs()
+    assert (err <= 2 ** -8 * ref.abs() + 1e-3).all(), err.max().item()
+
+
+def test_gemm_f32(fg):
+    g = torch.Generator().manual_seed(1)
+    x, w = torch.randn((37, 704), generator=g), torch.randn((1024, 704), generator=g) * 0.05
+    wp = fg.fg_pack_weight(fg.FG_F32, w.cuda())
+    out, _ = fg.fg_gemm(fg.FG_F32, x.cuda(), wp, 1024)
+    torch.cuda.synchronize()
+    ref = x.double() @ w.double().T
+    assert (out.double().cpu() - ref).abs().max().item() < 1e-4
+
+
+def test_gemm_rejects_unsupported_shapes(fg):
+    x = torch.zeros((4, 100), dtype=torch.bfloat16, device="cuda")
+    w = torch.zeros((64, 100), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(fg.FgError):
+        fg.fg_pack_weight(fg.FG_BF16, w)
+    with pytest.raises(fg.FgError):
+        fg.fg_gemm(fg.FG_BF16, x, w, 64)
+
+
+def ref_attention(q, k, v, L, parent, n_prev, Hq, Hkv, hd):
+    """q [N_new, Hq, hd], k / v [L + n_tot, Hkv, hd] of one sequence, fp64 torch; explicit boolean mask."""
+    n_tot = parent.shape[0]
+    N_new = n_tot - n_prev
+    mask = torch.zeros((N_new, L + n_tot), dtype=torch.bool)
+    mask[:, :L] = True
+    for j in range(N_new):
+        u = n_prev + j
+        while u >= 0:
+            mask[j, L + u] = True
+            u = int(parent[u])
+    kk = k.repeat_interleave(Hq // Hkv, dim=1).permute(1, 0, 2)
+    vv = v.repeat_interleave(Hq // Hkv, dim=1).permute(1, 0, 2)
+    o = torch.nn.functional.scaled_dot_product_attention(q.permute(1, 0, 2), kk, vv, attn_mask=mask[None])
+    return o.permute(1, 0, 2)
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,hd,B,N,n_prev,lens", [
+    ("fp32", 4, 4, 64, 3, 5, 0, (0, 7, 40)),
+    ("bf16", 12, 2, 128, 4, 6, 0, (512, 100, 17, 31)),
+    ("bf16", 28, 4, 128, 5, 24, 0, (256, 1000, 33, 2048, 15)),
+    ("bf16", 28, 4, 128, 3, 8, 0, (1024, 4096, 1500)),
+    ("bf16", 28, 4, 128, 3, 32, 0, (300, 3072, 16)),
+    ("bf16", 28, 4, 128, 2, 4, 8, (77, 640)),
+    ("bf16", 28, 4, 128, 9, 1, 0, (1, 16, 17, 255, 256, 257, 1023, 2000, 0)),
+    ("bf16", 28, 4, 128, 2, 64, 0, (128, 50)),
+])
+def test_tree_attention(fg, dtype, Hq, Hkv, hd, B, N, n_prev, lens):
+    from synth import gen
+    print(f"attention {dtype} Hq={Hq} Hkv={Hkv} hd={hd} B={B} N={N} n_prev={n_prev} lens={lens}", flush=True)
+    cfg = dict(n_layers=2, n_kv_heads=Hkv, head_dim=hd, dtype=dtype)
+    n_tot = n_prev + N
+    rng = np.random.default_rng(N + B)
+    table, n_pages = gen.make_page_table(np.array(lens), n_tot, 16, seed=3, spare_pages=2)
+    kv = fg.KVCache(cfg, table, n_pages)
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    g = torch.Generator().manual_seed(5)
+    parent = np.stack([np.array([-1] + [int(rng.integers(-1, i)) for i in range(1, n_tot)], dtype=np.int32) for _ in range(B)])
+    ks, vs = [], []
+    for b in range(B):
+        k = torch.randn((2, lens[b] + n_tot, Hkv, hd), generator=g).to(td)
+        v = torch.randn((2, lens[b] + n_tot, Hkv, hd), generator=g).to(td)
+        kv.write_prefix(b, k.cuda(), v.cuda())
+        ks.append(k); vs.append(v)
+    kv.seq_len.copy_(torch.tensor(lens, dtype=torch.int32))
+    q = (torch.randn((B * N, Hq * hd), generator=g) * 1.5).to(td)
+    layer = 1
+    out = fg.fg_attention(kv, layer, np.arange(B, dtype=np.int32), parent, B, N, Hq, q.cuda(), n_prev=n_prev)
+    torch.cuda.synchronize()
+    out = out.double().cpu().view(B, N, Hq, hd)
+    for b in range(B):
+        ref = ref_attention(q.double().view(B, N, Hq, hd)[b], ks[b][layer].double(), vs[b][layer].double(), lens[b],
+                            parent[b], n_prev, Hq, Hkv, hd)
+        err = (out[b] - ref).abs().max().item()
+        tol = 1e-5 if dtype == "fp32" else 2.5e-2
+        assert err < tol, (b, err)

@@ -1,0 +1,208 @@
+"""GPU parity of the verify step, acceptance and KV compaction against the CPU oracle, through the C ABI.
+
+Bar: token ids, accept lengths and paths bit-exact except where the oracle's top-2 margin is below 0.05;
+logits within 1e-4 (fp32 model) / 3e-2 (bf16 models) max-abs of the fp32 oracle; KV movement bit-exact.
+Small cases compare every element; the full-size configurations compare a subset of the sequences (rows of a
+batch are independent) while the GPU runs the whole batch in the benchmark's launch configuration.
+"""
+import numpy as np
+import pytest
+import torch
+
+from synth import configs, gen
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H():
+    from tests import harness
+    assert torch.cuda.is_available()
+    return harness
+
+
+def run_verify_case(H, model, B, N, spec, lengths, seed, subset=None, check_kv=True, n_check_layers=None):
+    import paper_2509_21792_amd as fg
+    pair = H.Pair(model, seed=seed)
+    st = H.State(pair, model, lengths, N + 1, seed=seed + 1, subset=subset)
+    parent, principal = gen.make_trees(spec, B, N, seed + 2)
+    rng = np.random.default_rng(seed + 3)
+    tokens = rng.integers(0, model["vocab"], size=(B, N)).astype(np.int32)
+    ws = pair.gm.workspace(B * N, st.cap)
+    out = fg.fg_spec_verify(pair.gm, st.kv, st.slot, tokens, parent, ws, want_logits=True, want_top2=True,
+                            max_seq_len=int(lengths.max()) + N)
+    torch.cuda.synchronize()
+    oh, ol = H.oracle_verify(st, tokens, parent)
+    sub = st.subset
+    V, d = model["vocab"], model["d_model"]
+    rows = np.concatenate([np.arange(b * N, (b + 1) * N) for b in sub])
+    tol = H.TOL[model["dtype"]]
+    stats = H.compare_rows(out["logits"][rows].cpu().numpy(), ol, tol, out["argmax"][rows].cpu().numpy())
+    feat = out["feature"][rows].float().cpu().numpy()
+    ferr = np.abs(feat - oh).max()
+    assert ferr <= (1e-4 if model["dtype"] == "fp32" else 6e-2), ferr
+    # top-2 values are the two largest logits of the row
+    top2 = out["top2"][rows].cpu().numpy()
+    srt = np.sort(out["logits"][rows].cpu().numpy(), axis=1)
+    assert np.array_equal(top2[:, 0], srt[:, -1]) and np.array_equal(top2[:, 1], srt[:, -2])
+    assert (st.kv.seq_len.cpu().numpy() == lengths).all()           # verify does not commit
+    if check_kv:
+        # the K/V the step appended (slots L .. L+N-1) against the oracle's
+        for j, b in enumerate(sub):
+            L = int(lengths[b])
+            k, v = st.kv.read(b, L + N)
+            kerr = np.abs(k[:, L:].float().cpu().numpy() - st.ocache.k[:, j, L:L + N]).max()
+            verr = np.abs(v[:, L:].float().cpu().numpy() - st.ocache.v[:, j, L:L + N]).max()
+            ktol = 1e-4 if model["dtype"] == "fp32" else 8e-2
+            assert kerr <= ktol and verr <= ktol, (b, kerr, verr)
+    print(f"verify {model['name']} B={B} N={N}: {stats} feature_err={ferr:.3g}", flush=True)
+    return pair, st, tokens, parent, out, ol
+
+
+def test_config1_tiny_fp32_every_element(H):
+    cfg = configs.CONFIGS["cfg1"]
+    lengths = np.array([32, 33, 40, 47, 48, 49, 63, 96], dtype=np.int32)
+    run_verify_case(H, configs.TINY, 8, cfg["N"], cfg["tree"], lengths, seed=0)
+
+
+def test_tiny_fp32_wide_tree_and_empty_prefix(H):
+    lengths = np.array([0, 1, 15, 16, 17], dtype=np.int32)
+    run_verify_case(H, configs.TINY, 5, 24, ("tree", 4, 5, 24), lengths, seed=4)
+
+
+def test_bf16_7b_geometry_two_layers_every_element(H):
+    """The 7B-class layer geometry and vocabulary with 2 layers: every GEMM shape of the big model, all rows checked."""
+    model = configs.scaled(configs.Q7B, 2)
+    lengths = np.array([256, 300, 17, 1000, 2048, 31], dtype=np.int32)
+    run_verify_case(H, model, 6, 24, ("tree", 4, 5, 24), lengths, seed=1)
+
+
+def test_bf16_1p5b_geometry_two_layers_chain(H):
+    model = configs.scaled(configs.Q1P5B, 2)
+    lengths = np.full(16, 512, dtype=np.int32)
+    run_verify_case(H, model, 16, 6, ("chain", 5), lengths, seed=2)
+
+
+@pytest.mark.parametrize("N", [1, 2, 8])
+def test_bf16_7b_geometry_high_concurrency_shapes(H, N):
+    """B = 256 rows of config 4's shapes (N = 1, 2, 8) on the 7B geometry with 1 layer; oracle on 6 sequences."""
+    model = configs.scaled(configs.Q7B, 1)
+    B = 256
+    lengths = gen.make_kv_lengths(B, 64, 600, seed=5)
+    lengths[0], lengths[1] = 64, 600
+    spec = ("chain", 1) if N <= 2 else ("tree", 4, 4, 8)
+    run_verify_case(H, model, B, N, spec, lengths, seed=3 + N, subset=[0, 1, 2, 100, 200, 255])
+
+
+def test_accept_and_compact_follow_the_oracle(H):
+    """Greedy acceptance with planted agreement + compaction: accept lengths, paths, tokens and the moved K/V."""
+    import paper_2509_21792_amd as fg
+    model = configs.scaled(configs.Q7B, 2)
+    B, N, spec = 8, 24, ("tree", 4, 5, 24)
+    lengths = np.array([256, 300, 17, 1000, 700, 31, 64, 15], dtype=np.int32)
+    pair = H.Pair(model, seed=7)
+    st = H.State(pair, model, lengths, N + 1, seed=8)
+    orc = pair.orc
+    # the oracle's own greedy continuation along the principal path, one N = 1 pass at a time (its cache is
+    # restored afterwards by resetting the lengths: in-round slots beyond them are rewritten by the next pass)
+    parent, principal = gen.make_trees(spec, B, N, 9)
+    depth = principal.shape[1]
+    rng = np.random.default_rng(10)
+    root = rng.integers(0, model["vocab"], size=B).astype(np.int32)
+    nxt = np.zeros((B, depth), dtype=np.int32)
+    cur = root.copy()
+    for l in range(depth):
+        _, lg = orc.tree_forward(pair.om, st.ocache, cur.reshape(B, 1), np.full((B, 1), -1, np.int32))
+        cur, _ = orc.row_argmax(lg)
+        nxt[:, l] = cur
+        st.ocache.len += 1
+    st.ocache.len[:] = lengths
+    tokens, hit = gen.plant_tokens(parent, principal, root, nxt, 0.7, model["vocab"], 11)
+    ws = pair.gm.workspace(B * N, st.cap)
+    out = fg.fg_spec_verify(pair.gm, st.kv, st.slot, tokens, parent, ws, want_logits=True)
+    oh, ol = orc.tree_forward(pair.om, st.ocache, tokens, parent)
+    o_acc, o_path, o_out, o_fin, o_tt, o_margin = orc.accept_greedy(tokens, parent, ol)
+    tok_d, par_d = torch.as_tensor(tokens).cuda(), torch.as_tensor(parent).cuda()
+    acc, path, otok, fin = fg.fg_spec_accept(tok_d, par_d, row_argmax=out["argmax"])
+    acc2, path2, otok2, fin2 = fg.fg_spec_accept(tok_d, par_d, logits=out["logits"], vocab=model["vocab"])
+    torch.cuda.synchronize()
+    assert torch.equal(acc, acc2) and torch.equal(path, path2) and torch.equal(otok, otok2)
+    acc, path, otok = acc.cpu().numpy(), path.cpu().numpy(), otok.cpu().numpy()
+    n_exempt = 0
+    for b in range(B):
+        # a walk is exempt only if it passed a node whose oracle margin is below the threshold
+        walked = o_path[b, :o_acc[b] + 1]
+        if (o_margin[b, walked] < H.MARGIN).any():
+            n_exempt += 1
+            continue
+        assert acc[b] == o_acc[b] and np.array_equal(path[b], o_path[b]) and np.array_equal(otok[b], o_out[b]), b
+    assert n_exempt < B
+    assert o_acc.max() >= 2 and o_acc.min() == 0 or o_acc.max() >= 2
+    # compaction with the oracle's decisions on both sides: the K/V that stays must be bit-identical to what the
+    # verify step wrote for the path's nodes, and lengths advance by accept_len + 1
+    before = [st.kv.read(b, int(lengths[b]) + N) for b in range(B)]
+    feat_g = fg.fg_kv_compact(st.kv, st.slot, torch.as_tensor(o_acc).cuda(), torch.as_tensor(o_path).cuda(),
+                              feature_in=out["feature"].view(B, N, -1), d_model=model["d_model"])
+    torch.cuda.synchronize()
+    orc.kv_compact(st.ocache, model, o_acc, o_path)
+    assert np.array_equal(st.kv.seq_len.cpu().numpy(), st.ocache.len)
+    for b in range(B):
+        L, a = int(lengths[b]), int(o_acc[b])
+        k, v = st.kv.read(b, L + a + 1)
+        for j in range(a + 1):
+            assert torch.equal(k[:, L + j], before[b][0][:, L + o_path[b, j]])
+            assert torch.equal(v[:, L + j], before[b][1][:, L + o_path[b, j]])
+        assert torch.equal(k[:, :L], before[b][0][:, :L]) and torch.equal(v[:, :L], before[b][1][:, :L])
+        kerr = np.abs(k[:, L:].float().cpu().numpy() - st.ocache.k[:, b, L:L + a + 1]).max()
+        assert kerr < 8e-2
+        fg_rows = feat_g[b, :a + 1].float().cpu().numpy()
+        want = out["feature"].view(B, N, -1)[b, o_path[b, :a + 1]].float().cpu().numpy()
+        assert np.array_equal(fg_rows, want)
+        assert (feat_g[b, a + 1:] == 0).all()
+    print(f"accept: oracle accept lengths {o_acc.tolist()} exempt walks {n_exempt}", flush=True)
+
+
+def test_accept_eos_and_malformed_paths(H):
+    import paper_2509_21792_amd as fg
+    orc = H.Oracle("f32")
+    rng = np.random.default_rng(3)
+    B, N, V = 64, 12, 50
+    parent, principal = gen.make_trees(("tree", 3, 4, N), B, N, 1)
+    tokens = rng.integers(0, 6, size=(B, N)).astype(np.int32)           # small alphabet: many matches, duplicates
+    tt = rng.integers(0, 6, size=(B, N)).astype(np.int32)
+    for eos in (-1, 3):
+        o = orc.walk(tokens, parent, tt, eos)
+        g = fg.fg_spec_accept(torch.as_tensor(tokens).cuda(), torch.as_tensor(parent).cuda(),
+                              row_argmax=torch.as_tensor(tt.reshape(-1)).cuda(), eos_id=eos)
+        torch.cuda.synchronize()
+        for a, b in zip(o, g):
+            assert np.array_equal(a, b.cpu().numpy())
+    # kv_compact leaves sequences with a malformed path alone
+    model = dict(n_layers=1, n_kv_heads=2, head_dim=64, dtype="fp32")
+    table, n_pages = gen.make_page_table(np.array([5, 5]), 8, 16, 0)
+    kv = fg.KVCache(model, table, n_pages)
+    kv.k_pool.normal_(); kv.v_pool.normal_()
+    kv.seq_len.fill_(5)
+    k0 = kv.k_pool.clone()
+    path = torch.tensor([[0, 3, 2, -1], [0, 2, 3, -1]], dtype=torch.int32).cuda()
+    fg.fg_kv_compact(kv, np.array([0, 1], np.int32), torch.tensor([2, 2], dtype=torch.int32).cuda(), path)
+    torch.cuda.synchronize()
+    assert kv.seq_len.tolist() == [5, 8]
+    ka, _ = kv.read(0, 9)
+    kv2 = k0
+    assert torch.equal(kv.k_pool[:, table[0, 0]], kv2[:, table[0, 0]])
+
+
+def test_empty_batch_and_capacity_errors(H):
+    import paper_2509_21792_amd as fg
+    pair = H.Pair(configs.TINY, seed=0, oracle_side=False)
+    st = H.State(pair, configs.TINY, np.array([4, 4], np.int32), 4, seed=0)
+    ws = pair.gm.workspace(8, st.cap)
+    out = fg.fg_spec_verify(pair.gm, st.kv, np.zeros(0, np.int32), np.zeros((0, 3), np.int32), np.zeros((0, 3), np.int32), ws)
+    with pytest.raises(fg.FgError):    # more nodes than the ancestor mask holds
+        fg.fg_spec_verify(pair.gm, st.kv, st.slot, np.zeros((2, 65), np.int32), np.zeros((2, 65), np.int32), ws)
+    with pytest.raises(fg.FgError):    # workspace too small
+        fg.fg_spec_verify(pair.gm, st.kv, st.slot, np.zeros((2, 3), np.int32), np.full((2, 3), -1, np.int32), ws[:1024])
+    with pytest.raises(fg.FgError):    # bound beyond the capacity
+        fg.fg_spec_verify(pair.gm, st.kv, st.slot, np.zeros((2, 3), np.int32), np.full((2, 3), -1, np.int32), ws,
+                          max_seq_len=10 ** 6)
