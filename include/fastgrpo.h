@@ -14,8 +14,10 @@
  *  - All device work is enqueued on the caller's stream (a hipStream_t passed as void*); calls are
  *    asynchronous and outputs are valid once the caller has synchronised that stream.  The library never
  *    allocates or frees device memory after fg_model_create (which allocates one RoPE table).
- *  - dtype FG_F32: every tensor fp32.  dtype FG_BF16: weights, activations and KV are bf16, accumulation,
- *    the residual stream, softmax and norm statistics are fp32.
+ *  - dtype FG_F32: every tensor fp32.  dtype FG_BF16 / FG_F16: weights, activations and KV are bf16 / fp16,
+ *    accumulation, the residual stream, softmax and norm statistics are fp32.  The two 16-bit modes run the
+ *    same kernels at the same MFMA rate and move the same bytes; fp16 keeps 3 more mantissa bits per
+ *    activation rounding (bf16-valued weights and KV are exactly representable in fp16 down to 6e-5).
  *  - A sequence's cache holds the K/V of all its tokens but the last emitted one, which is the root
  *    (node 0) of the next step's tree.  In-round node i of a sequence of committed length L lives in cache
  *    slot L + i at position L + depth(i), and attends to positions 0..L-1 and to its in-round ancestors
@@ -39,7 +41,7 @@ typedef enum {
     FG_ERR_UNIMPLEMENTED = -5
 } fg_status;
 
-enum { FG_F32 = 0, FG_BF16 = 1 };
+enum { FG_F32 = 0, FG_BF16 = 1, FG_F16 = 2 };
 enum { FG_MAX_NODES = 64 };                 /* in-round nodes per sequence (ancestor sets are 64-bit masks) */
 enum { FG_ACCEPT_GREEDY = 0, FG_ACCEPT_SAMPLE_MATCH = 1, FG_ACCEPT_REJECT = 2 };
 
@@ -47,7 +49,7 @@ typedef struct fg_model fg_model;           /* opaque */
 
 typedef struct {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
-    int32_t dtype;                          /* FG_F32 or FG_BF16                                            */
+    int32_t dtype;                          /* FG_F32, FG_BF16 or FG_F16                                    */
     int32_t max_pos;                        /* positions 0..max_pos-1 get a RoPE table entry                */
     float rms_eps, rope_theta;
 } fg_model_cfg;
@@ -118,7 +120,7 @@ int32_t fg_plan(int32_t B_cur, float C_peak, float alpha, int32_t K_max, int32_t
 /*
  * Weight packing (one-time, on the stream).  src is [n_out, n_in] row-major in `dtype`; with src2 != NULL
  * the logical matrix is [2 n_out, n_in] with rows interleaved in blocks of 32 (32 of src, 32 of src2, ...),
- * which is how gate and up are fused.  FG_F32: dst is that logical matrix row-major.  FG_BF16: dst holds it
+ * which is how gate and up are fused.  FG_F32: dst is that logical matrix row-major.  16-bit dtypes: dst holds it
  * as MFMA operand fragments: tile (n / 32, k / 16) is 1 KiB, lane ((k % 16) / 8) * 32 + n % 32 holds 8
  * consecutive k; the tiles of one 32-row band are contiguous in k.  Needs n_out % 32 == 0 and
  * n_in % 64 == 0 (FG_ERR_SHAPE).  dst has fg_packed_bytes(...) bytes and must not alias src.
@@ -241,7 +243,8 @@ int32_t fg_gemm(int32_t dtype, const void *x, const void *w_packed, void *out, i
                 int32_t n_in, int32_t epilogue, int32_t split_k, int32_t *split_k_used, void *stream);
 int32_t fg_attention(const fg_kv_cache *kv, int32_t layer, const fg_tree *tree, int32_t n_q_heads, const void *q,
                      void *out, void *workspace, int64_t workspace_bytes, void *stream);
-int64_t fg_attention_workspace_bytes(int32_t B, int32_t N, int32_t n_q_heads, int32_t head_dim, int32_t max_seq_len);
+int64_t fg_attention_workspace_bytes(int32_t B, int32_t N, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                     int32_t max_seq_len);
 
 #ifdef __cplusplus
 }

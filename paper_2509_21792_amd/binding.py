@@ -10,7 +10,7 @@ import os
 import numpy as np
 import torch
 
-FG_F32, FG_BF16 = 0, 1
+FG_F32, FG_BF16, FG_F16 = 0, 1, 2
 FG_MAX_NODES = 64
 ACCEPT_GREEDY, ACCEPT_SAMPLE_MATCH, ACCEPT_REJECT = 0, 1, 2
 
@@ -65,7 +65,7 @@ def lib():
         L.fg_workspace_bytes.restype = C.c_int64
         L.fg_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
         L.fg_attention_workspace_bytes.restype = C.c_int64
-        L.fg_attention_workspace_bytes.argtypes = [C.c_int32] * 5
+        L.fg_attention_workspace_bytes.argtypes = [C.c_int32] * 6
         L.fg_plan.argtypes = [C.c_int32, C.c_float, C.c_float, C.c_int32, C.c_int32, C.c_int32] + [C.POINTER(C.c_int32)] * 3
         L.fg_pack_weight.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p]
         L.fg_model_create.argtypes = [C.POINTER(ModelCfg), C.POINTER(Weights), C.POINTER(C.c_void_p)]
@@ -105,11 +105,15 @@ def _stream():
 
 
 def _tdtype(dtype):
-    return torch.bfloat16 if dtype == FG_BF16 else torch.float32
+    return {FG_F32: torch.float32, FG_BF16: torch.bfloat16, FG_F16: torch.float16}[dtype]
 
 
 def dtype_code(name):
-    return FG_BF16 if name == "bf16" else FG_F32
+    return {"fp32": FG_F32, "bf16": FG_BF16, "fp16": FG_F16}[name]
+
+
+def _code_of(t):
+    return {torch.float32: FG_F32, torch.bfloat16: FG_BF16, torch.float16: FG_F16}[t.dtype]
 
 
 # ---- host-only ---------------------------------------------------------------------------------------------
@@ -296,7 +300,7 @@ def fg_kv_compact(kv, slot, accept_len, path, feature_in=None, d_model=0):
     fdt = kv.dtype
     if feature_in is not None:
         fout = torch.empty((B, N, d_model), dtype=feature_in.dtype, device=dev)
-        fdt = FG_BF16 if feature_in.dtype == torch.bfloat16 else FG_F32
+        fdt = _code_of(feature_in)
     _check(lib().fg_kv_compact(C.byref(kv.c), _p(slot), _p(accept_len), _p(path), B, N, _p(feature_in), _p(fout), d_model,
                                fdt, _stream()))
     return fout
@@ -366,7 +370,7 @@ def fg_attention(kv, layer, slot, parent, B, N, n_q_heads, q, n_prev=0, max_seq_
     slot, parent = _dev_i32(slot, dev), _dev_i32(parent, dev)
     hd = kv.cfg["head_dim"]
     cap = kv.max_pages * kv.page_size
-    ws = torch.empty(lib().fg_attention_workspace_bytes(B, N, n_q_heads, hd, max_seq_len or cap), dtype=torch.uint8, device=dev)
+    ws = torch.empty(lib().fg_attention_workspace_bytes(B, N, n_q_heads, kv.cfg["n_kv_heads"], hd, max_seq_len or cap), dtype=torch.uint8, device=dev)
     out = torch.empty_like(q)
     tree = _tree(slot, None, parent, B, N, n_prev, max_seq_len)
     _check(lib().fg_attention(C.byref(kv.c), layer, C.byref(tree), n_q_heads, _p(q), _p(out), _p(ws), ws.numel(), _stream()))

@@ -23,7 +23,7 @@ int32_t fail(int32_t code, const char *fmt, ...)
 
 // launchers defined in the other translation units and not listed in fg_common.h
 int32_t launch_tree_prep_ex(const fg_tree *t, const int32_t *seq_len, int n_slots, TreeDev td, hipStream_t st);
-int32_t launch_swiglu_partials_bf16(const float *gu, int S, void *act, int M, int F, hipStream_t st);
+int32_t launch_swiglu_partials(int32_t dtype, const float *gu, int S, void *act, int M, int F, hipStream_t st);
 int32_t launch_attention_simple(const fg_kv_cache *kv, int layer, const fg_tree *t, TreeDev td, int Hq, const void *q, void *out,
                                 int max_keys, hipStream_t st);
 int32_t launch_attention_mfma(const fg_kv_cache *kv, int layer, const fg_tree *t, TreeDev td, int Hq, const void *q, void *out,
@@ -46,7 +46,7 @@ int32_t launch_frontier(int B, int K_in, int K, const int32_t *child_tok, const 
 int32_t launch_build_tree(const int32_t *cand_tok, const int32_t *cand_parent, const float *cand_score, int B, int C, int stride,
                           int N, int32_t *tokens, int32_t *parent, int32_t *sel, hipStream_t st);
 int32_t launch_commit_len(int32_t *seq_len, const int32_t *slot, const int32_t *n_commit, int B, int n_slots, hipStream_t st);
-int gemm_bf16_split_for(int M, int N, int K);
+int gemm_mfma_split_for(int M, int N, int K);
 
 }  // namespace fg
 
@@ -78,9 +78,9 @@ struct Carver {
 };
 
 // split-K factor the library will use for each GEMM of the step (0 = not a partial-sum GEMM)
-int split_for(const fg_model_cfg &c, int M, int N, int K) { return c.dtype == FG_BF16 ? gemm_bf16_split_for(M, N, K) : 1; }
+int split_for(const fg_model_cfg &c, int M, int N, int K) { return is16(c.dtype) ? gemm_mfma_split_for(M, N, K) : 1; }
 
-bool gate_up_fused(const fg_model_cfg &c, int M) { return c.dtype == FG_BF16 && M > 256; }
+bool gate_up_fused(const fg_model_cfg &c, int M) { return is16(c.dtype) && M > 256; }
 
 int64_t partial_floats(const fg_model_cfg &c, int M, bool is_draft)
 {
@@ -137,7 +137,7 @@ int64_t carve_step(const fg_model_cfg &c, int M, int max_keys, int B, int N, boo
 
 int32_t gemm_any(const fg_model_cfg &c, const void *x, const void *w, float *partials, int M, int N, int K, int *S, hipStream_t st)
 {
-    if (c.dtype == FG_BF16) return launch_gemm_bf16(x, w, partials, M, N, K, 0, 0, S, st);
+    if (is16(c.dtype)) return launch_gemm_mfma(c.dtype, x, w, partials, M, N, K, 0, 0, S, st);
     *S = 1;
     return launch_gemm_f32((const float *)x, (const float *)w, partials, M, N, K, st);
 }
@@ -207,10 +207,10 @@ int32_t run_layers(const fg_model *m, fg_kv_cache *kv, const fg_tree *t, const S
         if ((rc = gemm_any(c, w.att, m->wo[l], w.partials, M, d, hq, &S, st))) return rc;
         if ((rc = launch_add_rmsnorm(c.dtype, w.h, w.partials, S, 0, m->norm_ffn[l], w.a, nullptr, M, d, c.rms_eps, st))) return rc;
         if (gate_up_fused(c, M)) {
-            if ((rc = launch_gemm_bf16(w.a, m->wgu[l], w.act, M, 2 * F, d, 1, 1, nullptr, st))) return rc;
+            if ((rc = launch_gemm_mfma(c.dtype, w.a, m->wgu[l], w.act, M, 2 * F, d, 1, 1, nullptr, st))) return rc;
         } else {
             if ((rc = gemm_any(c, w.a, m->wgu[l], w.partials, M, 2 * F, d, &S, st))) return rc;
-            if (c.dtype == FG_BF16) rc = launch_swiglu_partials_bf16(w.partials, S, w.act, M, F, st);
+            if (is16(c.dtype)) rc = launch_swiglu_partials(c.dtype, w.partials, S, w.act, M, F, st);
             else rc = launch_swiglu_f32(w.partials, (float *)w.act, M, F, st);
             if (rc) return rc;
         }
@@ -268,7 +268,7 @@ int32_t fg_model_create(const fg_model_cfg *cfg, const fg_weights *w, fg_model *
 {
     if (!cfg || !w || !out) return fail(FG_ERR_INVALID_ARG, "fg_model_create: NULL argument");
     const fg_model_cfg &c = *cfg;
-    if (c.dtype != FG_F32 && c.dtype != FG_BF16) return fail(FG_ERR_INVALID_ARG, "unknown dtype %d", c.dtype);
+    if (!dtype_ok(c.dtype)) return fail(FG_ERR_INVALID_ARG, "unknown dtype %d", c.dtype);
     if (c.n_layers < 1 || c.d_model < 1 || c.n_q_heads < 1 || c.n_kv_heads < 1 || c.d_ffn < 1 || c.vocab < 1 || c.max_pos < 1)
         return fail(FG_ERR_INVALID_ARG, "model sizes must be positive");
     if (c.head_dim != 64 && c.head_dim != 128) return fail(FG_ERR_SHAPE, "head_dim must be 64 or 128 (got %d)", c.head_dim);
@@ -360,7 +360,7 @@ int32_t fg_spec_verify(fg_model *m, fg_kv_cache *kv, const fg_tree *tree, float 
     if ((rc = launch_add_rmsnorm(c.dtype, w.h, w.partials, S, 0, m->final_norm, feat, nullptr, M, c.d_model, c.rms_eps, st))) return rc;
     float *lg = logits ? logits : w.logits;
     if (lg) {
-        if (c.dtype == FG_BF16) rc = launch_gemm_bf16(feat, m->lm_head, lg, M, c.vocab, c.d_model, 0, 1, nullptr, st);
+        if (is16(c.dtype)) rc = launch_gemm_mfma(c.dtype, feat, m->lm_head, lg, M, c.vocab, c.d_model, 0, 1, nullptr, st);
         else rc = launch_gemm_f32((const float *)feat, (const float *)m->lm_head, lg, M, c.vocab, c.d_model, st);
         if (rc) return rc;
         if (row_argmax || row_top2)
@@ -420,7 +420,7 @@ int32_t fg_kv_compact(fg_kv_cache *kv, const int32_t *slot, const int32_t *accep
     if (B == 0) return FG_OK;
     if (!slot || !accept_len || !path) return fail(FG_ERR_INVALID_ARG, "fg_kv_compact: NULL input");
     if ((feature_in != nullptr) != (feature_out != nullptr)) return fail(FG_ERR_INVALID_ARG, "feature_in and feature_out go together");
-    if (kv->dtype != FG_F32 && kv->dtype != FG_BF16) return fail(FG_ERR_INVALID_ARG, "unknown cache dtype");
+    if (!dtype_ok(kv->dtype)) return fail(FG_ERR_INVALID_ARG, "unknown cache dtype");
     return launch_kv_compact(kv, slot, accept_len, path, B, N, feature_in, feature_out, d_model, feat_dtype, (hipStream_t)stream);
 }
 
@@ -454,7 +454,7 @@ int32_t fg_draft_step(fg_model *target, fg_model *draft, fg_kv_cache *draft_kv, 
     void *hid = out_feature ? out_feature : w.feat;
     if ((rc = launch_add_rmsnorm(c.dtype, w.h, w.partials, S, 0, draft->norm_attn[0], nullptr, hid, M, d, c.rms_eps, st))) return rc;
     if (child_tok) {
-        if (c.dtype == FG_BF16) rc = launch_gemm_bf16(hid, target->lm_head, w.logits, M, c.vocab, d, 0, 1, nullptr, st);
+        if (is16(c.dtype)) rc = launch_gemm_mfma(c.dtype, hid, target->lm_head, w.logits, M, c.vocab, d, 0, 1, nullptr, st);
         else rc = launch_gemm_f32((const float *)hid, (const float *)target->lm_head, w.logits, M, c.vocab, d, st);
         if (rc) return rc;
         if ((rc = launch_topk_logp(w.logits, M, c.vocab, K_draft, child_tok, child_logp, st))) return rc;
@@ -494,7 +494,7 @@ int32_t fg_gemm(int32_t dtype, const void *x, const void *w_packed, void *out, i
 {
     if (!x || !w_packed || !out || M < 0 || n_out < 1 || n_in < 1) return fail(FG_ERR_INVALID_ARG, "fg_gemm: bad argument");
     if (M == 0) return FG_OK;
-    if (dtype == FG_BF16) return launch_gemm_bf16(x, w_packed, out, M, n_out, n_in, epilogue, split_k, split_k_used, (hipStream_t)stream);
+    if (is16(dtype)) return launch_gemm_mfma(dtype, x, w_packed, out, M, n_out, n_in, epilogue, split_k, split_k_used, (hipStream_t)stream);
     if (dtype == FG_F32) {
         if (epilogue != 0) return fail(FG_ERR_UNIMPLEMENTED, "fp32 GEMM has no fused epilogue");
         if (split_k_used) *split_k_used = 1;
@@ -503,10 +503,12 @@ int32_t fg_gemm(int32_t dtype, const void *x, const void *w_packed, void *out, i
     return fail(FG_ERR_INVALID_ARG, "unknown dtype %d", dtype);
 }
 
-int64_t fg_attention_workspace_bytes(int32_t B, int32_t N, int32_t n_q_heads, int32_t head_dim, int32_t max_seq_len)
+int64_t fg_attention_workspace_bytes(int32_t B, int32_t N, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                     int32_t max_seq_len)
 {
-    // the kv-head count only lowers the need; size for the worst case of one kv head per query head group of 1
-    return (int64_t)B * N * 8 + (int64_t)B * N * 8 + 512 + attention_mfma_ws_bytes(B, N, n_q_heads, 1, head_dim, max_seq_len) + 4096;
+    if (B < 1 || N < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads) return 0;
+    return align_up((int64_t)B * N * 4, 256) + align_up((int64_t)B * N * 8, 256) +
+           attention_mfma_ws_bytes(B, N, n_q_heads, n_kv_heads, head_dim, max_seq_len) + 1024;
 }
 
 int32_t fg_attention(const fg_kv_cache *kv, int32_t layer, const fg_tree *tree, int32_t n_q_heads, const void *q, void *out,

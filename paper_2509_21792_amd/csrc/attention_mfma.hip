@@ -1,11 +1,324 @@
-// placeholder until the MFMA kernel lands
+// Tree-masked GQA attention over the paged cache on MFMA (16-bit operands, fp32 softmax and accumulation).
+//
+// Work item = (sequence, kv head, chunk of key positions).  All query rows that share the kv head -- the
+// G = Hq / Hkv query heads of every new node, G * N rows -- ride the same pass over K and V, so each K/V byte
+// is fetched from HBM once per (sequence, kv head) whatever N is.  A wave owns QW tiles of 16 query rows and
+// walks the chunk 32 key positions (two 16-token pages) at a time:
+//   S^T = K . Q^T        v_mfma_f32_16x16x32, A = K page rows straight from global memory (token-major pages),
+//                        B = Q fragments held in registers for the whole pass;
+//   online softmax       per query column; lanes l, l+16, l+32, l+48 hold the same column, 4 keys each;
+//   O^T += V^T . P^T     A = V^T fragments straight from global memory (pages store V transposed, so the 4
+//                        tokens a lane needs are 8 contiguous bytes), B = P^T taken from the S^T accumulators
+//                        in place: the contraction order is chosen so that no cross-lane shuffle is needed.
+// The contraction over head_dim is permuted as well (lane group g covers the contiguous quarter g of the row)
+// so that every K load is 64 contiguous bytes per lane.  Chunks write (m, l, O) partials; a merge kernel
+// combines them.  Key positions >= committed length are in-round nodes and are masked per query row with the
+// node's 64-bit ancestor set.
 #include "fg_common.h"
+
 namespace fg {
-bool attention_mfma_supported(const fg_kv_cache *, int, int) { return false; }
-int64_t attention_mfma_ws_bytes(int, int, int, int, int, int) { return 0; }
-int32_t launch_attention_mfma(const fg_kv_cache *, int, const fg_tree *, TreeDev, int, const void *, void *, int, void *, int64_t,
-                              hipStream_t)
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+union Frag16 {
+    uint4 u;
+    uint2 u2[2];
+    bf16x8_t b;
+    f16x8_t h;
+    uint16_t s[8];
+};
+
+template <typename T> __device__ __forceinline__ f32x4_t mfma16(const Frag16 &a, const Frag16 &b, f32x4_t c);
+template <> __device__ __forceinline__ f32x4_t mfma16<bf16_t>(const Frag16 &a, const Frag16 &b, f32x4_t c)
 {
-    return fail(FG_ERR_UNIMPLEMENTED, "MFMA attention not built");
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.b, b.b, c, 0, 0, 0);
 }
+template <> __device__ __forceinline__ f32x4_t mfma16<f16_t>(const Frag16 &a, const Frag16 &b, f32x4_t c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, b.h, c, 0, 0, 0);
+}
+template <typename T> __device__ __forceinline__ uint16_t bits16(float v);
+template <> __device__ __forceinline__ uint16_t bits16<bf16_t>(float v) { return f2bf(v); }
+template <> __device__ __forceinline__ uint16_t bits16<f16_t>(float v)
+{
+    f16_t h = (f16_t)v;
+    return *reinterpret_cast<uint16_t *>(&h);
+}
+
+struct AttnPlan {
+    int QR;        // padded query rows per (sequence, kv head): multiple of 16
+    int waves;     // waves per block
+    int CK;        // key positions per chunk (multiple of 32)
+    int n_chunks;  // chunks covering max_keys
+};
+
+template <int QW>
+static AttnPlan plan_attention(int B, int N, int Hq, int Hkv, int max_keys)
+{
+    AttnPlan p;
+    const int G = Hq / Hkv, QT = (G * N + 15) / 16;
+    p.QR = QT * 16;
+    p.waves = (QT + QW - 1) / QW;
+    const long pairs = (long)B * Hkv * p.waves;
+    long splits = (2048 + pairs - 1) / pairs;
+    if (splits < 1) splits = 1;
+    long ck = (max_keys + splits - 1) / splits;
+    long ck_min = 4L * p.QR;              // keeps the partial (m, l, O) traffic under ~1/4 of the K/V traffic
+    if (ck < ck_min) ck = ck_min;
+    ck = (ck + 31) / 32 * 32;
+    p.CK = (int)ck;
+    p.n_chunks = (max_keys + p.CK - 1) / p.CK;
+    if (p.n_chunks < 1) p.n_chunks = 1;
+    return p;
+}
+
+static int pick_qw(int N, int Hq, int Hkv) { return ((Hq / Hkv) * N + 15) / 16 <= 2 ? 2 : 4; }
+
+template <typename T, int HD, int QW>
+__global__ __launch_bounds__(64) void attn_mfma_kernel(const T *__restrict__ q, const T *__restrict__ k_pool,
+                                                         const T *__restrict__ v_pool, const int32_t *__restrict__ page_table,
+                                                         const int32_t *__restrict__ seq_len, const int32_t *__restrict__ slot,
+                                                         const uint64_t *__restrict__ mask, float *__restrict__ part_o,
+                                                         float *__restrict__ part_ml, int layer, int n_pages, int n_slots,
+                                                         int max_pages, int N, int n_prev, int Hq, int Hkv, int QR, int CK,
+                                                         int n_chunks, int n_items, int waves, float scale)
+{
+    constexpr int KK = HD / 32;   // MFMAs per S^T tile (contraction over head_dim)
+    constexpr int HT = HD / 16;   // 16-row tiles of O^T
+    // One wave per block.  Blocks are dealt to the 8 XCDs round-robin, so the waves that share one
+    // (sequence, kv head, chunk) item get block ids that differ by multiples of 8: they land on the same XCD
+    // and the item's K/V is fetched into one L2 only.
+    const int grp8 = blockIdx.x / (8 * waves), within = blockIdx.x % (8 * waves);
+    const int item = grp8 * 8 + (within & 7), wave = within >> 3;
+    if (item >= n_items) return;
+    const int chunk = item % n_chunks, hk = (item / n_chunks) % Hkv, b = item / (n_chunks * Hkv);
+    const int lane = threadIdx.x;
+    const int c = lane & 15, grp = lane >> 4;
+    const int G = Hq / Hkv, n_tot = n_prev + N, rows = G * N;
+    const int s = min(max(slot[b], 0), n_slots - 1);
+    const int L = seq_len[s];
+    const int total = min(L + n_tot, max_pages * 16);
+    const int t_begin = chunk * CK;
+    if (t_begin >= total) return;
+    const int t_end = min(t_begin + CK, total);
+    const int qt0 = wave * QW;
+    if (qt0 * 16 >= rows) return;
+
+    // query fragments and per-column masks
+    Frag16 qf[QW][KK];
+    uint64_t qmask[QW];
+#pragma unroll
+    for (int w = 0; w < QW; w++) {
+        int qi = (qt0 + w) * 16 + c;
+        bool ok = qi < rows;
+        int j = ok ? qi / G : 0, g = ok ? qi % G : 0;
+        qmask[w] = ok ? mask[(size_t)b * N + j] : 0ull;
+        const T *qp = q + ((size_t)b * N + j) * Hq * HD + (size_t)(hk * G + g) * HD + grp * (HD / 4);
+#pragma unroll
+        for (int kk = 0; kk < KK; kk++) {
+            if (ok) qf[w][kk].u = *reinterpret_cast<const uint4 *>(qp + kk * 8);
+            else qf[w][kk].u = make_uint4(0, 0, 0, 0);
+        }
+    }
+
+    float m_run[QW], l_run[QW];
+    f32x4_t o[QW][HT];
+#pragma unroll
+    for (int w = 0; w < QW; w++) {
+        m_run[w] = -INFINITY;
+        l_run[w] = 0.f;
+#pragma unroll
+        for (int h = 0; h < HT; h++) o[w][h] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+    }
+
+    const size_t head_stride = (size_t)16 * HD;  // elements per (page, kv head)
+    const int32_t *pt = page_table + (size_t)s * max_pages;
+
+    for (int t0 = t_begin; t0 < t_end; t0 += 32) {
+        // the two pages of this step (the second may lie beyond the sequence: clamp, its keys are masked)
+        int pi0 = t0 >> 4, pi1 = min(pi0 + 1, max_pages - 1);
+        int pg0 = min(max(pt[pi0], 0), n_pages - 1), pg1 = min(max(pt[pi1], 0), n_pages - 1);
+        const T *kb[2], *vb[2];
+        kb[0] = k_pool + (((size_t)layer * n_pages + pg0) * Hkv + hk) * head_stride;
+        kb[1] = k_pool + (((size_t)layer * n_pages + pg1) * Hkv + hk) * head_stride;
+        vb[0] = v_pool + (((size_t)layer * n_pages + pg0) * Hkv + hk) * head_stride;
+        vb[1] = v_pool + (((size_t)layer * n_pages + pg1) * Hkv + hk) * head_stride;
+
+        Frag16 kf[2][KK];
+#pragma unroll
+        for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+            for (int kk = 0; kk < KK; kk++)
+                kf[kt][kk].u = *reinterpret_cast<const uint4 *>(kb[kt] + (size_t)c * HD + grp * (HD / 4) + kk * 8);
+        Frag16 vf[HT];
+#pragma unroll
+        for (int h = 0; h < HT; h++) {
+            vf[h].u2[0] = *reinterpret_cast<const uint2 *>(vb[0] + (size_t)(h * 16 + c) * 16 + grp * 4);
+            vf[h].u2[1] = *reinterpret_cast<const uint2 *>(vb[1] + (size_t)(h * 16 + c) * 16 + grp * 4);
+        }
+        const bool tail = t0 + 32 > t_end;       // some key positions of this step are outside the chunk
+        const bool tree = t0 + 32 > L;           // some key positions are in-round nodes (masked per row)
+        if (tail) {
+            // values of positions that are never attended may be anything: zero them so 0 * x stays 0
+#pragma unroll
+            for (int h = 0; h < HT; h++)
+#pragma unroll
+                for (int jj = 0; jj < 8; jj++) {
+                    int t = t0 + (jj >> 2) * 16 + grp * 4 + (jj & 3);
+                    if (t >= t_end) vf[h].s[jj] = 0;
+                }
+        }
+
+#pragma unroll
+        for (int w = 0; w < QW; w++) {
+            if ((qt0 + w) * 16 >= rows) continue;
+            f32x4_t sacc[2];
+#pragma unroll
+            for (int kt = 0; kt < 2; kt++) {
+                sacc[kt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kk = 0; kk < KK; kk++) sacc[kt] = mfma16<T>(kf[kt][kk], qf[w][kk], sacc[kt]);
+            }
+            float sv[8];
+            float mx = -INFINITY;
+#pragma unroll
+            for (int jj = 0; jj < 8; jj++) {
+                float v = sacc[jj >> 2][jj & 3] * scale;
+                if (tail || tree) {
+                    int t = t0 + (jj >> 2) * 16 + grp * 4 + (jj & 3);
+                    bool valid = t < t_end && (t < L || ((qmask[w] >> (t - L)) & 1ull));
+                    v = valid ? v : -INFINITY;
+                }
+                sv[jj] = v;
+                mx = fmaxf(mx, v);
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_new = fmaxf(m_run[w], mx);
+            const float m_use = m_new == -INFINITY ? 0.f : m_new;   // nothing valid yet: keep everything at zero
+            const float alpha = __expf(m_run[w] - m_use);           // exp(-inf) = 0 on the first valid step
+            float ps = 0.f;
+            Frag16 pf;
+#pragma unroll
+            for (int jj = 0; jj < 8; jj++) {
+                float p = __expf(sv[jj] - m_use);
+                ps += p;
+                pf.s[jj] = bits16<T>(p);
+            }
+            ps += __shfl_xor(ps, 16, 64);
+            ps += __shfl_xor(ps, 32, 64);
+            l_run[w] = l_run[w] * alpha + ps;
+            m_run[w] = m_new;
+#pragma unroll
+            for (int h = 0; h < HT; h++) {
+                o[w][h] = o[w][h] * alpha;
+                o[w][h] = mfma16<T>(vf[h], pf, o[w][h]);
+            }
+        }
+    }
+
+    // partials: O^T lane holds head_dim rows h*16 + 4*grp + i of query column c
+#pragma unroll
+    for (int w = 0; w < QW; w++) {
+        int qi = (qt0 + w) * 16 + c;
+        if (qi >= rows) continue;
+        size_t row = (((size_t)b * Hkv + hk) * n_chunks + chunk) * QR + qi;
+#pragma unroll
+        for (int h = 0; h < HT; h++)
+            *reinterpret_cast<f32x4_t *>(part_o + row * HD + h * 16 + grp * 4) = o[w][h];
+        if (grp == 0) {
+            part_ml[row * 2] = m_run[w];
+            part_ml[row * 2 + 1] = l_run[w];
+        }
+    }
+}
+
+// Combine the chunks of one (row, query head): out = sum_c O_c e^(m_c - m) / sum_c l_c e^(m_c - m).
+template <typename T, int HD>
+__global__ __launch_bounds__(64) void attn_merge_kernel(const float *__restrict__ part_o, const float *__restrict__ part_ml,
+                                                        const int32_t *__restrict__ seq_len, const int32_t *__restrict__ slot,
+                                                        T *__restrict__ out, int n_slots, int max_pages, int N, int n_prev,
+                                                        int Hq, int Hkv, int QR, int CK, int n_chunks)
+{
+    const int r = blockIdx.x, hq = blockIdx.y, lane = threadIdx.x;
+    const int b = r / N, j = r % N, G = Hq / Hkv, hk = hq / G, g = hq % G;
+    const int s = min(max(slot[b], 0), n_slots - 1);
+    const int total = min(seq_len[s] + n_prev + N, max_pages * 16);
+    const int nc = min((total + CK - 1) / CK, n_chunks);
+    const int qi = j * G + g;
+    float m = -INFINITY;
+    for (int ch = 0; ch < nc; ch++) m = fmaxf(m, part_ml[((((size_t)b * Hkv + hk) * n_chunks + ch) * QR + qi) * 2]);
+    float den = 0.f, acc[HD / 64];
+#pragma unroll
+    for (int i = 0; i < HD / 64; i++) acc[i] = 0.f;
+    for (int ch = 0; ch < nc; ch++) {
+        size_t row = (((size_t)b * Hkv + hk) * n_chunks + ch) * QR + qi;
+        float mc = part_ml[row * 2], lc = part_ml[row * 2 + 1];
+        if (lc == 0.f) continue;
+        float wgt = __expf(mc - m);
+        den += lc * wgt;
+#pragma unroll
+        for (int i = 0; i < HD / 64; i++) acc[i] += part_o[row * HD + lane + 64 * i] * wgt;
+    }
+    const float inv = den > 0.f ? 1.f / den : 0.f;
+#pragma unroll
+    for (int i = 0; i < HD / 64; i++) out[(size_t)r * Hq * HD + (size_t)hq * HD + lane + 64 * i] = from_f<T>(acc[i] * inv);
+}
+
+bool attention_mfma_supported(const fg_kv_cache *kv, int Hq, int N)
+{
+    return is16(kv->dtype) && (kv->head_dim == 128 || kv->head_dim == 64) && kv->page_size == 16 &&
+           Hq % kv->n_kv_heads == 0 && Hq / kv->n_kv_heads <= 8 && N >= 1 && N <= FG_MAX_NODES;
+}
+
+int64_t attention_mfma_ws_bytes(int B, int N, int Hq, int Hkv, int hd, int max_keys)
+{
+    if (B < 1 || N < 1 || Hkv < 1 || Hq % Hkv) return 0;
+    AttnPlan p = pick_qw(N, Hq, Hkv) == 2 ? plan_attention<2>(B, N, Hq, Hkv, max_keys) : plan_attention<4>(B, N, Hq, Hkv, max_keys);
+    int64_t rows = (int64_t)B * Hkv * p.n_chunks * p.QR;
+    return align_up(rows * hd * 4, 256) + align_up(rows * 2 * 4, 256);
+}
+
+template <typename T, int HD, int QW>
+static int32_t launch_typed(const fg_kv_cache *kv, int layer, const fg_tree *t, TreeDev td, int Hq, const void *q, void *out,
+                            int max_keys, void *ws, int64_t ws_bytes, hipStream_t st)
+{
+    const int B = t->B, N = t->N, Hkv = kv->n_kv_heads;
+    AttnPlan p = plan_attention<QW>(B, N, Hq, Hkv, max_keys);
+    int64_t rows = (int64_t)B * Hkv * p.n_chunks * p.QR;
+    int64_t need = align_up(rows * HD * 4, 256) + align_up(rows * 2 * 4, 256);
+    if (!ws || ws_bytes < need) return fail(FG_ERR_CAPACITY, "attention workspace too small (%lld < %lld)", (long long)ws_bytes, (long long)need);
+    float *part_o = (float *)ws;
+    float *part_ml = (float *)((char *)ws + align_up(rows * HD * 4, 256));
+    const float scale = 1.0f / sqrtf((float)HD);
+    const int n_items = B * Hkv * p.n_chunks;
+    dim3 grid((unsigned)((n_items + 7) / 8 * 8 * p.waves));
+    hipLaunchKernelGGL((attn_mfma_kernel<T, HD, QW>), grid, dim3(64), 0, st, (const T *)q, (const T *)kv->k_pool,
+                       (const T *)kv->v_pool, kv->page_table, kv->seq_len, t->slot, td.mask, part_o, part_ml, layer, kv->n_pages,
+                       kv->n_slots, kv->max_pages_per_seq, N, t->n_prev, Hq, Hkv, p.QR, p.CK, p.n_chunks, n_items, p.waves,
+                       scale);
+    FG_LAUNCH_CHECK("attn_mfma");
+    hipLaunchKernelGGL((attn_merge_kernel<T, HD>), dim3(B * N, Hq), dim3(64), 0, st, part_o, part_ml, kv->seq_len, t->slot,
+                       (T *)out, kv->n_slots, kv->max_pages_per_seq, N, t->n_prev, Hq, Hkv, p.QR, p.CK, p.n_chunks);
+    FG_LAUNCH_CHECK("attn_merge");
+    return FG_OK;
+}
+
+int32_t launch_attention_mfma(const fg_kv_cache *kv, int layer, const fg_tree *t, TreeDev td, int Hq, const void *q, void *out,
+                              int max_keys, void *ws, int64_t ws_bytes, hipStream_t st)
+{
+    const int qw = pick_qw(t->N, Hq, kv->n_kv_heads);
+#define FG_ATTN(T, HD)                                                                                          \
+    return qw == 2 ? launch_typed<T, HD, 2>(kv, layer, t, td, Hq, q, out, max_keys, ws, ws_bytes, st)           \
+                   : launch_typed<T, HD, 4>(kv, layer, t, td, Hq, q, out, max_keys, ws, ws_bytes, st)
+    if (kv->dtype == FG_BF16) {
+        if (kv->head_dim == 128) { FG_ATTN(bf16_t, 128); } else { FG_ATTN(bf16_t, 64); }
+    } else {
+        if (kv->head_dim == 128) { FG_ATTN(f16_t, 128); } else { FG_ATTN(f16_t, 64); }
+    }
+#undef FG_ATTN
+}
+
 }  // namespace fg

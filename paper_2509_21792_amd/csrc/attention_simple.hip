@@ -70,16 +70,10 @@ int32_t launch_attention_simple(const fg_kv_cache *kv, int layer, const fg_tree 
                                      (int)(64 * 1024 / sizeof(float)) - hd, max_keys);
     const float scale = 1.0f / sqrtf((float)hd);
     dim3 grid(M, Hq);
-    if (kv->dtype == FG_BF16)
-        hipLaunchKernelGGL(attn_simple_kernel<bf16_t>, grid, dim3(64), lds, st, (const bf16_t *)q, (bf16_t *)out,
-                           (const bf16_t *)kv->k_pool, (const bf16_t *)kv->v_pool, kv->page_table, kv->seq_len, t->slot,
-                           td.mask, layer, kv->n_pages, kv->n_slots, kv->max_pages_per_seq, t->N, t->n_prev, Hq,
-                           kv->n_kv_heads, hd, max_keys, scale);
-    else
-        hipLaunchKernelGGL(attn_simple_kernel<float>, grid, dim3(64), lds, st, (const float *)q, (float *)out,
-                           (const float *)kv->k_pool, (const float *)kv->v_pool, kv->page_table, kv->seq_len, t->slot,
-                           td.mask, layer, kv->n_pages, kv->n_slots, kv->max_pages_per_seq, t->N, t->n_prev, Hq,
-                           kv->n_kv_heads, hd, max_keys, scale);
+    FG_DISPATCH(kv->dtype, T, hipLaunchKernelGGL(attn_simple_kernel<T>, grid, dim3(64), lds, st, (const T *)q, (T *)out,
+                                                 (const T *)kv->k_pool, (const T *)kv->v_pool, kv->page_table, kv->seq_len,
+                                                 t->slot, td.mask, layer, kv->n_pages, kv->n_slots, kv->max_pages_per_seq,
+                                                 t->N, t->n_prev, Hq, kv->n_kv_heads, hd, max_keys, scale));
     FG_LAUNCH_CHECK("attn_simple");
     return FG_OK;
 }

@@ -48,10 +48,7 @@ __global__ void embed_kernel(const T *embed, const int32_t *tokens, int vocab, f
 
 int32_t launch_embed(int32_t dtype, const void *embed, const int32_t *tokens, int vocab, float *h, int M, int d, hipStream_t st)
 {
-    if (dtype == FG_BF16)
-        hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(M), dim3(256), 0, st, (const bf16_t *)embed, tokens, vocab, h, d);
-    else
-        hipLaunchKernelGGL(embed_kernel<float>, dim3(M), dim3(256), 0, st, (const float *)embed, tokens, vocab, h, d);
+    FG_DISPATCH(dtype, T, hipLaunchKernelGGL(embed_kernel<T>, dim3(M), dim3(256), 0, st, (const T *)embed, tokens, vocab, h, d));
     FG_LAUNCH_CHECK("embed");
     return FG_OK;
 }
@@ -71,12 +68,8 @@ __global__ void concat_embed_kernel(const T *embed, const int32_t *tokens, int v
 int32_t launch_concat_embed(int32_t dtype, const void *embed, const int32_t *tokens, int vocab, const void *feat, void *cat,
                             int M, int d, hipStream_t st)
 {
-    if (dtype == FG_BF16)
-        hipLaunchKernelGGL(concat_embed_kernel<bf16_t>, dim3(M), dim3(256), 0, st, (const bf16_t *)embed, tokens, vocab,
-                           (const bf16_t *)feat, (bf16_t *)cat, d);
-    else
-        hipLaunchKernelGGL(concat_embed_kernel<float>, dim3(M), dim3(256), 0, st, (const float *)embed, tokens, vocab,
-                           (const float *)feat, (float *)cat, d);
+    FG_DISPATCH(dtype, T, hipLaunchKernelGGL(concat_embed_kernel<T>, dim3(M), dim3(256), 0, st, (const T *)embed, tokens, vocab,
+                                             (const T *)feat, (T *)cat, d));
     FG_LAUNCH_CHECK("concat_embed");
     return FG_OK;
 }
@@ -127,12 +120,8 @@ int32_t launch_add_rmsnorm(int32_t dtype, float *h, const float *partials, int S
                            void *h_copy, int M, int d, float eps, hipStream_t st)
 {
     if (d > NORM_THREADS * NORM_MAX_PER_THREAD) return fail(FG_ERR_SHAPE, "d_model %d too large for the norm kernel", d);
-    if (dtype == FG_BF16)
-        hipLaunchKernelGGL(add_rmsnorm_kernel<bf16_t>, dim3(M), dim3(NORM_THREADS), 0, st, h, partials, S, init,
-                           (const bf16_t *)gain, (bf16_t *)a, (bf16_t *)h_copy, M, d, eps);
-    else
-        hipLaunchKernelGGL(add_rmsnorm_kernel<float>, dim3(M), dim3(NORM_THREADS), 0, st, h, partials, S, init,
-                           (const float *)gain, (float *)a, (float *)h_copy, M, d, eps);
+    FG_DISPATCH(dtype, T, hipLaunchKernelGGL(add_rmsnorm_kernel<T>, dim3(M), dim3(NORM_THREADS), 0, st, h, partials, S, init,
+                                             (const T *)gain, (T *)a, (T *)h_copy, M, d, eps));
     FG_LAUNCH_CHECK("add_rmsnorm");
     return FG_OK;
 }
@@ -189,16 +178,10 @@ int32_t launch_rope_append(int32_t dtype, const float *qkv_partials, int S, cons
                            int layer, const float *rope_tab, int max_pos, int Hq, void *q_out, hipStream_t st)
 {
     int M = t->B * t->N;
-    if (dtype == FG_BF16)
-        hipLaunchKernelGGL(rope_append_kernel<bf16_t>, dim3(M), dim3(256), 0, st, qkv_partials, S, M, t->slot, td.pos,
-                           kv->seq_len, kv->page_table, (bf16_t *)kv->k_pool, (bf16_t *)kv->v_pool, layer, kv->n_pages,
-                           kv->n_slots, kv->max_pages_per_seq, t->N, t->n_prev, Hq, kv->n_kv_heads, kv->head_dim,
-                           (const float2 *)rope_tab, max_pos, (bf16_t *)q_out);
-    else
-        hipLaunchKernelGGL(rope_append_kernel<float>, dim3(M), dim3(256), 0, st, qkv_partials, S, M, t->slot, td.pos,
-                           kv->seq_len, kv->page_table, (float *)kv->k_pool, (float *)kv->v_pool, layer, kv->n_pages,
-                           kv->n_slots, kv->max_pages_per_seq, t->N, t->n_prev, Hq, kv->n_kv_heads, kv->head_dim,
-                           (const float2 *)rope_tab, max_pos, (float *)q_out);
+    FG_DISPATCH(dtype, T, hipLaunchKernelGGL(rope_append_kernel<T>, dim3(M), dim3(256), 0, st, qkv_partials, S, M, t->slot, td.pos,
+                                             kv->seq_len, kv->page_table, (T *)kv->k_pool, (T *)kv->v_pool, layer, kv->n_pages,
+                                             kv->n_slots, kv->max_pages_per_seq, t->N, t->n_prev, Hq, kv->n_kv_heads,
+                                             kv->head_dim, (const float2 *)rope_tab, max_pos, (T *)q_out));
     FG_LAUNCH_CHECK("rope_append");
     return FG_OK;
 }
@@ -222,8 +205,9 @@ int32_t launch_swiglu_f32(const float *gu, float *act, int M, int F, hipStream_t
     return FG_OK;
 }
 
-// sum split-K slabs of an interleaved gate/up output and apply SwiGLU: act[m, f] (bf16)
-__global__ void swiglu_partials_bf16_kernel(const float *gu, int S, bf16_t *act, int M, int F)
+// sum split-K slabs of an interleaved gate/up output and apply SwiGLU: act[m, f] (16-bit)
+template <typename T>
+__global__ void swiglu_partials_kernel(const float *gu, int S, T *act, int M, int F)
 {
     size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (size_t)M * F) return;
@@ -235,14 +219,18 @@ __global__ void swiglu_partials_bf16_kernel(const float *gu, int S, bf16_t *act,
         g += row[64 * t + j];
         u += row[64 * t + 32 + j];
     }
-    act[idx] = f2bf(g / (1.f + __expf(-g)) * u);
+    act[idx] = from_f<T>(g / (1.f + __expf(-g)) * u);
 }
 
-int32_t launch_swiglu_partials_bf16(const float *gu, int S, void *act, int M, int F, hipStream_t st)
+int32_t launch_swiglu_partials(int32_t dtype, const float *gu, int S, void *act, int M, int F, hipStream_t st)
 {
     size_t total = (size_t)M * F;
-    hipLaunchKernelGGL(swiglu_partials_bf16_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, gu, S,
-                       (bf16_t *)act, M, F);
+    if (dtype == FG_BF16)
+        hipLaunchKernelGGL(swiglu_partials_kernel<bf16_t>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, gu, S,
+                           (bf16_t *)act, M, F);
+    else
+        hipLaunchKernelGGL(swiglu_partials_kernel<f16_t>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, gu, S,
+                           (f16_t *)act, M, F);
     FG_LAUNCH_CHECK("swiglu_partials");
     return FG_OK;
 }

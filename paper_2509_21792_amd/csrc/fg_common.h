@@ -24,6 +24,7 @@ int32_t fail(int32_t code, const char *fmt, ...);
 
 // ---- element types --------------------------------------------------------------------------------
 typedef uint16_t bf16_t;  // storage only
+typedef _Float16 f16_t;
 
 __device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
 __device__ __forceinline__ bf16_t f2bf(float f)
@@ -35,11 +36,23 @@ __device__ __forceinline__ bf16_t f2bf(float f)
 template <typename T> __device__ __forceinline__ float to_f(T v);
 template <> __device__ __forceinline__ float to_f<float>(float v) { return v; }
 template <> __device__ __forceinline__ float to_f<bf16_t>(bf16_t v) { return bf2f(v); }
+template <> __device__ __forceinline__ float to_f<f16_t>(f16_t v) { return (float)v; }
 template <typename T> __device__ __forceinline__ T from_f(float v);
 template <> __device__ __forceinline__ float from_f<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16_t from_f<bf16_t>(float v) { return f2bf(v); }
+template <> __device__ __forceinline__ f16_t from_f<f16_t>(float v) { return (f16_t)v; }
 
-static inline size_t dtype_size(int32_t dtype) { return dtype == FG_BF16 ? 2 : 4; }
+static inline size_t dtype_size(int32_t dtype) { return dtype == FG_F32 ? 4 : 2; }
+static inline bool dtype_ok(int32_t dtype) { return dtype == FG_F32 || dtype == FG_BF16 || dtype == FG_F16; }
+static inline bool is16(int32_t dtype) { return dtype == FG_BF16 || dtype == FG_F16; }
+
+// run a statement with T bound to the element type of `dtype`
+#define FG_DISPATCH(dtype, T, ...)                                       \
+    do {                                                                 \
+        if ((dtype) == FG_BF16) { using T = fg::bf16_t; __VA_ARGS__; }   \
+        else if ((dtype) == FG_F16) { using T = fg::f16_t; __VA_ARGS__; } \
+        else { using T = float; __VA_ARGS__; }                           \
+    } while (0)
 static inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
 // ---- wave / block reductions (wave64) -------------------------------------------------------------
@@ -78,8 +91,8 @@ struct TreeDev {             // per-call derived tree data in the workspace
     uint64_t *mask;          // [B*N] in-round ancestors-or-self of each new node (bit i = in-round node i)
 };
 
-int32_t launch_gemm_bf16(const void *x, const void *wp, void *out, int M, int N, int K, int epilogue, int split_k,
-                         int *split_used, hipStream_t st);
+int32_t launch_gemm_mfma(int32_t dtype, const void *x, const void *wp, void *out, int M, int N, int K, int epilogue,
+                         int split_k, int *split_used, hipStream_t st);
 int32_t launch_gemm_f32(const float *x, const float *w, float *out, int M, int N, int K, hipStream_t st);
 int32_t launch_pack(int32_t dtype, const void *src, const void *src2, void *dst, int64_t n_out, int64_t n_in, hipStream_t st);
 

@@ -1,7 +1,8 @@
-// bf16 GEMM on MFMA for gfx950: out = X . W^T with W pre-packed as MFMA operand fragments.
+// 16-bit (bf16 or fp16 operands, fp32 accumulate) GEMM on MFMA for gfx950: out = X . W^T with W pre-packed as
+// MFMA operand fragments.
 //
 // W [N, K] is stored as 1 KiB tiles of 32 rows x 16 k: lane ((k % 16) / 8) * 32 + n % 32 of a tile holds the 8
-// consecutive k of row n -- exactly the per-lane operand of v_mfma_f32_32x32x16_bf16 -- and the tiles of one
+// consecutive k of row n -- exactly the per-lane operand of v_mfma_f32_32x32x16_{bf16,f16} -- and the tiles of one
 // 32-row band are contiguous in k.  A wave therefore streams its band of W straight from HBM into MFMA operand
 // registers with fully coalesced 16-byte loads (1 KiB per wave instruction, no LDS round trip, no swizzle).
 // The activation block X [M, K] (row-major, small or reused) is staged through LDS in the same fragment order,
@@ -15,19 +16,31 @@
 namespace fg {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
 union Frag {
     uint4 u;
-    bf16x8_t v;
+    bf16x8_t b;
+    f16x8_t h;
 };
+
+template <typename T> __device__ __forceinline__ f32x16_t mfma32(const Frag &a, const Frag &b, f32x16_t c);
+template <> __device__ __forceinline__ f32x16_t mfma32<bf16_t>(const Frag &a, const Frag &b, f32x16_t c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.b, b.b, c, 0, 0, 0);
+}
+template <> __device__ __forceinline__ f32x16_t mfma32<f16_t>(const Frag &a, const Frag &b, f32x16_t c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a.h, b.h, c, 0, 0, 0);
+}
 
 constexpr int KT = 4;  // k tiles (of 16) per chunk: 64 k
 
-template <int MT, int NT, int WM, int WN, int EPI>
-__global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(const bf16_t *__restrict__ X,
-                                                                  const uint4 *__restrict__ Wp, void *__restrict__ out,
-                                                                  int M, int N, int K, int chunks_per_split)
+template <typename T, int MT, int NT, int WM, int WN, int EPI>
+__global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(const T *__restrict__ X, const uint4 *__restrict__ Wp,
+                                                                  void *__restrict__ out, int M, int N, int K,
+                                                                  int chunks_per_split)
 {
     constexpr int THREADS = WM * WN * 64;
     constexpr int BM = WM * MT * 32;
@@ -109,7 +122,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(const bf16_t *__
                     xf.u = xs[buf][(((wm * MT + i) * KT + kt) << 6) + lane];
 #pragma unroll
                     for (int j = 0; j < NT; j++)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf.v, w[j][kt].v, acc[i][j], 0, 0, 0);
+                        acc[i][j] = mfma32<T>(xf, w[j][kt], acc[i][j]);
                 }
 #pragma unroll
                 for (int j = 0; j < NT; j++) w[j][kt].u = wband[j][(size_t)(nxt * KT + kt) * 64];
@@ -138,7 +151,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(const bf16_t *__
         }
     } else {
         // gate / up tiles alternate: tile 2t = gate, 2t + 1 = up, both for output columns 32 t .. 32 t + 31
-        bf16_t *o = reinterpret_cast<bf16_t *>(out);
+        T *o = reinterpret_cast<T *>(out);
         const int F = N >> 1;
 #pragma unroll
         for (int j = 0; j < NT; j += 2) {
@@ -153,7 +166,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(const bf16_t *__
                     if (m < M) {
                         float g = acc[i][j][r], u = acc[i][(j + 1) % NT][r];
                         float s = g / (1.f + __expf(-g));
-                        o[(size_t)m * F + f] = f2bf(s * u);
+                        o[(size_t)m * F + f] = from_f<T>(s * u);
                     }
                 }
         }
@@ -162,17 +175,15 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(const bf16_t *__
 
 // ---- host side -----------------------------------------------------------------------------------------
 
-struct GemmShape { int mt, nt, wm, wn; };
-
-template <int MT, int NT, int WM, int WN, int EPI>
+template <typename T, int MT, int NT, int WM, int WN, int EPI>
 static void launch_variant(const void *x, const void *wp, void *out, int M, int N, int K, int split, hipStream_t st)
 {
     const int n_tiles = N / 32, per_block = WN * NT;
     const int total_chunks = K / 64;
     const int cps = (total_chunks + split - 1) / split;
     dim3 grid((n_tiles + per_block - 1) / per_block, (M + WM * MT * 32 - 1) / (WM * MT * 32), split);
-    hipLaunchKernelGGL((gemm_bf16_kernel<MT, NT, WM, WN, EPI>), grid, dim3(WM * WN * 64), 0, st,
-                       reinterpret_cast<const bf16_t *>(x), reinterpret_cast<const uint4 *>(wp), out, M, N, K, cps);
+    hipLaunchKernelGGL((gemm_mfma_kernel<T, MT, NT, WM, WN, EPI>), grid, dim3(WM * WN * 64), 0, st,
+                       reinterpret_cast<const T *>(x), reinterpret_cast<const uint4 *>(wp), out, M, N, K, cps);
 }
 
 // Number of k splits: enough blocks to cover the chip a few times over when the output is narrow, never
@@ -193,30 +204,20 @@ static int choose_split(int M, int N, int K, int block_rows, int block_cols)
     return s;
 }
 
-int gemm_bf16_split_for(int M, int N, int K)
+int gemm_mfma_split_for(int M, int N, int K)
 {
     if (M <= 256) return choose_split(M, N, K, 256, 256);
     return choose_split(M, N, K, 256, 256);
 }
 
-int32_t launch_gemm_bf16(const void *x, const void *wp, void *out, int M, int N, int K, int epilogue, int split_k,
-                         int *split_used, hipStream_t st)
+template <typename T>
+static int32_t launch_gemm_typed(const void *x, const void *wp, void *out, int M, int N, int K, int epilogue, int split,
+                                 hipStream_t st)
 {
-    if (M <= 0) return FG_OK;
-    if (N % 32 || K % 64) return fail(FG_ERR_SHAPE, "bf16 GEMM needs n_out %% 32 == 0 and n_in %% 64 == 0 (got %d, %d)", N, K);
-    if (epilogue == 1 && (N % 64)) return fail(FG_ERR_SHAPE, "gate/up GEMM needs n_out %% 64 == 0");
-    int split = 1;
-    if (epilogue == 0) {
-        split = split_k > 0 ? split_k : gemm_bf16_split_for(M, N, K);
-        if (split > K / 64) split = K / 64;
-        int cps = (K / 64 + split - 1) / split;
-        split = (K / 64 + cps - 1) / cps;
-    }
-    if (split_used) *split_used = split;
-#define FG_GEMM_CASE(MT, NT, WM, WN)                                                                    \
-    do {                                                                                                \
-        if (epilogue == 0) launch_variant<MT, NT, WM, WN, 0>(x, wp, out, M, N, K, split, st);           \
-        else launch_variant<MT, NT, WM, WN, 1>(x, wp, out, M, N, K, split, st);                         \
+#define FG_GEMM_CASE(MT, NT, WM, WN)                                                                       \
+    do {                                                                                                   \
+        if (epilogue == 0) launch_variant<T, MT, NT, WM, WN, 0>(x, wp, out, M, N, K, split, st);           \
+        else launch_variant<T, MT, NT, WM, WN, 1>(x, wp, out, M, N, K, split, st);                         \
     } while (0)
     if (M <= 32) FG_GEMM_CASE(1, 2, 1, 4);
     else if (M <= 64) FG_GEMM_CASE(2, 2, 1, 4);
@@ -224,8 +225,27 @@ int32_t launch_gemm_bf16(const void *x, const void *wp, void *out, int M, int N,
     else if (M <= 256) FG_GEMM_CASE(8, 2, 1, 4);
     else FG_GEMM_CASE(4, 4, 2, 2);
 #undef FG_GEMM_CASE
-    FG_LAUNCH_CHECK("gemm_bf16");
+    FG_LAUNCH_CHECK("gemm_mfma");
     return FG_OK;
+}
+
+int32_t launch_gemm_mfma(int32_t dtype, const void *x, const void *wp, void *out, int M, int N, int K, int epilogue,
+                         int split_k, int *split_used, hipStream_t st)
+{
+    if (M <= 0) return FG_OK;
+    if (!is16(dtype)) return fail(FG_ERR_INVALID_ARG, "MFMA GEMM needs a 16-bit dtype");
+    if (N % 32 || K % 64) return fail(FG_ERR_SHAPE, "16-bit GEMM needs n_out %% 32 == 0 and n_in %% 64 == 0 (got %d, %d)", N, K);
+    if (epilogue == 1 && (N % 64)) return fail(FG_ERR_SHAPE, "gate/up GEMM needs n_out %% 64 == 0");
+    int split = 1;
+    if (epilogue == 0) {
+        split = split_k > 0 ? split_k : gemm_mfma_split_for(M, N, K);
+        if (split > K / 64) split = K / 64;
+        int cps = (K / 64 + split - 1) / split;
+        split = (K / 64 + cps - 1) / cps;
+    }
+    if (split_used) *split_used = split;
+    if (dtype == FG_BF16) return launch_gemm_typed<bf16_t>(x, wp, out, M, N, K, epilogue, split, st);
+    return launch_gemm_typed<f16_t>(x, wp, out, M, N, K, epilogue, split, st);
 }
 
 // ---- packing ---------------------------------------------------------------------------------------------
@@ -266,7 +286,7 @@ int32_t launch_pack(int32_t dtype, const void *src, const void *src2, void *dst,
     int64_t N = src2 ? 2 * n_out : n_out;
     if (n_out % 32 || n_in % 64) return fail(FG_ERR_SHAPE, "pack needs n_out %% 32 == 0 and n_in %% 64 == 0 (got %lld, %lld)",
                                              (long long)n_out, (long long)n_in);
-    if (dtype == FG_BF16) {
+    if (is16(dtype)) {
         int64_t total = (N / 32) * (n_in / 16) * 64;
         hipLaunchKernelGGL(pack_bf16_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                            (const bf16_t *)src, (const bf16_t *)src2, (uint4 *)dst, N, n_in);

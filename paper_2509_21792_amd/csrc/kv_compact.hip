@@ -73,19 +73,20 @@ int32_t launch_kv_compact(fg_kv_cache *kv, const int32_t *slot, const int32_t *a
 {
     dim3 grid(B, kv->n_layers * kv->n_kv_heads);
     int threads = kv->head_dim <= 64 ? 64 : 128;
-    if (kv->dtype == FG_BF16)
-        hipLaunchKernelGGL(kv_compact_kernel<bf16_t>, grid, dim3(threads), 0, st, (bf16_t *)kv->k_pool, (bf16_t *)kv->v_pool,
-                           kv->page_table, kv->seq_len, slot, accept_len, path, N, kv->n_pages, kv->n_slots,
-                           kv->max_pages_per_seq, kv->n_kv_heads, kv->head_dim);
-    else
+    // pure data movement: only the element width matters
+    if (kv->dtype == FG_F32)
         hipLaunchKernelGGL(kv_compact_kernel<float>, grid, dim3(threads), 0, st, (float *)kv->k_pool, (float *)kv->v_pool,
                            kv->page_table, kv->seq_len, slot, accept_len, path, N, kv->n_pages, kv->n_slots,
                            kv->max_pages_per_seq, kv->n_kv_heads, kv->head_dim);
+    else
+        hipLaunchKernelGGL(kv_compact_kernel<uint16_t>, grid, dim3(threads), 0, st, (uint16_t *)kv->k_pool,
+                           (uint16_t *)kv->v_pool, kv->page_table, kv->seq_len, slot, accept_len, path, N, kv->n_pages,
+                           kv->n_slots, kv->max_pages_per_seq, kv->n_kv_heads, kv->head_dim);
     FG_LAUNCH_CHECK("kv_compact");
     if (fin && fout) {
-        if (feat_dtype == FG_BF16)
-            hipLaunchKernelGGL(gather_feature_kernel<bf16_t>, dim3(B, N), dim3(256), 0, st, (const bf16_t *)fin, (bf16_t *)fout,
-                               accept_len, path, N, d);
+        if (feat_dtype != FG_F32)
+            hipLaunchKernelGGL(gather_feature_kernel<uint16_t>, dim3(B, N), dim3(256), 0, st, (const uint16_t *)fin,
+                               (uint16_t *)fout, accept_len, path, N, d);
         else
             hipLaunchKernelGGL(gather_feature_kernel<float>, dim3(B, N), dim3(256), 0, st, (const float *)fin, (float *)fout,
                                accept_len, path, N, d);

@@ -20,6 +20,13 @@ def draft_of(model):
     return d
 
 
+def with_dtype(model, dtype):
+    """The same model computed in another arithmetic type ("bf16", "fp16" or "fp32")."""
+    d = dict(model)
+    d["dtype"] = dtype
+    return d
+
+
 def scaled(model, n_layers):
     """The same layer geometry with fewer layers (for parity cases the CPU oracle finishes quickly)."""
     d = dict(model)

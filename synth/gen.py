@@ -16,8 +16,13 @@ def _gen(seed, device="cpu"):
 
 
 def _store(t, dtype):
-    """bf16 workloads hold bf16-representable values (rounded once, here); fp32 workloads keep fp32."""
-    return t.to(torch.bfloat16) if dtype == "bf16" else t
+    """16-bit workloads hold bf16-representable values (rounded once, here); fp32 workloads keep fp32.
+    "fp16" keeps those bf16-rounded values in an fp16 container (exact down to 6e-5, subnormal below)."""
+    if dtype == "bf16":
+        return t.to(torch.bfloat16)
+    if dtype == "fp16":
+        return t.to(torch.bfloat16).to(torch.float16)
+    return t
 
 
 def make_weights(model, seed, device="cpu", draft=False):

@@ -16,39 +16,47 @@ def fg():
     return m
 
 
-def bf16_randn(shape, gen, scale=1.0):
-    return (torch.randn(shape, generator=gen, dtype=torch.float32) * scale).to(torch.bfloat16)
+def bf16_randn(shape, gen, scale=1.0, dt=torch.bfloat16):
+    return (torch.randn(shape, generator=gen, dtype=torch.float32) * scale).to(torch.bfloat16).to(dt)
+
+
+CODES = {"bf16": 1, "fp16": 2}
+TD = {"bf16": torch.bfloat16, "fp16": torch.float16, "fp32": torch.float32}
 
 
 @pytest.mark.parametrize("M,N,K", [(1, 64, 64), (8, 4608, 3584), (48, 3584, 3584), (40, 96, 128), (130, 1024, 704 - 64),
                                    (192, 3584, 18944), (256, 512, 256), (257, 544, 192), (700, 4608, 1536)])
-def test_gemm_bf16_partial_epilogue(fg, M, N, K):
-    print(f"gemm M={M} N={N} K={K}", flush=True)
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+def test_gemm_16bit_partial_epilogue(fg, M, N, K, dtype):
+    print(f"gemm {dtype} M={M} N={N} K={K}", flush=True)
+    code = CODES[dtype]
     g = torch.Generator().manual_seed(M * 7 + N)
-    x, w = bf16_randn((M, K), g), bf16_randn((N, K), g, 0.05)
+    x, w = bf16_randn((M, K), g, dt=TD[dtype]), bf16_randn((N, K), g, 0.05, dt=TD[dtype])
     ref = x.double() @ w.double().T
-    wp = fg.fg_pack_weight(fg.FG_BF16, w.cuda())
+    wp = fg.fg_pack_weight(code, w.cuda())
     for split in (0, 1, 3):
-        out, used = fg.fg_gemm(fg.FG_BF16, x.cuda(), wp, N, epilogue=0, split_k=split)
+        out, used = fg.fg_gemm(code, x.cuda(), wp, N, epilogue=0, split_k=split)
         torch.cuda.synchronize()
         err = (out.double().cpu() - ref).abs().max().item()
         scale = ref.abs().max().item()
         assert err <= 2e-5 * scale + 1e-4, (split, used, err, scale)
     # run twice: split-K slabs are summed in a fixed order, so results are bitwise repeatable
-    a, _ = fg.fg_gemm(fg.FG_BF16, x.cuda(), wp, N)
-    b, _ = fg.fg_gemm(fg.FG_BF16, x.cuda(), wp, N)
+    a, _ = fg.fg_gemm(code, x.cuda(), wp, N)
+    b, _ = fg.fg_gemm(code, x.cuda(), wp, N)
     assert torch.equal(a, b)
 
 
 @pytest.mark.parametrize("M,F,K", [(8, 704, 256), (33, 1024, 128), (200, 18944, 3584), (300, 2048, 512), (1000, 1024, 256)])
-def test_gemm_bf16_swiglu_epilogue(fg, M, F, K):
-    print(f"swiglu gemm M={M} F={F} K={K}", flush=True)
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+def test_gemm_16bit_swiglu_epilogue(fg, M, F, K, dtype):
+    print(f"swiglu gemm {dtype} M={M} F={F} K={K}", flush=True)
     g = torch.Generator().manual_seed(M + F)
-    x, wg, wu = bf16_randn((M, K), g), bf16_randn((F, K), g, 0.05), bf16_randn((F, K), g, 0.05)
+    dt = TD[dtype]
+    x, wg, wu = bf16_randn((M, K), g, dt=dt), bf16_randn((F, K), g, 0.05, dt=dt), bf16_randn((F, K), g, 0.05, dt=dt)
     gate, up = x.double() @ wg.double().T, x.double() @ wu.double().T
     ref = torch.nn.functional.silu(gate) * up
-    wp = fg.fg_pack_weight(fg.FG_BF16, wg.cuda(), wu.cuda())
-    out, _ = fg.fg_gemm(fg.FG_BF16, x.cuda(), wp, 2 * F, epilogue=1)
+    wp = fg.fg_pack_weight(CODES[dtype], wg.cuda(), wu.cuda())
+    out, _ = fg.fg_gemm(CODES[dtype], x.cuda(), wp, 2 * F, epilogue=1)
     torch.cuda.synchronize()
     err = (out.double().cpu() - ref).abs()
     assert (err <= 2 ** -8 * ref.abs() + 1e-3).all(), err.max().item()
@@ -95,6 +103,10 @@ def ref_attention(q, k, v, L, parent, n_prev, Hq, Hkv, hd):
     ("bf16", 12, 2, 128, 4, 6, 0, (512, 100, 17, 31)),
     ("bf16", 28, 4, 128, 5, 24, 0, (256, 1000, 33, 2048, 15)),
     ("bf16", 28, 4, 128, 3, 8, 0, (1024, 4096, 1500)),
+    ("fp16", 28, 4, 128, 3, 8, 0, (1024, 4096, 1500)),
+    ("fp16", 28, 4, 128, 4, 24, 0, (640, 33, 2048, 15)),
+    ("fp16", 12, 2, 128, 3, 6, 2, (512, 100, 17)),
+    ("bf16", 8, 4, 64, 3, 5, 0, (70, 300, 5)),
     ("bf16", 28, 4, 128, 3, 32, 0, (300, 3072, 16)),
     ("bf16", 28, 4, 128, 2, 4, 8, (77, 640)),
     ("bf16", 28, 4, 128, 9, 1, 0, (1, 16, 17, 255, 256, 257, 1023, 2000, 0)),
@@ -108,13 +120,13 @@ def test_tree_attention(fg, dtype, Hq, Hkv, hd, B, N, n_prev, lens):
     rng = np.random.default_rng(N + B)
     table, n_pages = gen.make_page_table(np.array(lens), n_tot, 16, seed=3, spare_pages=2)
     kv = fg.KVCache(cfg, table, n_pages)
-    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    td = TD[dtype]
     g = torch.Generator().manual_seed(5)
     parent = np.stack([np.array([-1] + [int(rng.integers(-1, i)) for i in range(1, n_tot)], dtype=np.int32) for _ in range(B)])
     ks, vs = [], []
     for b in range(B):
-        k = torch.randn((2, lens[b] + n_tot, Hkv, hd), generator=g).to(td)
-        v = torch.randn((2, lens[b] + n_tot, Hkv, hd), generator=g).to(td)
+        k = torch.randn((2, lens[b] + n_tot, Hkv, hd), generator=g).to(torch.bfloat16 if td != torch.float32 else td).to(td)
+        v = torch.randn((2, lens[b] + n_tot, Hkv, hd), generator=g).to(torch.bfloat16 if td != torch.float32 else td).to(td)
         kv.write_prefix(b, k.cuda(), v.cuda())
         ks.append(k); vs.append(v)
     kv.seq_len.copy_(torch.tensor(lens, dtype=torch.int32))
@@ -127,5 +139,5 @@ def test_tree_attention(fg, dtype, Hq, Hkv, hd, B, N, n_prev, lens):
         ref = ref_attention(q.double().view(B, N, Hq, hd)[b], ks[b][layer].double(), vs[b][layer].double(), lens[b],
                             parent[b], n_prev, Hq, Hkv, hd)
         err = (out[b] - ref).abs().max().item()
-        tol = 1e-5 if dtype == "fp32" else 2.5e-2
+        tol = {"fp32": 1e-5, "bf16": 2.5e-2, "fp16": 4e-3}[dtype]
         assert err < tol, (b, err)

@@ -36,11 +36,12 @@ def run_verify_case(H, model, B, N, spec, lengths, seed, subset=None, check_kv=T
     sub = st.subset
     V, d = model["vocab"], model["d_model"]
     rows = np.concatenate([np.arange(b * N, (b + 1) * N) for b in sub])
-    tol = H.TOL[model["dtype"]]
-    stats = H.compare_rows(out["logits"][rows].cpu().numpy(), ol, tol, out["argmax"][rows].cpu().numpy())
+    tol = H.logit_tolerance(model, ol.size)
+    stats = H.compare_rows(out["logits"][rows].cpu().numpy(), ol, tol, out["argmax"][rows].cpu().numpy(),
+                           margin=H.decision_margin(model))
     feat = out["feature"][rows].float().cpu().numpy()
     ferr = np.abs(feat - oh).max()
-    assert ferr <= (1e-4 if model["dtype"] == "fp32" else 6e-2), ferr
+    assert ferr <= {"fp32": 1e-4, "fp16": 2e-2, "bf16": 0.25}[model["dtype"]], ferr
     # top-2 values are the two largest logits of the row
     top2 = out["top2"][rows].cpu().numpy()
     srt = np.sort(out["logits"][rows].cpu().numpy(), axis=1)
@@ -53,7 +54,7 @@ def run_verify_case(H, model, B, N, spec, lengths, seed, subset=None, check_kv=T
             k, v = st.kv.read(b, L + N)
             kerr = np.abs(k[:, L:].float().cpu().numpy() - st.ocache.k[:, j, L:L + N]).max()
             verr = np.abs(v[:, L:].float().cpu().numpy() - st.ocache.v[:, j, L:L + N]).max()
-            ktol = 1e-4 if model["dtype"] == "fp32" else 8e-2
+            ktol = {"fp32": 1e-4, "fp16": 2e-2, "bf16": 0.15}[model["dtype"]]
             assert kerr <= ktol and verr <= ktol, (b, kerr, verr)
     print(f"verify {model['name']} B={B} N={N}: {stats} feature_err={ferr:.3g}", flush=True)
     return pair, st, tokens, parent, out, ol
@@ -70,34 +71,39 @@ def test_tiny_fp32_wide_tree_and_empty_prefix(H):
     run_verify_case(H, configs.TINY, 5, 24, ("tree", 4, 5, 24), lengths, seed=4)
 
 
-def test_bf16_7b_geometry_two_layers_every_element(H):
+DT16 = ["fp16", "bf16"]
+
+
+@pytest.mark.parametrize("dtype", DT16)
+def test_7b_geometry_two_layers_every_element(H, dtype):
     """The 7B-class layer geometry and vocabulary with 2 layers: every GEMM shape of the big model, all rows checked."""
-    model = configs.scaled(configs.Q7B, 2)
+    model = configs.with_dtype(configs.scaled(configs.Q7B, 2), dtype)
     lengths = np.array([256, 300, 17, 1000, 2048, 31], dtype=np.int32)
     run_verify_case(H, model, 6, 24, ("tree", 4, 5, 24), lengths, seed=1)
 
 
-def test_bf16_1p5b_geometry_two_layers_chain(H):
-    model = configs.scaled(configs.Q1P5B, 2)
+@pytest.mark.parametrize("dtype", DT16)
+def test_1p5b_geometry_two_layers_chain(H, dtype):
+    model = configs.with_dtype(configs.scaled(configs.Q1P5B, 2), dtype)
     lengths = np.full(16, 512, dtype=np.int32)
     run_verify_case(H, model, 16, 6, ("chain", 5), lengths, seed=2)
 
 
-@pytest.mark.parametrize("N", [1, 2, 8])
-def test_bf16_7b_geometry_high_concurrency_shapes(H, N):
-    """B = 256 rows of config 4's shapes (N = 1, 2, 8) on the 7B geometry with 1 layer; oracle on 6 sequences."""
-    model = configs.scaled(configs.Q7B, 1)
+@pytest.mark.parametrize("N,dtype", [(1, "fp16"), (2, "bf16"), (4, "fp16"), (8, "fp16"), (8, "bf16")])
+def test_7b_geometry_high_concurrency_shapes(H, N, dtype):
+    """B = 256 rows of config 4's shapes (N = 1, 2, 4, 8) on the 7B geometry with 1 layer; oracle on 6 sequences."""
+    model = configs.with_dtype(configs.scaled(configs.Q7B, 1), dtype)
     B = 256
     lengths = gen.make_kv_lengths(B, 64, 600, seed=5)
     lengths[0], lengths[1] = 64, 600
-    spec = ("chain", 1) if N <= 2 else ("tree", 4, 4, 8)
+    spec = ("chain", 1) if N <= 2 else ("tree", 4, 4, N)
     run_verify_case(H, model, B, N, spec, lengths, seed=3 + N, subset=[0, 1, 2, 100, 200, 255])
 
 
 def test_accept_and_compact_follow_the_oracle(H):
     """Greedy acceptance with planted agreement + compaction: accept lengths, paths, tokens and the moved K/V."""
     import paper_2509_21792_amd as fg
-    model = configs.scaled(configs.Q7B, 2)
+    model = configs.with_dtype(configs.scaled(configs.Q7B, 2), "fp16")
     B, N, spec = 8, 24, ("tree", 4, 5, 24)
     lengths = np.array([256, 300, 17, 1000, 700, 31, 64, 15], dtype=np.int32)
     pair = H.Pair(model, seed=7)
@@ -154,7 +160,7 @@ def test_accept_and_compact_follow_the_oracle(H):
             assert torch.equal(v[:, L + j], before[b][1][:, L + o_path[b, j]])
         assert torch.equal(k[:, :L], before[b][0][:, :L]) and torch.equal(v[:, :L], before[b][1][:, :L])
         kerr = np.abs(k[:, L:].float().cpu().numpy() - st.ocache.k[:, b, L:L + a + 1]).max()
-        assert kerr < 8e-2
+        assert kerr < 2e-2
         fg_rows = feat_g[b, :a + 1].float().cpu().numpy()
         want = out["feature"].view(B, N, -1)[b, o_path[b, :a + 1]].float().cpu().numpy()
         assert np.array_equal(fg_rows, want)
