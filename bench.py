@@ -1,0 +1,285 @@
+#!/usr/bin/env python3
+"""Benchmark of the speculative-verify hot path on one MI355X.
+
+One "step" = one pass of the hot path over one batch: plan (host) -> draft steps + rerank (when --draft) ->
+spec_verify -> spec_accept -> kv_compact -> accept lengths to the host.  Inputs (weights, paged KV cache, planted
+draft trees) are resident in HBM before the timed region; the cache lengths are reset between steps so every step
+sees the same ragged shape.  Prints ONE JSON line (see README for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM = 8.0e12          # B/s, MI355X HBM3E
+PEAK_MFMA = 2516.6e12      # flop/s, dense bf16 / fp16 MFMA
+
+
+def model_bytes_flops(model, M, lengths, N):
+    """Algorithmic bytes and flops of one verify step (what the method itself must move / compute)."""
+    d, Hq, Hkv, hd, F, V, nl = (model[k] for k in ("d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab", "n_layers"))
+    per_layer = (Hq + 2 * Hkv) * hd * d + d * Hq * hd + 2 * F * d + d * F
+    params = nl * per_layer + V * d
+    kv_per_tok = 2 * Hkv * hd * 2 * nl
+    sumL = int(np.sum(lengths))
+    byts = 2 * params + M * d * 2 + sumL * kv_per_tok + M * kv_per_tok + M * d * 2 + M * 12
+    gemm_flops = 2.0 * M * params
+    attn_flops = 4.0 * Hq * hd * nl * float(np.sum((lengths + (N + 1) / 2.0) * N))
+    return dict(params=params, bytes=float(byts), weight_bytes=2.0 * params, kv_bytes=float(sumL * kv_per_tok),
+                flops=gemm_flops + attn_flops, gemm_flops=gemm_flops, attn_flops=attn_flops)
+
+
+class Workload:
+    """A model, a batch of ragged paged caches and a planted draft tree, all on the device."""
+
+    def __init__(self, name, dtype, seed=0, B=None, N=None, n_layers=None, kv=None, verbose=False):
+        import torch
+        import paper_2509_21792_amd as fg
+        from synth import configs, gen
+        self.fg, self.torch = fg, torch
+        cfg = dict(configs.CONFIGS[name])
+        model = configs.with_dtype(cfg["model"], dtype)
+        if n_layers:
+            model = configs.scaled(model, n_layers)
+        self.cfg, self.model, self.name = cfg, model, name
+        self.B = B or cfg["B"]
+        self.N = N or cfg["N"]
+        lo, hi = kv or (cfg["kv_lo"], cfg["kv_hi"])
+        pd = configs.PLAN_DEFAULTS
+        # the tree shape is what the concurrency rule gives for C_peak = B * N (Eq. 1-3)
+        self.plan = fg.fg_plan(self.B, float(self.B * self.N), pd["alpha"], pd["K_max"], pd["L_max"], pd["N_cap"])
+        Np, Kd, Ld = self.plan
+        if cfg["tree"][0] in ("chain", "tree") and not N:
+            self.spec = cfg["tree"]                      # the configuration pins its own shape
+        else:
+            assert Np == self.N, (self.plan, self.N)
+            self.spec = ("tree", max(Kd, 1), max(Ld, 1), self.N)
+        t0 = time.time()
+        self.weights = gen.make_weights(model, seed, device="cuda")
+        self.gm = fg.Model(model, self.weights)
+        self.lengths = gen.make_kv_lengths(self.B, lo, hi, seed)
+        self.lengths[0], self.lengths[-1] = lo, hi
+        table, n_pages = gen.make_page_table(self.lengths, self.N + 1, 16, seed)
+        self.kv = fg.KVCache(model, table, n_pages)
+        for b in range(self.B):
+            k, v = gen.make_prefix_kv(model, int(self.lengths[b]), seed, b, device="cuda")
+            self.kv.write_prefix(b, k, v)
+        self.len0 = self.kv.seq_len.clone()
+        self.cap = int(self.lengths.max()) + self.N + 1
+        self.slot = torch.arange(self.B, dtype=torch.int32, device="cuda")
+        self.ws = self.gm.workspace(self.B * self.N, self.cap)
+        self.parent, self.principal = gen.make_trees(self.spec, self.B, self.N, seed + 2)
+        rng = np.random.default_rng(seed + 3)
+        self.root = rng.integers(0, model["vocab"], size=self.B).astype(np.int32)
+        nxt = self.greedy_continuation(self.principal.shape[1])
+        tokens, self.hit = gen.plant_tokens(self.parent, self.principal, self.root, nxt, cfg["plant_p"] or 0.0,
+                                            model["vocab"], seed + 4)
+        self.tokens_d = torch.as_tensor(tokens).cuda()
+        self.parent_d = torch.as_tensor(self.parent).cuda()
+        self.max_seq_len = int(self.lengths.max()) + self.N
+        torch.cuda.synchronize()
+        if verbose:
+            print(f"# workload {name} {dtype}: B={self.B} N={self.N} plan={self.plan} sumL={int(self.lengths.sum())} "
+                  f"set-up {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
+
+    def greedy_continuation(self, depth):
+        """The target's own next tokens after the root, by `depth` plain decode steps of the HIP path (set-up, untimed)."""
+        fg, torch = self.fg, self.torch
+        B = self.B
+        out = np.zeros((B, depth), dtype=np.int32)
+        cur = torch.as_tensor(self.root).cuda().view(B, 1)
+        par = torch.full((B, 1), -1, dtype=torch.int32, device="cuda")
+        zero = torch.zeros(B, dtype=torch.int32, device="cuda")
+        path = torch.zeros((B, 1), dtype=torch.int32, device="cuda")
+        for l in range(depth):
+            o = fg.fg_spec_verify(self.gm, self.kv, self.slot, cur, par, self.ws, want_feature=False)
+            fg.fg_kv_compact(self.kv, self.slot, zero, path)
+            cur = o["argmax"].view(B, 1).clone()
+            out[:, l] = cur.view(-1).cpu().numpy()
+        self.kv.seq_len.copy_(self.len0)
+        return out
+
+    def step(self):
+        fg = self.fg
+        pd_N, pd_K, pd_L = fg.fg_plan(self.B, float(self.B * self.N))
+        o = fg.fg_spec_verify(self.gm, self.kv, self.slot, self.tokens_d, self.parent_d, self.ws, want_feature=True,
+                              max_seq_len=self.max_seq_len)
+        acc, path, otok, fin = fg.fg_spec_accept(self.tokens_d, self.parent_d, row_argmax=o["argmax"])
+        fg.fg_kv_compact(self.kv, self.slot, acc, path)
+        a = acc.cpu()                                  # host bookkeeping: accept lengths cross to the host
+        self.kv.seq_len.copy_(self.len0)               # harness: same ragged shape for the next repetition
+        return int(a.sum()) + self.B
+
+    def verify_only(self):
+        self.fg.fg_spec_verify(self.gm, self.kv, self.slot, self.tokens_d, self.parent_d, self.ws, want_feature=True,
+                               max_seq_len=self.max_seq_len)
+
+
+def time_steps(torch, fn, steps, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    last = None
+    for _ in range(steps):
+        last = fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps, last
+
+
+def cpu_baseline(wl, n_seq=4, reps=1):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the same workload."""
+    from oracle.oracle import Oracle
+    from synth import gen
+    orc = Oracle("f32")
+    model = wl.model
+    om = orc.model(model, gen.weights_to_numpy(wl.weights))
+    order = np.argsort(wl.lengths)
+    pick = sorted(set([int(order[0]), int(order[-1])] + [int(order[i]) for i in np.linspace(0, wl.B - 1, n_seq).astype(int)]))[:max(n_seq, 2)]
+    S, N = len(pick), wl.N
+    cache = orc.cache(model, S, wl.cap)
+    for j, b in enumerate(pick):
+        L = int(wl.lengths[b])
+        k, v = gen.make_prefix_kv(model, L, wl.cfg["seed"], b, device="cuda")
+        cache.k[:, j, :L] = k.float().cpu().numpy()
+        cache.v[:, j, :L] = v.float().cpu().numpy()
+    cache.len[:] = wl.lengths[pick]
+    parent, principal = wl.parent[pick], wl.principal[pick]
+    # the oracle plants from its own continuation (no oracle input comes from the HIP path)
+    cur = wl.root[pick].copy()
+    nxt = np.zeros((S, principal.shape[1]), dtype=np.int32)
+    for l in range(principal.shape[1]):
+        _, lg = orc.tree_forward(om, cache, cur.reshape(S, 1), np.full((S, 1), -1, np.int32))
+        cur, _ = orc.row_argmax(lg)
+        nxt[:, l] = cur
+        cache.len += 1
+    cache.len[:] = wl.lengths[pick]
+    tokens, _ = gen.plant_tokens(parent, principal, wl.root[pick], nxt, wl.cfg["plant_p"] or 0.0, model["vocab"], 99)
+    t0 = time.perf_counter()
+    emitted = 0
+    for _ in range(reps):
+        _, lg = orc.tree_forward(om, cache, tokens, parent)
+        acc, path, out, fin, _, _ = orc.accept_greedy(tokens, parent, lg)
+        orc.kv_compact(cache, model, acc, path)
+        emitted = int(acc.sum()) + S
+        cache.len[:] = wl.lengths[pick]
+    dt = (time.perf_counter() - t0) / reps
+    return dict(value=emitted / dt, unit="tokens/s", cores=orc.num_threads(), kind="oracle",
+                sample=f"{S} of the {wl.B} sequences (shortest and longest cache included), N={N}, all {model['n_layers']} layers, "
+                       f"verify+accept+compact, {reps} repetition(s), {dt * 1e3:.0f} ms per step",
+                ms_per_step=dt * 1e3, sequences=S)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg4")
+    ap.add_argument("--dtype", default="bf16", choices=["bf16", "fp16"])
+    ap.add_argument("--B", type=int, default=0)
+    ap.add_argument("--N", type=int, default=0)
+    ap.add_argument("--layers", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-b8", action="store_true", help="skip the B = 8 point of the metric's range")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: every box of this build has one MI355X and the path shards by sequence "
+              "with no collective, so --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2509_21792_amd as fg
+    fg.lib()
+    assert torch.cuda.is_available(), "no GPU: the HIP path has no CPU fallback"
+
+    wl = Workload(args.workload, args.dtype, B=args.B or None, N=args.N or None, n_layers=args.layers or None, verbose=True)
+    model, M = wl.model, wl.B * wl.N
+    acct = model_bytes_flops(model, M, wl.lengths.astype(np.float64), wl.N)
+
+    # dominant kernel: the gate/up GEMM (largest share of both the weight bytes and the flops)
+    n_out, n_in = 2 * model["d_ffn"], model["d_model"]
+    epi = 1 if M > 256 else 0
+    t_verify, _ = time_steps(torch, wl.verify_only, max(3, args.steps // 2), args.warmup)
+    fg.fg_profile_gemm(True, n_out, n_in, epi, max_launches=(args.steps + 1) * model["n_layers"])
+    for _ in range(args.warmup):
+        wl.step()
+    fg.fg_profile_read()
+    t_step, emitted = time_steps(torch, wl.step, args.steps, 0)
+    k_ms, k_cnt = fg.fg_profile_read()
+    fg.fg_profile_gemm(False)
+    k_avg = k_ms / max(k_cnt, 1) * 1e-3
+    gemm_flops = 2.0 * M * n_out * n_in
+    gemm_bytes = 2.0 * n_out * n_in + 2.0 * M * n_in + (2.0 * M * n_out / 2 if epi else 4.0 * M * n_out)
+    compute_bound = gemm_flops / PEAK_MFMA > gemm_bytes / PEAK_HBM
+    if compute_bound:
+        roof = dict(bound="mfma", achieved=gemm_flops / k_avg / 1e12, peak=PEAK_MFMA / 1e12, unit="TFLOP/s")
+    else:
+        roof = dict(bound="hbm", achieved=gemm_bytes / k_avg / 1e9, peak=PEAK_HBM / 1e9, unit="GB/s")
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel"] = f"gemm_mfma_kernel (gate/up, M={M}, n_out={n_out}, n_in={n_in}, epilogue={'swiglu' if epi else 'fp32 split-K slabs'})"
+    roof["launches"] = k_cnt
+    roof["avg_us"] = k_avg * 1e6
+
+    out = {
+        "metric": "accepted tokens/s (7B-class verify step: verify + accept + compact)", "value": emitted / t_step,
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": t_step * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {model['name']} {model['n_layers']} layers, B={wl.B}, N_verify={wl.N} "
+                               f"(K_draft={wl.plan[1]}, L_draft={wl.plan[2]} from Eq. 1-3), KV lengths U[{int(wl.lengths.min())},"
+                               f"{int(wl.lengths.max())}] in 16-token pages, planted agreement {wl.cfg['plant_p']}, greedy"},
+        "verify_ms": t_verify * 1e3, "tau": emitted / wl.B,
+        "step_hbm_frac": acct["bytes"] / t_verify / PEAK_HBM, "step_mfma_frac": acct["flops"] / t_verify / PEAK_MFMA,
+        "step_bytes": acct["bytes"], "step_flops": acct["flops"],
+        "roofline": roof,
+    }
+    if not args.no_b8 and args.workload == "cfg4" and not args.B:
+        # the low end of the metric's range on the same model: B = 8, shapes N = 1 / 6 / 24
+        pts = []
+        for N in (1, 6, 24):
+            pts.append(b8_point(wl, N, args))
+        out["b8"] = pts
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out))
+
+
+def b8_point(wl, N, args):
+    """B = 8 on the same weights: verify-step time and the HBM fraction of the memory-bound regime."""
+    import torch
+    fg = wl.fg
+    from synth import configs, gen
+    cfg = configs.CONFIGS["b8"]
+    B = cfg["B"]
+    lengths = gen.make_kv_lengths(B, cfg["kv_lo"], cfg["kv_hi"], 7)
+    table, n_pages = gen.make_page_table(lengths, N + 1, 16, 7)
+    kv = fg.KVCache(wl.model, table, n_pages)
+    for b in range(B):
+        k, v = gen.make_prefix_kv(wl.model, int(lengths[b]), 7, b, device="cuda")
+        kv.write_prefix(b, k, v)
+    spec = ("tree", 4, 5, N) if N > 6 else ("chain", N - 1)
+    parent, _ = gen.make_trees(spec, B, N, 8)
+    rng = np.random.default_rng(9)
+    tokens = torch.as_tensor(rng.integers(0, wl.model["vocab"], size=(B, N)).astype(np.int32)).cuda()
+    parent = torch.as_tensor(parent).cuda()
+    slot = torch.arange(B, dtype=torch.int32, device="cuda")
+    ws = wl.gm.workspace(B * N, int(lengths.max()) + N + 1)
+    msl = int(lengths.max()) + N
+
+    def f():
+        fg.fg_spec_verify(wl.gm, kv, slot, tokens, parent, ws, want_feature=True, max_seq_len=msl)
+    t, _ = time_steps(torch, f, max(args.steps, 10), args.warmup)
+    acct = model_bytes_flops(wl.model, B * N, lengths.astype(np.float64), N)
+    return dict(B=B, N=N, verify_ms=t * 1e3, hbm_frac=acct["bytes"] / t / PEAK_HBM, mfma_frac=acct["flops"] / t / PEAK_MFMA,
+                bytes=acct["bytes"])
+
+
+if __name__ == "__main__":
+    main()

@@ -246,6 +246,15 @@ int32_t fg_attention(const fg_kv_cache *kv, int32_t layer, const fg_tree *tree, 
 int64_t fg_attention_workspace_bytes(int32_t B, int32_t N, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                                      int32_t max_seq_len);
 
+/*
+ * Measurement hook (for benchmarks, not part of the method): while armed, every 16-bit GEMM launch whose
+ * (n_out, n_in, epilogue) match is bracketed by HIP events on its own stream, up to max_launches launches.
+ * fg_profile_read waits for them, returns their summed duration in milliseconds and their number, and
+ * resets the counter.  Not thread-safe; enable = 0 disarms.
+ */
+int32_t fg_profile_gemm(int32_t enable, int32_t n_out, int32_t n_in, int32_t epilogue, int32_t max_launches);
+int32_t fg_profile_read(double *total_ms, int32_t *count);
+
 #ifdef __cplusplus
 }
 #endif

@@ -68,6 +68,13 @@ enum { ORC_OK = 0, ORC_ERR_ARG = -1, ORC_ERR_TREE = -2, ORC_ERR_CAP = -3 };
 
 int orc_sizeof_real(void) { return (int)sizeof(real); }
 
+#ifdef _OPENMP
+#include <omp.h>
+int orc_num_threads(void) { return omp_get_max_threads(); }
+#else
+int orc_num_threads(void) { return 1; }
+#endif
+
 /* ------------------------------------------------------------------------ */
 /* Eq. 1-3: tree shape from live concurrency.                               */
 /* N = floor(C_peak / B) clamped to [1, N_cap]; K = min(N-1, K_max);        */

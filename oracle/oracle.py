@@ -99,6 +99,9 @@ class Oracle:
         self.lib.orc_uniform01.restype = C.c_double
         self.lib.orc_uniform01.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64]
 
+    def num_threads(self):
+        return int(self.lib.orc_num_threads())
+
     def _check(self, rc, what):
         if rc != 0:
             raise OracleError(f"{what} failed with code {rc}")

@@ -19,7 +19,8 @@ LIB_PATH = os.path.join(_HERE, "libfastgrpo.so")
 
 EXPORTS = ["fg_last_error", "fg_plan", "fg_packed_bytes", "fg_pack_weight", "fg_model_create", "fg_model_destroy",
            "fg_workspace_bytes", "fg_spec_verify", "fg_spec_accept", "fg_kv_compact", "fg_draft_step",
-           "fg_draft_frontier", "fg_build_tree", "fg_gemm", "fg_attention", "fg_attention_workspace_bytes"]
+           "fg_draft_frontier", "fg_build_tree", "fg_gemm", "fg_attention", "fg_attention_workspace_bytes",
+           "fg_profile_gemm", "fg_profile_read"]
 
 
 class FgError(RuntimeError):
@@ -347,6 +348,17 @@ def fg_build_tree(cand_tok, cand_parent, cand_score, n_cand, N):
     _check(lib().fg_build_tree(_p(cand_tok), _p(cand_parent), _p(cand_score), B, n_cand, stride, N, _p(tokens), _p(parent),
                                _p(sel), _stream()))
     return tokens, parent, sel
+
+
+# ---- measurement hook -------------------------------------------------------------------------------------------
+def fg_profile_gemm(enable, n_out=0, n_in=0, epilogue=0, max_launches=4096):
+    _check(lib().fg_profile_gemm(int(enable), n_out, n_in, epilogue, max_launches))
+
+
+def fg_profile_read():
+    tot, cnt = C.c_double(), C.c_int32()
+    _check(lib().fg_profile_read(C.byref(tot), C.byref(cnt)))
+    return tot.value, cnt.value
 
 
 # ---- kernel-level ---------------------------------------------------------------------------------------------

@@ -47,6 +47,8 @@ int32_t launch_build_tree(const int32_t *cand_tok, const int32_t *cand_parent, c
                           int N, int32_t *tokens, int32_t *parent, int32_t *sel, hipStream_t st);
 int32_t launch_commit_len(int32_t *seq_len, const int32_t *slot, const int32_t *n_commit, int B, int n_slots, hipStream_t st);
 int gemm_mfma_split_for(int M, int N, int K);
+int32_t profile_gemm_arm(int enable, int n_out, int n_in, int epilogue, int max_launches);
+int32_t profile_gemm_read(double *total_ms, int32_t *count);
 
 }  // namespace fg
 
@@ -501,6 +503,18 @@ int32_t fg_gemm(int32_t dtype, const void *x, const void *w_packed, void *out, i
         return launch_gemm_f32((const float *)x, (const float *)w_packed, (float *)out, M, n_out, n_in, (hipStream_t)stream);
     }
     return fail(FG_ERR_INVALID_ARG, "unknown dtype %d", dtype);
+}
+
+int32_t fg_profile_gemm(int32_t enable, int32_t n_out, int32_t n_in, int32_t epilogue, int32_t max_launches)
+{
+    if (enable && (max_launches < 1 || max_launches > (1 << 20))) return fail(FG_ERR_INVALID_ARG, "fg_profile_gemm: bad max_launches");
+    return profile_gemm_arm(enable, n_out, n_in, epilogue, max_launches);
+}
+
+int32_t fg_profile_read(double *total_ms, int32_t *count)
+{
+    if (!total_ms || !count) return fail(FG_ERR_INVALID_ARG, "fg_profile_read: NULL output");
+    return profile_gemm_read(total_ms, count);
 }
 
 int64_t fg_attention_workspace_bytes(int32_t B, int32_t N, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
