@@ -76,8 +76,60 @@ int32_t launch_concat_embed(int32_t dtype, const void *embed, const int32_t *tok
 
 // ---- residual add + RMSNorm ------------------------------------------------------------------------------
 // h[r] = (init ? 0 : h[r]) + sum_s partials[s][r];  a[r] = h[r] / sqrt(mean(h[r]^2) + eps) * gain.
-// One block per row; the row stays in registers between the two passes.
-constexpr int NORM_THREADS = 256, NORM_MAX_PER_THREAD = 32;  // d <= 8192
+// One block of 1024 threads per row, one float4 of the row per thread (two for d > 4096); the split-K slabs are
+// read as independent 16-byte loads so that a handful of rows (low concurrency) is not a chain of dependent
+// round trips.  The row stays in registers between the two passes.
+constexpr int NORM_THREADS = 1024, NORM_VEC_PER_THREAD = 2;  // d <= 8192, d % 4 == 0
+
+template <typename T> __device__ __forceinline__ void store4(T *p, float4 v);
+template <> __device__ __forceinline__ void store4<float>(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
+template <> __device__ __forceinline__ void store4<bf16_t>(bf16_t *p, float4 v)
+{
+    uint2 u;
+    u.x = (uint32_t)f2bf(v.x) | ((uint32_t)f2bf(v.y) << 16);
+    u.y = (uint32_t)f2bf(v.z) | ((uint32_t)f2bf(v.w) << 16);
+    *reinterpret_cast<uint2 *>(p) = u;
+}
+template <> __device__ __forceinline__ void store4<f16_t>(f16_t *p, float4 v)
+{
+    f16_t h[4] = {(f16_t)v.x, (f16_t)v.y, (f16_t)v.z, (f16_t)v.w};
+    *reinterpret_cast<uint2 *>(p) = *reinterpret_cast<uint2 *>(h);
+}
+template <typename T> __device__ __forceinline__ float4 load4(const T *p);
+template <> __device__ __forceinline__ float4 load4<float>(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+template <> __device__ __forceinline__ float4 load4<bf16_t>(const bf16_t *p)
+{
+    uint2 u = *reinterpret_cast<const uint2 *>(p);
+    return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u), __uint_as_float(u.y << 16),
+                       __uint_as_float(u.y & 0xffff0000u));
+}
+template <> __device__ __forceinline__ float4 load4<f16_t>(const f16_t *p)
+{
+    uint2 u = *reinterpret_cast<const uint2 *>(p);
+    const f16_t *h = reinterpret_cast<const f16_t *>(&u);
+    return make_float4((float)h[0], (float)h[1], (float)h[2], (float)h[3]);
+}
+
+// sum of S slabs at one float4 position; the loads are independent of each other
+__device__ __forceinline__ float4 slab_sum4(const float *base, size_t slab_stride, int S, float4 x)
+{
+    int s = 0;
+    for (; s + 4 <= S; s += 4) {
+        float4 a = *reinterpret_cast<const float4 *>(base + (size_t)s * slab_stride);
+        float4 b = *reinterpret_cast<const float4 *>(base + (size_t)(s + 1) * slab_stride);
+        float4 c = *reinterpret_cast<const float4 *>(base + (size_t)(s + 2) * slab_stride);
+        float4 d = *reinterpret_cast<const float4 *>(base + (size_t)(s + 3) * slab_stride);
+        x.x += a.x; x.y += a.y; x.z += a.z; x.w += a.w;
+        x.x += b.x; x.y += b.y; x.z += b.z; x.w += b.w;
+        x.x += c.x; x.y += c.y; x.z += c.z; x.w += c.w;
+        x.x += d.x; x.y += d.y; x.z += d.z; x.w += d.w;
+    }
+    for (; s < S; s++) {
+        float4 a = *reinterpret_cast<const float4 *>(base + (size_t)s * slab_stride);
+        x.x += a.x; x.y += a.y; x.z += a.z; x.w += a.w;
+    }
+    return x;
+}
 
 template <typename T>
 __global__ __launch_bounds__(NORM_THREADS) void add_rmsnorm_kernel(float *h, const float *partials, int S, int init,
@@ -85,18 +137,19 @@ __global__ __launch_bounds__(NORM_THREADS) void add_rmsnorm_kernel(float *h, con
 {
     __shared__ float red[NORM_THREADS / 64];
     const int r = blockIdx.x, tid = threadIdx.x;
-    float v[NORM_MAX_PER_THREAD];
+    const int nvec = d >> 2;
+    float4 v[NORM_VEC_PER_THREAD];
     float ss = 0.f;
 #pragma unroll
-    for (int i = 0; i < NORM_MAX_PER_THREAD; i++) {
-        int c = tid + i * NORM_THREADS;
-        if (c < d) {
-            float x = init ? 0.f : h[(size_t)r * d + c];
-            for (int s = 0; s < S; s++) x += partials[((size_t)s * M + r) * d + c];
+    for (int i = 0; i < NORM_VEC_PER_THREAD; i++) {
+        int c4 = tid + i * NORM_THREADS;
+        v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (c4 < nvec) {
+            float4 x = init ? make_float4(0.f, 0.f, 0.f, 0.f) : *reinterpret_cast<const float4 *>(h + (size_t)r * d + c4 * 4);
+            x = slab_sum4(partials + (size_t)r * d + c4 * 4, (size_t)M * d, S, x);
             v[i] = x;
-            ss += x * x;
-        } else
-            v[i] = 0.f;
+            ss += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
+        }
     }
     ss = wave_sum(ss);
     if ((tid & 63) == 0) red[tid >> 6] = ss;
@@ -106,12 +159,16 @@ __global__ __launch_bounds__(NORM_THREADS) void add_rmsnorm_kernel(float *h, con
     for (int i = 0; i < NORM_THREADS / 64; i++) tot += red[i];
     const float inv = 1.0f / sqrtf(tot / (float)d + eps);
 #pragma unroll
-    for (int i = 0; i < NORM_MAX_PER_THREAD; i++) {
-        int c = tid + i * NORM_THREADS;
-        if (c < d) {
-            if (S > 0 || init) h[(size_t)r * d + c] = v[i];
-            if (a) a[(size_t)r * d + c] = from_f<T>(v[i] * inv * to_f<T>(gain[c]));
-            if (h_copy) h_copy[(size_t)r * d + c] = from_f<T>(v[i]);
+    for (int i = 0; i < NORM_VEC_PER_THREAD; i++) {
+        int c4 = tid + i * NORM_THREADS;
+        if (c4 < nvec) {
+            size_t at = (size_t)r * d + c4 * 4;
+            if (S > 0 || init) *reinterpret_cast<float4 *>(h + at) = v[i];
+            if (a) {
+                float4 g = load4<T>(gain + c4 * 4);
+                store4<T>(a + at, make_float4(v[i].x * inv * g.x, v[i].y * inv * g.y, v[i].z * inv * g.z, v[i].w * inv * g.w));
+            }
+            if (h_copy) store4<T>(h_copy + at, v[i]);
         }
     }
 }
@@ -119,7 +176,9 @@ __global__ __launch_bounds__(NORM_THREADS) void add_rmsnorm_kernel(float *h, con
 int32_t launch_add_rmsnorm(int32_t dtype, float *h, const float *partials, int S, int init, const void *gain, void *a,
                            void *h_copy, int M, int d, float eps, hipStream_t st)
 {
-    if (d > NORM_THREADS * NORM_MAX_PER_THREAD) return fail(FG_ERR_SHAPE, "d_model %d too large for the norm kernel", d);
+    if (d > NORM_THREADS * NORM_VEC_PER_THREAD * 4 || d % 4)
+        return fail(FG_ERR_SHAPE, "d_model %d not supported by the norm kernel (multiple of 4, at most %d)", d,
+                    NORM_THREADS * NORM_VEC_PER_THREAD * 4);
     FG_DISPATCH(dtype, T, hipLaunchKernelGGL(add_rmsnorm_kernel<T>, dim3(M), dim3(NORM_THREADS), 0, st, h, partials, S, init,
                                              (const T *)gain, (T *)a, (T *)h_copy, M, d, eps));
     FG_LAUNCH_CHECK("add_rmsnorm");
@@ -129,48 +188,55 @@ int32_t launch_add_rmsnorm(int32_t dtype, float *h, const float *partials, int S
 // ---- RoPE + KV append -------------------------------------------------------------------------------------
 // Sums the QKV GEMM's split-K slabs, rotates q and k (rotate-half pairing i, i + hd/2; angles from the table
 // built in double precision at model creation), writes q rows for the attention kernel and the new node's
-// k (token-major) and v (transposed) into its page.
+// k (token-major) and v (transposed) into its page.  One block per row; a thread owns four consecutive pair
+// indices of one head (or four consecutive v elements), all slab loads independent.
 template <typename T>
-__global__ __launch_bounds__(256) void rope_append_kernel(const float *qkv, int S, int M, const int32_t *slot,
-                                                          const int32_t *pos, const int32_t *seq_len,
-                                                          const int32_t *page_table, T *k_pool, T *v_pool, int layer,
-                                                          int n_pages, int n_slots, int max_pages, int N, int n_prev,
-                                                          int Hq, int Hkv, int hd, const float2 *rope_tab, int max_pos,
-                                                          T *q_out)
+__global__ __launch_bounds__(1024) void rope_append_kernel(const float *qkv, int S, int M, const int32_t *slot,
+                                                           const int32_t *pos, const int32_t *seq_len,
+                                                           const int32_t *page_table, T *k_pool, T *v_pool, int layer,
+                                                           int n_pages, int n_slots, int max_pages, int N, int n_prev,
+                                                           int Hq, int Hkv, int hd, const float2 *rope_tab, int max_pos,
+                                                           T *q_out)
 {
     const int r = blockIdx.x, b = r / N, j = r % N;
-    const int QKVD = (Hq + 2 * Hkv) * hd, half = hd >> 1;
+    const int QKVD = (Hq + 2 * Hkv) * hd, half = hd >> 1, quads = half >> 2;
     const int s = min(max(slot[b], 0), n_slots - 1);
     const int p = min(max(pos[r], 0), max_pos - 1);
     const int at = seq_len[s] + n_prev + j;                 // cache slot of this node
     const int page_idx = min(at >> 4, max_pages - 1);
     const int page = min(max(page_table[(size_t)s * max_pages + page_idx], 0), n_pages - 1);
     const int t = at & 15;
-    auto val = [&](int c) {
-        float x = 0.f;
-        for (int z = 0; z < S; z++) x += qkv[((size_t)z * M + r) * QKVD + c];
-        return x;
-    };
-    // rotated pairs of q and k heads
-    for (int w = threadIdx.x; w < (Hq + Hkv) * half; w += blockDim.x) {
-        int head = w / half, i = w % half;
-        float a = val(head * hd + i), bb = val(head * hd + i + half);
-        float2 cs = rope_tab[(size_t)p * half + i];
-        float x0 = a * cs.x - bb * cs.y, x1 = bb * cs.x + a * cs.y;
-        if (head < Hq) {
-            q_out[(size_t)r * Hq * hd + head * hd + i] = from_f<T>(x0);
-            q_out[(size_t)r * Hq * hd + head * hd + i + half] = from_f<T>(x1);
+    const size_t slab = (size_t)M * QKVD;
+    const float *row = qkv + (size_t)r * QKVD;
+    const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int n_rot = (Hq + Hkv) * quads, n_v = Hkv * hd / 4;
+    for (int w = threadIdx.x; w < n_rot + n_v; w += blockDim.x) {
+        if (w < n_rot) {
+            int head = w / quads, i = (w % quads) * 4;
+            float4 a = slab_sum4(row + head * hd + i, slab, S, zero);
+            float4 bb = slab_sum4(row + head * hd + i + half, slab, S, zero);
+            const float2 *cs = rope_tab + (size_t)p * half + i;
+            float2 c0 = cs[0], c1 = cs[1], c2 = cs[2], c3 = cs[3];
+            float4 x0 = make_float4(a.x * c0.x - bb.x * c0.y, a.y * c1.x - bb.y * c1.y, a.z * c2.x - bb.z * c2.y,
+                                    a.w * c3.x - bb.w * c3.y);
+            float4 x1 = make_float4(bb.x * c0.x + a.x * c0.y, bb.y * c1.x + a.y * c1.y, bb.z * c2.x + a.z * c2.y,
+                                    bb.w * c3.x + a.w * c3.y);
+            if (head < Hq) {
+                T *o = q_out + (size_t)r * Hq * hd + head * hd + i;
+                store4<T>(o, x0);
+                store4<T>(o + half, x1);
+            } else {
+                int hk = head - Hq;
+                T *o = k_pool + ((((size_t)layer * n_pages + page) * Hkv + hk) * 16 + t) * hd + i;
+                store4<T>(o, x0);
+                store4<T>(o + half, x1);
+            }
         } else {
-            int hk = head - Hq;
-            size_t base = ((((size_t)layer * n_pages + page) * Hkv + hk) * 16 + t) * hd;
-            k_pool[base + i] = from_f<T>(x0);
-            k_pool[base + i + half] = from_f<T>(x1);
+            int e4 = (w - n_rot) * 4, hk = e4 / hd, e = e4 % hd;
+            float4 v = slab_sum4(row + (Hq + Hkv) * hd + e4, slab, S, zero);
+            T *o = v_pool + (((size_t)layer * n_pages + page) * Hkv + hk) * 16 * hd + (size_t)e * 16 + t;
+            o[0] = from_f<T>(v.x); o[16] = from_f<T>(v.y); o[32] = from_f<T>(v.z); o[48] = from_f<T>(v.w);
         }
-    }
-    for (int w = threadIdx.x; w < Hkv * hd; w += blockDim.x) {
-        int hk = w / hd, e = w % hd;
-        size_t base = (((size_t)layer * n_pages + page) * Hkv + hk) * 16 * hd;
-        v_pool[base + (size_t)e * 16 + t] = from_f<T>(val((Hq + Hkv) * hd + w));
     }
 }
 
@@ -178,10 +244,12 @@ int32_t launch_rope_append(int32_t dtype, const float *qkv_partials, int S, cons
                            int layer, const float *rope_tab, int max_pos, int Hq, void *q_out, hipStream_t st)
 {
     int M = t->B * t->N;
-    FG_DISPATCH(dtype, T, hipLaunchKernelGGL(rope_append_kernel<T>, dim3(M), dim3(256), 0, st, qkv_partials, S, M, t->slot, td.pos,
-                                             kv->seq_len, kv->page_table, (T *)kv->k_pool, (T *)kv->v_pool, layer, kv->n_pages,
-                                             kv->n_slots, kv->max_pages_per_seq, t->N, t->n_prev, Hq, kv->n_kv_heads,
-                                             kv->head_dim, (const float2 *)rope_tab, max_pos, (T *)q_out));
+    const int work = (Hq + kv->n_kv_heads) * (kv->head_dim / 8) + kv->n_kv_heads * kv->head_dim / 4;
+    const int threads = work >= 1024 ? 1024 : (work + 63) / 64 * 64;
+    FG_DISPATCH(dtype, T, hipLaunchKernelGGL(rope_append_kernel<T>, dim3(M), dim3(threads), 0, st, qkv_partials, S, M, t->slot,
+                                             td.pos, kv->seq_len, kv->page_table, (T *)kv->k_pool, (T *)kv->v_pool, layer,
+                                             kv->n_pages, kv->n_slots, kv->max_pages_per_seq, t->N, t->n_prev, Hq,
+                                             kv->n_kv_heads, kv->head_dim, (const float2 *)rope_tab, max_pos, (T *)q_out));
     FG_LAUNCH_CHECK("rope_append");
     return FG_OK;
 }
