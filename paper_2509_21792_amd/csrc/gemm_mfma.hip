@@ -11,6 +11,8 @@
 // Block = WM x WN waves; a wave owns MT x NT tiles of 32 x 32 outputs.  WM = 1 with MT = ceil(M / 32) is the
 // weight-streaming (memory-bound) shape: every byte of W is read exactly once per GEMM.  Split-K over
 // blockIdx.z writes fp32 partial slabs that the consumer kernel sums (no atomics: results are deterministic).
+#include <stdlib.h>
+
 #include <vector>
 
 #include "fg_common.h"
@@ -42,7 +44,7 @@ constexpr int KT = 4;  // k tiles (of 16) per chunk: 64 k
 template <typename T, int MT, int NT, int WM, int WN, int EPI>
 __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(const T *__restrict__ X, const uint4 *__restrict__ Wp,
                                                                   void *__restrict__ out, int M, int N, int K,
-                                                                  int chunks_per_split)
+                                                                  int chunks_per_split, int raster, int row_blocks)
 {
     constexpr int THREADS = WM * WN * 64;
     constexpr int BM = WM * MT * 32;
@@ -52,11 +54,32 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(const T *__restr
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
-    const int row0 = blockIdx.y * BM;
     const int n_tiles = N >> 5, k_tiles = K >> 4;
-    const int ntile0 = (blockIdx.x * WN + wn) * NT;
+    // Block -> (column band, row block, k split).  With several row blocks the grid is one-dimensional and
+    // XCD-aware: blocks are dealt to the 8 XCDs round-robin by linear id, so XCD x takes the units g * 8 + x
+    // (a unit = one k split of a group of BG adjacent bands) and runs the row_blocks x BG tiles of a unit back to
+    // back.  The ~32 blocks resident on an XCD then share BG bands of W and the row blocks of X through its L2.
+    int bx, by, bz;
+    if (raster) {
+        const int BG = raster;                                             // bands per group
+        const int n_bands = (n_tiles + WN * NT - 1) / (WN * NT);
+        const int n_bgroups = (n_bands + BG - 1) / BG;
+        const int splits = (k_tiles / KT + chunks_per_split - 1) / chunks_per_split;
+        const int per_group = row_blocks * BG;
+        const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+        const int unit = (local / per_group) * 8 + xcd, within = local % per_group;   // unit = (k split, band group)
+        if (unit >= n_bgroups * splits) return;
+        bz = unit / n_bgroups;
+        by = within % row_blocks;
+        bx = (unit % n_bgroups) * BG + within / row_blocks;
+        if (bx >= n_bands) return;
+    } else {
+        bx = blockIdx.x; by = blockIdx.y; bz = blockIdx.z;
+    }
+    const int row0 = by * BM;
+    const int ntile0 = (bx * WN + wn) * NT;
     const int total_chunks = k_tiles / KT;
-    const int c_begin = blockIdx.z * chunks_per_split;
+    const int c_begin = bz * chunks_per_split;
     const int c_end = min(c_begin + chunks_per_split, total_chunks);
     const int n_chunks = c_end - c_begin;
 
@@ -79,76 +102,100 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(const T *__restr
     uint4 xr[XLOADS];
     Frag w[NT][KT];
 
-    auto load_x = [&](int chunk) {
+    // X staging: thread t moves XLOADS 16-byte pieces per chunk; piece idx = i * THREADS + t is k-piece idx % 8
+    // (c) of block row idx / 8 (r), so 8 consecutive lanes read 128 contiguous bytes of one row.  Rows past M are
+    // clamped, not zeroed: an output row depends on its own X row only and rows >= M are never stored.
+    // LDS holds the chunk in MFMA fragment order (fragment (row tile, k tile) = 64 slots of 16 bytes, slot
+    // (k half) * 32 + row), with the slot XOR-swizzled by the k tile (bits 1-2) and the k half (bit 3): the 16
+    // lanes of a store phase (8 pieces of 2 rows) then fall into 16 different bank groups, and the 16 consecutive
+    // lanes of a fragment read still do.
+    const bf16_t *xsrc[XLOADS];
+    int xdst[XLOADS];
 #pragma unroll
-        for (int i = 0; i < XLOADS; i++) {
-            int idx = i * THREADS + tid;
-            int c = idx & 7, r = idx >> 3;
-            int row = row0 + r;
-            if (row < M)
-                xr[i] = *reinterpret_cast<const uint4 *>(X + (size_t)row * K + (size_t)chunk * 64 + c * 8);
-            else
-                xr[i] = make_uint4(0, 0, 0, 0);
-        }
-    };
-    auto store_x = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < XLOADS; i++) {
-            int idx = i * THREADS + tid;
-            int c = idx & 7, r = idx >> 3;
-            xs[buf][(((r >> 5) * KT + (c >> 1)) << 6) + ((c & 1) << 5) + (r & 31)] = xr[i];
-        }
-    };
+    for (int i = 0; i < XLOADS; i++) {
+        int idx = i * THREADS + tid;
+        int c = idx & 7, r = idx >> 3;
+        int row = min(row0 + r, M - 1);
+        xsrc[i] = reinterpret_cast<const bf16_t *>(X) + (size_t)row * K + c * 8;
+        xdst[i] = (((r >> 5) * KT + (c >> 1)) << 6) + ((((c & 1) << 5) + (r & 31)) ^ (((c >> 1) << 1) | ((c & 1) << 3)));
+    }
+#define FG_LOAD_X(chunk)                                                                                  \
+    _Pragma("unroll") for (int i = 0; i < XLOADS; i++) xr[i] = *reinterpret_cast<const uint4 *>(xsrc[i] + (size_t)(chunk) * 64)
+#define FG_STORE_X(buf) _Pragma("unroll") for (int i = 0; i < XLOADS; i++) xs[buf][xdst[i]] = xr[i]
 
     if (n_chunks > 0) {
-        load_x(c_begin);
+        FG_LOAD_X(c_begin);
 #pragma unroll
         for (int j = 0; j < NT; j++)
 #pragma unroll
             for (int kt = 0; kt < KT; kt++) w[j][kt].u = wband[j][(size_t)(c_begin * KT + kt) * 64];
-        store_x(0);
+        FG_STORE_X(0);
         __syncthreads();
-        // One chunk per iteration.  The next chunk's X goes global -> registers at the top and registers -> the
-        // other LDS buffer at the bottom; the next chunk's W fragment kt is requested right after the MFMAs that
-        // consumed the current fragment kt, so a full chunk of MFMA work covers its latency.  The last iteration
-        // re-requests its own chunk (clamped index) instead of branching.
+        // One chunk per iteration.  Latency cover:
+        //   W (HBM / L2)  fragment kt of the next chunk is requested into the registers of fragment kt right after
+        //                 the MFMAs that consumed it, so a full chunk of MFMA work covers its latency;
+        //   X (L2)        next chunk global -> registers at the top, registers -> the other LDS buffer at the bottom;
+        //   LDS           the X fragments of k tile kt + 1 are read while the MFMAs of tile kt run (xa / xb
+        //                 alternate); scheduling barriers keep the compiler from sinking the reads to their use.
+        // The last iteration re-requests its own chunk (clamped index) instead of branching.
+        Frag xa[MT], xb[MT];
+        const int lsw = lane ^ ((lane >> 5) << 3);   // k-half part of the swizzle
         for (int c = 0; c < n_chunks; c++) {
             const int buf = c & 1;
             const int nxt = c_begin + min(c + 1, n_chunks - 1);
-            load_x(nxt);
+            FG_LOAD_X(nxt);
+            const uint4 *xbase = &xs[buf][(wm * MT * KT) << 6];
 #pragma unroll
-            for (int kt = 0; kt < KT; kt++) {
+            for (int i = 0; i < MT; i++) xa[i].u = xbase[((i * KT) << 6) + lsw];
 #pragma unroll
-                for (int i = 0; i < MT; i++) {
-                    Frag xf;
-                    xf.u = xs[buf][(((wm * MT + i) * KT + kt) << 6) + lane];
+            for (int kt = 0; kt < KT; kt += 2) {
 #pragma unroll
-                    for (int j = 0; j < NT; j++)
-                        acc[i][j] = mfma32<T>(xf, w[j][kt], acc[i][j]);
-                }
+                for (int i = 0; i < MT; i++) xb[i].u = xbase[((i * KT + kt + 1) << 6) + (lsw ^ ((kt + 1) << 1))];
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < MT; i++)
+#pragma unroll
+                    for (int j = 0; j < NT; j++) acc[i][j] = mfma32<T>(xa[i], w[j][kt], acc[i][j]);
 #pragma unroll
                 for (int j = 0; j < NT; j++) w[j][kt].u = wband[j][(size_t)(nxt * KT + kt) * 64];
+                __builtin_amdgcn_sched_barrier(0);
+                if (kt + 2 < KT) {
+#pragma unroll
+                    for (int i = 0; i < MT; i++) xa[i].u = xbase[((i * KT + kt + 2) << 6) + (lsw ^ ((kt + 2) << 1))];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < MT; i++)
+#pragma unroll
+                    for (int j = 0; j < NT; j++) acc[i][j] = mfma32<T>(xb[i], w[j][kt + 1], acc[i][j]);
+#pragma unroll
+                for (int j = 0; j < NT; j++) w[j][kt + 1].u = wband[j][(size_t)(nxt * KT + kt + 1) * 64];
+                __builtin_amdgcn_sched_barrier(0);
             }
-            store_x(buf ^ 1);
+            FG_STORE_X(buf ^ 1);
             __syncthreads();
         }
     }
+#undef FG_LOAD_X
+#undef FG_STORE_X
 
-    // epilogue: lane holds column n = lane % 32 of each tile, rows 8 * (r / 4) + 4 * (lane / 32) + r % 4
+    // epilogue: lane holds column n = lane % 32 of each tile, rows 8 * (r / 4) + 4 * (lane / 32) + r % 4.
+    // 32-bit offsets (M * N < 2^31 is checked by the launcher) keep the address arithmetic out of the way.
     const int col_in_tile = lane & 31, row_half = (lane >> 5) * 4;
+    const int mrow0 = row0 + wm * MT * 32 + row_half;
     if (EPI == 0) {
-        float *o = reinterpret_cast<float *>(out) + (size_t)blockIdx.z * M * N;
+        float *o = reinterpret_cast<float *>(out) + (size_t)bz * M * N;
 #pragma unroll
         for (int j = 0; j < NT; j++) {
-            int nt = ntile0 + j;
+            const int nt = ntile0 + j;
             if (nt >= n_tiles) continue;
-            int n = nt * 32 + col_in_tile;
+            const int n = nt * 32 + col_in_tile;
 #pragma unroll
             for (int i = 0; i < MT; i++)
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
-                    int m = row0 + (wm * MT + i) * 32 + 8 * (r >> 2) + row_half + (r & 3);
-                    if (m < M) o[(size_t)m * N + n] = acc[i][j][r];
+                    const int m = mrow0 + i * 32 + 8 * (r >> 2) + (r & 3);
+                    if (m < M) o[m * N + n] = acc[i][j][r];
                 }
         }
     } else {
@@ -156,19 +203,18 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(const T *__restr
         T *o = reinterpret_cast<T *>(out);
         const int F = N >> 1;
 #pragma unroll
-        for (int j = 0; j < NT; j += 2) {
-            int nt = ntile0 + j;
+        for (int j = 0; j + 1 < NT; j += 2) {
+            const int nt = ntile0 + j;
             if (nt + 1 >= n_tiles) continue;  // n_tiles is even and pairs start at even tiles
-            int f = (nt >> 1) * 32 + col_in_tile;
+            const int f = (nt >> 1) * 32 + col_in_tile;
 #pragma unroll
             for (int i = 0; i < MT; i++)
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
-                    int m = row0 + (wm * MT + i) * 32 + 8 * (r >> 2) + row_half + (r & 3);
+                    const int m = mrow0 + i * 32 + 8 * (r >> 2) + (r & 3);
                     if (m < M) {
-                        float g = acc[i][j][r], u = acc[i][(j + 1) % NT][r];
-                        float s = g / (1.f + __expf(-g));
-                        o[(size_t)m * F + f] = from_f<T>(s * u);
+                        const float g = acc[i][j][r], u = acc[i][j + 1][r];
+                        o[m * F + f] = from_f<T>(g / (1.f + __expf(-g)) * u);
                     }
                 }
         }
@@ -187,15 +233,34 @@ struct GemmProfile {
 };
 static GemmProfile g_prof;
 
+static bool raster_enabled()
+{
+    static int v = -1;
+    if (v < 0) {
+        const char *e = getenv("FG_GEMM_RASTER");
+        v = e ? atoi(e) : 1;
+    }
+    return v != 0;
+}
+
 template <typename T, int MT, int NT, int WM, int WN, int EPI>
 static void launch_variant(const void *x, const void *wp, void *out, int M, int N, int K, int split, hipStream_t st)
 {
     const int n_tiles = N / 32, per_block = WN * NT;
     const int total_chunks = K / 64;
     const int cps = (total_chunks + split - 1) / split;
-    dim3 grid((n_tiles + per_block - 1) / per_block, (M + WM * MT * 32 - 1) / (WM * MT * 32), split);
-    hipLaunchKernelGGL((gemm_mfma_kernel<T, MT, NT, WM, WN, EPI>), grid, dim3(WM * WN * 64), 0, st,
-                       reinterpret_cast<const T *>(x), reinterpret_cast<const uint4 *>(wp), out, M, N, K, cps);
+    const int n_bands = (n_tiles + per_block - 1) / per_block, row_blocks = (M + WM * MT * 32 - 1) / (WM * MT * 32);
+    if (row_blocks > 1 && raster_enabled()) {
+        const int BG = n_bands >= 32 ? 4 : (n_bands >= 16 ? 2 : 1);
+        const int units = (n_bands + BG - 1) / BG * split;
+        dim3 grid((unsigned)(8 * ((units + 7) / 8) * row_blocks * BG));
+        hipLaunchKernelGGL((gemm_mfma_kernel<T, MT, NT, WM, WN, EPI>), grid, dim3(WM * WN * 64), 0, st,
+                           reinterpret_cast<const T *>(x), reinterpret_cast<const uint4 *>(wp), out, M, N, K, cps, BG, row_blocks);
+    } else {
+        dim3 grid(n_bands, row_blocks, split);
+        hipLaunchKernelGGL((gemm_mfma_kernel<T, MT, NT, WM, WN, EPI>), grid, dim3(WM * WN * 64), 0, st,
+                           reinterpret_cast<const T *>(x), reinterpret_cast<const uint4 *>(wp), out, M, N, K, cps, 0, row_blocks);
+    }
 }
 
 // Number of k splits: enough blocks to cover the chip a few times over when the output is narrow, never
@@ -222,6 +287,18 @@ int gemm_mfma_split_for(int M, int N, int K)
     return choose_split(M, N, K, 256, 256);
 }
 
+// Tile shape for M > 256 (FG_GEMM_BIG overrides for experiments): 0 = 256 x 256 as 1 x 4 waves of 256 x 64,
+// 1 = 256 x 256 as 2 x 2 waves of 128 x 128, 2 = 128 x 512 as 1 x 8 waves of 128 x 64 (two waves per SIMD).
+static int big_variant()
+{
+    static int v = -1;
+    if (v < 0) {
+        const char *e = getenv("FG_GEMM_BIG");
+        v = e ? atoi(e) : 0;
+    }
+    return v;
+}
+
 template <typename T>
 static int32_t launch_gemm_typed(const void *x, const void *wp, void *out, int M, int N, int K, int epilogue, int split,
                                  hipStream_t st)
@@ -234,7 +311,8 @@ static int32_t launch_gemm_typed(const void *x, const void *wp, void *out, int M
     if (M <= 32) FG_GEMM_CASE(1, 2, 1, 4);
     else if (M <= 64) FG_GEMM_CASE(2, 2, 1, 4);
     else if (M <= 128) FG_GEMM_CASE(4, 2, 1, 4);
-    else if (M <= 256) FG_GEMM_CASE(8, 2, 1, 4);
+    else if (M <= 256 || big_variant() == 0) FG_GEMM_CASE(8, 2, 1, 4);
+    else if (big_variant() == 2) FG_GEMM_CASE(4, 2, 1, 8);
     else FG_GEMM_CASE(4, 4, 2, 2);
 #undef FG_GEMM_CASE
     FG_LAUNCH_CHECK("gemm_mfma");
@@ -248,6 +326,7 @@ int32_t launch_gemm_mfma(int32_t dtype, const void *x, const void *wp, void *out
     if (!is16(dtype)) return fail(FG_ERR_INVALID_ARG, "MFMA GEMM needs a 16-bit dtype");
     if (N % 32 || K % 64) return fail(FG_ERR_SHAPE, "16-bit GEMM needs n_out %% 32 == 0 and n_in %% 64 == 0 (got %d, %d)", N, K);
     if (epilogue == 1 && (N % 64)) return fail(FG_ERR_SHAPE, "gate/up GEMM needs n_out %% 64 == 0");
+    if ((int64_t)M * N >= (1LL << 31)) return fail(FG_ERR_SHAPE, "GEMM output of %d x %d exceeds 2^31 elements", M, N);
     int split = 1;
     if (epilogue == 0) {
         split = split_k > 0 ? split_k : gemm_mfma_split_for(M, N, K);
