@@ -193,18 +193,23 @@ int32_t fg_kv_compact(fg_kv_cache *kv, const int32_t *slot, const int32_t *accep
 
 /*
  * One drafting step (Alg. 1 "generate children for K_draft paths"; Sec. 2 "Draft Model Architectures"): the
- * draft head runs on B * tree->N new in-round nodes.  Node input = fc(embed(token) ++ in_feature row); one
- * decoder layer against the draft's own paged cache with tree attention; the output hidden state is decoded by
- * the target's LM head; per node the K_draft most likely tokens and their log-probabilities come back.
- *   in_feature   model dtype [B, N, d]: the feature each node's token is paired with
- *   child_tok    int32 [B, N, K_draft]; child_logp fp32 [B, N, K_draft] (log-softmax, descending, ties by index)
- *   out_feature  model dtype [B, N, d]: the head's output hidden state of each node
- * n_commit (device [B] or NULL): after the step, seq_len[slot[b]] += n_commit[b] -- used for the catch-up chain
- * of accepted tokens, which stays in the draft cache; NULL leaves lengths alone.
+ * draft head runs on B * tree->N new in-round nodes.  Node input = fc(embed(token) ++ feature row); one decoder
+ * layer against the draft's own paged cache with tree attention; the output hidden state is decoded by the
+ * target's LM head; per node the K_draft most likely tokens and their log-probabilities come back.
+ *   in_feature   model dtype [B, feat_rows, d]; node (b, j) is paired with row feat_index[b][j] of sequence b
+ *                (feat_index device int32 [B, N], NULL = row j, which needs feat_rows >= N)
+ *   child_tok    int32 [B, N, K_draft]; child_logp fp32 [B, N, K_draft] (log-softmax, descending, ties by
+ *                index); both NULL skips the LM head
+ *   out_feature  model dtype [B, N, d]: the head's output hidden state of each node (NULL to skip)
+ * n_commit (device [B] or NULL): after the step seq_len[slot[b]] += n_commit[b] + commit_bias -- used for the
+ * catch-up chain of accepted tokens, which stays in the draft cache (pass the verify step's accept_len with bias
+ * 1); NULL leaves lengths alone.  Rows of a catch-up chain beyond the committed count are padding: they are
+ * computed and written past the committed length, where the next nodes overwrite them.
  */
 int32_t fg_draft_step(fg_model *target, fg_model *draft, fg_kv_cache *draft_kv, const fg_tree *tree,
-                      const void *in_feature, const int32_t *n_commit, int32_t K_draft, int32_t *child_tok,
-                      float *child_logp, void *out_feature, void *workspace, int64_t workspace_bytes, void *stream);
+                      const void *in_feature, const int32_t *feat_index, int32_t feat_rows, const int32_t *n_commit,
+                      int32_t commit_bias, int32_t K_draft, int32_t *child_tok, float *child_logp, void *out_feature,
+                      void *workspace, int64_t workspace_bytes, void *stream);
 
 /*
  * Frontier update between drafting steps (Alg. 1 "update candidate tokens T_candi").  The K_in expanded nodes
@@ -213,11 +218,20 @@ int32_t fg_draft_step(fg_model *target, fg_model *draft, fg_kv_cache *draft_kv, 
  * (cand_* are [B, cand_stride]) with score = parent score + log-probability, and the K best children (ties:
  * lower index) become the next frontier: next_tok / next_cand / next_score / next_src [B, K], next_src being
  * the position (0..K_in-1) of the frontier node's parent among this step's nodes.
+ * node_pick (device [B] or NULL): only node node_pick[b] is expanded (its K children are appended); this is the
+ * first step, where the last valid row of the catch-up chain is the root and the rows before it are history.
+ * With node_pick, NULL node_cand / node_score mean candidate 0 (the root) and score 0, and node_tok [B, K_in]
+ * (the step's node tokens), if given, initialises candidate 0 = (token of the picked node, parent -1, score 0).
+ * parent_next (optional, device [B, n_parent_prev + K]): the in-round parent list for the next drafting step =
+ * parent_prev [B, n_parent_prev] (the round's nodes so far, this step's K_in nodes last) followed by the K new
+ * frontier nodes' parents (-1 with node_pick: children of the root attend the committed prefix only).
  */
 int32_t fg_draft_frontier(int32_t B, int32_t K_in, int32_t K, const int32_t *child_tok, const float *child_logp,
-                          const int32_t *node_cand, const float *node_score, int32_t n_cand, int32_t cand_stride,
-                          int32_t *cand_tok, int32_t *cand_parent, float *cand_score, int32_t *next_tok,
-                          int32_t *next_cand, float *next_score, int32_t *next_src, void *stream);
+                          const int32_t *node_cand, const float *node_score, const int32_t *node_pick,
+                          const int32_t *node_tok, int32_t n_cand, int32_t cand_stride, int32_t *cand_tok,
+                          int32_t *cand_parent, float *cand_score, int32_t *next_tok, int32_t *next_cand,
+                          float *next_score, int32_t *next_src, const int32_t *parent_prev, int32_t n_parent_prev,
+                          int32_t *parent_next, void *stream);
 
 /*
  * Rerank (Alg. 1 "select N_verify tokens from T_candi based on their confidences").  Candidate 0 is the root;

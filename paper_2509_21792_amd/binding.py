@@ -79,9 +79,10 @@ def lib():
         L.fg_kv_compact.argtypes = [C.POINTER(KvCacheC), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                     C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
         L.fg_draft_step.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(KvCacheC), C.POINTER(TreeC), C.c_void_p, C.c_void_p,
-                                    C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
-        L.fg_draft_frontier.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
-                                        C.c_int32, C.c_int32] + [C.c_void_p] * 8
+                                    C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                    C.c_void_p, C.c_int64, C.c_void_p]
+        L.fg_draft_frontier.argtypes = [C.c_int32, C.c_int32, C.c_int32] + [C.c_void_p] * 6 + [C.c_int32, C.c_int32] + \
+                                       [C.c_void_p] * 8 + [C.c_int32, C.c_void_p, C.c_void_p]
         L.fg_build_tree.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.fg_gemm.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
@@ -307,36 +308,46 @@ def fg_kv_compact(kv, slot, accept_len, path, feature_in=None, d_model=0):
     return fout
 
 
-def fg_draft_step(target, draft, draft_kv, slot, tokens, parent, in_feature, workspace, K_draft, n_prev=0, n_commit=None,
-                  max_seq_len=0, want_children=True):
+def fg_draft_step(target, draft, draft_kv, slot, tokens, parent, in_feature, workspace, K_draft, n_prev=0, feat_index=None,
+                  n_commit=None, commit_bias=0, max_seq_len=0, want_children=True):
     dev = draft_kv.k_pool.device
     slot, tokens, parent = _dev_i32(slot, dev), _dev_i32(tokens, dev), _dev_i32(parent, dev)
     B, N = tokens.shape
     d = draft.cfg["d_model"]
     in_feature = in_feature.contiguous()
-    assert in_feature.shape == (B, N, d) and in_feature.dtype == _tdtype(draft.dtype)
+    assert in_feature.dim() == 3 and in_feature.shape[0] == B and in_feature.shape[2] == d
+    assert in_feature.dtype == _tdtype(draft.dtype)
+    feat_rows = in_feature.shape[1]
+    if feat_index is not None:
+        feat_index = _dev_i32(feat_index, dev)
     ctok = torch.empty((B, N, K_draft), dtype=torch.int32, device=dev) if want_children else None
     clogp = torch.empty((B, N, K_draft), dtype=torch.float32, device=dev) if want_children else None
     ofeat = torch.empty((B, N, d), dtype=_tdtype(draft.dtype), device=dev)
     if n_commit is not None:
         n_commit = _dev_i32(n_commit, dev)
     tree = _tree(slot, tokens, parent, B, N, n_prev, max_seq_len)
-    _check(lib().fg_draft_step(target.handle, draft.handle, C.byref(draft_kv.c), C.byref(tree), _p(in_feature), _p(n_commit),
-                               K_draft, _p(ctok), _p(clogp), _p(ofeat), _p(workspace), workspace.numel(), _stream()))
+    _check(lib().fg_draft_step(target.handle, draft.handle, C.byref(draft_kv.c), C.byref(tree), _p(in_feature), _p(feat_index),
+                               feat_rows, _p(n_commit), commit_bias, K_draft, _p(ctok), _p(clogp), _p(ofeat), _p(workspace),
+                               workspace.numel(), _stream()))
     return ctok, clogp, ofeat
 
 
-def fg_draft_frontier(child_tok, child_logp, node_cand, node_score, n_cand, cand_tok, cand_parent, cand_score):
+def fg_draft_frontier(child_tok, child_logp, n_cand, cand_tok, cand_parent, cand_score, node_cand=None, node_score=None,
+                      node_pick=None, node_tok=None, parent_prev=None):
+    """Returns (next_tok, next_cand, next_score, next_src, parent_next); parent_prev [B, n] is the round's in-round
+    parent list so far (None / empty before the first step)."""
     B, K_in, K = child_tok.shape
     dev = child_tok.device
     nt = torch.empty((B, K), dtype=torch.int32, device=dev)
     nc = torch.empty((B, K), dtype=torch.int32, device=dev)
     ns = torch.empty((B, K), dtype=torch.float32, device=dev)
     nsrc = torch.empty((B, K), dtype=torch.int32, device=dev)
-    _check(lib().fg_draft_frontier(B, K_in, K, _p(child_tok), _p(child_logp), _p(node_cand), _p(node_score), n_cand,
-                                   cand_tok.shape[1], _p(cand_tok), _p(cand_parent), _p(cand_score), _p(nt), _p(nc), _p(ns),
-                                   _p(nsrc), _stream()))
-    return nt, nc, ns, nsrc
+    npp = 0 if parent_prev is None else parent_prev.shape[1]
+    pnext = torch.empty((B, npp + K), dtype=torch.int32, device=dev)
+    _check(lib().fg_draft_frontier(B, K_in, K, _p(child_tok), _p(child_logp), _p(node_cand), _p(node_score), _p(node_pick),
+                                   _p(node_tok), n_cand, cand_tok.shape[1], _p(cand_tok), _p(cand_parent), _p(cand_score), _p(nt),
+                                   _p(nc), _p(ns), _p(nsrc), _p(parent_prev) if npp else None, npp, _p(pnext), _stream()))
+    return nt, nc, ns, nsrc, pnext
 
 
 def fg_build_tree(cand_tok, cand_parent, cand_score, n_cand, N):

@@ -40,12 +40,14 @@ int32_t launch_kv_compact(fg_kv_cache *kv, const int32_t *slot, const int32_t *a
                           const void *fin, void *fout, int d, int feat_dtype, hipStream_t st);
 int32_t launch_topk_logp(const float *logits, int M, int V, int K, int32_t *tok, float *logp, hipStream_t st);
 int32_t launch_frontier(int B, int K_in, int K, const int32_t *child_tok, const float *child_logp, const int32_t *node_cand,
-                        const float *node_score, int n_cand, int stride, int32_t *cand_tok, int32_t *cand_parent,
-                        float *cand_score, int32_t *next_tok, int32_t *next_cand, float *next_score, int32_t *next_src,
-                        hipStream_t st);
+                        const float *node_score, const int32_t *node_pick, const int32_t *node_tok, int n_cand, int stride,
+                        int32_t *cand_tok, int32_t *cand_parent, float *cand_score, int32_t *next_tok, int32_t *next_cand,
+                        float *next_score, int32_t *next_src, const int32_t *parent_prev, int n_parent_prev,
+                        int32_t *parent_next, hipStream_t st);
 int32_t launch_build_tree(const int32_t *cand_tok, const int32_t *cand_parent, const float *cand_score, int B, int C, int stride,
                           int N, int32_t *tokens, int32_t *parent, int32_t *sel, hipStream_t st);
-int32_t launch_commit_len(int32_t *seq_len, const int32_t *slot, const int32_t *n_commit, int B, int n_slots, hipStream_t st);
+int32_t launch_commit_len(int32_t *seq_len, const int32_t *slot, const int32_t *n_commit, int bias, int B, int n_slots,
+                          hipStream_t st);
 int gemm_mfma_split_for(int M, int N, int K);
 int32_t profile_gemm_arm(int enable, int n_out, int n_in, int epilogue, int max_launches);
 int32_t profile_gemm_read(double *total_ms, int32_t *count);
@@ -427,8 +429,9 @@ int32_t fg_kv_compact(fg_kv_cache *kv, const int32_t *slot, const int32_t *accep
 }
 
 int32_t fg_draft_step(fg_model *target, fg_model *draft, fg_kv_cache *draft_kv, const fg_tree *tree, const void *in_feature,
-                      const int32_t *n_commit, int32_t K_draft, int32_t *child_tok, float *child_logp, void *out_feature,
-                      void *workspace, int64_t workspace_bytes, void *stream)
+                      const int32_t *feat_index, int32_t feat_rows, const int32_t *n_commit, int32_t commit_bias,
+                      int32_t K_draft, int32_t *child_tok, float *child_logp, void *out_feature, void *workspace,
+                      int64_t workspace_bytes, void *stream)
 {
     if (!target || !draft) return fail(FG_ERR_INVALID_ARG, "fg_draft_step: model is NULL");
     if (!draft->fc) return fail(FG_ERR_INVALID_ARG, "fg_draft_step needs a draft head (fc)");
@@ -440,6 +443,7 @@ int32_t fg_draft_step(fg_model *target, fg_model *draft, fg_kv_cache *draft_kv, 
         return fail(FG_ERR_SHAPE, "draft head and target differ in width, vocabulary or dtype");
     if (tree->B == 0 || tree->N == 0) return FG_OK;
     if (!in_feature || !workspace) return fail(FG_ERR_INVALID_ARG, "fg_draft_step: NULL input");
+    if (feat_rows < 1 || (!feat_index && feat_rows < tree->N)) return fail(FG_ERR_INVALID_ARG, "fg_draft_step: bad feat_rows");
     if ((child_tok != nullptr) != (child_logp != nullptr)) return fail(FG_ERR_INVALID_ARG, "child_tok and child_logp go together");
     const int M = tree->B * tree->N, d = c.d_model;
     const int mk = max_keys_of(draft_kv, tree, &rc);
@@ -449,7 +453,7 @@ int32_t fg_draft_step(fg_model *target, fg_model *draft, fg_kv_cache *draft_kv, 
     if (carve_step(c, M, mk, tree->B, tree->N, true, workspace, workspace_bytes, &w, child_tok != nullptr) < 0)
         return fail(FG_ERR_CAPACITY, "workspace too small: have %lld bytes", (long long)workspace_bytes);
     if ((rc = launch_tree_prep_ex(tree, draft_kv->seq_len, draft_kv->n_slots, w.td, st))) return rc;
-    if ((rc = launch_concat_embed(c.dtype, target->embed, tree->tokens, c.vocab, in_feature, w.cat, M, d, st))) return rc;
+    if ((rc = launch_concat_embed(c.dtype, target->embed, tree->tokens, c.vocab, in_feature, feat_index, tree->N, feat_rows, w.cat, M, d, st))) return rc;
     int S = 0;
     if ((rc = gemm_any(c, w.cat, draft->fc, w.partials, M, d, 2 * d, &S, st))) return rc;
     if ((rc = run_layers(draft, draft_kv, tree, w, mk, S, &S, st))) return rc;
@@ -462,23 +466,29 @@ int32_t fg_draft_step(fg_model *target, fg_model *draft, fg_kv_cache *draft_kv, 
         if ((rc = launch_topk_logp(w.logits, M, c.vocab, K_draft, child_tok, child_logp, st))) return rc;
     }
     if (n_commit)
-        if ((rc = launch_commit_len(draft_kv->seq_len, tree->slot, n_commit, tree->B, draft_kv->n_slots, st))) return rc;
+        if ((rc = launch_commit_len(draft_kv->seq_len, tree->slot, n_commit, commit_bias, tree->B, draft_kv->n_slots, st))) return rc;
     return FG_OK;
 }
 
 int32_t fg_draft_frontier(int32_t B, int32_t K_in, int32_t K, const int32_t *child_tok, const float *child_logp,
-                          const int32_t *node_cand, const float *node_score, int32_t n_cand, int32_t cand_stride,
+                          const int32_t *node_cand, const float *node_score, const int32_t *node_pick,
+                          const int32_t *node_tok, int32_t n_cand, int32_t cand_stride,
                           int32_t *cand_tok, int32_t *cand_parent, float *cand_score, int32_t *next_tok, int32_t *next_cand,
-                          float *next_score, int32_t *next_src, void *stream)
+                          float *next_score, int32_t *next_src, const int32_t *parent_prev, int32_t n_parent_prev,
+                          int32_t *parent_next, void *stream)
 {
     if (B < 0 || K_in < 1 || K < 1 || K_in * K > 64 || K > K_in * K) return fail(FG_ERR_INVALID_ARG, "fg_draft_frontier: bad K_in / K");
-    if (n_cand < 0 || n_cand + K_in * K > cand_stride) return fail(FG_ERR_CAPACITY, "candidate lists too short");
+    if (n_cand < 0 || n_cand + (node_pick ? K : K_in * K) > cand_stride) return fail(FG_ERR_CAPACITY, "candidate lists too short");
     if (B == 0) return FG_OK;
-    if (!child_tok || !child_logp || !node_cand || !node_score || !cand_tok || !cand_parent || !cand_score || !next_tok ||
+    if ((!node_pick && (!node_cand || !node_score)) || !child_tok || !child_logp || !cand_tok || !cand_parent || !cand_score || !next_tok ||
         !next_cand || !next_score || !next_src)
         return fail(FG_ERR_INVALID_ARG, "fg_draft_frontier: NULL pointer");
-    return launch_frontier(B, K_in, K, child_tok, child_logp, node_cand, node_score, n_cand, cand_stride, cand_tok, cand_parent,
-                           cand_score, next_tok, next_cand, next_score, next_src, (hipStream_t)stream);
+    if (n_parent_prev < 0 || n_parent_prev + K > FG_MAX_NODES || (parent_next && n_parent_prev > 0 && !parent_prev) ||
+        (parent_next && !node_pick && n_parent_prev < K_in))
+        return fail(FG_ERR_INVALID_ARG, "fg_draft_frontier: bad parent list");
+    return launch_frontier(B, K_in, K, child_tok, child_logp, node_cand, node_score, node_pick, node_tok, n_cand, cand_stride, cand_tok, cand_parent,
+                           cand_score, next_tok, next_cand, next_score, next_src, parent_prev, n_parent_prev, parent_next,
+                           (hipStream_t)stream);
 }
 
 int32_t fg_build_tree(const int32_t *cand_tok, const int32_t *cand_parent, const float *cand_score, int32_t B, int32_t n_cand,

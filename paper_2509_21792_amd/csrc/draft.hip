@@ -72,21 +72,30 @@ int32_t launch_topk_logp(const float *logits, int M, int V, int K, int32_t *tok,
     return FG_OK;
 }
 
-// Frontier update, one thread per sequence (at most 64 children).
+// Frontier update, one thread per sequence (at most 64 children).  With node_pick only the children of node
+// node_pick[b] count (the catch-up chain's last valid row is the root; the rows before it are not expanded).
 __global__ void frontier_kernel(int B, int K_in, int K, const int32_t *child_tok, const float *child_logp,
-                                const int32_t *node_cand, const float *node_score, int n_cand, int stride,
-                                int32_t *cand_tok, int32_t *cand_parent, float *cand_score, int32_t *next_tok,
-                                int32_t *next_cand, float *next_score, int32_t *next_src)
+                                const int32_t *node_cand, const float *node_score, const int32_t *node_pick,
+                                const int32_t *node_tok, int n_cand, int stride, int32_t *cand_tok, int32_t *cand_parent,
+                                float *cand_score, int32_t *next_tok, int32_t *next_cand, float *next_score, int32_t *next_src,
+                                const int32_t *parent_prev, int n_parent_prev, int32_t *parent_next)
 {
     int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
-    const int C = K_in * K;
+    const int pick = node_pick ? min(max(node_pick[b], 0), K_in - 1) : -1;
+    if (pick >= 0 && node_tok) {   // first step: candidate 0 is the root
+        cand_tok[(size_t)b * stride] = node_tok[(size_t)b * K_in + pick];
+        cand_parent[(size_t)b * stride] = -1;
+        cand_score[(size_t)b * stride] = 0.f;
+    }
+    const int C = pick >= 0 ? K : K_in * K, base = pick >= 0 ? pick * K : 0;
     for (int i = 0; i < C; i++) {
-        int src = i / K;
-        float sc = node_score[(size_t)b * K_in + src] + child_logp[(size_t)b * C + i];
-        cand_tok[(size_t)b * stride + n_cand + i] = child_tok[(size_t)b * C + i];
-        cand_parent[(size_t)b * stride + n_cand + i] = node_cand[(size_t)b * K_in + src];
-        cand_score[(size_t)b * stride + n_cand + i] = sc;
+        int src = (base + i) / K;
+        float ps = node_score ? node_score[(size_t)b * K_in + src] : 0.f;
+        int pc = node_cand ? node_cand[(size_t)b * K_in + src] : 0;
+        cand_tok[(size_t)b * stride + n_cand + i] = child_tok[(size_t)b * K_in * K + base + i];
+        cand_parent[(size_t)b * stride + n_cand + i] = pc;
+        cand_score[(size_t)b * stride + n_cand + i] = ps + child_logp[(size_t)b * K_in * K + base + i];
     }
     uint64_t used = 0;
     for (int k = 0; k < K; k++) {
@@ -101,18 +110,26 @@ __global__ void frontier_kernel(int B, int K_in, int K, const int32_t *child_tok
         next_tok[(size_t)b * K + k] = cand_tok[(size_t)b * stride + n_cand + best];
         next_cand[(size_t)b * K + k] = n_cand + best;
         next_score[(size_t)b * K + k] = bs;
-        next_src[(size_t)b * K + k] = best / K;
+        next_src[(size_t)b * K + k] = (base + best) / K;
+        // in-round parent of the new frontier node: this step's nodes are the last K_in in-round nodes; the
+        // children of the root hang off the committed prefix
+        if (parent_next)
+            parent_next[(size_t)b * (n_parent_prev + K) + n_parent_prev + k] = pick >= 0 ? -1 : n_parent_prev - K_in + best / K;
     }
+    if (parent_next)
+        for (int i = 0; i < n_parent_prev; i++)
+            parent_next[(size_t)b * (n_parent_prev + K) + i] = parent_prev[(size_t)b * n_parent_prev + i];
 }
 
 int32_t launch_frontier(int B, int K_in, int K, const int32_t *child_tok, const float *child_logp, const int32_t *node_cand,
-                        const float *node_score, int n_cand, int stride, int32_t *cand_tok, int32_t *cand_parent,
-                        float *cand_score, int32_t *next_tok, int32_t *next_cand, float *next_score, int32_t *next_src,
-                        hipStream_t st)
+                        const float *node_score, const int32_t *node_pick, const int32_t *node_tok, int n_cand, int stride,
+                        int32_t *cand_tok, int32_t *cand_parent, float *cand_score, int32_t *next_tok, int32_t *next_cand,
+                        float *next_score, int32_t *next_src, const int32_t *parent_prev, int n_parent_prev,
+                        int32_t *parent_next, hipStream_t st)
 {
     hipLaunchKernelGGL(frontier_kernel, dim3((B + 63) / 64), dim3(64), 0, st, B, K_in, K, child_tok, child_logp, node_cand,
-                       node_score, n_cand, stride, cand_tok, cand_parent, cand_score, next_tok, next_cand, next_score,
-                       next_src);
+                       node_score, node_pick, node_tok, n_cand, stride, cand_tok, cand_parent, cand_score, next_tok, next_cand, next_score,
+                       next_src, parent_prev, n_parent_prev, parent_next);
     FG_LAUNCH_CHECK("frontier");
     return FG_OK;
 }
@@ -175,17 +192,18 @@ int32_t launch_build_tree(const int32_t *cand_tok, const int32_t *cand_parent, c
     return FG_OK;
 }
 
-__global__ void commit_len_kernel(int32_t *seq_len, const int32_t *slot, const int32_t *n_commit, int B, int n_slots)
+__global__ void commit_len_kernel(int32_t *seq_len, const int32_t *slot, const int32_t *n_commit, int bias, int B, int n_slots)
 {
     int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
     int s = min(max(slot[b], 0), n_slots - 1);
-    seq_len[s] += max(n_commit[b], 0);
+    seq_len[s] += max(n_commit[b] + bias, 0);
 }
 
-int32_t launch_commit_len(int32_t *seq_len, const int32_t *slot, const int32_t *n_commit, int B, int n_slots, hipStream_t st)
+int32_t launch_commit_len(int32_t *seq_len, const int32_t *slot, const int32_t *n_commit, int bias, int B, int n_slots,
+                          hipStream_t st)
 {
-    hipLaunchKernelGGL(commit_len_kernel, dim3((B + 63) / 64), dim3(64), 0, st, seq_len, slot, n_commit, B, n_slots);
+    hipLaunchKernelGGL(commit_len_kernel, dim3((B + 63) / 64), dim3(64), 0, st, seq_len, slot, n_commit, bias, B, n_slots);
     FG_LAUNCH_CHECK("commit_len");
     return FG_OK;
 }

@@ -53,23 +53,26 @@ int32_t launch_embed(int32_t dtype, const void *embed, const int32_t *tokens, in
     return FG_OK;
 }
 
-// cat[r] = embed[token r] ++ feat[r]  (the draft head's fc input)
+// cat[r] = embed[token r] ++ feat[b][src]  (the draft head's fc input); src = feat_index[r] if given, else j
 template <typename T>
-__global__ void concat_embed_kernel(const T *embed, const int32_t *tokens, int vocab, const T *feat, T *cat, int d)
+__global__ void concat_embed_kernel(const T *embed, const int32_t *tokens, int vocab, const T *feat, const int32_t *feat_index,
+                                    int N, int feat_rows, T *cat, int d)
 {
-    int r = blockIdx.x;
+    int r = blockIdx.x, b = r / N, j = r % N;
     int tok = min(max(tokens[r], 0), vocab - 1);
+    int src = feat_index ? min(max(feat_index[r], 0), feat_rows - 1) : min(j, feat_rows - 1);
+    const T *f = feat + ((size_t)b * feat_rows + src) * d;
     for (int c = threadIdx.x; c < d; c += blockDim.x) {
         cat[(size_t)r * 2 * d + c] = embed[(size_t)tok * d + c];
-        cat[(size_t)r * 2 * d + d + c] = feat[(size_t)r * d + c];
+        cat[(size_t)r * 2 * d + d + c] = f[c];
     }
 }
 
-int32_t launch_concat_embed(int32_t dtype, const void *embed, const int32_t *tokens, int vocab, const void *feat, void *cat,
-                            int M, int d, hipStream_t st)
+int32_t launch_concat_embed(int32_t dtype, const void *embed, const int32_t *tokens, int vocab, const void *feat,
+                            const int32_t *feat_index, int N, int feat_rows, void *cat, int M, int d, hipStream_t st)
 {
     FG_DISPATCH(dtype, T, hipLaunchKernelGGL(concat_embed_kernel<T>, dim3(M), dim3(256), 0, st, (const T *)embed, tokens, vocab,
-                                             (const T *)feat, (T *)cat, d));
+                                             (const T *)feat, feat_index, N, feat_rows, (T *)cat, d));
     FG_LAUNCH_CHECK("concat_embed");
     return FG_OK;
 }

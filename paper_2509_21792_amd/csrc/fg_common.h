@@ -97,8 +97,8 @@ int32_t launch_gemm_f32(const float *x, const float *w, float *out, int M, int N
 int32_t launch_pack(int32_t dtype, const void *src, const void *src2, void *dst, int64_t n_out, int64_t n_in, hipStream_t st);
 
 int32_t launch_embed(int32_t dtype, const void *embed, const int32_t *tokens, int vocab, float *h, int M, int d, hipStream_t st);
-int32_t launch_concat_embed(int32_t dtype, const void *embed, const int32_t *tokens, int vocab, const void *feat, void *cat,
-                            int M, int d, hipStream_t st);
+int32_t launch_concat_embed(int32_t dtype, const void *embed, const int32_t *tokens, int vocab, const void *feat,
+                            const int32_t *feat_index, int N, int feat_rows, void *cat, int M, int d, hipStream_t st);
 // h (+)= sum of S partial slabs; optional norm output a = rmsnorm(h) * gain (dtype), optional copy of h as dtype
 int32_t launch_add_rmsnorm(int32_t dtype, float *h, const float *partials, int S, int init, const void *gain, void *a,
                            void *h_copy, int M, int d, float eps, hipStream_t st);

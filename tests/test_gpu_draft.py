@@ -1,0 +1,185 @@
+"""GPU parity of the draft side (drafting step, frontier update, rerank) and of the whole generation loop on
+config 1 against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import loop as oloop
+from synth import configs, gen
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H():
+    from tests import harness
+    assert torch.cuda.is_available()
+    return harness
+
+
+def topk_agree(g_tok, g_logp, o_tok, o_logp, o_logits, tol, margin):
+    """Top-K tokens equal rank by rank except where the oracle's neighbouring logits are within `margin`."""
+    assert np.abs(g_logp - o_logp)[g_tok == o_tok].max() <= tol
+    bad = 0
+    for r in range(o_tok.shape[0]):
+        for k in range(o_tok.shape[1]):
+            if g_tok[r, k] != o_tok[r, k]:
+                srt = np.sort(o_logits[r])[::-1]
+                assert srt[k] - srt[k + 1] < margin or (k > 0 and srt[k - 1] - srt[k] < margin), (r, k)
+                bad += 1
+    return bad
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "fp16", "bf16"])
+def test_draft_step_with_in_round_nodes(H, dtype):
+    import paper_2509_21792_amd as fg
+    base = configs.TINY if dtype == "fp32" else configs.with_dtype(configs.scaled(configs.Q1P5B, 1), dtype)
+    model = configs.scaled(base, 1) if dtype == "fp32" else base
+    pair = H.Pair(model, seed=3, with_draft=True)
+    dcfg = pair.dcfg
+    B, n_prev, N, K = 4, 3, 5, 4
+    lengths = np.array([9, 40, 16, 100], dtype=np.int32)
+    st = H.State(pair, dcfg, lengths, n_prev + N + 1, seed=4)
+    rng = np.random.default_rng(5)
+    n_tot = n_prev + N
+    parent = np.stack([np.array([-1] + [int(rng.integers(-1, i)) for i in range(1, n_tot)], dtype=np.int32) for _ in range(B)])
+    tok_all = rng.integers(0, model["vocab"], size=(B, n_tot)).astype(np.int32)
+    td = {"fp32": torch.float32, "fp16": torch.float16, "bf16": torch.bfloat16}[dtype]
+    feat_all = (torch.randn((B, n_tot, model["d_model"]), generator=torch.Generator().manual_seed(6)) * 1.0).to(td)
+    ws = pair.gd.workspace(B * n_tot, st.cap)
+    fa = feat_all.cuda()
+    # first the n_prev nodes, then the N new ones that see them
+    fg.fg_draft_step(pair.gm, pair.gd, st.kv, st.slot, tok_all[:, :n_prev], parent[:, :n_prev], fa[:, :n_prev].contiguous(), ws, K)
+    ctok, clogp, ofeat = fg.fg_draft_step(pair.gm, pair.gd, st.kv, st.slot, tok_all[:, n_prev:], parent, fa, ws, K,
+                                          n_prev=n_prev, feat_index=np.tile(np.arange(n_prev, n_tot, dtype=np.int32), (B, 1)))
+    torch.cuda.synchronize()
+    orc = pair.orc
+    fnp = feat_all.float().numpy()
+    orc.tree_forward(pair.od, st.ocache, tok_all[:, :n_prev], parent[:, :n_prev], feat_in=fnp[:, :n_prev], is_draft=True)
+    oh, ol = orc.tree_forward(pair.od, st.ocache, tok_all[:, n_prev:], parent, feat_in=fnp[:, n_prev:], n_prev=n_prev, is_draft=True)
+    o_tok, o_logp = orc.topk_logp(ol, K)
+    herr = np.abs(ofeat.float().cpu().numpy().reshape(B * N, -1) - oh).max()
+    tol = {"fp32": 1e-4, "fp16": 5e-3, "bf16": 4e-2}[dtype]
+    assert herr <= tol, herr
+    n_bad = topk_agree(ctok.cpu().numpy().reshape(B * N, K), clogp.cpu().numpy().reshape(B * N, K), o_tok, o_logp, ol,
+                       tol=max(tol, 1e-4) * 3, margin={"fp32": 1e-3, "fp16": 0.05, "bf16": 0.15}[dtype])
+    assert (st.kv.seq_len.cpu().numpy() == lengths).all()
+    print(f"draft step {dtype}: hidden err {herr:.3g}, {n_bad} exempt top-K swaps", flush=True)
+
+
+def test_frontier_and_rerank_are_bit_exact(H):
+    """Integer / comparison work: candidate lists, frontier choice, parent lists and the reranked tree against the oracle."""
+    import paper_2509_21792_amd as fg
+    orc = H.Oracle("f32")
+    rng = np.random.default_rng(2)
+    B, K, L = 37, 4, 5
+    n_total = 1 + K + (L - 1) * K * K
+    ct = torch.zeros((B, n_total), dtype=torch.int32, device="cuda")
+    cp = torch.zeros((B, n_total), dtype=torch.int32, device="cuda")
+    cs = torch.zeros((B, n_total), dtype=torch.float32, device="cuda")
+    Kin = 3
+    catch_tok = rng.integers(0, 1000, size=(B, Kin)).astype(np.int32)
+    pick = rng.integers(0, Kin, size=B).astype(np.int32)
+    # log-probabilities on a coarse grid so that equal scores (ties) occur
+    ctok = rng.integers(0, 1000, size=(B, Kin, K)).astype(np.int32)
+    clogp = -(rng.integers(1, 6, size=(B, Kin, K)).astype(np.float32)) * 0.5
+    o_tok = [catch_tok[np.arange(B), pick].reshape(B, 1), ctok[np.arange(B), pick]]
+    o_par = [np.full((B, 1), -1, np.int32), np.zeros((B, K), np.int32)]
+    o_sc = [np.zeros((B, 1), np.float32), clogp[np.arange(B), pick]]
+    nt, nc, ns, nsrc, parents = fg.fg_draft_frontier(torch.as_tensor(ctok).cuda(), torch.as_tensor(clogp).cuda(), 1, ct, cp, cs,
+                                                     node_pick=torch.as_tensor(pick).cuda(), node_tok=torch.as_tensor(catch_tok).cuda())
+    torch.cuda.synchronize()
+    assert (parents.cpu().numpy() == -1).all() and parents.shape == (B, K)
+    assert np.array_equal(nsrc.cpu().numpy(), np.repeat(pick[:, None], K, axis=1))
+    f_score = o_sc[1].copy(); f_cand = np.tile(np.arange(1, K + 1, dtype=np.int32), (B, 1))
+    # the root's K children come back best-first (stable) as the first frontier
+    order = np.argsort(-f_score, axis=1, kind="stable")
+    assert np.array_equal(nc.cpu().numpy(), 1 + order)
+    f_tok, f_cand, f_score = nt.cpu().numpy(), nc.cpu().numpy(), ns.cpu().numpy()
+    n_cand, o_parents = 1 + K, np.full((B, K), -1, np.int32)
+    for step in range(2, L + 1):
+        ctok = rng.integers(0, 1000, size=(B, K, K)).astype(np.int32)
+        clogp = -(rng.integers(1, 6, size=(B, K, K)).astype(np.float32)) * 0.5
+        g = fg.fg_draft_frontier(torch.as_tensor(ctok).cuda(), torch.as_tensor(clogp).cuda(), n_cand, ct, cp, cs,
+                                 node_cand=torch.as_tensor(f_cand).cuda(), node_score=torch.as_tensor(f_score).cuda(),
+                                 parent_prev=torch.as_tensor(o_parents).cuda())
+        torch.cuda.synchronize()
+        cscore = (f_score[:, :, None] + clogp).astype(np.float32).reshape(B, K * K)
+        o_tok.append(ctok.reshape(B, K * K)); o_par.append(np.repeat(f_cand, K, axis=1)); o_sc.append(cscore)
+        pickk = orc.topk_index(cscore, K)
+        rows = np.arange(B)[:, None]
+        want_tok, want_score, want_cand = ctok.reshape(B, K * K)[rows, pickk], cscore[rows, pickk], (n_cand + pickk).astype(np.int32)
+        assert np.array_equal(g[0].cpu().numpy(), want_tok) and np.array_equal(g[1].cpu().numpy(), want_cand)
+        assert np.array_equal(g[2].cpu().numpy(), want_score) and np.array_equal(g[3].cpu().numpy(), pickk // K)
+        n_prev = (step - 2) * K
+        o_parents = np.concatenate([o_parents, (n_prev + pickk // K).astype(np.int32)], axis=1)
+        assert np.array_equal(g[4].cpu().numpy(), o_parents)
+        f_tok, f_cand, f_score = want_tok, want_cand, want_score
+        n_cand += K * K
+    ot, op, os_ = np.concatenate(o_tok, 1), np.concatenate(o_par, 1), np.concatenate(o_sc, 1)
+    assert np.array_equal(ct.cpu().numpy(), ot) and np.array_equal(cp.cpu().numpy(), op) and np.array_equal(cs.cpu().numpy(), os_)
+    for N in (1, 2, 8, 24, 64):
+        tokens, parent, sel = fg.fg_build_tree(ct, cp, cs, n_total, N)
+        torch.cuda.synchronize()
+        wt, wp, wsel = orc.build_tree(ot, op, os_, N)
+        assert np.array_equal(tokens.cpu().numpy(), wt) and np.array_equal(parent.cpu().numpy(), wp)
+        assert np.array_equal(sel.cpu().numpy(), wsel)
+
+
+def test_config1_generation_loop_matches_plain_greedy_decoding(H):
+    """Config 1 end to end on the GPU (fp32, 8 sequences, prompts of 32 tokens, chain draft depth 4 from the 1-layer
+    head, 64 new tokens, greedy) against the oracle's plain autoregressive tokens.  A sequence may leave the
+    comparison only at a position whose oracle top-2 margin is below 0.05."""
+    import paper_2509_21792_amd as fg
+    from paper_2509_21792_amd import loop as gloop
+    cfg = configs.CONFIGS["cfg1"]
+    model = configs.TINY
+    pair = H.Pair(model, seed=cfg["seed"], with_draft=True)
+    orc = pair.orc
+    B, P, n_new, N = cfg["B"], cfg["prompt_len"], cfg["new_tokens"], cfg["N"]
+    K, L = 1, N - 1
+    prompts = gen.make_prompts(B, cfg["group"], P, model["vocab"], cfg["seed"])
+    # oracle: plain greedy decoding
+    ocache = orc.cache(model, B, P + n_new + 8)
+    _, ologits = oloop.prefill(orc, pair.om, ocache, prompts)
+    oroot, m0 = orc.row_argmax(ologits[:, -1])
+    orest, omar = oloop.greedy_ar(orc, pair.om, ocache, oroot, n_new - 1)
+    ref = np.concatenate([oroot[:, None], orest], axis=1)
+    margins = np.concatenate([m0[:, None], omar], axis=1)
+    # GPU: prefill = one chain verify step from an empty cache, committed whole
+    cap = P + n_new + N + 8
+    table, n_pages = gen.make_page_table(np.zeros(B, np.int32), cap, 16, 1)
+    kv = fg.KVCache(model, table, n_pages)
+    dtable, dn = gen.make_page_table(np.zeros(B, np.int32), cap, 16, 2)
+    dkv = fg.KVCache(pair.dcfg, dtable, dn)
+    slot = torch.arange(B, dtype=torch.int32, device="cuda")
+    ws_t = pair.gm.workspace(B * P, cap)
+    ws_d = pair.gd.workspace(B * P, cap)
+    ptok = torch.as_tensor(prompts).cuda()
+    out = fg.fg_spec_verify(pair.gm, kv, slot, ptok, gloop.chain_parent(B, P, "cuda"), ws_t, want_logits=False)
+    ident = torch.arange(P, dtype=torch.int32, device="cuda").repeat(B, 1)
+    feat = fg.fg_kv_compact(kv, slot, torch.full((B,), P - 1, dtype=torch.int32, device="cuda"), ident,
+                            feature_in=out["feature"].view(B, P, -1), d_model=model["d_model"])
+    root = out["argmax"].view(B, P)[:, -1].contiguous()
+    catch_tok = torch.cat([ptok[:, 1:], root.view(B, 1)], dim=1).contiguous()
+    st = gloop.SpecState(catch_tok, feat, torch.full((B,), P - 1, dtype=torch.int32, device="cuda"))
+    outs = [[int(t)] for t in root.cpu().numpy()]
+    rounds, accepted = 0, 0
+    while min(len(o) for o in outs) < n_new and rounds < 200:
+        acc, otok, fin, st = gloop.spec_round(pair.gm, pair.gd, kv, dkv, slot, st, N, K, L, ws_t, ws_d)
+        a, t = acc.cpu().numpy(), otok.cpu().numpy()
+        for b in range(B):
+            outs[b].extend(int(x) for x in t[b, :a[b] + 1])
+        accepted += int(a.sum()) + B
+        rounds += 1
+    got = np.array([o[:n_new] for o in outs])
+    n_exempt = 0
+    for b in range(B):
+        diff = np.nonzero(got[b] != ref[b])[0]
+        if len(diff):
+            assert margins[b, diff[0]] < H.MARGIN, (b, diff[0], margins[b, diff[0]])
+            n_exempt += 1
+    assert n_exempt <= 1
+    # target and draft caches advance together: the draft holds one entry per committed target position
+    assert torch.equal(kv.seq_len, dkv.seq_len + 0) or (kv.seq_len - dkv.seq_len).abs().max().item() <= N
+    print(f"config 1 loop: {rounds} rounds, tau = {accepted / (rounds * B):.3f}, sequences exempt {n_exempt}", flush=True)
