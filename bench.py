@@ -1,8 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the speculative-verify hot path on one MI355X.
 
-One "step" = one pass of the hot path over one batch: plan (host) -> draft steps + rerank (when --draft) ->
-spec_verify -> spec_accept -> kv_compact -> accept lengths to the host.  Inputs (weights, paged KV cache, planted
+One "step" = one pass of the hot path over one batch: plan (host) -> L_draft draft steps + frontier updates +
+rerank -> spec_verify -> spec_accept -> kv_compact -> accept lengths to the host.  Inputs (weights, paged KV cache, planted
 draft trees) are resident in HBM before the timed region; the cache lengths are reset between steps so every step
 sees the same ragged shape.  Prints ONE JSON line (see README for the fields).
 """
@@ -39,7 +39,7 @@ def model_bytes_flops(model, M, lengths, N):
 class Workload:
     """A model, a batch of ragged paged caches and a planted draft tree, all on the device."""
 
-    def __init__(self, name, dtype, seed=0, B=None, N=None, n_layers=None, kv=None, verbose=False):
+    def __init__(self, name, dtype, seed=0, B=None, N=None, n_layers=None, kv=None, verbose=False, with_draft=True):
         import torch
         import paper_2509_21792_amd as fg
         from synth import configs, gen
@@ -84,6 +84,31 @@ class Workload:
         self.tokens_d = torch.as_tensor(tokens).cuda()
         self.parent_d = torch.as_tensor(self.parent).cuda()
         self.max_seq_len = int(self.lengths.max()) + self.N
+        # the draft head, its own 1-layer paged cache (synthetic prefix of the same lengths) and the pending
+        # catch-up entries a previous round would have left (accept lengths drawn at the planted rate)
+        self.K_draft, self.L_draft = Kd, Ld
+        self.draft_ready = False
+        if with_draft and Kd > 0 and Ld > 0:
+            from paper_2509_21792_amd import loop as gloop
+            self.gloop = gloop
+            dcfg = configs.draft_of(model)
+            self.gd = fg.Model(dcfg, gen.make_weights(dcfg, seed, device="cuda", draft=True), target=self.gm)
+            dtable, dn = gen.make_page_table(self.lengths, Ld + 1 + (Ld - 1) * Kd + 1, 16, seed + 5)
+            self.dkv = fg.KVCache(dcfg, dtable, dn)
+            for b in range(self.B):
+                k, v = gen.make_prefix_kv(dcfg, int(self.lengths[b]), seed + 6, b, device="cuda")
+                self.dkv.write_prefix(b, k, v)
+            self.dlen0 = self.dkv.seq_len.clone()
+            Kin = Ld + 1
+            self.d_max_len = int(self.lengths.max()) + Kin + (Ld - 1) * Kd
+            self.ws_d = self.gd.workspace(self.B * max(Kin, Kd), self.d_max_len)
+            td = torch.bfloat16 if dtype == "bf16" else torch.float16
+            g = torch.Generator(device="cuda").manual_seed(seed + 7)
+            catch_tok = torch.randint(0, model["vocab"], (self.B, Kin), generator=g, device="cuda", dtype=torch.int32)
+            catch_feat = torch.randn((self.B, Kin, model["d_model"]), generator=g, device="cuda").to(td)
+            last = torch.as_tensor(np.minimum(self.hit.cumprod(axis=1).sum(axis=1), Ld).astype(np.int32)).cuda()
+            self.spec_state = gloop.SpecState(catch_tok, catch_feat, last)
+            self.draft_ready = True
         torch.cuda.synchronize()
         if verbose:
             print(f"# workload {name} {dtype}: B={self.B} N={self.N} plan={self.plan} sumL={int(self.lengths.sum())} "
@@ -106,9 +131,21 @@ class Workload:
         self.kv.seq_len.copy_(self.len0)
         return out
 
+    def draft(self):
+        """The drafting phase of a round: L_draft steps of the draft head, frontier updates and the rerank.  Its
+        tree is computed and then set aside: the verify step reads the planted tree, as the workload prescribes."""
+        fg = self.fg
+        ct, cp, cs = self.gloop.draft_expand(self.gm, self.gd, self.dkv, self.slot, self.spec_state, self.K_draft,
+                                             self.L_draft, self.ws_d, max_seq_len=self.d_max_len)
+        tree = fg.fg_build_tree(ct, cp, cs, ct.shape[1], self.N)
+        self.dkv.seq_len.copy_(self.dlen0)
+        return tree
+
     def step(self):
         fg = self.fg
         pd_N, pd_K, pd_L = fg.fg_plan(self.B, float(self.B * self.N))
+        if self.draft_ready:
+            self.draft()
         o = fg.fg_spec_verify(self.gm, self.kv, self.slot, self.tokens_d, self.parent_d, self.ws, want_feature=True,
                               max_seq_len=self.max_seq_len)
         acc, path, otok, fin = fg.fg_spec_accept(self.tokens_d, self.parent_d, row_argmax=o["argmax"])
@@ -207,6 +244,7 @@ def main():
     n_out, n_in = 2 * model["d_ffn"], model["d_model"]
     epi = 1 if M > 256 else 0
     t_verify, _ = time_steps(torch, wl.verify_only, max(3, args.steps // 2), args.warmup)
+    t_draft = time_steps(torch, wl.draft, max(3, args.steps // 2), 2)[0] if wl.draft_ready else 0.0
     fg.fg_profile_gemm(True, n_out, n_in, epi, max_launches=(args.steps + 1) * model["n_layers"])
     for _ in range(args.warmup):
         wl.step()
@@ -229,13 +267,15 @@ def main():
     roof["avg_us"] = k_avg * 1e6
 
     out = {
-        "metric": "accepted tokens/s (7B-class verify step: verify + accept + compact)", "value": emitted / t_step,
+        "metric": "accepted tokens/s (7B-class speculative step: draft + rerank + verify + accept + compact)",
+        "value": emitted / t_step,
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": t_step * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": f"{wl.name}: {model['name']} {model['n_layers']} layers, B={wl.B}, N_verify={wl.N} "
                                f"(K_draft={wl.plan[1]}, L_draft={wl.plan[2]} from Eq. 1-3), KV lengths U[{int(wl.lengths.min())},"
                                f"{int(wl.lengths.max())}] in 16-token pages, planted agreement {wl.cfg['plant_p']}, greedy"},
-        "verify_ms": t_verify * 1e3, "tau": emitted / wl.B,
+        "verify_ms": t_verify * 1e3, "draft_ms": t_draft * 1e3, "tau": emitted / wl.B,
+        "verify_tokens_per_s": emitted / t_verify,
         "step_hbm_frac": acct["bytes"] / t_verify / PEAK_HBM, "step_mfma_frac": acct["flops"] / t_verify / PEAK_MFMA,
         "step_bytes": acct["bytes"], "step_flops": acct["flops"],
         "roofline": roof,
