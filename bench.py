@@ -20,6 +20,10 @@ if ROOT not in sys.path:
 
 PEAK_HBM = 8.0e12          # B/s, MI355X HBM3E
 PEAK_MFMA = 2516.6e12      # flop/s, dense bf16 / fp16 MFMA
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this benchmark,
+# scaled by what the same counters read for a plain 1 GiB copy (profiles/bench_cfg4_b256_n8_hbm_traffic_pmc.txt).
+# A recorded measurement, keyed by (workload, rows M); other workloads report null.
+MEASURED_TRAFFIC = {("cfg4", 2048): 766.3e6 + 72.6e6}
 
 
 def model_bytes_flops(model, M, lengths, N):
@@ -261,7 +265,9 @@ def main():
     else:
         roof = dict(bound="hbm", achieved=gemm_bytes / k_avg / 1e9, peak=PEAK_HBM / 1e9, unit="GB/s")
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    roof["traffic"] = MEASURED_TRAFFIC.get((wl.name, M))
+    roof["algorithmic"] = gemm_flops if compute_bound else gemm_bytes
+    roof["algorithmic_bytes"] = gemm_bytes
     roof["kernel"] = f"gemm_mfma_kernel (gate/up, M={M}, n_out={n_out}, n_in={n_in}, epilogue={'swiglu' if epi else 'fp32 split-K slabs'})"
     roof["launches"] = k_cnt
     roof["avg_us"] = k_avg * 1e6
