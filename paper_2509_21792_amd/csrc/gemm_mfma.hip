@@ -16,30 +16,10 @@
 #include <vector>
 
 #include "fg_common.h"
+#include "gemm_mfma.h"
 
 namespace fg {
 
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x16_t __attribute__((ext_vector_type(16)));
-
-union Frag {
-    uint4 u;
-    bf16x8_t b;
-    f16x8_t h;
-};
-
-template <typename T> __device__ __forceinline__ f32x16_t mfma32(const Frag &a, const Frag &b, f32x16_t c);
-template <> __device__ __forceinline__ f32x16_t mfma32<bf16_t>(const Frag &a, const Frag &b, f32x16_t c)
-{
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.b, b.b, c, 0, 0, 0);
-}
-template <> __device__ __forceinline__ f32x16_t mfma32<f16_t>(const Frag &a, const Frag &b, f32x16_t c)
-{
-    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a.h, b.h, c, 0, 0, 0);
-}
-
-constexpr int KT = 4;  // k tiles (of 16) per chunk: 64 k
 
 template <typename T, int MT, int NT, int WM, int WN, int EPI>
 __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(const T *__restrict__ X, const uint4 *__restrict__ Wp,
@@ -55,27 +35,8 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(const T *__restr
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int n_tiles = N >> 5, k_tiles = K >> 4;
-    // Block -> (column band, row block, k split).  With several row blocks the grid is one-dimensional and
-    // XCD-aware: blocks are dealt to the 8 XCDs round-robin by linear id, so XCD x takes the units g * 8 + x
-    // (a unit = one k split of a group of BG adjacent bands) and runs the row_blocks x BG tiles of a unit back to
-    // back.  The ~32 blocks resident on an XCD then share BG bands of W and the row blocks of X through its L2.
     int bx, by, bz;
-    if (raster) {
-        const int BG = raster;                                             // bands per group
-        const int n_bands = (n_tiles + WN * NT - 1) / (WN * NT);
-        const int n_bgroups = (n_bands + BG - 1) / BG;
-        const int splits = (k_tiles / KT + chunks_per_split - 1) / chunks_per_split;
-        const int per_group = row_blocks * BG;
-        const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-        const int unit = (local / per_group) * 8 + xcd, within = local % per_group;   // unit = (k split, band group)
-        if (unit >= n_bgroups * splits) return;
-        bz = unit / n_bgroups;
-        by = within % row_blocks;
-        bx = (unit % n_bgroups) * BG + within / row_blocks;
-        if (bx >= n_bands) return;
-    } else {
-        bx = blockIdx.x; by = blockIdx.y; bz = blockIdx.z;
-    }
+    if (!map_block(raster, n_tiles, WN * NT, k_tiles, chunks_per_split, row_blocks, bx, by, bz)) return;
     const int row0 = by * BM;
     const int ntile0 = (bx * WN + wn) * NT;
     const int total_chunks = k_tiles / KT;
@@ -179,46 +140,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(const T *__restr
 #undef FG_LOAD_X
 #undef FG_STORE_X
 
-    // epilogue: lane holds column n = lane % 32 of each tile, rows 8 * (r / 4) + 4 * (lane / 32) + r % 4.
-    // 32-bit offsets (M * N < 2^31 is checked by the launcher) keep the address arithmetic out of the way.
-    const int col_in_tile = lane & 31, row_half = (lane >> 5) * 4;
-    const int mrow0 = row0 + wm * MT * 32 + row_half;
-    if (EPI == 0) {
-        float *o = reinterpret_cast<float *>(out) + (size_t)bz * M * N;
-#pragma unroll
-        for (int j = 0; j < NT; j++) {
-            const int nt = ntile0 + j;
-            if (nt >= n_tiles) continue;
-            const int n = nt * 32 + col_in_tile;
-#pragma unroll
-            for (int i = 0; i < MT; i++)
-#pragma unroll
-                for (int r = 0; r < 16; r++) {
-                    const int m = mrow0 + i * 32 + 8 * (r >> 2) + (r & 3);
-                    if (m < M) o[m * N + n] = acc[i][j][r];
-                }
-        }
-    } else {
-        // gate / up tiles alternate: tile 2t = gate, 2t + 1 = up, both for output columns 32 t .. 32 t + 31
-        T *o = reinterpret_cast<T *>(out);
-        const int F = N >> 1;
-#pragma unroll
-        for (int j = 0; j + 1 < NT; j += 2) {
-            const int nt = ntile0 + j;
-            if (nt + 1 >= n_tiles) continue;  // n_tiles is even and pairs start at even tiles
-            const int f = (nt >> 1) * 32 + col_in_tile;
-#pragma unroll
-            for (int i = 0; i < MT; i++)
-#pragma unroll
-                for (int r = 0; r < 16; r++) {
-                    const int m = mrow0 + i * 32 + 8 * (r >> 2) + (r & 3);
-                    if (m < M) {
-                        const float g = acc[i][j][r], u = acc[i][j + 1][r];
-                        o[m * F + f] = from_f<T>(g / (1.f + __expf(-g)) * u);
-                    }
-                }
-        }
-    }
+    store_tiles<T, MT, NT, EPI>(acc, out, M, N, row0 + wm * MT * 32, ntile0, n_tiles, bz, lane);
 }
 
 // ---- host side -----------------------------------------------------------------------------------------
@@ -281,22 +203,26 @@ static int choose_split(int M, int N, int K, int block_rows, int block_cols)
     return s;
 }
 
-int gemm_mfma_split_for(int M, int N, int K)
-{
-    if (M <= 256) return choose_split(M, N, K, 256, 256);
-    return choose_split(M, N, K, 256, 256);
-}
-
-// Tile shape for M > 256 (FG_GEMM_BIG overrides for experiments): 0 = 256 x 256 as 1 x 4 waves of 256 x 64,
-// 1 = 256 x 256 as 2 x 2 waves of 128 x 128, 2 = 128 x 512 as 1 x 8 waves of 128 x 64 (two waves per SIMD).
+// More than 256 rows: the pipelined 256 x 256 kernel (gemm_mfma_big.hip).  FG_GEMM_BIG=0 keeps the streaming
+// kernel's 256-row shape for comparison.
+int32_t launch_gemm_mfma_big(int32_t dtype, const void *x, const void *wp, void *out, int M, int N, int K, int epilogue,
+                             int split, int raster_on, hipStream_t st);
 static int big_variant()
 {
     static int v = -1;
     if (v < 0) {
         const char *e = getenv("FG_GEMM_BIG");
-        v = e ? atoi(e) : 0;
+        v = e ? atoi(e) : 1;
     }
     return v;
+}
+
+int gemm_mfma_big_split_for(int M, int N, int K);
+
+int gemm_mfma_split_for(int M, int N, int K)
+{
+    if (M > 256 && big_variant()) return gemm_mfma_big_split_for(M, N, K);
+    return choose_split(M, N, K, 256, 256);
 }
 
 template <typename T>
@@ -311,9 +237,7 @@ static int32_t launch_gemm_typed(const void *x, const void *wp, void *out, int M
     if (M <= 32) FG_GEMM_CASE(1, 2, 1, 4);
     else if (M <= 64) FG_GEMM_CASE(2, 2, 1, 4);
     else if (M <= 128) FG_GEMM_CASE(4, 2, 1, 4);
-    else if (M <= 256 || big_variant() == 0) FG_GEMM_CASE(8, 2, 1, 4);
-    else if (big_variant() == 2) FG_GEMM_CASE(4, 2, 1, 8);
-    else FG_GEMM_CASE(4, 4, 2, 2);
+    else FG_GEMM_CASE(8, 2, 1, 4);
 #undef FG_GEMM_CASE
     FG_LAUNCH_CHECK("gemm_mfma");
     return FG_OK;
@@ -338,8 +262,10 @@ int32_t launch_gemm_mfma(int32_t dtype, const void *x, const void *wp, void *out
     const bool prof = g_prof.on && g_prof.n_out == N && g_prof.n_in == K && g_prof.epilogue == epilogue &&
                       g_prof.used < g_prof.start.size();
     if (prof) (void)hipEventRecord(g_prof.start[g_prof.used], st);
-    int32_t rc = dtype == FG_BF16 ? launch_gemm_typed<bf16_t>(x, wp, out, M, N, K, epilogue, split, st)
-                                  : launch_gemm_typed<f16_t>(x, wp, out, M, N, K, epilogue, split, st);
+    int32_t rc;
+    if (M > 256 && big_variant()) rc = launch_gemm_mfma_big(dtype, x, wp, out, M, N, K, epilogue, split, raster_enabled(), st);
+    else rc = dtype == FG_BF16 ? launch_gemm_typed<bf16_t>(x, wp, out, M, N, K, epilogue, split, st)
+                               : launch_gemm_typed<f16_t>(x, wp, out, M, N, K, epilogue, split, st);
     if (prof) (void)hipEventRecord(g_prof.stop[g_prof.used++], st);
     return rc;
 }

@@ -46,6 +46,23 @@ def test_gemm_16bit_partial_epilogue(fg, M, N, K, dtype):
     assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("chunks", [1, 2, 3, 4, 5, 6, 7, 8, 11, 12, 13, 19])
+def test_gemm_16bit_many_rows_every_k_tail(fg, chunks):
+    """More than 256 rows takes the pipelined kernel, whose main loop handles six 64-wide k chunks per trip: every
+    tail length, a ragged last row block and a ragged last column band."""
+    M, N, K = 300, 288, 64 * chunks
+    print(f"gemm many rows chunks={chunks}", flush=True)
+    g = torch.Generator().manual_seed(chunks)
+    for dtype in ("bf16", "fp16"):
+        x, w = bf16_randn((M, K), g, dt=TD[dtype]), bf16_randn((N, K), g, 0.05, dt=TD[dtype])
+        ref = x.double() @ w.double().T
+        wp = fg.fg_pack_weight(CODES[dtype], w.cuda())
+        out, used = fg.fg_gemm(CODES[dtype], x.cuda(), wp, N, epilogue=0, split_k=1)
+        torch.cuda.synchronize()
+        err = (out.double().cpu() - ref).abs().max().item()
+        assert used == 1 and err <= 2e-5 * ref.abs().max().item() + 1e-4, (dtype, err)
+
+
 @pytest.mark.parametrize("M,F,K", [(8, 704, 256), (33, 1024, 128), (200, 18944, 3584), (300, 2048, 512), (1000, 1024, 256)])
 @pytest.mark.parametrize("dtype", ["bf16", "fp16"])
 def test_gemm_16bit_swiglu_epilogue(fg, M, F, K, dtype):
