@@ -268,7 +268,7 @@ def main():
     roof["traffic"] = MEASURED_TRAFFIC.get((wl.name, M))
     roof["algorithmic"] = gemm_flops if compute_bound else gemm_bytes
     roof["algorithmic_bytes"] = gemm_bytes
-    roof["kernel"] = f"{"gemm_mfma_big_kernel" if M > 256 else "gemm_mfma_kernel"} (gate/up, M={M}, n_out={n_out}, n_in={n_in}, epilogue={'swiglu' if epi else 'fp32 split-K slabs'})"
+    roof["kernel"] = f"{'gemm_mfma_big_kernel' if M > 256 else 'gemm_mfma_kernel'} (gate/up, M={M}, n_out={n_out}, n_in={n_in}, epilogue={'swiglu' if epi else 'fp32 split-K slabs'})"
     roof["launches"] = k_cnt
     roof["avg_us"] = k_avg * 1e6
 
