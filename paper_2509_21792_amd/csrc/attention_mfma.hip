@@ -14,6 +14,10 @@
 // so that every K load is 64 contiguous bytes per lane.  Chunks write (m, l, O) partials; a merge kernel
 // combines them.  Key positions >= committed length are in-round nodes and are masked per query row with the
 // node's 64-bit ancestor set.
+#include <stdlib.h>
+
+#include <type_traits>
+
 #include "fg_common.h"
 
 namespace fg {
@@ -39,12 +43,46 @@ template <> __device__ __forceinline__ f32x4_t mfma16<f16_t>(const Frag16 &a, co
 {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, b.h, c, 0, 0, 0);
 }
-template <typename T> __device__ __forceinline__ uint16_t bits16(float v);
-template <> __device__ __forceinline__ uint16_t bits16<bf16_t>(float v) { return f2bf(v); }
-template <> __device__ __forceinline__ uint16_t bits16<f16_t>(float v)
+// two fp32 -> one packed pair of T, round to nearest even (v_cvt_pk_bf16_f32 / v_cvt_f16_f32 + pack)
+template <typename T> __device__ __forceinline__ uint32_t pack2(float a, float b);
+template <> __device__ __forceinline__ uint32_t pack2<bf16_t>(float a, float b)
 {
-    f16_t h = (f16_t)v;
-    return *reinterpret_cast<uint16_t *>(&h);
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    bf16x2_t r;
+    r[0] = (__bf16)a;
+    r[1] = (__bf16)b;
+    return *reinterpret_cast<uint32_t *>(&r);
+}
+template <> __device__ __forceinline__ uint32_t pack2<f16_t>(float a, float b)
+{
+    typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+    f16x2_t r;
+    r[0] = (_Float16)a;
+    r[1] = (_Float16)b;
+    return *reinterpret_cast<uint32_t *>(&r);
+}
+
+constexpr float RESCALE_LOG2 = 8.f;
+
+// Reductions over the four lanes l, l + 16, l + 32, l + 48 (one query column) with the row-swap instructions of
+// gfx950: swapping a register with a copy of itself leaves (lower half, lower half) and (upper, upper).
+__device__ __forceinline__ float group_max(float x)
+{
+    unsigned u = __float_as_uint(x);
+    auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    u = __float_as_uint(x);
+    r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float group_sum(float x)
+{
+    unsigned u = __float_as_uint(x);
+    auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    u = __float_as_uint(x);
+    r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
 struct AttnPlan {
@@ -62,7 +100,8 @@ static AttnPlan plan_attention(int B, int N, int Hq, int Hkv, int max_keys)
     p.QR = QT * 16;
     p.waves = (QT + QW - 1) / QW;
     const long pairs = (long)B * Hkv * p.waves;
-    long splits = (2048 + pairs - 1) / pairs;
+    static const long target = getenv("FG_ATTN_TARGET") ? atol(getenv("FG_ATTN_TARGET")) : 2048;
+    long splits = (target + pairs - 1) / pairs;
     if (splits < 1) splits = 1;
     long ck = (max_keys + splits - 1) / splits;
     long ck_min = 4L * p.QR;              // keeps the partial (m, l, O) traffic under ~1/4 of the K/V traffic
@@ -74,7 +113,12 @@ static AttnPlan plan_attention(int B, int N, int Hq, int Hkv, int max_keys)
     return p;
 }
 
-static int pick_qw(int N, int Hq, int Hkv) { return ((Hq / Hkv) * N + 15) / 16 <= 2 ? 2 : 4; }
+static int pick_qw(int N, int Hq, int Hkv)
+{
+    static const int forced = getenv("FG_ATTN_QW") ? atoi(getenv("FG_ATTN_QW")) : 0;
+    if (forced == 2 || forced == 4) return forced;
+    return ((Hq / Hkv) * N + 15) / 16 <= 2 ? 2 : 4;
+}
 
 template <typename T, int HD, int QW>
 __global__ __launch_bounds__(64) void attn_mfma_kernel(const T *__restrict__ q, const T *__restrict__ k_pool,
@@ -106,8 +150,9 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(const T *__restrict__ q, 
     const int qt0 = wave * QW;
     if (qt0 * 16 >= rows) return;
 
-    // query fragments and per-column masks
-    Frag16 qf[QW][KK];
+    // query fragments (parked in LDS: each lane reads back only what it wrote, so no barrier is needed; this
+    // frees QW * KK * 4 registers for the K / V double buffer) and per-column masks
+    __shared__ uint4 qs[QW * KK * 64];
     uint64_t qmask[QW];
 #pragma unroll
     for (int w = 0; w < QW; w++) {
@@ -118,8 +163,7 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(const T *__restrict__ q, 
         const T *qp = q + ((size_t)b * N + j) * Hq * HD + (size_t)(hk * G + g) * HD + grp * (HD / 4);
 #pragma unroll
         for (int kk = 0; kk < KK; kk++) {
-            if (ok) qf[w][kk].u = *reinterpret_cast<const uint4 *>(qp + kk * 8);
-            else qf[w][kk].u = make_uint4(0, 0, 0, 0);
+            qs[(w * KK + kk) * 64 + lane] = ok ? *reinterpret_cast<const uint4 *>(qp + kk * 8) : make_uint4(0, 0, 0, 0);
         }
     }
 
@@ -133,10 +177,14 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(const T *__restrict__ q, 
         for (int h = 0; h < HT; h++) o[w][h] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
     }
 
+    const float c2 = scale * 1.4426950408889634f;   // scores are exponentiated in base 2
     const size_t head_stride = (size_t)16 * HD;  // elements per (page, kv head)
     const int32_t *pt = page_table + (size_t)s * max_pages;
 
-    for (int t0 = t_begin; t0 < t_end; t0 += 32) {
+    // One step = 32 key positions (two pages).  The K / V fragments of step t + 1 are requested into a second
+    // register set before the arithmetic of step t starts, so that with one wave per SIMD the memory latency is
+    // covered by a whole step of MFMA and softmax work.
+    auto load_step = [&](int t0, Frag16 (&kf)[2][KK], Frag16 (&vf)[HT]) {
         // the two pages of this step (the second may lie beyond the sequence: clamp, its keys are masked)
         int pi0 = t0 >> 4, pi1 = min(pi0 + 1, max_pages - 1);
         int pg0 = min(max(pt[pi0], 0), n_pages - 1), pg1 = min(max(pt[pi1], 0), n_pages - 1);
@@ -146,20 +194,39 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(const T *__restrict__ q, 
         vb[0] = v_pool + (((size_t)layer * n_pages + pg0) * Hkv + hk) * head_stride;
         vb[1] = v_pool + (((size_t)layer * n_pages + pg1) * Hkv + hk) * head_stride;
 
-        Frag16 kf[2][KK];
 #pragma unroll
         for (int kt = 0; kt < 2; kt++)
 #pragma unroll
             for (int kk = 0; kk < KK; kk++)
                 kf[kt][kk].u = *reinterpret_cast<const uint4 *>(kb[kt] + (size_t)c * HD + grp * (HD / 4) + kk * 8);
-        Frag16 vf[HT];
 #pragma unroll
         for (int h = 0; h < HT; h++) {
             vf[h].u2[0] = *reinterpret_cast<const uint2 *>(vb[0] + (size_t)(h * 16 + c) * 16 + grp * 4);
             vf[h].u2[1] = *reinterpret_cast<const uint2 *>(vb[1] + (size_t)(h * 16 + c) * 16 + grp * 4);
         }
-        const bool tail = t0 + 32 > t_end;       // some key positions of this step are outside the chunk
-        const bool tree = t0 + 32 > L;           // some key positions are in-round nodes (masked per row)
+    };
+    auto used = [&](int w) { return (qt0 + w) * 16 < rows; };   // wave-uniform: tiles past the last query row idle
+    // One step over all tiles of the wave, in phases so that the independent tiles' MFMA and VALU chains overlap:
+    //   1  raw scores S^T = K . Q^T;
+    //   2  masking (MASKED steps: those that reach past the chunk or into the in-round nodes) and the test for a
+    //      moved exponent reference;
+    //   3  weights 2^(c2 (s - m_run)), their per-lane sums, the packed P^T fragments;
+    //   4  O^T += V^T . P^T.
+    // Lazy rescaling: m_run (one value per query column, identical in the four lane groups that share the column)
+    // only moves when some score exceeds it by more than RESCALE_LOG2 in base-2 units, or when the column had no
+    // valid key yet.  Each lane tests its own 8 scores, nothing crosses lanes; the weights are at most
+    // 2^RESCALE_LOG2 and exact to the same relative precision.  The FAST variant has no code that touches the
+    // accumulators outside the MFMAs (so they can stay in the accumulation registers for the whole loop): when
+    // some lane fires it returns false with nothing changed, and the step is redone by the variant that reduces
+    // the column maxima across the lane groups and rescales l and the accumulators.
+    auto compute_step = [&](auto masked_tag, auto fast_tag, int t0, Frag16 (&kf)[2][KK], Frag16 (&vf)[HT]) -> bool {
+        constexpr bool MASKED = decltype(masked_tag)::value, FAST = decltype(fast_tag)::value;
+        static_assert(!(MASKED && FAST), "masked steps run the full variant");
+        const bool tail = MASKED && t0 + 32 > t_end;   // some key positions of this step are outside the chunk
+        // an offset the compiler cannot see through keeps the loop-invariant query reads inside the loop
+        // (hoisted, they would take their QW * KK * 4 registers back)
+        int q_off;
+        asm volatile("v_mov_b32 %0, 0" : "=v"(q_off));
         if (tail) {
             // values of positions that are never attended may be anything: zero them so 0 * x stays 0
 #pragma unroll
@@ -170,58 +237,119 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(const T *__restrict__ q, 
                     if (t >= t_end) vf[h].s[jj] = 0;
                 }
         }
-
+        f32x4_t sacc[QW][2];
+        float mx[QW];
+        bool any_grow = false;
 #pragma unroll
         for (int w = 0; w < QW; w++) {
-            if ((qt0 + w) * 16 >= rows) continue;
-            f32x4_t sacc[2];
+            if (!used(w)) continue;
+            Frag16 qfr[KK];
+#pragma unroll
+            for (int kk = 0; kk < KK; kk++) qfr[kk].u = qs[(w * KK + kk) * 64 + lane + q_off];
 #pragma unroll
             for (int kt = 0; kt < 2; kt++) {
-                sacc[kt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+                sacc[w][kt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int kk = 0; kk < KK; kk++) sacc[kt] = mfma16<T>(kf[kt][kk], qf[w][kk], sacc[kt]);
-            }
-            float sv[8];
-            float mx = -INFINITY;
-#pragma unroll
-            for (int jj = 0; jj < 8; jj++) {
-                float v = sacc[jj >> 2][jj & 3] * scale;
-                if (tail || tree) {
-                    int t = t0 + (jj >> 2) * 16 + grp * 4 + (jj & 3);
-                    bool valid = t < t_end && (t < L || ((qmask[w] >> (t - L)) & 1ull));
-                    v = valid ? v : -INFINITY;
-                }
-                sv[jj] = v;
-                mx = fmaxf(mx, v);
-            }
-            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run[w], mx);
-            const float m_use = m_new == -INFINITY ? 0.f : m_new;   // nothing valid yet: keep everything at zero
-            const float alpha = __expf(m_run[w] - m_use);           // exp(-inf) = 0 on the first valid step
-            float ps = 0.f;
-            Frag16 pf;
-#pragma unroll
-            for (int jj = 0; jj < 8; jj++) {
-                float p = __expf(sv[jj] - m_use);
-                ps += p;
-                pf.s[jj] = bits16<T>(p);
-            }
-            ps += __shfl_xor(ps, 16, 64);
-            ps += __shfl_xor(ps, 32, 64);
-            l_run[w] = l_run[w] * alpha + ps;
-            m_run[w] = m_new;
-#pragma unroll
-            for (int h = 0; h < HT; h++) {
-                o[w][h] = o[w][h] * alpha;
-                o[w][h] = mfma16<T>(vf[h], pf, o[w][h]);
+                for (int kk = 0; kk < KK; kk++) sacc[w][kt] = mfma16<T>(kf[kt][kk], qfr[kk], sacc[w][kt]);
             }
         }
+#pragma unroll
+        for (int w = 0; w < QW; w++) {
+            mx[w] = -INFINITY;
+            if (!used(w)) continue;
+#pragma unroll
+            for (int jj = 0; jj < 8; jj++) {
+                float v = sacc[w][jj >> 2][jj & 3];
+                if (MASKED) {   // branch-free: in range, and either committed prefix or an ancestor bit
+                    const int t = t0 + (jj >> 2) * 16 + grp * 4 + (jj & 3);
+                    const uint32_t anc = (uint32_t)(qmask[w] >> min(max(t - L, 0), 63)) & 1u;
+                    const bool valid = (t < t_end) & ((t < L) | (anc != 0u));
+                    v = valid ? v : -INFINITY;
+                    sacc[w][jj >> 2][jj & 3] = v;
+                }
+                mx[w] = fmaxf(mx[w], v);
+            }
+            any_grow |= (mx[w] - m_run[w]) * c2 > RESCALE_LOG2;   // -inf vs finite: inf; -inf vs -inf: NaN (false)
+        }
+        if (__builtin_amdgcn_ballot_w64(any_grow) != 0ull) {
+            if (FAST) return false;
+#pragma unroll
+            for (int w = 0; w < QW; w++) {
+                if (!used(w)) continue;
+                const float cm = group_max(mx[w]);
+                const float m_new = fmaxf(m_run[w], cm);
+                const float m_use = m_new == -INFINITY ? 0.f : m_new;
+                const float alpha = __builtin_amdgcn_exp2f((m_run[w] - m_use) * c2);   // exp2(-inf) = 0 on the first valid step
+                l_run[w] *= alpha;
+#pragma unroll
+                for (int h = 0; h < HT; h++) o[w][h] = o[w][h] * alpha;
+                m_run[w] = m_new;
+            }
+        }
+        Frag16 pf[QW];
+#pragma unroll
+        for (int w = 0; w < QW; w++) {
+            if (!used(w)) continue;
+            const float mb = (m_run[w] == -INFINITY ? 0.f : m_run[w]) * c2;
+            float pv[8];
+#pragma unroll
+            for (int jj = 0; jj < 8; jj++) {
+                pv[jj] = __builtin_amdgcn_exp2f(fmaf(sacc[w][jj >> 2][jj & 3], c2, -mb));
+                l_run[w] += pv[jj];
+            }
+            pf[w].u = make_uint4(pack2<T>(pv[0], pv[1]), pack2<T>(pv[2], pv[3]), pack2<T>(pv[4], pv[5]), pack2<T>(pv[6], pv[7]));
+        }
+#pragma unroll
+        for (int w = 0; w < QW; w++) {
+            if (!used(w)) continue;
+#pragma unroll
+            for (int h = 0; h < HT; h++) o[w][h] = mfma16<T>(vf[h], pf[w], o[w][h]);
+        }
+        return true;
+    };
+    // Plain steps (entirely inside the chunk and the committed prefix) first, with the next step's fragments
+    // requested into a second register set before the arithmetic starts; then the at most three masked steps in a
+    // loop of their own, so that the variants' registers are never live together.
+    Frag16 kf[2][KK], vf[HT];
+    const int t_plain = t_begin + max(min(t_end, L) - t_begin, 0) / 32 * 32;
+    int t0 = t_begin;
+    if (t0 < t_plain) {
+        Frag16 kn[2][KK], vn[HT];
+        auto rotate = [&]() {
+#pragma unroll
+            for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+                for (int kk = 0; kk < KK; kk++) kf[kt][kk].u = kn[kt][kk].u;
+#pragma unroll
+            for (int h = 0; h < HT; h++) vf[h].u = vn[h].u;
+        };
+        load_step(t0, kf, vf);
+        while (t0 < t_plain) {
+            {   // a full step: the first of the chunk, and any step whose reference has to move
+                const bool has_next = t0 + 32 < t_plain;
+                if (has_next) load_step(t0 + 32, kn, vn);
+                compute_step(std::false_type{}, std::false_type{}, t0, kf, vf);
+                if (has_next) rotate();
+                t0 += 32;
+            }
+            while (t0 < t_plain) {
+                const bool has_next = t0 + 32 < t_plain;
+                if (has_next) load_step(t0 + 32, kn, vn);
+                if (!compute_step(std::false_type{}, std::true_type{}, t0, kf, vf)) break;   // redo it as a full step
+                if (has_next) rotate();
+                t0 += 32;
+            }
+        }
+    }
+    for (; t0 < t_end; t0 += 32) {
+        load_step(t0, kf, vf);
+        compute_step(std::true_type{}, std::false_type{}, t0, kf, vf);
     }
 
     // partials: O^T lane holds head_dim rows h*16 + 4*grp + i of query column c
 #pragma unroll
     for (int w = 0; w < QW; w++) {
+        const float l_col = group_sum(l_run[w]);   // the lanes kept their own partial sums
         int qi = (qt0 + w) * 16 + c;
         if (qi >= rows) continue;
         size_t row = (((size_t)b * Hkv + hk) * n_chunks + chunk) * QR + qi;
@@ -229,8 +357,8 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(const T *__restrict__ q, 
         for (int h = 0; h < HT; h++)
             *reinterpret_cast<f32x4_t *>(part_o + row * HD + h * 16 + grp * 4) = o[w][h];
         if (grp == 0) {
-            part_ml[row * 2] = m_run[w];
-            part_ml[row * 2 + 1] = l_run[w];
+            part_ml[row * 2] = m_run[w] * scale;   // the reference the weights were taken against, natural-log units
+            part_ml[row * 2 + 1] = l_col;
         }
     }
 }
