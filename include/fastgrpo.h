@@ -252,6 +252,9 @@ int32_t fg_build_tree(const int32_t *cand_tok, const int32_t *cand_parent, const
  *   epilogue 1: W is a gate/up interleaved matrix; out[M, n_out / 2] in dtype = silu(gate) * up.
  * fg_attention: tree attention of already-rotated queries q [B*N, Hq*hd] (dtype) over the cache, which must
  *   already hold the in-round nodes' K/V; out [B*N, Hq*hd] (dtype).
+ * fg_topk_logp: the draft's per-node expansion (Sec. 2, draft tree construction): for each of the M rows of
+ *   logits [M, vocab] (fp32, device) the K largest entries, ties to the lower token id, as tok [M, K] (int32)
+ *   and their log-softmax values logp [M, K] (fp32).  1 <= K <= 8, K <= vocab.
  */
 int32_t fg_gemm(int32_t dtype, const void *x, const void *w_packed, void *out, int32_t M, int32_t n_out,
                 int32_t n_in, int32_t epilogue, int32_t split_k, int32_t *split_k_used, void *stream);
@@ -259,6 +262,7 @@ int32_t fg_attention(const fg_kv_cache *kv, int32_t layer, const fg_tree *tree, 
                      void *out, void *workspace, int64_t workspace_bytes, void *stream);
 int64_t fg_attention_workspace_bytes(int32_t B, int32_t N, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                                      int32_t max_seq_len);
+int32_t fg_topk_logp(const float *logits, int32_t M, int32_t vocab, int32_t K, int32_t *tok, float *logp, void *stream);
 
 /*
  * Measurement hook (for benchmarks, not part of the method): while armed, every 16-bit GEMM launch whose

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libfastgrpo.so")
 EXPORTS = ["fg_last_error", "fg_plan", "fg_packed_bytes", "fg_pack_weight", "fg_model_create", "fg_model_destroy",
            "fg_workspace_bytes", "fg_spec_verify", "fg_spec_accept", "fg_kv_compact", "fg_draft_step",
            "fg_draft_frontier", "fg_build_tree", "fg_gemm", "fg_attention", "fg_attention_workspace_bytes",
-           "fg_profile_gemm", "fg_profile_read"]
+           "fg_topk_logp", "fg_profile_gemm", "fg_profile_read"]
 
 
 class FgError(RuntimeError):
@@ -83,6 +83,7 @@ def lib():
                                     C.c_void_p, C.c_int64, C.c_void_p]
         L.fg_draft_frontier.argtypes = [C.c_int32, C.c_int32, C.c_int32] + [C.c_void_p] * 6 + [C.c_int32, C.c_int32] + \
                                        [C.c_void_p] * 8 + [C.c_int32, C.c_void_p, C.c_void_p]
+        L.fg_topk_logp.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.fg_build_tree.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.fg_gemm.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
@@ -359,6 +360,14 @@ def fg_build_tree(cand_tok, cand_parent, cand_score, n_cand, N):
     _check(lib().fg_build_tree(_p(cand_tok), _p(cand_parent), _p(cand_score), B, n_cand, stride, N, _p(tokens), _p(parent),
                                _p(sel), _stream()))
     return tokens, parent, sel
+
+
+def fg_topk_logp(logits, K):
+    M, V = logits.shape
+    tok = torch.empty((M, K), dtype=torch.int32, device=logits.device)
+    logp = torch.empty((M, K), dtype=torch.float32, device=logits.device)
+    _check(lib().fg_topk_logp(_p(logits), M, V, K, _p(tok), _p(logp), _stream()))
+    return tok, logp
 
 
 # ---- measurement hook -------------------------------------------------------------------------------------------

@@ -515,6 +515,14 @@ int32_t fg_gemm(int32_t dtype, const void *x, const void *w_packed, void *out, i
     return fail(FG_ERR_INVALID_ARG, "unknown dtype %d", dtype);
 }
 
+int32_t fg_topk_logp(const float *logits, int32_t M, int32_t vocab, int32_t K, int32_t *tok, float *logp, void *stream)
+{
+    if (M < 0 || vocab < 1) return fail(FG_ERR_INVALID_ARG, "fg_topk_logp: bad sizes (M %d, vocab %d)", M, vocab);
+    if (M == 0) return FG_OK;
+    if (!logits || !tok || !logp) return fail(FG_ERR_INVALID_ARG, "fg_topk_logp: null pointer");
+    return launch_topk_logp(logits, M, vocab, K, tok, logp, (hipStream_t)stream);
+}
+
 int32_t fg_profile_gemm(int32_t enable, int32_t n_out, int32_t n_in, int32_t epilogue, int32_t max_launches)
 {
     if (enable && (max_launches < 1 || max_launches > (1 << 20))) return fail(FG_ERR_INVALID_ARG, "fg_profile_gemm: bad max_launches");

@@ -6,61 +6,115 @@ namespace fg {
 
 constexpr int TK_THREADS = 1024, TK_MAX = 8;
 
-// Per row: logsumexp over the vocabulary and the K largest logits (ties: lower index), by K block-wide argmax
-// passes that skip the tokens already taken.
+// Per row, in ONE pass over the logits: every thread keeps an online (max, sum of exponentials) pair and the
+// TK_MAX largest of its own elements, sorted (value descending, index ascending on ties: a thread meets its indices
+// in ascending order and a new element is placed behind equal ones).  The block then combines the pairs into the
+// row's logsumexp and pops the K overall winners from the heads of the threads' lists, one block-wide
+// (value, lowest index) arg-max per winner.
+struct TopList {
+    float v[TK_MAX];
+    int i[TK_MAX];
+};
+
+__device__ __forceinline__ void toplist_insert(TopList &t, float x, int idx)
+{
+    if (!(x > t.v[TK_MAX - 1])) return;
+    t.v[TK_MAX - 1] = x;
+    t.i[TK_MAX - 1] = idx;
+#pragma unroll
+    for (int j = TK_MAX - 1; j > 0; j--) {
+        const bool up = t.v[j] > t.v[j - 1];
+        const float fv = t.v[j - 1];
+        const int fi = t.i[j - 1];
+        t.v[j - 1] = up ? t.v[j] : fv;
+        t.i[j - 1] = up ? t.i[j] : fi;
+        t.v[j] = up ? fv : t.v[j];
+        t.i[j] = up ? fi : t.i[j];
+    }
+}
+
+__device__ __forceinline__ void online_add(float &m, float &sum, float x)
+{
+    if (x > m) {
+        sum = sum * __expf(m - x) + 1.f;   // m = -inf: exp(-inf) = 0
+        m = x;
+    } else {
+        sum += __expf(x - m);
+    }
+}
+
 __global__ __launch_bounds__(TK_THREADS) void topk_logp_kernel(const float *logits, int V, int K, int32_t *tok, float *logp)
 {
     __shared__ float rb[TK_THREADS / 64];
     __shared__ int ri[TK_THREADS / 64];
-    __shared__ int taken[TK_MAX];
-    __shared__ float lse_s;
+    __shared__ float sm[TK_THREADS / 64], ss[TK_THREADS / 64];
     const int r = blockIdx.x, tid = threadIdx.x;
     const float *row = logits + (size_t)r * V;
-    float mx = -INFINITY;
-    for (int v = tid; v < V; v += TK_THREADS) mx = fmaxf(mx, row[v]);
-    mx = wave_max(mx);
-    if ((tid & 63) == 0) rb[tid >> 6] = mx;
-    __syncthreads();
-    mx = -INFINITY;
-    for (int i = 0; i < TK_THREADS / 64; i++) mx = fmaxf(mx, rb[i]);
-    __syncthreads();
-    float den = 0.f;
-    for (int v = tid; v < V; v += TK_THREADS) den += expf(row[v] - mx);
-    den = wave_sum(den);
-    if ((tid & 63) == 0) rb[tid >> 6] = den;
-    __syncthreads();
-    if (tid == 0) {
-        float t = 0.f;
-        for (int i = 0; i < TK_THREADS / 64; i++) t += rb[i];
-        lse_s = mx + logf(t);
-    }
-    __syncthreads();
-    for (int k = 0; k < K; k++) {
-        float best = -INFINITY;
-        int bi = 0x7fffffff;
-        for (int v = tid; v < V; v += TK_THREADS) {
-            bool skip = false;
-            for (int t = 0; t < k; t++) skip |= (taken[t] == v);
-            float x = row[v];
-            if (!skip && x > best) { best = x; bi = v; }
+    TopList t;
+#pragma unroll
+    for (int j = 0; j < TK_MAX; j++) { t.v[j] = -INFINITY; t.i[j] = 0x7fffffff; }
+    float m = -INFINITY, sum = 0.f;
+    if ((V & 3) == 0) {
+        const float4 *row4 = reinterpret_cast<const float4 *>(row);
+        for (int q = tid; q < (V >> 2); q += TK_THREADS) {
+            const float4 x = row4[q];
+            const float xs[4] = {x.x, x.y, x.z, x.w};
+            const float m4 = fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w));
+            if (m4 > m) {   // one rescale per quad
+                sum *= __expf(m - m4);
+                m = m4;
+            }
+#pragma unroll
+            for (int c = 0; c < 4; c++) sum += __expf(xs[c] - m);
+            if (m4 > t.v[TK_MAX - 1]) {
+#pragma unroll
+                for (int c = 0; c < 4; c++) toplist_insert(t, xs[c], q * 4 + c);
+            }
         }
+    } else {
+        for (int v = tid; v < V; v += TK_THREADS) {
+            const float x = row[v];
+            online_add(m, sum, x);
+            toplist_insert(t, x, v);
+        }
+    }
+    // logsumexp of the row
+    const float wm = wave_max(m);
+    float wsum = sum * (m == -INFINITY ? 0.f : __expf(m - wm));
+    wsum = wave_sum(wsum);
+    if ((tid & 63) == 0) { sm[tid >> 6] = wm; ss[tid >> 6] = wsum; }
+    __syncthreads();
+    float bm = -INFINITY;
+    for (int i = 0; i < TK_THREADS / 64; i++) bm = fmaxf(bm, sm[i]);
+    float bs = 0.f;
+    for (int i = 0; i < TK_THREADS / 64; i++) bs += ss[i] * (sm[i] == -INFINITY ? 0.f : __expf(sm[i] - bm));
+    const float lse = bm + logf(bs);
+    // K winners
+    for (int k = 0; k < K; k++) {
+        float best = t.v[0];
+        int bi = t.i[0];
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) {
             float ob = __shfl_xor(best, o, 64);
             int oi = __shfl_xor(bi, o, 64);
             if (ob > best || (ob == best && oi < bi)) { best = ob; bi = oi; }
         }
-        __syncthreads();
+        __syncthreads();   // the previous round's readers are done with rb / ri
         if ((tid & 63) == 0) { rb[tid >> 6] = best; ri[tid >> 6] = bi; }
         __syncthreads();
-        if (tid == 0) {
-            for (int i = 1; i < TK_THREADS / 64; i++)
-                if (rb[i] > best || (rb[i] == best && ri[i] < bi)) { best = rb[i]; bi = ri[i]; }
-            taken[k] = bi;
-            tok[(size_t)r * K + k] = bi;
-            logp[(size_t)r * K + k] = best - lse_s;
+        best = rb[0]; bi = ri[0];
+        for (int i = 1; i < TK_THREADS / 64; i++)
+            if (rb[i] > best || (rb[i] == best && ri[i] < bi)) { best = rb[i]; bi = ri[i]; }
+        if (t.i[0] == bi) {   // this thread owned the winner: pop it
+#pragma unroll
+            for (int j = 0; j + 1 < TK_MAX; j++) { t.v[j] = t.v[j + 1]; t.i[j] = t.i[j + 1]; }
+            t.v[TK_MAX - 1] = -INFINITY;
+            t.i[TK_MAX - 1] = 0x7fffffff;
         }
-        __syncthreads();
+        if (tid == 0) {
+            tok[(size_t)r * K + k] = bi;
+            logp[(size_t)r * K + k] = best - lse;
+        }
     }
 }
 
@@ -134,60 +188,61 @@ int32_t launch_frontier(int B, int K_in, int K, const int32_t *child_tok, const 
     return FG_OK;
 }
 
-// Rerank, one thread per sequence; candidate count <= 128.
+// Rerank, one wave per sequence; at most 128 candidates, two per lane.  Candidate 0 (the root) is always in; a
+// non-root candidate is chosen when fewer than N - 1 others beat it (higher score, or equal score and lower
+// index); a chosen candidate's node index is the number of chosen ones before it in (depth, index) order.
 constexpr int BT_MAX_CAND = 128;
 
-__global__ void build_tree_kernel(const int32_t *cand_tok, const int32_t *cand_parent, const float *cand_score, int B, int C,
-                                  int stride, int N, int32_t *tokens, int32_t *parent, int32_t *sel)
+__global__ __launch_bounds__(64) void build_tree_kernel(const int32_t *cand_tok, const int32_t *cand_parent,
+                                                          const float *cand_score, int B, int C, int stride, int N,
+                                                          int32_t *tokens, int32_t *parent, int32_t *sel)
 {
-    int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= B) return;
+    __shared__ float sc[BT_MAX_CAND];
+    __shared__ int par[BT_MAX_CAND], dep[BT_MAX_CAND], chosen[BT_MAX_CAND], newidx[BT_MAX_CAND];
+    const int b = blockIdx.x, lane = threadIdx.x;
     const int32_t *ct = cand_tok + (size_t)b * stride, *cp = cand_parent + (size_t)b * stride;
     const float *cs = cand_score + (size_t)b * stride;
-    uint64_t chosen[2] = {1ull, 0ull};  // candidate 0 (the root) is always in
-    uint8_t depth[BT_MAX_CAND], newidx[BT_MAX_CAND];
-    depth[0] = 0;
-    int maxd = 0;
-    for (int i = 1; i < C; i++) {
+    for (int i = lane; i < C; i += 64) {
         int p = cp[i];
-        p = (p < 0 || p >= i) ? 0 : p;
-        depth[i] = depth[p] + 1;
+        par[i] = (i == 0) ? -1 : ((p < 0 || p >= i) ? 0 : p);   // malformed parents hang off the root
+        sc[i] = cs[i];
     }
-    for (int k = 1; k < N; k++) {
-        int best = -1;
-        float bs = 0.f;
-        for (int i = 1; i < C; i++) {
-            if ((chosen[i >> 6] >> (i & 63)) & 1ull) continue;
-            if (best < 0 || cs[i] > bs) { best = i; bs = cs[i]; }
-        }
-        if (best < 0) break;
-        chosen[best >> 6] |= 1ull << (best & 63);
-        if (depth[best] > maxd) maxd = depth[best];
+    __syncthreads();
+    for (int i = lane; i < C; i += 64) {
+        int d = 0;
+        for (int p = par[i]; p >= 0 && d < BT_MAX_CAND; p = par[p]) d++;
+        dep[i] = d;
+        int beat = 0;
+        const float mine = sc[i];
+        for (int j = 1; j < C; j++) beat += (sc[j] > mine) || (sc[j] == mine && j < i);
+        chosen[i] = (i == 0) || beat < N - 1;
     }
-    int n = 0;
-    for (int dd = 0; dd <= maxd; dd++)
-        for (int i = 0; i < C; i++) {
-            if (!((chosen[i >> 6] >> (i & 63)) & 1ull) || depth[i] != dd) continue;
-            newidx[i] = (uint8_t)n;
-            tokens[(size_t)b * N + n] = ct[i];
-            int par = -1;
-            if (i > 0) {
-                int p = cp[i];
-                p = (p < 0 || p >= i) ? 0 : p;
-                par = ((chosen[p >> 6] >> (p & 63)) & 1ull) ? newidx[p] : 0;   // unselected parent: re-attach to the root
-            }
-            parent[(size_t)b * N + n] = par;
-            if (sel) sel[(size_t)b * N + n] = i;
-            n++;
-        }
+    __syncthreads();
+    for (int i = lane; i < C; i += 64) {
+        int before = 0;
+        const int d = dep[i];
+        for (int j = 0; j < C; j++) before += chosen[j] && (dep[j] < d || (dep[j] == d && j < i));
+        newidx[i] = before;
+    }
+    __syncthreads();
+    for (int i = lane; i < C; i += 64) {
+        if (!chosen[i]) continue;
+        const int n = newidx[i];
+        int pn = -1;
+        if (i > 0) pn = chosen[par[i]] ? newidx[par[i]] : 0;   // unselected parent: re-attach to the root
+        tokens[(size_t)b * N + n] = ct[i];
+        parent[(size_t)b * N + n] = pn;
+        if (sel) sel[(size_t)b * N + n] = i;
+    }
 }
 
 int32_t launch_build_tree(const int32_t *cand_tok, const int32_t *cand_parent, const float *cand_score, int B, int C, int stride,
                           int N, int32_t *tokens, int32_t *parent, int32_t *sel, hipStream_t st)
 {
     if (C > BT_MAX_CAND) return fail(FG_ERR_CAPACITY, "at most %d candidates (got %d)", BT_MAX_CAND, C);
-    hipLaunchKernelGGL(build_tree_kernel, dim3((B + 63) / 64), dim3(64), 0, st, cand_tok, cand_parent, cand_score, B, C,
-                       stride, N, tokens, parent, sel);
+    if (B <= 0) return FG_OK;
+    hipLaunchKernelGGL(build_tree_kernel, dim3(B), dim3(64), 0, st, cand_tok, cand_parent, cand_score, B, C, stride, N, tokens,
+                       parent, sel);
     FG_LAUNCH_CHECK("build_tree");
     return FG_OK;
 }

@@ -183,3 +183,25 @@ def test_config1_generation_loop_matches_plain_greedy_decoding(H):
     # target and draft caches advance together: the draft holds one entry per committed target position
     assert torch.equal(kv.seq_len, dkv.seq_len + 0) or (kv.seq_len - dkv.seq_len).abs().max().item() <= N
     print(f"config 1 loop: {rounds} rounds, tau = {accepted / (rounds * B):.3f}, sequences exempt {n_exempt}", flush=True)
+
+
+@pytest.mark.parametrize("V,K", [(16, 3), (1000, 4), (1003, 8), (152064, 4), (152066, 1)])
+def test_topk_logp_ties_and_ragged_vocabulary(H, V, K):
+    """The one-pass kernel against the oracle: token ids exact, with planted ties inside a thread's stride, across
+    threads and across waves (lower id first), vocabularies that are and are not multiples of four."""
+    import paper_2509_21792_amd as fg
+    rng = np.random.default_rng(V + K)
+    M = 7
+    lg = (rng.standard_normal((M, V)) * 2).astype(np.float32)
+    top = lg.max() + 1.0
+    for r in range(M):      # ties among the winners
+        pos = rng.choice(V, size=min(5, V), replace=False)
+        lg[r, pos[:3]] = top + r
+        if V > 2100:
+            lg[r, [5, 5 + 1024, 5 + 2048]] = top + r        # same thread, later strides
+    from oracle.oracle import Oracle
+    o_tok, o_logp = Oracle("f64").topk_logp(lg, K)   # the fp32 build's sequential sum is itself off by ~7e-4 at this width
+    g_tok, g_logp = fg.fg_topk_logp(torch.as_tensor(lg).cuda(), K)
+    torch.cuda.synchronize()
+    assert np.array_equal(g_tok.cpu().numpy(), o_tok)
+    assert np.abs(g_logp.cpu().numpy() - o_logp).max() < 2e-5
