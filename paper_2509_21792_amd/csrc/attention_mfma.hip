@@ -376,20 +376,33 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(const float *__restrict_
     const int total = min(seq_len[s] + n_prev + N, max_pages * 16);
     const int nc = min((total + CK - 1) / CK, n_chunks);
     const int qi = j * G + g;
+    // lanes over chunks for the reference and the weights, then lanes over head_dim for the weighted sum (the
+    // chunk loop is unrolled so that its independent loads are in flight together)
+    const size_t row0 = (((size_t)b * Hkv + hk) * n_chunks) * QR + qi;   // chunk ch is row0 + ch * QR
     float m = -INFINITY;
-    for (int ch = 0; ch < nc; ch++) m = fmaxf(m, part_ml[((((size_t)b * Hkv + hk) * n_chunks + ch) * QR + qi) * 2]);
+    for (int ch = lane; ch < nc; ch += 64) m = fmaxf(m, part_ml[(row0 + (size_t)ch * QR) * 2]);
+    m = wave_max(m);
     float den = 0.f, acc[HD / 64];
 #pragma unroll
     for (int i = 0; i < HD / 64; i++) acc[i] = 0.f;
-    for (int ch = 0; ch < nc; ch++) {
-        size_t row = (((size_t)b * Hkv + hk) * n_chunks + ch) * QR + qi;
-        float mc = part_ml[row * 2], lc = part_ml[row * 2 + 1];
-        if (lc == 0.f) continue;
-        float wgt = __expf(mc - m);
-        den += lc * wgt;
+    for (int base = 0; base < nc; base += 64) {
+        const int ch = base + lane;
+        float wgt = 0.f;
+        if (ch < nc) {
+            const float2 ml = *reinterpret_cast<const float2 *>(part_ml + (row0 + (size_t)ch * QR) * 2);
+            wgt = ml.y == 0.f ? 0.f : __expf(ml.x - m);
+            den += ml.y * wgt;
+        }
+        const int cnt = min(64, nc - base);
+#pragma unroll 8
+        for (int cc = 0; cc < cnt; cc++) {
+            const float wc = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(wgt), cc));
+            const float *po = part_o + (row0 + (size_t)(base + cc) * QR) * HD + lane;
 #pragma unroll
-        for (int i = 0; i < HD / 64; i++) acc[i] += part_o[row * HD + lane + 64 * i] * wgt;
+            for (int i = 0; i < HD / 64; i++) acc[i] += po[64 * i] * wc;
+        }
     }
+    den = wave_sum(den);
     const float inv = den > 0.f ? 1.f / den : 0.f;
 #pragma unroll
     for (int i = 0; i < HD / 64; i++) out[(size_t)r * Hq * HD + (size_t)hq * HD + lane + 64 * i] = from_f<T>(acc[i] * inv);

@@ -326,10 +326,22 @@ __global__ __launch_bounds__(1024) void argmax_top2_kernel(const float *logits, 
     const int r = blockIdx.x, tid = threadIdx.x;
     const float *row = logits + (size_t)r * V;
     Top2 t = {-INFINITY, -INFINITY, 0x7fffffff};
-    for (int v = tid; v < V; v += blockDim.x) {
-        float x = row[v];
-        if (x > t.best) { t.second = t.best; t.best = x; t.idx = v; }   // v increases, so ties keep the lower index
-        else if (x > t.second) t.second = x;
+    // a thread meets its indices in ascending order, so a strict comparison keeps the lower index on ties
+    auto take = [&](float x, int v) {
+        const bool gt = x > t.best;
+        t.second = gt ? t.best : fmaxf(t.second, x);
+        t.idx = gt ? v : t.idx;
+        t.best = gt ? x : t.best;
+    };
+    if ((V & 3) == 0) {
+        const float4 *row4 = reinterpret_cast<const float4 *>(row);
+#pragma unroll 4
+        for (int q = tid; q < (V >> 2); q += 1024) {
+            const float4 x = row4[q];
+            take(x.x, 4 * q); take(x.y, 4 * q + 1); take(x.z, 4 * q + 2); take(x.w, 4 * q + 3);
+        }
+    } else {
+        for (int v = tid; v < V; v += 1024) take(row[v], v);
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
