@@ -200,6 +200,9 @@ int32_t fg_kv_compact(fg_kv_cache *kv, const int32_t *slot, const int32_t *accep
  *                (feat_index device int32 [B, N], NULL = row j, which needs feat_rows >= N)
  *   child_tok    int32 [B, N, K_draft]; child_logp fp32 [B, N, K_draft] (log-softmax, descending, ties by
  *                index); both NULL skips the LM head
+ *   expand_row   device int32 [B] or NULL: when given, only node expand_row[b] of each sequence is decoded by the
+ *                LM head (the root of a catch-up chain; the rows before it are history), and child_tok /
+ *                child_logp are [B, 1, K_draft]
  *   out_feature  model dtype [B, N, d]: the head's output hidden state of each node (NULL to skip)
  * n_commit (device [B] or NULL): after the step seq_len[slot[b]] += n_commit[b] + commit_bias -- used for the
  * catch-up chain of accepted tokens, which stays in the draft cache (pass the verify step's accept_len with bias
@@ -208,8 +211,8 @@ int32_t fg_kv_compact(fg_kv_cache *kv, const int32_t *slot, const int32_t *accep
  */
 int32_t fg_draft_step(fg_model *target, fg_model *draft, fg_kv_cache *draft_kv, const fg_tree *tree,
                       const void *in_feature, const int32_t *feat_index, int32_t feat_rows, const int32_t *n_commit,
-                      int32_t commit_bias, int32_t K_draft, int32_t *child_tok, float *child_logp, void *out_feature,
-                      void *workspace, int64_t workspace_bytes, void *stream);
+                      int32_t commit_bias, int32_t K_draft, const int32_t *expand_row, int32_t *child_tok,
+                      float *child_logp, void *out_feature, void *workspace, int64_t workspace_bytes, void *stream);
 
 /*
  * Frontier update between drafting steps (Alg. 1 "update candidate tokens T_candi").  The K_in expanded nodes
@@ -225,9 +228,11 @@ int32_t fg_draft_step(fg_model *target, fg_model *draft, fg_kv_cache *draft_kv, 
  * parent_next (optional, device [B, n_parent_prev + K]): the in-round parent list for the next drafting step =
  * parent_prev [B, n_parent_prev] (the round's nodes so far, this step's K_in nodes last) followed by the K new
  * frontier nodes' parents (-1 with node_pick: children of the root attend the committed prefix only).
+ * child_rows: rows per sequence in child_tok / child_logp: K_in, or 1 with node_pick when fg_draft_step decoded the
+ * picked row only (expand_row).
  */
 int32_t fg_draft_frontier(int32_t B, int32_t K_in, int32_t K, const int32_t *child_tok, const float *child_logp,
-                          const int32_t *node_cand, const float *node_score, const int32_t *node_pick,
+                          int32_t child_rows, const int32_t *node_cand, const float *node_score, const int32_t *node_pick,
                           const int32_t *node_tok, int32_t n_cand, int32_t cand_stride, int32_t *cand_tok,
                           int32_t *cand_parent, float *cand_score, int32_t *next_tok, int32_t *next_cand,
                           float *next_score, int32_t *next_src, const int32_t *parent_prev, int32_t n_parent_prev,

@@ -79,9 +79,10 @@ def lib():
         L.fg_kv_compact.argtypes = [C.POINTER(KvCacheC), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                     C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
         L.fg_draft_step.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(KvCacheC), C.POINTER(TreeC), C.c_void_p, C.c_void_p,
-                                    C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                    C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_void_p, C.c_int64, C.c_void_p]
-        L.fg_draft_frontier.argtypes = [C.c_int32, C.c_int32, C.c_int32] + [C.c_void_p] * 6 + [C.c_int32, C.c_int32] + \
+        L.fg_draft_frontier.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32] + [C.c_void_p] * 4 + \
+                                       [C.c_int32, C.c_int32] + \
                                        [C.c_void_p] * 8 + [C.c_int32, C.c_void_p, C.c_void_p]
         L.fg_topk_logp.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.fg_build_tree.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
@@ -310,7 +311,8 @@ def fg_kv_compact(kv, slot, accept_len, path, feature_in=None, d_model=0):
 
 
 def fg_draft_step(target, draft, draft_kv, slot, tokens, parent, in_feature, workspace, K_draft, n_prev=0, feat_index=None,
-                  n_commit=None, commit_bias=0, max_seq_len=0, want_children=True):
+                  n_commit=None, commit_bias=0, max_seq_len=0, want_children=True, expand_row=None):
+    """expand_row [B]: decode only that node of each sequence; the child lists are then [B, 1, K_draft]."""
     dev = draft_kv.k_pool.device
     slot, tokens, parent = _dev_i32(slot, dev), _dev_i32(tokens, dev), _dev_i32(parent, dev)
     B, N = tokens.shape
@@ -321,14 +323,17 @@ def fg_draft_step(target, draft, draft_kv, slot, tokens, parent, in_feature, wor
     feat_rows = in_feature.shape[1]
     if feat_index is not None:
         feat_index = _dev_i32(feat_index, dev)
-    ctok = torch.empty((B, N, K_draft), dtype=torch.int32, device=dev) if want_children else None
-    clogp = torch.empty((B, N, K_draft), dtype=torch.float32, device=dev) if want_children else None
+    rows = N if expand_row is None else 1
+    if expand_row is not None:
+        expand_row = _dev_i32(expand_row, dev)
+    ctok = torch.empty((B, rows, K_draft), dtype=torch.int32, device=dev) if want_children else None
+    clogp = torch.empty((B, rows, K_draft), dtype=torch.float32, device=dev) if want_children else None
     ofeat = torch.empty((B, N, d), dtype=_tdtype(draft.dtype), device=dev)
     if n_commit is not None:
         n_commit = _dev_i32(n_commit, dev)
     tree = _tree(slot, tokens, parent, B, N, n_prev, max_seq_len)
     _check(lib().fg_draft_step(target.handle, draft.handle, C.byref(draft_kv.c), C.byref(tree), _p(in_feature), _p(feat_index),
-                               feat_rows, _p(n_commit), commit_bias, K_draft, _p(ctok), _p(clogp), _p(ofeat), _p(workspace),
+                               feat_rows, _p(n_commit), commit_bias, K_draft, _p(expand_row), _p(ctok), _p(clogp), _p(ofeat), _p(workspace),
                                workspace.numel(), _stream()))
     return ctok, clogp, ofeat
 
@@ -337,7 +342,8 @@ def fg_draft_frontier(child_tok, child_logp, n_cand, cand_tok, cand_parent, cand
                       node_pick=None, node_tok=None, parent_prev=None):
     """Returns (next_tok, next_cand, next_score, next_src, parent_next); parent_prev [B, n] is the round's in-round
     parent list so far (None / empty before the first step)."""
-    B, K_in, K = child_tok.shape
+    B, child_rows, K = child_tok.shape
+    K_in = child_rows if node_tok is None else node_tok.shape[1]
     dev = child_tok.device
     nt = torch.empty((B, K), dtype=torch.int32, device=dev)
     nc = torch.empty((B, K), dtype=torch.int32, device=dev)
@@ -345,7 +351,7 @@ def fg_draft_frontier(child_tok, child_logp, n_cand, cand_tok, cand_parent, cand
     nsrc = torch.empty((B, K), dtype=torch.int32, device=dev)
     npp = 0 if parent_prev is None else parent_prev.shape[1]
     pnext = torch.empty((B, npp + K), dtype=torch.int32, device=dev)
-    _check(lib().fg_draft_frontier(B, K_in, K, _p(child_tok), _p(child_logp), _p(node_cand), _p(node_score), _p(node_pick),
+    _check(lib().fg_draft_frontier(B, K_in, K, _p(child_tok), _p(child_logp), child_rows, _p(node_cand), _p(node_score), _p(node_pick),
                                    _p(node_tok), n_cand, cand_tok.shape[1], _p(cand_tok), _p(cand_parent), _p(cand_score), _p(nt),
                                    _p(nc), _p(ns), _p(nsrc), _p(parent_prev) if npp else None, npp, _p(pnext), _stream()))
     return nt, nc, ns, nsrc, pnext

@@ -39,8 +39,9 @@ int32_t launch_reject(int B, int N, int V, const int32_t *tokens, const int32_t 
 int32_t launch_kv_compact(fg_kv_cache *kv, const int32_t *slot, const int32_t *accept_len, const int32_t *path, int B, int N,
                           const void *fin, void *fout, int d, int feat_dtype, hipStream_t st);
 int32_t launch_topk_logp(const float *logits, int M, int V, int K, int32_t *tok, float *logp, hipStream_t st);
-int32_t launch_frontier(int B, int K_in, int K, const int32_t *child_tok, const float *child_logp, const int32_t *node_cand,
-                        const float *node_score, const int32_t *node_pick, const int32_t *node_tok, int n_cand, int stride,
+int32_t launch_gather_rows(int32_t dtype, const void *src, const int32_t *pick, int B, int N, int d, void *dst, hipStream_t st);
+int32_t launch_frontier(int B, int K_in, int K, const int32_t *child_tok, const float *child_logp, int child_rows,
+                        const int32_t *node_cand, const float *node_score, const int32_t *node_pick, const int32_t *node_tok, int n_cand, int stride,
                         int32_t *cand_tok, int32_t *cand_parent, float *cand_score, int32_t *next_tok, int32_t *next_cand,
                         float *next_score, int32_t *next_src, const int32_t *parent_prev, int n_parent_prev,
                         int32_t *parent_next, hipStream_t st);
@@ -430,8 +431,8 @@ int32_t fg_kv_compact(fg_kv_cache *kv, const int32_t *slot, const int32_t *accep
 
 int32_t fg_draft_step(fg_model *target, fg_model *draft, fg_kv_cache *draft_kv, const fg_tree *tree, const void *in_feature,
                       const int32_t *feat_index, int32_t feat_rows, const int32_t *n_commit, int32_t commit_bias,
-                      int32_t K_draft, int32_t *child_tok, float *child_logp, void *out_feature, void *workspace,
-                      int64_t workspace_bytes, void *stream)
+                      int32_t K_draft, const int32_t *expand_row, int32_t *child_tok, float *child_logp, void *out_feature,
+                      void *workspace, int64_t workspace_bytes, void *stream)
 {
     if (!target || !draft) return fail(FG_ERR_INVALID_ARG, "fg_draft_step: model is NULL");
     if (!draft->fc) return fail(FG_ERR_INVALID_ARG, "fg_draft_step needs a draft head (fc)");
@@ -460,10 +461,16 @@ int32_t fg_draft_step(fg_model *target, fg_model *draft, fg_kv_cache *draft_kv, 
     void *hid = out_feature ? out_feature : w.feat;
     if ((rc = launch_add_rmsnorm(c.dtype, w.h, w.partials, S, 0, draft->norm_attn[0], nullptr, hid, M, d, c.rms_eps, st))) return rc;
     if (child_tok) {
-        if (is16(c.dtype)) rc = launch_gemm_mfma(c.dtype, hid, target->lm_head, w.logits, M, c.vocab, d, 0, 1, nullptr, st);
-        else rc = launch_gemm_f32((const float *)hid, (const float *)target->lm_head, w.logits, M, c.vocab, d, st);
+        int rows = M;
+        if (expand_row) {   // only the picked row of each sequence goes through the LM head
+            rows = tree->B;
+            if ((rc = launch_gather_rows(c.dtype, hid, expand_row, tree->B, tree->N, d, w.cat, st))) return rc;
+            hid = w.cat;
+        }
+        if (is16(c.dtype)) rc = launch_gemm_mfma(c.dtype, hid, target->lm_head, w.logits, rows, c.vocab, d, 0, 1, nullptr, st);
+        else rc = launch_gemm_f32((const float *)hid, (const float *)target->lm_head, w.logits, rows, c.vocab, d, st);
         if (rc) return rc;
-        if ((rc = launch_topk_logp(w.logits, M, c.vocab, K_draft, child_tok, child_logp, st))) return rc;
+        if ((rc = launch_topk_logp(w.logits, rows, c.vocab, K_draft, child_tok, child_logp, st))) return rc;
     }
     if (n_commit)
         if ((rc = launch_commit_len(draft_kv->seq_len, tree->slot, n_commit, commit_bias, tree->B, draft_kv->n_slots, st))) return rc;
@@ -471,13 +478,14 @@ int32_t fg_draft_step(fg_model *target, fg_model *draft, fg_kv_cache *draft_kv, 
 }
 
 int32_t fg_draft_frontier(int32_t B, int32_t K_in, int32_t K, const int32_t *child_tok, const float *child_logp,
-                          const int32_t *node_cand, const float *node_score, const int32_t *node_pick,
+                          int32_t child_rows, const int32_t *node_cand, const float *node_score, const int32_t *node_pick,
                           const int32_t *node_tok, int32_t n_cand, int32_t cand_stride,
                           int32_t *cand_tok, int32_t *cand_parent, float *cand_score, int32_t *next_tok, int32_t *next_cand,
                           float *next_score, int32_t *next_src, const int32_t *parent_prev, int32_t n_parent_prev,
                           int32_t *parent_next, void *stream)
 {
     if (B < 0 || K_in < 1 || K < 1 || K_in * K > 64 || K > K_in * K) return fail(FG_ERR_INVALID_ARG, "fg_draft_frontier: bad K_in / K");
+    if (child_rows != K_in && !(child_rows == 1 && node_pick)) return fail(FG_ERR_INVALID_ARG, "fg_draft_frontier: child_rows must be K_in, or 1 with node_pick");
     if (n_cand < 0 || n_cand + (node_pick ? K : K_in * K) > cand_stride) return fail(FG_ERR_CAPACITY, "candidate lists too short");
     if (B == 0) return FG_OK;
     if ((!node_pick && (!node_cand || !node_score)) || !child_tok || !child_logp || !cand_tok || !cand_parent || !cand_score || !next_tok ||
@@ -486,7 +494,7 @@ int32_t fg_draft_frontier(int32_t B, int32_t K_in, int32_t K, const int32_t *chi
     if (n_parent_prev < 0 || n_parent_prev + K > FG_MAX_NODES || (parent_next && n_parent_prev > 0 && !parent_prev) ||
         (parent_next && !node_pick && n_parent_prev < K_in))
         return fail(FG_ERR_INVALID_ARG, "fg_draft_frontier: bad parent list");
-    return launch_frontier(B, K_in, K, child_tok, child_logp, node_cand, node_score, node_pick, node_tok, n_cand, cand_stride, cand_tok, cand_parent,
+    return launch_frontier(B, K_in, K, child_tok, child_logp, child_rows, node_cand, node_score, node_pick, node_tok, n_cand, cand_stride, cand_tok, cand_parent,
                            cand_score, next_tok, next_cand, next_score, next_src, parent_prev, n_parent_prev, parent_next,
                            (hipStream_t)stream);
 }

@@ -128,7 +128,7 @@ int32_t launch_topk_logp(const float *logits, int M, int V, int K, int32_t *tok,
 
 // Frontier update, one thread per sequence (at most 64 children).  With node_pick only the children of node
 // node_pick[b] count (the catch-up chain's last valid row is the root; the rows before it are not expanded).
-__global__ void frontier_kernel(int B, int K_in, int K, const int32_t *child_tok, const float *child_logp,
+__global__ void frontier_kernel(int B, int K_in, int K, const int32_t *child_tok, const float *child_logp, int child_rows,
                                 const int32_t *node_cand, const float *node_score, const int32_t *node_pick,
                                 const int32_t *node_tok, int n_cand, int stride, int32_t *cand_tok, int32_t *cand_parent,
                                 float *cand_score, int32_t *next_tok, int32_t *next_cand, float *next_score, int32_t *next_src,
@@ -143,13 +143,15 @@ __global__ void frontier_kernel(int B, int K_in, int K, const int32_t *child_tok
         cand_score[(size_t)b * stride] = 0.f;
     }
     const int C = pick >= 0 ? K : K_in * K, base = pick >= 0 ? pick * K : 0;
+    // child lists: child_rows rows of K per sequence; with one row it is the picked node's
+    const size_t cbase = (size_t)b * child_rows * K + (child_rows == 1 ? 0 : base);
     for (int i = 0; i < C; i++) {
         int src = (base + i) / K;
         float ps = node_score ? node_score[(size_t)b * K_in + src] : 0.f;
         int pc = node_cand ? node_cand[(size_t)b * K_in + src] : 0;
-        cand_tok[(size_t)b * stride + n_cand + i] = child_tok[(size_t)b * K_in * K + base + i];
+        cand_tok[(size_t)b * stride + n_cand + i] = child_tok[cbase + i];
         cand_parent[(size_t)b * stride + n_cand + i] = pc;
-        cand_score[(size_t)b * stride + n_cand + i] = ps + child_logp[(size_t)b * K_in * K + base + i];
+        cand_score[(size_t)b * stride + n_cand + i] = ps + child_logp[cbase + i];
     }
     uint64_t used = 0;
     for (int k = 0; k < K; k++) {
@@ -175,13 +177,13 @@ __global__ void frontier_kernel(int B, int K_in, int K, const int32_t *child_tok
             parent_next[(size_t)b * (n_parent_prev + K) + i] = parent_prev[(size_t)b * n_parent_prev + i];
 }
 
-int32_t launch_frontier(int B, int K_in, int K, const int32_t *child_tok, const float *child_logp, const int32_t *node_cand,
-                        const float *node_score, const int32_t *node_pick, const int32_t *node_tok, int n_cand, int stride,
+int32_t launch_frontier(int B, int K_in, int K, const int32_t *child_tok, const float *child_logp, int child_rows,
+                        const int32_t *node_cand, const float *node_score, const int32_t *node_pick, const int32_t *node_tok, int n_cand, int stride,
                         int32_t *cand_tok, int32_t *cand_parent, float *cand_score, int32_t *next_tok, int32_t *next_cand,
                         float *next_score, int32_t *next_src, const int32_t *parent_prev, int n_parent_prev,
                         int32_t *parent_next, hipStream_t st)
 {
-    hipLaunchKernelGGL(frontier_kernel, dim3((B + 63) / 64), dim3(64), 0, st, B, K_in, K, child_tok, child_logp, node_cand,
+    hipLaunchKernelGGL(frontier_kernel, dim3((B + 63) / 64), dim3(64), 0, st, B, K_in, K, child_tok, child_logp, child_rows, node_cand,
                        node_score, node_pick, node_tok, n_cand, stride, cand_tok, cand_parent, cand_score, next_tok, next_cand, next_score,
                        next_src, parent_prev, n_parent_prev, parent_next);
     FG_LAUNCH_CHECK("frontier");

@@ -368,4 +368,24 @@ int32_t launch_argmax_top2(const float *logits, int M, int V, int32_t *idx, floa
     return FG_OK;
 }
 
+// dst[b] = src[b * N + clamp(pick[b])]: one row of d elements per sequence, 16 bytes per thread
+__global__ void gather_rows_kernel(const uint4 *src, const int32_t *pick, int B, int N, int vec_per_row, uint4 *dst)
+{
+    const int b = blockIdx.y, v = blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= vec_per_row) return;
+    const int j = min(max(pick[b], 0), N - 1);
+    dst[(size_t)b * vec_per_row + v] = src[((size_t)b * N + j) * vec_per_row + v];
+}
+
+int32_t launch_gather_rows(int32_t dtype, const void *src, const int32_t *pick, int B, int N, int d, void *dst, hipStream_t st)
+{
+    const int64_t row_bytes = (int64_t)d * dtype_size(dtype);
+    if (row_bytes % 16) return fail(FG_ERR_SHAPE, "row of %lld bytes is not a multiple of 16", (long long)row_bytes);
+    const int vec = (int)(row_bytes / 16);
+    hipLaunchKernelGGL(gather_rows_kernel, dim3((vec + 255) / 256, B), dim3(256), 0, st, (const uint4 *)src, pick, B, N, vec,
+                       (uint4 *)dst);
+    FG_LAUNCH_CHECK("gather_rows");
+    return FG_OK;
+}
+
 }  // namespace fg

@@ -33,7 +33,7 @@ def draft_expand(target, draft, dkv, slot, st, K, L, ws, max_seq_len=0):
     cand_score = torch.empty((B, n_total), dtype=torch.float32, device=dev)
     # step 1: the catch-up chain; its last valid row is the root, whose K best children open the tree
     ctok, clogp, ofeat = fg.fg_draft_step(target, draft, dkv, slot, st.catch_tok, chain_parent(B, Kin, dev), st.catch_feat, ws,
-                                          K, n_commit=st.last, commit_bias=1, max_seq_len=max_seq_len)
+                                          K, n_commit=st.last, commit_bias=1, max_seq_len=max_seq_len, expand_row=st.last)
     f_tok, f_cand, f_score, f_src, parents = fg.fg_draft_frontier(ctok, clogp, 1, cand_tok, cand_parent, cand_score,
                                                                  node_pick=st.last, node_tok=st.catch_tok)
     n_cand = 1 + K

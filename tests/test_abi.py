@@ -64,6 +64,6 @@ def test_bad_arguments_are_errors_not_crashes(L):
     assert L.fg_pack_weight(1, None, None, None, 32, 64, None) == -1
     assert L.fg_kv_compact(None, None, None, None, 1, 1, None, None, 0, 0, None) == -1
     assert L.fg_build_tree(None, None, None, 1, 4, 4, 8, None, None, None, None) == -1     # N > n_cand
-    assert L.fg_draft_frontier(1, 9, 8, *([None] * 6), 0, 100, *([None] * 8), 0, None, None, None) == -1   # K_in * K > 64
+    assert L.fg_draft_frontier(1, 9, 8, None, None, 9, *([None] * 4), 0, 100, *([None] * 8), 0, None, None, None) == -1   # K_in * K > 64
     assert L.fg_workspace_bytes(None, 8, 8) == 0
     assert L.fg_packed_bytes(1, 64, 128) == 64 * 128 * 2 and L.fg_packed_bytes(0, 64, 128) == 64 * 128 * 4

@@ -64,6 +64,15 @@ def test_draft_step_with_in_round_nodes(H, dtype):
     n_bad = topk_agree(ctok.cpu().numpy().reshape(B * N, K), clogp.cpu().numpy().reshape(B * N, K), o_tok, o_logp, ol,
                        tol=max(tol, 1e-4) * 3, margin={"fp32": 1e-3, "fp16": 0.05, "bf16": 0.15}[dtype])
     assert (st.kv.seq_len.cpu().numpy() == lengths).all()
+    # decoding one picked row per sequence gives that row's lists, bit for bit (the cache slots are rewritten alike)
+    pick = np.array([0, N - 1, 2, 1], dtype=np.int32)
+    ctok1, clogp1, ofeat1 = fg.fg_draft_step(pair.gm, pair.gd, st.kv, st.slot, tok_all[:, n_prev:], parent, fa, ws, K, n_prev=n_prev,
+                                             feat_index=np.tile(np.arange(n_prev, n_tot, dtype=np.int32), (B, 1)), expand_row=pick)
+    torch.cuda.synchronize()
+    assert ctok1.shape == (B, 1, K) and torch.equal(ofeat1, ofeat)
+    rows = torch.arange(B, device="cuda")
+    assert torch.equal(ctok1[:, 0], ctok[rows, torch.as_tensor(pick).cuda().long()])
+    assert torch.equal(clogp1[:, 0], clogp[rows, torch.as_tensor(pick).cuda().long()])
     print(f"draft step {dtype}: hidden err {herr:.3g}, {n_bad} exempt top-K swaps", flush=True)
 
 
@@ -89,6 +98,15 @@ def test_frontier_and_rerank_are_bit_exact(H):
     nt, nc, ns, nsrc, parents = fg.fg_draft_frontier(torch.as_tensor(ctok).cuda(), torch.as_tensor(clogp).cuda(), 1, ct, cp, cs,
                                                      node_pick=torch.as_tensor(pick).cuda(), node_tok=torch.as_tensor(catch_tok).cuda())
     torch.cuda.synchronize()
+    # the same first step from child lists that hold the picked row only (what a draft step with expand_row returns)
+    ct2, cp2, cs2 = torch.zeros_like(ct), torch.zeros_like(cp), torch.zeros_like(cs)
+    g2 = fg.fg_draft_frontier(torch.as_tensor(ctok[np.arange(B), pick][:, None]).cuda(),
+                              torch.as_tensor(clogp[np.arange(B), pick][:, None]).cuda(), 1, ct2, cp2, cs2,
+                              node_pick=torch.as_tensor(pick).cuda(), node_tok=torch.as_tensor(catch_tok).cuda())
+    torch.cuda.synchronize()
+    for a, b in zip((nt, nc, ns, nsrc, parents), g2):
+        assert torch.equal(a, b)
+    assert torch.equal(ct2[:, :1 + K], ct[:, :1 + K]) and torch.equal(cs2[:, :1 + K], cs[:, :1 + K])
     assert (parents.cpu().numpy() == -1).all() and parents.shape == (B, K)
     assert np.array_equal(nsrc.cpu().numpy(), np.repeat(pick[:, None], K, axis=1))
     f_score = o_sc[1].copy(); f_cand = np.tile(np.arange(1, K + 1, dtype=np.int32), (B, 1))
