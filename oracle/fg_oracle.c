@@ -29,6 +29,8 @@
  *   orc_gumbel_scores  chi-square against softmax(logits/T)
  *   orc_topk_logp      scipy logsumexp + argsort on small cases
  *   orc_build_tree     brute force on tiny candidate sets
+ *   orc_knee           exact break point of two-segment curves; invariance
+ *                      under affine maps of either axis
  *   draft head internals (fc + one layer, no final norm): fixed by this
  *   build's reading of Sec. 2 only -- "parity unpinned" beyond the shared
  *   layer code.
@@ -105,6 +107,38 @@ int orc_plan(int32_t B_cur, double C_peak, double alpha, int32_t K_max, int32_t 
         if (N > cand) N = cand;
     }
     *N_verify = (int32_t)N; *K_draft = (int32_t)K; *L_draft = (int32_t)L;
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Knee of a latency curve (appendix, empirical measurement of C_peak: the   */
+/* batch size at which latency stops being flat).  The paper names no        */
+/* detector; the reading taken: scale both axes to [0, 1] and return the     */
+/* sample that lies farthest below the chord through the first and the last  */
+/* sample (first such sample on ties).  x must increase strictly.            */
+/* ------------------------------------------------------------------------ */
+int orc_knee(const double *x, const double *y, int64_t n, int64_t *knee)
+{
+    if (!x || !y || !knee || n < 3) return ORC_ERR_ARG;
+    double ylo = y[0], yhi = y[0];
+    for (int64_t i = 1; i < n; i++) {
+        if (!(x[i] > x[i - 1])) return ORC_ERR_ARG;
+        if (y[i] < ylo) ylo = y[i];
+        if (y[i] > yhi) yhi = y[i];
+    }
+    const double xs = x[n - 1] - x[0], ys = yhi - ylo;
+    int64_t best = 0;
+    double best_d = 0.0;
+    if (ys > 0) {
+        const double y0 = (y[0] - ylo) / ys, y1 = (y[n - 1] - ylo) / ys;
+        for (int64_t i = 0; i < n; i++) {
+            const double xn = (x[i] - x[0]) / xs, yn = (y[i] - ylo) / ys;
+            const double chord = y0 + (y1 - y0) * xn;
+            const double d = chord - yn;
+            if (d > best_d) { best_d = d; best = i; }
+        }
+    }
+    *knee = best;
     return ORC_OK;
 }
 

@@ -114,6 +114,14 @@ class Oracle:
         self._check(rc, "orc_plan")
         return N.value, K.value, L.value
 
+    def knee(self, x, y):
+        """Index of the knee of the curve y(x) (appendix, measurement of C_peak)."""
+        x = np.ascontiguousarray(x, dtype=np.float64)
+        y = np.ascontiguousarray(y, dtype=np.float64)
+        k = C.c_int64()
+        self._check(self.lib.orc_knee(_ptr(x), _ptr(y), C.c_int64(len(x)), C.byref(k)), "orc_knee")
+        return k.value
+
     # -- forward ---------------------------------------------------------------------------------
     def model(self, cfg, weights, embed_from=None):
         return Model(self, cfg, weights, embed_from)

@@ -57,3 +57,42 @@ def test_plan_rejects_bad_arguments(orc32):
             orc32.plan(*args)
     with pytest.raises(OracleError):
         orc32.plan(4, 256.0, alpha=0.0)
+
+
+# ---- knee of a latency curve (appendix, empirical measurement of C_peak) --------------------------------------
+def two_segment(xs, brk, flat, slope):
+    return [flat if x <= brk else flat + slope * (x - brk) for x in xs]
+
+
+@pytest.mark.parametrize("brk", [2, 5, 17, 40, 63])
+def test_knee_of_a_two_segment_curve_is_its_break(orc32, brk):
+    """Flat, then linear: the chord's height above the curve grows up to the break and shrinks after it, so the
+    farthest sample is the break itself."""
+    xs = list(range(1, 65))
+    ys = two_segment(xs, brk, 3.0, 0.25)
+    assert xs[orc32.knee(xs, ys)] == brk
+
+
+def test_knee_is_invariant_under_affine_maps_of_either_axis(orc32):
+    xs = [1, 2, 4, 8, 16, 32, 64, 128, 256, 512]
+    ys = [4.0, 4.0, 4.01, 4.03, 4.05, 4.2, 4.9, 8.8, 17.0, 33.5]
+    k = orc32.knee(xs, ys)
+    assert orc32.knee([3 * x + 7 for x in xs], ys) == k
+    assert orc32.knee(xs, [1000 * y - 50 for y in ys]) == k
+    assert xs[k] in (32, 64)                   # the sample where the flat part ends, judged by eye
+
+
+def test_knee_edge_cases(orc32):
+    assert orc32.knee([1, 2, 3], [1.0, 2.0, 3.0]) == 0          # a straight line has no knee: first sample
+    assert orc32.knee([1, 2, 3, 4], [5.0, 5.0, 5.0, 5.0]) == 0  # constant
+    with pytest.raises(Exception):
+        orc32.knee([1, 2], [1.0, 2.0])
+    with pytest.raises(Exception):
+        orc32.knee([1, 1, 2], [1.0, 2.0, 3.0])                  # x must increase
+
+
+@settings(max_examples=100, deadline=None)
+@given(brk=st.integers(2, 30), flat=st.floats(0.5, 50.0), slope=st.floats(0.01, 10.0), n=st.integers(34, 80))
+def test_knee_break_property(orc32, brk, flat, slope, n):
+    xs = list(range(1, n + 1))
+    assert xs[orc32.knee(xs, two_segment(xs, brk, flat, slope))] == brk
