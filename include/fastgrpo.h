@@ -118,6 +118,24 @@ int32_t fg_plan(int32_t B_cur, float C_peak, float alpha, int32_t K_max, int32_t
                 int32_t *N_verify, int32_t *K_draft, int32_t *L_draft);
 
 /*
+ * Knee of a latency curve (appendix, "Empirical Measurement of C_peak": forward latency against batch size is
+ * flat while the pass is bound by weight traffic and rises once it is bound by compute; C_peak is the batch size
+ * at the knee).  Host only.  x[n] strictly increasing batch sizes, y[n] latencies (host pointers).  Both axes are
+ * scaled to [0, 1]; *knee_index is the sample farthest below the chord through the first and last sample (the
+ * first such sample on ties; 0 when the curve never dips below the chord).
+ * Errors: NULL pointers, n < 3, x not strictly increasing -> FG_ERR_INVALID_ARG.
+ */
+int32_t fg_knee(const double *x, const double *y, int32_t n, int32_t *knee_index);
+
+/*
+ * Row selection for the live set (Alg. 1, the update of B_cur: finished sequences leave the batch):
+ * dst[i] = src[index[i]] for i < n, rows of row_bytes bytes (a multiple of 4), all device pointers; index values
+ * are clamped into [0, n_src - 1].  dst must not overlap src.
+ */
+int32_t fg_select_rows(const void *src, int64_t row_bytes, int32_t n_src, const int32_t *index, int32_t n, void *dst,
+                       void *stream);
+
+/*
  * Weight packing (one-time, on the stream).  src is [n_out, n_in] row-major in `dtype`; with src2 != NULL
  * the logical matrix is [2 n_out, n_in] with rows interleaved in blocks of 32 (32 of src, 32 of src2, ...),
  * which is how gate and up are fused.  FG_F32: dst is that logical matrix row-major.  16-bit dtypes: dst holds it

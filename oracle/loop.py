@@ -134,3 +134,62 @@ def spec_generate(orc, target, cache, root, n_new, make_tree, eos_id=-1, max_rou
         live = nxt_live
         rnd += 1
     return outs, dict(accepted=accepted, verifications=verifs, live_history=hist)
+
+
+def adaptive_generate(orc, target, draft, cache, dcache, catch_tok, catch_feat, n_valid, first, budgets, c_peak,
+                      alpha=0.5, K_max=4, L_max=6, N_cap=64, eos_id=-1, max_rounds=10 ** 9):
+    """The concurrency-aware generation loop (Alg. 1): every round the tree shape (N, K, L) is re-planned from the
+    number of live sequences by Eq. 1-3; a round with N = 1 is plain decoding (the draft head still consumes its
+    pending entries, so that its cache stays in step); sequences leave the live set at EOS or when they have
+    budgets[b] tokens (first[b], already emitted, counts).
+
+    catch_tok [B, Kin], catch_feat [B, Kin, d], n_valid [B]: the draft head's pending entries after the prefill, the
+    last valid one being first[b]'s.  Returns (token lists, per-round history of dicts B, N, K, L, emitted).
+    """
+    B = len(first)
+    d = target.cfg["d_model"]
+    outs = [[int(first[b])] for b in range(B)]
+    pend_tok = {b: [int(t) for t in catch_tok[b, :n_valid[b]]] for b in range(B)}
+    pend_feat = {b: np.array(catch_feat[b, :n_valid[b]], dtype=np.float32) for b in range(B)}
+    live = [b for b in range(B) if budgets[b] > 1]
+    hist = []
+    while live and len(hist) < max_rounds:
+        slot = np.array(live, dtype=np.int32)
+        Bc = len(live)
+        N, K, L = orc.plan(Bc, c_peak, alpha, K_max, L_max, N_cap)
+        kin = max(len(pend_tok[b]) for b in live)
+        ct = np.zeros((Bc, kin), dtype=np.int32)
+        cf = np.zeros((Bc, kin, d), dtype=np.float32)
+        nv = np.zeros(Bc, dtype=np.int32)
+        for j, b in enumerate(live):
+            nv[j] = len(pend_tok[b])
+            ct[j, :nv[j]] = pend_tok[b]
+            cf[j, :nv[j]] = pend_feat[b]
+        if N == 1:
+            orc.tree_forward(draft, dcache, ct, chain_parent(Bc, kin), feat_in=cf, is_draft=True, slot=slot, want_logits=False)
+            dcache.len[slot] += nv
+            tokens = np.array([[outs[b][-1]] for b in live], dtype=np.int32)
+            parent = np.full((Bc, 1), -1, dtype=np.int32)
+        else:
+            cand = draft_expand(orc, target, draft, dcache, ct, cf, nv, K, L, slot=slot)
+            tokens, parent, _ = orc.build_tree(cand[0], cand[1], cand[2], N)
+        hidden, logits = orc.tree_forward(target, cache, tokens, parent, slot=slot)
+        acc, path, out, fin, _, _ = orc.accept_greedy(tokens, parent, logits, eos_id)
+        orc.kv_compact(cache, target.cfg, acc, path, slot=slot)
+        hidden = hidden.reshape(Bc, tokens.shape[1], d)
+        nxt_live, emitted_round = [], 0
+        for j, b in enumerate(live):
+            a = int(acc[j])
+            emitted = [int(t) for t in out[j, :a + 1]]
+            room = int(budgets[b]) - len(outs[b])
+            done = bool(fin[j]) or len(emitted) >= room
+            emitted = emitted[:room]
+            outs[b].extend(emitted)
+            emitted_round += len(emitted)
+            if not done:
+                pend_tok[b] = emitted
+                pend_feat[b] = hidden[j, path[j, :a + 1]]
+                nxt_live.append(b)
+        hist.append(dict(B=Bc, N=N, K=K, L=L, emitted=emitted_round))
+        live = nxt_live
+    return outs, hist

@@ -20,7 +20,8 @@ LIB_PATH = os.path.join(_HERE, "libfastgrpo.so")
 EXPORTS = ["fg_last_error", "fg_plan", "fg_packed_bytes", "fg_pack_weight", "fg_model_create", "fg_model_destroy",
            "fg_workspace_bytes", "fg_spec_verify", "fg_spec_accept", "fg_kv_compact", "fg_draft_step",
            "fg_draft_frontier", "fg_build_tree", "fg_gemm", "fg_attention", "fg_attention_workspace_bytes",
-           "fg_topk_logp", "fg_profile_gemm", "fg_profile_read"]
+           "fg_topk_logp", "fg_knee", "fg_select_rows", "fg_profile_gemm",
+           "fg_profile_read"]
 
 
 class FgError(RuntimeError):
@@ -84,6 +85,8 @@ def lib():
         L.fg_draft_frontier.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32] + [C.c_void_p] * 4 + \
                                        [C.c_int32, C.c_int32] + \
                                        [C.c_void_p] * 8 + [C.c_int32, C.c_void_p, C.c_void_p]
+        L.fg_knee.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]
+        L.fg_select_rows.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         L.fg_topk_logp.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.fg_build_tree.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -374,6 +377,24 @@ def fg_topk_logp(logits, K):
     logp = torch.empty((M, K), dtype=torch.float32, device=logits.device)
     _check(lib().fg_topk_logp(_p(logits), M, V, K, _p(tok), _p(logp), _stream()))
     return tok, logp
+
+
+def fg_knee(x, y):
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    y = np.ascontiguousarray(y, dtype=np.float64)
+    k = C.c_int32()
+    _check(lib().fg_knee(x.ctypes.data_as(C.c_void_p), y.ctypes.data_as(C.c_void_p), len(x), C.byref(k)))
+    return k.value
+
+
+def fg_select_rows(src, index):
+    """src [n_src, ...] contiguous device tensor, index int32 [n] on the device -> src[index] ([n, ...])."""
+    assert src.is_contiguous()
+    n_src = src.shape[0]
+    row_bytes = src[0].numel() * src.element_size() if n_src else 0
+    dst = torch.empty((index.shape[0],) + tuple(src.shape[1:]), dtype=src.dtype, device=src.device)
+    _check(lib().fg_select_rows(_p(src), row_bytes, n_src, _p(index), index.shape[0], _p(dst), _stream()))
+    return dst
 
 
 # ---- measurement hook -------------------------------------------------------------------------------------------

@@ -39,6 +39,7 @@ int32_t launch_reject(int B, int N, int V, const int32_t *tokens, const int32_t 
 int32_t launch_kv_compact(fg_kv_cache *kv, const int32_t *slot, const int32_t *accept_len, const int32_t *path, int B, int N,
                           const void *fin, void *fout, int d, int feat_dtype, hipStream_t st);
 int32_t launch_topk_logp(const float *logits, int M, int V, int K, int32_t *tok, float *logp, hipStream_t st);
+int32_t launch_select_rows(const void *src, int64_t row_bytes, int n_src, const int32_t *index, int n, void *dst, hipStream_t st);
 int32_t launch_gather_rows(int32_t dtype, const void *src, const int32_t *pick, int B, int N, int d, void *dst, hipStream_t st);
 int32_t launch_frontier(int B, int K_in, int K, const int32_t *child_tok, const float *child_logp, int child_rows,
                         const int32_t *node_cand, const float *node_score, const int32_t *node_pick, const int32_t *node_tok, int n_cand, int stride,
@@ -259,6 +260,37 @@ int32_t fg_plan(int32_t B_cur, float C_peak, float alpha, int32_t K_max, int32_t
     }
     *N_verify = (int32_t)N; *K_draft = (int32_t)K; *L_draft = (int32_t)L;
     return FG_OK;
+}
+
+int32_t fg_knee(const double *x, const double *y, int32_t n, int32_t *knee_index)
+{
+    if (!x || !y || !knee_index || n < 3) return fail(FG_ERR_INVALID_ARG, "fg_knee: NULL pointer or fewer than 3 samples");
+    double lo = y[0], hi = y[0];
+    for (int i = 1; i < n; i++) {
+        if (!(x[i] > x[i - 1])) return fail(FG_ERR_INVALID_ARG, "fg_knee: x must increase strictly (sample %d)", i);
+        lo = fmin(lo, y[i]);
+        hi = fmax(hi, y[i]);
+    }
+    int arg = 0;
+    if (hi > lo) {
+        // height of the chord above the curve, in units of the curve's range, with x mapped to [0, 1]
+        const double span = x[n - 1] - x[0], rise = y[n - 1] - y[0];
+        double far = 0.0;
+        for (int i = 0; i < n; i++) {
+            const double gap = (y[0] + rise * ((x[i] - x[0]) / span) - y[i]) / (hi - lo);
+            if (gap > far) { far = gap; arg = i; }
+        }
+    }
+    *knee_index = arg;
+    return FG_OK;
+}
+
+int32_t fg_select_rows(const void *src, int64_t row_bytes, int32_t n_src, const int32_t *index, int32_t n, void *dst, void *stream)
+{
+    if (n < 0 || n_src < 1 || row_bytes < 4 || row_bytes % 4) return fail(FG_ERR_INVALID_ARG, "fg_select_rows: bad sizes");
+    if (n == 0) return FG_OK;
+    if (!src || !index || !dst) return fail(FG_ERR_INVALID_ARG, "fg_select_rows: NULL pointer");
+    return launch_select_rows(src, row_bytes, n_src, index, n, dst, (hipStream_t)stream);
 }
 
 int64_t fg_packed_bytes(int32_t dtype, int64_t n_out_total, int64_t n_in) { return n_out_total * n_in * (int64_t)dtype_size(dtype); }

@@ -388,4 +388,24 @@ int32_t launch_gather_rows(int32_t dtype, const void *src, const int32_t *pick, 
     return FG_OK;
 }
 
+// dst[i] = src[clamp(index[i])], rows of `words` 32-bit words
+__global__ void select_rows_kernel(const uint32_t *src, int64_t words, int n_src, const int32_t *index, uint32_t *dst)
+{
+    const int i = blockIdx.y;
+    const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (w >= words) return;
+    const int j = min(max(index[i], 0), n_src - 1);
+    dst[(int64_t)i * words + w] = src[(int64_t)j * words + w];
+}
+
+int32_t launch_select_rows(const void *src, int64_t row_bytes, int n_src, const int32_t *index, int n, void *dst, hipStream_t st)
+{
+    const int64_t words = row_bytes / 4;
+    if (n > 65535) return fail(FG_ERR_CAPACITY, "fg_select_rows: at most 65535 rows per call (got %d)", n);
+    hipLaunchKernelGGL(select_rows_kernel, dim3((unsigned)((words + 255) / 256), n), dim3(256), 0, st, (const uint32_t *)src, words,
+                       n_src, index, (uint32_t *)dst);
+    FG_LAUNCH_CHECK("select_rows");
+    return FG_OK;
+}
+
 }  // namespace fg

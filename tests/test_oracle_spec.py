@@ -206,3 +206,30 @@ def test_kv_compact_moves_path_and_bumps_length(orc32):
     from oracle.oracle import OracleError
     with pytest.raises(OracleError):      # a path must increase
         orc32.kv_compact(cache, cfg, np.array([2]), np.array([[0, 3, 2, -1]], np.int32), slot=np.array([2]))
+
+
+def test_adaptive_loop_equals_ar_and_follows_the_rule(orc32, tiny):
+    """Alg. 1 with the concurrency rule in the loop: ragged budgets make the live set decay from 8 to 1, the plan is
+    re-derived every round, rounds with N = 1 are plain decoding; the emitted tokens are still exactly the
+    autoregressive ones, cut at each sequence's budget."""
+    cfg, target, draft, prompts = tiny
+    B, P = cfg["B"], cfg["prompt_len"]
+    budgets = np.array([6, 40, 17, 64, 9, 25, 33, 12], dtype=np.int32)[:B]
+    n_new = int(budgets.max())
+    ref, _, _ = ar_reference(orc32, target, prompts, n_new)
+    cache = orc32.cache(TINY, B, P + n_new + 72)
+    dcache = orc32.cache(draft.cfg, B, P + n_new + 72)
+    feat, logits = loop.prefill(orc32, target, cache, prompts)
+    root, _ = orc32.row_argmax(logits[:, -1])
+    catch_tok = np.concatenate([prompts[:, 1:], root[:, None]], axis=1).astype(np.int32)
+    c_peak = 12.0                               # N = floor(12 / B_cur): 1, 1, 2, 2, 3, 4, 6, 12 as B_cur falls from 8 to 1
+    outs, hist = loop.adaptive_generate(orc32, target, draft, cache, dcache, catch_tok, feat, np.full(B, P, np.int32), root,
+                                        budgets, c_peak, alpha=0.5, K_max=2, L_max=4)
+    for b in range(B):
+        assert outs[b] == [int(t) for t in ref[b, :budgets[b]]], b
+    live = [h["B"] for h in hist]
+    assert live[0] == B and live[-1] >= 1 and all(x >= y for x, y in zip(live, live[1:]))
+    for h in hist:
+        assert (h["N"], h["K"], h["L"]) == orc32.plan(h["B"], c_peak, 0.5, 2, 4, 64)
+    assert any(h["N"] == 1 for h in hist) and any(h["N"] > 1 for h in hist)
+    assert sum(h["emitted"] for h in hist) == int(budgets.sum()) - B
