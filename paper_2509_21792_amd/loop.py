@@ -62,3 +62,100 @@ def spec_round(target, draft, kv, dkv, slot, st, N, K, L, ws_t, ws_d, eos_id=-1,
     Kin = L + 1
     nxt = SpecState(otok[:, :Kin].contiguous(), feat[:, :Kin].contiguous(), acc)
     return acc, otok, fin, nxt
+
+
+def plain_round(target, draft, kv, dkv, slot, st, root, ws_t, ws_d, eos_id=-1, max_seq_len=0):
+    """A round with N_verify = 1 (Eq. 1 when the live batch alone fills C_peak): plain decoding of the root.  The
+    draft head still consumes its pending entries (no LM head) so that its cache stays in step with the target's."""
+    B = root.shape[0]
+    dev = root.device
+    Kin = st.catch_tok.shape[1]
+    fg.fg_draft_step(target, draft, dkv, slot, st.catch_tok, chain_parent(B, Kin, dev), st.catch_feat, ws_d, 1,
+                     n_commit=st.last, commit_bias=1, max_seq_len=max_seq_len, want_children=False)
+    tokens = root.view(B, 1)
+    parent = torch.full((B, 1), -1, dtype=torch.int32, device=dev)
+    out = fg.fg_spec_verify(target, kv, slot, tokens, parent, ws_t, max_seq_len=max_seq_len)
+    acc, path, otok, fin = fg.fg_spec_accept(tokens, parent, row_argmax=out["argmax"], eos_id=eos_id)
+    d = target.cfg["d_model"]
+    feat = fg.fg_kv_compact(kv, slot, acc, path, feature_in=out["feature"].view(B, 1, d), d_model=d)
+    return acc, otok, fin, SpecState(otok[:, :1].contiguous(), feat[:, :1].contiguous(), acc)
+
+
+def generate(target, draft, kv, dkv, slot, st, first, budgets, c_peak, ws_t, ws_d, alpha=0.5, K_max=4, L_max=6, N_cap=64,
+             eos_id=-1, max_seq_len=0, plan=None, max_rounds=10 ** 9):
+    """The concurrency-aware generation loop (Alg. 1): every round (N, K, L) is re-planned from the number of live
+    sequences (Eq. 1-3; `plan(B_cur) -> (N, K, L)` overrides the rule, e.g. a fixed shape for comparison), finished
+    sequences leave the batch (device rows are re-selected with fg_select_rows), and the host sees only the accepted
+    tokens of each round.
+
+    slot int32 [B] (device), st: the draft head's pending entries after the prefill, first int32 [B] (host): the
+    token already emitted per sequence, budgets [B] (host): tokens per sequence, first included.
+    Returns (token lists, per-round history of dicts B, N, K, L, emitted).
+    """
+    B = len(first)
+    dev = slot.device
+    outs = [[int(first[b])] for b in range(B)]
+    keep = [b for b in range(B) if budgets[b] > 1]
+    live = list(range(B))
+    hist = []
+
+    def reselect(rows):
+        nonlocal slot, st
+        idx = torch.as_tensor(np.asarray(rows, dtype=np.int32)).to(dev)
+        slot = fg.fg_select_rows(slot, idx)
+        st = SpecState(fg.fg_select_rows(st.catch_tok, idx), fg.fg_select_rows(st.catch_feat, idx), fg.fg_select_rows(st.last, idx))
+
+    if len(keep) < B:
+        reselect(keep)
+        live = keep
+    while live and len(hist) < max_rounds:
+        Bc = len(live)
+        N, K, L = plan(Bc) if plan else fg.fg_plan(Bc, c_peak, alpha, K_max, L_max, N_cap)
+        if N == 1:
+            root = torch.as_tensor(np.array([outs[b][-1] for b in live], dtype=np.int32)).to(dev)
+            acc, otok, fin, st = plain_round(target, draft, kv, dkv, slot, st, root, ws_t, ws_d, eos_id, max_seq_len)
+        else:
+            acc, otok, fin, st = spec_round(target, draft, kv, dkv, slot, st, N, K, L, ws_t, ws_d, eos_id, max_seq_len)
+        a, t, f = acc.cpu().numpy(), otok.cpu().numpy(), fin.cpu().numpy()     # the round's one trip to the host
+        rows, nxt_live, emitted_round = [], [], 0
+        for j, b in enumerate(live):
+            emitted = [int(x) for x in t[j, :a[j] + 1]]
+            room = int(budgets[b]) - len(outs[b])
+            done = bool(f[j]) or len(emitted) >= room
+            emitted = emitted[:room]
+            outs[b].extend(emitted)
+            emitted_round += len(emitted)
+            if not done:
+                rows.append(j)
+                nxt_live.append(b)
+        hist.append(dict(B=Bc, N=N, K=K, L=L, emitted=emitted_round))
+        if len(nxt_live) < Bc and nxt_live:
+            reselect(rows)
+        live = nxt_live
+    return outs, hist
+
+
+def measure_c_peak(target, kv, ws, batch_sizes, warmup=2, reps=5):
+    """Empirical C_peak (appendix): latency of one forward pass over B single-token inputs, for each B in
+    batch_sizes, timed with events on the current stream; the knee of the curve is C_peak.  The sequences start from
+    empty caches (the cache must have at least max(batch_sizes) slots); nothing is committed.
+    Returns (C_peak, latencies in ms)."""
+    dev = kv.k_pool.device
+    times = []
+    kv.seq_len.zero_()
+    for B in batch_sizes:
+        slot = torch.arange(B, dtype=torch.int32, device=dev)
+        tokens = torch.zeros((B, 1), dtype=torch.int32, device=dev)
+        parent = torch.full((B, 1), -1, dtype=torch.int32, device=dev)
+        for _ in range(warmup):
+            fg.fg_spec_verify(target, kv, slot, tokens, parent, ws, max_seq_len=16, want_feature=False)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fg.fg_spec_verify(target, kv, slot, tokens, parent, ws, max_seq_len=16, want_feature=False)
+        e1.record()
+        torch.cuda.synchronize()
+        times.append(e0.elapsed_time(e1) / reps)
+    k = fg.fg_knee(np.asarray(batch_sizes, dtype=np.float64), np.asarray(times, dtype=np.float64))
+    return int(batch_sizes[k]), times

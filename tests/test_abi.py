@@ -67,3 +67,21 @@ def test_bad_arguments_are_errors_not_crashes(L):
     assert L.fg_draft_frontier(1, 9, 8, None, None, 9, *([None] * 4), 0, 100, *([None] * 8), 0, None, None, None) == -1   # K_in * K > 64
     assert L.fg_workspace_bytes(None, 8, 8) == 0
     assert L.fg_packed_bytes(1, 64, 128) == 64 * 128 * 2 and L.fg_packed_bytes(0, 64, 128) == 64 * 128 * 4
+
+
+def test_knee_agrees_with_the_oracle_on_random_curves(L, orc32):
+    """Host arithmetic of the library against the oracle's independent implementation (appendix, C_peak knee)."""
+    import numpy as np
+    from paper_2509_21792_amd import binding
+    rng = np.random.default_rng(0)
+    for t in range(300):
+        n = int(rng.integers(3, 70))
+        x = np.cumsum(rng.integers(1, 5, size=n)).astype(float)
+        y = np.sort(rng.random(n)) * rng.random() * 10 if t % 2 else rng.random(n)
+        assert binding.fg_knee(x, y) == orc32.knee(x, y)
+    flat_then_up = [3.0] * 10 + [3.0 + 0.5 * i for i in range(1, 20)]
+    assert binding.fg_knee(list(range(1, 30)), flat_then_up) == 9
+    with pytest.raises(binding.FgError):
+        binding.fg_knee([1, 2], [1.0, 2.0])
+    with pytest.raises(binding.FgError):
+        binding.fg_knee([1, 1, 2], [1.0, 2.0, 3.0])

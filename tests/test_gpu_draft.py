@@ -223,3 +223,66 @@ def test_topk_logp_ties_and_ragged_vocabulary(H, V, K):
     torch.cuda.synchronize()
     assert np.array_equal(g_tok.cpu().numpy(), o_tok)
     assert np.abs(g_logp.cpu().numpy() - o_logp).max() < 2e-5
+
+
+def test_adaptive_generation_loop_follows_the_oracle(H):
+    """Alg. 1 with the concurrency rule in the loop, on the device: ragged budgets make the live set decay from 8
+    to 1, (N, K, L) is re-planned every round, N = 1 rounds are plain decoding, finished sequences leave the batch.
+    Tokens, the live-set history and the per-round plans must equal the oracle loop's (fp32; a sequence is exempt
+    only from the first position whose oracle top-2 margin is below the decision margin)."""
+    import paper_2509_21792_amd as fg
+    from paper_2509_21792_amd import loop as gloop
+    cfg = configs.CONFIGS["cfg1"]
+    model = configs.TINY
+    pair = H.Pair(model, seed=cfg["seed"], with_draft=True)
+    orc = pair.orc
+    B, P = cfg["B"], cfg["prompt_len"]
+    budgets = np.array([6, 40, 17, 64, 9, 25, 33, 12], dtype=np.int32)[:B]
+    n_new = int(budgets.max())
+    c_peak, alpha, K_max, L_max = 12.0, 0.5, 2, 4
+    prompts = gen.make_prompts(B, cfg["group"], P, model["vocab"], cfg["seed"])
+    # oracle
+    ocache = orc.cache(model, B, P + n_new + 72)
+    odcache = orc.cache(pair.dcfg, B, P + n_new + 72)
+    ofeat, ologits = oloop.prefill(orc, pair.om, ocache, prompts)
+    oroot, _ = orc.row_argmax(ologits[:, -1])
+    ocatch = np.concatenate([prompts[:, 1:], oroot[:, None]], axis=1).astype(np.int32)
+    want, want_hist = oloop.adaptive_generate(orc, pair.om, pair.od, ocache, odcache, ocatch, ofeat, np.full(B, P, np.int32), oroot,
+                                              budgets, c_peak, alpha=alpha, K_max=K_max, L_max=L_max)
+    # device: prefill = one chain verify step from an empty cache, committed whole
+    cap = P + n_new + 72
+    table, n_pages = gen.make_page_table(np.zeros(B, np.int32), cap, 16, 1)
+    kv = fg.KVCache(model, table, n_pages)
+    dtable, dn = gen.make_page_table(np.zeros(B, np.int32), cap, 16, 2)
+    dkv = fg.KVCache(pair.dcfg, dtable, dn)
+    slot = torch.arange(B, dtype=torch.int32, device="cuda")
+    ws_t = pair.gm.workspace(B * P, cap)
+    ws_d = pair.gd.workspace(B * P, cap)
+    ptok = torch.as_tensor(prompts).cuda()
+    out = fg.fg_spec_verify(pair.gm, kv, slot, ptok, gloop.chain_parent(B, P, "cuda"), ws_t, want_logits=False)
+    ident = torch.arange(P, dtype=torch.int32, device="cuda").repeat(B, 1)
+    feat = fg.fg_kv_compact(kv, slot, torch.full((B,), P - 1, dtype=torch.int32, device="cuda"), ident,
+                            feature_in=out["feature"].view(B, P, -1), d_model=model["d_model"])
+    root = out["argmax"].view(B, P)[:, -1].contiguous()
+    catch_tok = torch.cat([ptok[:, 1:], root.view(B, 1)], dim=1).contiguous()
+    st = gloop.SpecState(catch_tok, feat, torch.full((B,), P - 1, dtype=torch.int32, device="cuda"))
+    got, hist = gloop.generate(pair.gm, pair.gd, kv, dkv, slot, st, root.cpu().numpy(), budgets, c_peak, ws_t, ws_d,
+                               alpha=alpha, K_max=K_max, L_max=L_max, max_seq_len=cap)
+    assert np.array_equal(root.cpu().numpy(), oroot)
+    for b in range(B):
+        assert got[b] == want[b], (b, got[b], want[b])
+    assert hist == want_hist
+    assert any(h["N"] == 1 for h in hist) and any(h["N"] > 1 for h in hist) and hist[-1]["B"] == 1
+    print(f"adaptive loop: {len(hist)} rounds, live set {[h['B'] for h in hist][::4]}, N {[h['N'] for h in hist][::4]}", flush=True)
+
+
+def test_select_rows_and_knee(H):
+    import paper_2509_21792_amd as fg
+    g = torch.Generator().manual_seed(0)
+    src = torch.randn((37, 5, 12), generator=g).cuda()
+    idx = torch.tensor([36, 0, 5, 5, 17], dtype=torch.int32, device="cuda")
+    assert torch.equal(fg.fg_select_rows(src, idx), src[idx.long()])
+    s1 = torch.arange(50, dtype=torch.int32, device="cuda")
+    assert torch.equal(fg.fg_select_rows(s1, idx), s1[idx.long()])
+    h = src.to(torch.bfloat16).contiguous()
+    assert torch.equal(fg.fg_select_rows(h, idx), h[idx.long()])
