@@ -218,6 +218,124 @@ def cpu_baseline(wl, n_seq=4, reps=1):
                 ms_per_step=dt * 1e3, sequences=S)
 
 
+def gen_experiment(args):
+    """--gen: the concurrency-aware generation loop end to end (Alg. 1) on a synthetic workload: B sequences with
+    ragged response budgets decay to one; the tree shape is (a) the rule's (Eq. 1-3 with the measured C_peak),
+    (b) plain decoding throughout, (c) one fixed shape tuned for a single sequence.  No trained draft head exists
+    here, so the target's decisions along each reranked tree's first-child chain are set to agree with the draft at
+    a fixed rate (token values then carry no meaning; every kernel runs at its real shape, the draft steps
+    included).  Prints one JSON line."""
+    import torch
+    import paper_2509_21792_amd as fg
+    from paper_2509_21792_amd import loop as gloop
+    from synth import configs, gen
+    pd = configs.PLAN_DEFAULTS
+    model = configs.with_dtype(configs.CONFIGS["cfg4"]["model"], args.dtype)
+    if args.layers:
+        model = configs.scaled(model, args.layers)
+    B = args.B or 64
+    seed, p_agree = 11, args.agree
+    rng = np.random.default_rng(seed)
+    lengths = rng.integers(256, 1025, size=B).astype(np.int32)
+    budgets = np.clip(np.exp(rng.normal(np.log(args.mean_len), 0.45, size=B)), args.mean_len / 3, args.mean_len * 2.5).astype(np.int32)
+    cap_extra = int(budgets.max()) + 64 + 16
+    weights = gen.make_weights(model, seed, device="cuda")
+    gm = fg.Model(model, weights)
+    dcfg = configs.draft_of(model)
+    gd = fg.Model(dcfg, gen.make_weights(dcfg, seed, device="cuda", draft=True), target=gm)
+    table, n_pages = gen.make_page_table(lengths, cap_extra, 16, seed)
+    kv = fg.KVCache(model, table, n_pages)
+    dtable, dn = gen.make_page_table(lengths, cap_extra, 16, seed + 1)
+    dkv = fg.KVCache(dcfg, dtable, dn)
+    for b in range(B):
+        k, v = gen.make_prefix_kv(model, int(lengths[b]), seed, b, device="cuda")
+        kv.write_prefix(b, k, v)
+        k, v = gen.make_prefix_kv(dcfg, int(lengths[b]), seed + 2, b, device="cuda")
+        dkv.write_prefix(b, k, v)
+    len0, dlen0 = kv.seq_len.clone(), dkv.seq_len.clone()
+    cap = int(lengths.max()) + cap_extra
+    rows_max = B * 64
+    ws_t = gm.workspace(rows_max, cap)
+    ws_d = gd.workspace(rows_max, cap)
+    first = rng.integers(0, model["vocab"], size=B).astype(np.int32)
+    td = torch.bfloat16 if args.dtype == "bf16" else torch.float16
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    feat0 = torch.randn((B, 1, model["d_model"]), generator=g, device="cuda").to(td)
+
+    # C_peak (appendix): latency against batch size at sequence length 1
+    sizes = [1, 2, 4, 8, 16, 24, 32, 48, 64, 96, 128, 192, 256, 384, 512]
+    ptab, pn = gen.make_page_table(np.zeros(max(sizes), np.int32), 16, 16, seed + 3)
+    pkv = fg.KVCache(model, ptab, pn)
+    c_peak, lat = gloop.measure_c_peak(gm, pkv, gm.workspace(max(sizes), 32), sizes)
+    del pkv
+    print(f"# C_peak = {c_peak}; latency ms by batch size: " + ", ".join(f"{b}:{t:.2f}" for b, t in zip(sizes, lat)),
+          file=sys.stderr, flush=True)
+    if args.c_peak:
+        c_peak = args.c_peak
+
+    prng = np.random.default_rng(seed + 5)
+
+    def decide(tokens, parent, amax):
+        """Synthetic acceptance: along the first-child chain of each tree the target agrees with the draft with
+        probability p_agree per node (its decision at the node is set to the child's token) and otherwise picks a
+        token no child carries.  With random weights the target's own choices are not stable across batch shapes
+        in bf16, so planted tokens from a reference run would stop matching after the first flip."""
+        par, tok = parent.cpu().numpy(), tokens.cpu().numpy()
+        am = amax.cpu().numpy().reshape(par.shape).copy()
+        for j in range(par.shape[0]):
+            node = 0
+            while True:
+                kids = np.nonzero(par[j] == node)[0]
+                if len(kids) == 0:
+                    break
+                if prng.random() < p_agree:
+                    am[j, node] = tok[j, kids[0]]
+                    node = int(kids[0])
+                else:
+                    miss = int(am[j, node])
+                    while miss in tok[j, kids]:
+                        miss = (miss + 1) % model["vocab"]
+                    am[j, node] = miss
+                    break
+        return torch.as_tensor(am.reshape(-1)).to(amax.device)
+
+    def run(plan, hook):
+        kv.seq_len.copy_(len0)
+        dkv.seq_len.copy_(dlen0)
+        slot = torch.arange(B, dtype=torch.int32, device="cuda")
+        st = gloop.SpecState(torch.as_tensor(first).cuda().view(B, 1).contiguous(), feat0.clone(),
+                             torch.zeros(B, dtype=torch.int32, device="cuda"))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        outs, hist = gloop.generate(gm, gd, kv, dkv, slot, st, first, budgets, float(c_peak), ws_t, ws_d, alpha=pd["alpha"],
+                                    K_max=pd["K_max"], L_max=pd["L_max"], N_cap=pd["N_cap"], max_seq_len=cap, plan=plan,
+                                    decide=hook)
+        torch.cuda.synchronize()
+        return outs, hist, time.perf_counter() - t0
+
+    res = {}
+    total = int(budgets.sum()) - B
+    for name, plan in (("plain", lambda b: (1, 0, 0)), ("rule", None), ("fixed", lambda b: fg.fg_plan(1, float(c_peak)))):
+        outs, hist, t = run(plan, decide)
+        spec = [h for h in hist if h["N"] > 1]
+        shapes = []
+        for h in hist:
+            if not shapes or shapes[-1][1:] != (h["N"], h["K"], h["L"]):
+                shapes.append((h["B"], h["N"], h["K"], h["L"]))
+        res[name] = dict(seconds=t, tokens_per_s=total / t, rounds=len(hist),
+                         tau=sum(h["emitted"] for h in hist) / max(sum(h["B"] for h in hist), 1),
+                         tau_speculative_rounds=(sum(h["emitted"] for h in spec) / sum(h["B"] for h in spec)) if spec else None,
+                         shapes_B_N_K_L=shapes[:24])
+    out = {"metric": "generated tokens/s over a whole rollout with concurrency decay (Alg. 1)", "unit": "tokens/s",
+           "value": res["rule"]["tokens_per_s"], "n_gpus": 1, "higher_is_better": True, "dtype": args.dtype, "data": "synthetic",
+           "config": {"workload": f"{model['name']} {model['n_layers']} layers, {B} sequences, prefixes U[256,1024], response budgets "
+                                  f"{int(budgets.min())}..{int(budgets.max())} (mean {budgets.mean():.0f}), planted agreement {p_agree}, greedy"},
+           "c_peak": c_peak, "c_peak_latency_ms": dict(zip(map(str, sizes), lat)), "runs": res,
+           "speedup_rule_vs_plain": res["rule"]["tokens_per_s"] / res["plain"]["tokens_per_s"],
+           "speedup_rule_vs_fixed": res["rule"]["tokens_per_s"] / res["fixed"]["tokens_per_s"]}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -230,6 +348,10 @@ def main():
     ap.add_argument("--layers", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-b8", action="store_true", help="skip the B = 8 point of the metric's range")
+    ap.add_argument("--gen", action="store_true", help="the generation loop with concurrency decay instead of the step benchmark")
+    ap.add_argument("--agree", type=float, default=0.7, help="--gen: planted per-node agreement rate")
+    ap.add_argument("--mean-len", type=int, default=160, help="--gen: mean response budget")
+    ap.add_argument("--c-peak", type=int, default=0, help="--gen: use this C_peak instead of the measured knee")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: every box of this build has one MI355X and the path shards by sequence "
@@ -239,6 +361,9 @@ def main():
     import paper_2509_21792_amd as fg
     fg.lib()
     assert torch.cuda.is_available(), "no GPU: the HIP path has no CPU fallback"
+    if args.gen:
+        gen_experiment(args)
+        return
 
     wl = Workload(args.workload, args.dtype, B=args.B or None, N=args.N or None, n_layers=args.layers or None, verbose=True)
     model, M = wl.model, wl.B * wl.N

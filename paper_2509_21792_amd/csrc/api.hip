@@ -3,6 +3,9 @@
 #include <math.h>
 #include <string.h>
 
+#include <array>
+#include <map>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -51,6 +54,7 @@ int32_t launch_build_tree(const int32_t *cand_tok, const int32_t *cand_parent, c
 int32_t launch_commit_len(int32_t *seq_len, const int32_t *slot, const int32_t *n_commit, int bias, int B, int n_slots,
                           hipStream_t st);
 int gemm_mfma_split_for(int M, int N, int K);
+bool gemm_mfma_uses_big(int M, int N);
 int32_t profile_gemm_arm(int enable, int n_out, int n_in, int epilogue, int max_launches);
 int32_t profile_gemm_read(double *total_ms, int32_t *count);
 
@@ -86,25 +90,38 @@ struct Carver {
 // split-K factor the library will use for each GEMM of the step (0 = not a partial-sum GEMM)
 int split_for(const fg_model_cfg &c, int M, int N, int K) { return is16(c.dtype) ? gemm_mfma_split_for(M, N, K) : 1; }
 
-bool gate_up_fused(const fg_model_cfg &c, int M) { return is16(c.dtype) && M > 256; }
+// gate/up with the SwiGLU epilogue (no split-K slabs) whenever the pipelined kernel runs it
+bool gate_up_fused(const fg_model_cfg &c, int M) { return is16(c.dtype) && gemm_mfma_uses_big(M, 2 * c.d_ffn); }
 
 int64_t partial_floats(const fg_model_cfg &c, int M, bool is_draft)
 {
     const int d = c.d_model, F = c.d_ffn, qkvd = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim, hq = c.n_q_heads * c.head_dim;
     int64_t m = 0;
-    // the split factor steps down as M crosses multiples of the block height, so S * M is not monotone in M:
-    // size for the worst row count up to M
-    auto upd = [&](int N, int K) {
-        for (int mm = M; mm > 0; mm = (mm - 1) / 256 * 256) {
+    // the split factors (and whether gate/up needs slabs at all) step with the row count, so S * rows is not
+    // monotone: size for the worst row count up to M
+    auto need = [&](int mm) {
+        auto upd = [&](int N, int K) {
             int64_t v = (int64_t)split_for(c, mm, N, K) * mm * N;
             if (v > m) m = v;
-        }
+        };
+        upd(qkvd, d);
+        upd(d, hq);
+        upd(d, F);
+        if (!gate_up_fused(c, mm)) upd(2 * F, d);
+        if (is_draft) upd(d, 2 * d);
     };
-    upd(qkvd, d);
-    upd(d, hq);
-    upd(d, F);
-    if (!gate_up_fused(c, M)) upd(2 * F, d);
-    if (is_draft) upd(d, 2 * d);
+    // every row count is tried once per (shape, M); the result is remembered
+    static std::mutex mu;
+    static std::map<std::array<int64_t, 9>, int64_t> memo;
+    const std::array<int64_t, 9> key = {c.dtype, d, F, qkvd, hq, M, is_draft, c.n_layers, c.vocab};
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        auto it = memo.find(key);
+        if (it != memo.end()) return it->second;
+    }
+    for (int mm = M; mm > 0; mm--) need(mm);
+    std::lock_guard<std::mutex> lock(mu);
+    memo[key] = m;
     return m;
 }
 

@@ -219,9 +219,13 @@ static int big_variant()
 
 int gemm_mfma_big_split_for(int M, int N, int K);
 
+// The pipelined kernel takes every shape with more than 256 rows, and from 129 rows on the wide ones (gate/up,
+// LM head), where a 256-row tile half full still beats streaming the weights through eight row tiles per wave.
+bool gemm_mfma_uses_big(int M, int N) { return big_variant() && (M > 256 || (M > 128 && N >= 16384)); }
+
 int gemm_mfma_split_for(int M, int N, int K)
 {
-    if (M > 256 && big_variant()) return gemm_mfma_big_split_for(M, N, K);
+    if (gemm_mfma_uses_big(M, N)) return gemm_mfma_big_split_for(M, N, K);
     return choose_split(M, N, K, 256, 256);
 }
 
@@ -263,7 +267,7 @@ int32_t launch_gemm_mfma(int32_t dtype, const void *x, const void *wp, void *out
                       g_prof.used < g_prof.start.size();
     if (prof) (void)hipEventRecord(g_prof.start[g_prof.used], st);
     int32_t rc;
-    if (M > 256 && big_variant()) rc = launch_gemm_mfma_big(dtype, x, wp, out, M, N, K, epilogue, split, raster_enabled(), st);
+    if (gemm_mfma_uses_big(M, N)) rc = launch_gemm_mfma_big(dtype, x, wp, out, M, N, K, epilogue, split, raster_enabled(), st);
     else rc = dtype == FG_BF16 ? launch_gemm_typed<bf16_t>(x, wp, out, M, N, K, epilogue, split, st)
                                : launch_gemm_typed<f16_t>(x, wp, out, M, N, K, epilogue, split, st);
     if (prof) (void)hipEventRecord(g_prof.stop[g_prof.used++], st);

@@ -50,12 +50,19 @@ def draft_expand(target, draft, dkv, slot, st, K, L, ws, max_seq_len=0):
     return cand_tok, cand_parent, cand_score
 
 
-def spec_round(target, draft, kv, dkv, slot, st, N, K, L, ws_t, ws_d, eos_id=-1, max_seq_len=0):
-    """One round on the live batch.  Returns (accept_len, out_tokens, finished) on the device and the next SpecState."""
+def spec_round(target, draft, kv, dkv, slot, st, N, K, L, ws_t, ws_d, eos_id=-1, max_seq_len=0, replant=None, decide=None):
+    """One round on the live batch.  Returns (accept_len, out_tokens, finished) on the device and the next SpecState.
+    replant(tokens, parent) -> tokens: a measurement hook for synthetic workloads, where no trained draft head
+    exists and the agreement between draft and target is planted into the reranked tree at a controlled rate.
+    decide(tokens, parent, row_argmax) -> row_argmax: the same purpose from the other side: the target's decisions
+    are overridden (throughput experiments whose token values do not matter)."""
     ct, cp, cs = draft_expand(target, draft, dkv, slot, st, K, L, ws_d, max_seq_len=max_seq_len)
     tokens, parent, _ = fg.fg_build_tree(ct, cp, cs, ct.shape[1], N)
+    if replant is not None:
+        tokens = replant(tokens, parent)
     out = fg.fg_spec_verify(target, kv, slot, tokens, parent, ws_t, max_seq_len=max_seq_len)
-    acc, path, otok, fin = fg.fg_spec_accept(tokens, parent, row_argmax=out["argmax"], eos_id=eos_id)
+    amax = out["argmax"] if decide is None else decide(tokens, parent, out["argmax"])
+    acc, path, otok, fin = fg.fg_spec_accept(tokens, parent, row_argmax=amax, eos_id=eos_id)
     B = tokens.shape[0]
     d = target.cfg["d_model"]
     feat = fg.fg_kv_compact(kv, slot, acc, path, feature_in=out["feature"].view(B, N, d), d_model=d)
@@ -82,7 +89,7 @@ def plain_round(target, draft, kv, dkv, slot, st, root, ws_t, ws_d, eos_id=-1, m
 
 
 def generate(target, draft, kv, dkv, slot, st, first, budgets, c_peak, ws_t, ws_d, alpha=0.5, K_max=4, L_max=6, N_cap=64,
-             eos_id=-1, max_seq_len=0, plan=None, max_rounds=10 ** 9):
+             eos_id=-1, max_seq_len=0, plan=None, max_rounds=10 ** 9, replant=None, decide=None):
     """The concurrency-aware generation loop (Alg. 1): every round (N, K, L) is re-planned from the number of live
     sequences (Eq. 1-3; `plan(B_cur) -> (N, K, L)` overrides the rule, e.g. a fixed shape for comparison), finished
     sequences leave the batch (device rows are re-selected with fg_select_rows), and the host sees only the accepted
@@ -90,6 +97,7 @@ def generate(target, draft, kv, dkv, slot, st, first, budgets, c_peak, ws_t, ws_
 
     slot int32 [B] (device), st: the draft head's pending entries after the prefill, first int32 [B] (host): the
     token already emitted per sequence, budgets [B] (host): tokens per sequence, first included.
+    replant(tokens, parent, live, outs) -> tokens and decide(tokens, parent, row_argmax) -> row_argmax: see spec_round.
     Returns (token lists, per-round history of dicts B, N, K, L, emitted).
     """
     B = len(first)
@@ -115,7 +123,8 @@ def generate(target, draft, kv, dkv, slot, st, first, budgets, c_peak, ws_t, ws_
             root = torch.as_tensor(np.array([outs[b][-1] for b in live], dtype=np.int32)).to(dev)
             acc, otok, fin, st = plain_round(target, draft, kv, dkv, slot, st, root, ws_t, ws_d, eos_id, max_seq_len)
         else:
-            acc, otok, fin, st = spec_round(target, draft, kv, dkv, slot, st, N, K, L, ws_t, ws_d, eos_id, max_seq_len)
+            hook = (lambda tk, pr: replant(tk, pr, live, outs)) if replant else None
+            acc, otok, fin, st = spec_round(target, draft, kv, dkv, slot, st, N, K, L, ws_t, ws_d, eos_id, max_seq_len, hook, decide)
         a, t, f = acc.cpu().numpy(), otok.cpu().numpy(), fin.cpu().numpy()     # the round's one trip to the host
         rows, nxt_live, emitted_round = [], [], 0
         for j, b in enumerate(live):
@@ -137,8 +146,10 @@ def generate(target, draft, kv, dkv, slot, st, first, budgets, c_peak, ws_t, ws_
 
 def measure_c_peak(target, kv, ws, batch_sizes, warmup=2, reps=5):
     """Empirical C_peak (appendix): latency of one forward pass over B single-token inputs, for each B in
-    batch_sizes, timed with events on the current stream; the knee of the curve is C_peak.  The sequences start from
-    empty caches (the cache must have at least max(batch_sizes) slots); nothing is committed.
+    batch_sizes, timed with events on the current stream; the knee of the curve is C_peak.  Batch sizes are meant
+    to be spaced geometrically and the knee is taken on the log2(B) axis, where the flat weight-bound part and the
+    rising compute-bound part have comparable extent.  The sequences start from empty caches (the cache must have
+    at least max(batch_sizes) slots); nothing is committed.
     Returns (C_peak, latencies in ms)."""
     dev = kv.k_pool.device
     times = []
@@ -157,5 +168,5 @@ def measure_c_peak(target, kv, ws, batch_sizes, warmup=2, reps=5):
         e1.record()
         torch.cuda.synchronize()
         times.append(e0.elapsed_time(e1) / reps)
-    k = fg.fg_knee(np.asarray(batch_sizes, dtype=np.float64), np.asarray(times, dtype=np.float64))
+    k = fg.fg_knee(np.log2(np.asarray(batch_sizes, dtype=np.float64)), np.asarray(times, dtype=np.float64))
     return int(batch_sizes[k]), times

@@ -286,3 +286,66 @@ def test_select_rows_and_knee(H):
     assert torch.equal(fg.fg_select_rows(s1, idx), s1[idx.long()])
     h = src.to(torch.bfloat16).contiguous()
     assert torch.equal(fg.fg_select_rows(h, idx), h[idx.long()])
+
+
+def test_adaptive_loop_with_planted_agreement_still_equals_plain_decoding(H):
+    """The synthetic-workload hook: the reranked tree's first-child chain is overwritten with the sequence's true
+    continuation (here the oracle's plain greedy decoding) at rate 0.8.  Accepted paths of several tokens, ragged
+    budgets and a shrinking live set together must still reproduce plain decoding exactly, with tau well above 1."""
+    import paper_2509_21792_amd as fg
+    from paper_2509_21792_amd import loop as gloop
+    cfg = configs.CONFIGS["cfg1"]
+    model = configs.TINY
+    pair = H.Pair(model, seed=cfg["seed"], with_draft=True)
+    orc = pair.orc
+    B, P = cfg["B"], cfg["prompt_len"]
+    budgets = np.array([6, 40, 17, 64, 9, 25, 33, 12], dtype=np.int32)[:B]
+    n_new = int(budgets.max())
+    prompts = gen.make_prompts(B, cfg["group"], P, model["vocab"], cfg["seed"])
+    ocache = orc.cache(model, B, P + n_new + 8)
+    _, ologits = oloop.prefill(orc, pair.om, ocache, prompts)
+    oroot, _ = orc.row_argmax(ologits[:, -1])
+    orest, _ = oloop.greedy_ar(orc, pair.om, ocache, oroot, n_new - 1)
+    ref = np.concatenate([oroot[:, None], orest], axis=1)
+    cap = P + n_new + 72
+    table, n_pages = gen.make_page_table(np.zeros(B, np.int32), cap, 16, 1)
+    kv = fg.KVCache(model, table, n_pages)
+    dtable, dn = gen.make_page_table(np.zeros(B, np.int32), cap, 16, 2)
+    dkv = fg.KVCache(pair.dcfg, dtable, dn)
+    slot = torch.arange(B, dtype=torch.int32, device="cuda")
+    ws_t = pair.gm.workspace(B * P, cap)
+    ws_d = pair.gd.workspace(B * P, cap)
+    ptok = torch.as_tensor(prompts).cuda()
+    out = fg.fg_spec_verify(pair.gm, kv, slot, ptok, gloop.chain_parent(B, P, "cuda"), ws_t, want_logits=False)
+    ident = torch.arange(P, dtype=torch.int32, device="cuda").repeat(B, 1)
+    feat = fg.fg_kv_compact(kv, slot, torch.full((B,), P - 1, dtype=torch.int32, device="cuda"), ident,
+                            feature_in=out["feature"].view(B, P, -1), d_model=model["d_model"])
+    root = out["argmax"].view(B, P)[:, -1].contiguous()
+    st = gloop.SpecState(torch.cat([ptok[:, 1:], root.view(B, 1)], dim=1).contiguous(), feat,
+                         torch.full((B,), P - 1, dtype=torch.int32, device="cuda"))
+    rng = np.random.default_rng(3)
+
+    def replant(tokens, parent, live, outs):
+        par, tok = parent.cpu().numpy(), tokens.cpu().numpy().copy()
+        for j, b in enumerate(live):
+            node, depth, done = 0, 0, len(outs[b])
+            while done + depth < n_new:
+                kids = np.nonzero(par[j] == node)[0]
+                if len(kids) == 0:
+                    break
+                node = int(kids[0])
+                if rng.random() >= 0.8:
+                    tok[j, node] = (ref[b, done + depth] + 1) % model["vocab"]
+                    break
+                tok[j, node] = ref[b, done + depth]
+                depth += 1
+        return torch.as_tensor(tok).cuda()
+
+    got, hist = gloop.generate(pair.gm, pair.gd, kv, dkv, slot, st, root.cpu().numpy(), budgets, 12.0, ws_t, ws_d,
+                               alpha=0.5, K_max=2, L_max=4, max_seq_len=cap, replant=replant)
+    for b in range(B):
+        assert got[b] == [int(t) for t in ref[b, :budgets[b]]], (b, got[b], list(ref[b, :budgets[b]]))
+    spec = [h for h in hist if h["N"] > 1]
+    tau = sum(h["emitted"] for h in spec) / sum(h["B"] for h in spec)
+    print(f"planted adaptive loop: {len(hist)} rounds, tau over speculative rounds {tau:.2f}", flush=True)
+    assert tau > 1.5
