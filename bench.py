@@ -23,7 +23,7 @@ PEAK_MFMA = 2516.6e12      # flop/s, dense bf16 / fp16 MFMA
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this benchmark,
 # scaled by what the same counters read for a plain 1 GiB copy (profiles/bench_cfg4_b256_n8_hbm_traffic_pmc.txt).
 # A recorded measurement, keyed by (workload, rows M); other workloads report null.
-MEASURED_TRAFFIC = {("cfg4", 2048): 766.3e6 + 72.6e6}
+MEASURED_TRAFFIC = {("cfg4", 2048): 815.4e6 + 77.6e6}
 
 
 def model_bytes_flops(model, M, lengths, N):
@@ -374,7 +374,7 @@ def main():
     epi = 1 if M > 256 else 0
     t_verify, _ = time_steps(torch, wl.verify_only, max(3, args.steps // 2), args.warmup)
     t_draft = time_steps(torch, wl.draft, max(3, args.steps // 2), 2)[0] if wl.draft_ready else 0.0
-    fg.fg_profile_gemm(True, n_out, n_in, epi, max_launches=(args.steps + 1) * model["n_layers"])
+    fg.fg_profile_gemm(True, n_out, n_in, epi, max_launches=(args.steps + args.warmup + 1) * model["n_layers"], rows=M)
     for _ in range(args.warmup):
         wl.step()
     fg.fg_profile_read()

@@ -289,11 +289,11 @@ int32_t fg_topk_logp(const float *logits, int32_t M, int32_t vocab, int32_t K, i
 
 /*
  * Measurement hook (for benchmarks, not part of the method): while armed, every 16-bit GEMM launch whose
- * (n_out, n_in, epilogue) match is bracketed by HIP events on its own stream, up to max_launches launches.
+ * (rows, n_out, n_in, epilogue) match (rows = 0 matches any row count) is bracketed by HIP events on its own stream, up to max_launches launches.
  * fg_profile_read waits for them, returns their summed duration in milliseconds and their number, and
  * resets the counter.  Not thread-safe; enable = 0 disarms.
  */
-int32_t fg_profile_gemm(int32_t enable, int32_t n_out, int32_t n_in, int32_t epilogue, int32_t max_launches);
+int32_t fg_profile_gemm(int32_t enable, int32_t rows, int32_t n_out, int32_t n_in, int32_t epilogue, int32_t max_launches);
 int32_t fg_profile_read(double *total_ms, int32_t *count);
 
 #ifdef __cplusplus

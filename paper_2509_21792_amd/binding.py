@@ -398,8 +398,8 @@ def fg_select_rows(src, index):
 
 
 # ---- measurement hook -------------------------------------------------------------------------------------------
-def fg_profile_gemm(enable, n_out=0, n_in=0, epilogue=0, max_launches=4096):
-    _check(lib().fg_profile_gemm(int(enable), n_out, n_in, epilogue, max_launches))
+def fg_profile_gemm(enable, n_out=0, n_in=0, epilogue=0, max_launches=4096, rows=0):
+    _check(lib().fg_profile_gemm(int(enable), rows, n_out, n_in, epilogue, max_launches))
 
 
 def fg_profile_read():

@@ -55,7 +55,7 @@ int32_t launch_commit_len(int32_t *seq_len, const int32_t *slot, const int32_t *
                           hipStream_t st);
 int gemm_mfma_split_for(int M, int N, int K);
 bool gemm_mfma_uses_big(int M, int N);
-int32_t profile_gemm_arm(int enable, int n_out, int n_in, int epilogue, int max_launches);
+int32_t profile_gemm_arm(int enable, int rows, int n_out, int n_in, int epilogue, int max_launches);
 int32_t profile_gemm_read(double *total_ms, int32_t *count);
 
 }  // namespace fg
@@ -580,10 +580,10 @@ int32_t fg_topk_logp(const float *logits, int32_t M, int32_t vocab, int32_t K, i
     return launch_topk_logp(logits, M, vocab, K, tok, logp, (hipStream_t)stream);
 }
 
-int32_t fg_profile_gemm(int32_t enable, int32_t n_out, int32_t n_in, int32_t epilogue, int32_t max_launches)
+int32_t fg_profile_gemm(int32_t enable, int32_t rows, int32_t n_out, int32_t n_in, int32_t epilogue, int32_t max_launches)
 {
     if (enable && (max_launches < 1 || max_launches > (1 << 20))) return fail(FG_ERR_INVALID_ARG, "fg_profile_gemm: bad max_launches");
-    return profile_gemm_arm(enable, n_out, n_in, epilogue, max_launches);
+    return profile_gemm_arm(enable, rows, n_out, n_in, epilogue, max_launches);
 }
 
 int32_t fg_profile_read(double *total_ms, int32_t *count)

@@ -149,7 +149,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(const T *__restr
 // on the launch stream, so a benchmark can read that kernel's average duration inside its own timed region.
 struct GemmProfile {
     bool on = false;
-    int n_out = 0, n_in = 0, epilogue = 0;
+    int rows = 0, n_out = 0, n_in = 0, epilogue = 0;
     std::vector<hipEvent_t> start, stop;
     size_t used = 0;
 };
@@ -263,7 +263,7 @@ int32_t launch_gemm_mfma(int32_t dtype, const void *x, const void *wp, void *out
         split = (K / 64 + cps - 1) / cps;
     }
     if (split_used) *split_used = split;
-    const bool prof = g_prof.on && g_prof.n_out == N && g_prof.n_in == K && g_prof.epilogue == epilogue &&
+    const bool prof = g_prof.on && (g_prof.rows == 0 || g_prof.rows == M) && g_prof.n_out == N && g_prof.n_in == K && g_prof.epilogue == epilogue &&
                       g_prof.used < g_prof.start.size();
     if (prof) (void)hipEventRecord(g_prof.start[g_prof.used], st);
     int32_t rc;
@@ -274,7 +274,7 @@ int32_t launch_gemm_mfma(int32_t dtype, const void *x, const void *wp, void *out
     return rc;
 }
 
-int32_t profile_gemm_arm(int enable, int n_out, int n_in, int epilogue, int max_launches)
+int32_t profile_gemm_arm(int enable, int rows, int n_out, int n_in, int epilogue, int max_launches)
 {
     g_prof.on = false;
     g_prof.used = 0;
@@ -286,7 +286,7 @@ int32_t profile_gemm_arm(int enable, int n_out, int n_in, int epilogue, int max_
         g_prof.start.push_back(a);
         g_prof.stop.push_back(b);
     }
-    g_prof.n_out = n_out; g_prof.n_in = n_in; g_prof.epilogue = epilogue;
+    g_prof.rows = rows; g_prof.n_out = n_out; g_prof.n_in = n_in; g_prof.epilogue = epilogue;
     g_prof.on = true;
     return FG_OK;
 }
