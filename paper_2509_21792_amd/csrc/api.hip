@@ -30,7 +30,7 @@ int32_t launch_swiglu_partials(int32_t dtype, const float *gu, int S, void *act,
 int32_t launch_attention_simple(const fg_kv_cache *kv, int layer, const fg_tree *t, TreeDev td, int Hq, const void *q, void *out,
                                 int max_keys, hipStream_t st);
 int32_t launch_attention_mfma(const fg_kv_cache *kv, int layer, const fg_tree *t, TreeDev td, int Hq, const void *q, void *out,
-                              int max_keys, void *ws, int64_t ws_bytes, hipStream_t st);
+                              int max_keys, void *ws, int64_t ws_bytes, int reuse_order, hipStream_t st);
 int64_t attention_mfma_ws_bytes(int B, int N, int Hq, int Hkv, int hd, int max_keys);
 bool attention_mfma_supported(const fg_kv_cache *kv, int Hq, int N);
 int32_t launch_gumbel_argmax(const float *logits, int M, int V, float T, uint64_t seed, int64_t row0, int32_t *idx, hipStream_t st);
@@ -202,11 +202,12 @@ int max_keys_of(const fg_kv_cache *kv, const fg_tree *t, int32_t *rc)
     return mk;
 }
 
+// reuse_order: the workspace still holds the item order an earlier layer of the same step built
 int32_t attention_any(const fg_kv_cache *kv, int layer, const fg_tree *t, TreeDev td, int Hq, const void *q, void *out,
-                      int max_keys, void *ws, int64_t ws_bytes, hipStream_t st)
+                      int max_keys, void *ws, int64_t ws_bytes, int reuse_order, hipStream_t st)
 {
     if (attention_mfma_supported(kv, Hq, t->N))
-        return launch_attention_mfma(kv, layer, t, td, Hq, q, out, max_keys, ws, ws_bytes, st);
+        return launch_attention_mfma(kv, layer, t, td, Hq, q, out, max_keys, ws, ws_bytes, reuse_order, st);
     return launch_attention_simple(kv, layer, t, td, Hq, q, out, max_keys, st);
 }
 
@@ -226,7 +227,7 @@ int32_t run_layers(const fg_model *m, fg_kv_cache *kv, const fg_tree *t, const S
         init = 0;
         if ((rc = gemm_any(c, w.a, m->wqkv[l], w.partials, M, qkvd, d, &S, st))) return rc;
         if ((rc = launch_rope_append(c.dtype, w.partials, S, t, w.td, kv, l, (const float *)m->rope_tab, c.max_pos, c.n_q_heads, w.q, st))) return rc;
-        if ((rc = attention_any(kv, l, t, w.td, c.n_q_heads, w.q, w.att, max_keys, w.attn_ws, w.attn_ws_bytes, st))) return rc;
+        if ((rc = attention_any(kv, l, t, w.td, c.n_q_heads, w.q, w.att, max_keys, w.attn_ws, w.attn_ws_bytes, l > 0, st))) return rc;
         if ((rc = gemm_any(c, w.att, m->wo[l], w.partials, M, d, hq, &S, st))) return rc;
         if ((rc = launch_add_rmsnorm(c.dtype, w.h, w.partials, S, 0, m->norm_ffn[l], w.a, nullptr, M, d, c.rms_eps, st))) return rc;
         if (gate_up_fused(c, M)) {
@@ -623,7 +624,7 @@ int32_t fg_attention(const fg_kv_cache *kv, int32_t layer, const fg_tree *tree, 
     if (!cv.ok) return fail(FG_ERR_CAPACITY, "fg_attention: workspace too small");
     hipStream_t st = (hipStream_t)stream;
     if ((rc = launch_tree_prep_ex(tree, kv->seq_len, kv->n_slots, td, st))) return rc;
-    return attention_any(kv, layer, tree, td, n_q_heads, q, out, mk, aws, ab, st);
+    return attention_any(kv, layer, tree, td, n_q_heads, q, out, mk, aws, ab, 0, st);
 }
 
 }  // extern "C"

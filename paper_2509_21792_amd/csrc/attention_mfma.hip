@@ -121,13 +121,14 @@ static int pick_qw(int N, int Hq, int Hkv)
 }
 
 template <typename T, int HD, int QW>
-__global__ __launch_bounds__(64) void attn_mfma_kernel(const T *__restrict__ q, const T *__restrict__ k_pool,
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(QW == 2 ? 2 : 1, QW == 2 ? 2 : 1))) void attn_mfma_kernel(const T *__restrict__ q, const T *__restrict__ k_pool,
                                                          const T *__restrict__ v_pool, const int32_t *__restrict__ page_table,
                                                          const int32_t *__restrict__ seq_len, const int32_t *__restrict__ slot,
                                                          const uint64_t *__restrict__ mask, float *__restrict__ part_o,
                                                          float *__restrict__ part_ml, int layer, int n_pages, int n_slots,
                                                          int max_pages, int N, int n_prev, int Hq, int Hkv, int QR, int CK,
-                                                         int n_chunks, int n_items, int waves, float scale)
+                                                         int n_chunks, int n_items, int waves, float scale,
+                                                         const int32_t *__restrict__ order)
 {
     constexpr int KK = HD / 32;   // MFMAs per S^T tile (contraction over head_dim)
     constexpr int HT = HD / 16;   // 16-row tiles of O^T
@@ -135,8 +136,9 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(const T *__restrict__ q, 
     // (sequence, kv head, chunk) item get block ids that differ by multiples of 8: they land on the same XCD
     // and the item's K/V is fetched into one L2 only.
     const int grp8 = blockIdx.x / (8 * waves), within = blockIdx.x % (8 * waves);
-    const int item = grp8 * 8 + (within & 7), wave = within >> 3;
-    if (item >= n_items) return;
+    const int idx = grp8 * 8 + (within & 7), wave = within >> 3;
+    if (idx >= n_items) return;
+    const int item = order[idx];   // longest items first (see attn_order_kernel)
     const int chunk = item % n_chunks, hk = (item / n_chunks) % Hkv, b = item / (n_chunks * Hkv);
     const int lane = threadIdx.x;
     const int c = lane & 15, grp = lane >> 4;
@@ -144,9 +146,14 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(const T *__restrict__ q, 
     const int s = min(max(slot[b], 0), n_slots - 1);
     const int L = seq_len[s];
     const int total = min(L + n_tot, max_pages * 16);
-    const int t_begin = chunk * CK;
+    // the sequence's keys are cut into nc = ceil(total / CK) chunks of equal size (a multiple of 32): items of one
+    // launch then differ in work by at most the ratio of the longest to the shortest chunk, not by 0 .. CK
+    const int nc = min((total + CK - 1) / CK, n_chunks);
+    if (chunk >= nc) return;
+    const int ck = ((total + nc - 1) / nc + 31) / 32 * 32;
+    const int t_begin = chunk * ck;
     if (t_begin >= total) return;
-    const int t_end = min(t_begin + CK, total);
+    const int t_end = min(t_begin + ck, total);
     const int qt0 = wave * QW;
     if (qt0 * 16 >= rows) return;
 
@@ -363,6 +370,39 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(const T *__restrict__ q, 
     }
 }
 
+// Launch order of the (sequence, kv head, chunk) items: longest first.  Blocks are dispatched in index order and
+// a CU slot takes the next block when it finishes one, so with the long items up front the short ones fill the
+// gaps at the end (longest-processing-time-first list scheduling) instead of a long item starting last.  One block:
+// counting sort by size class (128 classes of the chunk length CK; empty items last); the order within a class
+// is whatever the atomics give, which only affects scheduling.
+__global__ __launch_bounds__(1024) void attn_order_kernel(const int32_t *__restrict__ seq_len, const int32_t *__restrict__ slot,
+                                                            int n_slots, int max_pages, int n_tot, int Hkv, int CK, int n_chunks,
+                                                            int n_items, int32_t *__restrict__ order)
+{
+    constexpr int NB = 130;
+    __shared__ int cnt[NB], base[NB];
+    for (int i = threadIdx.x; i < NB; i += 1024) cnt[i] = 0;
+    __syncthreads();
+    auto size_class = [&](int item) {
+        const int chunk = item % n_chunks, b = item / (n_chunks * Hkv);
+        const int s = min(max(slot[b], 0), n_slots - 1);
+        const int total = min(seq_len[s] + n_tot, max_pages * 16);
+        const int nc = min((total + CK - 1) / CK, n_chunks);
+        if (chunk >= nc) return NB - 1;
+        const int ck = ((total + nc - 1) / nc + 31) / 32 * 32;
+        const int keys = min(ck, total - chunk * ck);
+        return keys <= 0 ? NB - 1 : 128 - min(128, (int)((int64_t)keys * 128 / CK));
+    };
+    for (int item = threadIdx.x; item < n_items; item += 1024) atomicAdd(&cnt[size_class(item)], 1);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int i = 0; i < NB; i++) { base[i] = run; run += cnt[i]; }
+    }
+    __syncthreads();
+    for (int item = threadIdx.x; item < n_items; item += 1024) order[atomicAdd(&base[size_class(item)], 1)] = item;
+}
+
 // Combine the chunks of one (row, query head): out = sum_c O_c e^(m_c - m) / sum_c l_c e^(m_c - m).
 template <typename T, int HD>
 __global__ __launch_bounds__(64) void attn_merge_kernel(const float *__restrict__ part_o, const float *__restrict__ part_ml,
@@ -419,27 +459,33 @@ int64_t attention_mfma_ws_bytes(int B, int N, int Hq, int Hkv, int hd, int max_k
     if (B < 1 || N < 1 || Hkv < 1 || Hq % Hkv) return 0;
     AttnPlan p = pick_qw(N, Hq, Hkv) == 2 ? plan_attention<2>(B, N, Hq, Hkv, max_keys) : plan_attention<4>(B, N, Hq, Hkv, max_keys);
     int64_t rows = (int64_t)B * Hkv * p.n_chunks * p.QR;
-    return align_up(rows * hd * 4, 256) + align_up(rows * 2 * 4, 256);
+    return align_up(rows * hd * 4, 256) + align_up(rows * 2 * 4, 256) + align_up((int64_t)B * Hkv * p.n_chunks * 4, 256);
 }
 
 template <typename T, int HD, int QW>
 static int32_t launch_typed(const fg_kv_cache *kv, int layer, const fg_tree *t, TreeDev td, int Hq, const void *q, void *out,
-                            int max_keys, void *ws, int64_t ws_bytes, hipStream_t st)
+                            int max_keys, void *ws, int64_t ws_bytes, int reuse_order, hipStream_t st)
 {
     const int B = t->B, N = t->N, Hkv = kv->n_kv_heads;
     AttnPlan p = plan_attention<QW>(B, N, Hq, Hkv, max_keys);
     int64_t rows = (int64_t)B * Hkv * p.n_chunks * p.QR;
-    int64_t need = align_up(rows * HD * 4, 256) + align_up(rows * 2 * 4, 256);
+    const int n_items = B * Hkv * p.n_chunks;
+    int64_t need = align_up(rows * HD * 4, 256) + align_up(rows * 2 * 4, 256) + align_up((int64_t)n_items * 4, 256);
     if (!ws || ws_bytes < need) return fail(FG_ERR_CAPACITY, "attention workspace too small (%lld < %lld)", (long long)ws_bytes, (long long)need);
     float *part_o = (float *)ws;
     float *part_ml = (float *)((char *)ws + align_up(rows * HD * 4, 256));
+    int32_t *order = (int32_t *)((char *)part_ml + align_up(rows * 2 * 4, 256));
     const float scale = 1.0f / sqrtf((float)HD);
-    const int n_items = B * Hkv * p.n_chunks;
+    if (!reuse_order) {   // lengths do not change within a step: the layers after the first reuse the order
+        hipLaunchKernelGGL(attn_order_kernel, dim3(1), dim3(1024), 0, st, kv->seq_len, t->slot, kv->n_slots, kv->max_pages_per_seq,
+                           t->n_prev + N, Hkv, p.CK, p.n_chunks, n_items, order);
+        FG_LAUNCH_CHECK("attn_order");
+    }
     dim3 grid((unsigned)((n_items + 7) / 8 * 8 * p.waves));
     hipLaunchKernelGGL((attn_mfma_kernel<T, HD, QW>), grid, dim3(64), 0, st, (const T *)q, (const T *)kv->k_pool,
                        (const T *)kv->v_pool, kv->page_table, kv->seq_len, t->slot, td.mask, part_o, part_ml, layer, kv->n_pages,
                        kv->n_slots, kv->max_pages_per_seq, N, t->n_prev, Hq, Hkv, p.QR, p.CK, p.n_chunks, n_items, p.waves,
-                       scale);
+                       scale, order);
     FG_LAUNCH_CHECK("attn_mfma");
     hipLaunchKernelGGL((attn_merge_kernel<T, HD>), dim3(B * N, Hq), dim3(64), 0, st, part_o, part_ml, kv->seq_len, t->slot,
                        (T *)out, kv->n_slots, kv->max_pages_per_seq, N, t->n_prev, Hq, Hkv, p.QR, p.CK, p.n_chunks);
@@ -448,12 +494,12 @@ static int32_t launch_typed(const fg_kv_cache *kv, int layer, const fg_tree *t, 
 }
 
 int32_t launch_attention_mfma(const fg_kv_cache *kv, int layer, const fg_tree *t, TreeDev td, int Hq, const void *q, void *out,
-                              int max_keys, void *ws, int64_t ws_bytes, hipStream_t st)
+                              int max_keys, void *ws, int64_t ws_bytes, int reuse_order, hipStream_t st)
 {
     const int qw = pick_qw(t->N, Hq, kv->n_kv_heads);
 #define FG_ATTN(T, HD)                                                                                          \
-    return qw == 2 ? launch_typed<T, HD, 2>(kv, layer, t, td, Hq, q, out, max_keys, ws, ws_bytes, st)           \
-                   : launch_typed<T, HD, 4>(kv, layer, t, td, Hq, q, out, max_keys, ws, ws_bytes, st)
+    return qw == 2 ? launch_typed<T, HD, 2>(kv, layer, t, td, Hq, q, out, max_keys, ws, ws_bytes, reuse_order, st) \
+                   : launch_typed<T, HD, 4>(kv, layer, t, td, Hq, q, out, max_keys, ws, ws_bytes, reuse_order, st)
     if (kv->dtype == FG_BF16) {
         if (kv->head_dim == 128) { FG_ATTN(bf16_t, 128); } else { FG_ATTN(bf16_t, 64); }
     } else {
