@@ -71,6 +71,21 @@ def test_tiny_fp32_wide_tree_and_empty_prefix(H):
     run_verify_case(H, configs.TINY, 5, 24, ("tree", 4, 5, 24), lengths, seed=4)
 
 
+def test_tiny_fp32_maximum_tree_and_page_edges(H):
+    """The largest tree the ancestor masks hold (64 nodes, depth 6 paths and a 63-deep chain), cache lengths on and
+    around page boundaries so that the in-round slots straddle up to five pages."""
+    lengths = np.array([0, 15, 16, 31, 1, 200, 255], dtype=np.int32)
+    run_verify_case(H, configs.TINY, 7, 64, ("tree", 4, 6, 64), lengths, seed=9)
+    run_verify_case(H, configs.TINY, 3, 64, ("chain", 63), np.array([7, 64, 129], dtype=np.int32), seed=10)
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+def test_1p5b_geometry_one_layer_maximum_tree(H, dtype):
+    """64-node trees through the 16-bit kernels (12 query tiles per kv head in the attention, M = 192 rows)."""
+    model = configs.with_dtype(configs.scaled(configs.Q1P5B, 1), dtype)
+    run_verify_case(H, model, 3, 64, ("tree", 4, 6, 64), np.array([5, 300, 1000], dtype=np.int32), seed=11)
+
+
 DT16 = ["fp16", "bf16"]
 
 
