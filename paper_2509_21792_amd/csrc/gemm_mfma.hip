@@ -185,22 +185,28 @@ static void launch_variant(const void *x, const void *wp, void *out, int M, int 
     }
 }
 
-// Number of k splits: enough blocks to cover the chip a few times over when the output is narrow, never
-// fewer than two chunks per split, and only for the fp32-partial epilogue.
+// Number of k splits of the weight-streaming kernel (fp32-partial epilogue only), by a small cost model in
+// microseconds: streaming W takes its bytes over 5.3 TB/s, stretched when there are too few blocks to keep the
+// memory system busy (about three blocks per CU for up to 32 rows, where a block is light, half of that above);
+// every split adds a slab of M x N fp32 that is written here and read back by the consumer (about 2 TB/s for
+// the pair).  Measured on the 7B-class and 1.5B-class shapes: gate/up at 48-128 rows wants 3 splits where a
+// fixed block target gave 6 (60 -> 47 us at 48 rows, 81 -> 61 at 96), the narrow outputs keep the maximum.
 static int choose_split(int M, int N, int K, int block_rows, int block_cols)
 {
-    const int blocks = ((N + block_cols - 1) / block_cols) * ((M + block_rows - 1) / block_rows);
+    const int bands = ((N + block_cols - 1) / block_cols) * ((M + block_rows - 1) / block_rows);
     const int total_chunks = K / 64;
-    int want = (768 + blocks - 1) / blocks;
-    if (M > 256) want = (320 + blocks - 1) / blocks;
-    int s = want < 1 ? 1 : want;
-    if (s > 16) s = 16;
-    if (s > total_chunks / 2) s = total_chunks / 2;
-    if (s < 1) s = 1;
-    // make every split non-empty
-    int cps = (total_chunks + s - 1) / s;
-    s = (total_chunks + cps - 1) / cps;
-    return s;
+    const double w_us = 2.0 * N * K / 5.3e6, slab_us = 4.0 * M * N / 2.0e6;
+    const double sat = M <= 32 ? 800.0 : 400.0;
+    int best = 1;
+    double best_cost = 1e30;
+    for (int s = 1; s <= 16 && s <= (total_chunks >= 2 ? total_chunks / 2 : 1); s++) {
+        const int cps = (total_chunks + s - 1) / s;
+        if ((total_chunks + cps - 1) / cps != s) continue;   // some split would be empty
+        const double util = bands * s >= sat ? 1.0 : bands * s / sat;
+        const double cost = w_us / util + s * slab_us;
+        if (cost < best_cost) { best_cost = cost; best = s; }
+    }
+    return best;
 }
 
 // More than 256 rows: the pipelined 256 x 256 kernel (gemm_mfma_big.hip).  FG_GEMM_BIG=0 keeps the streaming
