@@ -170,3 +170,40 @@ def measure_c_peak(target, kv, ws, batch_sizes, warmup=2, reps=5):
         times.append(e0.elapsed_time(e1) / reps)
     k = fg.fg_knee(np.log2(np.asarray(batch_sizes, dtype=np.float64)), np.asarray(times, dtype=np.float64))
     return int(batch_sizes[k]), times
+
+
+def prefill(target, draft, kv, dkv, slot, prompts, ws_t, ws_d, chunk=64, max_seq_len=0):
+    """Run the prompts [B, P] (device int32) through the target and commit them, in chain steps of at most `chunk`
+    tokens (a chain of n tokens is a tree whose node i has parent i - 1, so one verify step prefills n positions
+    against everything committed before; n <= 64, the width of the ancestor masks).  The draft head consumes the
+    matching entries (token t + 1 paired with the target's feature t) as it goes, except the last one, whose token
+    is the first generated one.  Returns (first [B] int32 on the device: the arg-max after the last prompt token,
+    SpecState holding that last pending entry)."""
+    B, P = prompts.shape
+    dev = prompts.device
+    d = target.cfg["d_model"]
+    prev_feat = None          # feature of the last position of the previous chunk, waiting for its token
+    first = None
+    for p0 in range(0, P, chunk):
+        n = min(chunk, P - p0)
+        tok = prompts[:, p0:p0 + n].contiguous()
+        par = chain_parent(B, n, dev)
+        out = fg.fg_spec_verify(target, kv, slot, tok, par, ws_t, max_seq_len=max_seq_len)
+        ident = torch.arange(n, dtype=torch.int32, device=dev).repeat(B, 1)
+        feat = fg.fg_kv_compact(kv, slot, torch.full((B,), n - 1, dtype=torch.int32, device=dev), ident,
+                                feature_in=out["feature"].view(B, n, d), d_model=d)
+        # draft entries completed by this chunk: (prompt token t + 1, feature t) for t = p0 - 1 .. p0 + n - 2
+        if draft is not None:
+            if prev_feat is None:
+                e_tok, e_feat = tok[:, 1:].contiguous(), feat[:, :n - 1].contiguous()
+            else:
+                e_tok, e_feat = tok, torch.cat([prev_feat, feat[:, :n - 1]], dim=1).contiguous()
+            m = e_tok.shape[1]
+            if m > 0:
+                fg.fg_draft_step(target, draft, dkv, slot, e_tok, chain_parent(B, m, dev), e_feat, ws_d, 1,
+                                 n_commit=torch.full((B,), m, dtype=torch.int32, device=dev), commit_bias=0,
+                                 max_seq_len=max_seq_len, want_children=False)
+        prev_feat = feat[:, n - 1:n].contiguous()
+        first = out["argmax"].view(B, n)[:, -1].contiguous()
+    st = SpecState(first.view(B, 1).contiguous(), prev_feat, torch.zeros(B, dtype=torch.int32, device=dev))
+    return first, st

@@ -349,3 +349,43 @@ def test_adaptive_loop_with_planted_agreement_still_equals_plain_decoding(H):
     tau = sum(h["emitted"] for h in spec) / sum(h["B"] for h in spec)
     print(f"planted adaptive loop: {len(hist)} rounds, tau over speculative rounds {tau:.2f}", flush=True)
     assert tau > 1.5
+
+
+def test_chunked_prefill_then_adaptive_generation(H):
+    """Prompts of 150 tokens prefilled in chain steps of 64, 64 and 22 positions (target and draft caches), then the
+    concurrency-aware loop: first tokens, emitted tokens, round history and both cache lengths equal the oracle's,
+    which prefills the whole prompt in one pass."""
+    import paper_2509_21792_amd as fg
+    from paper_2509_21792_amd import loop as gloop
+    model = configs.TINY
+    pair = H.Pair(model, seed=21, with_draft=True)
+    orc = pair.orc
+    B, P = 3, 150
+    budgets = np.array([5, 30, 14], dtype=np.int32)
+    n_new = int(budgets.max())
+    c_peak, alpha, K_max, L_max = 6.0, 0.5, 2, 3
+    prompts = gen.make_prompts(B, 1, P, model["vocab"], 21)
+    ocache = orc.cache(model, B, P + n_new + 72)
+    odcache = orc.cache(pair.dcfg, B, P + n_new + 72)
+    ofeat, ologits = oloop.prefill(orc, pair.om, ocache, prompts)
+    oroot, _ = orc.row_argmax(ologits[:, -1])
+    ocatch = np.concatenate([prompts[:, 1:], oroot[:, None]], axis=1).astype(np.int32)
+    want, want_hist = oloop.adaptive_generate(orc, pair.om, pair.od, ocache, odcache, ocatch, ofeat, np.full(B, P, np.int32), oroot,
+                                              budgets, c_peak, alpha=alpha, K_max=K_max, L_max=L_max)
+    cap = P + n_new + 72
+    table, n_pages = gen.make_page_table(np.zeros(B, np.int32), cap, 16, 1)
+    kv = fg.KVCache(model, table, n_pages)
+    dtable, dn = gen.make_page_table(np.zeros(B, np.int32), cap, 16, 2)
+    dkv = fg.KVCache(pair.dcfg, dtable, dn)
+    slot = torch.arange(B, dtype=torch.int32, device="cuda")
+    ws_t = pair.gm.workspace(B * 64, cap)
+    ws_d = pair.gd.workspace(B * 64, cap)
+    first, st = gloop.prefill(pair.gm, pair.gd, kv, dkv, slot, torch.as_tensor(prompts).cuda(), ws_t, ws_d, max_seq_len=cap)
+    torch.cuda.synchronize()
+    assert np.array_equal(first.cpu().numpy(), oroot)
+    assert (kv.seq_len.cpu().numpy() == P).all() and (dkv.seq_len.cpu().numpy() == P - 1).all()
+    got, hist = gloop.generate(pair.gm, pair.gd, kv, dkv, slot, st, first.cpu().numpy(), budgets, c_peak, ws_t, ws_d,
+                               alpha=alpha, K_max=K_max, L_max=L_max, max_seq_len=cap)
+    for b in range(B):
+        assert got[b] == want[b], (b, got[b], want[b])
+    assert hist == want_hist
