@@ -405,12 +405,14 @@ __global__ __launch_bounds__(1024) void attn_order_kernel(const int32_t *__restr
 
 // Combine the chunks of one (row, query head): out = sum_c O_c e^(m_c - m) / sum_c l_c e^(m_c - m).
 template <typename T, int HD>
-__global__ __launch_bounds__(64) void attn_merge_kernel(const float *__restrict__ part_o, const float *__restrict__ part_ml,
+__global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict__ part_o, const float *__restrict__ part_ml,
                                                         const int32_t *__restrict__ seq_len, const int32_t *__restrict__ slot,
                                                         T *__restrict__ out, int n_slots, int max_pages, int N, int n_prev,
                                                         int Hq, int Hkv, int QR, int CK, int n_chunks)
 {
-    const int r = blockIdx.x, hq = blockIdx.y, lane = threadIdx.x;
+    // one wave per (row, query head), four heads per block
+    const int r = blockIdx.x, hq = blockIdx.y * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (hq >= Hq) return;
     const int b = r / N, j = r % N, G = Hq / Hkv, hk = hq / G, g = hq % G;
     const int s = min(max(slot[b], 0), n_slots - 1);
     const int total = min(seq_len[s] + n_prev + N, max_pages * 16);
@@ -487,7 +489,7 @@ static int32_t launch_typed(const fg_kv_cache *kv, int layer, const fg_tree *t, 
                        kv->n_slots, kv->max_pages_per_seq, N, t->n_prev, Hq, Hkv, p.QR, p.CK, p.n_chunks, n_items, p.waves,
                        scale, order);
     FG_LAUNCH_CHECK("attn_mfma");
-    hipLaunchKernelGGL((attn_merge_kernel<T, HD>), dim3(B * N, Hq), dim3(64), 0, st, part_o, part_ml, kv->seq_len, t->slot,
+    hipLaunchKernelGGL((attn_merge_kernel<T, HD>), dim3(B * N, (Hq + 3) / 4), dim3(256), 0, st, part_o, part_ml, kv->seq_len, t->slot,
                        (T *)out, kv->n_slots, kv->max_pages_per_seq, N, t->n_prev, Hq, Hkv, p.QR, p.CK, p.n_chunks);
     FG_LAUNCH_CHECK("attn_merge");
     return FG_OK;

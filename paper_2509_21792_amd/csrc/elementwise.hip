@@ -276,26 +276,28 @@ int32_t launch_swiglu_f32(const float *gu, float *act, int M, int F, hipStream_t
     return FG_OK;
 }
 
-// sum split-K slabs of an interleaved gate/up output and apply SwiGLU: act[m, f] (16-bit)
+// sum split-K slabs of an interleaved gate/up output and apply SwiGLU: act[m, f] (16-bit); a thread owns four
+// consecutive features (one float4 of gate and one of up per slab, all slab loads independent)
 template <typename T>
 __global__ void swiglu_partials_kernel(const float *gu, int S, T *act, int M, int F)
 {
-    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (size_t)M * F) return;
-    int m = idx / F, f = idx % F;
-    int t = f >> 5, j = f & 31;
-    float g = 0.f, u = 0.f;
-    for (int s = 0; s < S; s++) {
-        const float *row = gu + ((size_t)s * M + m) * 2 * F;
-        g += row[64 * t + j];
-        u += row[64 * t + 32 + j];
-    }
-    act[idx] = from_f<T>(g / (1.f + __expf(-g)) * u);
+    const size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // quad index over [M, F / 4]
+    const int fq = F >> 2;
+    if (q >= (size_t)M * fq) return;
+    const int m = (int)(q / fq), f = (int)(q % fq) * 4;
+    const int t = f >> 5, j = f & 31;
+    const size_t slab = (size_t)M * 2 * F;
+    const float *row = gu + (size_t)m * 2 * F + 64 * t + j;
+    const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+    const float4 g = slab_sum4(row, slab, S, zero), u = slab_sum4(row + 32, slab, S, zero);
+    store4<T>(act + (size_t)m * F + f, make_float4(g.x / (1.f + __expf(-g.x)) * u.x, g.y / (1.f + __expf(-g.y)) * u.y,
+                                                   g.z / (1.f + __expf(-g.z)) * u.z, g.w / (1.f + __expf(-g.w)) * u.w));
 }
 
 int32_t launch_swiglu_partials(int32_t dtype, const float *gu, int S, void *act, int M, int F, hipStream_t st)
 {
-    size_t total = (size_t)M * F;
+    if (F % 32) return fail(FG_ERR_SHAPE, "d_ffn %d is not a multiple of 32", F);
+    const size_t total = (size_t)M * (F / 4);
     if (dtype == FG_BF16)
         hipLaunchKernelGGL(swiglu_partials_kernel<bf16_t>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, gu, S,
                            (bf16_t *)act, M, F);
