@@ -25,7 +25,7 @@ int32_t fail(int32_t code, const char *fmt, ...)
 }
 
 // launchers defined in the other translation units and not listed in fg_common.h
-int32_t launch_tree_prep_ex(const fg_tree *t, const int32_t *seq_len, int n_slots, TreeDev td, hipStream_t st);
+int32_t launch_tree_prep_ex(const fg_tree *t, const fg_kv_cache *kv, TreeDev td, hipStream_t st);
 int32_t launch_swiglu_partials(int32_t dtype, const float *gu, int S, void *act, int M, int F, hipStream_t st);
 int32_t launch_attention_simple(const fg_kv_cache *kv, int layer, const fg_tree *t, TreeDev td, int Hq, const void *q, void *out,
                                 int max_keys, hipStream_t st);
@@ -142,6 +142,7 @@ int64_t carve_step(const fg_model_cfg &c, int M, int max_keys, int B, int N, boo
     StepWs s;
     s.td.pos = cv.take<int32_t>(M);
     s.td.mask = cv.take<uint64_t>(M);
+    s.td.dest = cv.take<int32_t>(M);
     s.h = cv.take<float>((int64_t)M * d);
     s.partials = cv.take<float>(partial_floats(c, M, is_draft));
     s.a = cv.take<char>((int64_t)M * d * es);
@@ -407,7 +408,7 @@ int32_t fg_spec_verify(fg_model *m, fg_kv_cache *kv, const fg_tree *tree, float 
     const bool need_logits = !logits && (row_argmax || row_top2);
     if (carve_step(c, M, mk, tree->B, tree->N, false, workspace, workspace_bytes, &w, need_logits) < 0)
         return fail(FG_ERR_CAPACITY, "workspace too small: have %lld bytes", (long long)workspace_bytes);
-    if ((rc = launch_tree_prep_ex(tree, kv->seq_len, kv->n_slots, w.td, st))) return rc;
+    if ((rc = launch_tree_prep_ex(tree, kv, w.td, st))) return rc;
     if ((rc = launch_embed(c.dtype, m->embed, tree->tokens, c.vocab, w.h, M, c.d_model, st))) return rc;
     int S = 0;
     if ((rc = run_layers(m, kv, tree, w, mk, 0, &S, st))) return rc;
@@ -503,7 +504,7 @@ int32_t fg_draft_step(fg_model *target, fg_model *draft, fg_kv_cache *draft_kv, 
     StepWs w;
     if (carve_step(c, M, mk, tree->B, tree->N, true, workspace, workspace_bytes, &w, child_tok != nullptr) < 0)
         return fail(FG_ERR_CAPACITY, "workspace too small: have %lld bytes", (long long)workspace_bytes);
-    if ((rc = launch_tree_prep_ex(tree, draft_kv->seq_len, draft_kv->n_slots, w.td, st))) return rc;
+    if ((rc = launch_tree_prep_ex(tree, draft_kv, w.td, st))) return rc;
     if ((rc = launch_concat_embed(c.dtype, target->embed, tree->tokens, c.vocab, in_feature, feat_index, tree->N, feat_rows, w.cat, M, d, st))) return rc;
     int S = 0;
     if ((rc = gemm_any(c, w.cat, draft->fc, w.partials, M, d, 2 * d, &S, st))) return rc;
@@ -597,7 +598,7 @@ int64_t fg_attention_workspace_bytes(int32_t B, int32_t N, int32_t n_q_heads, in
                                      int32_t max_seq_len)
 {
     if (B < 1 || N < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads) return 0;
-    return align_up((int64_t)B * N * 4, 256) + align_up((int64_t)B * N * 8, 256) +
+    return 2 * align_up((int64_t)B * N * 4, 256) + align_up((int64_t)B * N * 8, 256) +
            attention_mfma_ws_bytes(B, N, n_q_heads, n_kv_heads, head_dim, max_seq_len) + 1024;
 }
 
@@ -619,11 +620,12 @@ int32_t fg_attention(const fg_kv_cache *kv, int32_t layer, const fg_tree *tree, 
     TreeDev td;
     td.pos = cv.take<int32_t>(M);
     td.mask = cv.take<uint64_t>(M);
+    td.dest = cv.take<int32_t>(M);
     int64_t ab = attention_mfma_ws_bytes(tree->B, tree->N, n_q_heads, kv->n_kv_heads, kv->head_dim, mk);
     void *aws = cv.take<char>(ab);
     if (!cv.ok) return fail(FG_ERR_CAPACITY, "fg_attention: workspace too small");
     hipStream_t st = (hipStream_t)stream;
-    if ((rc = launch_tree_prep_ex(tree, kv->seq_len, kv->n_slots, td, st))) return rc;
+    if ((rc = launch_tree_prep_ex(tree, kv, td, st))) return rc;
     return attention_any(kv, layer, tree, td, n_q_heads, q, out, mk, aws, ab, 0, st);
 }
 

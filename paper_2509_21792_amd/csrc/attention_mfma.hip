@@ -123,12 +123,11 @@ static int pick_qw(int N, int Hq, int Hkv)
 template <typename T, int HD, int QW>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(QW == 2 ? 2 : 1, QW == 2 ? 2 : 1))) void attn_mfma_kernel(const T *__restrict__ q, const T *__restrict__ k_pool,
                                                          const T *__restrict__ v_pool, const int32_t *__restrict__ page_table,
-                                                         const int32_t *__restrict__ seq_len, const int32_t *__restrict__ slot,
                                                          const uint64_t *__restrict__ mask, float *__restrict__ part_o,
-                                                         float *__restrict__ part_ml, int layer, int n_pages, int n_slots,
+                                                         float *__restrict__ part_ml, int layer, int n_pages,
                                                          int max_pages, int N, int n_prev, int Hq, int Hkv, int QR, int CK,
                                                          int n_chunks, int n_items, int waves, float scale,
-                                                         const int32_t *__restrict__ order)
+                                                         const int4 *__restrict__ order)
 {
     constexpr int KK = HD / 32;   // MFMAs per S^T tile (contraction over head_dim)
     constexpr int HT = HD / 16;   // 16-row tiles of O^T
@@ -138,24 +137,35 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(QW == 2 ? 2 
     const int grp8 = blockIdx.x / (8 * waves), within = blockIdx.x % (8 * waves);
     const int idx = grp8 * 8 + (within & 7), wave = within >> 3;
     if (idx >= n_items) return;
-    const int item = order[idx];   // longest items first (see attn_order_kernel)
+    const int4 desc = order[idx];   // longest items first (see attn_order_kernel): item, cache slot, committed length
+    const int item = desc.x, s = desc.y, L = desc.z;
     const int chunk = item % n_chunks, hk = (item / n_chunks) % Hkv, b = item / (n_chunks * Hkv);
     const int lane = threadIdx.x;
     const int c = lane & 15, grp = lane >> 4;
     const int G = Hq / Hkv, n_tot = n_prev + N, rows = G * N;
-    const int s = min(max(slot[b], 0), n_slots - 1);
-    const int L = seq_len[s];
+    const int qt0 = wave * QW;
+    if (qt0 * 16 >= rows) return;
     const int total = min(L + n_tot, max_pages * 16);
     // the sequence's keys are cut into nc = ceil(total / CK) chunks of equal size (a multiple of 32): items of one
     // launch then differ in work by at most the ratio of the longest to the shortest chunk, not by 0 .. CK
     const int nc = min((total + CK - 1) / CK, n_chunks);
-    if (chunk >= nc) return;
-    const int ck = ((total + nc - 1) / nc + 31) / 32 * 32;
+    const int ck = ((total + max(nc, 1) - 1) / max(nc, 1) + 31) / 32 * 32;
     const int t_begin = chunk * ck;
-    if (t_begin >= total) return;
+    if (chunk >= nc || t_begin >= total) {
+        // a chunk beyond the sequence: publish l = 0 so that the merge can read every chunk without knowing the length
+        if (grp == 0) {
+#pragma unroll
+            for (int w = 0; w < QW; w++) {
+                const int qi = (qt0 + w) * 16 + c;
+                if (qi < rows) {
+                    const size_t row = (((size_t)b * Hkv + hk) * n_chunks + chunk) * QR + qi;
+                    *reinterpret_cast<float2 *>(part_ml + row * 2) = make_float2(0.f, 0.f);
+                }
+            }
+        }
+        return;
+    }
     const int t_end = min(t_begin + ck, total);
-    const int qt0 = wave * QW;
-    if (qt0 * 16 >= rows) return;
 
     // query fragments (parked in LDS: each lane reads back only what it wrote, so no barrier is needed; this
     // frees QW * KK * 4 registers for the K / V double buffer) and per-column masks
@@ -374,76 +384,114 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(QW == 2 ? 2 
 // a CU slot takes the next block when it finishes one, so with the long items up front the short ones fill the
 // gaps at the end (longest-processing-time-first list scheduling) instead of a long item starting last.  One block:
 // counting sort by size class (128 classes of the chunk length CK; empty items last); the order within a class
-// is whatever the atomics give, which only affects scheduling.
+// is whatever the atomics give, which only affects scheduling.  Each entry carries what the attention kernel
+// would otherwise fetch through two more dependent loads: (item, cache slot, committed length, 0).
 __global__ __launch_bounds__(1024) void attn_order_kernel(const int32_t *__restrict__ seq_len, const int32_t *__restrict__ slot,
                                                             int n_slots, int max_pages, int n_tot, int Hkv, int CK, int n_chunks,
-                                                            int n_items, int32_t *__restrict__ order)
+                                                            int n_items, int4 *__restrict__ order)
 {
     constexpr int NB = 130;
     __shared__ int cnt[NB], base[NB];
     for (int i = threadIdx.x; i < NB; i += 1024) cnt[i] = 0;
     __syncthreads();
-    auto size_class = [&](int item) {
+    auto describe = [&](int item, int &s, int &L) {
         const int chunk = item % n_chunks, b = item / (n_chunks * Hkv);
-        const int s = min(max(slot[b], 0), n_slots - 1);
-        const int total = min(seq_len[s] + n_tot, max_pages * 16);
+        s = min(max(slot[b], 0), n_slots - 1);
+        L = seq_len[s];
+        const int total = min(L + n_tot, max_pages * 16);
         const int nc = min((total + CK - 1) / CK, n_chunks);
         if (chunk >= nc) return NB - 1;
         const int ck = ((total + nc - 1) / nc + 31) / 32 * 32;
         const int keys = min(ck, total - chunk * ck);
         return keys <= 0 ? NB - 1 : 128 - min(128, (int)((int64_t)keys * 128 / CK));
     };
-    for (int item = threadIdx.x; item < n_items; item += 1024) atomicAdd(&cnt[size_class(item)], 1);
+    int s, L;
+    for (int item = threadIdx.x; item < n_items; item += 1024) atomicAdd(&cnt[describe(item, s, L)], 1);
     __syncthreads();
     if (threadIdx.x == 0) {
         int run = 0;
         for (int i = 0; i < NB; i++) { base[i] = run; run += cnt[i]; }
     }
     __syncthreads();
-    for (int item = threadIdx.x; item < n_items; item += 1024) order[atomicAdd(&base[size_class(item)], 1)] = item;
+    for (int item = threadIdx.x; item < n_items; item += 1024) {
+        const int cls = describe(item, s, L);
+        order[atomicAdd(&base[cls], 1)] = make_int4(item, s, L, 0);
+    }
 }
 
-// Combine the chunks of one (row, query head): out = sum_c O_c e^(m_c - m) / sum_c l_c e^(m_c - m).
+// Combine the chunks of one (row, query head): out = sum_c O_c e^(m_c - m) / sum_c l_c e^(m_c - m).  Every chunk
+// slot of the launch holds (m, l) -- l = 0 for chunks beyond the sequence, whose O is then never used -- so nothing
+// here waits on the sequence length: the (m, l) loads and the first CB chunks' O loads are in flight together.
+template <typename T, int HD, int CB>
+__device__ __forceinline__ void merge_row(const float *__restrict__ part_o, const float *__restrict__ part_ml, size_t row0,
+                                          int QR, int n_chunks, int lane, float (&acc)[HD / 64], float &den)
+{
+    float m = -INFINITY;
+    float2 ml0 = make_float2(0.f, 0.f);
+    if (lane < n_chunks) ml0 = *reinterpret_cast<const float2 *>(part_ml + (row0 + (size_t)lane * QR) * 2);
+    // O of the first CB chunks (indices clamped: the surplus copies get weight 0)
+    float v0[CB][HD / 64];
+#pragma unroll
+    for (int cc = 0; cc < CB; cc++) {
+        const float *po = part_o + (row0 + (size_t)min(cc, n_chunks - 1) * QR) * HD + lane;
+#pragma unroll
+        for (int i = 0; i < HD / 64; i++) v0[cc][i] = po[64 * i];
+    }
+    m = ml0.y > 0.f ? ml0.x : -INFINITY;
+    for (int ch = 64 + lane; ch < n_chunks; ch += 64) {
+        const float2 ml = *reinterpret_cast<const float2 *>(part_ml + (row0 + (size_t)ch * QR) * 2);
+        m = fmaxf(m, ml.y > 0.f ? ml.x : -INFINITY);
+    }
+    m = wave_max(m);
+    float wgt = ml0.y > 0.f ? __expf(ml0.x - m) : 0.f;
+    den = ml0.y * wgt;
+#pragma unroll
+    for (int cc = 0; cc < CB; cc++) {
+        const float wc = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(wgt), cc));
+#pragma unroll
+        for (int i = 0; i < HD / 64; i++) acc[i] += wc != 0.f ? v0[cc][i] * wc : 0.f;
+    }
+    // the rest, eight chunks' loads at a time
+    for (int base = 0; base < n_chunks; base += 64) {
+        if (base) {
+            const int ch = base + lane;
+            wgt = 0.f;
+            if (ch < n_chunks) {
+                const float2 ml = *reinterpret_cast<const float2 *>(part_ml + (row0 + (size_t)ch * QR) * 2);
+                wgt = ml.y > 0.f ? __expf(ml.x - m) : 0.f;
+                den += ml.y * wgt;
+            }
+        }
+        const int cnt = min(64, n_chunks - base);
+#pragma unroll 8
+        for (int cc = base ? 0 : CB; cc < cnt; cc++) {
+            const float wc = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(wgt), cc));
+            const float *po = part_o + (row0 + (size_t)(base + cc) * QR) * HD + lane;
+#pragma unroll
+            for (int i = 0; i < HD / 64; i++) {
+                const float v = po[64 * i];
+                acc[i] += wc != 0.f ? v * wc : 0.f;
+            }
+        }
+    }
+}
+
 template <typename T, int HD>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict__ part_o, const float *__restrict__ part_ml,
-                                                        const int32_t *__restrict__ seq_len, const int32_t *__restrict__ slot,
-                                                        T *__restrict__ out, int n_slots, int max_pages, int N, int n_prev,
-                                                        int Hq, int Hkv, int QR, int CK, int n_chunks)
+                                                        T *__restrict__ out, int N, int Hq, int Hkv, int QR, int n_chunks)
 {
     // one wave per (row, query head), four heads per block
     const int r = blockIdx.x, hq = blockIdx.y * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (hq >= Hq) return;
     const int b = r / N, j = r % N, G = Hq / Hkv, hk = hq / G, g = hq % G;
-    const int s = min(max(slot[b], 0), n_slots - 1);
-    const int total = min(seq_len[s] + n_prev + N, max_pages * 16);
-    const int nc = min((total + CK - 1) / CK, n_chunks);
     const int qi = j * G + g;
-    // lanes over chunks for the reference and the weights, then lanes over head_dim for the weighted sum (the
-    // chunk loop is unrolled so that its independent loads are in flight together)
     const size_t row0 = (((size_t)b * Hkv + hk) * n_chunks) * QR + qi;   // chunk ch is row0 + ch * QR
-    float m = -INFINITY;
-    for (int ch = lane; ch < nc; ch += 64) m = fmaxf(m, part_ml[(row0 + (size_t)ch * QR) * 2]);
-    m = wave_max(m);
     float den = 0.f, acc[HD / 64];
 #pragma unroll
     for (int i = 0; i < HD / 64; i++) acc[i] = 0.f;
-    for (int base = 0; base < nc; base += 64) {
-        const int ch = base + lane;
-        float wgt = 0.f;
-        if (ch < nc) {
-            const float2 ml = *reinterpret_cast<const float2 *>(part_ml + (row0 + (size_t)ch * QR) * 2);
-            wgt = ml.y == 0.f ? 0.f : __expf(ml.x - m);
-            den += ml.y * wgt;
-        }
-        const int cnt = min(64, nc - base);
-#pragma unroll 8
-        for (int cc = 0; cc < cnt; cc++) {
-            const float wc = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(wgt), cc));
-            const float *po = part_o + (row0 + (size_t)(base + cc) * QR) * HD + lane;
-#pragma unroll
-            for (int i = 0; i < HD / 64; i++) acc[i] += po[64 * i] * wc;
-        }
-    }
+    if (n_chunks <= 4) merge_row<T, HD, 4>(part_o, part_ml, row0, QR, n_chunks, lane, acc, den);
+    else if (n_chunks <= 16) merge_row<T, HD, 16>(part_o, part_ml, row0, QR, n_chunks, lane, acc, den);
+    else merge_row<T, HD, 32>(part_o, part_ml, row0, QR, n_chunks, lane, acc, den);
     den = wave_sum(den);
     const float inv = den > 0.f ? 1.f / den : 0.f;
 #pragma unroll
@@ -461,7 +509,7 @@ int64_t attention_mfma_ws_bytes(int B, int N, int Hq, int Hkv, int hd, int max_k
     if (B < 1 || N < 1 || Hkv < 1 || Hq % Hkv) return 0;
     AttnPlan p = pick_qw(N, Hq, Hkv) == 2 ? plan_attention<2>(B, N, Hq, Hkv, max_keys) : plan_attention<4>(B, N, Hq, Hkv, max_keys);
     int64_t rows = (int64_t)B * Hkv * p.n_chunks * p.QR;
-    return align_up(rows * hd * 4, 256) + align_up(rows * 2 * 4, 256) + align_up((int64_t)B * Hkv * p.n_chunks * 4, 256);
+    return align_up(rows * hd * 4, 256) + align_up(rows * 2 * 4, 256) + align_up((int64_t)B * Hkv * p.n_chunks * 16, 256);
 }
 
 template <typename T, int HD, int QW>
@@ -472,11 +520,11 @@ static int32_t launch_typed(const fg_kv_cache *kv, int layer, const fg_tree *t, 
     AttnPlan p = plan_attention<QW>(B, N, Hq, Hkv, max_keys);
     int64_t rows = (int64_t)B * Hkv * p.n_chunks * p.QR;
     const int n_items = B * Hkv * p.n_chunks;
-    int64_t need = align_up(rows * HD * 4, 256) + align_up(rows * 2 * 4, 256) + align_up((int64_t)n_items * 4, 256);
+    int64_t need = align_up(rows * HD * 4, 256) + align_up(rows * 2 * 4, 256) + align_up((int64_t)n_items * 16, 256);
     if (!ws || ws_bytes < need) return fail(FG_ERR_CAPACITY, "attention workspace too small (%lld < %lld)", (long long)ws_bytes, (long long)need);
     float *part_o = (float *)ws;
     float *part_ml = (float *)((char *)ws + align_up(rows * HD * 4, 256));
-    int32_t *order = (int32_t *)((char *)part_ml + align_up(rows * 2 * 4, 256));
+    int4 *order = (int4 *)((char *)part_ml + align_up(rows * 2 * 4, 256));
     const float scale = 1.0f / sqrtf((float)HD);
     if (!reuse_order) {   // lengths do not change within a step: the layers after the first reuse the order
         hipLaunchKernelGGL(attn_order_kernel, dim3(1), dim3(1024), 0, st, kv->seq_len, t->slot, kv->n_slots, kv->max_pages_per_seq,
@@ -485,12 +533,12 @@ static int32_t launch_typed(const fg_kv_cache *kv, int layer, const fg_tree *t, 
     }
     dim3 grid((unsigned)((n_items + 7) / 8 * 8 * p.waves));
     hipLaunchKernelGGL((attn_mfma_kernel<T, HD, QW>), grid, dim3(64), 0, st, (const T *)q, (const T *)kv->k_pool,
-                       (const T *)kv->v_pool, kv->page_table, kv->seq_len, t->slot, td.mask, part_o, part_ml, layer, kv->n_pages,
-                       kv->n_slots, kv->max_pages_per_seq, N, t->n_prev, Hq, Hkv, p.QR, p.CK, p.n_chunks, n_items, p.waves,
+                       (const T *)kv->v_pool, kv->page_table, td.mask, part_o, part_ml, layer, kv->n_pages,
+                       kv->max_pages_per_seq, N, t->n_prev, Hq, Hkv, p.QR, p.CK, p.n_chunks, n_items, p.waves,
                        scale, order);
     FG_LAUNCH_CHECK("attn_mfma");
-    hipLaunchKernelGGL((attn_merge_kernel<T, HD>), dim3(B * N, (Hq + 3) / 4), dim3(256), 0, st, part_o, part_ml, kv->seq_len, t->slot,
-                       (T *)out, kv->n_slots, kv->max_pages_per_seq, N, t->n_prev, Hq, Hkv, p.QR, p.CK, p.n_chunks);
+    hipLaunchKernelGGL((attn_merge_kernel<T, HD>), dim3(B * N, (Hq + 3) / 4), dim3(256), 0, st, part_o, part_ml,
+                       (T *)out, N, Hq, Hkv, p.QR, p.n_chunks);
     FG_LAUNCH_CHECK("attn_merge");
     return FG_OK;
 }

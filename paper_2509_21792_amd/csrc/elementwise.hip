@@ -6,10 +6,12 @@
 namespace fg {
 
 // ---- tree preparation ------------------------------------------------------------------------------------
-// For every new node: its position (committed length + depth) and the 64-bit set of its in-round
-// ancestors-or-self.  Parents are clamped so that a malformed tree cannot loop or index out of range.
-__global__ void tree_prep_kernel(const int32_t *slot, const int32_t *parent, const int32_t *seq_len, int B, int N,
-                                 int n_prev, int n_slots, int32_t *pos, uint64_t *mask)
+// For every new node: its position (committed length + depth), the 64-bit set of its in-round
+// ancestors-or-self, and the cache cell it is appended to (the same in every layer).  Parents are clamped so that
+// a malformed tree cannot loop or index out of range.
+__global__ void tree_prep_kernel(const int32_t *slot, const int32_t *parent, const int32_t *seq_len,
+                                 const int32_t *page_table, int B, int N, int n_prev, int n_slots, int max_pages, int n_pages,
+                                 int32_t *pos, uint64_t *mask, int32_t *dest)
 {
     int r = blockIdx.x * blockDim.x + threadIdx.x;
     if (r >= B * N) return;
@@ -24,15 +26,21 @@ __global__ void tree_prep_kernel(const int32_t *slot, const int32_t *parent, con
         u = p;
     }
     int s = min(max(slot[b], 0), n_slots - 1);
-    pos[r] = seq_len[s] + depth;
+    const int L = seq_len[s];
+    pos[r] = L + depth;
     mask[r] = m;
+    const int at = L + n_prev + j;
+    const int page_idx = min(max(at >> 4, 0), max_pages - 1);
+    const int page = min(max(page_table[(size_t)s * max_pages + page_idx], 0), n_pages - 1);
+    dest[r] = page * 16 + (at & 15);
 }
 
-int32_t launch_tree_prep_ex(const fg_tree *t, const int32_t *seq_len, int n_slots, TreeDev td, hipStream_t st)
+int32_t launch_tree_prep_ex(const fg_tree *t, const fg_kv_cache *kv, TreeDev td, hipStream_t st)
 {
     int M = t->B * t->N;
-    hipLaunchKernelGGL(tree_prep_kernel, dim3((M + 127) / 128), dim3(128), 0, st, t->slot, t->parent, seq_len, t->B, t->N,
-                       t->n_prev, n_slots, td.pos, td.mask);
+    hipLaunchKernelGGL(tree_prep_kernel, dim3((M + 127) / 128), dim3(128), 0, st, t->slot, t->parent, kv->seq_len,
+                       kv->page_table, t->B, t->N, t->n_prev, kv->n_slots, kv->max_pages_per_seq, kv->n_pages, td.pos, td.mask,
+                       td.dest);
     FG_LAUNCH_CHECK("tree_prep");
     return FG_OK;
 }
@@ -191,55 +199,50 @@ int32_t launch_add_rmsnorm(int32_t dtype, float *h, const float *partials, int S
 // ---- RoPE + KV append -------------------------------------------------------------------------------------
 // Sums the QKV GEMM's split-K slabs, rotates q and k (rotate-half pairing i, i + hd/2; angles from the table
 // built in double precision at model creation), writes q rows for the attention kernel and the new node's
-// k (token-major) and v (transposed) into its page.  One block per row; a thread owns four consecutive pair
-// indices of one head (or four consecutive v elements), all slab loads independent.
+// k (token-major) and v (transposed) into its cache cell.  A thread owns four consecutive pair indices of one
+// head (or four consecutive v elements), all slab loads independent.  A row is cut over gridDim.y blocks: with few
+// rows one block per row would pull the whole slab sum through a handful of CUs.
 template <typename T>
-__global__ __launch_bounds__(1024) void rope_append_kernel(const float *qkv, int S, int M, const int32_t *slot,
-                                                           const int32_t *pos, const int32_t *seq_len,
-                                                           const int32_t *page_table, T *k_pool, T *v_pool, int layer,
-                                                           int n_pages, int n_slots, int max_pages, int N, int n_prev,
-                                                           int Hq, int Hkv, int hd, const float2 *rope_tab, int max_pos,
-                                                           T *q_out)
+__global__ __launch_bounds__(1024) void rope_append_kernel(const float *qkv, int S, int M, const int32_t *pos,
+                                                           const int32_t *dest, T *k_pool, T *v_pool, int layer,
+                                                           int n_pages, int Hq, int Hkv, int hd, const float2 *rope_tab,
+                                                           int max_pos, T *q_out)
 {
-    const int r = blockIdx.x, b = r / N, j = r % N;
+    const int r = blockIdx.x;
     const int QKVD = (Hq + 2 * Hkv) * hd, half = hd >> 1, quads = half >> 2;
-    const int s = min(max(slot[b], 0), n_slots - 1);
-    const int p = min(max(pos[r], 0), max_pos - 1);
-    const int at = seq_len[s] + n_prev + j;                 // cache slot of this node
-    const int page_idx = min(at >> 4, max_pages - 1);
-    const int page = min(max(page_table[(size_t)s * max_pages + page_idx], 0), n_pages - 1);
-    const int t = at & 15;
+    const int n_rot = (Hq + Hkv) * quads, n_v = Hkv * hd / 4;
+    const int w = blockIdx.y * blockDim.x + threadIdx.x;
+    if (w >= n_rot + n_v) return;
     const size_t slab = (size_t)M * QKVD;
     const float *row = qkv + (size_t)r * QKVD;
     const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
-    const int n_rot = (Hq + Hkv) * quads, n_v = Hkv * hd / 4;
-    for (int w = threadIdx.x; w < n_rot + n_v; w += blockDim.x) {
-        if (w < n_rot) {
-            int head = w / quads, i = (w % quads) * 4;
-            float4 a = slab_sum4(row + head * hd + i, slab, S, zero);
-            float4 bb = slab_sum4(row + head * hd + i + half, slab, S, zero);
-            const float2 *cs = rope_tab + (size_t)p * half + i;
-            float2 c0 = cs[0], c1 = cs[1], c2 = cs[2], c3 = cs[3];
-            float4 x0 = make_float4(a.x * c0.x - bb.x * c0.y, a.y * c1.x - bb.y * c1.y, a.z * c2.x - bb.z * c2.y,
-                                    a.w * c3.x - bb.w * c3.y);
-            float4 x1 = make_float4(bb.x * c0.x + a.x * c0.y, bb.y * c1.x + a.y * c1.y, bb.z * c2.x + a.z * c2.y,
-                                    bb.w * c3.x + a.w * c3.y);
-            if (head < Hq) {
-                T *o = q_out + (size_t)r * Hq * hd + head * hd + i;
-                store4<T>(o, x0);
-                store4<T>(o + half, x1);
-            } else {
-                int hk = head - Hq;
-                T *o = k_pool + ((((size_t)layer * n_pages + page) * Hkv + hk) * 16 + t) * hd + i;
-                store4<T>(o, x0);
-                store4<T>(o + half, x1);
-            }
+    if (w < n_rot) {
+        int head = w / quads, i = (w % quads) * 4;
+        float4 a = slab_sum4(row + head * hd + i, slab, S, zero);
+        float4 bb = slab_sum4(row + head * hd + i + half, slab, S, zero);
+        const int p = min(max(pos[r], 0), max_pos - 1);
+        const float2 *cs = rope_tab + (size_t)p * half + i;
+        float2 c0 = cs[0], c1 = cs[1], c2 = cs[2], c3 = cs[3];
+        float4 x0 = make_float4(a.x * c0.x - bb.x * c0.y, a.y * c1.x - bb.y * c1.y, a.z * c2.x - bb.z * c2.y,
+                                a.w * c3.x - bb.w * c3.y);
+        float4 x1 = make_float4(bb.x * c0.x + a.x * c0.y, bb.y * c1.x + a.y * c1.y, bb.z * c2.x + a.z * c2.y,
+                                bb.w * c3.x + a.w * c3.y);
+        if (head < Hq) {
+            T *o = q_out + (size_t)r * Hq * hd + head * hd + i;
+            store4<T>(o, x0);
+            store4<T>(o + half, x1);
         } else {
-            int e4 = (w - n_rot) * 4, hk = e4 / hd, e = e4 % hd;
-            float4 v = slab_sum4(row + (Hq + Hkv) * hd + e4, slab, S, zero);
-            T *o = v_pool + (((size_t)layer * n_pages + page) * Hkv + hk) * 16 * hd + (size_t)e * 16 + t;
-            o[0] = from_f<T>(v.x); o[16] = from_f<T>(v.y); o[32] = from_f<T>(v.z); o[48] = from_f<T>(v.w);
+            const int cell = dest[r], page = cell >> 4, t = cell & 15, hk = head - Hq;
+            T *o = k_pool + ((((size_t)layer * n_pages + page) * Hkv + hk) * 16 + t) * hd + i;
+            store4<T>(o, x0);
+            store4<T>(o + half, x1);
         }
+    } else {
+        int e4 = (w - n_rot) * 4, hk = e4 / hd, e = e4 % hd;
+        float4 v = slab_sum4(row + (Hq + Hkv) * hd + e4, slab, S, zero);
+        const int cell = dest[r], page = cell >> 4, t = cell & 15;
+        T *o = v_pool + (((size_t)layer * n_pages + page) * Hkv + hk) * 16 * hd + (size_t)e * 16 + t;
+        o[0] = from_f<T>(v.x); o[16] = from_f<T>(v.y); o[32] = from_f<T>(v.z); o[48] = from_f<T>(v.w);
     }
 }
 
@@ -248,11 +251,14 @@ int32_t launch_rope_append(int32_t dtype, const float *qkv_partials, int S, cons
 {
     int M = t->B * t->N;
     const int work = (Hq + kv->n_kv_heads) * (kv->head_dim / 8) + kv->n_kv_heads * kv->head_dim / 4;
-    const int threads = work >= 1024 ? 1024 : (work + 63) / 64 * 64;
-    FG_DISPATCH(dtype, T, hipLaunchKernelGGL(rope_append_kernel<T>, dim3(M), dim3(threads), 0, st, qkv_partials, S, M, t->slot,
-                                             td.pos, kv->seq_len, kv->page_table, (T *)kv->k_pool, (T *)kv->v_pool, layer,
-                                             kv->n_pages, kv->n_slots, kv->max_pages_per_seq, t->N, t->n_prev, Hq,
-                                             kv->n_kv_heads, kv->head_dim, (const float2 *)rope_tab, max_pos, (T *)q_out));
+    // about 512 blocks in all when there are few rows, whole rows per block when there are many
+    int threads = 1024;
+    while (threads > 64 && (int64_t)M * ((work + threads - 1) / threads) < 512) threads >>= 1;
+    if (threads > (work + 63) / 64 * 64) threads = (work + 63) / 64 * 64;
+    FG_DISPATCH(dtype, T, hipLaunchKernelGGL(rope_append_kernel<T>, dim3(M, (work + threads - 1) / threads), dim3(threads), 0, st,
+                                             qkv_partials, S, M, td.pos, td.dest, (T *)kv->k_pool, (T *)kv->v_pool, layer,
+                                             kv->n_pages, Hq, kv->n_kv_heads, kv->head_dim, (const float2 *)rope_tab, max_pos,
+                                             (T *)q_out));
     FG_LAUNCH_CHECK("rope_append");
     return FG_OK;
 }

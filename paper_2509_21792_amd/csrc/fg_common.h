@@ -89,6 +89,7 @@ __device__ __forceinline__ float gumbel_from_key(uint64_t key, uint64_t v) { ret
 struct TreeDev {             // per-call derived tree data in the workspace
     int32_t *pos;            // [B*N] position of each new node
     uint64_t *mask;          // [B*N] in-round ancestors-or-self of each new node (bit i = in-round node i)
+    int32_t *dest;           // [B*N] cache cell of each new node: page * 16 + position in the page (same in every layer)
 };
 
 int32_t launch_gemm_mfma(int32_t dtype, const void *x, const void *wp, void *out, int M, int N, int K, int epilogue,
