@@ -20,6 +20,14 @@
 
 namespace fg {
 
+// W is read exactly once per GEMM by this kernel (one row block): a streaming load that does not displace the
+// activations and slabs in the caches.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream(const uint4 *p)
+{
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
 
 template <typename T, int MT, int NT, int WM, int WN, int EPI>
 __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(const T *__restrict__ X, const uint4 *__restrict__ Wp,
@@ -89,7 +97,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(const T *__restr
 #pragma unroll
         for (int j = 0; j < NT; j++)
 #pragma unroll
-            for (int kt = 0; kt < KT; kt++) w[j][kt].u = wband[j][(size_t)(c_begin * KT + kt) * 64];
+            for (int kt = 0; kt < KT; kt++) w[j][kt].u = load_stream(wband[j] + (size_t)(c_begin * KT + kt) * 64);
         FG_STORE_X(0);
         __syncthreads();
         // One chunk per iteration.  Latency cover:
@@ -118,7 +126,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(const T *__restr
 #pragma unroll
                     for (int j = 0; j < NT; j++) acc[i][j] = mfma32<T>(xa[i], w[j][kt], acc[i][j]);
 #pragma unroll
-                for (int j = 0; j < NT; j++) w[j][kt].u = wband[j][(size_t)(nxt * KT + kt) * 64];
+                for (int j = 0; j < NT; j++) w[j][kt].u = load_stream(wband[j] + (size_t)(nxt * KT + kt) * 64);
                 __builtin_amdgcn_sched_barrier(0);
                 if (kt + 2 < KT) {
 #pragma unroll
@@ -130,7 +138,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(const T *__restr
 #pragma unroll
                     for (int j = 0; j < NT; j++) acc[i][j] = mfma32<T>(xb[i], w[j][kt + 1], acc[i][j]);
 #pragma unroll
-                for (int j = 0; j < NT; j++) w[j][kt + 1].u = wband[j][(size_t)(nxt * KT + kt + 1) * 64];
+                for (int j = 0; j < NT; j++) w[j][kt + 1].u = load_stream(wband[j] + (size_t)(nxt * KT + kt + 1) * 64);
                 __builtin_amdgcn_sched_barrier(0);
             }
             FG_STORE_X(buf ^ 1);
