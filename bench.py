@@ -372,7 +372,7 @@ def main():
 
     # dominant kernel: the gate/up GEMM (largest share of both the weight bytes and the flops)
     n_out, n_in = 2 * model["d_ffn"], model["d_model"]
-    epi = 1 if (M > 256 or (M > 128 and n_out >= 16384)) else 0     # the library fuses SwiGLU where the pipelined kernel runs
+    epi = 1 if (M <= 64 or M > 256 or (M > 128 and n_out >= 16384)) else 0     # the library fuses SwiGLU in the few-row and the pipelined kernels
     t_verify, _ = time_steps(torch, wl.verify_only, max(3, args.steps // 2), args.warmup)
     t_draft = time_steps(torch, wl.draft, max(3, args.steps // 2), 2)[0] if wl.draft_ready else 0.0
     fg.fg_profile_gemm(True, n_out, n_in, epi, max_launches=(args.steps + args.warmup + 1) * model["n_layers"], rows=M)
@@ -395,7 +395,8 @@ def main():
     roof["traffic"] = MEASURED_TRAFFIC.get((wl.name, M))
     roof["algorithmic"] = gemm_flops if compute_bound else gemm_bytes
     roof["algorithmic_bytes"] = gemm_bytes
-    roof["kernel"] = f"{'gemm_mfma_big_kernel' if M > 256 else 'gemm_mfma_kernel'} (gate/up, M={M}, n_out={n_out}, n_in={n_in}, epilogue={'swiglu' if epi else 'fp32 split-K slabs'})"
+    kname = "gemm_mfma_big_kernel" if (M > 256 or (M > 128 and n_out >= 16384)) else ("gemm_mfma_skinny_kernel" if M <= 64 else "gemm_mfma_kernel")
+    roof["kernel"] = f"{kname} (gate/up, M={M}, n_out={n_out}, n_in={n_in}, epilogue={'swiglu' if epi else 'fp32 split-K slabs'})"
     roof["launches"] = k_cnt
     roof["avg_us"] = k_avg * 1e6
 

@@ -237,8 +237,34 @@ int gemm_mfma_big_split_for(int M, int N, int K);
 // LM head), where a 256-row tile half full still beats streaming the weights through eight row tiles per wave.
 bool gemm_mfma_uses_big(int M, int N) { return big_variant() && (M > 256 || (M > 128 && N >= 16384)); }
 
+// At most 64 rows: the few-row kernel (gemm_mfma_skinny.hip), which splits k inside the block.  Measured on the
+// 7B-class shapes against the streaming kernel: gate/up with its SwiGLU fused 46.6 / 49.5 / 57.7 us at 8 / 32 / 64
+// rows against 48.8 / 56.8 / 53.0 plus a 4.4 - 5.5 us SwiGLU pass over the slabs; down 22.0 / 26.1 us at 8 / 48
+// rows with 4 slabs against 22.4 / 33.7 with 16; the LM head 167 against 177 us at 8 rows, level at 32 and behind
+// above (220 against 200 us at 48), so the widest outputs stay with the streaming kernel from 33 rows on.
+// FG_GEMM_FEW=0 switches it off for comparison.
+int32_t launch_gemm_mfma_skinny(int32_t dtype, const void *x, const void *wp, void *out, int M, int N, int K, int epilogue,
+                                int split, hipStream_t st);
+int gemm_mfma_skinny_split_for(int M, int N, int K);
+static int few_variant()
+{
+    static int v = -1;
+    if (v < 0) {
+        const char *e = getenv("FG_GEMM_FEW");
+        v = e ? atoi(e) : 1;
+    }
+    return v;
+}
+bool gemm_mfma_uses_few(int M, int N, int epilogue)
+{
+    return few_variant() && M <= 64 && (epilogue == 1 || N < 16384 || M <= 32);
+}
+// Whether the gate/up GEMM of M rows applies SwiGLU in its own epilogue (no slabs, no separate pass).
+bool gemm_mfma_fuses_swiglu(int M, int N) { return gemm_mfma_uses_big(M, N) || gemm_mfma_uses_few(M, N, 1); }
+
 int gemm_mfma_split_for(int M, int N, int K)
 {
+    if (gemm_mfma_uses_few(M, N, 0)) return gemm_mfma_skinny_split_for(M, N, K);
     if (gemm_mfma_uses_big(M, N)) return gemm_mfma_big_split_for(M, N, K);
     return choose_split(M, N, K, 256, 256);
 }
@@ -281,7 +307,8 @@ int32_t launch_gemm_mfma(int32_t dtype, const void *x, const void *wp, void *out
                       g_prof.used < g_prof.start.size();
     if (prof) (void)hipEventRecord(g_prof.start[g_prof.used], st);
     int32_t rc;
-    if (gemm_mfma_uses_big(M, N)) rc = launch_gemm_mfma_big(dtype, x, wp, out, M, N, K, epilogue, split, raster_enabled(), st);
+    if (gemm_mfma_uses_few(M, N, epilogue)) rc = launch_gemm_mfma_skinny(dtype, x, wp, out, M, N, K, epilogue, split, st);
+    else if (gemm_mfma_uses_big(M, N)) rc = launch_gemm_mfma_big(dtype, x, wp, out, M, N, K, epilogue, split, raster_enabled(), st);
     else rc = dtype == FG_BF16 ? launch_gemm_typed<bf16_t>(x, wp, out, M, N, K, epilogue, split, st)
                                : launch_gemm_typed<f16_t>(x, wp, out, M, N, K, epilogue, split, st);
     if (prof) (void)hipEventRecord(g_prof.stop[g_prof.used++], st);
