@@ -14,6 +14,8 @@
 // load issued before it and flatten the ring.  At the end the four partial accumulators meet in LDS, tile by tile:
 //   EPI 0  fp32 partial slab of the block's k split (narrow outputs still want a few splits across blocks),
 //   EPI 1  W is the gate/up interleaved matrix: silu(gate) * up, stored as T.
+// Measured alternatives on the 7B-class gate/up at 8 rows (46.2 us as built): four bands per block 54.7 us (too few
+// blocks), a ring of eight chunks 47.3 us (no gain, and two row tiles then spill).
 #include "fg_common.h"
 #include "gemm_mfma.h"
 
@@ -30,11 +32,10 @@ __device__ __forceinline__ uint4 sk_load_stream(const uint4 *p)
 constexpr int SK_DEPTH = 4;   // chunks in flight per wave (even: the LDS buffer of a chunk is its ring slot & 1)
 constexpr int SK_NT = 2;      // 32-column bands per block
 
-template <typename T, int MT, int EPI>
+template <typename T, int MT, int EPI, int NT, int D>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 1 ? 4 : 3))) void gemm_mfma_skinny_kernel(const T *__restrict__ X, const uint4 *__restrict__ Wp,
                                                                 void *__restrict__ out, int M, int N, int K, int chunks_per_split)
 {
-    constexpr int NT = SK_NT, D = SK_DEPTH;
     constexpr int BM = MT * 32;
     constexpr int XLOADS = BM * 8 / 256;   // 16-byte pieces of X per thread per chunk
     static_assert(BM * 8 % 256 == 0, "X staging must divide evenly");
@@ -166,10 +167,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 1 ? 4
                         const int nt = ntile0 + j;
                         if (nt < n_tiles) reinterpret_cast<float *>(out)[((size_t)bz * M + m) * N + nt * 32 + (lane & 31)] = s[j][k];
                     }
-                } else if (ntile0 + 1 < n_tiles) {
+                } else {
                     // tiles alternate gate / up for the same 32 features
-                    const int f = (ntile0 >> 1) * 32 + (lane & 31);
-                    reinterpret_cast<T *>(out)[(size_t)m * F + f] = from_f<T>(s[0][k] / (1.f + __expf(-s[0][k])) * s[1][k]);
+#pragma unroll
+                    for (int j = 0; j + 1 < NT; j += 2) {
+                        if (ntile0 + j + 1 >= n_tiles) continue;
+                        const int f = ((ntile0 + j) >> 1) * 32 + (lane & 31);
+                        reinterpret_cast<T *>(out)[(size_t)m * F + f] = from_f<T>(s[j][k] / (1.f + __expf(-s[j][k])) * s[j + 1][k]);
+                    }
                 }
             }
         }
@@ -197,25 +202,25 @@ int gemm_mfma_skinny_split_for(int M, int N, int K)
     return best;
 }
 
-template <typename T, int MT>
+template <typename T, int MT, int NT, int D = SK_DEPTH>
 static void launch_skinny_mt(const void *x, const void *wp, void *out, int M, int N, int K, int epilogue, int split, hipStream_t st)
 {
     // chunks per split in whole rounds of the ring (a split past the end of k then writes a slab of zeros)
-    const int chunks = K / 64, cps = ((chunks + split - 1) / split + SK_DEPTH - 1) / SK_DEPTH * SK_DEPTH;
-    dim3 grid((N / 32 + SK_NT - 1) / SK_NT, 1, split);
+    const int chunks = K / 64, cps = ((chunks + split - 1) / split + D - 1) / D * D;
+    dim3 grid((N / 32 + NT - 1) / NT, 1, split);
     if (epilogue == 0)
-        hipLaunchKernelGGL((gemm_mfma_skinny_kernel<T, MT, 0>), grid, dim3(256), 0, st, reinterpret_cast<const T *>(x),
+        hipLaunchKernelGGL((gemm_mfma_skinny_kernel<T, MT, 0, NT, D>), grid, dim3(256), 0, st, reinterpret_cast<const T *>(x),
                            reinterpret_cast<const uint4 *>(wp), out, M, N, K, cps);
     else
-        hipLaunchKernelGGL((gemm_mfma_skinny_kernel<T, MT, 1>), grid, dim3(256), 0, st, reinterpret_cast<const T *>(x),
+        hipLaunchKernelGGL((gemm_mfma_skinny_kernel<T, MT, 1, NT, D>), grid, dim3(256), 0, st, reinterpret_cast<const T *>(x),
                            reinterpret_cast<const uint4 *>(wp), out, M, N, K, cps);
 }
 
 template <typename T>
 static void launch_skinny_typed(const void *x, const void *wp, void *out, int M, int N, int K, int epilogue, int split, hipStream_t st)
 {
-    if (M <= 32) launch_skinny_mt<T, 1>(x, wp, out, M, N, K, epilogue, split, st);
-    else launch_skinny_mt<T, 2>(x, wp, out, M, N, K, epilogue, split, st);
+    if (M <= 32) launch_skinny_mt<T, 1, SK_NT>(x, wp, out, M, N, K, epilogue, split, st);
+    else launch_skinny_mt<T, 2, SK_NT>(x, wp, out, M, N, K, epilogue, split, st);
 }
 
 // Shapes were validated by the caller (launch_gemm_mfma); M <= 64.

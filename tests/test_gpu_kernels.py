@@ -63,6 +63,34 @@ def test_gemm_16bit_many_rows_every_k_tail(fg, chunks):
         assert used == 1 and err <= 2e-5 * ref.abs().max().item() + 1e-4, (dtype, err)
 
 
+@pytest.mark.parametrize("chunks", [1, 2, 3, 4, 5, 7, 8, 9, 13, 18])
+def test_gemm_16bit_few_rows_every_k_tail(fg, chunks):
+    """At most 64 rows takes the few-row kernel (k split inside the block, rounds of four 64-wide k chunks): every
+    tail length of the last round, one and two row tiles with ragged ends, an odd number of column bands, requested
+    splits that leave the last split short or empty, and the fused SwiGLU epilogue."""
+    K = 64 * chunks
+    print(f"gemm few rows chunks={chunks}", flush=True)
+    g = torch.Generator().manual_seed(100 + chunks)
+    for dtype, M in (("bf16", 1), ("fp16", 31), ("bf16", 33), ("fp16", 64)):
+        N = 96 + 64 * (M % 3)          # 3, 5 or 7 bands of 32 columns
+        x, w = bf16_randn((M, K), g, dt=TD[dtype]), bf16_randn((N, K), g, 0.05, dt=TD[dtype])
+        ref = x.double() @ w.double().T
+        wp = fg.fg_pack_weight(CODES[dtype], w.cuda())
+        for split in (0, 1, 2, 3, 5):
+            out, used = fg.fg_gemm(CODES[dtype], x.cuda(), wp, N, epilogue=0, split_k=split)
+            torch.cuda.synchronize()
+            err = (out.double().cpu() - ref).abs().max().item()
+            assert err <= 2e-5 * ref.abs().max().item() + 1e-4, (dtype, M, split, used, err)
+        F = 64
+        wg, wu = bf16_randn((F, K), g, 0.05, dt=TD[dtype]), bf16_randn((F, K), g, 0.05, dt=TD[dtype])
+        act = torch.nn.functional.silu(x.double() @ wg.double().T) * (x.double() @ wu.double().T)
+        wp2 = fg.fg_pack_weight(CODES[dtype], wg.cuda(), wu.cuda())
+        out, _ = fg.fg_gemm(CODES[dtype], x.cuda(), wp2, 2 * F, epilogue=1)
+        torch.cuda.synchronize()
+        err = (out.double().cpu() - act).abs()
+        assert (err <= 2 ** -8 * act.abs() + 1e-3).all(), (dtype, M, err.max().item())
+
+
 @pytest.mark.parametrize("M,F,K", [(8, 704, 256), (33, 1024, 128), (200, 18944, 3584), (300, 2048, 512), (1000, 1024, 256)])
 @pytest.mark.parametrize("dtype", ["bf16", "fp16"])
 def test_gemm_16bit_swiglu_epilogue(fg, M, F, K, dtype):
