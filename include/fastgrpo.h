@@ -76,9 +76,17 @@ typedef struct {
 } fg_weights;
 
 /*
- * Paged KV cache, caller-owned.  Page p of layer l, kv head h:
- *   k_pool[((l * n_pages + p) * n_kv_heads + h) * page_size * head_dim + t * head_dim + e]   (token-major)
- *   v_pool[((l * n_pages + p) * n_kv_heads + h) * page_size * head_dim + e * page_size + t]   (transposed)
+ * Paged KV cache, caller-owned.  Page p of layer l, kv head h starts at element
+ * ((l * n_pages + p) * n_kv_heads + h) * page_size * head_dim of either pool; within it, token t, dim e is at
+ *   v_pool: e * page_size + t                                                     (transposed)
+ *   k_pool: t * head_dim + e                                                      (token-major: FG_F32, or
+ *                                                                                  head_dim % 32 != 0)
+ *   k_pool: (((r / 8) * 4 + g) * 16 + t) * 8 + r % 8, g = e / (head_dim / 4),     (16-bit, head_dim % 32 == 0:
+ *           r = e % (head_dim / 4)                                                 MFMA operand order, so that the
+ *                                                                                  attention kernel reads 1 KiB
+ *                                                                                  runs)
+ * The library fills the cache itself (fg_spec_verify / fg_draft_step append, fg_kv_compact moves); a caller only
+ * needs the formulas to plant or inspect contents.
  * Token t of a sequence in cache slot s is entry t % page_size of page page_table[s][t / page_size].
  * page_size must be 16.  seq_len[s] is the committed length; only fg_kv_compact changes it.
  */

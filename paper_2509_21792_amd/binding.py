@@ -234,18 +234,35 @@ class KVCache:
         pages = self.page_table[slot, (t // self.page_size)].long()
         return pages, (t % self.page_size)
 
+    def _k_offsets(self):
+        """[page_size, hd] element offsets of (token, dim) inside one (page, kv head) block of k_pool: MFMA operand
+        order for 16-bit caches with head_dim % 32 == 0, token-major otherwise (see fastgrpo.h)."""
+        hd, dev = self.cfg["head_dim"], self.k_pool.device
+        t = torch.arange(self.page_size, device=dev)[:, None]
+        e = torch.arange(hd, device=dev)[None, :]
+        if self.dtype in (FG_BF16, FG_F16) and hd % 32 == 0 and self.page_size == 16:
+            q = hd // 4
+            g, r = e // q, e % q
+            return (((r // 8) * 4 + g) * 16 + t) * 8 + r % 8
+        return t * hd + e
+
     def write_prefix(self, slot, k, v):
         """Set-up helper: k, v [n_layers, L, Hkv, hd] become positions 0..L-1 of `slot`; seq_len[slot] = L."""
         L = k.shape[1]
         pages, off = self._where(slot, L)
-        self.k_pool[:, pages, :, off, :] = k.to(self.k_pool.dtype).permute(1, 0, 2, 3)
+        nl, n_pages, Hkv = self.k_pool.shape[:3]
+        flat = self.k_pool.view(nl, n_pages, Hkv, -1)
+        # index tensors [L, 1] and [L, hd] around a slice: the result is laid out [L, hd, n_layers, Hkv]
+        flat[:, pages[:, None], :, self._k_offsets()[off]] = k.to(self.k_pool.dtype).permute(1, 3, 0, 2)
         self.v_pool[:, pages, :, :, off] = v.to(self.v_pool.dtype).permute(1, 0, 2, 3)
         self.seq_len[slot] = L
 
     def read(self, slot, L):
         """Test helper: positions 0..L-1 of `slot` as contiguous k, v [n_layers, L, Hkv, hd]."""
         pages, off = self._where(slot, L)
-        k = self.k_pool[:, pages, :, off, :].permute(1, 0, 2, 3).contiguous()
+        nl, n_pages, Hkv = self.k_pool.shape[:3]
+        flat = self.k_pool.view(nl, n_pages, Hkv, -1)
+        k = flat[:, pages[:, None], :, self._k_offsets()[off]].permute(2, 0, 3, 1).contiguous()
         v = self.v_pool[:, pages, :, :, off].permute(1, 0, 2, 3).contiguous()
         return k, v
 

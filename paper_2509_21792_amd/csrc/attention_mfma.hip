@@ -4,7 +4,7 @@
 // G = Hq / Hkv query heads of every new node, G * N rows -- ride the same pass over K and V, so each K/V byte
 // is fetched from HBM once per (sequence, kv head) whatever N is.  A wave owns QW tiles of 16 query rows and
 // walks the chunk 32 key positions (two 16-token pages) at a time:
-//   S^T = K . Q^T        v_mfma_f32_16x16x32, A = K page rows straight from global memory (token-major pages),
+//   S^T = K . Q^T        v_mfma_f32_16x16x32, A = K fragments straight from global memory (pages in fragment order),
 //                        B = Q fragments held in registers for the whole pass;
 //   online softmax       per query column; lanes l, l+16, l+32, l+48 hold the same column, 4 keys each;
 //   O^T += V^T . P^T     A = V^T fragments straight from global memory (pages store V transposed, so the 4
@@ -120,7 +120,27 @@ static int pick_qw(int N, int Hq, int Hkv)
     return ((Hq / Hkv) * N + 15) / 16 <= 2 ? 2 : 4;
 }
 
-template <typename T, int HD, int QW>
+// K / V loads.  Every cache line of K (pages in fragment order) and of V^T is touched by exactly one load
+// instruction of a wave.  When an item has a single wave (STREAM) its K / V are read once per launch and the
+// loads are non-temporal: measured on the 7B-class cache at B = 256, 327 -> 288 us per layer at N = 8 and
+// 283 -> 242 at N = 1.  Items shared by two or three waves keep ordinary loads, so that the later waves hit in L2
+// (with streaming loads 105 -> 108 us at B = 64, N = 24).
+typedef uint32_t attn_u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t attn_u32x2_t __attribute__((ext_vector_type(2)));
+template <bool STREAM, typename T> __device__ __forceinline__ uint4 load16(const T *p)
+{
+    if (!STREAM) return *reinterpret_cast<const uint4 *>(p);
+    const attn_u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const attn_u32x4_t *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+template <bool STREAM, typename T> __device__ __forceinline__ uint2 load8(const T *p)
+{
+    if (!STREAM) return *reinterpret_cast<const uint2 *>(p);
+    const attn_u32x2_t v = __builtin_nontemporal_load(reinterpret_cast<const attn_u32x2_t *>(p));
+    return make_uint2(v.x, v.y);
+}
+
+template <typename T, int HD, int QW, bool STREAM>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(QW == 2 ? 2 : 1, QW == 2 ? 2 : 1))) void attn_mfma_kernel(const T *__restrict__ q, const T *__restrict__ k_pool,
                                                          const T *__restrict__ v_pool, const int32_t *__restrict__ page_table,
                                                          const uint64_t *__restrict__ mask, float *__restrict__ part_o,
@@ -215,11 +235,11 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(QW == 2 ? 2 
         for (int kt = 0; kt < 2; kt++)
 #pragma unroll
             for (int kk = 0; kk < KK; kk++)
-                kf[kt][kk].u = *reinterpret_cast<const uint4 *>(kb[kt] + (size_t)c * HD + grp * (HD / 4) + kk * 8);
+                kf[kt][kk].u = load16<STREAM>(kb[kt] + kk * 512 + lane * 8);   // fragment kk of the page: 1 KiB, contiguous
 #pragma unroll
         for (int h = 0; h < HT; h++) {
-            vf[h].u2[0] = *reinterpret_cast<const uint2 *>(vb[0] + (size_t)(h * 16 + c) * 16 + grp * 4);
-            vf[h].u2[1] = *reinterpret_cast<const uint2 *>(vb[1] + (size_t)(h * 16 + c) * 16 + grp * 4);
+            vf[h].u2[0] = load8<STREAM>(vb[0] + (size_t)(h * 16 + c) * 16 + grp * 4);
+            vf[h].u2[1] = load8<STREAM>(vb[1] + (size_t)(h * 16 + c) * 16 + grp * 4);
         }
     };
     auto used = [&](int w) { return (qt0 + w) * 16 < rows; };   // wave-uniform: tiles past the last query row idle
@@ -532,10 +552,14 @@ static int32_t launch_typed(const fg_kv_cache *kv, int layer, const fg_tree *t, 
         FG_LAUNCH_CHECK("attn_order");
     }
     dim3 grid((unsigned)((n_items + 7) / 8 * 8 * p.waves));
-    hipLaunchKernelGGL((attn_mfma_kernel<T, HD, QW>), grid, dim3(64), 0, st, (const T *)q, (const T *)kv->k_pool,
-                       (const T *)kv->v_pool, kv->page_table, td.mask, part_o, part_ml, layer, kv->n_pages,
-                       kv->max_pages_per_seq, N, t->n_prev, Hq, Hkv, p.QR, p.CK, p.n_chunks, n_items, p.waves,
-                       scale, order);
+#define FG_ATTN_LAUNCH(STREAM)                                                                                      \
+    hipLaunchKernelGGL((attn_mfma_kernel<T, HD, QW, STREAM>), grid, dim3(64), 0, st, (const T *)q, (const T *)kv->k_pool, \
+                       (const T *)kv->v_pool, kv->page_table, td.mask, part_o, part_ml, layer, kv->n_pages,            \
+                       kv->max_pages_per_seq, N, t->n_prev, Hq, Hkv, p.QR, p.CK, p.n_chunks, n_items, p.waves, scale,  \
+                       order)
+    if (p.waves == 1) FG_ATTN_LAUNCH(true);
+    else FG_ATTN_LAUNCH(false);
+#undef FG_ATTN_LAUNCH
     FG_LAUNCH_CHECK("attn_mfma");
     hipLaunchKernelGGL((attn_merge_kernel<T, HD>), dim3(B * N, (Hq + 3) / 4), dim3(256), 0, st, part_o, part_ml,
                        (T *)out, N, Hq, Hkv, p.QR, p.n_chunks);

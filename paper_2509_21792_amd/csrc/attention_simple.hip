@@ -11,7 +11,7 @@ __global__ __launch_bounds__(64) void attn_simple_kernel(const T *q, T *out, con
                                                          const int32_t *page_table, const int32_t *seq_len,
                                                          const int32_t *slot, const uint64_t *mask, int layer, int n_pages,
                                                          int n_slots, int max_pages, int N, int n_prev, int Hq, int Hkv,
-                                                         int hd, int max_keys, float scale)
+                                                         int hd, int max_keys, float scale, int k_frag)
 {
     extern __shared__ float sm[];  // [max_keys] scores / probabilities, then [hd] the query
     const int r = blockIdx.x, hq = blockIdx.y, lane = threadIdx.x;
@@ -31,9 +31,9 @@ __global__ __launch_bounds__(64) void attn_simple_kernel(const T *q, T *out, con
         float sc = -INFINITY;
         if (valid) {
             int page = min(max(page_table[(size_t)s * max_pages + (t >> 4)], 0), n_pages - 1);
-            const T *kr = k_pool + ((((size_t)layer * n_pages + page) * Hkv + hk) * 16 + (t & 15)) * hd;
+            const T *kr = k_pool + (((size_t)layer * n_pages + page) * Hkv + hk) * 16 * hd;
             float dot = 0.f;
-            for (int e = 0; e < hd; e++) dot += qs[e] * to_f<T>(kr[e]);
+            for (int e = 0; e < hd; e++) dot += qs[e] * to_f<T>(kr[k_page_offset(k_frag, hd, t & 15, e)]);
             sc = dot * scale;
         }
         sm[t] = sc;
@@ -73,7 +73,8 @@ int32_t launch_attention_simple(const fg_kv_cache *kv, int layer, const fg_tree 
     FG_DISPATCH(kv->dtype, T, hipLaunchKernelGGL(attn_simple_kernel<T>, grid, dim3(64), lds, st, (const T *)q, (T *)out,
                                                  (const T *)kv->k_pool, (const T *)kv->v_pool, kv->page_table, kv->seq_len,
                                                  t->slot, td.mask, layer, kv->n_pages, kv->n_slots, kv->max_pages_per_seq,
-                                                 t->N, t->n_prev, Hq, kv->n_kv_heads, hd, max_keys, scale));
+                                                 t->N, t->n_prev, Hq, kv->n_kv_heads, hd, max_keys, scale,
+                                                 (int)k_fragment_major(kv->dtype, hd, kv->page_size)));
     FG_LAUNCH_CHECK("attn_simple");
     return FG_OK;
 }

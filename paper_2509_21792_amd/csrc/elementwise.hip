@@ -199,14 +199,14 @@ int32_t launch_add_rmsnorm(int32_t dtype, float *h, const float *partials, int S
 // ---- RoPE + KV append -------------------------------------------------------------------------------------
 // Sums the QKV GEMM's split-K slabs, rotates q and k (rotate-half pairing i, i + hd/2; angles from the table
 // built in double precision at model creation), writes q rows for the attention kernel and the new node's
-// k (token-major) and v (transposed) into its cache cell.  A thread owns four consecutive pair indices of one
+// k (in the cache's K page layout) and v (transposed) into its cache cell.  A thread owns four consecutive pair indices of one
 // head (or four consecutive v elements), all slab loads independent.  A row is cut over gridDim.y blocks: with few
 // rows one block per row would pull the whole slab sum through a handful of CUs.
 template <typename T>
 __global__ __launch_bounds__(1024) void rope_append_kernel(const float *qkv, int S, int M, const int32_t *pos,
                                                            const int32_t *dest, T *k_pool, T *v_pool, int layer,
                                                            int n_pages, int Hq, int Hkv, int hd, const float2 *rope_tab,
-                                                           int max_pos, T *q_out)
+                                                           int max_pos, T *q_out, int k_frag)
 {
     const int r = blockIdx.x;
     const int QKVD = (Hq + 2 * Hkv) * hd, half = hd >> 1, quads = half >> 2;
@@ -233,9 +233,9 @@ __global__ __launch_bounds__(1024) void rope_append_kernel(const float *qkv, int
             store4<T>(o + half, x1);
         } else {
             const int cell = dest[r], page = cell >> 4, t = cell & 15, hk = head - Hq;
-            T *o = k_pool + ((((size_t)layer * n_pages + page) * Hkv + hk) * 16 + t) * hd + i;
-            store4<T>(o, x0);
-            store4<T>(o + half, x1);
+            T *o = k_pool + (((size_t)layer * n_pages + page) * Hkv + hk) * 16 * hd;
+            store4<T>(o + k_page_offset(k_frag, hd, t, i), x0);
+            store4<T>(o + k_page_offset(k_frag, hd, t, i + half), x1);
         }
     } else {
         int e4 = (w - n_rot) * 4, hk = e4 / hd, e = e4 % hd;
@@ -258,7 +258,7 @@ int32_t launch_rope_append(int32_t dtype, const float *qkv_partials, int S, cons
     FG_DISPATCH(dtype, T, hipLaunchKernelGGL(rope_append_kernel<T>, dim3(M, (work + threads - 1) / threads), dim3(threads), 0, st,
                                              qkv_partials, S, M, td.pos, td.dest, (T *)kv->k_pool, (T *)kv->v_pool, layer,
                                              kv->n_pages, Hq, kv->n_kv_heads, kv->head_dim, (const float2 *)rope_tab, max_pos,
-                                             (T *)q_out));
+                                             (T *)q_out, (int)k_fragment_major(kv->dtype, kv->head_dim, kv->page_size)));
     FG_LAUNCH_CHECK("rope_append");
     return FG_OK;
 }

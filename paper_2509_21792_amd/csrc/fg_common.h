@@ -46,6 +46,22 @@ static inline size_t dtype_size(int32_t dtype) { return dtype == FG_F32 ? 4 : 2;
 static inline bool dtype_ok(int32_t dtype) { return dtype == FG_F32 || dtype == FG_BF16 || dtype == FG_F16; }
 static inline bool is16(int32_t dtype) { return dtype == FG_BF16 || dtype == FG_F16; }
 
+// K page layout of one (layer, page, kv head): page_size x head_dim elements.  16-bit caches with 16-token pages
+// and head_dim a multiple of 32 keep a page in MFMA operand order -- head_dim / 32 fragments of 64 x 8 elements,
+// fragment kk = [lane = grp * 16 + token][8] holding dims grp * (head_dim / 4) + kk * 8 .. + 7 -- so that the
+// attention kernel fetches a fragment as one contiguous 1 KiB; everything else is token-major [token][dim].
+// Four consecutive dims that start at a multiple of four are contiguous in both layouts.
+static inline bool k_fragment_major(int32_t dtype, int head_dim, int page_size)
+{
+    return is16(dtype) && page_size == 16 && head_dim % 32 == 0;
+}
+__host__ __device__ __forceinline__ int k_page_offset(bool fragment_major, int head_dim, int t, int e)
+{
+    if (!fragment_major) return t * head_dim + e;
+    const int q = head_dim >> 2, grp = e / q, r = e - grp * q;
+    return (((r >> 3) * 4 + grp) * 16 + t) * 8 + (r & 7);
+}
+
 // run a statement with T bound to the element type of `dtype`
 #define FG_DISPATCH(dtype, T, ...)                                       \
     do {                                                                 \

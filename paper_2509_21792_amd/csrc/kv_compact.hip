@@ -21,7 +21,7 @@ __device__ __forceinline__ bool path_ok(const int32_t *p, int a, int N)
 template <typename T>
 __global__ void kv_compact_kernel(T *k_pool, T *v_pool, const int32_t *page_table, const int32_t *seq_len,
                                   const int32_t *slot, const int32_t *accept_len, const int32_t *path, int N, int n_pages,
-                                  int n_slots, int max_pages, int Hkv, int hd)
+                                  int n_slots, int max_pages, int Hkv, int hd, int k_frag)
 {
     const int b = blockIdx.x, lh = blockIdx.y;  // lh = layer * Hkv + head
     const int layer = lh / Hkv, hk = lh % Hkv;
@@ -39,7 +39,7 @@ __global__ void kv_compact_kernel(T *k_pool, T *v_pool, const int32_t *page_tabl
             int pd = min(max(page_table[(size_t)s * max_pages + (dst >> 4)], 0), n_pages - 1);
             size_t bs = (((size_t)layer * n_pages + ps) * Hkv + hk) * 16 * hd;
             size_t bd = (((size_t)layer * n_pages + pd) * Hkv + hk) * 16 * hd;
-            k_pool[bd + (size_t)(dst & 15) * hd + e] = k_pool[bs + (size_t)(src & 15) * hd + e];
+            k_pool[bd + k_page_offset(k_frag, hd, dst & 15, e)] = k_pool[bs + k_page_offset(k_frag, hd, src & 15, e)];
             v_pool[bd + (size_t)e * 16 + (dst & 15)] = v_pool[bs + (size_t)e * 16 + (src & 15)];
         }
     }
@@ -77,11 +77,11 @@ int32_t launch_kv_compact(fg_kv_cache *kv, const int32_t *slot, const int32_t *a
     if (kv->dtype == FG_F32)
         hipLaunchKernelGGL(kv_compact_kernel<float>, grid, dim3(threads), 0, st, (float *)kv->k_pool, (float *)kv->v_pool,
                            kv->page_table, kv->seq_len, slot, accept_len, path, N, kv->n_pages, kv->n_slots,
-                           kv->max_pages_per_seq, kv->n_kv_heads, kv->head_dim);
+                           kv->max_pages_per_seq, kv->n_kv_heads, kv->head_dim, (int)k_fragment_major(kv->dtype, kv->head_dim, kv->page_size));
     else
         hipLaunchKernelGGL(kv_compact_kernel<uint16_t>, grid, dim3(threads), 0, st, (uint16_t *)kv->k_pool,
                            (uint16_t *)kv->v_pool, kv->page_table, kv->seq_len, slot, accept_len, path, N, kv->n_pages,
-                           kv->n_slots, kv->max_pages_per_seq, kv->n_kv_heads, kv->head_dim);
+                           kv->n_slots, kv->max_pages_per_seq, kv->n_kv_heads, kv->head_dim, (int)k_fragment_major(kv->dtype, kv->head_dim, kv->page_size));
     FG_LAUNCH_CHECK("kv_compact");
     if (fin && fout) {
         if (feat_dtype != FG_F32)

@@ -85,3 +85,33 @@ def test_knee_agrees_with_the_oracle_on_random_curves(L, orc32):
         binding.fg_knee([1, 2], [1.0, 2.0])
     with pytest.raises(binding.FgError):
         binding.fg_knee([1, 1, 2], [1.0, 2.0, 3.0])
+
+
+def test_kv_cache_helper_follows_the_documented_k_layout():
+    """The Python cache helper plants and reads K through the page layouts the header documents: MFMA operand order
+    for 16-bit caches with head_dim % 32 == 0, token-major otherwise.  Runs on CPU tensors (no kernel involved)."""
+    import numpy as np
+    import torch
+    import paper_2509_21792_amd.binding as bd
+    for dtype, hd in (("bf16", 128), ("fp16", 64), ("fp32", 16), ("bf16", 48)):
+        cfg = dict(n_layers=2, n_kv_heads=3, head_dim=hd, dtype=dtype)
+        pt = np.array([[3, 1, 4], [0, 2, 5]], np.int32)
+        kv = bd.KVCache(cfg, pt, 6, device="cpu")
+        L = 37
+        g = torch.Generator().manual_seed(hd)
+        k = torch.randn(2, L, 3, hd, generator=g).to(kv.k_pool.dtype)
+        v = torch.randn(2, L, 3, hd, generator=g).to(kv.k_pool.dtype)
+        kv.write_prefix(1, k, v)
+        k2, v2 = kv.read(1, L)
+        assert torch.equal(k2, k) and torch.equal(v2, v), (dtype, hd)
+        flat = kv.k_pool.view(2, 6, 3, -1)
+        for (l, t, h, e) in ((1, 20, 2, hd - 1), (0, 5, 0, 9), (1, 36, 1, hd // 2 + 3)):
+            page, tt = pt[1, t // 16], t % 16
+            if dtype != "fp32" and hd % 32 == 0:
+                q = hd // 4
+                grp, r = e // q, e % q
+                off = (((r // 8) * 4 + grp) * 16 + tt) * 8 + r % 8
+            else:
+                off = tt * hd + e
+            assert flat[l, page, h, off] == k[l, t, h, e], (dtype, hd, l, t, h, e)
+        assert kv.v_pool[1, pt[1, 1], 2, 7, 4] == v[1, 20, 2, 7]
