@@ -10,8 +10,11 @@
 //   O^T += V^T . P^T     A = V^T fragments straight from global memory (pages store V transposed, so the 4
 //                        tokens a lane needs are 8 contiguous bytes), B = P^T taken from the S^T accumulators
 //                        in place: the contraction order is chosen so that no cross-lane shuffle is needed.
-// The contraction over head_dim is permuted as well (lane group g covers the contiguous quarter g of the row)
-// so that every K load is 64 contiguous bytes per lane.  Chunks write (m, l, O) partials; a merge kernel
+// The contraction over head_dim is permuted as well (lane group g covers the contiguous quarter g of the row),
+// and the cache keeps K pages in that fragment order, so that every K load of a wave is one contiguous KiB.
+// Measured and set aside: K / V of two steps in flight through LDS stages (direct-to-LDS buffer loads, query
+// fragments back in registers) instead of one step in a second register set: 305 against 291 us per layer at
+// B = 256, N = 8 -- the kernel is not short of bytes in flight.  Chunks write (m, l, O) partials; a merge kernel
 // combines them.  Key positions >= committed length are in-round nodes and are masked per query row with the
 // node's 64-bit ancestor set.
 #include <stdlib.h>
