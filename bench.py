@@ -24,7 +24,7 @@ PEAK_MFMA = 2516.6e12      # flop/s, dense bf16 / fp16 MFMA
 # scaled by what the same counters read for a plain 1 GiB copy.
 # A recorded measurement, keyed by (workload, rows M); other workloads report null.
 MEASURED_TRAFFIC = {("cfg4", 2048): 815.4e6 + 77.6e6,      # profiles/bench_cfg4_b256_n8_hbm_traffic_pmc.txt
-                    ("b8", 8): 272.4e6 + 7.3e6}            # profiles/verify_b8_n1_memory_bound_regime.txt
+                    ("b8", 8): 273.6e6 + 0.3e6}            # profiles/verify_b8_n1_memory_bound_regime.txt
 
 
 def model_bytes_flops(model, M, lengths, N):
@@ -372,7 +372,9 @@ def main():
 
     # dominant kernel: the gate/up GEMM (largest share of both the weight bytes and the flops)
     n_out, n_in = 2 * model["d_ffn"], model["d_model"]
-    epi = 1 if (M <= 64 or M > 256 or (M > 128 and n_out >= 16384)) else 0     # the library fuses SwiGLU in the few-row and the pipelined kernels
+    big = M > 256 or (M > 128 and n_out >= 16384)
+    few = M <= 64 or (M <= 128 and (n_out < 16384 or (n_out + 63) // 64 <= 512))   # the library's kernel choice for gate/up
+    epi = 1 if (big or few) else 0     # the few-row and the pipelined kernels fuse SwiGLU
     t_verify, _ = time_steps(torch, wl.verify_only, max(3, args.steps // 2), args.warmup)
     t_draft = time_steps(torch, wl.draft, max(3, args.steps // 2), 2)[0] if wl.draft_ready else 0.0
     fg.fg_profile_gemm(True, n_out, n_in, epi, max_launches=(args.steps + args.warmup + 1) * model["n_layers"], rows=M)
@@ -395,7 +397,7 @@ def main():
     roof["traffic"] = MEASURED_TRAFFIC.get((wl.name, M))
     roof["algorithmic"] = gemm_flops if compute_bound else gemm_bytes
     roof["algorithmic_bytes"] = gemm_bytes
-    kname = "gemm_mfma_big_kernel" if (M > 256 or (M > 128 and n_out >= 16384)) else ("gemm_mfma_skinny_kernel" if M <= 64 else "gemm_mfma_kernel")
+    kname = "gemm_mfma_big_kernel" if big else ("gemm_mfma_skinny_kernel" if few else "gemm_mfma_kernel")
     roof["kernel"] = f"{kname} (gate/up, M={M}, n_out={n_out}, n_in={n_in}, epilogue={'swiglu' if epi else 'fp32 split-K slabs'})"
     roof["launches"] = k_cnt
     roof["avg_us"] = k_avg * 1e6

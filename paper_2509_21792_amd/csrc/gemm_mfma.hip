@@ -237,11 +237,16 @@ int gemm_mfma_big_split_for(int M, int N, int K);
 // LM head), where a 256-row tile half full still beats streaming the weights through eight row tiles per wave.
 bool gemm_mfma_uses_big(int M, int N) { return big_variant() && (M > 256 || (M > 128 && N >= 16384)); }
 
-// At most 64 rows: the few-row kernel (gemm_mfma_skinny.hip), which splits k inside the block.  Measured on the
-// 7B-class shapes against the streaming kernel: gate/up with its SwiGLU fused 46.6 / 49.5 / 57.7 us at 8 / 32 / 64
-// rows against 48.8 / 56.8 / 53.0 plus a 4.4 - 5.5 us SwiGLU pass over the slabs; down 22.0 / 26.1 us at 8 / 48
-// rows with 4 slabs against 22.4 / 33.7 with 16; the LM head 167 against 177 us at 8 rows, level at 32 and behind
-// above (220 against 200 us at 48), so the widest outputs stay with the streaming kernel from 33 rows on.
+// Few rows: the kernel that splits k inside the block (gemm_mfma_skinny.hip).  Measured on the 7B-class and
+// 1.5B-class shapes against the streaming kernel:
+//   narrow outputs (QKV, O, down), up to 128 rows: 22.0 / 26.1 / 33.2 / 38.7 us for the 7B down projection at
+//     8 / 48 / 96 / 128 rows with 4 slabs, against 22.4 / 33.7 / 41.8 / 45.1 with 16; 1.5B down at 96 rows 11.2
+//     against 20.3 us;
+//   gate/up with its SwiGLU fused: 46.6 / 49.5 / 57.7 us at 8 / 32 / 64 rows (7B) against 48.8 / 56.8 / 53.0 plus a
+//     4.4 - 5.5 us SwiGLU pass over the slabs.  From 65 rows on a block holds three or four row tiles and two
+//     blocks fit a CU: 1.5B gate/up (280 blocks, one round) 24.2 against 24.4 + 5.4 us at 96 rows, 7B gate/up (592
+//     blocks, a round and a bit) 75 against 58.6 + 6;
+//   the LM head: 167 against 177 us at 8 rows, level at 32, behind above (220 against 200 us at 48).
 // FG_GEMM_FEW=0 switches it off for comparison.
 int32_t launch_gemm_mfma_skinny(int32_t dtype, const void *x, const void *wp, void *out, int M, int N, int K, int epilogue,
                                 int split, hipStream_t st);
@@ -257,7 +262,10 @@ static int few_variant()
 }
 bool gemm_mfma_uses_few(int M, int N, int epilogue)
 {
-    return few_variant() && M <= 64 && (epilogue == 1 || N < 16384 || M <= 32);
+    if (!few_variant() || M > 128) return false;
+    if (N < 16384) return true;
+    if (epilogue == 1) return M <= 64 || (N + 63) / 64 <= 512;
+    return M <= 32;
 }
 // Whether the gate/up GEMM of M rows applies SwiGLU in its own epilogue (no slabs, no separate pass).
 bool gemm_mfma_fuses_swiglu(int M, int N) { return gemm_mfma_uses_big(M, N) || gemm_mfma_uses_few(M, N, 1); }

@@ -1,4 +1,4 @@
-// Few-row shape of the 16-bit MFMA GEMM (at most 64 rows): out = X . W^T, bound by the HBM traffic of W.
+// Few-row shape of the 16-bit MFMA GEMM (at most 128 rows): out = X . W^T, bound by the HBM traffic of W.
 //
 // A block owns 64 output columns (two 32-column bands of the packed W) and all rows; its four waves split the
 // contraction *inside* the block: of every 64-wide k chunk, wave w takes k tile w (16 wide).  Four waves side by
@@ -15,7 +15,9 @@
 //   EPI 0  fp32 partial slab of the block's k split (narrow outputs still want a few splits across blocks),
 //   EPI 1  W is the gate/up interleaved matrix: silu(gate) * up, stored as T.
 // Measured alternatives on the 7B-class gate/up at 8 rows (46.2 us as built): four bands per block 54.7 us (too few
-// blocks), a ring of eight chunks 47.3 us (no gain, and two row tiles then spill).
+// blocks), a ring of eight chunks 47.3 us (no gain, and two row tiles then spill).  Three and four row tiles (65 - 128
+// rows) need 208 - 256 registers: two blocks per CU, which is enough for the narrow outputs' grids of at most 256
+// blocks.
 #include "fg_common.h"
 #include "gemm_mfma.h"
 
@@ -33,7 +35,7 @@ constexpr int SK_DEPTH = 4;   // chunks in flight per wave (even: the LDS buffer
 constexpr int SK_NT = 2;      // 32-column bands per block
 
 template <typename T, int MT, int EPI, int NT, int D>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 1 ? 4 : 3))) void gemm_mfma_skinny_kernel(const T *__restrict__ X, const uint4 *__restrict__ Wp,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 1 ? 4 : (MT == 2 ? 3 : 1)))) void gemm_mfma_skinny_kernel(const T *__restrict__ X, const uint4 *__restrict__ Wp,
                                                                 void *__restrict__ out, int M, int N, int K, int chunks_per_split)
 {
     constexpr int BM = MT * 32;
@@ -220,14 +222,16 @@ template <typename T>
 static void launch_skinny_typed(const void *x, const void *wp, void *out, int M, int N, int K, int epilogue, int split, hipStream_t st)
 {
     if (M <= 32) launch_skinny_mt<T, 1, SK_NT>(x, wp, out, M, N, K, epilogue, split, st);
-    else launch_skinny_mt<T, 2, SK_NT>(x, wp, out, M, N, K, epilogue, split, st);
+    else if (M <= 64) launch_skinny_mt<T, 2, SK_NT>(x, wp, out, M, N, K, epilogue, split, st);
+    else if (M <= 96) launch_skinny_mt<T, 3, SK_NT>(x, wp, out, M, N, K, epilogue, split, st);
+    else launch_skinny_mt<T, 4, SK_NT>(x, wp, out, M, N, K, epilogue, split, st);
 }
 
-// Shapes were validated by the caller (launch_gemm_mfma); M <= 64.
+// Shapes were validated by the caller (launch_gemm_mfma); M <= 128.
 int32_t launch_gemm_mfma_skinny(int32_t dtype, const void *x, const void *wp, void *out, int M, int N, int K, int epilogue,
                                 int split, hipStream_t st)
 {
-    if (M > 64) return fail(FG_ERR_SHAPE, "few-row GEMM takes at most 64 rows (got %d)", M);
+    if (M > 128) return fail(FG_ERR_SHAPE, "few-row GEMM takes at most 128 rows (got %d)", M);
     if (dtype == FG_BF16) launch_skinny_typed<bf16_t>(x, wp, out, M, N, K, epilogue, split, st);
     else launch_skinny_typed<f16_t>(x, wp, out, M, N, K, epilogue, split, st);
     FG_LAUNCH_CHECK("gemm_mfma_skinny");
