@@ -260,19 +260,23 @@ static int few_variant()
     }
     return v;
 }
-bool gemm_mfma_uses_few(int M, int N, int epilogue)
+bool gemm_mfma_uses_few(int M, int N, int K, int epilogue)
 {
-    if (!few_variant() || M > 128) return false;
-    if (N < 16384) return true;
+    if (!few_variant()) return false;
+    // narrow outputs: up to 128 rows in one row block; up to 256 rows (two row blocks) when k is short -- the 7B O
+    // projection 14.8 / 17.7 us at 192 / 256 rows against 23 - 27 in the large-tile kernels, while with k = 18944
+    // the 64-column blocks are bound by their X traffic (65 against 58 - 62 us)
+    if (N < 16384) return M <= 128 || (M <= 256 && K <= 4096);
+    if (M > 128) return false;
     if (epilogue == 1) return M <= 64 || (N + 63) / 64 <= 512;
     return M <= 32;
 }
 // Whether the gate/up GEMM of M rows applies SwiGLU in its own epilogue (no slabs, no separate pass).
-bool gemm_mfma_fuses_swiglu(int M, int N) { return gemm_mfma_uses_big(M, N) || gemm_mfma_uses_few(M, N, 1); }
+bool gemm_mfma_fuses_swiglu(int M, int N) { return gemm_mfma_uses_big(M, N) || gemm_mfma_uses_few(M, N, 0, 1); }
 
 int gemm_mfma_split_for(int M, int N, int K)
 {
-    if (gemm_mfma_uses_few(M, N, 0)) return gemm_mfma_skinny_split_for(M, N, K);
+    if (gemm_mfma_uses_few(M, N, K, 0)) return gemm_mfma_skinny_split_for(M, N, K);
     if (gemm_mfma_uses_big(M, N)) return gemm_mfma_big_split_for(M, N, K);
     return choose_split(M, N, K, 256, 256);
 }
@@ -315,7 +319,7 @@ int32_t launch_gemm_mfma(int32_t dtype, const void *x, const void *wp, void *out
                       g_prof.used < g_prof.start.size();
     if (prof) (void)hipEventRecord(g_prof.start[g_prof.used], st);
     int32_t rc;
-    if (gemm_mfma_uses_few(M, N, epilogue)) rc = launch_gemm_mfma_skinny(dtype, x, wp, out, M, N, K, epilogue, split, st);
+    if (gemm_mfma_uses_few(M, N, K, epilogue)) rc = launch_gemm_mfma_skinny(dtype, x, wp, out, M, N, K, epilogue, split, st);
     else if (gemm_mfma_uses_big(M, N)) rc = launch_gemm_mfma_big(dtype, x, wp, out, M, N, K, epilogue, split, raster_enabled(), st);
     else rc = dtype == FG_BF16 ? launch_gemm_typed<bf16_t>(x, wp, out, M, N, K, epilogue, split, st)
                                : launch_gemm_typed<f16_t>(x, wp, out, M, N, K, epilogue, split, st);

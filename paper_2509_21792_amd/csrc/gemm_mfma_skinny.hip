@@ -1,4 +1,4 @@
-// Few-row shape of the 16-bit MFMA GEMM (at most 128 rows): out = X . W^T, bound by the HBM traffic of W.
+// Few-row shape of the 16-bit MFMA GEMM (at most 128 rows per block; short-k shapes take two row blocks): out = X . W^T, bound by the HBM traffic of W.
 //
 // A block owns 64 output columns (two 32-column bands of the packed W) and all rows; its four waves split the
 // contraction *inside* the block: of every 64-wide k chunk, wave w takes k tile w (16 wide).  Four waves side by
@@ -36,7 +36,8 @@ constexpr int SK_NT = 2;      // 32-column bands per block
 
 template <typename T, int MT, int EPI, int NT, int D>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 1 ? 4 : (MT == 2 ? 3 : 1)))) void gemm_mfma_skinny_kernel(const T *__restrict__ X, const uint4 *__restrict__ Wp,
-                                                                void *__restrict__ out, int M, int N, int K, int chunks_per_split)
+                                                                void *__restrict__ out, int M, int N, int K, int chunks_per_split,
+                                                                int row_blocks, int col_blocks, int splits)
 {
     constexpr int BM = MT * 32;
     constexpr int XLOADS = BM * 8 / 256;   // 16-byte pieces of X per thread per chunk
@@ -48,7 +49,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 1 ? 4
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n_tiles = N >> 5, k_tiles = K >> 4;
-    const int ntile0 = blockIdx.x * NT, bz = blockIdx.z;
+    // Block -> (column block, k split, row block).  Workgroups are dealt to the 8 XCDs round-robin by linear id: the
+    // row blocks of one (column block, k split) unit get ids that differ by multiples of 8, so they run on the same
+    // XCD at about the same time and the unit's W is fetched from HBM once (the other row blocks hit in that L2).
+    const int grp8 = blockIdx.x / (8 * row_blocks), within = blockIdx.x % (8 * row_blocks);
+    const int unit = grp8 * 8 + (within & 7), rb = within >> 3;
+    if (unit >= col_blocks * splits) return;
+    const int ntile0 = (unit % col_blocks) * NT, bz = unit / col_blocks;
+    const int row0 = rb * BM;
     const int total_chunks = k_tiles / KT;
     const int c_begin = bz * chunks_per_split;
     const int c_end = min(c_begin + chunks_per_split, total_chunks);
@@ -79,7 +87,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 1 ? 4
     for (int i = 0; i < XLOADS; i++) {
         const int idx = i * 256 + tid;
         const int c = idx & 7, r = idx >> 3;
-        const int row = min(r, M - 1);
+        const int row = min(row0 + r, M - 1);
         xsrc[i] = reinterpret_cast<const bf16_t *>(X) + (size_t)row * K + c * 8;
         xdst[i] = (((r >> 5) * KT + (c >> 1)) << 6) + ((((c & 1) << 5) + (r & 31)) ^ (((c >> 1) << 1) | ((c & 1) << 3)));
     }
@@ -137,18 +145,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 1 ? 4
     const int F = N >> 1;
 #pragma unroll
     for (int i = 0; i < MT; i++) {
-        if (i * 32 >= M) break;
+        if (row0 + i * 32 >= M) break;
         __syncthreads();   // the X buffers / the previous tile's readers are done
 #pragma unroll
         for (int j = 0; j < NT; j++)
 #pragma unroll
             for (int q = 0; q < 4; q++)
-                if (i * 32 + 8 * q < M)
+                if (row0 + i * 32 + 8 * q < M)
                     red[((wave * NT + j) * 4 + q) * 64 + lane] =
                         (sk_f32x4_t){acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
         __syncthreads();
-        const int q = wave, m0 = i * 32 + 8 * q + 4 * (lane >> 5);
-        if (i * 32 + 8 * q < M) {
+        const int q = wave, m0 = row0 + i * 32 + 8 * q + 4 * (lane >> 5);
+        if (row0 + i * 32 + 8 * q < M) {
             float s[NT][4];
 #pragma unroll
             for (int j = 0; j < NT; j++) {
@@ -188,10 +196,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 1 ? 4
 // for 8 - 16 splits; O: 4; QKV: 3 of 72), so: the largest split that keeps the grid within 256 blocks and every
 // split at least one round of the ring long, and among those the fewest splits that give the same longest split
 // (the blocks run side by side, so the longest split is the duration).
+int gemm_mfma_skinny_row_blocks(int M);
 int gemm_mfma_skinny_split_for(int M, int N, int K)
 {
-    (void)M;
-    const int col_blocks = (N / 32 + SK_NT - 1) / SK_NT, chunks = K / 64;
+    const int col_blocks = (N / 32 + SK_NT - 1) / SK_NT * gemm_mfma_skinny_row_blocks(M), chunks = K / 64;
     int s_hi = 256 / col_blocks;
     if (s_hi > 16) s_hi = 16;
     if (s_hi > chunks / SK_DEPTH) s_hi = chunks / SK_DEPTH;
@@ -209,29 +217,36 @@ static void launch_skinny_mt(const void *x, const void *wp, void *out, int M, in
 {
     // chunks per split in whole rounds of the ring (a split past the end of k then writes a slab of zeros)
     const int chunks = K / 64, cps = ((chunks + split - 1) / split + D - 1) / D * D;
-    dim3 grid((N / 32 + NT - 1) / NT, 1, split);
+    const int col_blocks = (N / 32 + NT - 1) / NT, row_blocks = (M + MT * 32 - 1) / (MT * 32);
+    const int units = col_blocks * split;
+    dim3 grid((unsigned)((units + 7) / 8 * 8 * row_blocks));
     if (epilogue == 0)
         hipLaunchKernelGGL((gemm_mfma_skinny_kernel<T, MT, 0, NT, D>), grid, dim3(256), 0, st, reinterpret_cast<const T *>(x),
-                           reinterpret_cast<const uint4 *>(wp), out, M, N, K, cps);
+                           reinterpret_cast<const uint4 *>(wp), out, M, N, K, cps, row_blocks, col_blocks, split);
     else
         hipLaunchKernelGGL((gemm_mfma_skinny_kernel<T, MT, 1, NT, D>), grid, dim3(256), 0, st, reinterpret_cast<const T *>(x),
-                           reinterpret_cast<const uint4 *>(wp), out, M, N, K, cps);
+                           reinterpret_cast<const uint4 *>(wp), out, M, N, K, cps, row_blocks, col_blocks, split);
 }
+
+// Row tiles per block: one block of up to four tiles for up to 128 rows, otherwise the rows are cut evenly over
+// blocks of three or four tiles.
+int gemm_mfma_skinny_row_blocks(int M) { return (M + 127) / 128; }
 
 template <typename T>
 static void launch_skinny_typed(const void *x, const void *wp, void *out, int M, int N, int K, int epilogue, int split, hipStream_t st)
 {
-    if (M <= 32) launch_skinny_mt<T, 1, SK_NT>(x, wp, out, M, N, K, epilogue, split, st);
-    else if (M <= 64) launch_skinny_mt<T, 2, SK_NT>(x, wp, out, M, N, K, epilogue, split, st);
-    else if (M <= 96) launch_skinny_mt<T, 3, SK_NT>(x, wp, out, M, N, K, epilogue, split, st);
+    const int rb = gemm_mfma_skinny_row_blocks(M), per = (M + rb - 1) / rb;   // rows per block
+    if (per <= 32) launch_skinny_mt<T, 1, SK_NT>(x, wp, out, M, N, K, epilogue, split, st);
+    else if (per <= 64) launch_skinny_mt<T, 2, SK_NT>(x, wp, out, M, N, K, epilogue, split, st);
+    else if (per <= 96) launch_skinny_mt<T, 3, SK_NT>(x, wp, out, M, N, K, epilogue, split, st);
     else launch_skinny_mt<T, 4, SK_NT>(x, wp, out, M, N, K, epilogue, split, st);
 }
 
-// Shapes were validated by the caller (launch_gemm_mfma); M <= 128.
+// Shapes were validated by the caller (launch_gemm_mfma).
 int32_t launch_gemm_mfma_skinny(int32_t dtype, const void *x, const void *wp, void *out, int M, int N, int K, int epilogue,
                                 int split, hipStream_t st)
 {
-    if (M > 128) return fail(FG_ERR_SHAPE, "few-row GEMM takes at most 128 rows (got %d)", M);
+    if (M > 512) return fail(FG_ERR_SHAPE, "few-row GEMM takes at most 512 rows (got %d)", M);
     if (dtype == FG_BF16) launch_skinny_typed<bf16_t>(x, wp, out, M, N, K, epilogue, split, st);
     else launch_skinny_typed<f16_t>(x, wp, out, M, N, K, epilogue, split, st);
     FG_LAUNCH_CHECK("gemm_mfma_skinny");

@@ -66,12 +66,13 @@ def test_gemm_16bit_many_rows_every_k_tail(fg, chunks):
 @pytest.mark.parametrize("chunks", [1, 2, 3, 4, 5, 7, 8, 9, 13, 18])
 def test_gemm_16bit_few_rows_every_k_tail(fg, chunks):
     """Up to 128 rows (narrow outputs) takes the few-row kernel (k split inside the block, rounds of four 64-wide k
-    chunks): every tail length of the last round, one to four row tiles with ragged ends, an odd number of column bands, requested
+    chunks): every tail length of the last round, one to four row tiles with ragged ends, two row blocks, an odd number of column bands, requested
     splits that leave the last split short or empty, and the fused SwiGLU epilogue."""
     K = 64 * chunks
     print(f"gemm few rows chunks={chunks}", flush=True)
     g = torch.Generator().manual_seed(100 + chunks)
-    for dtype, M in (("bf16", 1), ("fp16", 31), ("bf16", 33), ("fp16", 64), ("bf16", 65), ("fp16", 96), ("bf16", 127)):
+    for dtype, M in (("bf16", 1), ("fp16", 31), ("bf16", 33), ("fp16", 64), ("bf16", 65), ("fp16", 96), ("bf16", 127),
+                     ("fp16", 129), ("bf16", 200), ("fp16", 256)):   # two row blocks (short k)
         N = 96 + 64 * (M % 3)          # 3, 5 or 7 bands of 32 columns
         x, w = bf16_randn((M, K), g, dt=TD[dtype]), bf16_randn((N, K), g, 0.05, dt=TD[dtype])
         ref = x.double() @ w.double().T
