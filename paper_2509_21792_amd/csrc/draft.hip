@@ -5,6 +5,7 @@
 namespace fg {
 
 constexpr int TK_THREADS = 1024, TK_MAX = 8;
+constexpr int TK_REDO = -1;   // first token of a row the selective kernel hands to the general one
 
 // Per row, in ONE pass over the logits: every thread keeps an online (max, sum of exponentials) pair and the
 // TK_MAX largest of its own elements, sorted (value descending, index ascending on ties: a thread meets its indices
@@ -43,12 +44,14 @@ __device__ __forceinline__ void online_add(float &m, float &sum, float x)
     }
 }
 
-__global__ __launch_bounds__(TK_THREADS) void topk_logp_kernel(const float *logits, int V, int K, int32_t *tok, float *logp)
+__global__ __launch_bounds__(TK_THREADS) void topk_logp_kernel(const float *logits, int V, int K, int32_t *tok, float *logp,
+                                                               int only_marked)
 {
     __shared__ float rb[TK_THREADS / 64];
     __shared__ int ri[TK_THREADS / 64];
     __shared__ float sm[TK_THREADS / 64], ss[TK_THREADS / 64];
     const int r = blockIdx.x, tid = threadIdx.x;
+    if (only_marked && tok[(size_t)r * K] != TK_REDO) return;   // the selective kernel finished this row
     const float *row = logits + (size_t)r * V;
     TopList t;
 #pragma unroll
@@ -118,10 +121,143 @@ __global__ __launch_bounds__(TK_THREADS) void topk_logp_kernel(const float *logi
     }
 }
 
+// The same result for rows whose vocabulary is a multiple of four, with far less arithmetic per element.  The
+// general kernel keeps a sorted list per thread; some lane of a wave wants an insertion at almost every step, so
+// every wave walks the insertion code for all of its elements (70 us for a row of 152 064 whatever the number of
+// rows up to 256).  Here the one pass over the row only takes each thread's maximum and its online sum of
+// exponentials.  The K-th largest of the 1024 thread maxima, tau, is a lower bound of the row's K-th largest entry,
+// and entries >= tau can only sit in threads whose maximum is >= tau -- K of them unless values tie.  Their few
+// quads are read again (a few KiB, cooperatively), the entries >= tau are collected in LDS, and K block-wide
+// (value, lowest index) arg-max rounds pick the winners as before.  Rows with more tied candidates than the lists
+// hold are marked (first token = TK_REDO) and redone by the general kernel, which is launched behind this one and
+// returns at once for every other row.
+constexpr int TK_HOT_MAX = 64, TK_CAND_MAX = 2 * TK_THREADS;
+
+__global__ __launch_bounds__(TK_THREADS) void topk_logp_select_kernel(const float *logits, int V, int K, int32_t *tok, float *logp)
+{
+    __shared__ float rb[TK_THREADS / 64];
+    __shared__ int ri[TK_THREADS / 64];
+    __shared__ float sm[TK_THREADS / 64], ss[TK_THREADS / 64];
+    __shared__ int hot[TK_HOT_MAX];
+    __shared__ int hot_n, cand_n;
+    __shared__ float cv[TK_CAND_MAX];
+    __shared__ int ci[TK_CAND_MAX];
+    const int r = blockIdx.x, tid = threadIdx.x;
+    const float4 *row4 = reinterpret_cast<const float4 *>(logits + (size_t)r * V);
+    const int nq = V >> 2, qpt = (nq + TK_THREADS - 1) / TK_THREADS;
+    if (tid == 0) { hot_n = 0; cand_n = 0; }
+
+    // pass over the row: thread maximum and online sum of exponentials, four quads requested together
+    float m = -INFINITY, sum = 0.f;
+    auto take = [&](const float4 x) {
+        const float m4 = fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w));
+        if (m4 > m) {   // one rescale per quad
+            sum *= __expf(m - m4);
+            m = m4;
+        }
+        sum += (__expf(x.x - m) + __expf(x.y - m)) + (__expf(x.z - m) + __expf(x.w - m));
+    };
+    int q = tid;
+    for (; q + 3 * TK_THREADS < nq; q += 4 * TK_THREADS) {
+        const float4 x0 = row4[q], x1 = row4[q + TK_THREADS], x2 = row4[q + 2 * TK_THREADS], x3 = row4[q + 3 * TK_THREADS];
+        take(x0); take(x1); take(x2); take(x3);
+    }
+    for (; q < nq; q += TK_THREADS) take(row4[q]);
+
+    // logsumexp of the row
+    const float wm = wave_max(m);
+    float wsum = sum * (m == -INFINITY ? 0.f : __expf(m - wm));
+    wsum = wave_sum(wsum);
+    if ((tid & 63) == 0) { sm[tid >> 6] = wm; ss[tid >> 6] = wsum; }
+    __syncthreads();
+    float bm = -INFINITY;
+    for (int i = 0; i < TK_THREADS / 64; i++) bm = fmaxf(bm, sm[i]);
+    float bs = 0.f;
+    for (int i = 0; i < TK_THREADS / 64; i++) bs += ss[i] * (sm[i] == -INFINITY ? 0.f : __expf(sm[i] - bm));
+    const float lse = bm + logf(bs);
+
+    // block-wide (value, lowest index) arg-max over one (value, index) pair per thread
+    auto block_argmax = [&](float &best, int &bi) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            float ob = __shfl_xor(best, o, 64);
+            int oi = __shfl_xor(bi, o, 64);
+            if (ob > best || (ob == best && oi < bi)) { best = ob; bi = oi; }
+        }
+        __syncthreads();   // the previous round's readers are done with rb / ri
+        if ((tid & 63) == 0) { rb[tid >> 6] = best; ri[tid >> 6] = bi; }
+        __syncthreads();
+        best = rb[0]; bi = ri[0];
+        for (int i = 1; i < TK_THREADS / 64; i++)
+            if (rb[i] > best || (rb[i] == best && ri[i] < bi)) { best = rb[i]; bi = ri[i]; }
+    };
+
+    // tau = the K-th largest thread maximum
+    float cur = m, tau = -INFINITY;
+    for (int k = 0; k < K; k++) {
+        float best = cur;
+        int bi = tid;
+        block_argmax(best, bi);
+        if (bi == tid) cur = -INFINITY;
+        tau = best;
+    }
+    // threads that can hold an entry >= tau, then their quads once more
+    if (m >= tau) {
+        const int p = atomicAdd(&hot_n, 1);
+        if (p < TK_HOT_MAX) hot[p] = tid;
+    }
+    __syncthreads();
+    const int n_hot = hot_n;
+    bool redo = n_hot > TK_HOT_MAX || !(tau > -INFINITY);
+    if (!redo) {
+        for (int it = tid; it < n_hot * qpt; it += TK_THREADS) {
+            const int qq = hot[it / qpt] + (it % qpt) * TK_THREADS;
+            if (qq >= nq) continue;
+            const float4 x = row4[qq];
+            const float xs[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+            for (int c = 0; c < 4; c++)
+                if (xs[c] >= tau) {
+                    const int p = atomicAdd(&cand_n, 1);
+                    if (p < TK_CAND_MAX) { cv[p] = xs[c]; ci[p] = qq * 4 + c; }
+                }
+        }
+        __syncthreads();
+        redo = cand_n > TK_CAND_MAX;
+    }
+    if (redo) {
+        if (tid == 0) tok[(size_t)r * K] = TK_REDO;
+        return;
+    }
+    // K winners among the candidates: a thread owns candidates tid and tid + TK_THREADS
+    const int n_cand = cand_n;
+    float v0 = tid < n_cand ? cv[tid] : -INFINITY, v1 = tid + TK_THREADS < n_cand ? cv[tid + TK_THREADS] : -INFINITY;
+    int i0 = tid < n_cand ? ci[tid] : 0x7fffffff, i1 = tid + TK_THREADS < n_cand ? ci[tid + TK_THREADS] : 0x7fffffff;
+    if (v1 > v0 || (v1 == v0 && i1 < i0)) {
+        const float tv = v0; v0 = v1; v1 = tv;
+        const int ti = i0; i0 = i1; i1 = ti;
+    }
+    for (int k = 0; k < K; k++) {
+        float best = v0;
+        int bi = i0;
+        block_argmax(best, bi);
+        if (i0 == bi) { v0 = v1; i0 = i1; v1 = -INFINITY; i1 = 0x7fffffff; }   // this thread owned the winner
+        if (tid == 0) {
+            tok[(size_t)r * K + k] = bi;
+            logp[(size_t)r * K + k] = best - lse;
+        }
+    }
+}
+
 int32_t launch_topk_logp(const float *logits, int M, int V, int K, int32_t *tok, float *logp, hipStream_t st)
 {
     if (K < 1 || K > TK_MAX || K > V) return fail(FG_ERR_INVALID_ARG, "K_draft must be in 1..%d (got %d)", TK_MAX, K);
-    hipLaunchKernelGGL(topk_logp_kernel, dim3(M), dim3(TK_THREADS), 0, st, logits, V, K, tok, logp);
+    const bool selective = (V & 3) == 0 && V >= 4 * TK_THREADS;
+    if (selective) {
+        hipLaunchKernelGGL(topk_logp_select_kernel, dim3(M), dim3(TK_THREADS), 0, st, logits, V, K, tok, logp);
+        FG_LAUNCH_CHECK("topk_logp_select");
+    }
+    hipLaunchKernelGGL(topk_logp_kernel, dim3(M), dim3(TK_THREADS), 0, st, logits, V, K, tok, logp, selective ? 1 : 0);
     FG_LAUNCH_CHECK("topk_logp");
     return FG_OK;
 }

@@ -205,7 +205,7 @@ def test_config1_generation_loop_matches_plain_greedy_decoding(H):
 
 @pytest.mark.parametrize("V,K", [(16, 3), (1000, 4), (1003, 8), (152064, 4), (152066, 1)])
 def test_topk_logp_ties_and_ragged_vocabulary(H, V, K):
-    """The one-pass kernel against the oracle: token ids exact, with planted ties inside a thread's stride, across
+    """The top-K kernels against the oracle: token ids exact, with planted ties inside a thread's stride, across
     threads and across waves (lower id first), vocabularies that are and are not multiples of four."""
     import paper_2509_21792_amd as fg
     rng = np.random.default_rng(V + K)
@@ -219,6 +219,25 @@ def test_topk_logp_ties_and_ragged_vocabulary(H, V, K):
             lg[r, [5, 5 + 1024, 5 + 2048]] = top + r        # same thread, later strides
     from oracle.oracle import Oracle
     o_tok, o_logp = Oracle("f64").topk_logp(lg, K)   # the fp32 build's sequential sum is itself off by ~7e-4 at this width
+    g_tok, g_logp = fg.fg_topk_logp(torch.as_tensor(lg).cuda(), K)
+    torch.cuda.synchronize()
+    assert np.array_equal(g_tok.cpu().numpy(), o_tok)
+    assert np.abs(g_logp.cpu().numpy() - o_logp).max() < 2e-5
+
+
+def test_topk_logp_many_ties(H):
+    """Rows where the selective top-K kernel cannot decide from a few threads' entries -- every logit equal, or a
+    plateau of equal maxima wider than its candidate lists -- are redone by the general kernel; a plateau that still
+    fits stays on the selective path.  Token ids exact (lowest ids first)."""
+    import paper_2509_21792_amd as fg
+    from oracle.oracle import Oracle
+    V, K = 8192, 5
+    rng = np.random.default_rng(5)
+    lg = (rng.standard_normal((4, V))).astype(np.float32)
+    lg[0, :] = 0.25                                     # all equal: every thread ties
+    lg[1, rng.choice(V, size=3000, replace=False)] = 9.0   # a plateau of 3000 maxima
+    lg[2, rng.choice(V, size=30, replace=False)] = 9.0     # a plateau of 30 maxima
+    o_tok, o_logp = Oracle("f64").topk_logp(lg, K)
     g_tok, g_logp = fg.fg_topk_logp(torch.as_tensor(lg).cuda(), K)
     torch.cuda.synchronize()
     assert np.array_equal(g_tok.cpu().numpy(), o_tok)
