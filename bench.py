@@ -352,7 +352,9 @@ def main():
     ap.add_argument("--gen", action="store_true", help="the generation loop with concurrency decay instead of the step benchmark")
     ap.add_argument("--agree", type=float, default=0.7, help="--gen: planted per-node agreement rate")
     ap.add_argument("--mean-len", type=int, default=160, help="--gen: mean response budget")
-    ap.add_argument("--c-peak", type=int, default=0, help="--gen: use this C_peak instead of the measured knee")
+    ap.add_argument("--c-peak", type=int, default=0, help="--gen, --sweep: use this C_peak instead of the measured knee")
+    ap.add_argument("--sweep", action="store_true",
+                    help="the metric's range: B = 8 ... 256 on the 7B-class target, each with the shape Eq. 1-3 give")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: every box of this build has one MI355X and the path shards by sequence "
@@ -364,6 +366,9 @@ def main():
     assert torch.cuda.is_available(), "no GPU: the HIP path has no CPU fallback"
     if args.gen:
         gen_experiment(args)
+        return
+    if args.sweep:
+        sweep(args)
         return
 
     wl = Workload(args.workload, args.dtype, B=args.B or None, N=args.N or None, n_layers=args.layers or None, verbose=True)
@@ -425,6 +430,50 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))
+
+
+def sweep(args):
+    """B = 8, 16, ..., 256 sequences with KV lengths U[256, 2048] on the 7B-class target, each batch with the tree
+    shape the concurrency rule gives it (Eq. 1-3, C_peak = the measured knee unless --c-peak): whole-round and
+    verify-step times, accepted tokens/s and the step's fractions of the HBM and MFMA peaks."""
+    import gc
+    import torch
+    import paper_2509_21792_amd as fg
+    from paper_2509_21792_amd import loop as gloop
+    from synth import configs, gen
+    cfg = configs.CONFIGS["b8"]
+    model = configs.with_dtype(cfg["model"], args.dtype)
+    c_peak, lat, sizes = args.c_peak, None, [1, 2, 4, 8, 16, 24, 32, 48, 64, 96, 128, 192, 256, 384, 512]
+    if not c_peak:
+        gm = fg.Model(model, gen.make_weights(model, 0, device="cuda"))
+        ptab, pn = gen.make_page_table(np.zeros(max(sizes), np.int32), 16, 16, 3)
+        pkv = fg.KVCache(model, ptab, pn)
+        c_peak, lat = gloop.measure_c_peak(gm, pkv, gm.workspace(max(sizes), 32), sizes)
+        del gm, pkv
+        gc.collect()
+        torch.cuda.empty_cache()
+    pd = configs.PLAN_DEFAULTS
+    points = []
+    for B in (8, 16, 32, 64, 128, 256):
+        N, K, L = fg.fg_plan(B, float(c_peak), pd["alpha"], pd["K_max"], pd["L_max"], pd["N_cap"])
+        wl = Workload("b8", args.dtype, B=B, N=N, verbose=True)
+        t_verify, _ = time_steps(torch, wl.verify_only, max(3, args.steps // 2), args.warmup)
+        t_step, emitted = time_steps(torch, wl.step, args.steps, args.warmup)
+        acct = model_bytes_flops(wl.model, B * N, wl.lengths.astype(np.float64), N)
+        points.append(dict(B=B, N=N, K_draft=K, L_draft=L, round_ms=t_step * 1e3, verify_ms=t_verify * 1e3,
+                           accepted_tokens_per_s=emitted / t_step, tau=emitted / B,
+                           step_hbm_frac=acct["bytes"] / t_verify / PEAK_HBM, step_mfma_frac=acct["flops"] / t_verify / PEAK_MFMA))
+        print(f"# B={B} N={N} K={K} L={L}: round {t_step * 1e3:.2f} ms, verify {t_verify * 1e3:.2f} ms, "
+              f"{emitted / t_step:.0f} tokens/s", file=sys.stderr, flush=True)
+        del wl
+        gc.collect()
+        torch.cuda.empty_cache()
+    print(json.dumps({"metric": "accepted tokens/s and verify-step ms over B = 8 ... 256 with rule-chosen shapes",
+                      "unit": "tokens/s", "n_gpus": 1, "dtype": args.dtype, "data": "synthetic",
+                      "config": {"workload": f"{model['name']} {model['n_layers']} layers, KV lengths U[{cfg['kv_lo']},{cfg['kv_hi']}], "
+                                             f"planted agreement {cfg['plant_p']}, greedy"},
+                      "c_peak": c_peak, "c_peak_latency_ms": None if lat is None else {str(b): t for b, t in zip(sizes, lat)},
+                      "points": points}))
 
 
 def b8_point(wl, N, args):
