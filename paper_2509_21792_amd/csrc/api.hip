@@ -55,7 +55,7 @@ int32_t launch_commit_len(int32_t *seq_len, const int32_t *slot, const int32_t *
                           hipStream_t st);
 int gemm_mfma_split_for(int M, int N, int K);
 bool gemm_mfma_uses_big(int M, int N);
-bool gemm_mfma_fuses_swiglu(int M, int N);
+bool gemm_mfma_fuses_swiglu(int M, int N, int K);
 int32_t profile_gemm_arm(int enable, int rows, int n_out, int n_in, int epilogue, int max_launches);
 int32_t profile_gemm_read(double *total_ms, int32_t *count);
 
@@ -92,7 +92,7 @@ struct Carver {
 int split_for(const fg_model_cfg &c, int M, int N, int K) { return is16(c.dtype) ? gemm_mfma_split_for(M, N, K) : 1; }
 
 // gate/up with the SwiGLU epilogue (no split-K slabs) whenever the pipelined kernel runs it
-bool gate_up_fused(const fg_model_cfg &c, int M) { return is16(c.dtype) && gemm_mfma_fuses_swiglu(M, 2 * c.d_ffn); }
+bool gate_up_fused(const fg_model_cfg &c, int M) { return is16(c.dtype) && gemm_mfma_fuses_swiglu(M, 2 * c.d_ffn, c.d_model); }
 
 int64_t partial_floats(const fg_model_cfg &c, int M, bool is_draft)
 {

@@ -236,6 +236,10 @@ int gemm_mfma_big_split_for(int M, int N, int K);
 // The pipelined kernel takes every shape with more than 256 rows, and from 129 rows on the wide ones (gate/up,
 // LM head), where a 256-row tile half full still beats streaming the weights through eight row tiles per wave.
 bool gemm_mfma_uses_big(int M, int N) { return big_variant() && (M > 256 || (M > 128 && N >= 16384)); }
+// ... and the narrow outputs with a long contraction from 129 rows on: with up to 16 k splits the 7B down
+// projection takes 42 - 47 us at 160 - 256 rows against 58 - 62 in the streaming kernel, whose single chunk of W in
+// flight per wave leaves every chunk waiting a full memory latency.
+static bool uses_big_narrow(int M, int N, int K) { return big_variant() && N < 16384 && M > 128; }   // after the few-row test
 
 // Few rows: the kernel that splits k inside the block (gemm_mfma_skinny.hip).  Measured on the 7B-class and
 // 1.5B-class shapes against the streaming kernel:
@@ -263,21 +267,22 @@ static int few_variant()
 bool gemm_mfma_uses_few(int M, int N, int K, int epilogue)
 {
     if (!few_variant()) return false;
-    // narrow outputs: up to 128 rows in one row block; up to 256 rows (two row blocks) when k is short -- the 7B O
-    // projection 14.8 / 17.7 us at 192 / 256 rows against 23 - 27 in the large-tile kernels, while with k = 18944
-    // the 64-column blocks are bound by their X traffic (65 against 58 - 62 us)
-    if (N < 16384) return M <= 128 || (M <= 256 && K <= 4096);
+    // narrow outputs: up to 128 rows in one row block; up to 256 rows (two row blocks) while the X traffic of the
+    // 64-column blocks (column blocks x M x K x 2 bytes, all from L2) stays small -- the 7B O projection (103 MB)
+    // 14.8 / 17.7 us at 192 / 256 rows against 23 - 27 in the large-tile kernels, the 1.5B down projection (82 MB)
+    // 15 against 25 - 30 us at 192 rows, while the 7B down projection (543 MB) takes 65 against 47 - 62 us
+    if (N < 16384) return M <= 128 || (M <= 256 && (int64_t)((N + 63) / 64) * M * K <= (56LL << 20));
     if (M > 128) return false;
     if (epilogue == 1) return M <= 64 || (N + 63) / 64 <= 512;
     return M <= 32;
 }
 // Whether the gate/up GEMM of M rows applies SwiGLU in its own epilogue (no slabs, no separate pass).
-bool gemm_mfma_fuses_swiglu(int M, int N) { return gemm_mfma_uses_big(M, N) || gemm_mfma_uses_few(M, N, 0, 1); }
+bool gemm_mfma_fuses_swiglu(int M, int N, int K) { return gemm_mfma_uses_big(M, N) || gemm_mfma_uses_few(M, N, K, 1); }
 
 int gemm_mfma_split_for(int M, int N, int K)
 {
     if (gemm_mfma_uses_few(M, N, K, 0)) return gemm_mfma_skinny_split_for(M, N, K);
-    if (gemm_mfma_uses_big(M, N)) return gemm_mfma_big_split_for(M, N, K);
+    if (gemm_mfma_uses_big(M, N) || uses_big_narrow(M, N, K)) return gemm_mfma_big_split_for(M, N, K);
     return choose_split(M, N, K, 256, 256);
 }
 
@@ -320,7 +325,7 @@ int32_t launch_gemm_mfma(int32_t dtype, const void *x, const void *wp, void *out
     if (prof) (void)hipEventRecord(g_prof.start[g_prof.used], st);
     int32_t rc;
     if (gemm_mfma_uses_few(M, N, K, epilogue)) rc = launch_gemm_mfma_skinny(dtype, x, wp, out, M, N, K, epilogue, split, st);
-    else if (gemm_mfma_uses_big(M, N)) rc = launch_gemm_mfma_big(dtype, x, wp, out, M, N, K, epilogue, split, raster_enabled(), st);
+    else if (gemm_mfma_uses_big(M, N) || uses_big_narrow(M, N, K)) rc = launch_gemm_mfma_big(dtype, x, wp, out, M, N, K, epilogue, split, raster_enabled(), st);
     else rc = dtype == FG_BF16 ? launch_gemm_typed<bf16_t>(x, wp, out, M, N, K, epilogue, split, st)
                                : launch_gemm_typed<f16_t>(x, wp, out, M, N, K, epilogue, split, st);
     if (prof) (void)hipEventRecord(g_prof.stop[g_prof.used++], st);

@@ -205,7 +205,8 @@ static BigPlan plan_big(int M, int N, int K, int fixed_split)
     const int n_bands = (N / 32 + 7) / 8, row_blocks = (M + 255) / 256, chunks = K / 64;
     BigPlan best{1, 1};
     double best_cost = 1e30;
-    for (int s = 1; s <= 8; s++) {
+    const int s_max = row_blocks == 1 ? 16 : 8;   // one row block: the slabs are small, the grid needs the splits
+    for (int s = 1; s <= s_max; s++) {
         if (fixed_split > 0 && s != fixed_split) continue;
         if (fixed_split <= 0 && s > 1 && chunks / s < 8) break;
         const int cps = (chunks + s - 1) / s;
