@@ -115,6 +115,18 @@ def test_7b_geometry_high_concurrency_shapes(H, N, dtype):
     run_verify_case(H, model, B, N, spec, lengths, seed=3 + N, subset=[0, 1, 2, 100, 200, 255])
 
 
+@pytest.mark.parametrize("B,N,dtype", [(32, 1, "bf16"), (33, 1, "fp16"), (64, 1, "fp16"), (65, 1, "bf16"), (24, 4, "fp16"),
+                                       (128, 1, "fp16"), (129, 1, "bf16"), (48, 4, "fp16"), (100, 2, "bf16")])
+def test_7b_geometry_rows_at_the_gemm_kernels_boundaries(H, B, N, dtype):
+    """Row counts on both sides of every switch between the GEMM kernels (few-row with one to four row tiles and
+    with two row blocks, streaming, pipelined) on the 7B geometry with 1 layer; oracle on 5 sequences."""
+    model = configs.with_dtype(configs.scaled(configs.Q7B, 1), dtype)
+    lengths = gen.make_kv_lengths(B, 40, 500, seed=B)
+    lengths[0], lengths[1] = 40, 500
+    spec = ("chain", N - 1) if N <= 2 else ("tree", 3, 3, N)
+    run_verify_case(H, model, B, N, spec, lengths, seed=20 + B, subset=[0, 1, 2, B // 2, B - 1])
+
+
 def test_accept_and_compact_follow_the_oracle(H):
     """Greedy acceptance with planted agreement + compaction: accept lengths, paths, tokens and the moved K/V."""
     import paper_2509_21792_amd as fg
