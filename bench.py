@@ -4,7 +4,9 @@
 One "step" = one pass of the hot path over one batch: plan (host) -> L_draft draft steps + frontier updates +
 rerank -> spec_verify -> spec_accept -> kv_compact -> accept lengths to the host.  Inputs (weights, paged KV cache, planted
 draft trees) are resident in HBM before the timed region; the cache lengths are reset between steps so every step
-sees the same ragged shape.  Prints ONE JSON line (see README for the fields).
+sees the same ragged shape.  Prints ONE JSON line: the metric (accepted tokens/s of the whole round), the round /
+verify / draft times, the step's fractions of the HBM and MFMA peaks, `roofline` for the dominant kernel (the gate/up
+GEMM, timed with HIP events inside the timed region), the B = 8 points and `cpu_baseline` (the oracle on a sample).
 """
 import argparse
 import json
@@ -176,7 +178,7 @@ def time_steps(torch, fn, steps, warmup):
     return (time.perf_counter() - t0) / steps, last
 
 
-def cpu_baseline(wl, n_seq=4, reps=1):
+def cpu_baseline(wl, n_seq=4, reps=8):
     """The oracle as it stands, timed on the host cores on a bounded sample of the same workload."""
     from oracle.oracle import Oracle
     from synth import gen
