@@ -161,6 +161,28 @@ class Workload:
         self.kv.seq_len.copy_(self.len0)               # harness: same ragged shape for the next repetition
         return int(a.sum()) + self.B
 
+    def device_round(self):
+        """The device side of `step` (everything but the trip to the host), as one callable for a HIP graph."""
+        fg = self.fg
+        if self.draft_ready:
+            self.draft()
+        o = fg.fg_spec_verify(self.gm, self.kv, self.slot, self.tokens_d, self.parent_d, self.ws, want_feature=True,
+                              max_seq_len=self.max_seq_len)
+        acc, path, otok, fin = fg.fg_spec_accept(self.tokens_d, self.parent_d, row_argmax=o["argmax"])
+        fg.fg_kv_compact(self.kv, self.slot, acc, path)
+        self.kv.seq_len.copy_(self.len0)               # harness: same ragged shape for the next repetition
+        return acc
+
+    def step_graph(self):
+        """`step` with the device side recorded once as a HIP graph and replayed (after an eager step has run)."""
+        torch = self.torch
+        if not hasattr(self, "_graph"):
+            self._graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(self._graph):
+                self._graph_acc = self.device_round()
+        self._graph.replay()
+        return int(self._graph_acc.cpu().sum()) + self.B
+
     def verify_only(self):
         self.fg.fg_spec_verify(self.gm, self.kv, self.slot, self.tokens_d, self.parent_d, self.ws, want_feature=True,
                                max_seq_len=self.max_seq_len)
@@ -355,6 +377,7 @@ def main():
     ap.add_argument("--agree", type=float, default=0.7, help="--gen: planted per-node agreement rate")
     ap.add_argument("--mean-len", type=int, default=160, help="--gen: mean response budget")
     ap.add_argument("--c-peak", type=int, default=0, help="--gen, --sweep: use this C_peak instead of the measured knee")
+    ap.add_argument("--graph", action="store_true", help="also time the round with its device side replayed as a HIP graph")
     ap.add_argument("--sweep", action="store_true",
                     help="the metric's range: B = 8 ... 256 on the 7B-class target, each with the shape Eq. 1-3 give")
     args = ap.parse_args()
@@ -423,6 +446,11 @@ def main():
         "step_bytes": acct["bytes"], "step_flops": acct["flops"],
         "roofline": roof,
     }
+    if args.graph:
+        t_graph, emitted_g = time_steps(torch, wl.step_graph, args.steps, args.warmup)
+        assert emitted_g == emitted, (emitted_g, emitted)
+        out["graph_ms_per_step"] = t_graph * 1e3
+        out["graph_value"] = emitted_g / t_graph
     if not args.no_b8 and args.workload == "cfg4" and not args.B:
         # the low end of the metric's range on the same model: B = 8, shapes N = 1 / 6 / 24
         pts = []

@@ -88,8 +88,45 @@ def plain_round(target, draft, kv, dkv, slot, st, root, ws_t, ws_d, eos_id=-1, m
     return acc, otok, fin, SpecState(otok[:, :1].contiguous(), feat[:, :1].contiguous(), acc)
 
 
+class RoundGraph:
+    """One round of a fixed shape (B, N, K, L, pending entries per sequence) recorded once as a HIP graph and replayed:
+    at a small live batch a round is some 350 short launches, and the host's launch rate, not the GPU, sets its
+    pace.  The round's inputs live in buffers the graph owns; `run` copies the caller's state in and replays.  The
+    outputs are graph-owned tensors that the next replay overwrites (the caller reads or copies them first -- the
+    generation loop copies them into the next round's inputs).  Record only after the same calls have run eagerly
+    once (code objects are loaded at a kernel's first launch, which a capture cannot do)."""
+
+    replays = 0     # over all instances (tests and measurements read it)
+
+    def __init__(self, target, draft, kv, dkv, B, N, K, L, kin, ws_t, ws_d, eos_id, max_seq_len):
+        dev = kv.k_pool.device
+        d = target.cfg["d_model"]
+        self.slot = torch.zeros(B, dtype=torch.int32, device=dev)
+        self.st = SpecState(torch.zeros((B, kin), dtype=torch.int32, device=dev),
+                            torch.zeros((B, kin, d), dtype=kv.k_pool.dtype, device=dev),
+                            torch.zeros(B, dtype=torch.int32, device=dev))
+        self.root = torch.zeros(B, dtype=torch.int32, device=dev)
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            if N == 1:
+                self.out = plain_round(target, draft, kv, dkv, self.slot, self.st, self.root, ws_t, ws_d, eos_id, max_seq_len)
+            else:
+                self.out = spec_round(target, draft, kv, dkv, self.slot, self.st, N, K, L, ws_t, ws_d, eos_id, max_seq_len)
+
+    def run(self, slot, st, root=None):
+        self.slot.copy_(slot)
+        self.st.catch_tok.copy_(st.catch_tok)
+        self.st.catch_feat.copy_(st.catch_feat)
+        self.st.last.copy_(st.last)
+        if root is not None:
+            self.root.copy_(root)
+        self.graph.replay()
+        RoundGraph.replays += 1
+        return self.out
+
+
 def generate(target, draft, kv, dkv, slot, st, first, budgets, c_peak, ws_t, ws_d, alpha=0.5, K_max=4, L_max=6, N_cap=64,
-             eos_id=-1, max_seq_len=0, plan=None, max_rounds=10 ** 9, replant=None, decide=None):
+             eos_id=-1, max_seq_len=0, plan=None, max_rounds=10 ** 9, replant=None, decide=None, graphs=False):
     """The concurrency-aware generation loop (Alg. 1): every round (N, K, L) is re-planned from the number of live
     sequences (Eq. 1-3; `plan(B_cur) -> (N, K, L)` overrides the rule, e.g. a fixed shape for comparison), finished
     sequences leave the batch (device rows are re-selected with fg_select_rows), and the host sees only the accepted
@@ -98,6 +135,8 @@ def generate(target, draft, kv, dkv, slot, st, first, budgets, c_peak, ws_t, ws_
     slot int32 [B] (device), st: the draft head's pending entries after the prefill, first int32 [B] (host): the
     token already emitted per sequence, budgets [B] (host): tokens per sequence, first included.
     replant(tokens, parent, live, outs) -> tokens and decide(tokens, parent, row_argmax) -> row_argmax: see spec_round.
+    graphs: replay each round shape as a HIP graph from its second use on (RoundGraph; not with the two hooks, which
+    run host code inside the round; max_seq_len should then be a bound that holds for the whole rollout).
     Returns (token lists, per-round history of dicts B, N, K, L, emitted).
     """
     B = len(first)
@@ -106,6 +145,7 @@ def generate(target, draft, kv, dkv, slot, st, first, budgets, c_peak, ws_t, ws_
     keep = [b for b in range(B) if budgets[b] > 1]
     live = list(range(B))
     hist = []
+    seen, recorded = {}, {}      # round shapes met so far, and their recorded graphs
 
     def reselect(rows):
         nonlocal slot, st
@@ -119,12 +159,18 @@ def generate(target, draft, kv, dkv, slot, st, first, budgets, c_peak, ws_t, ws_
     while live and len(hist) < max_rounds:
         Bc = len(live)
         N, K, L = plan(Bc) if plan else fg.fg_plan(Bc, c_peak, alpha, K_max, L_max, N_cap)
-        if N == 1:
-            root = torch.as_tensor(np.array([outs[b][-1] for b in live], dtype=np.int32)).to(dev)
+        root = torch.as_tensor(np.array([outs[b][-1] for b in live], dtype=np.int32)).to(dev) if N == 1 else None
+        key = (Bc, N, K, L, st.catch_tok.shape[1])
+        if graphs and replant is None and decide is None and seen.get(key, 0) >= 1:
+            if key not in recorded:
+                recorded[key] = RoundGraph(target, draft, kv, dkv, Bc, N, K, L, key[4], ws_t, ws_d, eos_id, max_seq_len)
+            acc, otok, fin, st = recorded[key].run(slot, st, root)
+        elif N == 1:
             acc, otok, fin, st = plain_round(target, draft, kv, dkv, slot, st, root, ws_t, ws_d, eos_id, max_seq_len)
         else:
             hook = (lambda tk, pr: replant(tk, pr, live, outs)) if replant else None
             acc, otok, fin, st = spec_round(target, draft, kv, dkv, slot, st, N, K, L, ws_t, ws_d, eos_id, max_seq_len, hook, decide)
+        seen[key] = seen.get(key, 0) + 1
         a, t, f = acc.cpu().numpy(), otok.cpu().numpy(), fin.cpu().numpy()     # the round's one trip to the host
         rows, nxt_live, emitted_round = [], [], 0
         for j, b in enumerate(live):

@@ -293,6 +293,21 @@ def test_adaptive_generation_loop_follows_the_oracle(H):
     assert hist == want_hist
     assert any(h["N"] == 1 for h in hist) and any(h["N"] > 1 for h in hist) and hist[-1]["B"] == 1
     print(f"adaptive loop: {len(hist)} rounds, live set {[h['B'] for h in hist][::4]}, N {[h['N'] for h in hist][::4]}", flush=True)
+    # the same rollout with every round shape replayed as a HIP graph from its second use on: fresh caches, same
+    # prefill; replays alternate with the loop's eager work (row re-selection, first uses of new shapes, host copies)
+    kv2, dkv2 = fg.KVCache(model, table, n_pages), fg.KVCache(pair.dcfg, dtable, dn)
+    out2 = fg.fg_spec_verify(pair.gm, kv2, slot, ptok, gloop.chain_parent(B, P, "cuda"), ws_t, want_logits=False)
+    feat2 = fg.fg_kv_compact(kv2, slot, torch.full((B,), P - 1, dtype=torch.int32, device="cuda"), ident,
+                             feature_in=out2["feature"].view(B, P, -1), d_model=model["d_model"])
+    st2 = gloop.SpecState(catch_tok.clone(), feat2, torch.full((B,), P - 1, dtype=torch.int32, device="cuda"))
+    before = gloop.RoundGraph.replays
+    got2, hist2 = gloop.generate(pair.gm, pair.gd, kv2, dkv2, slot, st2, root.cpu().numpy(), budgets, c_peak, ws_t, ws_d,
+                                 alpha=alpha, K_max=K_max, L_max=L_max, max_seq_len=cap, graphs=True)
+    n_replays = gloop.RoundGraph.replays - before
+    assert got2 == got and hist2 == hist
+    assert n_replays >= len(hist) // 3, (n_replays, len(hist))
+    assert torch.equal(kv2.seq_len, kv.seq_len) and torch.equal(dkv2.seq_len, dkv.seq_len)
+    print(f"adaptive loop with recorded rounds: {n_replays} of {len(hist)} rounds replayed", flush=True)
 
 
 def test_select_rows_and_knee(H):
