@@ -377,6 +377,8 @@ def main():
     ap.add_argument("--agree", type=float, default=0.7, help="--gen: planted per-node agreement rate")
     ap.add_argument("--mean-len", type=int, default=160, help="--gen: mean response budget")
     ap.add_argument("--c-peak", type=int, default=0, help="--gen, --sweep: use this C_peak instead of the measured knee")
+    ap.add_argument("--prefill", type=int, default=0, metavar="P",
+                    help="prefill B prompts of P tokens through chain verify steps of 64 positions (target + draft head)")
     ap.add_argument("--graph", action="store_true", help="also time the round with its device side replayed as a HIP graph")
     ap.add_argument("--sweep", action="store_true",
                     help="the metric's range: B = 8 ... 256 on the 7B-class target, each with the shape Eq. 1-3 give")
@@ -394,6 +396,9 @@ def main():
         return
     if args.sweep:
         sweep(args)
+        return
+    if args.prefill:
+        prefill_bench(args)
         return
 
     wl = Workload(args.workload, args.dtype, B=args.B or None, N=args.N or None, n_layers=args.layers or None, verbose=True)
@@ -504,6 +509,41 @@ def sweep(args):
                                              f"planted agreement {cfg['plant_p']}, greedy"},
                       "c_peak": c_peak, "c_peak_latency_ms": None if lat is None else {str(b): t for b, t in zip(sizes, lat)},
                       "points": points}))
+
+
+def prefill_bench(args):
+    """Prompts of P tokens for B sequences through the prefill of the generation loop: chain verify steps of 64
+    positions per sequence (M = 64 B rows per step, the pipelined GEMM and the tree attention kernel with a chain
+    mask), the draft head consuming its entries alongside.  Tokens/s over the whole prefill."""
+    import torch
+    import paper_2509_21792_amd as fg
+    from paper_2509_21792_amd import loop as gloop
+    from synth import configs, gen
+    model = configs.with_dtype(configs.CONFIGS["cfg4"]["model"], args.dtype)
+    B, P = args.B or 64, args.prefill
+    gm = fg.Model(model, gen.make_weights(model, 0, device="cuda"))
+    dcfg = configs.draft_of(model)
+    gd = fg.Model(dcfg, gen.make_weights(dcfg, 0, device="cuda", draft=True), target=gm)
+    table, n_pages = gen.make_page_table(np.zeros(B, np.int32), P + 80, 16, 1)
+    dtable, dn = gen.make_page_table(np.zeros(B, np.int32), P + 80, 16, 2)
+    kv, dkv = fg.KVCache(model, table, n_pages), fg.KVCache(dcfg, dtable, dn)
+    slot = torch.arange(B, dtype=torch.int32, device="cuda")
+    ws_t, ws_d = gm.workspace(B * 64, P + 80), gd.workspace(B * 64, P + 80)
+    prompts = torch.randint(0, model["vocab"], (B, P), dtype=torch.int32, device="cuda",
+                            generator=torch.Generator(device="cuda").manual_seed(3))
+
+    def run():
+        kv.seq_len.zero_()
+        dkv.seq_len.zero_()
+        gloop.prefill(gm, gd, kv, dkv, slot, prompts, ws_t, ws_d, max_seq_len=P + 64)
+    t, _ = time_steps(torch, run, max(2, args.steps // 5), 1)
+    acct = model_bytes_flops(model, B * P, np.zeros(1), 1)
+    attn_flops = 4.0 * model["n_q_heads"] * model["head_dim"] * model["n_layers"] * B * P * (P + 1) / 2.0
+    flops = acct["gemm_flops"] - 2.0 * B * P * model["vocab"] * model["d_model"] + attn_flops   # no LM head but for the last step
+    print(json.dumps({"metric": "prefill tokens/s (chain verify steps of 64 positions, target + draft head)", "unit": "tokens/s",
+                      "value": B * P / t, "n_gpus": 1, "dtype": args.dtype, "data": "synthetic",
+                      "config": {"workload": f"{model['name']} {model['n_layers']} layers, {B} prompts of {P} tokens"},
+                      "seconds": t, "mfma_frac": flops / t / PEAK_MFMA}))
 
 
 def b8_point(wl, N, args):

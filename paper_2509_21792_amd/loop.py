@@ -234,7 +234,8 @@ def prefill(target, draft, kv, dkv, slot, prompts, ws_t, ws_d, chunk=64, max_seq
         n = min(chunk, P - p0)
         tok = prompts[:, p0:p0 + n].contiguous()
         par = chain_parent(B, n, dev)
-        out = fg.fg_spec_verify(target, kv, slot, tok, par, ws_t, max_seq_len=max_seq_len)
+        last = p0 + n >= P      # only the last chunk's logits are needed (the first generated token)
+        out = fg.fg_spec_verify(target, kv, slot, tok, par, ws_t, max_seq_len=max_seq_len, want_argmax=last)
         ident = torch.arange(n, dtype=torch.int32, device=dev).repeat(B, 1)
         feat = fg.fg_kv_compact(kv, slot, torch.full((B,), n - 1, dtype=torch.int32, device=dev), ident,
                                 feature_in=out["feature"].view(B, n, d), d_model=d)
@@ -250,6 +251,7 @@ def prefill(target, draft, kv, dkv, slot, prompts, ws_t, ws_d, chunk=64, max_seq
                                  n_commit=torch.full((B,), m, dtype=torch.int32, device=dev), commit_bias=0,
                                  max_seq_len=max_seq_len, want_children=False)
         prev_feat = feat[:, n - 1:n].contiguous()
-        first = out["argmax"].view(B, n)[:, -1].contiguous()
+        if last:
+            first = out["argmax"].view(B, n)[:, -1].contiguous()
     st = SpecState(first.view(B, 1).contiguous(), prev_feat, torch.zeros(B, dtype=torch.int32, device=dev))
     return first, st
