@@ -1,9 +1,10 @@
-// Few-row shape of the 16-bit MFMA GEMM (at most 128 rows per block; short-k shapes take two row blocks): out = X . W^T, bound by the HBM traffic of W.
+// Few-row shape of the 16-bit MFMA GEMM: out = X . W^T for up to 128 rows per block, bound by the HBM traffic of W
+// (short-k shapes of up to 256 rows take two row blocks).
 //
-// A block owns 64 output columns (two 32-column bands of the packed W) and all rows; its four waves split the
-// contraction *inside* the block: of every 64-wide k chunk, wave w takes k tile w (16 wide).  Four waves side by
-// side over 256 columns need a k split across blocks to fill the chip, and every such split is a slab of M x N
-// fp32 written here and read back by the consumer; the split inside the block gives the same number of
+// A block owns 64 output columns (two 32-column bands of the packed W) and up to four 32-row tiles; its four waves
+// split the contraction *inside* the block: of every 64-wide k chunk, wave w takes k tile w (16 wide).  Four waves
+// side by side over 256 columns need a k split across blocks to fill the chip, and every such split is a slab of
+// M x N fp32 written here and read back by the consumer; the split inside the block gives the same number of
 // independent W streams with a quarter of the slabs -- none at all for the wide matrices (gate/up, LM head),
 // so gate/up applies SwiGLU in its own epilogue and needs no separate pass.
 //
