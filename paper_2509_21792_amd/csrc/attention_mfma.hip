@@ -521,6 +521,45 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict
     for (int i = 0; i < HD / 64; i++) out[(size_t)r * Hq * HD + (size_t)hq * HD + lane + 64 * i] = from_f<T>(acc[i] * inv);
 }
 
+// The same combination when there are at most four chunk slots (large batches: a sequence is one to three chunks).
+// A thread owns four consecutive dims of one (row, query head) and recomputes the row's few weights itself, so there
+// is no cross-lane step at all: eight loads per thread, all in flight together, 32 (row, head) pairs per block at
+// head_dim 128 instead of four.  27 -> 14 us per layer at B = 256, N = 8.
+template <typename T, int HD>
+__global__ __launch_bounds__(256) void attn_merge_few_kernel(const float *__restrict__ part_o, const float *__restrict__ part_ml,
+                                                            T *__restrict__ out, int M, int N, int Hq, int Hkv, int QR, int n_chunks)
+{
+    constexpr int TPP = HD / 4;   // threads per (row, head)
+    const int pair = blockIdx.x * (256 / TPP) + threadIdx.x / TPP, e4 = (threadIdx.x % TPP) * 4;
+    if (pair >= M * Hq) return;
+    const int r = pair / Hq, hq = pair % Hq;
+    const int b = r / N, j = r % N, G = Hq / Hkv, hk = hq / G, g = hq % G;
+    const size_t row0 = (((size_t)b * Hkv + hk) * n_chunks) * QR + (j * G + g);   // chunk ch is row0 + ch * QR
+    float2 ml[4];
+    f32x4_t v[4];
+#pragma unroll
+    for (int c = 0; c < 4; c++) {
+        const size_t row = row0 + (size_t)min(c, n_chunks - 1) * QR;   // clamped: the surplus copies are not used
+        ml[c] = *reinterpret_cast<const float2 *>(part_ml + row * 2);
+        v[c] = *reinterpret_cast<const f32x4_t *>(part_o + row * HD + e4);
+    }
+    float m = -INFINITY;
+#pragma unroll
+    for (int c = 0; c < 4; c++)
+        if (c < n_chunks && ml[c].y > 0.f) m = fmaxf(m, ml[c].x);
+    float den = 0.f;
+    f32x4_t acc = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < 4; c++) {
+        const float w = (c < n_chunks && ml[c].y > 0.f) ? __expf(ml[c].x - m) : 0.f;
+        den += ml[c].y * w;
+        if (w != 0.f) acc += v[c] * w;   // O of an empty chunk may hold anything
+    }
+    const float inv = den > 0.f ? 1.f / den : 0.f;
+    *reinterpret_cast<uint2 *>(out + (size_t)r * Hq * HD + (size_t)hq * HD + e4) =
+        make_uint2(pack2<T>(acc[0] * inv, acc[1] * inv), pack2<T>(acc[2] * inv, acc[3] * inv));
+}
+
 bool attention_mfma_supported(const fg_kv_cache *kv, int Hq, int N)
 {
     return is16(kv->dtype) && (kv->head_dim == 128 || kv->head_dim == 64) && kv->page_size == 16 &&
@@ -564,8 +603,12 @@ static int32_t launch_typed(const fg_kv_cache *kv, int layer, const fg_tree *t, 
     else FG_ATTN_LAUNCH(false);
 #undef FG_ATTN_LAUNCH
     FG_LAUNCH_CHECK("attn_mfma");
-    hipLaunchKernelGGL((attn_merge_kernel<T, HD>), dim3(B * N, (Hq + 3) / 4), dim3(256), 0, st, part_o, part_ml,
-                       (T *)out, N, Hq, Hkv, p.QR, p.n_chunks);
+    if (p.n_chunks <= 4)
+        hipLaunchKernelGGL((attn_merge_few_kernel<T, HD>), dim3((unsigned)(((int64_t)B * N * Hq + 256 / (HD / 4) - 1) / (256 / (HD / 4)))),
+                           dim3(256), 0, st, part_o, part_ml, (T *)out, B * N, N, Hq, Hkv, p.QR, p.n_chunks);
+    else
+        hipLaunchKernelGGL((attn_merge_kernel<T, HD>), dim3(B * N, (Hq + 3) / 4), dim3(256), 0, st, part_o, part_ml,
+                           (T *)out, N, Hq, Hkv, p.QR, p.n_chunks);
     FG_LAUNCH_CHECK("attn_merge");
     return FG_OK;
 }
