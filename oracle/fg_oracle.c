@@ -29,6 +29,10 @@
  *   orc_gumbel_scores  chi-square against softmax(logits/T)
  *   orc_topk_logp      scipy logsumexp + argsort on small cases
  *   orc_build_tree     brute force on tiny candidate sets
+ *   orc_topk_index + the frontier / candidate-list bookkeeping of
+ *   oracle/loop.py: draft_expand
+ *                      brute force over every token path of a tiny vocabulary
+ *                      (tests/test_oracle_draft_expand.py)
  *   orc_knee           exact break point of two-segment curves; invariance
  *                      under affine maps of either axis
  *   draft head internals (fc + one layer, no final norm): fixed by this
