@@ -361,6 +361,63 @@ def gen_experiment(args):
     print(json.dumps(out))
 
 
+def ceilings(args):
+    """--ceilings: what this GPU sustains for the two resources the path is bound by, next to the nominal peaks:
+    a read-only stream and a plain copy over buffers far larger than the last-level cache, and a register-resident
+    MFMA loop on every SIMD (short bursts and a sustained run, where the clock settles under the power limit)."""
+    import torch
+    import paper_2509_21792_amd as fg
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+
+    nbytes = 4 << 30
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    src.random_(0, 255)
+    dst = torch.empty(nbytes // 2, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(1 << 20, dtype=torch.float32, device="cuda")
+    out = {"metric": "achievable ceilings (measured) next to the nominal peaks", "n_gpus": 1, "data": "synthetic",
+           "config": {"workload": "ceiling probes: 4 GiB read stream, 2 GiB copy, register-resident MFMA loop"},
+           "nominal": {"hbm_GBps": PEAK_HBM / 1e9, "mfma_16bit_TFLOPs": PEAK_MFMA / 1e12}}
+    reads = {}
+    for nt in (0, 1):
+        for blocks in (1024, 2048, 4096, 8192, 16384):
+            t = timed(lambda: fg.fg_probe_read(src, nt, blocks, sink), 5)
+            reads[f"{'nontemporal' if nt else 'plain'}_{blocks}_blocks"] = nbytes / t / 1e9
+    out["hbm_read_GBps"] = reads
+    out["hbm_read_best_GBps"] = max(reads.values())
+    copies = {}
+    half = src[:nbytes // 2]
+    for blocks in (2048, 4096, 8192, 16384):
+        t = timed(lambda: fg.fg_probe_copy(half, dst, blocks), 5)
+        copies[f"{blocks}_blocks"] = 2 * (nbytes // 2) / t / 1e9
+    out["hbm_copy_GBps_read_plus_write"] = copies
+    out["hbm_copy_best_GBps"] = max(copies.values())
+    mf = {}
+    flop_per_wave_iter = 16 * 2.0 * 32 * 32 * 16
+    for name, code in (("bf16", fg.FG_BF16), ("fp16", fg.FG_F16)):
+        for rnd in (1, 0):                      # hashed operands that toggle the buses like real data / constant ones
+            for wps in (1, 2):                  # waves per SIMD: 256 CUs x 4 SIMDs x wps waves
+                blocks = 256 * wps
+                for label, iters, reps in (("burst_1ms", 4000 // wps, 3), ("sustained_200ms", 80000 // wps, 10)):
+                    t = timed(lambda: fg.fg_probe_mfma(code, iters, rnd, blocks, sink), reps)
+                    tf = blocks * 4 * iters * flop_per_wave_iter / t / 1e12
+                    mf[f"{name}_{'random' if rnd else 'constant'}_operands_{wps}_waves_per_simd_{label}"] = dict(
+                        TFLOPs=tf, implied_clock_GHz=tf / (PEAK_MFMA / 1e12) * 2.4, ms_per_launch=t * 1e3)
+    out["mfma_loop"] = mf
+    out["mfma_sustained_best_TFLOPs"] = max(v["TFLOPs"] for k, v in mf.items() if "sustained" in k and "random" in k)
+    out["mfma_burst_best_TFLOPs"] = max(v["TFLOPs"] for k, v in mf.items() if "burst" in k and "random" in k)
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -382,6 +439,8 @@ def main():
     ap.add_argument("--graph", action="store_true", help="also time the round with its device side replayed as a HIP graph")
     ap.add_argument("--sweep", action="store_true",
                     help="the metric's range: B = 8 ... 256 on the 7B-class target, each with the shape Eq. 1-3 give")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="measure the achievable HBM stream rate and MFMA rate of this GPU (probe kernels) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: every box of this build has one MI355X and the path shards by sequence "
@@ -391,6 +450,9 @@ def main():
     import paper_2509_21792_amd as fg
     fg.lib()
     assert torch.cuda.is_available(), "no GPU: the HIP path has no CPU fallback"
+    if args.ceilings:
+        ceilings(args)
+        return
     if args.gen:
         gen_experiment(args)
         return

@@ -304,6 +304,21 @@ int32_t fg_topk_logp(const float *logits, int32_t M, int32_t vocab, int32_t K, i
 int32_t fg_profile_gemm(int32_t enable, int32_t rows, int32_t n_out, int32_t n_in, int32_t epilogue, int32_t max_launches);
 int32_t fg_profile_read(double *total_ms, int32_t *count);
 
+/*
+ * Ceiling probes (measurement only): what the GPU sustains for the two resources the path is bound by.
+ * fg_probe_read: `blocks` blocks of 256 threads stream `bytes` (a multiple of 16) from src with 16-byte loads, four in
+ *   flight per lane, ordinary or non-temporal; sink: device, blocks * 4 bytes (written only on a magic checksum).
+ * fg_probe_copy: the same stream written to dst (the plain copy whose FETCH_SIZE / WRITE_SIZE counter readings scale
+ *   the traffic figures of the other kernels).
+ * fg_probe_mfma: blocks x 4 waves each issue iters * 16 v_mfma_f32_32x32x16 (dtype FG_BF16 or FG_F16) on operands that
+ *   never leave registers: iters * 16 * 32768 flop per wave; random_operands != 0 rotates four hashed fragment pairs
+ *   (operand buses toggle as on real data, which sets the power draw and so the sustained clock), 0 uses one constant
+ *   pair; sink: device, blocks * 1024 bytes (practically never written).
+ */
+int32_t fg_probe_read(const void *src, int64_t bytes, int32_t nontemporal, int32_t blocks, void *sink, void *stream);
+int32_t fg_probe_copy(const void *src, void *dst, int64_t bytes, int32_t blocks, void *stream);
+int32_t fg_probe_mfma(int32_t dtype, int32_t iters, int32_t random_operands, int32_t blocks, void *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,7 @@ EXPORTS = ["fg_last_error", "fg_plan", "fg_packed_bytes", "fg_pack_weight", "fg_
            "fg_workspace_bytes", "fg_spec_verify", "fg_spec_accept", "fg_kv_compact", "fg_draft_step",
            "fg_draft_frontier", "fg_build_tree", "fg_gemm", "fg_attention", "fg_attention_workspace_bytes",
            "fg_topk_logp", "fg_knee", "fg_select_rows", "fg_profile_gemm",
-           "fg_profile_read"]
+           "fg_profile_read", "fg_probe_read", "fg_probe_copy", "fg_probe_mfma"]
 
 
 class FgError(RuntimeError):
@@ -77,6 +77,9 @@ def lib():
         L.fg_spec_accept.argtypes = [C.POINTER(TreeC), C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_void_p,
                                      C.c_void_p, C.c_uint64, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        L.fg_probe_read.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        L.fg_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p]
+        L.fg_probe_mfma.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.fg_kv_compact.argtypes = [C.POINTER(KvCacheC), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                     C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
         L.fg_draft_step.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(KvCacheC), C.POINTER(TreeC), C.c_void_p, C.c_void_p,
@@ -423,6 +426,19 @@ def fg_profile_read():
     tot, cnt = C.c_double(), C.c_int32()
     _check(lib().fg_profile_read(C.byref(tot), C.byref(cnt)))
     return tot.value, cnt.value
+
+
+# ---- ceiling probes ---------------------------------------------------------------------------------------------
+def fg_probe_read(src, nontemporal, blocks, sink):
+    _check(lib().fg_probe_read(_p(src), src.numel() * src.element_size(), int(nontemporal), blocks, _p(sink), _stream()))
+
+
+def fg_probe_copy(src, dst, blocks):
+    _check(lib().fg_probe_copy(_p(src), _p(dst), src.numel() * src.element_size(), blocks, _stream()))
+
+
+def fg_probe_mfma(dtype, iters, random_operands, blocks, sink):
+    _check(lib().fg_probe_mfma(dtype, iters, int(random_operands), blocks, _p(sink), _stream()))
 
 
 # ---- kernel-level ---------------------------------------------------------------------------------------------

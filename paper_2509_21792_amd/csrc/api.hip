@@ -56,6 +56,9 @@ int32_t launch_commit_len(int32_t *seq_len, const int32_t *slot, const int32_t *
 int gemm_mfma_split_for(int M, int N, int K);
 bool gemm_mfma_uses_big(int M, int N);
 bool gemm_mfma_fuses_swiglu(int M, int N, int K);
+int32_t launch_probe_read(const void *src, int64_t bytes, int nontemporal, int blocks, void *sink, hipStream_t st);
+int32_t launch_probe_copy(const void *src, void *dst, int64_t bytes, int blocks, hipStream_t st);
+int32_t launch_probe_mfma(int32_t dtype, int iters, int random, int blocks, void *sink, hipStream_t st);
 int32_t profile_gemm_arm(int enable, int rows, int n_out, int n_in, int epilogue, int max_launches);
 int32_t profile_gemm_read(double *total_ms, int32_t *count);
 
@@ -593,6 +596,24 @@ int32_t fg_profile_read(double *total_ms, int32_t *count)
 {
     if (!total_ms || !count) return fail(FG_ERR_INVALID_ARG, "fg_profile_read: NULL output");
     return profile_gemm_read(total_ms, count);
+}
+
+int32_t fg_probe_read(const void *src, int64_t bytes, int32_t nontemporal, int32_t blocks, void *sink, void *stream)
+{
+    if (!src || !sink || bytes < 16 || bytes % 16 || blocks < 1) return fail(FG_ERR_INVALID_ARG, "fg_probe_read: bad argument");
+    return launch_probe_read(src, bytes, nontemporal, blocks, sink, (hipStream_t)stream);
+}
+
+int32_t fg_probe_copy(const void *src, void *dst, int64_t bytes, int32_t blocks, void *stream)
+{
+    if (!src || !dst || bytes < 16 || bytes % 16 || blocks < 1) return fail(FG_ERR_INVALID_ARG, "fg_probe_copy: bad argument");
+    return launch_probe_copy(src, dst, bytes, blocks, (hipStream_t)stream);
+}
+
+int32_t fg_probe_mfma(int32_t dtype, int32_t iters, int32_t random_operands, int32_t blocks, void *sink, void *stream)
+{
+    if (!is16(dtype) || !sink || iters < 1 || blocks < 1) return fail(FG_ERR_INVALID_ARG, "fg_probe_mfma: bad argument");
+    return launch_probe_mfma(dtype, iters, random_operands, blocks, sink, (hipStream_t)stream);
 }
 
 int64_t fg_attention_workspace_bytes(int32_t B, int32_t N, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
