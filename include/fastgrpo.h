@@ -205,6 +205,23 @@ int32_t fg_spec_accept(const fg_tree *tree, int32_t mode, const float *logits, c
                        void *stream);
 
 /*
+ * fg_spec_accept for callers that cannot allocate device memory or hand over a workspace: code running under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, outputs and errors as
+ * fg_spec_accept minus the workspace: the per-row target tokens (greedy from logits, sample match) or the p / q
+ * vectors (rejection mode) live in a static device array of FG_STATIC_SCRATCH_BYTES that each GPU holds from the
+ * first use of the library until the process ends.  Calls that need more (B * N * 4 bytes, or B * 2 * vocab * 4 in
+ * rejection mode) fail with FG_ERR_CAPACITY.  It calls no allocator.  The array's device address is looked up once
+ * per device (at fg_model_create, else at the first call on that device; do that first call outside a capture).
+ * All calls on one GPU share the array: calls that overlap in time on one GPU (different streams or threads) race;
+ * calls on one stream are ordered and every call rewrites what it reads, so nothing needs clearing between calls.
+ */
+enum { FG_STATIC_SCRATCH_BYTES = 4 << 20 };
+int32_t fg_spec_accept_static(const fg_tree *tree, int32_t mode, const float *logits, const int32_t *row_argmax,
+                              int32_t vocab, float temperature, const float *draft_probs, const float *uniforms,
+                              uint64_t seed, int64_t row0, int32_t eos_id, int32_t *accept_len, int32_t *path,
+                              int32_t *out_tokens, int32_t *finished, void *stream);
+
+/*
  * KV compaction in place (implied by Alg. 1 "update S_generated": rejected nodes are dropped).  For sequence b
  * with committed length L: in-round slot L + path[b][j] moves to L + j for j = 0..accept_len[b], K and V of
  * every layer and head; then seq_len += accept_len[b] + 1.  path rows must increase strictly with

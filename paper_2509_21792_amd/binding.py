@@ -21,7 +21,8 @@ EXPORTS = ["fg_last_error", "fg_plan", "fg_packed_bytes", "fg_pack_weight", "fg_
            "fg_workspace_bytes", "fg_spec_verify", "fg_spec_accept", "fg_kv_compact", "fg_draft_step",
            "fg_draft_frontier", "fg_build_tree", "fg_gemm", "fg_attention", "fg_attention_workspace_bytes",
            "fg_topk_logp", "fg_knee", "fg_select_rows", "fg_profile_gemm",
-           "fg_profile_read", "fg_probe_read", "fg_probe_copy", "fg_probe_mfma"]
+           "fg_profile_read", "fg_spec_accept_static", "fg_probe_read", "fg_probe_copy", "fg_probe_mfma"]
+STATIC_SCRATCH_BYTES = 4 << 20
 
 
 class FgError(RuntimeError):
@@ -77,6 +78,7 @@ def lib():
         L.fg_spec_accept.argtypes = [C.POINTER(TreeC), C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_void_p,
                                      C.c_void_p, C.c_uint64, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        L.fg_spec_accept_static.argtypes = L.fg_spec_accept.argtypes[:15] + [C.c_void_p]
         L.fg_probe_read.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.fg_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p]
         L.fg_probe_mfma.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
@@ -317,6 +319,22 @@ def fg_spec_accept(tokens, parent, mode=ACCEPT_GREEDY, logits=None, row_argmax=N
                                 _p(uniforms), seed, row0, eos_id, _p(acc), _p(path), _p(out), _p(fin), _p(workspace),
                                 workspace.numel(), _stream()))
     return acc, path, out, fin
+
+
+def fg_spec_accept_static(tokens, parent, mode=ACCEPT_GREEDY, logits=None, row_argmax=None, vocab=0, temperature=1.0,
+                          draft_probs=None, uniforms=None, seed=0, row0=0, eos_id=-1, out=None):
+    """fg_spec_accept on the library's static scratch.  `out` = (accept_len, path, out_tokens, finished) tensors to
+    write into (a caller that may not allocate passes them); allocated here otherwise."""
+    dev = tokens.device
+    B, N = tokens.shape
+    if out is None:
+        out = (torch.empty(B, dtype=torch.int32, device=dev), torch.empty((B, N), dtype=torch.int32, device=dev),
+               torch.empty((B, N), dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev))
+    acc, path, otok, fin = out
+    tree = _tree(None, tokens, parent, B, N, 0, 0)
+    _check(lib().fg_spec_accept_static(C.byref(tree), mode, _p(logits), _p(row_argmax), vocab, temperature, _p(draft_probs),
+                                       _p(uniforms), seed, row0, eos_id, _p(acc), _p(path), _p(otok), _p(fin), _stream()))
+    return acc, path, otok, fin
 
 
 def fg_kv_compact(kv, slot, accept_len, path, feature_in=None, d_model=0):

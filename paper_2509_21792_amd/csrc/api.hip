@@ -249,6 +249,31 @@ int32_t run_layers(const fg_model *m, fg_kv_cache *kv, const fg_tree *t, const S
     return FG_OK;
 }
 
+// ---- scratch of the allocation-free entry point -----------------------------------------------------------------
+// A file-scope device array: every GPU the library runs on holds its own copy from the moment the code object is
+// loaded until the process ends.  In host code the array's name is only a handle for the runtime; its device
+// address is looked up once per device and kept, and only that address is ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[FG_STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[MAX_DEVICES] = {};
+
+int32_t scratch_of_current_device(void **out)
+{
+    int dev = -1;
+    FG_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(FG_ERR_CAPACITY, "device index %d beyond %d", dev, MAX_DEVICES);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        FG_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(FG_ERR_HIP, "hipGetSymbolAddress returned a null address for the scratch array");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return FG_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -367,6 +392,8 @@ int32_t fg_model_create(const fg_model_cfg *cfg, const fg_weights *w, fg_model *
         delete m;
         return fail(FG_ERR_HIP, "RoPE table: %s", hipGetErrorString(e));
     }
+    void *scratch_ptr = nullptr;
+    (void)scratch_of_current_device(&scratch_ptr);   // set-up: the allocation-free entry point finds its address resolved
     *out = m;
     return FG_OK;
 }
@@ -469,6 +496,26 @@ int32_t fg_spec_accept(const fg_tree *tree, int32_t mode, const float *logits, c
                              eos_id, (float *)workspace, accept_len, path, out_tokens, finished, st);
     }
     return fail(FG_ERR_INVALID_ARG, "unknown acceptance mode %d", mode);
+}
+
+int32_t fg_spec_accept_static(const fg_tree *tree, int32_t mode, const float *logits, const int32_t *row_argmax, int32_t vocab,
+                              float temperature, const float *draft_probs, const float *uniforms, uint64_t seed, int64_t row0,
+                              int32_t eos_id, int32_t *accept_len, int32_t *path, int32_t *out_tokens, int32_t *finished,
+                              void *stream)
+{
+    if (!tree) return fail(FG_ERR_INVALID_ARG, "tree is NULL");
+    if (tree->B < 0 || tree->N < 0) return fail(FG_ERR_INVALID_ARG, "negative B / N");
+    int64_t need = 0;
+    if (mode == FG_ACCEPT_REJECT) need = (int64_t)tree->B * 2 * (vocab > 0 ? vocab : 0) * 4;
+    else if (mode == FG_ACCEPT_SAMPLE_MATCH || !row_argmax) need = (int64_t)tree->B * tree->N * 4;
+    if (need > FG_STATIC_SCRATCH_BYTES)
+        return fail(FG_ERR_CAPACITY, "fg_spec_accept_static: this call needs %lld bytes of scratch, the static array holds %d "
+                                     "(use fg_spec_accept with a caller-provided workspace)", (long long)need, (int)FG_STATIC_SCRATCH_BYTES);
+    void *ptr = nullptr;
+    int32_t rc;
+    if ((rc = scratch_of_current_device(&ptr))) return rc;
+    return fg_spec_accept(tree, mode, logits, row_argmax, vocab, temperature, draft_probs, uniforms, seed, row0, eos_id,
+                          accept_len, path, out_tokens, finished, ptr, FG_STATIC_SCRATCH_BYTES, stream);
 }
 
 int32_t fg_kv_compact(fg_kv_cache *kv, const int32_t *slot, const int32_t *accept_len, const int32_t *path, int32_t B, int32_t N,
