@@ -298,6 +298,11 @@ int32_t fg_build_tree(const int32_t *cand_tok, const int32_t *cand_parent, const
  *   epilogue 0: out fp32 [split_k][M][n_out] partial sums (split_k >= 1; 0 lets the library choose and
  *               returns the value through *split_k_used); the caller adds the slabs.
  *   epilogue 1: W is a gate/up interleaved matrix; out[M, n_out / 2] in dtype = silu(gate) * up.
+ *   epilogue 3: out fp32 [M, n_out] += x . W^T in place (the residual add of the O and down projections; 16-bit
+ *               dtypes, pipelined kernel only).
+ *   variant: 0 = the kernel the library picks for the shape; 1 = weight-streaming kernel, 2 = few-row kernel (at most
+ *               512 rows), 3 / 4 / 5 = pipelined kernel with 256- / 128- / 160-row blocks.  16-bit dtypes only.
+ * fg_gemm_kernel_name: the kernel the library picks for a 16-bit GEMM of this shape and epilogue (a static string).
  * fg_attention: tree attention of already-rotated queries q [B*N, Hq*hd] (dtype) over the cache, which must
  *   already hold the in-round nodes' K/V; out [B*N, Hq*hd] (dtype).
  * fg_topk_logp: the draft's per-node expansion (Sec. 2, draft tree construction): for each of the M rows of
@@ -305,7 +310,8 @@ int32_t fg_build_tree(const int32_t *cand_tok, const int32_t *cand_parent, const
  *   and their log-softmax values logp [M, K] (fp32).  1 <= K <= 8, K <= vocab.
  */
 int32_t fg_gemm(int32_t dtype, const void *x, const void *w_packed, void *out, int32_t M, int32_t n_out,
-                int32_t n_in, int32_t epilogue, int32_t split_k, int32_t *split_k_used, void *stream);
+                int32_t n_in, int32_t epilogue, int32_t split_k, int32_t *split_k_used, int32_t variant, void *stream);
+const char *fg_gemm_kernel_name(int32_t M, int32_t n_out, int32_t n_in, int32_t epilogue);
 int32_t fg_attention(const fg_kv_cache *kv, int32_t layer, const fg_tree *tree, int32_t n_q_heads, const void *q,
                      void *out, void *workspace, int64_t workspace_bytes, void *stream);
 int64_t fg_attention_workspace_bytes(int32_t B, int32_t N, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
@@ -313,13 +319,17 @@ int64_t fg_attention_workspace_bytes(int32_t B, int32_t N, int32_t n_q_heads, in
 int32_t fg_topk_logp(const float *logits, int32_t M, int32_t vocab, int32_t K, int32_t *tok, float *logp, void *stream);
 
 /*
- * Measurement hook (for benchmarks, not part of the method): while armed, every 16-bit GEMM launch whose
- * (rows, n_out, n_in, epilogue) match (rows = 0 matches any row count) is bracketed by HIP events on its own stream, up to max_launches launches.
- * fg_profile_read waits for them, returns their summed duration in milliseconds and their number, and
- * resets the counter.  Not thread-safe; enable = 0 disarms.
+ * Stage timing of one model (measurement only, off by default).  While enabled, the entry points that run this model
+ * (fg_spec_verify for a target, fg_draft_step for a draft head) record a HIP event on their stream before every group
+ * of launches and one at their end, at most max_marks in all; the time between two consecutive events is charged to
+ * the stage the first announces, so the stages of a call add up to the call.  fg_model_profile_read waits for the last
+ * event, fills ms[FG_STAGE_COUNT] and launches[FG_STAGE_COUNT] (host arrays) and starts a new collection.  A model is
+ * driven from one thread (one stream) at a time, and so is its timing.  Not to be enabled under graph capture.
  */
-int32_t fg_profile_gemm(int32_t enable, int32_t rows, int32_t n_out, int32_t n_in, int32_t epilogue, int32_t max_launches);
-int32_t fg_profile_read(double *total_ms, int32_t *count);
+enum { FG_STAGE_END = -1, FG_STAGE_PREP = 0, FG_STAGE_NORM, FG_STAGE_QKV, FG_STAGE_ROPE, FG_STAGE_ATTENTION, FG_STAGE_O,
+       FG_STAGE_GATE_UP, FG_STAGE_SWIGLU, FG_STAGE_DOWN, FG_STAGE_LM_HEAD, FG_STAGE_SELECT, FG_STAGE_FC, FG_STAGE_COUNT };
+int32_t fg_model_profile(fg_model *m, int32_t enable, int32_t max_marks);
+int32_t fg_model_profile_read(fg_model *m, double *ms, int32_t *launches);
 
 /*
  * Ceiling probes (measurement only): what the GPU sustains for the two resources the path is bound by.

@@ -20,8 +20,8 @@ LIB_PATH = os.path.join(_HERE, "libfastgrpo.so")
 EXPORTS = ["fg_last_error", "fg_plan", "fg_packed_bytes", "fg_pack_weight", "fg_model_create", "fg_model_destroy",
            "fg_workspace_bytes", "fg_spec_verify", "fg_spec_accept", "fg_kv_compact", "fg_draft_step",
            "fg_draft_frontier", "fg_build_tree", "fg_gemm", "fg_attention", "fg_attention_workspace_bytes",
-           "fg_topk_logp", "fg_knee", "fg_select_rows", "fg_profile_gemm",
-           "fg_profile_read", "fg_spec_accept_static", "fg_probe_read", "fg_probe_copy", "fg_probe_mfma"]
+           "fg_topk_logp", "fg_knee", "fg_select_rows", "fg_model_profile",
+           "fg_model_profile_read", "fg_gemm_kernel_name", "fg_spec_accept_static", "fg_probe_read", "fg_probe_copy", "fg_probe_mfma"]
 STATIC_SCRATCH_BYTES = 4 << 20
 
 
@@ -96,7 +96,11 @@ def lib():
         L.fg_build_tree.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.fg_gemm.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
-                              C.c_int32, C.POINTER(C.c_int32), C.c_void_p]
+                              C.c_int32, C.POINTER(C.c_int32), C.c_int32, C.c_void_p]
+        L.fg_gemm_kernel_name.restype = C.c_char_p
+        L.fg_gemm_kernel_name.argtypes = [C.c_int32] * 4
+        L.fg_model_profile.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+        L.fg_model_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
         L.fg_attention.argtypes = [C.POINTER(KvCacheC), C.c_int32, C.POINTER(TreeC), C.c_int32, C.c_void_p, C.c_void_p,
                                    C.c_void_p, C.c_int64, C.c_void_p]
         _lib = L
@@ -435,15 +439,24 @@ def fg_select_rows(src, index):
     return dst
 
 
-# ---- measurement hook -------------------------------------------------------------------------------------------
-def fg_profile_gemm(enable, n_out=0, n_in=0, epilogue=0, max_launches=4096, rows=0):
-    _check(lib().fg_profile_gemm(int(enable), rows, n_out, n_in, epilogue, max_launches))
+# ---- stage timing ------------------------------------------------------------------------------------------------
+STAGES = ["prep", "norm", "qkv", "rope", "attention", "o", "gate_up", "swiglu", "down", "lm_head", "select", "fc"]
 
 
-def fg_profile_read():
-    tot, cnt = C.c_double(), C.c_int32()
-    _check(lib().fg_profile_read(C.byref(tot), C.byref(cnt)))
-    return tot.value, cnt.value
+def fg_model_profile(model, enable, max_marks=1 << 16):
+    _check(lib().fg_model_profile(model.handle, int(enable), max_marks))
+
+
+def fg_model_profile_read(model):
+    """{stage: (milliseconds, launches)} since the last read."""
+    n = len(STAGES)
+    ms, cnt = (C.c_double * n)(), (C.c_int32 * n)()
+    _check(lib().fg_model_profile_read(model.handle, ms, cnt))
+    return {STAGES[i]: (ms[i], cnt[i]) for i in range(n)}
+
+
+def fg_gemm_kernel_name(M, n_out, n_in, epilogue=0):
+    return lib().fg_gemm_kernel_name(M, n_out, n_in, epilogue).decode()
 
 
 # ---- ceiling probes ---------------------------------------------------------------------------------------------
@@ -460,18 +473,22 @@ def fg_probe_mfma(dtype, iters, random_operands, blocks, sink):
 
 
 # ---- kernel-level ---------------------------------------------------------------------------------------------
-def fg_gemm(dtype, x, w_packed, n_out, epilogue=0, split_k=0):
+def fg_gemm(dtype, x, w_packed, n_out, epilogue=0, split_k=0, variant=0, out=None):
+    """epilogue 0: returns (slabs [split, M, n_out] fp32, split): the caller adds the slabs.  1: (silu(gate) * up, 1).
+    3: `out` fp32 [M, n_out] is updated in place and returned."""
     x = x.contiguous()
     M, n_in = x.shape
     used = C.c_int32(1)
     if epilogue == 0:
         smax = 16 if split_k == 0 else split_k
         out = torch.empty((smax, M, n_out), dtype=torch.float32, device=x.device)
-    else:
+    elif epilogue == 1:
         out = torch.empty((M, n_out // 2), dtype=x.dtype, device=x.device)
-    _check(lib().fg_gemm(dtype, _p(x), _p(w_packed), _p(out), M, n_out, n_in, epilogue, split_k, C.byref(used), _stream()))
+    else:
+        assert out is not None and out.dtype == torch.float32 and out.shape == (M, n_out) and out.is_contiguous()
+    _check(lib().fg_gemm(dtype, _p(x), _p(w_packed), _p(out), M, n_out, n_in, epilogue, split_k, C.byref(used), variant, _stream()))
     if epilogue == 0:
-        return out[:used.value].sum(dim=0) if used.value > 1 else out[0], used.value
+        return out[:used.value], used.value
     return out, 1
 
 

@@ -54,17 +54,25 @@ int32_t launch_build_tree(const int32_t *cand_tok, const int32_t *cand_parent, c
 int32_t launch_commit_len(int32_t *seq_len, const int32_t *slot, const int32_t *n_commit, int bias, int B, int n_slots,
                           hipStream_t st);
 int gemm_mfma_split_for(int M, int N, int K);
-bool gemm_mfma_uses_big(int M, int N);
 bool gemm_mfma_fuses_swiglu(int M, int N, int K);
 int32_t launch_probe_read(const void *src, int64_t bytes, int nontemporal, int blocks, void *sink, hipStream_t st);
 int32_t launch_probe_copy(const void *src, void *dst, int64_t bytes, int blocks, hipStream_t st);
 int32_t launch_probe_mfma(int32_t dtype, int iters, int random, int blocks, void *sink, hipStream_t st);
-int32_t profile_gemm_arm(int enable, int rows, int n_out, int n_in, int epilogue, int max_launches);
-int32_t profile_gemm_read(double *total_ms, int32_t *count);
+const char *gemm_mfma_kernel_name(int M, int N, int K, int epilogue);
 
 }  // namespace fg
 
 using namespace fg;
+
+// Stage timing of one model (fg_model_profile): an event is recorded before every launch group of the entry points
+// that run this model, and one at their end; the time between two consecutive events belongs to the stage the
+// first one announces.
+struct StageProf {
+    bool on = false;
+    std::vector<hipEvent_t> ev;
+    std::vector<int8_t> stage;   // stage[i]: what runs after event i (-1: nothing, the end of an entry point)
+    size_t used = 0;
+};
 
 struct fg_model {
     fg_model_cfg cfg;
@@ -72,9 +80,18 @@ struct fg_model {
     std::vector<const void *> wqkv, wo, wgu, wdown, norm_attn, norm_ffn;
     float2 *rope_tab;  // device [max_pos][head_dim / 2] (cos, sin), angles evaluated in double
     int device;
+    StageProf prof;
 };
 
 namespace {
+
+inline void mark(const fg_model *m, int stage, hipStream_t st)
+{
+    StageProf &p = const_cast<fg_model *>(m)->prof;
+    if (!p.on || p.used >= p.ev.size()) return;
+    (void)hipEventRecord(p.ev[p.used], st);
+    p.stage[p.used++] = (int8_t)stage;
+}
 
 struct Carver {
     char *base;
@@ -218,32 +235,65 @@ int32_t attention_any(const fg_kv_cache *kv, int layer, const fg_tree *t, TreeDe
 
 // The decoder layers shared by the target's verify step and the draft head.  On entry h holds the layer
 // input when first_S == 0, otherwise `partials` holds first_S slabs whose sum is the layer input (h is
-// initialised from them).  On exit `partials` holds *last_S slabs that still have to be added to h.
+// initialised from them).  On exit `partials` holds *last_S slabs that still have to be added to h (0: h is complete).
+// With enough rows for the pipelined GEMM to run without a k split, the row-wise steps ride in the GEMM epilogues: the
+// QKV projection rotates q / k and appends k / v itself, the O and down projections add into h, and the norms read h
+// alone.
 int32_t run_layers(const fg_model *m, fg_kv_cache *kv, const fg_tree *t, const StepWs &w, int max_keys, int first_S,
                    int *last_S, hipStream_t st)
 {
     const fg_model_cfg &c = m->cfg;
     const int M = t->B * t->N, d = c.d_model, F = c.d_ffn, hq = c.n_q_heads * c.head_dim;
     const int qkvd = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+    const bool f16 = is16(c.dtype);
+    const bool fuse_rope = f16 && gemm_mfma_fusable(M, qkvd, d, EPI_ROPE) && qkvd % 256 == 0 && kv->page_size == 16;
+    const bool fuse_o = f16 && gemm_mfma_fusable(M, d, hq, EPI_RESIDUAL);
+    const bool fuse_down = f16 && gemm_mfma_fusable(M, d, F, EPI_RESIDUAL);
+    GemmEpi rope;
+    rope.pos = w.td.pos; rope.dest = w.td.dest; rope.k_pool = kv->k_pool; rope.v_pool = kv->v_pool; rope.q_out = w.q;
+    rope.rope_tab = m->rope_tab; rope.n_pages = kv->n_pages; rope.Hq = c.n_q_heads; rope.Hkv = c.n_kv_heads; rope.hd = c.head_dim;
+    rope.max_pos = c.max_pos; rope.k_frag = (int)k_fragment_major(kv->dtype, kv->head_dim, kv->page_size);
+    GemmEpi resid;
+    resid.h = w.h;
     int S = first_S, init = first_S > 0 ? 1 : 0;
     int32_t rc;
     for (int l = 0; l < c.n_layers; l++) {
+        mark(m, FG_STAGE_NORM, st);
         if ((rc = launch_add_rmsnorm(c.dtype, w.h, w.partials, S, init, m->norm_attn[l], w.a, nullptr, M, d, c.rms_eps, st))) return rc;
         init = 0;
-        if ((rc = gemm_any(c, w.a, m->wqkv[l], w.partials, M, qkvd, d, &S, st))) return rc;
-        if ((rc = launch_rope_append(c.dtype, w.partials, S, t, w.td, kv, l, (const float *)m->rope_tab, c.max_pos, c.n_q_heads, w.q, st))) return rc;
+        mark(m, FG_STAGE_QKV, st);
+        if (fuse_rope) {
+            rope.layer = l;
+            if ((rc = launch_gemm_mfma(c.dtype, w.a, m->wqkv[l], nullptr, M, qkvd, d, EPI_ROPE, 1, nullptr, st, &rope))) return rc;
+        } else {
+            if ((rc = gemm_any(c, w.a, m->wqkv[l], w.partials, M, qkvd, d, &S, st))) return rc;
+            mark(m, FG_STAGE_ROPE, st);
+            if ((rc = launch_rope_append(c.dtype, w.partials, S, t, w.td, kv, l, (const float *)m->rope_tab, c.max_pos, c.n_q_heads, w.q, st))) return rc;
+        }
+        mark(m, FG_STAGE_ATTENTION, st);
         if ((rc = attention_any(kv, l, t, w.td, c.n_q_heads, w.q, w.att, max_keys, w.attn_ws, w.attn_ws_bytes, l > 0, st))) return rc;
-        if ((rc = gemm_any(c, w.att, m->wo[l], w.partials, M, d, hq, &S, st))) return rc;
+        mark(m, FG_STAGE_O, st);
+        if (fuse_o) {
+            if ((rc = launch_gemm_mfma(c.dtype, w.att, m->wo[l], nullptr, M, d, hq, EPI_RESIDUAL, 1, nullptr, st, &resid))) return rc;
+            S = 0;
+        } else if ((rc = gemm_any(c, w.att, m->wo[l], w.partials, M, d, hq, &S, st))) return rc;
+        mark(m, FG_STAGE_NORM, st);
         if ((rc = launch_add_rmsnorm(c.dtype, w.h, w.partials, S, 0, m->norm_ffn[l], w.a, nullptr, M, d, c.rms_eps, st))) return rc;
+        mark(m, FG_STAGE_GATE_UP, st);
         if (gate_up_fused(c, M)) {
-            if ((rc = launch_gemm_mfma(c.dtype, w.a, m->wgu[l], w.act, M, 2 * F, d, 1, 1, nullptr, st))) return rc;
+            if ((rc = launch_gemm_mfma(c.dtype, w.a, m->wgu[l], w.act, M, 2 * F, d, EPI_SWIGLU, 1, nullptr, st))) return rc;
         } else {
             if ((rc = gemm_any(c, w.a, m->wgu[l], w.partials, M, 2 * F, d, &S, st))) return rc;
-            if (is16(c.dtype)) rc = launch_swiglu_partials(c.dtype, w.partials, S, w.act, M, F, st);
+            mark(m, FG_STAGE_SWIGLU, st);
+            if (f16) rc = launch_swiglu_partials(c.dtype, w.partials, S, w.act, M, F, st);
             else rc = launch_swiglu_f32(w.partials, (float *)w.act, M, F, st);
             if (rc) return rc;
         }
-        if ((rc = gemm_any(c, w.act, m->wdown[l], w.partials, M, d, F, &S, st))) return rc;
+        mark(m, FG_STAGE_DOWN, st);
+        if (fuse_down) {
+            if ((rc = launch_gemm_mfma(c.dtype, w.act, m->wdown[l], nullptr, M, d, F, EPI_RESIDUAL, 1, nullptr, st, &resid))) return rc;
+            S = 0;
+        } else if ((rc = gemm_any(c, w.act, m->wdown[l], w.partials, M, d, F, &S, st))) return rc;
     }
     *last_S = S;
     return FG_OK;
@@ -402,6 +452,7 @@ int32_t fg_model_destroy(fg_model *m)
 {
     if (!m) return FG_OK;
     if (m->rope_tab) (void)hipFree(m->rope_tab);
+    for (hipEvent_t e : m->prof.ev) (void)hipEventDestroy(e);
     delete m;
     return FG_OK;
 }
@@ -439,20 +490,26 @@ int32_t fg_spec_verify(fg_model *m, fg_kv_cache *kv, const fg_tree *tree, float 
     const bool need_logits = !logits && (row_argmax || row_top2);
     if (carve_step(c, M, mk, tree->B, tree->N, false, workspace, workspace_bytes, &w, need_logits) < 0)
         return fail(FG_ERR_CAPACITY, "workspace too small: have %lld bytes", (long long)workspace_bytes);
+    mark(m, FG_STAGE_PREP, st);
     if ((rc = launch_tree_prep_ex(tree, kv, w.td, st))) return rc;
     if ((rc = launch_embed(c.dtype, m->embed, tree->tokens, c.vocab, w.h, M, c.d_model, st))) return rc;
     int S = 0;
     if ((rc = run_layers(m, kv, tree, w, mk, 0, &S, st))) return rc;
     void *feat = feature ? feature : w.feat;
+    mark(m, FG_STAGE_NORM, st);
     if ((rc = launch_add_rmsnorm(c.dtype, w.h, w.partials, S, 0, m->final_norm, feat, nullptr, M, c.d_model, c.rms_eps, st))) return rc;
     float *lg = logits ? logits : w.logits;
     if (lg) {
+        mark(m, FG_STAGE_LM_HEAD, st);
         if (is16(c.dtype)) rc = launch_gemm_mfma(c.dtype, feat, m->lm_head, lg, M, c.vocab, c.d_model, 0, 1, nullptr, st);
         else rc = launch_gemm_f32((const float *)feat, (const float *)m->lm_head, lg, M, c.vocab, c.d_model, st);
         if (rc) return rc;
-        if (row_argmax || row_top2)
+        if (row_argmax || row_top2) {
+            mark(m, FG_STAGE_SELECT, st);
             if ((rc = launch_argmax_top2(lg, M, c.vocab, row_argmax, row_top2, st))) return rc;
+        }
     }
+    mark(m, FG_STAGE_END, st);
     return FG_OK;
 }
 
@@ -555,27 +612,36 @@ int32_t fg_draft_step(fg_model *target, fg_model *draft, fg_kv_cache *draft_kv, 
     StepWs w;
     if (carve_step(c, M, mk, tree->B, tree->N, true, workspace, workspace_bytes, &w, child_tok != nullptr) < 0)
         return fail(FG_ERR_CAPACITY, "workspace too small: have %lld bytes", (long long)workspace_bytes);
+    mark(draft, FG_STAGE_PREP, st);
     if ((rc = launch_tree_prep_ex(tree, draft_kv, w.td, st))) return rc;
     if ((rc = launch_concat_embed(c.dtype, target->embed, tree->tokens, c.vocab, in_feature, feat_index, tree->N, feat_rows, w.cat, M, d, st))) return rc;
     int S = 0;
+    mark(draft, FG_STAGE_FC, st);
     if ((rc = gemm_any(c, w.cat, draft->fc, w.partials, M, d, 2 * d, &S, st))) return rc;
     if ((rc = run_layers(draft, draft_kv, tree, w, mk, S, &S, st))) return rc;
     void *hid = out_feature ? out_feature : w.feat;
+    mark(draft, FG_STAGE_NORM, st);
     if ((rc = launch_add_rmsnorm(c.dtype, w.h, w.partials, S, 0, draft->norm_attn[0], nullptr, hid, M, d, c.rms_eps, st))) return rc;
     if (child_tok) {
         int rows = M;
         if (expand_row) {   // only the picked row of each sequence goes through the LM head
             rows = tree->B;
+            mark(draft, FG_STAGE_PREP, st);
             if ((rc = launch_gather_rows(c.dtype, hid, expand_row, tree->B, tree->N, d, w.cat, st))) return rc;
             hid = w.cat;
         }
+        mark(draft, FG_STAGE_LM_HEAD, st);
         if (is16(c.dtype)) rc = launch_gemm_mfma(c.dtype, hid, target->lm_head, w.logits, rows, c.vocab, d, 0, 1, nullptr, st);
         else rc = launch_gemm_f32((const float *)hid, (const float *)target->lm_head, w.logits, rows, c.vocab, d, st);
         if (rc) return rc;
+        mark(draft, FG_STAGE_SELECT, st);
         if ((rc = launch_topk_logp(w.logits, rows, c.vocab, K_draft, child_tok, child_logp, st))) return rc;
     }
-    if (n_commit)
+    if (n_commit) {
+        mark(draft, FG_STAGE_PREP, st);
         if ((rc = launch_commit_len(draft_kv->seq_len, tree->slot, n_commit, commit_bias, tree->B, draft_kv->n_slots, st))) return rc;
+    }
+    mark(draft, FG_STAGE_END, st);
     return FG_OK;
 }
 
@@ -612,17 +678,30 @@ int32_t fg_build_tree(const int32_t *cand_tok, const int32_t *cand_parent, const
 }
 
 int32_t fg_gemm(int32_t dtype, const void *x, const void *w_packed, void *out, int32_t M, int32_t n_out, int32_t n_in,
-                int32_t epilogue, int32_t split_k, int32_t *split_k_used, void *stream)
+                int32_t epilogue, int32_t split_k, int32_t *split_k_used, int32_t variant, void *stream)
 {
     if (!x || !w_packed || !out || M < 0 || n_out < 1 || n_in < 1) return fail(FG_ERR_INVALID_ARG, "fg_gemm: bad argument");
+    if (epilogue != EPI_SLABS && epilogue != EPI_SWIGLU && epilogue != EPI_RESIDUAL) return fail(FG_ERR_INVALID_ARG, "fg_gemm: epilogue %d", epilogue);
     if (M == 0) return FG_OK;
-    if (is16(dtype)) return launch_gemm_mfma(dtype, x, w_packed, out, M, n_out, n_in, epilogue, split_k, split_k_used, (hipStream_t)stream);
+    if (is16(dtype)) {
+        GemmEpi ep;
+        ep.h = (float *)out;
+        if (epilogue == EPI_RESIDUAL && (variant == 1 || variant == 2)) return fail(FG_ERR_INVALID_ARG, "fg_gemm: the residual epilogue needs the pipelined kernel");
+        return launch_gemm_mfma(dtype, x, w_packed, out, M, n_out, n_in, epilogue, epilogue == EPI_SLABS ? split_k : 1, split_k_used,
+                                (hipStream_t)stream, &ep, variant);
+    }
     if (dtype == FG_F32) {
         if (epilogue != 0) return fail(FG_ERR_UNIMPLEMENTED, "fp32 GEMM has no fused epilogue");
         if (split_k_used) *split_k_used = 1;
         return launch_gemm_f32((const float *)x, (const float *)w_packed, (float *)out, M, n_out, n_in, (hipStream_t)stream);
     }
     return fail(FG_ERR_INVALID_ARG, "unknown dtype %d", dtype);
+}
+
+const char *fg_gemm_kernel_name(int32_t M, int32_t n_out, int32_t n_in, int32_t epilogue)
+{
+    if (M < 1 || n_out < 1 || n_in < 1 || epilogue < 0 || epilogue > EPI_RESIDUAL) return "";
+    return gemm_mfma_kernel_name(M, n_out, n_in, epilogue);
 }
 
 int32_t fg_topk_logp(const float *logits, int32_t M, int32_t vocab, int32_t K, int32_t *tok, float *logp, void *stream)
@@ -633,16 +712,40 @@ int32_t fg_topk_logp(const float *logits, int32_t M, int32_t vocab, int32_t K, i
     return launch_topk_logp(logits, M, vocab, K, tok, logp, (hipStream_t)stream);
 }
 
-int32_t fg_profile_gemm(int32_t enable, int32_t rows, int32_t n_out, int32_t n_in, int32_t epilogue, int32_t max_launches)
+int32_t fg_model_profile(fg_model *m, int32_t enable, int32_t max_marks)
 {
-    if (enable && (max_launches < 1 || max_launches > (1 << 20))) return fail(FG_ERR_INVALID_ARG, "fg_profile_gemm: bad max_launches");
-    return profile_gemm_arm(enable, rows, n_out, n_in, epilogue, max_launches);
+    if (!m) return fail(FG_ERR_INVALID_ARG, "fg_model_profile: model is NULL");
+    StageProf &p = m->prof;
+    p.on = false;
+    p.used = 0;
+    if (!enable) return FG_OK;
+    if (max_marks < 2 || max_marks > (1 << 22)) return fail(FG_ERR_INVALID_ARG, "fg_model_profile: bad max_marks");
+    while ((int)p.ev.size() < max_marks) {
+        hipEvent_t e;
+        FG_HIP(hipEventCreate(&e));
+        p.ev.push_back(e);
+    }
+    p.stage.resize(p.ev.size());
+    p.on = true;
+    return FG_OK;
 }
 
-int32_t fg_profile_read(double *total_ms, int32_t *count)
+int32_t fg_model_profile_read(fg_model *m, double *ms, int32_t *launches)
 {
-    if (!total_ms || !count) return fail(FG_ERR_INVALID_ARG, "fg_profile_read: NULL output");
-    return profile_gemm_read(total_ms, count);
+    if (!m || !ms || !launches) return fail(FG_ERR_INVALID_ARG, "fg_model_profile_read: NULL argument");
+    StageProf &p = m->prof;
+    for (int i = 0; i < FG_STAGE_COUNT; i++) { ms[i] = 0.0; launches[i] = 0; }
+    if (p.used > 0) FG_HIP(hipEventSynchronize(p.ev[p.used - 1]));
+    for (size_t i = 0; i + 1 < p.used; i++) {
+        const int sg = p.stage[i];
+        if (sg < 0 || sg >= FG_STAGE_COUNT) continue;
+        float t = 0.f;
+        FG_HIP(hipEventElapsedTime(&t, p.ev[i], p.ev[i + 1]));
+        ms[sg] += t;
+        launches[sg]++;
+    }
+    p.used = 0;
+    return FG_OK;
 }
 
 int32_t fg_probe_read(const void *src, int64_t bytes, int32_t nontemporal, int32_t blocks, void *sink, void *stream)

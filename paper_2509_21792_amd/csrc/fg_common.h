@@ -108,8 +108,31 @@ struct TreeDev {             // per-call derived tree data in the workspace
     int32_t *dest;           // [B*N] cache cell of each new node: page * 16 + position in the page (same in every layer)
 };
 
+// Epilogues of the 16-bit GEMM.  SLABS and SWIGLU exist in every kernel; ROPE, RESIDUAL and TOPK only in the pipelined
+// kernel without a k split (gemm_mfma_fusable says whether a shape gets them; the caller otherwise takes SLABS and runs
+// the separate row-wise kernel).
+enum { EPI_SLABS = 0, EPI_SWIGLU = 1, EPI_ROPE = 2, EPI_RESIDUAL = 3, EPI_TOPK = 4 };
+struct GemmEpi {
+    // EPI_ROPE: the GEMM is the QKV projection.  q and k heads are rotated (pairing i, i + hd/2) at pos[row]; q rows go
+    // to q_out [M, Hq * hd], the node's k and v into its cache cell dest[row] (page * 16 + slot) of `layer`.
+    const int32_t *pos = nullptr, *dest = nullptr;
+    void *k_pool = nullptr, *v_pool = nullptr, *q_out = nullptr;
+    const float2 *rope_tab = nullptr;
+    int layer = 0, n_pages = 0, Hq = 0, Hkv = 0, hd = 0, max_pos = 0, k_frag = 0;
+    // EPI_RESIDUAL: h [M, N] fp32 += x . W^T
+    float *h = nullptr;
+    // EPI_TOPK: per row and 256-column block the topk largest outputs (value, column; ties to the lower column) and
+    // the block's (max, sum of exp(x - max)): part_val / part_idx [M][blocks][topk], part_ms [M][blocks][2]
+    int topk = 0;
+    float *part_val = nullptr;
+    int32_t *part_idx = nullptr;
+    float *part_ms = nullptr;
+};
+// variant: 0 = the library's choice of kernel; 1 streaming, 2 few-row, 3 / 4 / 5 pipelined with 256- / 128- / 160-row
+// blocks (kernel-level measurements and tests)
 int32_t launch_gemm_mfma(int32_t dtype, const void *x, const void *wp, void *out, int M, int N, int K, int epilogue,
-                         int split_k, int *split_used, hipStream_t st);
+                         int split_k, int *split_used, hipStream_t st, const GemmEpi *epi = nullptr, int variant = 0);
+bool gemm_mfma_fusable(int M, int N, int K, int kind);
 int32_t launch_gemm_f32(const float *x, const float *w, float *out, int M, int N, int K, hipStream_t st);
 int32_t launch_pack(int32_t dtype, const void *src, const void *src2, void *dst, int64_t n_out, int64_t n_in, hipStream_t st);
 

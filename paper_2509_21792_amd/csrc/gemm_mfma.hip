@@ -11,10 +11,6 @@
 // Block = WM x WN waves; a wave owns MT x NT tiles of 32 x 32 outputs.  WM = 1 with MT = ceil(M / 32) is the
 // weight-streaming (memory-bound) shape: every byte of W is read exactly once per GEMM.  Split-K over
 // blockIdx.z writes fp32 partial slabs that the consumer kernel sums (no atomics: results are deterministic).
-#include <stdlib.h>
-
-#include <vector>
-
 #include "fg_common.h"
 #include "gemm_mfma.h"
 
@@ -153,26 +149,6 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(const T *__restr
 
 // ---- host side -----------------------------------------------------------------------------------------
 
-// Measurement hook: when armed for one GEMM shape, every matching launch is bracketed by a pair of HIP events
-// on the launch stream, so a benchmark can read that kernel's average duration inside its own timed region.
-struct GemmProfile {
-    bool on = false;
-    int rows = 0, n_out = 0, n_in = 0, epilogue = 0;
-    std::vector<hipEvent_t> start, stop;
-    size_t used = 0;
-};
-static GemmProfile g_prof;
-
-static bool raster_enabled()
-{
-    static int v = -1;
-    if (v < 0) {
-        const char *e = getenv("FG_GEMM_RASTER");
-        v = e ? atoi(e) : 1;
-    }
-    return v != 0;
-}
-
 template <typename T, int MT, int NT, int WM, int WN, int EPI>
 static void launch_variant(const void *x, const void *wp, void *out, int M, int N, int K, int split, hipStream_t st)
 {
@@ -180,7 +156,7 @@ static void launch_variant(const void *x, const void *wp, void *out, int M, int 
     const int total_chunks = K / 64;
     const int cps = (total_chunks + split - 1) / split;
     const int n_bands = (n_tiles + per_block - 1) / per_block, row_blocks = (M + WM * MT * 32 - 1) / (WM * MT * 32);
-    if (row_blocks > 1 && raster_enabled()) {
+    if (row_blocks > 1) {
         const int BG = n_bands >= 32 ? 4 : (n_bands >= 16 ? 2 : 1);
         const int units = (n_bands + BG - 1) / BG * split;
         dim3 grid((unsigned)(8 * ((units + 7) / 8) * row_blocks * BG));
@@ -217,74 +193,65 @@ static int choose_split(int M, int N, int K, int block_rows, int block_cols)
     return best;
 }
 
-// More than 256 rows: the pipelined 256 x 256 kernel (gemm_mfma_big.hip).  FG_GEMM_BIG=0 keeps the streaming
-// kernel's 256-row shape for comparison.
 int32_t launch_gemm_mfma_big(int32_t dtype, const void *x, const void *wp, void *out, int M, int N, int K, int epilogue,
-                             int split, int raster_on, hipStream_t st);
-static int big_variant()
-{
-    static int v = -1;
-    if (v < 0) {
-        const char *e = getenv("FG_GEMM_BIG");
-        v = e ? atoi(e) : 1;
-    }
-    return v;
-}
-
+                             int split, int fixed_mt, const GemmEpi *epi, hipStream_t st);
 int gemm_mfma_big_split_for(int M, int N, int K);
-
-// The pipelined kernel takes every shape with more than 256 rows, and from 129 rows on the wide ones (gate/up,
-// LM head), where a 256-row tile half full still beats streaming the weights through eight row tiles per wave.
-bool gemm_mfma_uses_big(int M, int N) { return big_variant() && (M > 256 || (M > 128 && N >= 16384)); }
-// ... and the narrow outputs with a long contraction from 129 rows on: with up to 16 k splits the 7B down
-// projection takes 42 - 47 us at 160 - 256 rows against 58 - 62 in the streaming kernel, whose single chunk of W in
-// flight per wave leaves every chunk waiting a full memory latency.
-static bool uses_big_narrow(int M, int N, int K) { return big_variant() && N < 16384 && M > 128; }   // after the few-row test
-
-// Few rows: the kernel that splits k inside the block (gemm_mfma_skinny.hip).  Measured on the 7B-class and
-// 1.5B-class shapes against the streaming kernel:
-//   narrow outputs (QKV, O, down), up to 128 rows: 22.0 / 26.1 / 33.2 / 38.7 us for the 7B down projection at
-//     8 / 48 / 96 / 128 rows with 4 slabs, against 22.4 / 33.7 / 41.8 / 45.1 with 16; 1.5B down at 96 rows 11.2
-//     against 20.3 us;
-//   gate/up with its SwiGLU fused: 46.6 / 49.5 / 57.7 us at 8 / 32 / 64 rows (7B) against 48.8 / 56.8 / 53.0 plus a
-//     4.4 - 5.5 us SwiGLU pass over the slabs.  From 65 rows on a block holds three or four row tiles and two
-//     blocks fit a CU: 1.5B gate/up (280 blocks, one round) 24.2 against 24.4 + 5.4 us at 96 rows, 7B gate/up (592
-//     blocks, a round and a bit) 75 against 58.6 + 6;
-//   the LM head: 167 against 177 us at 8 rows, level at 32, behind above (220 against 200 us at 48).
-// FG_GEMM_FEW=0 switches it off for comparison.
 int32_t launch_gemm_mfma_skinny(int32_t dtype, const void *x, const void *wp, void *out, int M, int N, int K, int epilogue,
                                 int split, hipStream_t st);
 int gemm_mfma_skinny_split_for(int M, int N, int K);
-static int few_variant()
+
+// Which kernel runs a shape.  All thresholds are measurements on the 7B-class and 1.5B-class matrices; "wide" means
+// at least 16384 output columns (gate/up, the LM head), "narrow" the QKV, O and down projections.
+//   few-row kernel (gemm_mfma_skinny.hip, k split inside the block):
+//     narrow outputs up to 128 rows in one row block -- 22.0 / 26.1 / 33.2 / 38.7 us for the 7B down projection at
+//       8 / 48 / 96 / 128 rows with 4 slabs, against 22.4 / 33.7 / 41.8 / 45.1 with the streaming kernel's 16 -- and up
+//       to 256 rows (two row blocks) while the X traffic of the 64-column blocks (column blocks x M x K x 2 bytes, all
+//       from L2) stays small: the 7B O projection (103 MB) 14.8 / 17.7 us at 192 / 256 rows against 23 - 27 in the
+//       large-tile kernels, while the 7B down projection (543 MB) takes 65 against 47 - 62;
+//     gate/up with its SwiGLU fused up to 64 rows (46.6 / 49.5 / 57.7 us at 8 / 32 / 64 rows against 48.8 / 56.8 / 53.0
+//       plus a 4.4 - 5.5 us SwiGLU pass), and up to 128 rows when at most 512 column blocks keep it to one round;
+//     the LM head up to 32 rows (167 against 177 us at 8 rows, level at 32, behind above);
+//   pipelined kernel (gemm_mfma_big.hip): more than 256 rows; from 129 rows the wide outputs (a 256-row tile half
+//     full still beats streaming the weights through eight row tiles per wave) and the narrow ones with up to 16 k
+//     splits (the 7B down projection 42 - 47 us at 160 - 256 rows against 58 - 62 in the streaming kernel);
+//   streaming kernel (this file): the rest, i.e. 33 / 65 - 128 rows of the wide outputs.
+enum { KERNEL_STREAMING = 1, KERNEL_FEW = 2, KERNEL_BIG = 3 };
+static int kernel_for(int M, int N, int K, int epilogue)
 {
-    static int v = -1;
-    if (v < 0) {
-        const char *e = getenv("FG_GEMM_FEW");
-        v = e ? atoi(e) : 1;
+    if (epilogue >= EPI_ROPE) return KERNEL_BIG;
+    if (N < 16384) {
+        if (M <= 128 || (M <= 256 && (int64_t)((N + 63) / 64) * M * K <= (56LL << 20))) return KERNEL_FEW;
+        return KERNEL_BIG;
     }
-    return v;
+    if (M > 128) return KERNEL_BIG;
+    if (epilogue == EPI_SWIGLU) return (M <= 64 || (N + 63) / 64 <= 512) ? KERNEL_FEW : KERNEL_STREAMING;
+    return M <= 32 ? KERNEL_FEW : KERNEL_STREAMING;
 }
-bool gemm_mfma_uses_few(int M, int N, int K, int epilogue)
-{
-    if (!few_variant()) return false;
-    // narrow outputs: up to 128 rows in one row block; up to 256 rows (two row blocks) while the X traffic of the
-    // 64-column blocks (column blocks x M x K x 2 bytes, all from L2) stays small -- the 7B O projection (103 MB)
-    // 14.8 / 17.7 us at 192 / 256 rows against 23 - 27 in the large-tile kernels, the 1.5B down projection (82 MB)
-    // 15 against 25 - 30 us at 192 rows, while the 7B down projection (543 MB) takes 65 against 47 - 62 us
-    if (N < 16384) return M <= 128 || (M <= 256 && (int64_t)((N + 63) / 64) * M * K <= (56LL << 20));
-    if (M > 128) return false;
-    if (epilogue == 1) return M <= 64 || (N + 63) / 64 <= 512;
-    return M <= 32;
-}
+static int kernel_of_variant(int variant) { return variant == 1 ? KERNEL_STREAMING : (variant == 2 ? KERNEL_FEW : KERNEL_BIG); }
+
 // Whether the gate/up GEMM of M rows applies SwiGLU in its own epilogue (no slabs, no separate pass).
-bool gemm_mfma_fuses_swiglu(int M, int N, int K) { return gemm_mfma_uses_big(M, N) || gemm_mfma_uses_few(M, N, K, 1); }
+bool gemm_mfma_fuses_swiglu(int M, int N, int K) { return kernel_for(M, N, K, EPI_SWIGLU) != KERNEL_STREAMING; }
+
+// Whether a GEMM of this shape runs the fused epilogue `kind` (RoPE + append, residual add, top-k partials): they
+// exist in the pipelined kernel without a k split, which pays from four 256-row blocks on (below that the grid
+// needs k splits, hence slabs, to fill the chip).
+bool gemm_mfma_fusable(int M, int N, int K, int kind)
+{
+    if (kind < EPI_ROPE) return true;
+    if (kind > EPI_RESIDUAL) return false;
+    return M >= 1024 && (int64_t)M * K < (1LL << 30);
+}
 
 int gemm_mfma_split_for(int M, int N, int K)
 {
-    if (gemm_mfma_uses_few(M, N, K, 0)) return gemm_mfma_skinny_split_for(M, N, K);
-    if (gemm_mfma_uses_big(M, N) || uses_big_narrow(M, N, K)) return gemm_mfma_big_split_for(M, N, K);
+    const int k = kernel_for(M, N, K, EPI_SLABS);
+    if (k == KERNEL_FEW) return gemm_mfma_skinny_split_for(M, N, K);
+    if (k == KERNEL_BIG) return gemm_mfma_big_split_for(M, N, K);
     return choose_split(M, N, K, 256, 256);
 }
+
+static const char *const KERNEL_NAMES[] = {"", "gemm_mfma_kernel", "gemm_mfma_skinny_kernel", "gemm_mfma_big_kernel"};
+const char *gemm_mfma_kernel_name(int M, int N, int K, int epilogue) { return KERNEL_NAMES[kernel_for(M, N, K, epilogue)]; }
 
 template <typename T>
 static int32_t launch_gemm_typed(const void *x, const void *wp, void *out, int M, int N, int K, int epilogue, int split,
@@ -305,63 +272,33 @@ static int32_t launch_gemm_typed(const void *x, const void *wp, void *out, int M
 }
 
 int32_t launch_gemm_mfma(int32_t dtype, const void *x, const void *wp, void *out, int M, int N, int K, int epilogue,
-                         int split_k, int *split_used, hipStream_t st)
+                         int split_k, int *split_used, hipStream_t st, const GemmEpi *epi, int variant)
 {
     if (M <= 0) return FG_OK;
     if (!is16(dtype)) return fail(FG_ERR_INVALID_ARG, "MFMA GEMM needs a 16-bit dtype");
     if (N % 32 || K % 64) return fail(FG_ERR_SHAPE, "16-bit GEMM needs n_out %% 32 == 0 and n_in %% 64 == 0 (got %d, %d)", N, K);
-    if (epilogue == 1 && (N % 64)) return fail(FG_ERR_SHAPE, "gate/up GEMM needs n_out %% 64 == 0");
+    if (epilogue == EPI_SWIGLU && (N % 64)) return fail(FG_ERR_SHAPE, "gate/up GEMM needs n_out %% 64 == 0");
     if ((int64_t)M * N >= (1LL << 31)) return fail(FG_ERR_SHAPE, "GEMM output of %d x %d exceeds 2^31 elements", M, N);
+    if (variant < 0 || variant > 5) return fail(FG_ERR_INVALID_ARG, "unknown GEMM variant %d", variant);
+    const int kernel = variant ? kernel_of_variant(variant) : kernel_for(M, N, K, epilogue);
+    if (epilogue >= EPI_ROPE && kernel != KERNEL_BIG) return fail(FG_ERR_INVALID_ARG, "GEMM epilogue %d exists in the pipelined kernel only", epilogue);
+    if (kernel == KERNEL_FEW && M > 512) return fail(FG_ERR_SHAPE, "the few-row kernel takes at most 512 rows (got %d)", M);
+    if (kernel == KERNEL_STREAMING && M > 256 && epilogue != EPI_SLABS && epilogue != EPI_SWIGLU) return fail(FG_ERR_INVALID_ARG, "bad epilogue");
     int split = 1;
-    if (epilogue == 0) {
-        split = split_k > 0 ? split_k : gemm_mfma_split_for(M, N, K);
+    if (epilogue == EPI_SLABS) {
+        if (split_k > 0) split = split_k;
+        else if (kernel == KERNEL_FEW) split = gemm_mfma_skinny_split_for(M, N, K);
+        else if (kernel == KERNEL_BIG) split = gemm_mfma_big_split_for(M, N, K);
+        else split = choose_split(M, N, K, 256, 256);
         if (split > K / 64) split = K / 64;
         int cps = (K / 64 + split - 1) / split;
         split = (K / 64 + cps - 1) / cps;
     }
     if (split_used) *split_used = split;
-    const bool prof = g_prof.on && (g_prof.rows == 0 || g_prof.rows == M) && g_prof.n_out == N && g_prof.n_in == K && g_prof.epilogue == epilogue &&
-                      g_prof.used < g_prof.start.size();
-    if (prof) (void)hipEventRecord(g_prof.start[g_prof.used], st);
-    int32_t rc;
-    if (gemm_mfma_uses_few(M, N, K, epilogue)) rc = launch_gemm_mfma_skinny(dtype, x, wp, out, M, N, K, epilogue, split, st);
-    else if (gemm_mfma_uses_big(M, N) || uses_big_narrow(M, N, K)) rc = launch_gemm_mfma_big(dtype, x, wp, out, M, N, K, epilogue, split, raster_enabled(), st);
-    else rc = dtype == FG_BF16 ? launch_gemm_typed<bf16_t>(x, wp, out, M, N, K, epilogue, split, st)
-                               : launch_gemm_typed<f16_t>(x, wp, out, M, N, K, epilogue, split, st);
-    if (prof) (void)hipEventRecord(g_prof.stop[g_prof.used++], st);
-    return rc;
-}
-
-int32_t profile_gemm_arm(int enable, int rows, int n_out, int n_in, int epilogue, int max_launches)
-{
-    g_prof.on = false;
-    g_prof.used = 0;
-    if (!enable) return FG_OK;
-    while ((int)g_prof.start.size() < max_launches) {
-        hipEvent_t a, b;
-        FG_HIP(hipEventCreate(&a));
-        FG_HIP(hipEventCreate(&b));
-        g_prof.start.push_back(a);
-        g_prof.stop.push_back(b);
-    }
-    g_prof.rows = rows; g_prof.n_out = n_out; g_prof.n_in = n_in; g_prof.epilogue = epilogue;
-    g_prof.on = true;
-    return FG_OK;
-}
-
-int32_t profile_gemm_read(double *total_ms, int32_t *count)
-{
-    double tot = 0;
-    for (size_t i = 0; i < g_prof.used; i++) {
-        FG_HIP(hipEventSynchronize(g_prof.stop[i]));
-        float ms = 0.f;
-        FG_HIP(hipEventElapsedTime(&ms, g_prof.start[i], g_prof.stop[i]));
-        tot += ms;
-    }
-    *total_ms = tot;
-    *count = (int32_t)g_prof.used;
-    g_prof.used = 0;
-    return FG_OK;
+    if (kernel == KERNEL_FEW) return launch_gemm_mfma_skinny(dtype, x, wp, out, M, N, K, epilogue, split, st);
+    if (kernel == KERNEL_BIG) return launch_gemm_mfma_big(dtype, x, wp, out, M, N, K, epilogue, split, variant == 3 ? 8 : (variant == 4 ? 4 : (variant == 5 ? 5 : 0)), epi, st);
+    return dtype == FG_BF16 ? launch_gemm_typed<bf16_t>(x, wp, out, M, N, K, epilogue, split, st)
+                            : launch_gemm_typed<f16_t>(x, wp, out, M, N, K, epilogue, split, st);
 }
 
 // ---- packing ---------------------------------------------------------------------------------------------

@@ -1,78 +1,193 @@
-// Compute-bound shape of the 16-bit MFMA GEMM (more than 256 rows): out = X . W^T on 256 x 256 tiles.
+// Compute-bound shape of the 16-bit MFMA GEMM (more than 256 rows): out = X . W^T on (32 MT) x 256 tiles, MT = 8 or 4.
 //
-// Block = 4 waves side by side, each owning 256 rows x 64 columns (8 x 2 tiles of v_mfma_f32_32x32x16).  With one
-// wave per SIMD nothing hides a stall, so both operands are requested two 64-wide k chunks ahead:
+// Block = 4 waves side by side, each owning 32 MT rows x 64 columns (MT x 2 tiles of v_mfma_f32_32x32x16).  MT = 8
+// fills the register file with one wave per SIMD, so nothing hides a stall and both operands are requested two
+// 64-wide k chunks ahead; MT = 4 leaves room for a second block per CU, whose main loop covers the first one's
+// prologue and epilogue (and doubles the number of tiles for the narrow outputs, which otherwise leave CUs idle):
 //   W  packed fragments, global -> registers, two register sets that alternate by chunk; the set of chunk c is
 //      refilled with chunk c + 2 fragment by fragment right after the MFMAs that consumed it;
 //   X  row-major activations, global -> LDS directly (buffer_load_dwordx4 ... lds: 64 lanes x 16 bytes land in 1 KiB of
-//      consecutive LDS), into a ring of three 32 KiB stages.  A stage holds 256 rows x 128 bytes; the 16-byte
+//      consecutive LDS), into a ring of three stages.  A stage holds 32 MT rows x 128 bytes; the 16-byte
 //      piece p of row r holds the k octet p ^ ((r >> 1) & 7).  The permutation is applied to the *global*
 //      address each lane requests (a row's eight lanes still cover its 128 contiguous bytes), and makes the
 //      ds_read_b128 fragment reads (16 lanes = 16 rows, one octet) fall into 16 different bank groups.
 // One barrier per chunk, placed before the last k tile: by then every wave has read all fragments of the current
-// stage, so the stage can be handed to the loads of chunk c + 3 while the last 16 MFMAs run and the first
+// stage, so the stage can be handed to the loads of chunk c + 3 while the last MFMAs run and the first
 // fragments of the next chunk are read.
 //
 // vmcnt bookkeeping (loads retire in issue order).  Per chunk a wave issues, in this order: the W fragments of k
-// tiles 0-2 (6 loads), [wait + barrier], the 8 X loads, the W fragments of k tile 3 (2 loads).  At the wait of
+// tiles 0-2 (6 loads), [wait + barrier], the MT X loads, the W fragments of k tile 3 (2 loads).  At the wait of
 // chunk c the X loads of chunk c + 1 (issued two chunks earlier) must have landed; younger than them are
-// 2 + 6 + 8 + 2 + 6 = 24 loads, hence s_waitcnt vmcnt(24).  The prologue issues its loads in the same interleaving
-// so that the count holds from the first chunk on, and chunks past the end are clamped (re-requested), not
-// skipped, so that it holds to the last.  Scheduling barriers pin the loads to their side of each wait.
+// 2 + 6 + MT + 2 + 6 = 16 + MT loads, hence s_waitcnt vmcnt(16 + MT).  The prologue issues its loads in the same
+// interleaving so that the count holds from the first chunk on, and chunks past the end are clamped (re-requested),
+// not skipped, so that it holds to the last.  Scheduling barriers pin the loads to their side of each wait.
+//
+// Epilogues (no k split for the last three): fp32 slabs; SwiGLU of interleaved gate / up tiles; the QKV projection's
+// RoPE + KV append + q rows; residual add into the fp32 stream; per-block top-k / log-sum-exp partials of an LM head.
 #include "fg_common.h"
 #include "gemm_mfma.h"
 
 namespace fg {
 
 constexpr int BIG_STAGES = 3;
-constexpr int BIG_STAGE_U4 = 256 * 8;   // uint4 slots per stage: 256 rows x 8 pieces
 
 // s_waitcnt immediate on gfx9: vmcnt[3:0] | expcnt << 4 | lgkmcnt << 8 | vmcnt[5:4] << 14
 constexpr int waitcnt_imm(int vm, int lgkm) { return (vm & 15) | (7 << 4) | ((lgkm & 15) << 8) | ((vm >> 4) << 14); }
 
-template <typename T, int EPI>
-__global__ __launch_bounds__(256) void gemm_mfma_big_kernel(const T *__restrict__ X, const uint4 *__restrict__ Wp,
+// ---- epilogues of a wave's MT x 2 tiles (columns of tiles nt0 and nt1, rows row0 ..) ---------------------------------
+// A lane holds column lane % 32 of each tile and rows 32 i + 8 (r / 4) + 4 (lane / 32) + r % 4 of the block.
+
+// QKV projection: a wave's two tiles are the columns e and e + hd/2 of one head, so a lane holds both members of every
+// rotate-half pair of its rows.  q and k rows leave through a 4 KiB transposing tile in LDS (one per wave, 32 rows at a
+// time): the accumulator layout has a lane on one column of 16 rows, the stores want 16 contiguous bytes of one row --
+// 8 consecutive head dims, which are contiguous in q rows and in both K page layouts.  LDS serves a wave's accesses in
+// order, so the tile needs no barrier.  v (pages transposed: consecutive dims 32 bytes apart) is stored directly.
+template <typename T, int MT>
+__device__ __forceinline__ void epilogue_rope(f32x16_t (&acc)[MT][2], const GemmEpi &ep, int M, int row0, int nt0, int n_tiles,
+                                              int lane, T *tile)
+{
+    if (nt0 >= n_tiles) return;
+    const int hd = ep.hd, half = hd >> 1, Hq = ep.Hq, Hkv = ep.Hkv;
+    const int head = (nt0 * 32) / hd;              // the same for the whole wave
+    const int ebase = nt0 * 32 - head * hd;        // head dim of the low tile's first column
+    const int c = lane & 31, rh = (lane >> 5) * 4;
+    const size_t page_elems = (size_t)16 * hd;
+    if (head >= Hq + Hkv) {
+        const int hk = head - Hq - Hkv, e0 = ebase + c, e1 = e0 + half;
+        T *vp = reinterpret_cast<T *>(ep.v_pool);
+#pragma unroll
+        for (int i = 0; i < MT; i++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) {
+                const int m = row0 + i * 32 + 8 * (r >> 2) + rh + (r & 3);
+                if (m < M) {
+                    const int cell = ep.dest[m], page = cell >> 4, t = cell & 15;
+                    T *o = vp + (((size_t)ep.layer * ep.n_pages + page) * Hkv + hk) * page_elems + t;
+                    o[e0 * 16] = from_f<T>(acc[i][0][r]);
+                    o[e1 * 16] = from_f<T>(acc[i][1][r]);
+                }
+            }
+        return;
+    }
+    const bool is_q = head < Hq;
+    T *qo = reinterpret_cast<T *>(ep.q_out) + head * hd;
+    T *kp = reinterpret_cast<T *>(ep.k_pool);
+    const int hk = head - Hq;
+#pragma unroll
+    for (int i = 0; i < MT; i++) {
+        if (row0 + i * 32 >= M) break;
+        // positions of the lane's 16 rows (four groups of four consecutive rows; the position array is padded to a
+        // multiple of 64 entries by its 256-byte alignment in the workspace), then their table entries, all in flight
+        int pos[16];
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+            const int m0 = row0 + i * 32 + 8 * q + rh;
+            int4 p4 = make_int4(0, 0, 0, 0);
+            if (m0 < M) p4 = *reinterpret_cast<const int4 *>(ep.pos + m0);
+            pos[4 * q] = p4.x; pos[4 * q + 1] = p4.y; pos[4 * q + 2] = p4.z; pos[4 * q + 3] = p4.w;
+        }
+        float2 cs[16];
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+            const int p = min(max(pos[r], 0), ep.max_pos - 1);
+            cs[r] = ep.rope_tab[(size_t)p * half + ebase + c];
+        }
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+            const int rr = 8 * (r >> 2) + rh + (r & 3);
+            const float a = acc[i][0][r], b = acc[i][1][r];
+            tile[rr * 64 + c] = from_f<T>(a * cs[r].x - b * cs[r].y);
+            tile[rr * 64 + 32 + c] = from_f<T>(b * cs[r].x + a * cs[r].y);
+        }
+        // 256 pieces of 16 bytes: piece = (row, segment); segments 0-3 are dims ebase + 8 s .., 4-7 the rotated partners
+#pragma unroll
+        for (int t = 0; t < 4; t++) {
+            const int piece = lane + 64 * t, rr = piece >> 3, seg = piece & 7;
+            const uint4 v = *reinterpret_cast<const uint4 *>(tile + rr * 64 + seg * 8);
+            const int m = row0 + i * 32 + rr;
+            if (m < M) {
+                const int e = seg < 4 ? ebase + seg * 8 : ebase + half + (seg - 4) * 8;
+                if (is_q) {
+                    *reinterpret_cast<uint4 *>(qo + (size_t)m * Hq * hd + e) = v;
+                } else {
+                    const int cell = ep.dest[m], page = cell >> 4, tk = cell & 15;
+                    T *o = kp + (((size_t)ep.layer * ep.n_pages + page) * Hkv + hk) * page_elems;
+                    *reinterpret_cast<uint4 *>(o + k_page_offset(ep.k_frag, hd, tk, e)) = v;
+                }
+            }
+        }
+    }
+}
+
+template <typename T, int MT, int EPI>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 4 ? 2 : 1))) void gemm_mfma_big_kernel(const T *__restrict__ X, const uint4 *__restrict__ Wp,
                                                              void *__restrict__ out, int M, int N, int K, int chunks_per_split,
-                                                             int raster, int row_blocks)
+                                                             int n_bands, int row_blocks, int per_xcd, int n_tile_total, GemmEpi ep)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the buffer-descriptor builtins exist in the device pass only
-    constexpr int MT = 8, NT = 2, WN = 4, BM = 256;
+    constexpr int NT = 2, WN = 4, BM = MT * 32;
+    constexpr int STAGE_U4 = BM * 8;   // uint4 slots per stage: BM rows x 8 pieces
     // one variable per stage: the compiler orders LDS reads after direct-to-LDS loads per variable, so distinct
     // variables keep the reads of one stage from waiting on the loads in flight to the others
-    __shared__ uint4 xs0[BIG_STAGE_U4], xs1[BIG_STAGE_U4], xs2[BIG_STAGE_U4];
+    __shared__ uint4 xs0[STAGE_U4], xs1[STAGE_U4], xs2[STAGE_U4];
 
     const int tid = threadIdx.x, lane = tid & 63, wn = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n_tiles = N >> 5, k_tiles = K >> 4;
-    int bx, by, bz;
-    if (!map_block(raster, n_tiles, WN * NT, k_tiles, chunks_per_split, row_blocks, bx, by, bz)) return;
+    // Block -> tile.  Workgroups are dealt to the 8 XCDs round-robin by linear id; XCD x takes the tiles
+    // x * per_xcd .. (x + 1) * per_xcd - 1 of the order (k split, column band, row block), row block fastest: every XCD
+    // gets the same number of tiles (to within one), and the ~32 tiles resident on it are a few adjacent bands times
+    // all row blocks, which share W bands and X row blocks through its L2.
+    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    const int tile_id = xcd * per_xcd + local;
+    if (local >= per_xcd || tile_id >= n_tile_total) return;
+    const int per_split = n_bands * row_blocks;
+    const int bz = tile_id / per_split, rem = tile_id - bz * per_split;
+    const int bx = rem / row_blocks, by = rem - bx * row_blocks;
     const int row0 = by * BM;
-    const int ntile0 = (bx * WN + wn) * NT;
+    // the wave's two column tiles: adjacent ones, except for the QKV epilogue with 128-wide heads, where a wave takes
+    // the tiles 64 columns apart that hold the two members of the rotate-half pairs
+    int ntile[NT];
+    if (EPI == EPI_ROPE && ep.hd == 128) {
+        ntile[0] = bx * 8 + (wn >> 1) * 4 + (wn & 1);
+        ntile[1] = ntile[0] + 2;
+    } else {
+        ntile[0] = (bx * WN + wn) * NT;
+        ntile[1] = ntile[0] + 1;
+    }
     const int total_chunks = k_tiles / KT;
     const int c_begin = bz * chunks_per_split;
     const int c_end = min(c_begin + chunks_per_split, total_chunks);
     const int n_chunks = c_end - c_begin;
     if (n_chunks <= 0) return;
 
+    // The accumulators start at zero -- or, for the residual epilogue, at the tile of h they are added to: those loads
+    // fly with the prologue's, and the epilogue is then a plain store.
     f32x16_t acc[MT][NT];
 #pragma unroll
     for (int i = 0; i < MT; i++)
 #pragma unroll
         for (int j = 0; j < NT; j++)
 #pragma unroll
-            for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
+            for (int r = 0; r < 16; r++) {
+                acc[i][j][r] = 0.f;
+                if (EPI == EPI_RESIDUAL) {
+                    const int m = row0 + i * 32 + 8 * (r >> 2) + (lane >> 5) * 4 + (r & 3);
+                    if (m < M && ntile[j] < n_tiles) acc[i][j][r] = ep.h[m * N + ntile[j] * 32 + (lane & 31)];
+                }
+            }
 
     // W: lane pointer into each of the wave's two bands (clamped on a ragged last block; never stored)
     const uint4 *wband[NT];
 #pragma unroll
     for (int j = 0; j < NT; j++) {
-        int t = min(ntile0 + j, n_tiles - 1);
+        int t = min(ntile[j], n_tiles - 1);
         wband[j] = Wp + ((size_t)t * k_tiles) * 64 + lane;
     }
-    // X: wave wn brings rows 64 wn .. 64 wn + 63 of the block, 8 rows per load; lane = (row in the 8, piece p)
-    int xoff[8];
+    // X: wave wn brings rows 8 MT wn .. 8 MT (wn + 1) - 1 of the block, 8 rows per load; lane = (row in the 8, piece p)
+    int xoff[MT];
 #pragma unroll
-    for (int i = 0; i < 8; i++) {
-        const int r = wn * 64 + i * 8 + (lane >> 3), p = lane & 7;
+    for (int i = 0; i < MT; i++) {
+        const int r = wn * (MT * 8) + i * 8 + (lane >> 3), p = lane & 7;
         const int row = min(row0 + r, M - 1);
         xoff[i] = (row * K + ((p ^ ((r >> 1) & 7)) << 3)) * 2;   // bytes
     }
@@ -91,8 +206,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_big_kernel(const T *__restrict_
     Frag w0[NT][KT], w1[NT][KT], xa[MT], xb[MT];
 
 #define FG_X_ISSUE(chunk, stage)                                                                          \
-    _Pragma("unroll") for (int i = 0; i < 8; i++) __builtin_amdgcn_raw_ptr_buffer_load_lds(               \
-        xrsrc, (stage) + (wn * 64 + i * 8) * 8, 16, xoff[i], __builtin_amdgcn_readfirstlane((chunk) * 128), 0, 0)
+    _Pragma("unroll") for (int i = 0; i < MT; i++) __builtin_amdgcn_raw_ptr_buffer_load_lds(              \
+        xrsrc, (stage) + (wn * (MT * 8) + i * 8) * 8, 16, xoff[i], __builtin_amdgcn_readfirstlane((chunk) * 128), 0, 0)
 #define FG_W_LOAD(set, chunk, kt) \
     _Pragma("unroll") for (int j = 0; j < NT; j++) set[j][kt].u = wband[j][(size_t)((chunk) * KT + (kt)) * 64]
 #define FG_X_READ(dst, stage_base, kt) \
@@ -119,18 +234,18 @@ __global__ __launch_bounds__(256) void gemm_mfma_big_kernel(const T *__restrict_
     FG_FENCE();
     FG_W_LOAD(w1, clampc(c_begin + 1), 3);
     FG_FENCE();
-    // X(0) landed.  Only the 16 direct-to-LDS loads behind it are counted: the compiler may move the register
+    // X(0) landed.  Only the 2 MT direct-to-LDS loads behind it are counted: the compiler may move the register
     // loads of the prologue, and a stricter wait costs nothing here.
-    __builtin_amdgcn_s_waitcnt(waitcnt_imm(16, 0));
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * MT, 0));
     __builtin_amdgcn_s_barrier();
     FG_FENCE();
     FG_X_READ(xa, xs0, 0);
 
     // One chunk: `cur` holds its W fragments and is refilled with chunk c + 2; st = its stage, sn = the next one.
-    // Within a k tile the instruction stream is laid out as 8 x {2 MFMAs, 1 fragment read (, 1 X load)} followed by
+    // Within a k tile the instruction stream is laid out as MT x {2 MFMAs, 1 fragment read (, 1 X load)} followed by
     // the two W loads, so that the LDS and memory instructions issue under the running MFMAs instead of in a clump.
 #define FG_PIPE(with_x)                                                                               \
-    _Pragma("unroll") for (int q = 0; q < 8; q++) {                                                   \
+    _Pragma("unroll") for (int q = 0; q < MT; q++) {                                                  \
         __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                            \
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                            \
         if (with_x) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                \
@@ -156,7 +271,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_big_kernel(const T *__restrict_
         FG_W_LOAD(cur, c2, 2);                                                                        \
         FG_PIPE(0);                                                                                     \
         FG_FENCE();                                                                                   \
-        __builtin_amdgcn_s_waitcnt(waitcnt_imm(24, 0));                                               \
+        __builtin_amdgcn_s_waitcnt(waitcnt_imm(16 + MT, 0));                                          \
         __builtin_amdgcn_s_barrier();                                                                 \
         FG_FENCE();                                                                                   \
         FG_X_ISSUE(c3, st);                                                                           \
@@ -191,71 +306,98 @@ __global__ __launch_bounds__(256) void gemm_mfma_big_kernel(const T *__restrict_
 #undef FG_MFMA
 #undef FG_FENCE
 
-    store_tiles<T, MT, NT, EPI>(acc, out, M, N, row0, ntile0, n_tiles, bz, lane);
+    if (EPI == EPI_ROPE) {
+        __syncthreads();   // every wave has drained its loads into, and finished reading, the stages: stage 0 is free
+        epilogue_rope<T, MT>(acc, ep, M, row0, ntile[0], n_tiles, lane, reinterpret_cast<T *>(xs0) + wn * 2048);
+    } else if (EPI == EPI_RESIDUAL) {
+        store_tiles<T, MT, NT, EPI_SLABS>(acc, ep.h, M, N, row0, ntile[0], n_tiles, 0, lane);
+    } else {
+        store_tiles<T, MT, NT, EPI>(acc, out, M, N, row0, ntile[0], n_tiles, bz, lane);
+    }
 #endif
 }
 
-// Split and band-group choice by a small cost model (in microseconds).  The grid deals whole units (one k split of
-// one group of BG bands, row_blocks x BG tiles) to the 8 XCDs, so the busiest XCD sets the number of rounds its 32
-// CUs need; a round costs the split's chunks plus about 8 chunk-times of prologue and epilogue; every extra split
-// adds an fp32 slab the consumer has to read back.
-struct BigPlan { int split, bg; };
-static BigPlan plan_big(int M, int N, int K, int fixed_split)
+// Split and block-height choice.  Tiles are dealt evenly to the 8 XCDs and then to their 32 CUs, so the busiest CU runs
+// ceil(ceil(tiles / 8) / 32) blocks one after the other (or side by side, sharing the matrix pipe: the same time); a
+// block costs the split's chunks plus about 8 chunk-times of prologue and epilogue, a chunk 1.45 us for 256 rows and in
+// proportion (+9 %) for shorter blocks; every extra split adds an fp32 slab the consumer has to read back.  Measured
+// on the 7B-class shapes (us, 2048 rows): QKV 99 in 256-row blocks (144 tiles), 103 in 128-row blocks (288), against
+// 61 predicted for 160-row blocks (234 tiles, one round); O 92 / 55 (256 / 128 rows); down 414 / 241, 236 with two
+// splits of 256-row blocks.  The wide outputs (gate/up, LM head) have thousands of tiles: 128-row blocks, two to a CU,
+// each one's prologue and epilogue under the other's main loop, are 4 - 8 % faster up to 2048 rows (gate/up 486 against
+// 506 us at 2048 rows, 248 against 269 at 1024) and 2 % slower at 4096.
+struct BigPlan { int split, mt; };
+static BigPlan plan_big(int M, int N, int K, int fixed_split, int fixed_mt)
 {
-    const int n_bands = (N / 32 + 7) / 8, row_blocks = (M + 255) / 256, chunks = K / 64;
-    BigPlan best{1, 1};
+    const int n_bands = (N / 32 + 7) / 8, chunks = K / 64;
+    if (N >= 16384 && fixed_mt <= 0) fixed_mt = M <= 2048 ? 4 : 8;
+    BigPlan best{fixed_split > 0 ? fixed_split : 1, fixed_mt > 0 ? fixed_mt : 8};
     double best_cost = 1e30;
-    const int s_max = row_blocks == 1 ? 16 : 8;   // one row block: the slabs are small, the grid needs the splits
-    for (int s = 1; s <= s_max; s++) {
-        if (fixed_split > 0 && s != fixed_split) continue;
-        if (fixed_split <= 0 && s > 1 && chunks / s < 8) break;
-        const int cps = (chunks + s - 1) / s;
-        if ((chunks + cps - 1) / cps != s) continue;   // some split would be empty
-        for (int bg = 1; bg <= 4; bg *= 2) {
-            const int units = (n_bands + bg - 1) / bg * s;
-            const int xcd_blocks = (units + 7) / 8 * row_blocks * bg;
-            const int rounds = (xcd_blocks + 31) / 32;
-            double cost = rounds * (cps + 8) * 1.45 + (s - 1) * (double)M * N * 4 * 1.3 / 4.5e6;
-            cost -= 0.01 * bg;   // equal otherwise: wider groups share more of X in L2
-            if (cost < best_cost) { best_cost = cost; best = BigPlan{s, bg}; }
+    static const int heights[3] = {8, 5, 4};
+    for (int mt : heights) {
+        if (fixed_mt > 0 && mt != fixed_mt) continue;
+        const int row_blocks = (M + 32 * mt - 1) / (32 * mt);
+        const int s_max = row_blocks == 1 ? 16 : 8;   // one row block: the slabs are small, the grid needs the splits
+        const double chunk_us = 1.45 * mt / 8 * (mt == 8 ? 1.0 : 1.09);
+        for (int s = 1; s <= s_max; s++) {
+            if (fixed_split > 0 && s != fixed_split) continue;
+            if (fixed_split <= 0 && s > 1 && chunks / s < 8) break;
+            const int cps = (chunks + s - 1) / s;
+            if ((chunks + cps - 1) / cps != s) continue;   // some split would be empty
+            const int per_xcd = (n_bands * row_blocks * s + 7) / 8, per_cu = (per_xcd + 31) / 32;
+            double cost = per_cu * (cps + (mt == 4 && per_cu >= 2 ? 2 : 8)) * chunk_us;
+            cost += (s - 1) * (double)M * N * 4 * 1.3 / 4.5e6;
+            if (cost < best_cost) { best_cost = cost; best = BigPlan{s, mt}; }
         }
     }
-    if (fixed_split > 0 && best_cost == 1e30) best = BigPlan{fixed_split, 1};
     return best;
 }
 
-int gemm_mfma_big_split_for(int M, int N, int K) { return plan_big(M, N, K, 0).split; }
+int gemm_mfma_big_split_for(int M, int N, int K) { return plan_big(M, N, K, 0, 0).split; }
 
-template <typename T>
-static void launch_big_typed(const void *x, const void *wp, void *out, int M, int N, int K, int epilogue, int split, int raster_on,
-                             hipStream_t st)
+template <typename T, int MT>
+static void launch_big_typed(const void *x, const void *wp, void *out, int M, int N, int K, int epilogue, int split,
+                             const GemmEpi &ep, hipStream_t st)
 {
     const int n_tiles = N / 32, per_block = 8;
     const int total_chunks = K / 64;
     const int cps = (total_chunks + split - 1) / split;
-    const int n_bands = (n_tiles + per_block - 1) / per_block, row_blocks = (M + 255) / 256;
-    dim3 grid(n_bands, row_blocks, split);
-    int BG = 0;
-    if (raster_on) {
-        BG = plan_big(M, N, K, split).bg;
-        const int units = (n_bands + BG - 1) / BG * split;
-        grid = dim3((unsigned)(8 * ((units + 7) / 8) * row_blocks * BG));
+    const int n_bands = (n_tiles + per_block - 1) / per_block, row_blocks = (M + 32 * MT - 1) / (32 * MT);
+    const int total = n_bands * row_blocks * split, per_xcd = (total + 7) / 8;
+    const dim3 grid((unsigned)(8 * per_xcd));
+#define FG_BIG_LAUNCH(E)                                                                                          \
+    hipLaunchKernelGGL((gemm_mfma_big_kernel<T, MT, E>), grid, dim3(256), 0, st, reinterpret_cast<const T *>(x),  \
+                       reinterpret_cast<const uint4 *>(wp), out, M, N, K, cps, n_bands, row_blocks, per_xcd, total, ep)
+    switch (epilogue) {
+    case EPI_SLABS: FG_BIG_LAUNCH(EPI_SLABS); break;
+    case EPI_SWIGLU: FG_BIG_LAUNCH(EPI_SWIGLU); break;
+    case EPI_ROPE: FG_BIG_LAUNCH(EPI_ROPE); break;
+    default: FG_BIG_LAUNCH(EPI_RESIDUAL); break;
     }
-    if (epilogue == 0)
-        hipLaunchKernelGGL((gemm_mfma_big_kernel<T, 0>), grid, dim3(256), 0, st, reinterpret_cast<const T *>(x),
-                           reinterpret_cast<const uint4 *>(wp), out, M, N, K, cps, BG, row_blocks);
-    else
-        hipLaunchKernelGGL((gemm_mfma_big_kernel<T, 1>), grid, dim3(256), 0, st, reinterpret_cast<const T *>(x),
-                           reinterpret_cast<const uint4 *>(wp), out, M, N, K, cps, BG, row_blocks);
+#undef FG_BIG_LAUNCH
 }
 
 // Shapes were validated by the caller (launch_gemm_mfma); M * K < 2^30 is needed by the 32-bit byte offsets.
+// fixed_mt: 0 = the plan's block height, else 8, 5 or 4 (row tiles of 32 per block).
 int32_t launch_gemm_mfma_big(int32_t dtype, const void *x, const void *wp, void *out, int M, int N, int K, int epilogue,
-                             int split, int raster_on, hipStream_t st)
+                             int split, int fixed_mt, const GemmEpi *epi, hipStream_t st)
 {
     if ((int64_t)M * K >= (1LL << 30)) return fail(FG_ERR_SHAPE, "GEMM input of %d x %d exceeds 2^30 elements", M, K);
-    if (dtype == FG_BF16) launch_big_typed<bf16_t>(x, wp, out, M, N, K, epilogue, split, raster_on, st);
-    else launch_big_typed<f16_t>(x, wp, out, M, N, K, epilogue, split, raster_on, st);
+    if (epilogue >= EPI_ROPE && split != 1) return fail(FG_ERR_INVALID_ARG, "fused GEMM epilogue %d cannot run with a k split", epilogue);
+    if (epilogue > EPI_RESIDUAL) return fail(FG_ERR_UNIMPLEMENTED, "GEMM epilogue %d", epilogue);
+    if (epilogue >= EPI_ROPE && !epi) return fail(FG_ERR_INVALID_ARG, "GEMM epilogue %d needs its arguments", epilogue);
+    if (epilogue == EPI_ROPE && (epi->hd != 64 && epi->hd != 128)) return fail(FG_ERR_SHAPE, "RoPE epilogue needs head_dim 64 or 128");
+    const BigPlan p = plan_big(M, N, K, split, fixed_mt);
+    const GemmEpi ep = epi ? *epi : GemmEpi();
+#define FG_BIG_MT(T)                                                                                   \
+    do {                                                                                               \
+        if (p.mt == 8) launch_big_typed<T, 8>(x, wp, out, M, N, K, epilogue, split, ep, st);           \
+        else if (p.mt == 5) launch_big_typed<T, 5>(x, wp, out, M, N, K, epilogue, split, ep, st);      \
+        else launch_big_typed<T, 4>(x, wp, out, M, N, K, epilogue, split, ep, st);                     \
+    } while (0)
+    if (dtype == FG_BF16) FG_BIG_MT(bf16_t);
+    else FG_BIG_MT(f16_t);
+#undef FG_BIG_MT
     FG_LAUNCH_CHECK("gemm_mfma_big");
     return FG_OK;
 }

@@ -24,6 +24,16 @@ CODES = {"bf16": 1, "fp16": 2}
 TD = {"bf16": torch.bfloat16, "fp16": torch.float16, "fp32": torch.float32}
 
 
+def gemm_sum(fg, code, x, wp, N, **kw):
+    """x . W^T through fg_gemm's partial-sum epilogue: the k-split slabs added in slab order (what the library's
+    consumer kernels do); returns (sum [M, N] fp32, number of slabs)."""
+    slabs, used = fg.fg_gemm(code, x, wp, N, epilogue=0, **kw)
+    out = slabs[0].clone()
+    for s in range(1, used):
+        out += slabs[s]
+    return out, used
+
+
 @pytest.mark.parametrize("M,N,K", [(1, 64, 64), (8, 4608, 3584), (48, 3584, 3584), (40, 96, 128), (130, 1024, 704 - 64),
                                    (192, 3584, 18944), (256, 512, 256), (257, 544, 192), (700, 4608, 1536)])
 @pytest.mark.parametrize("dtype", ["bf16", "fp16"])
@@ -35,14 +45,14 @@ def test_gemm_16bit_partial_epilogue(fg, M, N, K, dtype):
     ref = x.double() @ w.double().T
     wp = fg.fg_pack_weight(code, w.cuda())
     for split in (0, 1, 3):
-        out, used = fg.fg_gemm(code, x.cuda(), wp, N, epilogue=0, split_k=split)
+        out, used = gemm_sum(fg, code, x.cuda(), wp, N, split_k=split)
         torch.cuda.synchronize()
         err = (out.double().cpu() - ref).abs().max().item()
         scale = ref.abs().max().item()
         assert err <= 2e-5 * scale + 1e-4, (split, used, err, scale)
     # run twice: split-K slabs are summed in a fixed order, so results are bitwise repeatable
-    a, _ = fg.fg_gemm(code, x.cuda(), wp, N)
-    b, _ = fg.fg_gemm(code, x.cuda(), wp, N)
+    a, _ = gemm_sum(fg, code, x.cuda(), wp, N)
+    b, _ = gemm_sum(fg, code, x.cuda(), wp, N)
     assert torch.equal(a, b)
 
 
@@ -57,7 +67,7 @@ def test_gemm_16bit_many_rows_every_k_tail(fg, chunks):
         x, w = bf16_randn((M, K), g, dt=TD[dtype]), bf16_randn((N, K), g, 0.05, dt=TD[dtype])
         ref = x.double() @ w.double().T
         wp = fg.fg_pack_weight(CODES[dtype], w.cuda())
-        out, used = fg.fg_gemm(CODES[dtype], x.cuda(), wp, N, epilogue=0, split_k=1)
+        out, used = gemm_sum(fg, CODES[dtype], x.cuda(), wp, N, split_k=1)
         torch.cuda.synchronize()
         err = (out.double().cpu() - ref).abs().max().item()
         assert used == 1 and err <= 2e-5 * ref.abs().max().item() + 1e-4, (dtype, err)
@@ -78,7 +88,7 @@ def test_gemm_16bit_few_rows_every_k_tail(fg, chunks):
         ref = x.double() @ w.double().T
         wp = fg.fg_pack_weight(CODES[dtype], w.cuda())
         for split in (0, 1, 2, 3, 5):
-            out, used = fg.fg_gemm(CODES[dtype], x.cuda(), wp, N, epilogue=0, split_k=split)
+            out, used = gemm_sum(fg, CODES[dtype], x.cuda(), wp, N, split_k=split)
             torch.cuda.synchronize()
             err = (out.double().cpu() - ref).abs().max().item()
             assert err <= 2e-5 * ref.abs().max().item() + 1e-4, (dtype, M, split, used, err)
@@ -108,11 +118,63 @@ def test_gemm_16bit_swiglu_epilogue(fg, M, F, K, dtype):
     assert (err <= 2 ** -8 * ref.abs() + 1e-3).all(), err.max().item()
 
 
+@pytest.mark.parametrize("variant", [3, 4, 5])
+@pytest.mark.parametrize("chunks", [1, 2, 5, 6, 7, 13])
+def test_gemm_16bit_pipelined_block_heights_and_residual_epilogue(fg, variant, chunks):
+    """The pipelined kernel with 256-row and with 128-row blocks (the latter two to a CU), forced through fg_gemm's
+    variant: partial-sum slabs with and without a k split, SwiGLU, and the residual epilogue (out += x . W^T in place),
+    on ragged row blocks and a ragged last column band."""
+    print(f"pipelined variant {variant} chunks={chunks}", flush=True)
+    K = 64 * chunks
+    g = torch.Generator().manual_seed(17 * variant + chunks)
+    for dtype, M, N in (("bf16", 300, 288), ("fp16", 129, 544), ("bf16", 1100, 256), ("fp16", 640, 96)):
+        code, dt = CODES[dtype], TD[dtype]
+        x, w = bf16_randn((M, K), g, dt=dt), bf16_randn((N, K), g, 0.05, dt=dt)
+        ref = x.double() @ w.double().T
+        wp = fg.fg_pack_weight(code, w.cuda())
+        for split in (1, 2):
+            out, used = gemm_sum(fg, code, x.cuda(), wp, N, split_k=split, variant=variant)
+            torch.cuda.synchronize()
+            err = (out.double().cpu() - ref).abs().max().item()
+            assert err <= 2e-5 * ref.abs().max().item() + 1e-4, (dtype, M, N, split, used, err)
+        h0 = torch.randn((M, N), generator=g, dtype=torch.float32)
+        h = h0.clone().cuda()
+        fg.fg_gemm(code, x.cuda(), wp, N, epilogue=3, variant=variant, out=h)
+        torch.cuda.synchronize()
+        err = (h.double().cpu() - (h0.double() + ref)).abs().max().item()
+        assert err <= 2e-5 * ref.abs().max().item() + 1e-4, (dtype, M, N, "residual", err)
+        F = 64 if N % 64 else N // 2
+        wg, wu = bf16_randn((F, K), g, 0.05, dt=dt), bf16_randn((F, K), g, 0.05, dt=dt)
+        act = torch.nn.functional.silu(x.double() @ wg.double().T) * (x.double() @ wu.double().T)
+        wp2 = fg.fg_pack_weight(code, wg.cuda(), wu.cuda())
+        out, _ = fg.fg_gemm(code, x.cuda(), wp2, 2 * F, epilogue=1, variant=variant)
+        torch.cuda.synchronize()
+        err = (out.double().cpu() - act).abs()
+        assert (err <= 2 ** -8 * act.abs() + 1e-3).all(), (dtype, M, err.max().item())
+
+
+def test_gemm_residual_epilogue_is_the_library_choice_for_many_rows(fg):
+    """At 1024 rows and more the O / down projections add into the residual stream in their own epilogue."""
+    M, N, K = 1024, 512, 320
+    g = torch.Generator().manual_seed(5)
+    x, w = bf16_randn((M, K), g), bf16_randn((N, K), g, 0.05)
+    wp = fg.fg_pack_weight(fg.FG_BF16, w.cuda())
+    h0 = torch.randn((M, N), generator=g, dtype=torch.float32)
+    h = h0.clone().cuda()
+    fg.fg_gemm(fg.FG_BF16, x.cuda(), wp, N, epilogue=3, out=h)
+    torch.cuda.synchronize()
+    ref = h0.double() + x.double() @ w.double().T
+    assert (h.double().cpu() - ref).abs().max().item() <= 1e-4 + 2e-5 * ref.abs().max().item()
+    assert fg.fg_gemm_kernel_name(M, N, K, 3) == "gemm_mfma_big_kernel"
+    with pytest.raises(fg.FgError):
+        fg.fg_gemm(fg.FG_BF16, x.cuda(), wp, N, epilogue=3, variant=2, out=h)
+
+
 def test_gemm_f32(fg):
     g = torch.Generator().manual_seed(1)
     x, w = torch.randn((37, 704), generator=g), torch.randn((1024, 704), generator=g) * 0.05
     wp = fg.fg_pack_weight(fg.FG_F32, w.cuda())
-    out, _ = fg.fg_gemm(fg.FG_F32, x.cuda(), wp, 1024)
+    out, _ = gemm_sum(fg, fg.FG_F32, x.cuda(), wp, 1024)
     torch.cuda.synchronize()
     ref = x.double() @ w.double().T
     assert (out.double().cpu() - ref).abs().max().item() < 1e-4
