@@ -719,8 +719,15 @@ def b8_point(wl, N, args):
     with torch.cuda.graph(graph):
         f()
     tg = time_each(torch, graph.replay, max(args.steps, 30), args.warmup)
+    # where the step's time goes (a separate pass: at this size the events between launches cost a few per cent)
+    reps = 20
+    fg.fg_model_profile(wl.gm, True, max_marks=(reps + 1) * (wl.model["n_layers"] * 10 + 16))
+    for _ in range(reps):
+        f()
+    stage_us = {k: v[0] / reps * 1e3 for k, v in fg.fg_model_profile_read(wl.gm).items() if v[1]}
+    fg.fg_model_profile(wl.gm, False)
     acct = model_bytes_flops(wl.model, B * N, lengths.astype(np.float64), N)
-    return dict(B=B, N=N, verify_ms=t * 1e3, hbm_frac=acct["bytes"] / t / PEAK_HBM, mfma_frac=acct["flops"] / t / PEAK_MFMA,
+    return dict(B=B, N=N, verify_ms=t * 1e3, stage_us=stage_us, hbm_frac=acct["bytes"] / t / PEAK_HBM, mfma_frac=acct["flops"] / t / PEAK_MFMA,
                 verify_spread=spread(ts), graph_verify_ms=tg[0] * 1e3, graph_hbm_frac=acct["bytes"] / tg[0] / PEAK_HBM,
                 graph_verify_spread=spread(tg), bytes=acct["bytes"])
 

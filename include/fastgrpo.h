@@ -88,12 +88,22 @@ typedef struct {
  * The library fills the cache itself (fg_spec_verify / fg_draft_step append, fg_kv_compact moves); a caller only
  * needs the formulas to plant or inspect contents.
  * Token t of a sequence in cache slot s is entry t % page_size of page page_table[s][t / page_size].
- * page_size must be 16.  seq_len[s] is the committed length; only fg_kv_compact changes it.
+ * page_size must be 16.  seq_len[s] is the committed length; only fg_kv_compact (and fg_draft_step's n_commit) change it.
+ *
+ * Capacity.  Lengths live on the device, so the host cannot know that a call runs past a sequence's page table
+ * (max_pages_per_seq * page_size tokens) or past the RoPE table (max_pos); the kernels then do no harm and say so in
+ * `status` (device int32, zeroed by the caller, optional): a new node whose slot lies beyond the page table is not
+ * appended (FG_CACHE_OVERFLOW; its logits are still computed, without itself among its keys), a commit or compaction
+ * that would run past the page table is not applied and the length stays (FG_CACHE_OVERFLOW), a position beyond max_pos
+ * is rotated as max_pos - 1 (FG_POS_OVERFLOW).  Committed tokens are never overwritten.  A caller that knows its
+ * lengths on the host should check before the call; the flags are the backstop.
  */
+typedef enum { FG_CACHE_OVERFLOW = 1, FG_POS_OVERFLOW = 2 } fg_cache_flags;
 typedef struct {
     void *k_pool, *v_pool;          /* device                                                               */
     const int32_t *page_table;      /* device [n_slots][max_pages_per_seq]                                  */
     int32_t *seq_len;               /* device [n_slots]                                                     */
+    int32_t *status;                /* device [1] or NULL: sticky fg_cache_flags the kernels OR in          */
     int32_t n_layers, n_kv_heads, head_dim, dtype;
     int32_t page_size, max_pages_per_seq, n_pages, n_slots;
 } fg_kv_cache;
@@ -136,7 +146,7 @@ int32_t fg_plan(int32_t B_cur, float C_peak, float alpha, int32_t K_max, int32_t
 int32_t fg_knee(const double *x, const double *y, int32_t n, int32_t *knee_index);
 
 /*
- * Row selection for the live set (Alg. 1, the update of B_cur: finished sequences leave the batch):
+ * Row selection for the live set (Alg. 1, the update of the live batch size: finished sequences leave the batch):
  * dst[i] = src[index[i]] for i < n, rows of row_bytes bytes (a multiple of 4), all device pointers; index values
  * are clamped into [0, n_src - 1].  dst must not overlap src.
  */
@@ -161,12 +171,18 @@ int32_t fg_pack_weight(int32_t dtype, const void *src, const void *src2, void *d
 int32_t fg_model_create(const fg_model_cfg *cfg, const fg_weights *w, fg_model **out);
 int32_t fg_model_destroy(fg_model *m);
 
-/* Bytes of caller-provided device workspace fg_spec_verify / fg_draft_step need for up to max_rows = B * N
- * rows per call with caches of at most max_seq_len tokens.  256-byte aligned base expected. */
+/* Bytes of caller-provided device workspace that suffice for every fg_spec_verify / fg_draft_step call on this model
+ * with B * N <= max_rows rows (any B, any N <= FG_MAX_NODES, logits kept in the workspace) and caches of at most
+ * max_seq_len tokens.  256-byte aligned base expected.  Host only.  fg_workspace_bytes_for is the same from a
+ * configuration (is_draft: the model has an fc matrix); fg_step_workspace_bytes is what one call of a given shape
+ * carves (with_logits: logits == NULL while row_argmax / row_top2 / child lists are asked for).  0 on bad arguments. */
 int64_t fg_workspace_bytes(const fg_model *m, int32_t max_rows, int32_t max_seq_len);
+int64_t fg_workspace_bytes_for(const fg_model_cfg *cfg, int32_t is_draft, int32_t max_rows, int32_t max_seq_len);
+int64_t fg_step_workspace_bytes(const fg_model_cfg *cfg, int32_t is_draft, int32_t B, int32_t N, int32_t max_seq_len,
+                                int32_t with_logits);
 
 /*
- * Verification (Alg. 1 "verify selected tokens in parallel"; Sec. 2): one target forward over the B * N new
+ * Verification (Alg. 1, the verification step; Sec. 2 "Verification Strategies"): one target forward over the B * N new
  * nodes with tree attention against the paged cache.  Appends K/V of every node at slots seq_len + n_prev + j
  * (lengths are NOT changed; fg_kv_compact commits).  Outputs, each optional (NULL to skip), row r = b * N + j:
  *   logits      fp32 [B*N, vocab]
@@ -181,8 +197,9 @@ int32_t fg_spec_verify(fg_model *m, fg_kv_cache *kv, const fg_tree *tree, float 
                        int32_t *row_argmax, float *row_top2, void *workspace, int64_t workspace_bytes, void *stream);
 
 /*
- * Acceptance (Alg. 1 "extract accepted tokens"; Sec. 2 "accepts the longest path whose generated tokens match
- * the draft tokens under strict token-level comparison").  Per sequence, from the root: the target's token t
+ * Acceptance (Alg. 1, the step after verification; Sec. 2 "Verification Strategies": the longest root path whose
+ * draft tokens each equal the token the target itself emits at the parent survives).  Per sequence, from the root: the
+ * target's token t
  * after the current node u is
  *   FG_ACCEPT_GREEDY        row_argmax[u] if given, else the argmax of logits[u];
  *   FG_ACCEPT_SAMPLE_MATCH  argmax_v logits[u][v] / temperature + Gumbel(seed, row0 + row of u, v);
@@ -222,7 +239,7 @@ int32_t fg_spec_accept_static(const fg_tree *tree, int32_t mode, const float *lo
                               int32_t *out_tokens, int32_t *finished, void *stream);
 
 /*
- * KV compaction in place (implied by Alg. 1 "update S_generated": rejected nodes are dropped).  For sequence b
+ * KV compaction in place (implied by Alg. 1, the update of the generated sequences: rejected nodes are dropped).  For sequence b
  * with committed length L: in-round slot L + path[b][j] moves to L + j for j = 0..accept_len[b], K and V of
  * every layer and head; then seq_len += accept_len[b] + 1.  path rows must increase strictly with
  * path[j] >= j (what fg_spec_accept emits); rows that do not are left untouched and their length unchanged.
@@ -235,7 +252,7 @@ int32_t fg_kv_compact(fg_kv_cache *kv, const int32_t *slot, const int32_t *accep
                       int32_t feat_dtype, void *stream);
 
 /*
- * One drafting step (Alg. 1 "generate children for K_draft paths"; Sec. 2 "Draft Model Architectures"): the
+ * One drafting step (Alg. 1, the drafting loop's child generation; Sec. 2 "Draft Model Architectures"): the
  * draft head runs on B * tree->N new in-round nodes.  Node input = fc(embed(token) ++ feature row); one decoder
  * layer against the draft's own paged cache with tree attention; the output hidden state is decoded by the
  * target's LM head; per node the K_draft most likely tokens and their log-probabilities come back.
@@ -258,7 +275,7 @@ int32_t fg_draft_step(fg_model *target, fg_model *draft, fg_kv_cache *draft_kv, 
                       float *child_logp, void *out_feature, void *workspace, int64_t workspace_bytes, void *stream);
 
 /*
- * Frontier update between drafting steps (Alg. 1 "update candidate tokens T_candi").  The K_in expanded nodes
+ * Frontier update between drafting steps (Alg. 1, the drafting loop's update of the candidate set).  The K_in expanded nodes
  * of this step have candidate indices node_cand [B, K_in] and scores node_score [B, K_in]; their K_in * K
  * children (child_tok / child_logp from fg_draft_step) are appended to the candidate lists at index n_cand
  * (cand_* are [B, cand_stride]) with score = parent score + log-probability, and the K best children (ties:
@@ -282,7 +299,7 @@ int32_t fg_draft_frontier(int32_t B, int32_t K_in, int32_t K, const int32_t *chi
                           int32_t *parent_next, void *stream);
 
 /*
- * Rerank (Alg. 1 "select N_verify tokens from T_candi based on their confidences").  Candidate 0 is the root;
+ * Rerank (Alg. 1, the selection of the N_verify most confident candidates).  Candidate 0 is the root;
  * cand_parent[i] < i.  Selects the root and the N - 1 best-scoring other candidates (ties: lower index), orders
  * them by (depth, candidate index) and writes tokens [B, N], parent [B, N] (parent[0] = -1, parent[i] < i) and
  * sel [B, N] (candidate index of each node; optional).  Scores must not increase from parent to child; a

@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfastgrpo.so")
 
 EXPORTS = ["fg_last_error", "fg_plan", "fg_packed_bytes", "fg_pack_weight", "fg_model_create", "fg_model_destroy",
-           "fg_workspace_bytes", "fg_spec_verify", "fg_spec_accept", "fg_kv_compact", "fg_draft_step",
+           "fg_workspace_bytes", "fg_workspace_bytes_for", "fg_step_workspace_bytes", "fg_spec_verify", "fg_spec_accept", "fg_kv_compact", "fg_draft_step",
            "fg_draft_frontier", "fg_build_tree", "fg_gemm", "fg_attention", "fg_attention_workspace_bytes",
            "fg_topk_logp", "fg_knee", "fg_select_rows", "fg_model_profile",
            "fg_model_profile_read", "fg_gemm_kernel_name", "fg_spec_accept_static", "fg_probe_read", "fg_probe_copy", "fg_probe_mfma"]
@@ -42,7 +42,8 @@ class Weights(C.Structure):
 
 
 class KvCacheC(C.Structure):
-    _fields_ = [("k_pool", C.c_void_p), ("v_pool", C.c_void_p), ("page_table", C.c_void_p), ("seq_len", C.c_void_p)] + \
+    _fields_ = [("k_pool", C.c_void_p), ("v_pool", C.c_void_p), ("page_table", C.c_void_p), ("seq_len", C.c_void_p),
+                ("status", C.c_void_p)] + \
                [(n, C.c_int32) for n in ("n_layers", "n_kv_heads", "head_dim", "dtype", "page_size", "max_pages_per_seq",
                                          "n_pages", "n_slots")]
 
@@ -67,6 +68,10 @@ def lib():
         L.fg_packed_bytes.argtypes = [C.c_int32, C.c_int64, C.c_int64]
         L.fg_workspace_bytes.restype = C.c_int64
         L.fg_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+        L.fg_workspace_bytes_for.restype = C.c_int64
+        L.fg_workspace_bytes_for.argtypes = [C.POINTER(ModelCfg), C.c_int32, C.c_int32, C.c_int32]
+        L.fg_step_workspace_bytes.restype = C.c_int64
+        L.fg_step_workspace_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
         L.fg_attention_workspace_bytes.restype = C.c_int64
         L.fg_attention_workspace_bytes.argtypes = [C.c_int32] * 6
         L.fg_plan.argtypes = [C.c_int32, C.c_float, C.c_float, C.c_int32, C.c_int32, C.c_int32] + [C.POINTER(C.c_int32)] * 3
@@ -139,6 +144,23 @@ def fg_plan(B_cur, C_peak, alpha=0.5, K_max=4, L_max=6, N_cap=64):
     return N.value, K.value, Lr.value
 
 
+def model_cfg_struct(cfg, max_pos=8192):
+    return ModelCfg(cfg["n_layers"], cfg["d_model"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["d_ffn"],
+                    cfg["vocab"], dtype_code(cfg["dtype"]), max_pos, cfg.get("rms_eps", 1e-6), cfg.get("rope_theta", 10000.0))
+
+
+def fg_workspace_bytes_for(cfg, is_draft, max_rows, max_seq_len):
+    """Host only: the workspace that suffices for every call of at most max_rows rows (see fastgrpo.h)."""
+    c = model_cfg_struct(cfg)
+    return lib().fg_workspace_bytes_for(C.byref(c), int(is_draft), max_rows, max_seq_len)
+
+
+def fg_step_workspace_bytes(cfg, is_draft, B, N, max_seq_len, with_logits=True):
+    """Host only: what one call of shape (B, N) carves from its workspace."""
+    c = model_cfg_struct(cfg)
+    return lib().fg_step_workspace_bytes(C.byref(c), int(is_draft), B, N, max_seq_len, int(with_logits))
+
+
 # ---- weights and model ---------------------------------------------------------------------------------------
 def fg_pack_weight(dtype, src, src2=None):
     """src [n_out, n_in] (and optionally src2 of the same shape, interleaved in blocks of 32 rows) -> packed tensor."""
@@ -199,8 +221,8 @@ class Model:
             tab = (C.c_void_p * nl)(*[t.data_ptr() for t in lst])
             self._tabs.append(tab)
             setattr(w, k, C.cast(tab, C.POINTER(C.c_void_p)))
-        c = ModelCfg(cfg["n_layers"], cfg["d_model"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["d_ffn"],
-                     cfg["vocab"], self.dtype, max_pos, cfg.get("rms_eps", 1e-6), cfg.get("rope_theta", 10000.0))
+        c = model_cfg_struct(cfg, max_pos)
+        self.max_pos = max_pos
         h = C.c_void_p()
         torch.cuda.current_stream().synchronize()
         _check(lib().fg_model_create(C.byref(c), C.byref(w), C.byref(h)))
@@ -235,8 +257,23 @@ class KVCache:
         self.k_pool = torch.zeros((nl, n_pages, Hkv, page_size, hd), dtype=td, device=device)
         self.v_pool = torch.zeros((nl, n_pages, Hkv, hd, page_size), dtype=td, device=device)
         self.seq_len = torch.zeros(self.n_slots, dtype=torch.int32, device=device)
+        self.status = torch.zeros(1, dtype=torch.int32, device=device)
         self.c = KvCacheC(self.k_pool.data_ptr(), self.v_pool.data_ptr(), self.page_table.data_ptr(), self.seq_len.data_ptr(),
-                          nl, Hkv, hd, self.dtype, page_size, self.max_pages, n_pages, self.n_slots)
+                          self.status.data_ptr(), nl, Hkv, hd, self.dtype, page_size, self.max_pages, n_pages, self.n_slots)
+
+    @property
+    def capacity(self):
+        return self.max_pages * self.page_size
+
+    def check(self):
+        """Raise if a call since the last check ran past a page table or the RoPE table (reads the status word: one
+        small device-to-host copy)."""
+        flags = int(self.status.item())
+        if flags:
+            self.status.zero_()
+            what = [n for bit, n in ((1, "a sequence ran past its page table (nothing was appended or committed for it)"),
+                                     (2, "a position beyond the RoPE table was clamped")) if flags & bit]
+            raise FgError(-3, "; ".join(what))
 
     def _where(self, slot, L):
         t = torch.arange(L, device=self.k_pool.device)

@@ -25,7 +25,7 @@ int32_t fail(int32_t code, const char *fmt, ...)
 }
 
 // launchers defined in the other translation units and not listed in fg_common.h
-int32_t launch_tree_prep_ex(const fg_tree *t, const fg_kv_cache *kv, TreeDev td, hipStream_t st);
+int32_t launch_tree_prep_ex(const fg_tree *t, const fg_kv_cache *kv, TreeDev td, int max_pos, hipStream_t st);
 int32_t launch_swiglu_partials(int32_t dtype, const float *gu, int S, void *act, int M, int F, hipStream_t st);
 int32_t launch_attention_simple(const fg_kv_cache *kv, int layer, const fg_tree *t, TreeDev td, int Hq, const void *q, void *out,
                                 int max_keys, hipStream_t st);
@@ -52,7 +52,7 @@ int32_t launch_frontier(int B, int K_in, int K, const int32_t *child_tok, const 
 int32_t launch_build_tree(const int32_t *cand_tok, const int32_t *cand_parent, const float *cand_score, int B, int C, int stride,
                           int N, int32_t *tokens, int32_t *parent, int32_t *sel, hipStream_t st);
 int32_t launch_commit_len(int32_t *seq_len, const int32_t *slot, const int32_t *n_commit, int bias, int B, int n_slots,
-                          hipStream_t st);
+                          int capacity, int32_t *status, hipStream_t st);
 int gemm_mfma_split_for(int M, int N, int K);
 bool gemm_mfma_fuses_swiglu(int M, int N, int K);
 int32_t launch_probe_read(const void *src, int64_t bytes, int nontemporal, int blocks, void *sink, hipStream_t st);
@@ -154,8 +154,9 @@ struct StepWs {
     int64_t attn_ws_bytes;
 };
 
+// attn_bytes_override >= 0: size the attention workspace with that figure instead of the one of this (B, N)
 int64_t carve_step(const fg_model_cfg &c, int M, int max_keys, int B, int N, bool is_draft, void *base, int64_t cap, StepWs *w,
-                   bool need_logits)
+                   bool need_logits, int64_t attn_bytes_override = -1)
 {
     Carver cv(base, cap);
     const int64_t es = dtype_size(c.dtype);
@@ -173,11 +174,36 @@ int64_t carve_step(const fg_model_cfg &c, int M, int max_keys, int B, int N, boo
     s.feat = cv.take<char>((int64_t)M * d * es);
     s.cat = is_draft ? (void *)cv.take<char>((int64_t)M * 2 * d * es) : nullptr;
     s.logits = need_logits ? cv.take<float>((int64_t)M * c.vocab) : nullptr;
-    s.attn_ws_bytes = attention_mfma_ws_bytes(B, N, c.n_q_heads, c.n_kv_heads, c.head_dim, max_keys);
+    s.attn_ws_bytes = attn_bytes_override >= 0 ? attn_bytes_override
+                                               : attention_mfma_ws_bytes(B, N, c.n_q_heads, c.n_kv_heads, c.head_dim, max_keys);
     s.attn_ws = cv.take<char>(s.attn_ws_bytes);
     if (w) *w = s;
     if (base && !cv.ok) return -1;
     return align_up(cv.off, 256);
+}
+
+// The largest attention workspace any call of at most max_rows rows can need: the figure depends on how the keys of
+// a (sequence, kv head) pair are cut into chunks, which is monotone neither in B nor in N, so every shape
+// (N = 1 .. FG_MAX_NODES, B = 1 .. max_rows / N) is evaluated once and the result remembered.
+int64_t max_attention_ws(const fg_model_cfg &c, int max_rows, int max_keys)
+{
+    static std::mutex mu;
+    static std::map<std::array<int64_t, 5>, int64_t> memo;
+    const std::array<int64_t, 5> key = {c.n_q_heads, c.n_kv_heads, c.head_dim, max_rows, max_keys};
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        auto it = memo.find(key);
+        if (it != memo.end()) return it->second;
+    }
+    int64_t best = 0;
+    for (int N = 1; N <= FG_MAX_NODES && N <= max_rows; N++)
+        for (int B = 1; B * N <= max_rows; B++) {
+            const int64_t v = attention_mfma_ws_bytes(B, N, c.n_q_heads, c.n_kv_heads, c.head_dim, max_keys);
+            if (v > best) best = v;
+        }
+    std::lock_guard<std::mutex> lock(mu);
+    memo[key] = best;
+    return best;
 }
 
 int32_t gemm_any(const fg_model_cfg &c, const void *x, const void *w, float *partials, int M, int N, int K, int *S, hipStream_t st)
@@ -457,18 +483,24 @@ int32_t fg_model_destroy(fg_model *m)
     return FG_OK;
 }
 
+int64_t fg_workspace_bytes_for(const fg_model_cfg *cfg, int32_t is_draft, int32_t max_rows, int32_t max_seq_len)
+{
+    if (!cfg || max_rows < 1 || max_seq_len < 1 || !dtype_ok(cfg->dtype) || cfg->n_kv_heads < 1 || cfg->n_q_heads % cfg->n_kv_heads) return 0;
+    // every piece but the attention workspace grows with the row count; that one takes its maximum over all shapes
+    const int64_t attn = max_attention_ws(*cfg, max_rows, max_seq_len);
+    return carve_step(*cfg, max_rows, max_seq_len, max_rows, 1, is_draft != 0, nullptr, 0, nullptr, true, attn) + (1 << 20);
+}
+
+int64_t fg_step_workspace_bytes(const fg_model_cfg *cfg, int32_t is_draft, int32_t B, int32_t N, int32_t max_seq_len, int32_t with_logits)
+{
+    if (!cfg || B < 1 || N < 1 || max_seq_len < 1 || !dtype_ok(cfg->dtype) || cfg->n_kv_heads < 1 || cfg->n_q_heads % cfg->n_kv_heads) return 0;
+    return carve_step(*cfg, B * N, max_seq_len, B, N, is_draft != 0, nullptr, 0, nullptr, with_logits != 0);
+}
+
 int64_t fg_workspace_bytes(const fg_model *m, int32_t max_rows, int32_t max_seq_len)
 {
-    if (!m || max_rows < 1 || max_seq_len < 1) return 0;
-    // B and N only enter through the attention workspace, which is largest at N = 1 (B = max_rows) for split
-    // bookkeeping and at N = 64 for rows per sequence; take the maximum over the two extremes and powers of two.
-    int64_t best = 0;
-    for (int N = 1; N <= FG_MAX_NODES; N *= 2) {
-        int B = (max_rows + N - 1) / N;
-        int64_t v = carve_step(m->cfg, max_rows, max_seq_len, B, N, m->fc != nullptr, nullptr, 0, nullptr, true);
-        if (v > best) best = v;
-    }
-    return best + (1 << 20);
+    if (!m) return 0;
+    return fg_workspace_bytes_for(&m->cfg, m->fc != nullptr, max_rows, max_seq_len);
 }
 
 int32_t fg_spec_verify(fg_model *m, fg_kv_cache *kv, const fg_tree *tree, float *logits, void *feature, int32_t *row_argmax,
@@ -491,7 +523,7 @@ int32_t fg_spec_verify(fg_model *m, fg_kv_cache *kv, const fg_tree *tree, float 
     if (carve_step(c, M, mk, tree->B, tree->N, false, workspace, workspace_bytes, &w, need_logits) < 0)
         return fail(FG_ERR_CAPACITY, "workspace too small: have %lld bytes", (long long)workspace_bytes);
     mark(m, FG_STAGE_PREP, st);
-    if ((rc = launch_tree_prep_ex(tree, kv, w.td, st))) return rc;
+    if ((rc = launch_tree_prep_ex(tree, kv, w.td, c.max_pos, st))) return rc;
     if ((rc = launch_embed(c.dtype, m->embed, tree->tokens, c.vocab, w.h, M, c.d_model, st))) return rc;
     int S = 0;
     if ((rc = run_layers(m, kv, tree, w, mk, 0, &S, st))) return rc;
@@ -613,7 +645,7 @@ int32_t fg_draft_step(fg_model *target, fg_model *draft, fg_kv_cache *draft_kv, 
     if (carve_step(c, M, mk, tree->B, tree->N, true, workspace, workspace_bytes, &w, child_tok != nullptr) < 0)
         return fail(FG_ERR_CAPACITY, "workspace too small: have %lld bytes", (long long)workspace_bytes);
     mark(draft, FG_STAGE_PREP, st);
-    if ((rc = launch_tree_prep_ex(tree, draft_kv, w.td, st))) return rc;
+    if ((rc = launch_tree_prep_ex(tree, draft_kv, w.td, c.max_pos, st))) return rc;
     if ((rc = launch_concat_embed(c.dtype, target->embed, tree->tokens, c.vocab, in_feature, feat_index, tree->N, feat_rows, w.cat, M, d, st))) return rc;
     int S = 0;
     mark(draft, FG_STAGE_FC, st);
@@ -639,7 +671,8 @@ int32_t fg_draft_step(fg_model *target, fg_model *draft, fg_kv_cache *draft_kv, 
     }
     if (n_commit) {
         mark(draft, FG_STAGE_PREP, st);
-        if ((rc = launch_commit_len(draft_kv->seq_len, tree->slot, n_commit, commit_bias, tree->B, draft_kv->n_slots, st))) return rc;
+        if ((rc = launch_commit_len(draft_kv->seq_len, tree->slot, n_commit, commit_bias, tree->B, draft_kv->n_slots,
+                                    draft_kv->max_pages_per_seq * draft_kv->page_size, draft_kv->status, st))) return rc;
     }
     mark(draft, FG_STAGE_END, st);
     return FG_OK;
@@ -797,7 +830,7 @@ int32_t fg_attention(const fg_kv_cache *kv, int32_t layer, const fg_tree *tree, 
     void *aws = cv.take<char>(ab);
     if (!cv.ok) return fail(FG_ERR_CAPACITY, "fg_attention: workspace too small");
     hipStream_t st = (hipStream_t)stream;
-    if ((rc = launch_tree_prep_ex(tree, kv, td, st))) return rc;
+    if ((rc = launch_tree_prep_ex(tree, kv, td, 0, st))) return rc;
     return attention_any(kv, layer, tree, td, n_q_heads, q, out, mk, aws, ab, 0, st);
 }
 

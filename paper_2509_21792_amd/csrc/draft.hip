@@ -385,18 +385,26 @@ int32_t launch_build_tree(const int32_t *cand_tok, const int32_t *cand_parent, c
     return FG_OK;
 }
 
-__global__ void commit_len_kernel(int32_t *seq_len, const int32_t *slot, const int32_t *n_commit, int bias, int B, int n_slots)
+// A commit that would run past the page table is not applied and raises FG_CACHE_OVERFLOW in the cache's status word.
+__global__ void commit_len_kernel(int32_t *seq_len, const int32_t *slot, const int32_t *n_commit, int bias, int B, int n_slots,
+                                  int capacity, int32_t *status)
 {
     int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
     int s = min(max(slot[b], 0), n_slots - 1);
-    seq_len[s] += max(n_commit[b] + bias, 0);
+    const int L = seq_len[s] + max(n_commit[b] + bias, 0);
+    if (L > capacity) {
+        if (status) atomicOr(status, (int32_t)FG_CACHE_OVERFLOW);
+        return;
+    }
+    seq_len[s] = L;
 }
 
 int32_t launch_commit_len(int32_t *seq_len, const int32_t *slot, const int32_t *n_commit, int bias, int B, int n_slots,
-                          hipStream_t st)
+                          int capacity, int32_t *status, hipStream_t st)
 {
-    hipLaunchKernelGGL(commit_len_kernel, dim3((B + 63) / 64), dim3(64), 0, st, seq_len, slot, n_commit, bias, B, n_slots);
+    hipLaunchKernelGGL(commit_len_kernel, dim3((B + 63) / 64), dim3(64), 0, st, seq_len, slot, n_commit, bias, B, n_slots,
+                       capacity, status);
     FG_LAUNCH_CHECK("commit_len");
     return FG_OK;
 }

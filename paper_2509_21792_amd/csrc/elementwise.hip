@@ -8,10 +8,12 @@ namespace fg {
 // ---- tree preparation ------------------------------------------------------------------------------------
 // For every new node: its position (committed length + depth), the 64-bit set of its in-round
 // ancestors-or-self, and the cache cell it is appended to (the same in every layer).  Parents are clamped so that
-// a malformed tree cannot loop or index out of range.
+// a malformed tree cannot loop or index out of range.  A node whose slot lies beyond the sequence's page table gets
+// cell -1 -- nothing is appended for it -- and raises FG_CACHE_OVERFLOW in the cache's status word; a position the
+// RoPE table does not cover raises FG_POS_OVERFLOW (the position is clamped where it is used).
 __global__ void tree_prep_kernel(const int32_t *slot, const int32_t *parent, const int32_t *seq_len,
                                  const int32_t *page_table, int B, int N, int n_prev, int n_slots, int max_pages, int n_pages,
-                                 int32_t *pos, uint64_t *mask, int32_t *dest)
+                                 int max_pos, int32_t *pos, uint64_t *mask, int32_t *dest, int32_t *status)
 {
     int r = blockIdx.x * blockDim.x + threadIdx.x;
     if (r >= B * N) return;
@@ -30,17 +32,22 @@ __global__ void tree_prep_kernel(const int32_t *slot, const int32_t *parent, con
     pos[r] = L + depth;
     mask[r] = m;
     const int at = L + n_prev + j;
-    const int page_idx = min(max(at >> 4, 0), max_pages - 1);
-    const int page = min(max(page_table[(size_t)s * max_pages + page_idx], 0), n_pages - 1);
-    dest[r] = page * 16 + (at & 15);
+    if (at < 0 || (at >> 4) >= max_pages) {
+        dest[r] = -1;
+        if (status) atomicOr(status, (int32_t)FG_CACHE_OVERFLOW);
+    } else {
+        const int page = min(max(page_table[(size_t)s * max_pages + (at >> 4)], 0), n_pages - 1);
+        dest[r] = page * 16 + (at & 15);
+    }
+    if (status && max_pos > 0 && (L + depth >= max_pos || L + depth < 0)) atomicOr(status, (int32_t)FG_POS_OVERFLOW);
 }
 
-int32_t launch_tree_prep_ex(const fg_tree *t, const fg_kv_cache *kv, TreeDev td, hipStream_t st)
+int32_t launch_tree_prep_ex(const fg_tree *t, const fg_kv_cache *kv, TreeDev td, int max_pos, hipStream_t st)
 {
     int M = t->B * t->N;
     hipLaunchKernelGGL(tree_prep_kernel, dim3((M + 127) / 128), dim3(128), 0, st, t->slot, t->parent, kv->seq_len,
-                       kv->page_table, t->B, t->N, t->n_prev, kv->n_slots, kv->max_pages_per_seq, kv->n_pages, td.pos, td.mask,
-                       td.dest);
+                       kv->page_table, t->B, t->N, t->n_prev, kv->n_slots, kv->max_pages_per_seq, kv->n_pages, max_pos, td.pos,
+                       td.mask, td.dest, kv->status);
     FG_LAUNCH_CHECK("tree_prep");
     return FG_OK;
 }
@@ -233,6 +240,7 @@ __global__ __launch_bounds__(1024) void rope_append_kernel(const float *qkv, int
             store4<T>(o + half, x1);
         } else {
             const int cell = dest[r], page = cell >> 4, t = cell & 15, hk = head - Hq;
+            if (cell < 0) return;   // beyond the page table: not appended
             T *o = k_pool + (((size_t)layer * n_pages + page) * Hkv + hk) * 16 * hd;
             store4<T>(o + k_page_offset(k_frag, hd, t, i), x0);
             store4<T>(o + k_page_offset(k_frag, hd, t, i + half), x1);
@@ -241,6 +249,7 @@ __global__ __launch_bounds__(1024) void rope_append_kernel(const float *qkv, int
         int e4 = (w - n_rot) * 4, hk = e4 / hd, e = e4 % hd;
         float4 v = slab_sum4(row + (Hq + Hkv) * hd + e4, slab, S, zero);
         const int cell = dest[r], page = cell >> 4, t = cell & 15;
+        if (cell < 0) return;
         T *o = v_pool + (((size_t)layer * n_pages + page) * Hkv + hk) * 16 * hd + (size_t)e * 16 + t;
         o[0] = from_f<T>(v.x); o[16] = from_f<T>(v.y); o[32] = from_f<T>(v.z); o[48] = from_f<T>(v.w);
     }

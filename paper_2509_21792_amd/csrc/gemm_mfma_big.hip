@@ -60,8 +60,8 @@ __device__ __forceinline__ void epilogue_rope(f32x16_t (&acc)[MT][2], const Gemm
 #pragma unroll
             for (int r = 0; r < 16; r++) {
                 const int m = row0 + i * 32 + 8 * (r >> 2) + rh + (r & 3);
-                if (m < M) {
-                    const int cell = ep.dest[m], page = cell >> 4, t = cell & 15;
+                const int cell = m < M ? ep.dest[m] : -1, page = cell >> 4, t = cell & 15;
+                if (cell >= 0) {   // -1: beyond the page table, not appended
                     T *o = vp + (((size_t)ep.layer * ep.n_pages + page) * Hkv + hk) * page_elems + t;
                     o[e0 * 16] = from_f<T>(acc[i][0][r]);
                     o[e1 * 16] = from_f<T>(acc[i][1][r]);
@@ -111,8 +111,10 @@ __device__ __forceinline__ void epilogue_rope(f32x16_t (&acc)[MT][2], const Gemm
                     *reinterpret_cast<uint4 *>(qo + (size_t)m * Hq * hd + e) = v;
                 } else {
                     const int cell = ep.dest[m], page = cell >> 4, tk = cell & 15;
-                    T *o = kp + (((size_t)ep.layer * ep.n_pages + page) * Hkv + hk) * page_elems;
-                    *reinterpret_cast<uint4 *>(o + k_page_offset(ep.k_frag, hd, tk, e)) = v;
+                    if (cell >= 0) {   // -1: beyond the page table, not appended
+                        T *o = kp + (((size_t)ep.layer * ep.n_pages + page) * Hkv + hk) * page_elems;
+                        *reinterpret_cast<uint4 *>(o + k_page_offset(ep.k_frag, hd, tk, e)) = v;
+                    }
                 }
             }
         }

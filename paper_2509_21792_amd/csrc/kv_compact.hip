@@ -45,15 +45,23 @@ __global__ void kv_compact_kernel(T *k_pool, T *v_pool, const int32_t *page_tabl
     }
 }
 
+// The same conditions as kv_compact_kernel: a path that is malformed, or whose last node lies beyond the page table
+// (nothing was moved), leaves the length alone; the latter raises FG_CACHE_OVERFLOW in the cache's status word.
 __global__ void bump_len_kernel(int32_t *seq_len, const int32_t *slot, const int32_t *accept_len, const int32_t *path, int B,
-                                int N, int n_slots)
+                                int N, int n_slots, int max_pages, int32_t *status)
 {
     int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
     int a = accept_len[b];
-    if (!path_ok(path + (size_t)b * N, a, N)) return;
+    const int32_t *p = path + (size_t)b * N;
+    if (!path_ok(p, a, N)) return;
     int s = min(max(slot[b], 0), n_slots - 1);
-    seq_len[s] += a + 1;
+    const int L = seq_len[s];
+    if (((L + p[a]) >> 4) >= max_pages) {
+        if (status) atomicOr(status, (int32_t)FG_CACHE_OVERFLOW);
+        return;
+    }
+    seq_len[s] = L + a + 1;
 }
 
 template <typename T>
@@ -93,7 +101,7 @@ int32_t launch_kv_compact(fg_kv_cache *kv, const int32_t *slot, const int32_t *a
         FG_LAUNCH_CHECK("gather_feature");
     }
     hipLaunchKernelGGL(bump_len_kernel, dim3((B + 63) / 64), dim3(64), 0, st, kv->seq_len, slot, accept_len, path, B, N,
-                       kv->n_slots);
+                       kv->n_slots, kv->max_pages_per_seq, kv->status);
     FG_LAUNCH_CHECK("bump_len");
     return FG_OK;
 }

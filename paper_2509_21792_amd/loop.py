@@ -142,6 +142,11 @@ def generate(target, draft, kv, dkv, slot, st, first, budgets, c_peak, ws_t, ws_
     B = len(first)
     dev = slot.device
     outs = [[int(first[b])] for b in range(B)]
+    # committed lengths at the start (one copy, before the loop): with the tokens emitted since, the host knows every
+    # sequence's length and refuses a round that would run past a page table or the RoPE table
+    len0 = kv.seq_len[slot.long()].cpu().numpy().astype(np.int64)
+    dlen0 = dkv.seq_len[slot.long()].cpu().numpy().astype(np.int64)
+    limit = min(kv.capacity, dkv.capacity, target.max_pos, draft.max_pos)
     keep = [b for b in range(B) if budgets[b] > 1]
     live = list(range(B))
     hist = []
@@ -159,6 +164,11 @@ def generate(target, draft, kv, dkv, slot, st, first, budgets, c_peak, ws_t, ws_
     while live and len(hist) < max_rounds:
         Bc = len(live)
         N, K, L = plan(Bc) if plan else fg.fg_plan(Bc, c_peak, alpha, K_max, L_max, N_cap)
+        # the round appends N nodes behind the committed tokens (the draft cache: its pending entries and K (L - 1) nodes)
+        longest = max(max(len0[b], dlen0[b]) + len(outs[b]) - 1 for b in live)
+        need = longest + max(N, st.catch_tok.shape[1] + K * max(L - 1, 0))
+        if need > limit:
+            raise fg.FgError(-3, f"round of N = {N} nodes needs {need} cache positions, the caches / RoPE tables hold {limit}")
         root = torch.as_tensor(np.array([outs[b][-1] for b in live], dtype=np.int32)).to(dev) if N == 1 else None
         key = (Bc, N, K, L, st.catch_tok.shape[1])
         if graphs and replant is None and decide is None and seen.get(key, 0) >= 1:
@@ -187,6 +197,8 @@ def generate(target, draft, kv, dkv, slot, st, first, budgets, c_peak, ws_t, ws_
         if len(nxt_live) < Bc and nxt_live:
             reselect(rows)
         live = nxt_live
+    kv.check()      # the device-side backstop: raises if any call ran past a page table after all
+    dkv.check()
     return outs, hist
 
 

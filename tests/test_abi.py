@@ -115,3 +115,29 @@ def test_kv_cache_helper_follows_the_documented_k_layout():
                 off = tt * hd + e
             assert flat[l, page, h, off] == k[l, t, h, e], (dtype, hd, l, t, h, e)
         assert kv.v_pool[1, pt[1, 1], 2, 7, 4] == v[1, 20, 2, 7]
+
+
+@pytest.mark.parametrize("model_name,max_rows,cap", [("7b", 160, 4096), ("7b", 640, 4096), ("1.5b", 640, 2048), ("7b", 1408, 2100)])
+def test_workspace_bound_covers_every_call_shape(model_name, max_rows, cap):
+    """fg_workspace_bytes_for(max_rows) must cover what any single call with B * N <= max_rows carves (host only): the
+    attention part depends on how keys are cut into chunks, which is monotone neither in B nor in N (Eq. 1 produces
+    N = 3, 5, 10, 44 ... as readily as powers of two)."""
+    from synth import configs
+    import paper_2509_21792_amd as fg
+    cfg = configs.Q7B if model_name == "7b" else configs.Q1P5B
+    for is_draft in (False, True):
+        bound = fg.binding.fg_workspace_bytes_for(cfg, is_draft, max_rows, cap)
+        assert bound > 0
+        worst = 0
+        for N in range(1, 65):
+            for B in sorted(set([1, 2, 3, max_rows // N // 2, max_rows // N - 1, max_rows // N])):
+                if B < 1 or B * N > max_rows:
+                    continue
+                need = fg.binding.fg_step_workspace_bytes(cfg, is_draft, B, N, cap, with_logits=True)
+                assert 0 < need <= bound, (is_draft, B, N, need, bound)
+                worst = max(worst, need)
+        assert worst > 0.5 * bound          # the bound is not absurdly loose either
+    # the shapes named as failing before the bound took every (B, N) into account
+    for B, N in ((32, 5), (16, 3), (32, 44), (64, 10)):
+        if B * N <= max_rows:
+            assert fg.binding.fg_step_workspace_bytes(cfg, False, B, N, cap) <= fg.binding.fg_workspace_bytes_for(cfg, False, B * N, cap)

@@ -239,3 +239,46 @@ def test_empty_batch_and_capacity_errors(H):
     with pytest.raises(fg.FgError):    # bound beyond the capacity
         fg.fg_spec_verify(pair.gm, st.kv, st.slot, np.zeros((2, 3), np.int32), np.full((2, 3), -1, np.int32), ws,
                           max_seq_len=10 ** 6)
+
+
+@pytest.mark.parametrize("dtype,B", [("fp32", 2), ("bf16", 2), ("fp16", 400)])
+def test_running_past_the_page_table_is_flagged_and_harms_nothing(H, dtype, B):
+    """Sequence 1's page table ends right behind its committed tokens: a verify step with three new nodes cannot append
+    them, and accepting two of them cannot be committed.  The status word says so (FG_CACHE_OVERFLOW), the pool is
+    untouched outside the other sequences' cells and both lengths of sequence 1 stay; the sequences with room are served
+    as usual.  400 sequences take the GEMM whose epilogue appends K / V itself."""
+    import paper_2509_21792_amd as fg
+    model = configs.with_dtype(configs.TINY, dtype)
+    pair = H.Pair(model, seed=2, oracle_side=False)
+    lengths = np.full(B, 20, np.int32)
+    lengths[1] = 32
+    st = H.State(pair, model, lengths, 0, seed=4)      # tables hold ceil(32 / 16) = 2 pages: sequence 1 is full
+    assert st.kv.capacity == 32
+    N = 3
+    tokens = np.random.default_rng(0).integers(0, model["vocab"], size=(B, N)).astype(np.int32)
+    parent = np.tile(np.array([-1, 0, 1], np.int32), (B, 1))
+    ws = pair.gm.workspace(B * N, st.kv.capacity)
+    k_before, v_before = st.kv.k_pool.clone(), st.kv.v_pool.clone()
+    fg.fg_spec_verify(pair.gm, st.kv, st.slot, tokens, parent, ws)
+    torch.cuda.synchronize()
+    assert int(st.kv.status.item()) & 1
+    # only the other sequences' three cells (slots 20..22 of their second pages) changed
+    changed_k = (st.kv.k_pool != k_before).flatten(2).any(dim=2).any(dim=0)      # [n_pages]
+    changed_v = (st.kv.v_pool != v_before).flatten(2).any(dim=2).any(dim=0)
+    pages = sorted(int(st.kv.page_table[b, 1]) for b in range(B) if b != 1)
+    assert changed_k.nonzero().flatten().tolist() == pages and changed_v.nonzero().flatten().tolist() == pages
+    k1, v1 = st.kv.read(1, 32)
+    acc = torch.full((B,), 2, dtype=torch.int32, device="cuda")
+    path = torch.tensor([[0, 1, 2]] * B, dtype=torch.int32, device="cuda")
+    st.kv.status.zero_()
+    fg.fg_kv_compact(st.kv, st.slot, acc, path)
+    torch.cuda.synchronize()
+    want = lengths + 3
+    want[1] = 32
+    assert st.kv.seq_len.cpu().tolist() == want.tolist()
+    with pytest.raises(fg.FgError) as e:
+        st.kv.check()
+    assert e.value.code == -3 and int(st.kv.status.item()) == 0       # check() reports once and clears
+    k1b, v1b = st.kv.read(1, 32)
+    assert torch.equal(k1, k1b) and torch.equal(v1, v1b)
+    st.kv.check()                                                      # clean again
