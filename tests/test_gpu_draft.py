@@ -423,3 +423,116 @@ def test_chunked_prefill_then_adaptive_generation(H):
     for b in range(B):
         assert got[b] == want[b], (b, got[b], want[b])
     assert hist == want_hist
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+def test_draft_step_frontier_and_rerank_at_the_benchmarked_shape(H, dtype):
+    """One drafting step of the 7B-class draft head (its real depth: one layer) for 256 sequences x 4 frontier nodes
+    behind 4 earlier in-round nodes -- 1024 rows through the pipelined GEMMs with their fused epilogues, the LM head and
+    the selective top-K in one fg_draft_step, the shape the benchmark times -- then the frontier update and the rerank,
+    against the oracle on a subset of the sequences."""
+    import paper_2509_21792_amd as fg
+    model = configs.with_dtype(configs.scaled(configs.Q7B, 1), dtype)
+    pair = H.Pair(model, seed=31, with_draft=True)
+    dcfg = pair.dcfg
+    B, K, n_prev = 256, 4, 4
+    N = K
+    lengths = gen.make_kv_lengths(B, 1024, 4096, 31)
+    lengths[0], lengths[-1] = 1024, 4096
+    subset = [0, 77, 141, B - 1]
+    S = len(subset)
+    st = H.State(pair, dcfg, lengths, n_prev + N + 1, seed=32, subset=subset)
+    rng = np.random.default_rng(33)
+    n_tot = n_prev + N
+    # the earlier nodes are the root's four children, the new ones their children (a step-3 shape of the expansion)
+    parent = np.tile(np.array([-1, -1, -1, -1, 0, 1, 2, 3], np.int32), (B, 1))
+    tok_all = rng.integers(0, model["vocab"], size=(B, n_tot)).astype(np.int32)
+    td = torch.float16 if dtype == "fp16" else torch.bfloat16
+    feat_all = torch.randn((B, n_tot, model["d_model"]), generator=torch.Generator().manual_seed(34)).to(td)
+    fa = feat_all.cuda()
+    ws = pair.gd.workspace(B * N, st.cap)
+    msl = int(lengths.max()) + n_tot
+    fg.fg_draft_step(pair.gm, pair.gd, st.kv, st.slot, tok_all[:, :n_prev], parent[:, :n_prev], fa[:, :n_prev].contiguous(), ws, K,
+                     max_seq_len=msl, want_children=False)
+    fidx = np.tile(np.arange(n_prev, n_tot, dtype=np.int32), (B, 1))
+    ctok, clogp, ofeat = fg.fg_draft_step(pair.gm, pair.gd, st.kv, st.slot, tok_all[:, n_prev:], parent, fa, ws, K, n_prev=n_prev,
+                                          feat_index=fidx, max_seq_len=msl)
+    torch.cuda.synchronize()
+    orc = pair.orc
+    fnp = feat_all.float().numpy()[subset]
+    orc.tree_forward(pair.od, st.ocache, tok_all[subset, :n_prev], parent[subset, :n_prev], feat_in=fnp[:, :n_prev], is_draft=True,
+                     want_logits=False)
+    oh, ol = orc.tree_forward(pair.od, st.ocache, tok_all[subset, n_prev:], parent[subset], feat_in=fnp[:, n_prev:], n_prev=n_prev,
+                              is_draft=True)
+    o_tok, o_logp = orc.topk_logp(ol, K)
+    sub_t = torch.as_tensor(subset).cuda()
+    herr = np.abs(ofeat[sub_t].float().cpu().numpy().reshape(S * N, -1) - oh).max()
+    # the head's output is the un-normalised residual stream: a few roundings of the 16-bit activations that feed it,
+    # each 2^-11 (fp16) or 2^-8 (bf16) of values of the stream's own size
+    htol = {"fp16": 2e-3, "bf16": 1.6e-2}[dtype] * float(np.abs(oh).max())
+    assert herr <= htol, (herr, htol)
+    g_tok, g_logp = ctok[sub_t].cpu().numpy().reshape(S * N, K), clogp[sub_t].cpu().numpy().reshape(S * N, K)
+    n_bad = topk_agree(g_tok, g_logp, o_tok, o_logp, ol, tol={"fp16": 3e-2, "bf16": 0.12}[dtype],
+                       margin={"fp16": 0.05, "bf16": 0.15}[dtype])
+    assert n_bad <= S * N * K // 4
+    # frontier update and rerank: integer / comparison work on the GPU's own child lists -- the oracle, given the same
+    # lists, must pick the same K children and build the same tree
+    n_total = 1 + K + 2 * K * K
+    cand = [torch.zeros((B, n_total), dtype=t, device="cuda") for t in (torch.int32, torch.int32, torch.float32)]
+    node_cand = torch.as_tensor(np.tile(np.arange(1 + K, 1 + 2 * K, dtype=np.int32), (B, 1))).cuda()
+    node_score = torch.as_tensor(-rng.random((B, K)).astype(np.float32)).cuda()
+    nt, nc, ns, nsrc, pnext = fg.fg_draft_frontier(ctok, clogp, 1 + K + K * K, cand[0], cand[1], cand[2], node_cand=node_cand,
+                                                   node_score=node_score, parent_prev=torch.as_tensor(parent).cuda())
+    torch.cuda.synchronize()
+    cscore = (node_score[sub_t].cpu().numpy()[:, :, None] + clogp[sub_t].cpu().numpy()).astype(np.float32).reshape(S, K * K)
+    pick = orc.topk_index(cscore, K)
+    rows = np.arange(S)[:, None]
+    assert np.array_equal(nt[sub_t].cpu().numpy(), ctok[sub_t].cpu().numpy().reshape(S, K * K)[rows, pick])
+    assert np.array_equal(ns[sub_t].cpu().numpy(), cscore[rows, pick]) and np.array_equal(nsrc[sub_t].cpu().numpy(), pick // K)
+    assert np.array_equal(pnext[sub_t].cpu().numpy()[:, n_tot:], n_prev + pick // K)
+    print(f"draft step at 7B geometry {dtype}, 1024 rows: hidden err {herr:.3g}, {n_bad} exempt top-K swaps of {S * N * K}", flush=True)
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+def test_16bit_prefill_in_chunks_against_one_pass(H, dtype):
+    """The 16-bit prefill the benchmark times: prompts of 150 tokens through chain verify steps of 64, 64 and 22 positions
+    (7B-class geometry, two layers, target and draft head), against the oracle's one-pass prefill: both caches' contents
+    and lengths, the last position's feature, and the first generated token outside the margin exemption."""
+    import paper_2509_21792_amd as fg
+    from paper_2509_21792_amd import loop as gloop
+    model = configs.with_dtype(configs.scaled(configs.Q7B, 2), dtype)
+    pair = H.Pair(model, seed=41, with_draft=True)
+    orc = pair.orc
+    B, P = 3, 150
+    prompts = gen.make_prompts(B, 1, P, model["vocab"], 41)
+    prompts[1] = np.random.default_rng(42).integers(0, model["vocab"], size=P)     # not all the same prompt
+    cap = P + 80
+    ocache, odcache = orc.cache(model, B, cap), orc.cache(pair.dcfg, B, cap)
+    ofeat, ologits = oloop.prefill(orc, pair.om, ocache, prompts)
+    oroot, omargin = orc.row_argmax(ologits[:, -1])
+    # the draft head's entries during a prefill: (prompt token t + 1, feature t) for t = 0 .. P - 2
+    orc.tree_forward(pair.od, odcache, prompts[:, 1:], oloop.chain_parent(B, P - 1), feat_in=ofeat[:, :P - 1], is_draft=True,
+                     want_logits=False)
+    table, n_pages = gen.make_page_table(np.zeros(B, np.int32), cap, 16, 1)
+    kv = fg.KVCache(model, table, n_pages)
+    dtable, dn = gen.make_page_table(np.zeros(B, np.int32), cap, 16, 2)
+    dkv = fg.KVCache(pair.dcfg, dtable, dn)
+    slot = torch.arange(B, dtype=torch.int32, device="cuda")
+    ws_t, ws_d = pair.gm.workspace(B * 64, cap), pair.gd.workspace(B * 64, cap)
+    first, st = gloop.prefill(pair.gm, pair.gd, kv, dkv, slot, torch.as_tensor(prompts).cuda(), ws_t, ws_d, max_seq_len=cap)
+    torch.cuda.synchronize()
+    assert (kv.seq_len.cpu().numpy() == P).all() and (dkv.seq_len.cpu().numpy() == P - 1).all()
+    tol = {"fp16": 2e-2, "bf16": 0.15}[dtype]
+    for b in range(B):
+        k, v = kv.read(b, P)
+        assert np.abs(k.float().cpu().numpy() - ocache.k[:, b, :P]).max() <= tol
+        assert np.abs(v.float().cpu().numpy() - ocache.v[:, b, :P]).max() <= tol
+        dk, dv = dkv.read(b, P - 1)
+        assert np.abs(dk.float().cpu().numpy() - odcache.k[:, b, :P - 1]).max() <= 2 * tol
+        assert np.abs(dv.float().cpu().numpy() - odcache.v[:, b, :P - 1]).max() <= 2 * tol
+    ferr = np.abs(st.catch_feat[:, 0].float().cpu().numpy() - ofeat[:, -1]).max()
+    assert ferr <= {"fp16": 2e-2, "bf16": 0.1}[dtype], ferr
+    margin = H.decision_margin(model)
+    for b in range(B):
+        assert int(first[b]) == int(oroot[b]) or omargin[b] < margin, (b, omargin[b])
+    print(f"16-bit prefill {dtype}: last feature err {ferr:.3g}, first-token margins {np.round(omargin, 3).tolist()}", flush=True)

@@ -36,10 +36,15 @@ def oracle_continuation(pair, st, root_sub, depth):
     return nxt
 
 
-def run_greedy_config(H, name, dtype, n_sub, N=None):
+def run_greedy_config(H, name, dtype, n_sub, N=None, n_layers=None, margin=None):
+    """n_layers: the same geometry with fewer layers; margin: the top-2 margin below which a decision is exempt (default:
+    the stated 0.05 for fp16, the derived one for bf16)."""
     import paper_2509_21792_amd as fg
     cfg = configs.CONFIGS[name]
     model = configs.with_dtype(cfg["model"], dtype)
+    if n_layers:
+        model = configs.scaled(model, n_layers)
+    margin = margin or H.decision_margin(model)
     B = cfg["B"]
     N = N or cfg["N"]
     spec = cfg["tree"] if cfg["tree"][0] != "plan" else ("tree", 4, 4, N)
@@ -63,13 +68,16 @@ def run_greedy_config(H, name, dtype, n_sub, N=None):
     oh, ol = H.oracle_verify(st, tokens, parent)
     rows = np.concatenate([np.arange(b * N, (b + 1) * N) for b in subset])
     stats = H.compare_rows(out["logits"][rows].cpu().numpy(), ol, H.logit_tolerance(model, ol.size),
-                           out["argmax"][rows].cpu().numpy(), margin=H.decision_margin(model))
+                           out["argmax"][rows].cpu().numpy(), margin=margin)
+    # the error's size, not only its maximum: a fault that the max-abs bound of the bf16 mode would let through (a
+    # dropped key, a wrong slab) multiplies the rms error; rounding alone keeps it at the predicted figure
+    assert stats["rms"] <= H.rms_tolerance(model), (stats["rms"], H.rms_tolerance(model))
     o_acc, o_path, o_out, o_fin, o_tt, o_margin = pair.orc.accept_greedy(tokens[subset], parent[subset], ol)
     acc, path, otok = acc.cpu().numpy(), path.cpu().numpy(), otok.cpu().numpy()
     exempt = 0
     for j, b in enumerate(subset):
         walked = o_path[j, :o_acc[j] + 1]
-        if (o_margin[j, walked] < H.decision_margin(model)).any():
+        if (o_margin[j, walked] < margin).any():
             exempt += 1
             continue
         assert acc[b] == o_acc[j] and np.array_equal(path[b], o_path[j]) and np.array_equal(otok[b], o_out[j]), b
@@ -86,7 +94,7 @@ def run_greedy_config(H, name, dtype, n_sub, N=None):
             assert torch.equal(v[:, L + jj], before[b][1][:, L + path[b, jj]])
     tau = float((o_acc + 1).mean())
     print(f"{name} {dtype} B={B} N={N}: {stats} oracle tau on subset {tau:.2f}, exempt walks {exempt}/{len(subset)}", flush=True)
-    if dtype != "bf16":      # with bf16 activations the widened margin can exempt every walk at this depth
+    if dtype != "bf16" or margin <= H.MARGIN:   # with bf16 activations at full depth the widened margin can exempt every walk
         assert exempt < len(subset)
 
 
@@ -105,8 +113,17 @@ def test_config4_7b_high_concurrency(H, N):
     run_greedy_config(H, "cfg4", "fp16", n_sub=4, N=N)
 
 
-def test_config4_7b_high_concurrency_bf16(H):
-    run_greedy_config(H, "cfg4", "bf16", n_sub=4, N=8)
+@pytest.mark.parametrize("N", [1, 4, 8])
+def test_config4_7b_high_concurrency_bf16(H, N):
+    run_greedy_config(H, "cfg4", "bf16", n_sub=4, N=N)
+
+
+@pytest.mark.parametrize("name", ["cfg3", "cfg4"])
+def test_bf16_decisions_at_the_stated_margin_on_a_shallow_model(H, name):
+    """Two layers of the 7B-class geometry, bf16 activations, whole batch: the rounding error is still small enough
+    (a logit-error difference of about 0.01) for the stated 0.05 margin to be the exemption, so token ids, accept lengths
+    and paths are held to it, and not every walk may be exempt."""
+    run_greedy_config(H, name, "bf16", n_sub=8, n_layers=2, margin=H.MARGIN)
 
 
 def test_config5_7b_tree_rejection_sampling(H):
@@ -119,7 +136,7 @@ def test_config5_7b_tree_rejection_sampling(H):
     B, N, T, V = cfg["B"], cfg["N"], cfg["temperature"], cfg["model"]["vocab"]
     lengths = gen.make_kv_lengths(B, cfg["kv_lo"], cfg["kv_hi"], cfg["seed"])
     lengths[0], lengths[-1] = cfg["kv_lo"], cfg["kv_hi"]
-    subset = [0, 37, 90, B - 1]
+    subset = [0, 19, 37, 58, 73, 90, 111, B - 1]
     S = len(subset)
     pair = H.Pair(model, seed=cfg["seed"])
     orc = pair.orc
@@ -170,7 +187,11 @@ def test_config5_7b_tree_rejection_sampling(H):
         o = orc.accept_reject(tokens[b:b + 1], parent[b:b + 1], ol[j * N:(j + 1) * N], q_sub[j * N:(j + 1) * N], unif[b:b + 1],
                               T, seed, row0 + b * N)
         acc, path, otok, fin, bonus_margin, gap = o
-        if gap[0] < 2e-2:       # an accept test closer to its uniform than the logits tolerance can resolve
+        # An accept test compares a uniform with p(x) / q(x), p from the logits.  Under the stated logits tolerance
+        # (3e-2 max-abs) p(x) moves by up to a factor e^(2 * 3e-2) (its own logit up, the normaliser down): 6 % of a ratio
+        # that is at most 1 where the test is close.  A uniform nearer than 2e-2 to its ratio is inside that band: such a
+        # walk is exempt, as a sub-margin arg-max is in greedy mode.  Planted nodes keep a gap of 0.1.
+        if gap[0] < 2e-2:
             exempt += 1
             continue
         assert g[0][b].item() == acc[0] and np.array_equal(g[1][b].cpu().numpy(), path[0]), b
@@ -179,4 +200,4 @@ def test_config5_7b_tree_rejection_sampling(H):
         if bonus_margin[0] >= H.MARGIN:
             assert g[2][b, a].item() == otok[0, a]
     print(f"cfg5 {dtype}: {stats}, exempt {exempt}/{S}, accept lengths {g[0][subset].cpu().tolist()}", flush=True)
-    assert exempt < S
+    assert exempt <= S // 2
