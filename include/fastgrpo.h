@@ -325,6 +325,11 @@ int32_t fg_build_tree(const int32_t *cand_tok, const int32_t *cand_parent, const
  * fg_topk_logp: the draft's per-node expansion (Sec. 2, draft tree construction): for each of the M rows of
  *   logits [M, vocab] (fp32, device) the K largest entries, ties to the lower token id, as tok [M, K] (int32)
  *   and their log-softmax values logp [M, K] (fp32).  1 <= K <= 8, K <= vocab.
+ * fg_lm_head_topk: the same lists straight from the hidden states x [M, d_model] (dtype) and the packed LM head
+ *   [vocab, d_model], the selection done in the GEMM's epilogue, so that no [M, vocab] tensor is written: per row and
+ *   256-token block the K best (value, token) and (max, sum exp), then a merge.  What fg_spec_verify (K = 2, for the row
+ *   arg-max and top-2) and fg_draft_step do when no logits are asked for; from 129 rows and 16384 tokens on
+ *   (FG_ERR_SHAPE below).  workspace: fg_lm_head_topk_workspace_bytes(M, vocab, K) bytes, device.
  */
 int32_t fg_gemm(int32_t dtype, const void *x, const void *w_packed, void *out, int32_t M, int32_t n_out,
                 int32_t n_in, int32_t epilogue, int32_t split_k, int32_t *split_k_used, int32_t variant, void *stream);
@@ -334,6 +339,9 @@ int32_t fg_attention(const fg_kv_cache *kv, int32_t layer, const fg_tree *tree, 
 int64_t fg_attention_workspace_bytes(int32_t B, int32_t N, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                                      int32_t max_seq_len);
 int32_t fg_topk_logp(const float *logits, int32_t M, int32_t vocab, int32_t K, int32_t *tok, float *logp, void *stream);
+int64_t fg_lm_head_topk_workspace_bytes(int32_t M, int32_t vocab, int32_t K);
+int32_t fg_lm_head_topk(int32_t dtype, const void *x, const void *lm_head_packed, int32_t M, int32_t vocab, int32_t d_model,
+                        int32_t K, int32_t *tok, float *logp, void *workspace, int64_t workspace_bytes, void *stream);
 
 /*
  * Stage timing of one model (measurement only, off by default).  While enabled, the entry points that run this model

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libfastgrpo.so")
 EXPORTS = ["fg_last_error", "fg_plan", "fg_packed_bytes", "fg_pack_weight", "fg_model_create", "fg_model_destroy",
            "fg_workspace_bytes", "fg_workspace_bytes_for", "fg_step_workspace_bytes", "fg_spec_verify", "fg_spec_accept", "fg_kv_compact", "fg_draft_step",
            "fg_draft_frontier", "fg_build_tree", "fg_gemm", "fg_attention", "fg_attention_workspace_bytes",
-           "fg_topk_logp", "fg_knee", "fg_select_rows", "fg_model_profile",
+           "fg_topk_logp", "fg_lm_head_topk", "fg_lm_head_topk_workspace_bytes", "fg_knee", "fg_select_rows", "fg_model_profile",
            "fg_model_profile_read", "fg_gemm_kernel_name", "fg_spec_accept_static", "fg_probe_read", "fg_probe_copy", "fg_probe_mfma"]
 STATIC_SCRATCH_BYTES = 4 << 20
 
@@ -98,6 +98,10 @@ def lib():
         L.fg_knee.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]
         L.fg_select_rows.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         L.fg_topk_logp.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.fg_lm_head_topk_workspace_bytes.restype = C.c_int64
+        L.fg_lm_head_topk_workspace_bytes.argtypes = [C.c_int32] * 3
+        L.fg_lm_head_topk.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                      C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         L.fg_build_tree.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.fg_gemm.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
@@ -455,6 +459,17 @@ def fg_topk_logp(logits, K):
     tok = torch.empty((M, K), dtype=torch.int32, device=logits.device)
     logp = torch.empty((M, K), dtype=torch.float32, device=logits.device)
     _check(lib().fg_topk_logp(_p(logits), M, V, K, _p(tok), _p(logp), _stream()))
+    return tok, logp
+
+
+def fg_lm_head_topk(dtype, x, lm_head_packed, vocab, K):
+    """Top-K tokens and log-probabilities of x . lm_head^T with the selection in the GEMM's epilogue."""
+    x = x.contiguous()
+    M, d = x.shape
+    tok = torch.empty((M, K), dtype=torch.int32, device=x.device)
+    logp = torch.empty((M, K), dtype=torch.float32, device=x.device)
+    ws = torch.empty(max(lib().fg_lm_head_topk_workspace_bytes(M, vocab, K), 256), dtype=torch.uint8, device=x.device)
+    _check(lib().fg_lm_head_topk(dtype, _p(x), _p(lm_head_packed), M, vocab, d, K, _p(tok), _p(logp), _p(ws), ws.numel(), _stream()))
     return tok, logp
 
 

@@ -42,6 +42,8 @@ int32_t launch_reject(int B, int N, int V, const int32_t *tokens, const int32_t 
 int32_t launch_kv_compact(fg_kv_cache *kv, const int32_t *slot, const int32_t *accept_len, const int32_t *path, int B, int N,
                           const void *fin, void *fout, int d, int feat_dtype, hipStream_t st);
 int32_t launch_topk_logp(const float *logits, int M, int V, int K, int32_t *tok, float *logp, hipStream_t st);
+int32_t launch_topk_merge(const float *part_val, const int32_t *part_idx, const float *part_ms, int M, int n_blocks, int K,
+                          int32_t *tok, float *logp, int32_t *row_argmax, float *row_top2, hipStream_t st);
 int32_t launch_select_rows(const void *src, int64_t row_bytes, int n_src, const int32_t *index, int n, void *dst, hipStream_t st);
 int32_t launch_gather_rows(int32_t dtype, const void *src, const int32_t *pick, int B, int N, int d, void *dst, hipStream_t st);
 int32_t launch_frontier(int B, int K_in, int K, const int32_t *child_tok, const float *child_logp, int child_rows,
@@ -211,6 +213,25 @@ int32_t gemm_any(const fg_model_cfg &c, const void *x, const void *w, float *par
     if (is16(c.dtype)) return launch_gemm_mfma(c.dtype, x, w, partials, M, N, K, 0, 0, S, st);
     *S = 1;
     return launch_gemm_f32((const float *)x, (const float *)w, partials, M, N, K, st);
+}
+
+// LM head with the selection in the GEMM's epilogue: x [M, d] . W^T -> per-block top-k / (max, sum exp) partials in
+// `scratch` (the region a materialised [M, V] fp32 logits tensor would take: the partials need under a third of it) ->
+// the K best tokens of each row with their log-probabilities, and / or the row arg-max and top-2 values.
+int64_t lm_head_topk_bytes(int M, int V, int K) { return (int64_t)M * ((V + 255) / 256) * (K * 8 + 8) + 1024; }
+
+int32_t lm_head_topk(int32_t dtype, const void *x, const void *lm_head, int M, int V, int d, int K, bool want_logp, void *scratch,
+                     int32_t *tok, float *logp, int32_t *row_argmax, float *row_top2, hipStream_t st)
+{
+    const int nb = (V + 255) / 256;
+    GemmEpi ep;
+    ep.topk = K;
+    ep.part_val = (float *)scratch;
+    ep.part_idx = (int32_t *)(ep.part_val + (size_t)M * nb * K);
+    ep.part_ms = want_logp ? (float *)(ep.part_idx + (size_t)M * nb * K) : nullptr;
+    int32_t rc;
+    if ((rc = launch_gemm_mfma(dtype, x, lm_head, nullptr, M, V, d, EPI_TOPK, 1, nullptr, st, &ep))) return rc;
+    return launch_topk_merge(ep.part_val, ep.part_idx, ep.part_ms, M, nb, K, tok, logp, row_argmax, row_top2, st);
 }
 
 int32_t check_cache(const fg_model *m, const fg_kv_cache *kv)
@@ -531,7 +552,12 @@ int32_t fg_spec_verify(fg_model *m, fg_kv_cache *kv, const fg_tree *tree, float 
     mark(m, FG_STAGE_NORM, st);
     if ((rc = launch_add_rmsnorm(c.dtype, w.h, w.partials, S, 0, m->final_norm, feat, nullptr, M, c.d_model, c.rms_eps, st))) return rc;
     float *lg = logits ? logits : w.logits;
-    if (lg) {
+    if (!logits && lg && is16(c.dtype) && gemm_mfma_fusable(M, c.vocab, c.d_model, EPI_TOPK)) {
+        // only the decisions are wanted: the LM head selects in its epilogue and no [M, V] tensor is written
+        mark(m, FG_STAGE_LM_HEAD, st);
+        if ((rc = lm_head_topk(c.dtype, feat, m->lm_head, M, c.vocab, c.d_model, 2, false, w.logits, nullptr, nullptr, row_argmax,
+                               row_top2, st))) return rc;
+    } else if (lg) {
         mark(m, FG_STAGE_LM_HEAD, st);
         if (is16(c.dtype)) rc = launch_gemm_mfma(c.dtype, feat, m->lm_head, lg, M, c.vocab, c.d_model, 0, 1, nullptr, st);
         else rc = launch_gemm_f32((const float *)feat, (const float *)m->lm_head, lg, M, c.vocab, c.d_model, st);
@@ -662,12 +688,18 @@ int32_t fg_draft_step(fg_model *target, fg_model *draft, fg_kv_cache *draft_kv, 
             if ((rc = launch_gather_rows(c.dtype, hid, expand_row, tree->B, tree->N, d, w.cat, st))) return rc;
             hid = w.cat;
         }
+        if (K_draft < 1 || K_draft > 8 || K_draft > c.vocab) return fail(FG_ERR_INVALID_ARG, "K_draft must be in 1..8 (got %d)", K_draft);
         mark(draft, FG_STAGE_LM_HEAD, st);
-        if (is16(c.dtype)) rc = launch_gemm_mfma(c.dtype, hid, target->lm_head, w.logits, rows, c.vocab, d, 0, 1, nullptr, st);
-        else rc = launch_gemm_f32((const float *)hid, (const float *)target->lm_head, w.logits, rows, c.vocab, d, st);
-        if (rc) return rc;
-        mark(draft, FG_STAGE_SELECT, st);
-        if ((rc = launch_topk_logp(w.logits, rows, c.vocab, K_draft, child_tok, child_logp, st))) return rc;
+        if (is16(c.dtype) && gemm_mfma_fusable(rows, c.vocab, d, EPI_TOPK)) {
+            if ((rc = lm_head_topk(c.dtype, hid, target->lm_head, rows, c.vocab, d, K_draft, true, w.logits, child_tok, child_logp,
+                                   nullptr, nullptr, st))) return rc;
+        } else {
+            if (is16(c.dtype)) rc = launch_gemm_mfma(c.dtype, hid, target->lm_head, w.logits, rows, c.vocab, d, 0, 1, nullptr, st);
+            else rc = launch_gemm_f32((const float *)hid, (const float *)target->lm_head, w.logits, rows, c.vocab, d, st);
+            if (rc) return rc;
+            mark(draft, FG_STAGE_SELECT, st);
+            if ((rc = launch_topk_logp(w.logits, rows, c.vocab, K_draft, child_tok, child_logp, st))) return rc;
+        }
     }
     if (n_commit) {
         mark(draft, FG_STAGE_PREP, st);
@@ -743,6 +775,26 @@ int32_t fg_topk_logp(const float *logits, int32_t M, int32_t vocab, int32_t K, i
     if (M == 0) return FG_OK;
     if (!logits || !tok || !logp) return fail(FG_ERR_INVALID_ARG, "fg_topk_logp: null pointer");
     return launch_topk_logp(logits, M, vocab, K, tok, logp, (hipStream_t)stream);
+}
+
+int64_t fg_lm_head_topk_workspace_bytes(int32_t M, int32_t vocab, int32_t K)
+{
+    if (M < 1 || vocab < 1 || K < 1 || K > 8) return 0;
+    return lm_head_topk_bytes(M, vocab, K);
+}
+
+int32_t fg_lm_head_topk(int32_t dtype, const void *x, const void *lm_head_packed, int32_t M, int32_t vocab, int32_t d_model, int32_t K,
+                        int32_t *tok, float *logp, void *workspace, int64_t workspace_bytes, void *stream)
+{
+    if (!x || !lm_head_packed || !tok || !logp || !workspace || M < 0 || vocab < 1 || d_model < 1)
+        return fail(FG_ERR_INVALID_ARG, "fg_lm_head_topk: bad argument");
+    if (K < 1 || K > 8 || K > vocab) return fail(FG_ERR_INVALID_ARG, "fg_lm_head_topk: K must be in 1..8 (got %d)", K);
+    if (M == 0) return FG_OK;
+    if (!is16(dtype) || vocab % 32 || d_model % 64) return fail(FG_ERR_SHAPE, "fg_lm_head_topk: 16-bit dtypes, vocab %% 32 == 0, d_model %% 64 == 0");
+    if (!gemm_mfma_fusable(M, vocab, d_model, EPI_TOPK))
+        return fail(FG_ERR_SHAPE, "fg_lm_head_topk: the selecting epilogue runs from 129 rows and 16384 tokens on (got %d, %d)", M, vocab);
+    if (workspace_bytes < lm_head_topk_bytes(M, vocab, K)) return fail(FG_ERR_CAPACITY, "fg_lm_head_topk: workspace too small");
+    return lm_head_topk(dtype, x, lm_head_packed, M, vocab, d_model, K, true, workspace, tok, logp, nullptr, nullptr, (hipStream_t)stream);
 }
 
 int32_t fg_model_profile(fg_model *m, int32_t enable, int32_t max_marks)

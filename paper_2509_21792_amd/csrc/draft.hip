@@ -262,6 +262,84 @@ int32_t launch_topk_logp(const float *logits, int M, int V, int K, int32_t *tok,
     return FG_OK;
 }
 
+// ---- merge of the LM head's per-block partials (the GEMM's top-k epilogue) ----------------------------------------
+// One block per row: the row's n_blocks x K (value, column) candidates and n_blocks (max, sum exp) pairs become the K
+// largest entries of the row (ties to the lower column), their log-softmax values (when the pairs are given) and / or
+// the arg-max and the two largest values.
+constexpr int TM_THREADS = 256;
+__global__ __launch_bounds__(TM_THREADS) void topk_merge_kernel(const float *__restrict__ part_val, const int32_t *__restrict__ part_idx,
+                                                                const float *__restrict__ part_ms, int n_blocks, int K,
+                                                                int32_t *tok, float *logp, int32_t *row_argmax, float *row_top2)
+{
+    __shared__ float rb[TM_THREADS / 64];
+    __shared__ int ri[TM_THREADS / 64];
+    const int r = blockIdx.x, tid = threadIdx.x;
+    const int n = n_blocks * K;
+    const float *pv = part_val + (size_t)r * n;
+    const int32_t *pi = part_idx + (size_t)r * n;
+    float lse = 0.f;
+    if (part_ms) {
+        const float *ms = part_ms + (size_t)r * n_blocks * 2;
+        float mx = -INFINITY;
+        for (int b = tid; b < n_blocks; b += TM_THREADS) mx = fmaxf(mx, ms[2 * b]);
+        mx = wave_max(mx);
+        if ((tid & 63) == 0) rb[tid >> 6] = mx;
+        __syncthreads();
+        mx = rb[0];
+        for (int i = 1; i < TM_THREADS / 64; i++) mx = fmaxf(mx, rb[i]);
+        __syncthreads();
+        float sum = 0.f;
+        for (int b = tid; b < n_blocks; b += TM_THREADS) sum += ms[2 * b + 1] * __expf(ms[2 * b] - mx);
+        sum = wave_sum(sum);
+        if ((tid & 63) == 0) rb[tid >> 6] = sum;
+        __syncthreads();
+        sum = 0.f;
+        for (int i = 0; i < TM_THREADS / 64; i++) sum += rb[i];
+        lse = mx + logf(sum);
+        __syncthreads();
+    }
+    float lv = INFINITY;
+    int li = -1;
+    for (int k = 0; k < K; k++) {
+        float best = -INFINITY;
+        int bi = 0x7fffffff;
+        for (int e = tid; e < n; e += TM_THREADS) {
+            const float v = pv[e];
+            const int c = pi[e];
+            const bool after = lv > v || (lv == v && li < c);
+            if (after && (v > best || (v == best && c < bi))) { best = v; bi = c; }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const float ob = __shfl_xor(best, o, 64);
+            const int oi = __shfl_xor(bi, o, 64);
+            if (ob > best || (ob == best && oi < bi)) { best = ob; bi = oi; }
+        }
+        __syncthreads();
+        if ((tid & 63) == 0) { rb[tid >> 6] = best; ri[tid >> 6] = bi; }
+        __syncthreads();
+        best = rb[0]; bi = ri[0];
+        for (int i = 1; i < TM_THREADS / 64; i++)
+            if (rb[i] > best || (rb[i] == best && ri[i] < bi)) { best = rb[i]; bi = ri[i]; }
+        lv = best; li = bi;
+        if (tid == 0) {
+            if (tok) tok[(size_t)r * K + k] = bi;
+            if (logp) logp[(size_t)r * K + k] = best - lse;
+            if (k == 0 && row_argmax) row_argmax[r] = bi;
+            if (k < 2 && row_top2) row_top2[2 * r + k] = best;
+        }
+    }
+}
+
+int32_t launch_topk_merge(const float *part_val, const int32_t *part_idx, const float *part_ms, int M, int n_blocks, int K,
+                          int32_t *tok, float *logp, int32_t *row_argmax, float *row_top2, hipStream_t st)
+{
+    hipLaunchKernelGGL(topk_merge_kernel, dim3(M), dim3(TM_THREADS), 0, st, part_val, part_idx, part_ms, n_blocks, K, tok, logp,
+                       row_argmax, row_top2);
+    FG_LAUNCH_CHECK("topk_merge");
+    return FG_OK;
+}
+
 // Frontier update, one thread per sequence (at most 64 children).  With node_pick only the children of node
 // node_pick[b] count (the catch-up chain's last valid row is the root; the rows before it are not expanded).
 __global__ void frontier_kernel(int B, int K_in, int K, const int32_t *child_tok, const float *child_logp, int child_rows,

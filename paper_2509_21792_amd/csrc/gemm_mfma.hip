@@ -238,8 +238,10 @@ bool gemm_mfma_fuses_swiglu(int M, int N, int K) { return kernel_for(M, N, K, EP
 bool gemm_mfma_fusable(int M, int N, int K, int kind)
 {
     if (kind < EPI_ROPE) return true;
-    if (kind > EPI_RESIDUAL) return false;
-    return M >= 1024 && (int64_t)M * K < (1LL << 30);
+    if (kind > EPI_TOPK || (int64_t)M * K >= (1LL << 30)) return false;
+    // the top-k epilogue is for LM heads: thousands of tiles, no k split at any row count the pipelined kernel takes
+    if (kind == EPI_TOPK) return N >= 16384 && M > 128;
+    return M >= 1024;
 }
 
 int gemm_mfma_split_for(int M, int N, int K)

@@ -121,6 +121,90 @@ __device__ __forceinline__ void epilogue_rope(f32x16_t (&acc)[MT][2], const Gemm
     }
 }
 
+// LM head: per row and per 256-column block, the topk largest outputs (value, column; ties to the lower column) and
+// the block's (max, sum exp(x - max)), so that no [M, vocab] tensor has to exist.  The accumulator layout has a lane on
+// one column of 16 rows; the selection wants a row's 256 columns together.  16 rows at a time go through a
+// 16 x 256 fp32 tile in LDS (stage 0 of the main loop, free by now): the four waves write their 64 columns each, then a
+// row belongs to 16 consecutive lanes, a lane holding the columns 4 s + 64 v + u (s = lane % 16; v, u = 0..3 -- the
+// float4 reads of 16 lanes cover all 64 banks).  topk rounds follow: every lane offers its best entry that comes after
+// the previous winner in the order (value descending, column ascending), a 4-step exchange inside the 16 lanes picks
+// the round's winner.
+__device__ __forceinline__ bool topk_before(float va, int ia, float vb, int ib) { return va > vb || (va == vb && ia < ib); }
+
+template <int MT>
+__device__ __forceinline__ void epilogue_topk(f32x16_t (&acc)[MT][2], const GemmEpi &ep, int M, int N, int row0, int bx, int n_bands,
+                                              int wn, int lane, float *tile)
+{
+    const int c = lane & 31, hsel = lane >> 5, tid = wn * 64 + lane;
+    const int row16 = tid >> 4, seg = tid & 15;
+    const int K = ep.topk;
+#pragma unroll
+    for (int i = 0; i < MT; i++) {
+#pragma unroll
+        for (int half = 0; half < 2; half++) {
+            if (row0 + i * 32 + half * 16 >= M) break;   // the same for the whole block
+            __syncthreads();                              // the previous tile's readers are done
+#pragma unroll
+            for (int qq = 0; qq < 2; qq++)
+#pragma unroll
+                for (int k = 0; k < 4; k++)
+#pragma unroll
+                    for (int j = 0; j < 2; j++)
+                        tile[(8 * qq + 4 * hsel + k) * 256 + wn * 64 + j * 32 + c] = acc[i][j][4 * (2 * half + qq) + k];
+            __syncthreads();
+            float v[16];
+            int col[16];
+#pragma unroll
+            for (int vv = 0; vv < 4; vv++) {
+                const float4 x = *reinterpret_cast<const float4 *>(tile + row16 * 256 + seg * 4 + 64 * vv);
+                const float xs[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+                for (int u = 0; u < 4; u++) {
+                    const int cc = bx * 256 + seg * 4 + 64 * vv + u;
+                    col[4 * vv + u] = cc < N ? cc : 0x7fffffff;     // columns past the matrix never win a round
+                    v[4 * vv + u] = cc < N ? xs[u] : -INFINITY;
+                }
+            }
+            const int m = row0 + i * 32 + half * 16 + row16;
+            float lv = INFINITY, bmax = -INFINITY;
+            int li = -1;
+            for (int k = 0; k < K; k++) {
+                float best = -INFINITY;
+                int bi = 0x7fffffff;
+#pragma unroll
+                for (int e = 0; e < 16; e++) {
+                    const bool after = topk_before(lv, li, v[e], col[e]);      // the previous winner comes before it
+                    if (after && topk_before(v[e], col[e], best, bi)) { best = v[e]; bi = col[e]; }
+                }
+#pragma unroll
+                for (int o = 1; o < 16; o <<= 1) {
+                    const float ob = __shfl_xor(best, o, 64);
+                    const int oi = __shfl_xor(bi, o, 64);
+                    if (topk_before(ob, oi, best, bi)) { best = ob; bi = oi; }
+                }
+                if (k == 0) bmax = best;
+                lv = best; li = bi;
+                if (seg == 0 && m < M) {
+                    const size_t at = ((size_t)m * n_bands + bx) * K + k;
+                    ep.part_val[at] = best;
+                    ep.part_idx[at] = bi;
+                }
+            }
+            if (ep.part_ms) {
+                float sum = 0.f;
+#pragma unroll
+                for (int e = 0; e < 16; e++) sum += v[e] > -INFINITY ? __expf(v[e] - bmax) : 0.f;
+#pragma unroll
+                for (int o = 1; o < 16; o <<= 1) sum += __shfl_xor(sum, o, 64);
+                if (seg == 0 && m < M) {
+                    ep.part_ms[((size_t)m * n_bands + bx) * 2] = bmax;
+                    ep.part_ms[((size_t)m * n_bands + bx) * 2 + 1] = sum;
+                }
+            }
+        }
+    }
+}
+
 template <typename T, int MT, int EPI>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 4 ? 2 : 1))) void gemm_mfma_big_kernel(const T *__restrict__ X, const uint4 *__restrict__ Wp,
                                                              void *__restrict__ out, int M, int N, int K, int chunks_per_split,
@@ -313,6 +397,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 4 ? 2
         epilogue_rope<T, MT>(acc, ep, M, row0, ntile[0], n_tiles, lane, reinterpret_cast<T *>(xs0) + wn * 2048);
     } else if (EPI == EPI_RESIDUAL) {
         store_tiles<T, MT, NT, EPI_SLABS>(acc, ep.h, M, N, row0, ntile[0], n_tiles, 0, lane);
+    } else if (EPI == EPI_TOPK) {
+        epilogue_topk<MT>(acc, ep, M, N, row0, bx, n_bands, wn, lane, reinterpret_cast<float *>(xs0));
     } else {
         store_tiles<T, MT, NT, EPI>(acc, out, M, N, row0, ntile[0], n_tiles, bz, lane);
     }
@@ -374,6 +460,7 @@ static void launch_big_typed(const void *x, const void *wp, void *out, int M, in
     case EPI_SLABS: FG_BIG_LAUNCH(EPI_SLABS); break;
     case EPI_SWIGLU: FG_BIG_LAUNCH(EPI_SWIGLU); break;
     case EPI_ROPE: FG_BIG_LAUNCH(EPI_ROPE); break;
+    case EPI_TOPK: FG_BIG_LAUNCH(EPI_TOPK); break;
     default: FG_BIG_LAUNCH(EPI_RESIDUAL); break;
     }
 #undef FG_BIG_LAUNCH
@@ -386,7 +473,9 @@ int32_t launch_gemm_mfma_big(int32_t dtype, const void *x, const void *wp, void 
 {
     if ((int64_t)M * K >= (1LL << 30)) return fail(FG_ERR_SHAPE, "GEMM input of %d x %d exceeds 2^30 elements", M, K);
     if (epilogue >= EPI_ROPE && split != 1) return fail(FG_ERR_INVALID_ARG, "fused GEMM epilogue %d cannot run with a k split", epilogue);
-    if (epilogue > EPI_RESIDUAL) return fail(FG_ERR_UNIMPLEMENTED, "GEMM epilogue %d", epilogue);
+    if (epilogue > EPI_TOPK) return fail(FG_ERR_UNIMPLEMENTED, "GEMM epilogue %d", epilogue);
+    if (epilogue == EPI_TOPK && (epi->topk < 1 || epi->topk > 8 || !epi->part_val || !epi->part_idx))
+        return fail(FG_ERR_INVALID_ARG, "top-k epilogue needs 1 <= k <= 8 and its partial buffers");
     if (epilogue >= EPI_ROPE && !epi) return fail(FG_ERR_INVALID_ARG, "GEMM epilogue %d needs its arguments", epilogue);
     if (epilogue == EPI_ROPE && (epi->hd != 64 && epi->hd != 128)) return fail(FG_ERR_SHAPE, "RoPE epilogue needs head_dim 64 or 128");
     const BigPlan p = plan_big(M, N, K, split, fixed_mt);

@@ -249,3 +249,37 @@ def test_tree_attention(fg, dtype, Hq, Hkv, hd, B, N, n_prev, lens):
         err = (out[b] - ref).abs().max().item()
         tol = {"fp32": 1e-5, "bf16": 2.5e-2, "fp16": 4e-3}[dtype]
         assert err < tol, (b, err)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+@pytest.mark.parametrize("M,V,K", [(129, 16384, 4), (300, 16480, 1), (1030, 16640, 8), (520, 33024, 2)])
+def test_lm_head_with_the_selection_in_its_epilogue(fg, dtype, M, V, K):
+    """fg_lm_head_topk (per-block top-K / log-sum-exp partials in the GEMM epilogue + merge, no [M, V] tensor) against the
+    two-kernel path on the same accumulators (fg_gemm slabs, then the oracle's definition of top-K / log-softmax on
+    them): token ids bit-exact, including exact ties between duplicated vocabulary rows (the lower id must win, within a
+    block and across blocks) and a vocabulary that ends inside a 256-token block; log-probabilities to fp32 rounding."""
+    from oracle.oracle import Oracle
+    print(f"lm head top-k {dtype} M={M} V={V} K={K}", flush=True)
+    code, dt, d = CODES[dtype], TD[dtype], 192
+    g = torch.Generator().manual_seed(M + V + K)
+    x, w = bf16_randn((M, d), g, dt=dt), bf16_randn((V, d), g, 0.3, dt=dt)
+    # duplicated rows: exact ties inside one block, across blocks, and at the very end of the vocabulary
+    w[7] = w[3]; w[300] = w[3]; w[V - 1] = w[V - 200]; w[9000] = w[8999]; w[9001] = w[8999]
+    # a dominant direction so that the duplicated rows are among the winners of some rows
+    x[::3] = (w[3].float() * 4).to(dt); x[1::3] = (w[V - 200].float() * 4).to(dt); x[2::7] = (w[8999].float() * 4).to(dt)
+    wp = fg.fg_pack_weight(code, w.cuda())
+    tok, logp = fg.fg_lm_head_topk(code, x.cuda(), wp, V, K)
+    slabs, used = fg.fg_gemm(code, x.cuda(), wp, V, epilogue=0, split_k=1)
+    torch.cuda.synchronize()
+    assert used == 1
+    logits = slabs[0].cpu().numpy()
+    o_tok, o_logp = Oracle("f32").topk_logp(logits, K)
+    assert np.array_equal(tok.cpu().numpy(), o_tok)
+    # log p = logit - logsumexp: both near the largest logit (tens, with the planted direction), each good to a few ulp
+    assert np.abs(logp.cpu().numpy() - o_logp).max() <= 1e-5 + 1e-6 * float(np.abs(logits).max())
+    # the ties were really there: some row has the duplicated tokens next to each other in rank order
+    if K >= 2:
+        assert any({3, 7} <= set(r) or {V - 200, V - 1} <= set(r) or {8999, 9000} <= set(r) for r in o_tok.tolist())
+    # the library's own one-pass kernel on the same logits agrees too
+    t2, l2 = fg.fg_topk_logp(slabs[0], K)
+    assert torch.equal(t2, tok)
