@@ -431,6 +431,12 @@ def ceilings(args):
             reads[f"{'nontemporal' if nt else 'plain'}_{blocks}_blocks"] = nbytes / t / 1e9
     out["hbm_read_GBps"] = reads
     out["hbm_read_best_GBps"] = max(reads.values())
+    paged = {}
+    for blocks in (2048, 4096, 8192, 16384, 32768):
+        t = timed(lambda: fg.fg_probe_read(src, 2, blocks, sink), 5)
+        paged[f"{blocks}_blocks"] = nbytes / t / 1e9
+    out["hbm_read_scattered_4KiB_pages_GBps"] = paged
+    out["hbm_read_scattered_4KiB_pages_best_GBps"] = max(paged.values())
     copies = {}
     half = src[:nbytes // 2]
     for blocks in (2048, 4096, 8192, 16384):
@@ -520,6 +526,8 @@ def main():
         for _ in range(args.warmup):
             wl.step()
         fg.fg_model_profile(wl.gm, True, max_marks=(args.steps + 1) * (model["n_layers"] * 10 + 16))
+        if wl.draft_ready:
+            fg.fg_model_profile(wl.gd, True, max_marks=(args.steps + 1) * 32 * (wl.L_draft + 1))
         torch.cuda.synchronize()
         per_step = []
         t0 = time.perf_counter()
@@ -533,6 +541,10 @@ def main():
         stages = fg.fg_model_profile_read(wl.gm)
         fg.fg_model_profile(wl.gm, False)
         st_ms = {k: v[0] / args.steps for k, v in stages.items() if v[1]}
+        draft_st_ms = None
+        if wl.draft_ready:
+            draft_st_ms = {k: v[0] / args.steps for k, v in fg.fg_model_profile_read(wl.gd).items() if v[1]}
+            fg.fg_model_profile(wl.gd, False)
         n_out, n_in = 2 * model["d_ffn"], model["d_model"]
         k_cnt = stages["gate_up"][1]
         assert k_cnt == args.steps * model["n_layers"], (k_cnt, args.steps)
@@ -574,7 +586,7 @@ def main():
             "step_hbm_frac": acct["bytes"] / t_verify / PEAK_HBM, "step_mfma_frac": acct["flops"] / t_verify / PEAK_MFMA,
             "step_bytes": acct["bytes"], "step_flops": acct["flops"],
             # per launch group of the verify step, from the stage timing inside the timed region (ms per step)
-            "verify_stage_ms": st_ms,
+            "verify_stage_ms": st_ms, "draft_stage_ms": draft_st_ms,
             "gemm_frac": acct["gemm_flops"] / (gemm_ms * 1e-3) / PEAK_MFMA if gemm_ms else None,
             "attn_frac": (acct["kv_bytes"] + M * 2.0 * model["n_q_heads"] * model["head_dim"] * 2 * model["n_layers"]) / (attn_ms * 1e-3) / PEAK_HBM if attn_ms else None,
             "gemm_ms": gemm_ms, "attn_ms": attn_ms,

@@ -359,7 +359,9 @@ int32_t fg_model_profile_read(fg_model *m, double *ms, int32_t *launches);
 /*
  * Ceiling probes (measurement only): what the GPU sustains for the two resources the path is bound by.
  * fg_probe_read: `blocks` blocks of 256 threads stream `bytes` (a multiple of 16) from src with 16-byte loads, four in
- *   flight per lane, ordinary or non-temporal; sink: device, blocks * 4 bytes (written only on a magic checksum).
+ *   flight per lane; nontemporal 0: ordinary loads, 1: non-temporal loads, 2: non-temporal loads of 4 KiB pages visited
+ *   in a hashed order, one page per wave at a time (the pattern of a paged KV cache; bytes a power of two);
+ *   sink: device, blocks * 4 bytes (written only on a magic checksum).
  * fg_probe_copy: the same stream written to dst (the plain copy whose FETCH_SIZE / WRITE_SIZE counter readings scale
  *   the traffic figures of the other kernels).
  * fg_probe_mfma: blocks x 4 waves each issue iters * 16 v_mfma_f32_32x32x16 (dtype FG_BF16 or FG_F16) on operands that

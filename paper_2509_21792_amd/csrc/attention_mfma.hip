@@ -224,10 +224,15 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(QW == 2 ? 2 
     // One step = 32 key positions (two pages).  The K / V fragments of step t + 1 are requested into a second
     // register set before the arithmetic of step t starts, so that with one wave per SIMD the memory latency is
     // covered by a whole step of MFMA and softmax work.
-    auto load_step = [&](int t0, Frag16 (&kf)[2][KK], Frag16 (&vf)[HT]) {
-        // the two pages of this step (the second may lie beyond the sequence: clamp, its keys are masked)
-        int pi0 = t0 >> 4, pi1 = min(pi0 + 1, max_pages - 1);
-        int pg0 = min(max(pt[pi0], 0), n_pages - 1), pg1 = min(max(pt[pi1], 0), n_pages - 1);
+    // The two pages of the step that starts at key position t0 (the second may lie beyond the sequence: clamped, its
+    // keys are masked).  Page ids are wave-uniform loads; they are fetched one step before the K / V loads that need
+    // them, so that a step's K / V requests do not wait behind a page-table round trip of their own.
+    auto pages_of = [&](int t0, int &pg0, int &pg1) {
+        const int pi0 = min(t0 >> 4, max_pages - 1), pi1 = min(pi0 + 1, max_pages - 1);
+        pg0 = min(max(pt[pi0], 0), n_pages - 1);
+        pg1 = min(max(pt[pi1], 0), n_pages - 1);
+    };
+    auto load_pages = [&](int pg0, int pg1, Frag16 (&kf)[2][KK], Frag16 (&vf)[HT]) {
         const T *kb[2], *vb[2];
         kb[0] = k_pool + (((size_t)layer * n_pages + pg0) * Hkv + hk) * head_stride;
         kb[1] = k_pool + (((size_t)layer * n_pages + pg1) * Hkv + hk) * head_stride;
@@ -244,6 +249,11 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(QW == 2 ? 2 
             vf[h].u2[0] = load8<STREAM>(vb[0] + (size_t)(h * 16 + c) * 16 + grp * 4);
             vf[h].u2[1] = load8<STREAM>(vb[1] + (size_t)(h * 16 + c) * 16 + grp * 4);
         }
+    };
+    auto load_step = [&](int t0, Frag16 (&kf)[2][KK], Frag16 (&vf)[HT]) {
+        int pg0, pg1;
+        pages_of(t0, pg0, pg1);
+        load_pages(pg0, pg1, kf, vf);
     };
     auto used = [&](int w) { return (qt0 + w) * 16 < rows; };   // wave-uniform: tiles past the last query row idle
     // One step over all tiles of the wave, in phases so that the independent tiles' MFMA and VALU chains overlap:
@@ -364,18 +374,30 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(QW == 2 ? 2 
             for (int h = 0; h < HT; h++) vf[h].u = vn[h].u;
         };
         load_step(t0, kf, vf);
+        int pn0, pn1;                      // pages of the next step to be requested (t0 + 32, then t0 + 64, ...)
+        pages_of(t0 + 32, pn0, pn1);
         while (t0 < t_plain) {
             {   // a full step: the first of the chunk, and any step whose reference has to move
                 const bool has_next = t0 + 32 < t_plain;
-                if (has_next) load_step(t0 + 32, kn, vn);
+                if (has_next) {
+                    load_pages(pn0, pn1, kn, vn);
+                    pages_of(t0 + 64, pn0, pn1);
+                }
                 compute_step(std::false_type{}, std::false_type{}, t0, kf, vf);
                 if (has_next) rotate();
                 t0 += 32;
             }
             while (t0 < t_plain) {
                 const bool has_next = t0 + 32 < t_plain;
-                if (has_next) load_step(t0 + 32, kn, vn);
-                if (!compute_step(std::false_type{}, std::true_type{}, t0, kf, vf)) break;   // redo it as a full step
+                if (has_next) {
+                    load_pages(pn0, pn1, kn, vn);
+                    pages_of(t0 + 64, pn0, pn1);
+                }
+                if (!compute_step(std::false_type{}, std::true_type{}, t0, kf, vf)) {   // redo it as a full step
+                    // the pages of t0 + 64 were just fetched; the outer loop requests t0 + 32 again
+                    pages_of(t0 + 32, pn0, pn1);
+                    break;
+                }
                 if (has_next) rotate();
                 t0 += 32;
             }

@@ -196,6 +196,7 @@ static int choose_split(int M, int N, int K, int block_rows, int block_cols)
 int32_t launch_gemm_mfma_big(int32_t dtype, const void *x, const void *wp, void *out, int M, int N, int K, int epilogue,
                              int split, int fixed_mt, const GemmEpi *epi, hipStream_t st);
 int gemm_mfma_big_split_for(int M, int N, int K);
+int gemm_mfma_big_unsplit_tiles(int M, int N, int K, int epilogue);
 int32_t launch_gemm_mfma_skinny(int32_t dtype, const void *x, const void *wp, void *out, int M, int N, int K, int epilogue,
                                 int split, hipStream_t st);
 int gemm_mfma_skinny_split_for(int M, int N, int K);
@@ -233,15 +234,18 @@ static int kernel_of_variant(int variant) { return variant == 1 ? KERNEL_STREAMI
 bool gemm_mfma_fuses_swiglu(int M, int N, int K) { return kernel_for(M, N, K, EPI_SWIGLU) != KERNEL_STREAMING; }
 
 // Whether a GEMM of this shape runs the fused epilogue `kind` (RoPE + append, residual add, top-k partials): they
-// exist in the pipelined kernel without a k split, which pays from four 256-row blocks on (below that the grid
-// needs k splits, hence slabs, to fill the chip).
+// exist in the pipelined kernel without a k split, which pays once the unsplit launch has tiles for three quarters
+// of the CUs; below that the grid needs k splits, hence slabs, to fill the chip.  Measured on the 7B-class shapes, us
+// per layer, unsplit with the fused epilogue against split with slabs and the separate row-wise kernel: at 1024 rows
+// QKV 76 against 52, O 56 against 34, down 224 against 113 (112 - 144 tiles); at 2048 rows 96 / 62 / 244 against
+// 93 / 68 / 250 (224 - 234 tiles).
 bool gemm_mfma_fusable(int M, int N, int K, int kind)
 {
     if (kind < EPI_ROPE) return true;
     if (kind > EPI_TOPK || (int64_t)M * K >= (1LL << 30)) return false;
     // the top-k epilogue is for LM heads: thousands of tiles, no k split at any row count the pipelined kernel takes
     if (kind == EPI_TOPK) return N >= 16384 && M > 128;
-    return M >= 1024;
+    return M > 256 && gemm_mfma_big_unsplit_tiles(M, N, K, kind) >= 192;
 }
 
 int gemm_mfma_split_for(int M, int N, int K)

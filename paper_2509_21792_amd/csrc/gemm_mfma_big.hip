@@ -73,47 +73,57 @@ __device__ __forceinline__ void epilogue_rope(f32x16_t (&acc)[MT][2], const Gemm
     T *qo = reinterpret_cast<T *>(ep.q_out) + head * hd;
     T *kp = reinterpret_cast<T *>(ep.k_pool);
     const int hk = head - Hq;
+    // Every global round trip of this epilogue is exposed (one wave per SIMD, nothing else to run), so there are as few
+    // as possible: the positions of all the lane's rows in one batch (groups of four consecutive rows; the position
+    // array is padded to a multiple of 64 entries by its 256-byte alignment in the workspace), then the table entries
+    // one row tile ahead of the tile being rotated.
+    int4 p4[MT][4];
 #pragma unroll
-    for (int i = 0; i < MT; i++) {
-        if (row0 + i * 32 >= M) break;
-        // positions of the lane's 16 rows (four groups of four consecutive rows; the position array is padded to a
-        // multiple of 64 entries by its 256-byte alignment in the workspace), then their table entries, all in flight
-        int pos[16];
+    for (int i = 0; i < MT; i++)
 #pragma unroll
         for (int q = 0; q < 4; q++) {
             const int m0 = row0 + i * 32 + 8 * q + rh;
-            int4 p4 = make_int4(0, 0, 0, 0);
-            if (m0 < M) p4 = *reinterpret_cast<const int4 *>(ep.pos + m0);
-            pos[4 * q] = p4.x; pos[4 * q + 1] = p4.y; pos[4 * q + 2] = p4.z; pos[4 * q + 3] = p4.w;
+            p4[i][q] = m0 < M ? *reinterpret_cast<const int4 *>(ep.pos + m0) : make_int4(0, 0, 0, 0);
         }
-        float2 cs[16];
+    float2 cs[2][16];
+    auto load_table = [&](int i, float2 (&dst)[16]) {
 #pragma unroll
         for (int r = 0; r < 16; r++) {
-            const int p = min(max(pos[r], 0), ep.max_pos - 1);
-            cs[r] = ep.rope_tab[(size_t)p * half + ebase + c];
+            const int4 v = p4[i][r >> 2];
+            const int pr = (r & 3) == 0 ? v.x : ((r & 3) == 1 ? v.y : ((r & 3) == 2 ? v.z : v.w));
+            const int p = min(max(pr, 0), ep.max_pos - 1);
+            dst[r] = ep.rope_tab[(size_t)p * half + ebase + c];
         }
+    };
+    load_table(0, cs[0]);
 #pragma unroll
-        for (int r = 0; r < 16; r++) {
-            const int rr = 8 * (r >> 2) + rh + (r & 3);
-            const float a = acc[i][0][r], b = acc[i][1][r];
-            tile[rr * 64 + c] = from_f<T>(a * cs[r].x - b * cs[r].y);
-            tile[rr * 64 + 32 + c] = from_f<T>(b * cs[r].x + a * cs[r].y);
-        }
-        // 256 pieces of 16 bytes: piece = (row, segment); segments 0-3 are dims ebase + 8 s .., 4-7 the rotated partners
+    for (int i = 0; i < MT; i++) {
+        if (i + 1 < MT) load_table(i + 1, cs[(i + 1) & 1]);
+        if (row0 + i * 32 < M) {
 #pragma unroll
-        for (int t = 0; t < 4; t++) {
-            const int piece = lane + 64 * t, rr = piece >> 3, seg = piece & 7;
-            const uint4 v = *reinterpret_cast<const uint4 *>(tile + rr * 64 + seg * 8);
-            const int m = row0 + i * 32 + rr;
-            if (m < M) {
-                const int e = seg < 4 ? ebase + seg * 8 : ebase + half + (seg - 4) * 8;
-                if (is_q) {
-                    *reinterpret_cast<uint4 *>(qo + (size_t)m * Hq * hd + e) = v;
-                } else {
-                    const int cell = ep.dest[m], page = cell >> 4, tk = cell & 15;
-                    if (cell >= 0) {   // -1: beyond the page table, not appended
-                        T *o = kp + (((size_t)ep.layer * ep.n_pages + page) * Hkv + hk) * page_elems;
-                        *reinterpret_cast<uint4 *>(o + k_page_offset(ep.k_frag, hd, tk, e)) = v;
+            for (int r = 0; r < 16; r++) {
+                const int rr = 8 * (r >> 2) + rh + (r & 3);
+                const float a = acc[i][0][r], b = acc[i][1][r];
+                const float2 t = cs[i & 1][r];
+                tile[rr * 64 + c] = from_f<T>(a * t.x - b * t.y);
+                tile[rr * 64 + 32 + c] = from_f<T>(b * t.x + a * t.y);
+            }
+            // 256 pieces of 16 bytes: piece = (row, segment); segments 0-3 are dims ebase + 8 s .., 4-7 the rotated partners
+#pragma unroll
+            for (int t = 0; t < 4; t++) {
+                const int piece = lane + 64 * t, rr = piece >> 3, seg = piece & 7;
+                const uint4 v = *reinterpret_cast<const uint4 *>(tile + rr * 64 + seg * 8);
+                const int m = row0 + i * 32 + rr;
+                if (m < M) {
+                    const int e = seg < 4 ? ebase + seg * 8 : ebase + half + (seg - 4) * 8;
+                    if (is_q) {
+                        *reinterpret_cast<uint4 *>(qo + (size_t)m * Hq * hd + e) = v;
+                    } else {
+                        const int cell = ep.dest[m], page = cell >> 4, tk = cell & 15;
+                        if (cell >= 0) {   // -1: beyond the page table, not appended
+                            T *o = kp + (((size_t)ep.layer * ep.n_pages + page) * Hkv + hk) * page_elems;
+                            *reinterpret_cast<uint4 *>(o + k_page_offset(ep.k_frag, hd, tk, e)) = v;
+                        }
                     }
                 }
             }
@@ -142,7 +152,8 @@ __device__ __forceinline__ void epilogue_topk(f32x16_t (&acc)[MT][2], const Gemm
     for (int i = 0; i < MT; i++) {
 #pragma unroll
         for (int half = 0; half < 2; half++) {
-            if (row0 + i * 32 + half * 16 >= M) break;   // the same for the whole block
+            // (no early exit from the unrolled loops: the accumulators must stay in registers, indexed by constants)
+            if (row0 + i * 32 + half * 16 < M) {   // the same for the whole block
             __syncthreads();                              // the previous tile's readers are done
 #pragma unroll
             for (int qq = 0; qq < 2; qq++)
@@ -200,6 +211,7 @@ __device__ __forceinline__ void epilogue_topk(f32x16_t (&acc)[MT][2], const Gemm
                     ep.part_ms[((size_t)m * n_bands + bx) * 2] = bmax;
                     ep.part_ms[((size_t)m * n_bands + bx) * 2 + 1] = sum;
                 }
+            }
             }
         }
     }
@@ -414,16 +426,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 4 ? 2
 // splits of 256-row blocks.  The wide outputs (gate/up, LM head) have thousands of tiles: 128-row blocks, two to a CU,
 // each one's prologue and epilogue under the other's main loop, are 4 - 8 % faster up to 2048 rows (gate/up 486 against
 // 506 us at 2048 rows, 248 against 269 at 1024) and 2 % slower at 4096.
+// The residual and top-k epilogues exist for 128- and 160-row blocks only: with 256 accumulator registers per lane the
+// extra live values of those epilogues (the tile of h, the selection's scratch) do not fit and the compiler spills.
 struct BigPlan { int split, mt; };
-static BigPlan plan_big(int M, int N, int K, int fixed_split, int fixed_mt)
+static bool tall_blocks_ok(int epilogue) { return epilogue != EPI_RESIDUAL && epilogue != EPI_TOPK; }
+static BigPlan plan_big(int M, int N, int K, int fixed_split, int fixed_mt, int epilogue = EPI_SLABS)
 {
     const int n_bands = (N / 32 + 7) / 8, chunks = K / 64;
-    if (N >= 16384 && fixed_mt <= 0) fixed_mt = M <= 2048 ? 4 : 8;
+    if (!tall_blocks_ok(epilogue) && fixed_mt == 8) fixed_mt = 0;
+    if (N >= 16384 && fixed_mt <= 0) fixed_mt = (M <= 2048 || !tall_blocks_ok(epilogue)) ? 4 : 8;
     BigPlan best{fixed_split > 0 ? fixed_split : 1, fixed_mt > 0 ? fixed_mt : 8};
     double best_cost = 1e30;
     static const int heights[3] = {8, 5, 4};
     for (int mt : heights) {
         if (fixed_mt > 0 && mt != fixed_mt) continue;
+        if (mt == 8 && !tall_blocks_ok(epilogue)) continue;
         const int row_blocks = (M + 32 * mt - 1) / (32 * mt);
         const int s_max = row_blocks == 1 ? 16 : 8;   // one row block: the slabs are small, the grid needs the splits
         const double chunk_us = 1.45 * mt / 8 * (mt == 8 ? 1.0 : 1.09);
@@ -443,6 +460,13 @@ static BigPlan plan_big(int M, int N, int K, int fixed_split, int fixed_mt)
 
 int gemm_mfma_big_split_for(int M, int N, int K) { return plan_big(M, N, K, 0, 0).split; }
 
+// Tiles of the launch when the shape runs without a k split (what the fused epilogues need).
+int gemm_mfma_big_unsplit_tiles(int M, int N, int K, int epilogue)
+{
+    const BigPlan p = plan_big(M, N, K, 1, 0, epilogue);
+    return (N / 32 + 7) / 8 * ((M + 32 * p.mt - 1) / (32 * p.mt));
+}
+
 template <typename T, int MT>
 static void launch_big_typed(const void *x, const void *wp, void *out, int M, int N, int K, int epilogue, int split,
                              const GemmEpi &ep, hipStream_t st)
@@ -460,8 +484,12 @@ static void launch_big_typed(const void *x, const void *wp, void *out, int M, in
     case EPI_SLABS: FG_BIG_LAUNCH(EPI_SLABS); break;
     case EPI_SWIGLU: FG_BIG_LAUNCH(EPI_SWIGLU); break;
     case EPI_ROPE: FG_BIG_LAUNCH(EPI_ROPE); break;
-    case EPI_TOPK: FG_BIG_LAUNCH(EPI_TOPK); break;
-    default: FG_BIG_LAUNCH(EPI_RESIDUAL); break;
+    default:
+        if constexpr (MT != 8) {   // the plan never pairs these epilogues with 256-row blocks
+            if (epilogue == EPI_TOPK) FG_BIG_LAUNCH(EPI_TOPK);
+            else FG_BIG_LAUNCH(EPI_RESIDUAL);
+        }
+        break;
     }
 #undef FG_BIG_LAUNCH
 }
@@ -478,7 +506,7 @@ int32_t launch_gemm_mfma_big(int32_t dtype, const void *x, const void *wp, void 
         return fail(FG_ERR_INVALID_ARG, "top-k epilogue needs 1 <= k <= 8 and its partial buffers");
     if (epilogue >= EPI_ROPE && !epi) return fail(FG_ERR_INVALID_ARG, "GEMM epilogue %d needs its arguments", epilogue);
     if (epilogue == EPI_ROPE && (epi->hd != 64 && epi->hd != 128)) return fail(FG_ERR_SHAPE, "RoPE epilogue needs head_dim 64 or 128");
-    const BigPlan p = plan_big(M, N, K, split, fixed_mt);
+    const BigPlan p = plan_big(M, N, K, split, fixed_mt, epilogue);
     const GemmEpi ep = epi ? *epi : GemmEpi();
 #define FG_BIG_MT(T)                                                                                   \
     do {                                                                                               \

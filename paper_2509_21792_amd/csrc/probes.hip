@@ -39,6 +39,29 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const uint4 *__restrict
     if (acc == 0x9e3779b9u && threadIdx.x == 0) sink[blockIdx.x] = acc;
 }
 
+// The same read stream in 4 KiB pieces at scattered addresses: a wave reads one 4 KiB page (four 1 KiB loads in
+// flight), and the pages are visited in a hashed order -- the access pattern of a paged KV cache whose pages were
+// handed out in no particular order (one K or V page of one kv head is 16 tokens x 128 dims x 2 bytes = 4 KiB).
+__global__ __launch_bounds__(256) void probe_read_paged_kernel(const uint4 *__restrict__ src, int64_t n_pages, uint32_t *sink)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = (int64_t)gridDim.x * 4;
+    uint32_t acc = 0;
+    for (int64_t i = wave; i < n_pages; i += n_waves) {
+        // a bijection of [0, n_pages) when n_pages is a power of two: odd multiplier, then a xor-shift
+        uint64_t p = ((uint64_t)i * 0x9E3779B97F4A7C15ULL) & (uint64_t)(n_pages - 1);
+        p ^= p >> 7;
+        p &= (uint64_t)(n_pages - 1);
+        const uint4 *page = src + p * 256 + lane;
+        const probe_u32x4_t a = __builtin_nontemporal_load(reinterpret_cast<const probe_u32x4_t *>(page));
+        const probe_u32x4_t b = __builtin_nontemporal_load(reinterpret_cast<const probe_u32x4_t *>(page + 64));
+        const probe_u32x4_t c = __builtin_nontemporal_load(reinterpret_cast<const probe_u32x4_t *>(page + 128));
+        const probe_u32x4_t d = __builtin_nontemporal_load(reinterpret_cast<const probe_u32x4_t *>(page + 192));
+        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    }
+    if (acc == 0x9e3779b9u && lane == 0) sink[blockIdx.x] = acc;
+}
+
 __global__ __launch_bounds__(256) void probe_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, int64_t n_vec)
 {
     const int64_t stride = (int64_t)gridDim.x * 256;
@@ -98,6 +121,11 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, int random, 
 int32_t launch_probe_read(const void *src, int64_t bytes, int nontemporal, int blocks, void *sink, hipStream_t st)
 {
     const int64_t n_vec = bytes / 16;
+    if (nontemporal == 2) {   // scattered 4 KiB pages; the caller checked that bytes is a power of two
+        hipLaunchKernelGGL(probe_read_paged_kernel, dim3(blocks), dim3(256), 0, st, (const uint4 *)src, bytes / 4096, (uint32_t *)sink);
+        FG_LAUNCH_CHECK("probe_read_paged");
+        return FG_OK;
+    }
     if (nontemporal) hipLaunchKernelGGL(probe_read_kernel<1>, dim3(blocks), dim3(256), 0, st, (const uint4 *)src, n_vec, (uint32_t *)sink);
     else hipLaunchKernelGGL(probe_read_kernel<0>, dim3(blocks), dim3(256), 0, st, (const uint4 *)src, n_vec, (uint32_t *)sink);
     FG_LAUNCH_CHECK("probe_read");
