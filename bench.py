@@ -330,8 +330,9 @@ def gen_experiment(args):
     pkv = fg.KVCache(model, ptab, pn)
     c_peak, lat = gloop.measure_c_peak(gm, pkv, gm.workspace(max(sizes), 32), sizes)
     del pkv
-    print(f"# C_peak = {c_peak}; latency ms by batch size: " + ", ".join(f"{b}:{t:.2f}" for b, t in zip(sizes, lat)),
-          file=sys.stderr, flush=True)
+    c_peak_linear = int(sizes[fg.fg_knee(sizes, lat, log2_axis=False)])     # the knee on the batch-size axis itself
+    print(f"# C_peak = {c_peak} (knee on the log2 B axis; {c_peak_linear} on the B axis); latency ms by batch size: " +
+          ", ".join(f"{b}:{t:.2f}" for b, t in zip(sizes, lat)), file=sys.stderr, flush=True)
     if args.c_peak:
         c_peak = args.c_peak
 
@@ -392,10 +393,58 @@ def gen_experiment(args):
            "value": res["rule"]["tokens_per_s"], "n_gpus": 1, "higher_is_better": True, "dtype": args.dtype, "data": "synthetic",
            "config": {"workload": f"{model['name']} {model['n_layers']} layers, {B} sequences, prefixes U[256,1024], response budgets "
                                   f"{int(budgets.min())}..{int(budgets.max())} (mean {budgets.mean():.0f}), planted agreement {p_agree}, greedy"},
-           "c_peak": c_peak, "c_peak_latency_ms": dict(zip(map(str, sizes), lat)), "runs": res,
+           "c_peak": c_peak, "c_peak_knee_on_linear_axis": c_peak_linear, "c_peak_latency_ms": dict(zip(map(str, sizes), lat)),
+           "runs": res,
            "speedup_rule_vs_plain": res["rule"]["tokens_per_s"] / res["plain"]["tokens_per_s"],
            "speedup_rule_vs_fixed": res["rule"]["tokens_per_s"] / res["fixed"]["tokens_per_s"]}
     print(json.dumps(out))
+
+
+def gemm_kernel_bench(args):
+    """--gemm NAME: one GEMM of the 7B-class layer at --rows rows, launched --reps times through the kernel-level entry
+    point (the command the per-kernel rocprofv3 summaries under profiles/ are taken with).  The weights of --cycle
+    different layers are used in turn so that, as in the step, they come from HBM and not from the last-level cache."""
+    import torch
+    import paper_2509_21792_amd as fg
+    from synth import configs
+    m = configs.Q7B
+    d, F, V = m["d_model"], m["d_ffn"], m["vocab"]
+    qkvd = (m["n_q_heads"] + 2 * m["n_kv_heads"]) * m["head_dim"]
+    shapes = {"qkv": (qkvd, d, 0), "o": (d, d, 0), "o_residual": (d, d, 3), "gate_up": (2 * F, d, 1), "down": (d, F, 0),
+              "down_residual": (d, F, 3), "lm_head": (V, d, 0), "lm_head_topk": (V, d, 4)}
+    n_out, n_in, epi = shapes[args.gemm]
+    M = args.rows
+    code = fg.FG_BF16 if args.dtype == "bf16" else fg.FG_F16
+    td = torch.bfloat16 if args.dtype == "bf16" else torch.float16
+    g = torch.Generator(device="cuda").manual_seed(0)
+
+    def rnd(*shape):
+        return (torch.randn(*shape, generator=g, device="cuda") * 0.05).to(torch.bfloat16).to(td)
+    n_w = 1 if n_out >= 100000 else args.cycle
+    ws = []
+    for _ in range(n_w):
+        if epi == 1:
+            ws.append(fg.fg_pack_weight(code, rnd(n_out // 2, n_in), rnd(n_out // 2, n_in)))
+        else:
+            ws.append(fg.fg_pack_weight(code, rnd(n_out, n_in)))
+    x = rnd(M, n_in)
+    h = torch.zeros((M, n_out), dtype=torch.float32, device="cuda") if epi == 3 else None
+    it = [0]
+
+    def f():
+        w = ws[it[0] % n_w]
+        it[0] += 1
+        if epi == 4:
+            fg.fg_lm_head_topk(code, x, w, V, 2)
+        else:
+            fg.fg_gemm(code, x, w, n_out, epilogue=epi, split_k=args.split, variant=args.variant, out=h)
+    ts = time_each(torch, f, args.reps, 5)
+    flops = 2.0 * M * n_out * n_in
+    byts = 2.0 * n_out * n_in + 2.0 * M * n_in
+    print(json.dumps({"metric": "one GEMM of the 7B-class layer (kernel-level entry point)", "n_gpus": 1, "dtype": args.dtype,
+                      "data": "synthetic", "config": {"workload": f"{args.gemm} M={M} n_out={n_out} n_in={n_in} variant={args.variant} split={args.split}"},
+                      "kernel": fg.fg_gemm_kernel_name(M, n_out, n_in, min(epi, 3)), "us": spread(ts), "TFLOPs": flops / ts[0] / 1e12,
+                      "mfma_frac": flops / ts[0] / PEAK_MFMA, "weight_stream_GBps": byts / ts[0] / 1e9}))
 
 
 def ceilings(args):
@@ -485,6 +534,13 @@ def main():
     ap.add_argument("--graph", action="store_true", help="also time the round with its device side replayed as a HIP graph")
     ap.add_argument("--sweep", action="store_true",
                     help="the metric's range: B = 8 ... 256 on the 7B-class target, each with the shape Eq. 1-3 give")
+    ap.add_argument("--gemm", default="", choices=["", "qkv", "o", "o_residual", "gate_up", "down", "down_residual", "lm_head", "lm_head_topk"],
+                    help="time one GEMM of the 7B-class layer through the kernel-level entry point and exit")
+    ap.add_argument("--rows", type=int, default=2048, help="--gemm: rows M")
+    ap.add_argument("--reps", type=int, default=56, help="--gemm: timed launches")
+    ap.add_argument("--variant", type=int, default=0, help="--gemm: 0 = the library's kernel choice, 1-5 force one (see fastgrpo.h)")
+    ap.add_argument("--split", type=int, default=0, help="--gemm: k splits of the partial-sum epilogue (0 = the library's choice)")
+    ap.add_argument("--cycle", type=int, default=8, help="--gemm: number of different weight matrices used in turn")
     ap.add_argument("--ceilings", action="store_true",
                     help="measure the achievable HBM stream rate and MFMA rate of this GPU (probe kernels) and exit")
     args = ap.parse_args()
@@ -496,6 +552,9 @@ def main():
     import paper_2509_21792_amd as fg
     fg.lib()
     assert torch.cuda.is_available(), "no GPU: the HIP path has no CPU fallback"
+    if args.gemm:
+        gemm_kernel_bench(args)
+        return
     if args.ceilings:
         ceilings(args)
         return

@@ -138,12 +138,13 @@ int32_t fg_plan(int32_t B_cur, float C_peak, float alpha, int32_t K_max, int32_t
 /*
  * Knee of a latency curve (appendix, "Empirical Measurement of C_peak": forward latency against batch size is
  * flat while the pass is bound by weight traffic and rises once it is bound by compute; C_peak is the batch size
- * at the knee).  Host only.  x[n] strictly increasing batch sizes, y[n] latencies (host pointers).  Both axes are
- * scaled to [0, 1]; *knee_index is the sample farthest below the chord through the first and last sample (the
- * first such sample on ties; 0 when the curve never dips below the chord).
- * Errors: NULL pointers, n < 3, x not strictly increasing -> FG_ERR_INVALID_ARG.
+ * at the knee).  Host only.  x[n] strictly increasing batch sizes, y[n] latencies (host pointers).  log2_axis != 0
+ * takes the abscissa as log2(x) (batch sizes sampled geometrically), 0 as x itself (the appendix plots latency against
+ * the batch size).  Both axes are scaled to [0, 1]; *knee_index is the sample farthest below the chord through the
+ * first and last sample (the first such sample on ties; 0 when the curve never dips below the chord).
+ * Errors: NULL pointers, n < 3, x not strictly increasing (or not positive with log2_axis) -> FG_ERR_INVALID_ARG.
  */
-int32_t fg_knee(const double *x, const double *y, int32_t n, int32_t *knee_index);
+int32_t fg_knee(const double *x, const double *y, int32_t n, int32_t log2_axis, int32_t *knee_index);
 
 /*
  * Row selection for the live set (Alg. 1, the update of the live batch size: finished sequences leave the batch):

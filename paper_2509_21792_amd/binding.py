@@ -95,7 +95,7 @@ def lib():
         L.fg_draft_frontier.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32] + [C.c_void_p] * 4 + \
                                        [C.c_int32, C.c_int32] + \
                                        [C.c_void_p] * 8 + [C.c_int32, C.c_void_p, C.c_void_p]
-        L.fg_knee.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]
+        L.fg_knee.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]
         L.fg_select_rows.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         L.fg_topk_logp.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.fg_lm_head_topk_workspace_bytes.restype = C.c_int64
@@ -473,11 +473,11 @@ def fg_lm_head_topk(dtype, x, lm_head_packed, vocab, K):
     return tok, logp
 
 
-def fg_knee(x, y):
+def fg_knee(x, y, log2_axis=False):
     x = np.ascontiguousarray(x, dtype=np.float64)
     y = np.ascontiguousarray(y, dtype=np.float64)
     k = C.c_int32()
-    _check(lib().fg_knee(x.ctypes.data_as(C.c_void_p), y.ctypes.data_as(C.c_void_p), len(x), C.byref(k)))
+    _check(lib().fg_knee(x.ctypes.data_as(C.c_void_p), y.ctypes.data_as(C.c_void_p), len(x), int(log2_axis), C.byref(k)))
     return k.value
 
 

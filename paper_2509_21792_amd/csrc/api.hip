@@ -407,9 +407,16 @@ int32_t fg_plan(int32_t B_cur, float C_peak, float alpha, int32_t K_max, int32_t
     return FG_OK;
 }
 
-int32_t fg_knee(const double *x, const double *y, int32_t n, int32_t *knee_index)
+int32_t fg_knee(const double *x_in, const double *y, int32_t n, int32_t log2_axis, int32_t *knee_index)
 {
-    if (!x || !y || !knee_index || n < 3) return fail(FG_ERR_INVALID_ARG, "fg_knee: NULL pointer or fewer than 3 samples");
+    if (!x_in || !y || !knee_index || n < 3) return fail(FG_ERR_INVALID_ARG, "fg_knee: NULL pointer or fewer than 3 samples");
+    std::vector<double> xs(x_in, x_in + n);
+    if (log2_axis)
+        for (int i = 0; i < n; i++) {
+            if (!(xs[i] > 0.0)) return fail(FG_ERR_INVALID_ARG, "fg_knee: a log2 axis needs positive x (sample %d)", i);
+            xs[i] = log2(xs[i]);
+        }
+    const double *x = xs.data();
     double lo = y[0], hi = y[0];
     for (int i = 1; i < n; i++) {
         if (!(x[i] > x[i - 1])) return fail(FG_ERR_INVALID_ARG, "fg_knee: x must increase strictly (sample %d)", i);

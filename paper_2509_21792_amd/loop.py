@@ -202,12 +202,13 @@ def generate(target, draft, kv, dkv, slot, st, first, budgets, c_peak, ws_t, ws_
     return outs, hist
 
 
-def measure_c_peak(target, kv, ws, batch_sizes, warmup=2, reps=5):
+def measure_c_peak(target, kv, ws, batch_sizes, warmup=2, reps=5, log2_axis=True):
     """Empirical C_peak (appendix): latency of one forward pass over B single-token inputs, for each B in
     batch_sizes, timed with events on the current stream; the knee of the curve is C_peak.  Batch sizes are meant
     to be spaced geometrically and the knee is taken on the log2(B) axis, where the flat weight-bound part and the
     rising compute-bound part have comparable extent.  The sequences start from empty caches (the cache must have
-    at least max(batch_sizes) slots); nothing is committed.
+    at least max(batch_sizes) slots); nothing is committed.  log2_axis=False takes the knee on the batch-size axis
+    itself, as the appendix plots it (fg_knee(times) can be called again on the returned latencies for the other axis).
     Returns (C_peak, latencies in ms)."""
     dev = kv.k_pool.device
     times = []
@@ -226,7 +227,7 @@ def measure_c_peak(target, kv, ws, batch_sizes, warmup=2, reps=5):
         e1.record()
         torch.cuda.synchronize()
         times.append(e0.elapsed_time(e1) / reps)
-    k = fg.fg_knee(np.log2(np.asarray(batch_sizes, dtype=np.float64)), np.asarray(times, dtype=np.float64))
+    k = fg.fg_knee(batch_sizes, times, log2_axis=log2_axis)
     return int(batch_sizes[k]), times
 
 

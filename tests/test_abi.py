@@ -81,6 +81,11 @@ def test_knee_agrees_with_the_oracle_on_random_curves(L, orc32):
         assert binding.fg_knee(x, y) == orc32.knee(x, y)
     flat_then_up = [3.0] * 10 + [3.0 + 0.5 * i for i in range(1, 20)]
     assert binding.fg_knee(list(range(1, 30)), flat_then_up) == 9
+    # the log2 axis is the library's own arithmetic: the same as handing it log2(x)
+    xs = [1, 2, 4, 8, 16, 32, 64, 128, 256, 512]
+    ys = [3.0, 3.0, 3.05, 3.1, 3.1, 3.3, 3.9, 5.1, 6.8, 9.2]
+    assert binding.fg_knee(xs, ys, log2_axis=True) == binding.fg_knee(np.log2(xs), ys) == orc32.knee(np.log2(xs), ys)
+    assert binding.fg_knee(xs, ys) == orc32.knee(xs, ys)
     with pytest.raises(binding.FgError):
         binding.fg_knee([1, 2], [1.0, 2.0])
     with pytest.raises(binding.FgError):
