@@ -35,6 +35,11 @@
  *                      (tests/test_oracle_draft_expand.py)
  *   orc_knee           exact break point of two-segment curves; invariance
  *                      under affine maps of either axis
+ *   orc_draft_train    central finite differences (fp64 build) and torch
+ *                      autograd on the same forward written with torch ops;
+ *                      the loss itself (the paper names none) is this build's
+ *                      reading -- "parity unpinned" as to which loss
+ *   orc_adamw          torch.optim.AdamW
  *   draft head internals (fc + one layer, no final norm): fixed by this
  *   build's reading of Sec. 2 only -- "parity unpinned" beyond the shared
  *   layer code.
@@ -671,4 +676,270 @@ int orc_build_tree(const int32_t *cand_tok, const int32_t *cand_parent, const fl
     }
     free(chosen); free(depth); free(newidx);
     return rc;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Online draft learning (Sec. 4.2 "Draft Model Learning with Online Target  */
+/* Feedback"; Alg. 1, the draft training phase).  The draft head is trained  */
+/* on what the generation phase left behind: the tokens the target emitted   */
+/* and the target's hidden states ("logits and hidden states", which are     */
+/* cached).  The paper names no loss; the reading taken is the one of the    */
+/* draft-head work it follows for pre-training (Sec. 5.1): per position,     */
+/*   L = mean_e smooth_l1(h_hat[e] - f_next[e])                               */
+/*     + w_ce * CE(softmax(lm_head f_next), softmax(lm_head h_hat)),          */
+/* h_hat = the head's output for the entry (token t+1, target feature t),    */
+/* f_next = the target's feature t+1, averaged over the valid entries.       */
+/* Each sequence is one teacher-forced chain from an empty draft cache        */
+/* (causal attention inside the chain).  This function returns the loss and  */
+/* the gradient of every draft parameter; embedding and LM head are the      */
+/* target's and frozen.                                                       */
+/* Pins: central finite differences in the fp64 build, and the same forward  */
+/* written with torch ops differentiated by autograd (tests/test_oracle_      */
+/* train.py).                                                                 */
+/* ------------------------------------------------------------------------ */
+
+/* out[m, k] = sum_n dy[m, n] * W[n, k] */
+static void matmul_nn(real *out, const real *dy, const real *W, int64_t M, int64_t N, int64_t K)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; m++) {
+        real *o = out + m * K;
+        for (int64_t k = 0; k < K; k++) o[k] = 0;
+        for (int64_t n = 0; n < N; n++) {
+            const real g = dy[m * N + n];
+            const real *w = W + n * K;
+            for (int64_t k = 0; k < K; k++) o[k] += g * w[k];
+        }
+    }
+}
+
+/* dW[n, k] = sum_m dy[m, n] * x[m, k] */
+static void matmul_tn(real *dW, const real *dy, const real *x, int64_t M, int64_t N, int64_t K)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; n++) {
+        real *o = dW + n * K;
+        for (int64_t k = 0; k < K; k++) o[k] = 0;
+        for (int64_t m = 0; m < M; m++) {
+            const real g = dy[m * N + n];
+            const real *a = x + m * K;
+            for (int64_t k = 0; k < K; k++) o[k] += g * a[k];
+        }
+    }
+}
+
+/* y = x * inv * g with inv = (mean(x^2) + eps)^(-1/2):
+ * dx = inv * (g . dy) - x * inv^3 * sum_k (g . dy)_k x_k / d;  dg += sum over rows of dy * x * inv */
+static void rmsnorm_backward(real *dx, real *dg, const real *dy, const real *x, const real *g, int64_t M, int64_t d, double eps)
+{
+    for (int64_t k = 0; k < d; k++) dg[k] = 0;
+    for (int64_t m = 0; m < M; m++) {
+        real ss = 0;
+        for (int64_t k = 0; k < d; k++) ss += x[m * d + k] * x[m * d + k];
+        const real inv = (real)1 / (real)sqrt((double)(ss / (real)d) + eps);
+        real dot = 0;
+        for (int64_t k = 0; k < d; k++) dot += g[k] * dy[m * d + k] * x[m * d + k];
+        for (int64_t k = 0; k < d; k++) {
+            dx[m * d + k] = inv * g[k] * dy[m * d + k] - x[m * d + k] * inv * inv * inv * dot / (real)d;
+            dg[k] += dy[m * d + k] * x[m * d + k] * inv;
+        }
+    }
+}
+
+/* the transpose of rope_head's rotation (it is orthogonal) */
+static void rope_head_backward(real *dv, int hd, int64_t pos, double theta)
+{
+    int half = hd / 2;
+    for (int i = 0; i < half; i++) {
+        double ang = (double)pos * pow(theta, -2.0 * (double)i / (double)hd);
+        real c = (real)cos(ang), s = (real)sin(ang);
+        real a = dv[i], b = dv[i + half];
+        dv[i] = a * c + b * s;
+        dv[i + half] = b * c - a * s;
+    }
+}
+
+/*
+ * tokens [B, T], feat_in / feat_tgt [B, T, d], n_valid [B]: entries t < n_valid[b] carry loss (the rest is padding
+ * behind them, which causal attention keeps from influencing them).  loss[0] = regression term, loss[1] = cross-entropy
+ * term (before the weight); the total is loss[0] + w_ce * loss[1].  Gradients of the total: g_* in the shapes of the
+ * weights.  One decoder layer (n_layers must be 1).
+ */
+int orc_draft_train(const orc_cfg *c, const orc_weights *w, int32_t B, int32_t T, const int32_t *tokens, const real *feat_in,
+                    const real *feat_tgt, const int32_t *n_valid, double w_ce, real *loss, real *g_fc, real *g_wqkv, real *g_wo,
+                    real *g_gate, real *g_up, real *g_down, real *g_norm_attn, real *g_norm_ffn)
+{
+    if (c->n_layers != 1 || B < 1 || T < 1 || c->n_q_heads % c->n_kv_heads || c->head_dim % 2) return ORC_ERR_ARG;
+    const int d = c->d_model, Hq = c->n_q_heads, Hkv = c->n_kv_heads, hd = c->head_dim, F = c->d_ffn, V = c->vocab;
+    const int grp = Hq / Hkv, qkvd = (Hq + 2 * Hkv) * hd, M = B * T;
+    int64_t n_tot = 0;
+    for (int b = 0; b < B; b++) {
+        if (n_valid[b] < 0 || n_valid[b] > T) return ORC_ERR_ARG;
+        n_tot += n_valid[b];
+    }
+    if (n_tot == 0) return ORC_ERR_ARG;
+    for (int r = 0; r < M; r++)
+        if (tokens[r] < 0 || tokens[r] >= V) return ORC_ERR_ARG;
+#define ALLOC(n) ((real *)calloc((size_t)(n), sizeof(real)))
+    real *cat = ALLOC((size_t)M * 2 * d), *h0 = ALLOC((size_t)M * d), *a1 = ALLOC((size_t)M * d), *qkv = ALLOC((size_t)M * qkvd);
+    real *P = ALLOC((size_t)B * Hq * T * T), *att = ALLOC((size_t)M * Hq * hd), *proj = ALLOC((size_t)M * d), *h1 = ALLOC((size_t)M * d);
+    real *a2 = ALLOC((size_t)M * d), *gate = ALLOC((size_t)M * F), *up = ALLOC((size_t)M * F), *act = ALLOC((size_t)M * F);
+    real *h2 = ALLOC((size_t)M * d), *z = ALLOC((size_t)M * V), *zt = ALLOC((size_t)M * V);
+    /* ---- forward ---- */
+    for (int r = 0; r < M; r++) {
+        memcpy(cat + (size_t)r * 2 * d, w->embed + (size_t)tokens[r] * d, sizeof(real) * d);
+        memcpy(cat + (size_t)r * 2 * d + d, feat_in + (size_t)r * d, sizeof(real) * d);
+    }
+    matmul_nt(h0, cat, w->fc, M, d, 2 * d);
+    rmsnorm(a1, h0, w->norm_attn[0], M, d, c->rms_eps);
+    matmul_nt(qkv, a1, w->wqkv[0], M, qkvd, d);
+    for (int b = 0; b < B; b++)
+        for (int t = 0; t < T; t++)
+            for (int hh = 0; hh < Hq + Hkv; hh++) rope_head(qkv + (size_t)(b * T + t) * qkvd + (size_t)hh * hd, hd, t, c->rope_theta);
+    const real scale = (real)1 / (real)sqrt((double)hd);
+    for (int b = 0; b < B; b++)
+        for (int hq = 0; hq < Hq; hq++) {
+            const int hk = hq / grp;
+            for (int t = 0; t < T; t++) {
+                const real *q = qkv + (size_t)(b * T + t) * qkvd + (size_t)hq * hd;
+                real *p = P + (((size_t)b * Hq + hq) * T + t) * T;
+                real mx = 0;
+                for (int s = 0; s <= t; s++) {
+                    const real *k = qkv + (size_t)(b * T + s) * qkvd + (size_t)(Hq + hk) * hd;
+                    real sc = 0;
+                    for (int e = 0; e < hd; e++) sc += q[e] * k[e];
+                    p[s] = sc * scale;
+                    if (s == 0 || p[s] > mx) mx = p[s];
+                }
+                real den = 0;
+                for (int s = 0; s <= t; s++) { p[s] = (real)exp((double)(p[s] - mx)); den += p[s]; }
+                real *o = att + (size_t)(b * T + t) * Hq * hd + (size_t)hq * hd;
+                for (int s = 0; s <= t; s++) {
+                    p[s] /= den;
+                    const real *v = qkv + (size_t)(b * T + s) * qkvd + (size_t)(Hq + Hkv + hk) * hd;
+                    for (int e = 0; e < hd; e++) o[e] += p[s] * v[e];
+                }
+            }
+        }
+    matmul_nt(proj, att, w->wo[0], M, d, (int64_t)Hq * hd);
+    for (size_t i = 0; i < (size_t)M * d; i++) h1[i] = h0[i] + proj[i];
+    rmsnorm(a2, h1, w->norm_ffn[0], M, d, c->rms_eps);
+    matmul_nt(gate, a2, w->w_gate[0], M, F, d);
+    matmul_nt(up, a2, w->w_up[0], M, F, d);
+    for (size_t i = 0; i < (size_t)M * F; i++) act[i] = gate[i] / ((real)1 + (real)exp((double)-gate[i])) * up[i];
+    matmul_nt(proj, act, w->w_down[0], M, d, F);
+    for (size_t i = 0; i < (size_t)M * d; i++) h2[i] = h1[i] + proj[i];
+    matmul_nt(z, h2, w->lm_head, M, V, d);
+    matmul_nt(zt, feat_tgt, w->lm_head, M, V, d);
+    /* ---- loss and its gradient with respect to h2 (dh2) and z (dz, kept in z) ---- */
+    real *dh2 = ALLOC((size_t)M * d);
+    double l_reg = 0, l_ce = 0;
+    for (int b = 0; b < B; b++)
+        for (int t = 0; t < T; t++) {
+            const int r = b * T + t;
+            real *zr = z + (size_t)r * V, *ztr = zt + (size_t)r * V;
+            if (t >= n_valid[b]) {
+                for (int v = 0; v < V; v++) zr[v] = 0;
+                continue;
+            }
+            for (int e = 0; e < d; e++) {
+                const real df = h2[(size_t)r * d + e] - feat_tgt[(size_t)r * d + e];
+                const real ad = df < 0 ? -df : df;
+                l_reg += (double)(ad < 1 ? (real)0.5 * df * df : ad - (real)0.5) / d;
+                dh2[(size_t)r * d + e] = (ad < 1 ? df : (df < 0 ? (real)-1 : (real)1)) / (real)d / (real)n_tot;
+            }
+            real mq = zr[0], mp = ztr[0];
+            for (int v = 1; v < V; v++) { if (zr[v] > mq) mq = zr[v]; if (ztr[v] > mp) mp = ztr[v]; }
+            double sq = 0, sp = 0;
+            for (int v = 0; v < V; v++) { sq += exp((double)(zr[v] - mq)); sp += exp((double)(ztr[v] - mp)); }
+            const double lq = (double)mq + log(sq), lp = (double)mp + log(sp);
+            for (int v = 0; v < V; v++) {
+                const double pv = exp((double)ztr[v] - lp), qv = exp((double)zr[v] - lq);
+                l_ce -= pv * ((double)zr[v] - lq);
+                zr[v] = (real)(w_ce * (qv - pv) / (double)n_tot);     /* d loss / d z */
+            }
+        }
+    loss[0] = (real)(l_reg / (double)n_tot);
+    loss[1] = (real)(l_ce / (double)n_tot);
+    /* ---- backward ---- */
+    real *tmp = ALLOC((size_t)M * d), *dact = ALLOC((size_t)M * F), *dgate = ALLOC((size_t)M * F), *dup = ALLOC((size_t)M * F);
+    real *da = ALLOC((size_t)M * d), *dh1 = ALLOC((size_t)M * d), *datt = ALLOC((size_t)M * Hq * hd), *dqkv = ALLOC((size_t)M * qkvd);
+    real *dh0 = ALLOC((size_t)M * d);
+    matmul_nn(tmp, z, w->lm_head, M, V, d);                       /* through the frozen LM head */
+    for (size_t i = 0; i < (size_t)M * d; i++) dh2[i] += tmp[i];
+    matmul_tn(g_down, dh2, act, M, d, F);
+    matmul_nn(dact, dh2, w->w_down[0], M, d, F);
+    for (size_t i = 0; i < (size_t)M * F; i++) {
+        const real g = gate[i], sg = (real)1 / ((real)1 + (real)exp((double)-g));
+        dup[i] = dact[i] * g * sg;
+        dgate[i] = dact[i] * up[i] * (sg + g * sg * ((real)1 - sg));
+    }
+    matmul_tn(g_gate, dgate, a2, M, F, d);
+    matmul_tn(g_up, dup, a2, M, F, d);
+    matmul_nn(da, dgate, w->w_gate[0], M, F, d);
+    matmul_nn(tmp, dup, w->w_up[0], M, F, d);
+    for (size_t i = 0; i < (size_t)M * d; i++) da[i] += tmp[i];
+    rmsnorm_backward(tmp, g_norm_ffn, da, h1, w->norm_ffn[0], M, d, c->rms_eps);
+    for (size_t i = 0; i < (size_t)M * d; i++) dh1[i] = dh2[i] + tmp[i];
+    matmul_tn(g_wo, dh1, att, M, d, (int64_t)Hq * hd);
+    matmul_nn(datt, dh1, w->wo[0], M, d, (int64_t)Hq * hd);
+    for (int b = 0; b < B; b++)
+        for (int hq = 0; hq < Hq; hq++) {
+            const int hk = hq / grp;
+            for (int t = 0; t < T; t++) {
+                const real *p = P + (((size_t)b * Hq + hq) * T + t) * T;
+                const real *dout = datt + (size_t)(b * T + t) * Hq * hd + (size_t)hq * hd;
+                const real *q = qkv + (size_t)(b * T + t) * qkvd + (size_t)hq * hd;
+                real *dq = dqkv + (size_t)(b * T + t) * qkvd + (size_t)hq * hd;
+                real dot = 0;
+                for (int s = 0; s <= t; s++) {
+                    const real *v = qkv + (size_t)(b * T + s) * qkvd + (size_t)(Hq + Hkv + hk) * hd;
+                    real dp = 0;
+                    for (int e = 0; e < hd; e++) dp += dout[e] * v[e];
+                    dot += dp * p[s];
+                }
+                for (int s = 0; s <= t; s++) {
+                    const real *k = qkv + (size_t)(b * T + s) * qkvd + (size_t)(Hq + hk) * hd;
+                    const real *v = qkv + (size_t)(b * T + s) * qkvd + (size_t)(Hq + Hkv + hk) * hd;
+                    real *dk = dqkv + (size_t)(b * T + s) * qkvd + (size_t)(Hq + hk) * hd;
+                    real *dv = dqkv + (size_t)(b * T + s) * qkvd + (size_t)(Hq + Hkv + hk) * hd;
+                    real dp = 0;
+                    for (int e = 0; e < hd; e++) dp += dout[e] * v[e];
+                    const real ds = p[s] * (dp - dot) * scale;
+                    for (int e = 0; e < hd; e++) {
+                        dq[e] += ds * k[e];
+                        dk[e] += ds * q[e];
+                        dv[e] += p[s] * dout[e];
+                    }
+                }
+            }
+        }
+    for (int b = 0; b < B; b++)
+        for (int t = 0; t < T; t++)
+            for (int hh = 0; hh < Hq + Hkv; hh++) rope_head_backward(dqkv + (size_t)(b * T + t) * qkvd + (size_t)hh * hd, hd, t, c->rope_theta);
+    matmul_tn(g_wqkv, dqkv, a1, M, qkvd, d);
+    matmul_nn(da, dqkv, w->wqkv[0], M, qkvd, d);
+    rmsnorm_backward(tmp, g_norm_attn, da, h0, w->norm_attn[0], M, d, c->rms_eps);
+    for (size_t i = 0; i < (size_t)M * d; i++) dh0[i] = dh1[i] + tmp[i];
+    matmul_tn(g_fc, dh0, cat, M, d, 2 * d);
+#undef ALLOC
+    free(cat); free(h0); free(a1); free(qkv); free(P); free(att); free(proj); free(h1); free(a2); free(gate); free(up); free(act);
+    free(h2); free(z); free(zt); free(dh2); free(tmp); free(dact); free(dgate); free(dup); free(da); free(dh1); free(datt);
+    free(dqkv); free(dh0);
+    return ORC_OK;
+}
+
+/* One AdamW step (the optimiser Sec. 5.1 names), decoupled weight decay, bias-corrected moments:
+ * m = b1 m + (1 - b1) g;  v = b2 v + (1 - b2) g^2;  p -= lr (m / (1 - b1^t) / (sqrt(v / (1 - b2^t)) + eps) + wd p). */
+int orc_adamw(real *p, const real *g, real *m, real *v, int64_t n, double lr, double b1, double b2, double eps, double wd, int32_t step)
+{
+    if (n < 0 || step < 1) return ORC_ERR_ARG;
+    const double c1 = 1.0 - pow(b1, step), c2 = 1.0 - pow(b2, step);
+    for (int64_t i = 0; i < n; i++) {
+        m[i] = (real)(b1 * m[i] + (1.0 - b1) * g[i]);
+        v[i] = (real)(b2 * v[i] + (1.0 - b2) * (double)g[i] * g[i]);
+        const double upd = ((double)m[i] / c1) / (sqrt((double)v[i] / c2) + eps) + wd * (double)p[i];
+        p[i] = (real)((double)p[i] - lr * upd);
+    }
+    return ORC_OK;
 }

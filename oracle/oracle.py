@@ -265,3 +265,33 @@ class Oracle:
                                      C.c_int32(Cn), C.c_int32(N), _ptr(tokens), _ptr(parent), _ptr(sel))
         self._check(rc, "orc_build_tree")
         return tokens, parent, sel
+
+    # -- online draft learning -------------------------------------------------------------------
+    def draft_train(self, draft, tokens, feat_in, feat_tgt, n_valid, w_ce=0.1):
+        """Loss terms and gradients of every draft parameter (see orc_draft_train).  Returns (loss [2], grads dict)."""
+        cfg = draft.cfg
+        tokens = _i32(tokens)
+        B, T = tokens.shape
+        d, F = cfg["d_model"], cfg["d_ffn"]
+        qkvd = (cfg["n_q_heads"] + 2 * cfg["n_kv_heads"]) * cfg["head_dim"]
+        hq = cfg["n_q_heads"] * cfg["head_dim"]
+        feat_in = np.ascontiguousarray(feat_in, dtype=self.real)
+        feat_tgt = np.ascontiguousarray(feat_tgt, dtype=self.real)
+        n_valid = _i32(n_valid)
+        loss = np.zeros(2, dtype=self.real)
+        shapes = dict(fc=(d, 2 * d), wqkv=(qkvd, d), wo=(d, hq), w_gate=(F, d), w_up=(F, d), w_down=(d, F), norm_attn=(d,), norm_ffn=(d,))
+        g = {k: np.zeros(s, dtype=self.real) for k, s in shapes.items()}
+        rc = self.lib.orc_draft_train(C.byref(draft.c), C.byref(draft.w), C.c_int32(B), C.c_int32(T), _ptr(tokens), _ptr(feat_in),
+                                      _ptr(feat_tgt), _ptr(n_valid), C.c_double(w_ce), _ptr(loss), _ptr(g["fc"]), _ptr(g["wqkv"]),
+                                      _ptr(g["wo"]), _ptr(g["w_gate"]), _ptr(g["w_up"]), _ptr(g["w_down"]), _ptr(g["norm_attn"]),
+                                      _ptr(g["norm_ffn"]))
+        self._check(rc, "orc_draft_train")
+        return loss, g
+
+    def adamw(self, p, g, m, v, lr, b1, b2, eps, wd, step):
+        """In place on p, m, v (arrays of the oracle's real type)."""
+        assert p.dtype == self.real and m.dtype == self.real and v.dtype == self.real
+        g = np.ascontiguousarray(g, dtype=self.real)
+        rc = self.lib.orc_adamw(_ptr(p), _ptr(g), _ptr(m), _ptr(v), C.c_int64(p.size), C.c_double(lr), C.c_double(b1),
+                                C.c_double(b2), C.c_double(eps), C.c_double(wd), C.c_int32(step))
+        self._check(rc, "orc_adamw")
