@@ -311,6 +311,44 @@ int32_t fg_build_tree(const int32_t *cand_tok, const int32_t *cand_parent, const
                       int32_t *sel, void *stream);
 
 /*
+ * Online draft learning (Sec. 4.2 "Draft Model Learning with Online Target Feedback"; Alg. 1, the draft training phase):
+ * the draft head is trained on what the generation phase cached -- the tokens the target emitted and the target's
+ * features.  Training computes in fp32 on fp32 master parameters, whatever type the generation path runs in; the
+ * updated head reaches it by casting and re-packing the matrices (fg_pack_weight) into a new draft model.
+ *
+ * fg_draft_params: the head's parameters, row-major [out, in] fp32 device arrays the caller owns: fc [d, 2d],
+ * wqkv [(Hq + 2 Hkv) hd, d] (q rows, k rows, v rows), wo [d, Hq hd], w_gate / w_up [F, d], w_down [d, F], the two norm
+ * gains [d].  The same struct describes gradients and the optimiser's two moment sets.
+ *
+ * fg_draft_train_grad: B sequences, each one teacher-forced chain of T entries from an empty draft cache (causal
+ * attention inside the chain, positions 0 .. T-1); entry t pairs tokens[b][t] (token t + 1) with feat_in[b][t] (the
+ * target's feature t) and is trained towards feat_tgt[b][t] (the target's feature t + 1); entries t >= n_valid[b] are
+ * padding.  With h the head's output, per valid entry
+ *   L = mean_e smooth_l1(h[e] - feat_tgt[e]) + w_ce * CE(softmax(lm_head . feat_tgt), softmax(lm_head . h)),
+ * averaged over the valid entries (the paper names no loss: this is the one of the draft-head pre-training it follows,
+ * Sec. 5.1).  Outputs: loss (device, 2 floats: the regression and the cross-entropy term, unweighted) and the gradient
+ * of the total in `grad`.  embed, lm_head: the target's, fp32 row-major [vocab, d], frozen.  tokens int32 [B, T],
+ * feat_in / feat_tgt fp32 [B, T, d], n_valid int32 [B], all device.  cfg: the draft head's (n_layers must be 1; the dtype
+ * field is ignored).  d, F, Hq hd, vocab multiples of 4; T * 4 bytes of LDS per block (T <= 8192).
+ * workspace: fg_draft_train_workspace_bytes(cfg, B, T).  Deterministic: no atomics, fixed summation orders.
+ *
+ * fg_draft_adamw: one AdamW step on every parameter (decoupled weight decay, bias-corrected moments; step counts
+ * from 1): m = b1 m + (1 - b1) g; v = b2 v + (1 - b2) g^2; p -= lr (m / (1 - b1^step) / (sqrt(v / (1 - b2^step)) + eps)
+ * + weight_decay p).
+ */
+typedef struct {
+    float *fc, *wqkv, *wo, *w_gate, *w_up, *w_down, *norm_attn, *norm_ffn;
+} fg_draft_params;
+int64_t fg_draft_train_workspace_bytes(const fg_model_cfg *cfg, int32_t B, int32_t T);
+int32_t fg_draft_train_grad(const fg_model_cfg *cfg, const float *embed, const float *lm_head, const fg_draft_params *w,
+                            const int32_t *tokens, const float *feat_in, const float *feat_tgt, const int32_t *n_valid,
+                            int32_t B, int32_t T, float w_ce, fg_draft_params *grad, float *loss, void *workspace,
+                            int64_t workspace_bytes, void *stream);
+int32_t fg_draft_adamw(const fg_model_cfg *cfg, fg_draft_params *w, const fg_draft_params *grad, fg_draft_params *m,
+                       fg_draft_params *v, float lr, float beta1, float beta2, float eps, float weight_decay, int32_t step,
+                       void *stream);
+
+/*
  * Kernel-level entry points (unit parity and per-kernel measurement).
  * fg_gemm: out = x . W^T for packed W [n_out, n_in]; x is [M, n_in] row-major in dtype.
  *   epilogue 0: out fp32 [split_k][M][n_out] partial sums (split_k >= 1; 0 lets the library choose and

@@ -21,7 +21,7 @@ EXPORTS = ["fg_last_error", "fg_plan", "fg_packed_bytes", "fg_pack_weight", "fg_
            "fg_workspace_bytes", "fg_workspace_bytes_for", "fg_step_workspace_bytes", "fg_spec_verify", "fg_spec_accept", "fg_kv_compact", "fg_draft_step",
            "fg_draft_frontier", "fg_build_tree", "fg_gemm", "fg_attention", "fg_attention_workspace_bytes",
            "fg_topk_logp", "fg_lm_head_topk", "fg_lm_head_topk_workspace_bytes", "fg_knee", "fg_select_rows", "fg_model_profile",
-           "fg_model_profile_read", "fg_gemm_kernel_name", "fg_spec_accept_static", "fg_probe_read", "fg_probe_copy", "fg_probe_mfma"]
+           "fg_model_profile_read", "fg_gemm_kernel_name", "fg_spec_accept_static", "fg_draft_train_workspace_bytes", "fg_draft_train_grad", "fg_draft_adamw", "fg_probe_read", "fg_probe_copy", "fg_probe_mfma"]
 STATIC_SCRATCH_BYTES = 4 << 20
 
 
@@ -46,6 +46,10 @@ class KvCacheC(C.Structure):
                 ("status", C.c_void_p)] + \
                [(n, C.c_int32) for n in ("n_layers", "n_kv_heads", "head_dim", "dtype", "page_size", "max_pages_per_seq",
                                          "n_pages", "n_slots")]
+
+
+class DraftParamsC(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("fc", "wqkv", "wo", "w_gate", "w_up", "w_down", "norm_attn", "norm_ffn")]
 
 
 class TreeC(C.Structure):
@@ -87,6 +91,13 @@ def lib():
         L.fg_probe_read.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.fg_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p]
         L.fg_probe_mfma.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        L.fg_draft_train_workspace_bytes.restype = C.c_int64
+        L.fg_draft_train_workspace_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int32, C.c_int32]
+        L.fg_draft_train_grad.argtypes = [C.POINTER(ModelCfg), C.c_void_p, C.c_void_p, C.POINTER(DraftParamsC), C.c_void_p, C.c_void_p,
+                                          C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.POINTER(DraftParamsC), C.c_void_p,
+                                          C.c_void_p, C.c_int64, C.c_void_p]
+        L.fg_draft_adamw.argtypes = [C.POINTER(ModelCfg), C.POINTER(DraftParamsC), C.POINTER(DraftParamsC), C.POINTER(DraftParamsC),
+                                     C.POINTER(DraftParamsC)] + [C.c_float] * 5 + [C.c_int32, C.c_void_p]
         L.fg_kv_compact.argtypes = [C.POINTER(KvCacheC), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                     C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
         L.fg_draft_step.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(KvCacheC), C.POINTER(TreeC), C.c_void_p, C.c_void_p,
@@ -489,6 +500,50 @@ def fg_select_rows(src, index):
     dst = torch.empty((index.shape[0],) + tuple(src.shape[1:]), dtype=src.dtype, device=src.device)
     _check(lib().fg_select_rows(_p(src), row_bytes, n_src, _p(index), index.shape[0], _p(dst), _stream()))
     return dst
+
+
+# ---- online draft learning -------------------------------------------------------------------------------------------
+PARAM_NAMES = ("fc", "wqkv", "wo", "w_gate", "w_up", "w_down", "norm_attn", "norm_ffn")
+
+
+def draft_param_shapes(cfg):
+    d, F = cfg["d_model"], cfg["d_ffn"]
+    hq = cfg["n_q_heads"] * cfg["head_dim"]
+    qkvd = (cfg["n_q_heads"] + 2 * cfg["n_kv_heads"]) * cfg["head_dim"]
+    return dict(fc=(d, 2 * d), wqkv=(qkvd, d), wo=(d, hq), w_gate=(F, d), w_up=(F, d), w_down=(d, F), norm_attn=(d,), norm_ffn=(d,))
+
+
+def _params_struct(p):
+    for n in PARAM_NAMES:
+        assert p[n].dtype == torch.float32 and p[n].is_contiguous() and p[n].is_cuda, n
+    return DraftParamsC(*[p[n].data_ptr() for n in PARAM_NAMES])
+
+
+def fg_draft_train_grad(cfg, embed, lm_head, w, tokens, feat_in, feat_tgt, n_valid, w_ce=0.1, grad=None, workspace=None):
+    """Loss terms (device tensor [2]) and gradients (dict of fp32 tensors shaped like `w`) of the draft head's training
+    loss; embed / lm_head: the target's, fp32 row-major on the device."""
+    dev = tokens.device
+    B, T = tokens.shape
+    c = model_cfg_struct(dict(cfg, dtype="fp32"))
+    if grad is None:
+        grad = {n: torch.empty(s, dtype=torch.float32, device=dev) for n, s in draft_param_shapes(cfg).items()}
+    if workspace is None:
+        workspace = torch.empty(lib().fg_draft_train_workspace_bytes(C.byref(c), B, T), dtype=torch.uint8, device=dev)
+    loss = torch.empty(2, dtype=torch.float32, device=dev)
+    ws, gs = _params_struct(w), _params_struct(grad)
+    for t in (embed, lm_head, feat_in, feat_tgt):
+        assert t.dtype == torch.float32 and t.is_contiguous()
+    _check(lib().fg_draft_train_grad(C.byref(c), _p(embed), _p(lm_head), C.byref(ws), _p(_dev_i32(tokens, dev)), _p(feat_in), _p(feat_tgt),
+                                     _p(_dev_i32(n_valid, dev)), B, T, w_ce, C.byref(gs), _p(loss), _p(workspace), workspace.numel(),
+                                     _stream()))
+    return loss, grad
+
+
+def fg_draft_adamw(cfg, w, grad, m, v, lr, step, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01):
+    c = model_cfg_struct(dict(cfg, dtype="fp32"))
+    ws, gs, ms, vs = (_params_struct(x) for x in (w, grad, m, v))
+    _check(lib().fg_draft_adamw(C.byref(c), C.byref(ws), C.byref(gs), C.byref(ms), C.byref(vs), lr, beta1, beta2, eps, weight_decay,
+                                step, _stream()))
 
 
 # ---- stage timing ------------------------------------------------------------------------------------------------

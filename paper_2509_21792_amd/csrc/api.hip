@@ -61,6 +61,12 @@ int32_t launch_probe_read(const void *src, int64_t bytes, int nontemporal, int b
 int32_t launch_probe_copy(const void *src, void *dst, int64_t bytes, int blocks, hipStream_t st);
 int32_t launch_probe_mfma(int32_t dtype, int iters, int random, int blocks, void *sink, hipStream_t st);
 const char *gemm_mfma_kernel_name(int M, int N, int K, int epilogue);
+int64_t draft_train_ws_bytes(const fg_model_cfg &c, int B, int T);
+int32_t launch_draft_train_grad(const fg_model_cfg &c, const float *embed, const float *lm_head, const fg_draft_params *w,
+                                const int32_t *tokens, const float *feat_in, const float *feat_tgt, const int32_t *n_valid, int B,
+                                int T, float w_ce, fg_draft_params *g, float *loss, void *ws, int64_t ws_bytes, hipStream_t st);
+int32_t launch_adamw(float *p, const float *g, float *m, float *v, int64_t n, float lr, float b1, float b2, float eps, float wd,
+                     int step, hipStream_t st);
 
 }  // namespace fg
 
@@ -782,6 +788,67 @@ int32_t fg_topk_logp(const float *logits, int32_t M, int32_t vocab, int32_t K, i
     if (M == 0) return FG_OK;
     if (!logits || !tok || !logp) return fail(FG_ERR_INVALID_ARG, "fg_topk_logp: null pointer");
     return launch_topk_logp(logits, M, vocab, K, tok, logp, (hipStream_t)stream);
+}
+
+static int32_t check_train_cfg(const fg_model_cfg *c)
+{
+    if (!c) return fail(FG_ERR_INVALID_ARG, "draft training: configuration is NULL");
+    if (c->n_layers != 1) return fail(FG_ERR_SHAPE, "draft training: the head has one decoder layer (got %d)", c->n_layers);
+    if (c->d_model < 4 || c->d_ffn < 4 || c->vocab < 4 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->n_q_heads % c->n_kv_heads ||
+        c->head_dim < 2 || c->head_dim % 2)
+        return fail(FG_ERR_INVALID_ARG, "draft training: bad model sizes");
+    if (c->d_model % 4 || c->d_ffn % 4 || c->vocab % 4 || (c->n_q_heads * c->head_dim) % 4 || (c->n_kv_heads * c->head_dim) % 4)
+        return fail(FG_ERR_SHAPE, "draft training: d_model, d_ffn, vocab, Hq*hd and Hkv*hd must be multiples of 4");
+    return FG_OK;
+}
+
+static bool params_ok(const fg_draft_params *p)
+{
+    return p && p->fc && p->wqkv && p->wo && p->w_gate && p->w_up && p->w_down && p->norm_attn && p->norm_ffn;
+}
+
+int64_t fg_draft_train_workspace_bytes(const fg_model_cfg *cfg, int32_t B, int32_t T)
+{
+    if (check_train_cfg(cfg) || B < 1 || T < 1) return 0;
+    return draft_train_ws_bytes(*cfg, B, T);
+}
+
+int32_t fg_draft_train_grad(const fg_model_cfg *cfg, const float *embed, const float *lm_head, const fg_draft_params *w,
+                            const int32_t *tokens, const float *feat_in, const float *feat_tgt, const int32_t *n_valid, int32_t B,
+                            int32_t T, float w_ce, fg_draft_params *grad, float *loss, void *workspace, int64_t workspace_bytes,
+                            void *stream)
+{
+    int32_t rc;
+    if ((rc = check_train_cfg(cfg))) return rc;
+    if (B < 0 || T < 0) return fail(FG_ERR_INVALID_ARG, "fg_draft_train_grad: negative B / T");
+    if (B == 0 || T == 0) return FG_OK;
+    if (T > 8192) return fail(FG_ERR_CAPACITY, "fg_draft_train_grad: chains of at most 8192 entries (got %d)", T);
+    if ((int64_t)B * T * (int64_t)cfg->vocab >= (1LL << 31) * 4) return fail(FG_ERR_CAPACITY, "fg_draft_train_grad: B * T * vocab too large");
+    if (!embed || !lm_head || !params_ok(w) || !params_ok(grad) || !tokens || !feat_in || !feat_tgt || !n_valid || !loss || !workspace)
+        return fail(FG_ERR_INVALID_ARG, "fg_draft_train_grad: NULL pointer");
+    return launch_draft_train_grad(*cfg, embed, lm_head, w, tokens, feat_in, feat_tgt, n_valid, B, T, w_ce, grad, loss, workspace,
+                                   workspace_bytes, (hipStream_t)stream);
+}
+
+int32_t fg_draft_adamw(const fg_model_cfg *cfg, fg_draft_params *w, const fg_draft_params *grad, fg_draft_params *m,
+                       fg_draft_params *v, float lr, float beta1, float beta2, float eps, float weight_decay, int32_t step,
+                       void *stream)
+{
+    int32_t rc;
+    if ((rc = check_train_cfg(cfg))) return rc;
+    if (!params_ok(w) || !params_ok(grad) || !params_ok(m) || !params_ok(v)) return fail(FG_ERR_INVALID_ARG, "fg_draft_adamw: NULL pointer");
+    if (step < 1 || !(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps > 0.f))
+        return fail(FG_ERR_INVALID_ARG, "fg_draft_adamw: step >= 1, betas in [0, 1), eps > 0");
+    const int64_t d = cfg->d_model, F = cfg->d_ffn, hq = (int64_t)cfg->n_q_heads * cfg->head_dim;
+    const int64_t qkvd = (int64_t)(cfg->n_q_heads + 2 * cfg->n_kv_heads) * cfg->head_dim;
+    const int64_t sizes[8] = {d * 2 * d, qkvd * d, d * hq, F * d, F * d, d * F, d, d};
+    float *pw[8] = {w->fc, w->wqkv, w->wo, w->w_gate, w->w_up, w->w_down, w->norm_attn, w->norm_ffn};
+    const float *pg[8] = {grad->fc, grad->wqkv, grad->wo, grad->w_gate, grad->w_up, grad->w_down, grad->norm_attn, grad->norm_ffn};
+    float *pm[8] = {m->fc, m->wqkv, m->wo, m->w_gate, m->w_up, m->w_down, m->norm_attn, m->norm_ffn};
+    float *pv[8] = {v->fc, v->wqkv, v->wo, v->w_gate, v->w_up, v->w_down, v->norm_attn, v->norm_ffn};
+    for (int i = 0; i < 8; i++)
+        if ((rc = launch_adamw(pw[i], pg[i], pm[i], pv[i], sizes[i], lr, beta1, beta2, eps, weight_decay, step, (hipStream_t)stream))) return rc;
+    return FG_OK;
 }
 
 int64_t fg_lm_head_topk_workspace_bytes(int32_t M, int32_t vocab, int32_t K)

@@ -1,0 +1,464 @@
+// Online draft learning (Sec. 4.2 "Draft Model Learning with Online Target Feedback"; Alg. 1, the draft training
+// phase): loss and gradients of the one-layer draft head on the tokens and hidden states the generation phase cached,
+// and the AdamW update.  Everything here computes in fp32 on fp32 master parameters; the generation path gets the
+// updated head by re-packing them (fg_pack_weight).  The phase is a few per cent of a training iteration (Sec. 4.2), so
+// these kernels are plain: a register-tiled fp32 GEMM in the three operand orders a backward pass needs, and row-wise
+// kernels for norm, RoPE, causal attention, SwiGLU and the loss, each with its backward.
+#include "fg_common.h"
+
+namespace fg {
+
+// ---- fp32 GEMM: C[m, n] = sum_k A(m, k) B(k, n) (+ add[m, n]) ----------------------------------------------------
+// A(m, k) sits at A[m * lda + k] (AK: k contiguous) or A[k * lda + m] (m contiguous); B(k, n) at B[n * ldb + k] (BK: k
+// contiguous) or B[k * ldb + n] (n contiguous).  128 x 128 tile, 256 threads, 8 x 8 outputs per thread, 16-wide k steps
+// through LDS.  Contiguous dimensions and leading dimensions are multiples of 4 (checked by the launcher), so global
+// loads are float4 with whole-vector guards.
+constexpr int SG_BM = 128, SG_BN = 128, SG_BK = 16;
+
+template <bool AK, bool BK>
+__global__ __launch_bounds__(256) void sgemm_kernel(const float *__restrict__ A, const float *__restrict__ Bm, float *__restrict__ C,
+                                                    const float *__restrict__ add, int M, int N, int K, int lda, int ldb, int ldc)
+{
+    __shared__ float As[SG_BK][SG_BM + 4], Bs[SG_BK][SG_BN + 4];
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int m0 = blockIdx.y * SG_BM, n0 = blockIdx.x * SG_BN;
+    float acc[8][8];
+#pragma unroll
+    for (int i = 0; i < 8; i++)
+#pragma unroll
+        for (int j = 0; j < 8; j++) acc[i][j] = 0.f;
+    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int k0 = 0; k0 < K; k0 += SG_BK) {
+        // stage the two tiles (2048 elements each: two float4 per thread)
+#pragma unroll
+        for (int it = 0; it < 2; it++) {
+            if (AK) {   // vectors along k: row = index / 4, k quad = index % 4
+                const int idx = tid + it * 256, r = idx >> 2, kq = (idx & 3) * 4;
+                const int m = m0 + r, k = k0 + kq;
+                const float4 v = (m < M && k < K) ? *reinterpret_cast<const float4 *>(A + (size_t)m * lda + k) : zero4;
+                As[kq][r] = v.x; As[kq + 1][r] = v.y; As[kq + 2][r] = v.z; As[kq + 3][r] = v.w;
+            } else {    // vectors along m: k = index / 32, m quad = index % 32
+                const int idx = tid + it * 256, kk = idx >> 5, mq = (idx & 31) * 4;
+                const int m = m0 + mq, k = k0 + kk;
+                const float4 v = (m < M && k < K) ? *reinterpret_cast<const float4 *>(A + (size_t)k * lda + m) : zero4;
+                *reinterpret_cast<float4 *>(&As[kk][mq]) = v;
+            }
+            if (BK) {
+                const int idx = tid + it * 256, r = idx >> 2, kq = (idx & 3) * 4;
+                const int n = n0 + r, k = k0 + kq;
+                const float4 v = (n < N && k < K) ? *reinterpret_cast<const float4 *>(Bm + (size_t)n * ldb + k) : zero4;
+                Bs[kq][r] = v.x; Bs[kq + 1][r] = v.y; Bs[kq + 2][r] = v.z; Bs[kq + 3][r] = v.w;
+            } else {
+                const int idx = tid + it * 256, kk = idx >> 5, nq = (idx & 31) * 4;
+                const int n = n0 + nq, k = k0 + kk;
+                const float4 v = (n < N && k < K) ? *reinterpret_cast<const float4 *>(Bm + (size_t)k * ldb + n) : zero4;
+                *reinterpret_cast<float4 *>(&Bs[kk][nq]) = v;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < SG_BK; kk++) {
+            const float4 a0 = *reinterpret_cast<const float4 *>(&As[kk][ty * 8]), a1 = *reinterpret_cast<const float4 *>(&As[kk][ty * 8 + 4]);
+            const float4 b0 = *reinterpret_cast<const float4 *>(&Bs[kk][tx * 8]), b1 = *reinterpret_cast<const float4 *>(&Bs[kk][tx * 8 + 4]);
+            const float a[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+            const float b[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+            for (int i = 0; i < 8; i++)
+#pragma unroll
+                for (int j = 0; j < 8; j++) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+        const int m = m0 + ty * 8 + i;
+        if (m >= M) continue;
+#pragma unroll
+        for (int jq = 0; jq < 2; jq++) {
+            const int n = n0 + tx * 8 + jq * 4;
+            if (n >= N) continue;      // N is a multiple of 4: a quad is inside or outside as a whole
+            float4 v = make_float4(acc[i][jq * 4], acc[i][jq * 4 + 1], acc[i][jq * 4 + 2], acc[i][jq * 4 + 3]);
+            if (add) {
+                const float4 o = *reinterpret_cast<const float4 *>(add + (size_t)m * ldc + n);
+                v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+            }
+            *reinterpret_cast<float4 *>(C + (size_t)m * ldc + n) = v;
+        }
+    }
+}
+
+// op 0: C = A[M,K] . B[N,K]^T (forward);  1: C = A[M,K] . B[K,N] (input gradient);  2: C = A[K,M]^T . B[K,N] (weight gradient)
+static int32_t sgemm(int op, const float *A, const float *B, float *C, const float *add, int M, int N, int K, hipStream_t st)
+{
+    if (M <= 0 || N <= 0 || K <= 0) return FG_OK;
+    if (N % 4 || (op != 2 && K % 4) || (op == 2 && M % 4)) return fail(FG_ERR_SHAPE, "training GEMM needs dimensions in multiples of 4 (%d, %d, %d)", M, N, K);
+    const dim3 grid((N + SG_BN - 1) / SG_BN, (M + SG_BM - 1) / SG_BM);
+    if (op == 0) hipLaunchKernelGGL((sgemm_kernel<true, true>), grid, dim3(256), 0, st, A, B, C, add, M, N, K, K, K, N);
+    else if (op == 1) hipLaunchKernelGGL((sgemm_kernel<true, false>), grid, dim3(256), 0, st, A, B, C, add, M, N, K, K, N, N);
+    else hipLaunchKernelGGL((sgemm_kernel<false, false>), grid, dim3(256), 0, st, A, B, C, add, M, N, K, M, N, N);
+    FG_LAUNCH_CHECK("sgemm");
+    return FG_OK;
+}
+
+// ---- row-wise kernels ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ float block_sum256(float v, float *red)
+{
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return red[0] + red[1] + red[2] + red[3];
+}
+__device__ __forceinline__ float block_max256(float v, float *red)
+{
+    v = wave_max(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}
+
+// cat[r] = embed[token r] ++ feat[r]
+__global__ void train_concat_kernel(const float *embed, const int32_t *tokens, int vocab, const float *feat, float *cat, int d)
+{
+    const int r = blockIdx.x, tok = min(max(tokens[r], 0), vocab - 1);
+    for (int c = threadIdx.x; c < d; c += blockDim.x) {
+        cat[(size_t)r * 2 * d + c] = embed[(size_t)tok * d + c];
+        cat[(size_t)r * 2 * d + d + c] = feat[(size_t)r * d + c];
+    }
+}
+
+// y = x * inv * g, inv = (mean(x^2) + eps)^(-1/2) kept per row for the backward pass
+__global__ __launch_bounds__(256) void rms_fwd_kernel(const float *x, const float *g, float *y, float *inv_out, int d, float eps)
+{
+    __shared__ float red[4];
+    const int r = blockIdx.x;
+    float ss = 0.f;
+    for (int c = threadIdx.x; c < d; c += 256) { const float v = x[(size_t)r * d + c]; ss += v * v; }
+    ss = block_sum256(ss, red);
+    const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+    if (threadIdx.x == 0) inv_out[r] = inv;
+    for (int c = threadIdx.x; c < d; c += 256) y[(size_t)r * d + c] = x[(size_t)r * d + c] * inv * g[c];
+}
+
+// dx = add + inv * (g . dy) - x * inv^3 * sum_k (g . dy)_k x_k / d
+__global__ __launch_bounds__(256) void rms_bwd_kernel(const float *dy, const float *x, const float *g, const float *inv_in,
+                                                      const float *add, float *dx, int d)
+{
+    __shared__ float red[4];
+    const int r = blockIdx.x;
+    const float inv = inv_in[r];
+    float dot = 0.f;
+    for (int c = threadIdx.x; c < d; c += 256) dot += g[c] * dy[(size_t)r * d + c] * x[(size_t)r * d + c];
+    dot = block_sum256(dot, red);
+    const float k3 = inv * inv * inv * dot / (float)d;
+    for (int c = threadIdx.x; c < d; c += 256) {
+        const size_t at = (size_t)r * d + c;
+        dx[at] = add[at] + inv * g[c] * dy[at] - x[at] * k3;
+    }
+}
+
+// dg[c] = sum over rows of dy * x * inv (a thread owns a column and walks the rows in order: no atomics)
+__global__ void rms_dgain_kernel(const float *dy, const float *x, const float *inv, float *dg, int M, int d)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= d) return;
+    float s = 0.f;
+    for (int r = 0; r < M; r++) s += dy[(size_t)r * d + c] * x[(size_t)r * d + c] * inv[r];
+    dg[c] = s;
+}
+
+// rotate-half RoPE of the q and k heads of qkv [M, qkvd] in place at position row % T; dir = +1 forward, -1 the
+// transpose (the backward pass).  Angles in double, as the table of the generation path is built.
+__global__ void train_rope_kernel(float *qkv, int T, int n_rot_heads, int hd, int qkvd, double theta, int dir)
+{
+    const int r = blockIdx.x, half = hd >> 1, pos = r % T;
+    for (int w = threadIdx.x; w < n_rot_heads * half; w += blockDim.x) {
+        const int head = w / half, i = w % half;
+        const double ang = (double)pos * pow(theta, -2.0 * (double)i / (double)hd);
+        const float c = (float)cos(ang), s = (float)sin(ang) * (float)dir;
+        float *p = qkv + (size_t)r * qkvd + (size_t)head * hd;
+        const float a = p[i], b = p[i + half];
+        p[i] = a * c - b * s;
+        p[i + half] = b * c + a * s;
+    }
+}
+
+// causal attention inside each chain: one block per (sequence, query head, query position).  P [B, Hq, T, T] is kept.
+__global__ __launch_bounds__(256) void train_attn_fwd_kernel(const float *qkv, float *P, float *att, int T, int Hq, int Hkv, int hd,
+                                                             int qkvd, float scale)
+{
+    extern __shared__ float sc[];   // T scores
+    __shared__ float red[4];
+    const int t = blockIdx.x, hq = blockIdx.y, b = blockIdx.z, hk = hq / (Hq / Hkv);
+    const float *q = qkv + (size_t)(b * T + t) * qkvd + (size_t)hq * hd;
+    float mx = -INFINITY;
+    for (int s = threadIdx.x; s <= t; s += 256) {
+        const float *k = qkv + (size_t)(b * T + s) * qkvd + (size_t)(Hq + hk) * hd;
+        float a = 0.f;
+        for (int e = 0; e < hd; e++) a += q[e] * k[e];
+        a *= scale;
+        sc[s] = a;
+        mx = fmaxf(mx, a);
+    }
+    mx = block_max256(mx, red);
+    float den = 0.f;
+    for (int s = threadIdx.x; s <= t; s += 256) { const float e = expf(sc[s] - mx); sc[s] = e; den += e; }
+    den = block_sum256(den, red);
+    float *prow = P + (((size_t)b * Hq + hq) * T + t) * T;
+    for (int s = threadIdx.x; s < T; s += 256) {
+        const float p = s <= t ? sc[s] / den : 0.f;
+        prow[s] = p;
+        if (s <= t) sc[s] = p;
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < hd; e += 256) {
+        float o = 0.f;
+        for (int s = 0; s <= t; s++) o += sc[s] * qkv[(size_t)(b * T + s) * qkvd + (size_t)(Hq + Hkv + hk) * hd + e];
+        att[(size_t)(b * T + t) * Hq * hd + (size_t)hq * hd + e] = o;
+    }
+}
+
+// dS = P . (dP - sum_s dP P) * scale (kept, [B, Hq, T, T]) and dq; one block per (sequence, query head, query position)
+__global__ __launch_bounds__(256) void train_attn_bwd_q_kernel(const float *qkv, const float *P, const float *datt, float *dS,
+                                                               float *dqkv, int T, int Hq, int Hkv, int hd, int qkvd, float scale)
+{
+    extern __shared__ float ds[];   // T entries
+    __shared__ float red[4];
+    const int t = blockIdx.x, hq = blockIdx.y, b = blockIdx.z, hk = hq / (Hq / Hkv);
+    const float *dout = datt + (size_t)(b * T + t) * Hq * hd + (size_t)hq * hd;
+    const float *prow = P + (((size_t)b * Hq + hq) * T + t) * T;
+    float dot = 0.f;
+    for (int s = threadIdx.x; s <= t; s += 256) {
+        const float *v = qkv + (size_t)(b * T + s) * qkvd + (size_t)(Hq + Hkv + hk) * hd;
+        float dp = 0.f;
+        for (int e = 0; e < hd; e++) dp += dout[e] * v[e];
+        ds[s] = dp;
+        dot += dp * prow[s];
+    }
+    dot = block_sum256(dot, red);
+    float *dsrow = dS + (((size_t)b * Hq + hq) * T + t) * T;
+    for (int s = threadIdx.x; s < T; s += 256) {
+        const float g = s <= t ? prow[s] * (ds[s] - dot) * scale : 0.f;
+        dsrow[s] = g;
+        if (s <= t) ds[s] = g;
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < hd; e += 256) {
+        float a = 0.f;
+        for (int s = 0; s <= t; s++) a += ds[s] * qkv[(size_t)(b * T + s) * qkvd + (size_t)(Hq + hk) * hd + e];
+        dqkv[(size_t)(b * T + t) * qkvd + (size_t)hq * hd + e] = a;
+    }
+}
+
+// dk[s] = sum over the kv head's query heads and t >= s of dS[t, s] q[t];  dv[s] = the same sum of P[t, s] dout[t];
+// one block per (sequence, kv head, key position), a thread per head dim: fixed summation order, no atomics
+__global__ void train_attn_bwd_kv_kernel(const float *qkv, const float *P, const float *dS, const float *datt, float *dqkv, int T,
+                                         int Hq, int Hkv, int hd, int qkvd)
+{
+    const int s = blockIdx.x, hk = blockIdx.y, b = blockIdx.z, G = Hq / Hkv;
+    for (int e = threadIdx.x; e < hd; e += blockDim.x) {
+        float dk = 0.f, dv = 0.f;
+        for (int g = 0; g < G; g++) {
+            const int hq = hk * G + g;
+            for (int t = s; t < T; t++) {
+                const size_t at = (((size_t)b * Hq + hq) * T + t) * T + s;
+                dk += dS[at] * qkv[(size_t)(b * T + t) * qkvd + (size_t)hq * hd + e];
+                dv += P[at] * datt[(size_t)(b * T + t) * Hq * hd + (size_t)hq * hd + e];
+            }
+        }
+        dqkv[(size_t)(b * T + s) * qkvd + (size_t)(Hq + hk) * hd + e] = dk;
+        dqkv[(size_t)(b * T + s) * qkvd + (size_t)(Hq + Hkv + hk) * hd + e] = dv;
+    }
+}
+
+__global__ void train_swiglu_fwd_kernel(const float *gate, const float *up, float *act, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) { const float g = gate[i]; act[i] = g / (1.f + expf(-g)) * up[i]; }
+}
+
+__global__ void train_swiglu_bwd_kernel(const float *dact, const float *gate, const float *up, float *dgate, float *dup, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const float g = gate[i], sg = 1.f / (1.f + expf(-g));
+    dup[i] = dact[i] * g * sg;
+    dgate[i] = dact[i] * up[i] * (sg + g * sg * (1.f - sg));
+}
+
+// Per row: the regression term and its gradient, the cross-entropy term between softmax(zt) and softmax(z), and the
+// gradient of the total with respect to z, written over z.  Rows past n_valid get zero gradients and no loss.
+__global__ __launch_bounds__(256) void train_loss_kernel(const float *h2, const float *feat_tgt, float *z, const float *zt,
+                                                         const int32_t *n_valid, const int32_t *n_tot_dev, int T, int d, int V,
+                                                         float w_ce, float *dh2, float *row_loss)
+{
+    __shared__ float red[4];
+    const int r = blockIdx.x, b = r / T, t = r % T;
+    float *zr = z + (size_t)r * V;
+    const float *ztr = zt + (size_t)r * V;
+    if (t >= n_valid[b]) {
+        for (int v = threadIdx.x; v < V; v += 256) zr[v] = 0.f;
+        for (int e = threadIdx.x; e < d; e += 256) dh2[(size_t)r * d + e] = 0.f;
+        if (threadIdx.x == 0) { row_loss[2 * r] = 0.f; row_loss[2 * r + 1] = 0.f; }
+        return;
+    }
+    const float n_tot = (float)n_tot_dev[0];
+    float reg = 0.f;
+    for (int e = threadIdx.x; e < d; e += 256) {
+        const float df = h2[(size_t)r * d + e] - feat_tgt[(size_t)r * d + e], ad = fabsf(df);
+        reg += ad < 1.f ? 0.5f * df * df : ad - 0.5f;
+        dh2[(size_t)r * d + e] = (ad < 1.f ? df : (df < 0.f ? -1.f : 1.f)) / (float)d / n_tot;
+    }
+    reg = block_sum256(reg, red) / (float)d;
+    float mq = -INFINITY, mp = -INFINITY;
+    for (int v = threadIdx.x; v < V; v += 256) { mq = fmaxf(mq, zr[v]); mp = fmaxf(mp, ztr[v]); }
+    mq = block_max256(mq, red);
+    mp = block_max256(mp, red);
+    float sq = 0.f, sp = 0.f;
+    for (int v = threadIdx.x; v < V; v += 256) { sq += expf(zr[v] - mq); sp += expf(ztr[v] - mp); }
+    sq = block_sum256(sq, red);
+    sp = block_sum256(sp, red);
+    const float lq = mq + logf(sq), lp = mp + logf(sp);
+    float ce = 0.f;
+    for (int v = threadIdx.x; v < V; v += 256) {
+        const float pv = expf(ztr[v] - lp), zq = zr[v], qv = expf(zq - lq);
+        ce -= pv * (zq - lq);
+        zr[v] = w_ce * (qv - pv) / n_tot;
+    }
+    ce = block_sum256(ce, red);
+    if (threadIdx.x == 0) { row_loss[2 * r] = reg; row_loss[2 * r + 1] = ce; }
+}
+
+// n_tot = sum of n_valid (one thread: B is small); later: loss = sum of the row terms in row order / n_tot
+__global__ void train_count_kernel(const int32_t *n_valid, int B, int T, int32_t *n_tot)
+{
+    int s = 0;
+    for (int b = 0; b < B; b++) s += min(max(n_valid[b], 0), T);
+    n_tot[0] = max(s, 1);
+}
+__global__ void train_loss_reduce_kernel(const float *row_loss, int M, const int32_t *n_tot, float *loss)
+{
+    __shared__ float red[4];
+    float a = 0.f, c = 0.f;
+    for (int r = threadIdx.x; r < M; r += 256) { a += row_loss[2 * r]; c += row_loss[2 * r + 1]; }
+    a = block_sum256(a, red);
+    c = block_sum256(c, red);
+    if (threadIdx.x == 0) { loss[0] = a / (float)n_tot[0]; loss[1] = c / (float)n_tot[0]; }
+}
+
+__global__ void adamw_kernel(float *p, const float *g, float *m, float *v, size_t n, float lr, float b1, float b2, float eps,
+                             float wd, float c1, float c2)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const float gi = g[i];
+    const float mi = b1 * m[i] + (1.f - b1) * gi, vi = b2 * v[i] + (1.f - b2) * gi * gi;
+    m[i] = mi;
+    v[i] = vi;
+    p[i] -= lr * ((mi / c1) / (sqrtf(vi / c2) + eps) + wd * p[i]);
+}
+
+// ---- the step ----------------------------------------------------------------------------------------------------------
+struct TrainWs {
+    float *cat, *h0, *a1, *inv1, *qkv, *P, *dS, *att, *h1, *a2, *inv2, *gate, *up, *act, *h2, *z, *zt, *dh2, *dact, *dgate, *dup,
+        *da, *dh1, *datt, *dqkv, *dx, *row_loss;
+    int32_t *n_tot;
+};
+
+static int64_t carve_train(const fg_model_cfg &c, int B, int T, void *base, int64_t cap, TrainWs *w)
+{
+    const int64_t M = (int64_t)B * T, d = c.d_model, F = c.d_ffn, V = c.vocab, hq = (int64_t)c.n_q_heads * c.head_dim;
+    const int64_t qkvd = (int64_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+    int64_t off = 0;
+    auto take = [&](int64_t n) {
+        off = align_up(off, 256);
+        float *p = (float *)((char *)base + off);
+        off += n * 4;
+        return p;
+    };
+    TrainWs s;
+    s.cat = take(M * 2 * d); s.h0 = take(M * d); s.a1 = take(M * d); s.inv1 = take(M); s.qkv = take(M * qkvd);
+    s.P = take((int64_t)B * c.n_q_heads * T * T); s.dS = take((int64_t)B * c.n_q_heads * T * T); s.att = take(M * hq);
+    s.h1 = take(M * d); s.a2 = take(M * d); s.inv2 = take(M); s.gate = take(M * F); s.up = take(M * F); s.act = take(M * F);
+    s.h2 = take(M * d); s.z = take(M * V); s.zt = take(M * V); s.dh2 = take(M * d); s.dact = take(M * F); s.dgate = take(M * F);
+    s.dup = take(M * F); s.da = take(M * d); s.dh1 = take(M * d); s.datt = take(M * hq); s.dqkv = take(M * qkvd); s.dx = take(M * d);
+    s.row_loss = take(M * 2); s.n_tot = (int32_t *)take(64);
+    if (w) *w = s;
+    if (base && off > cap) return -1;
+    return align_up(off, 256);
+}
+
+int64_t draft_train_ws_bytes(const fg_model_cfg &c, int B, int T) { return carve_train(c, B, T, nullptr, 0, nullptr); }
+
+int32_t launch_draft_train_grad(const fg_model_cfg &c, const float *embed, const float *lm_head, const fg_draft_params *w,
+                                const int32_t *tokens, const float *feat_in, const float *feat_tgt, const int32_t *n_valid, int B,
+                                int T, float w_ce, fg_draft_params *g, float *loss, void *ws, int64_t ws_bytes, hipStream_t st)
+{
+    TrainWs s;
+    if (carve_train(c, B, T, ws, ws_bytes, &s) < 0) return fail(FG_ERR_CAPACITY, "fg_draft_train_grad: workspace too small");
+    const int M = B * T, d = c.d_model, F = c.d_ffn, V = c.vocab, Hq = c.n_q_heads, Hkv = c.n_kv_heads, hd = c.head_dim;
+    const int hq = Hq * hd, qkvd = (Hq + 2 * Hkv) * hd;
+    const float scale = 1.0f / sqrtf((float)hd);
+    const size_t lds = (size_t)T * sizeof(float);
+    int32_t rc;
+    // forward
+    hipLaunchKernelGGL(train_count_kernel, dim3(1), dim3(1), 0, st, n_valid, B, T, s.n_tot);
+    hipLaunchKernelGGL(train_concat_kernel, dim3(M), dim3(256), 0, st, embed, tokens, V, feat_in, s.cat, d);
+    if ((rc = sgemm(0, s.cat, w->fc, s.h0, nullptr, M, d, 2 * d, st))) return rc;
+    hipLaunchKernelGGL(rms_fwd_kernel, dim3(M), dim3(256), 0, st, s.h0, w->norm_attn, s.a1, s.inv1, d, c.rms_eps);
+    if ((rc = sgemm(0, s.a1, w->wqkv, s.qkv, nullptr, M, qkvd, d, st))) return rc;
+    hipLaunchKernelGGL(train_rope_kernel, dim3(M), dim3(256), 0, st, s.qkv, T, Hq + Hkv, hd, qkvd, (double)c.rope_theta, 1);
+    hipLaunchKernelGGL(train_attn_fwd_kernel, dim3(T, Hq, B), dim3(256), lds, st, s.qkv, s.P, s.att, T, Hq, Hkv, hd, qkvd, scale);
+    if ((rc = sgemm(0, s.att, w->wo, s.h1, s.h0, M, d, hq, st))) return rc;
+    hipLaunchKernelGGL(rms_fwd_kernel, dim3(M), dim3(256), 0, st, s.h1, w->norm_ffn, s.a2, s.inv2, d, c.rms_eps);
+    if ((rc = sgemm(0, s.a2, w->w_gate, s.gate, nullptr, M, F, d, st))) return rc;
+    if ((rc = sgemm(0, s.a2, w->w_up, s.up, nullptr, M, F, d, st))) return rc;
+    const size_t nf = (size_t)M * F;
+    hipLaunchKernelGGL(train_swiglu_fwd_kernel, dim3((unsigned)((nf + 255) / 256)), dim3(256), 0, st, s.gate, s.up, s.act, nf);
+    if ((rc = sgemm(0, s.act, w->w_down, s.h2, s.h1, M, d, F, st))) return rc;
+    if ((rc = sgemm(0, s.h2, lm_head, s.z, nullptr, M, V, d, st))) return rc;
+    if ((rc = sgemm(0, feat_tgt, lm_head, s.zt, nullptr, M, V, d, st))) return rc;
+    // loss, d loss / d z (over z) and the regression part of d loss / d h2
+    hipLaunchKernelGGL(train_loss_kernel, dim3(M), dim3(256), 0, st, s.h2, feat_tgt, s.z, s.zt, n_valid, s.n_tot, T, d, V, w_ce, s.dh2,
+                       s.row_loss);
+    hipLaunchKernelGGL(train_loss_reduce_kernel, dim3(1), dim3(256), 0, st, s.row_loss, M, s.n_tot, loss);
+    // backward
+    if ((rc = sgemm(1, s.z, lm_head, s.dh2, s.dh2, M, d, V, st))) return rc;              // through the frozen LM head
+    if ((rc = sgemm(2, s.dh2, s.act, g->w_down, nullptr, d, F, M, st))) return rc;
+    if ((rc = sgemm(1, s.dh2, w->w_down, s.dact, nullptr, M, F, d, st))) return rc;
+    hipLaunchKernelGGL(train_swiglu_bwd_kernel, dim3((unsigned)((nf + 255) / 256)), dim3(256), 0, st, s.dact, s.gate, s.up, s.dgate,
+                       s.dup, nf);
+    if ((rc = sgemm(2, s.dgate, s.a2, g->w_gate, nullptr, F, d, M, st))) return rc;
+    if ((rc = sgemm(2, s.dup, s.a2, g->w_up, nullptr, F, d, M, st))) return rc;
+    if ((rc = sgemm(1, s.dgate, w->w_gate, s.da, nullptr, M, d, F, st))) return rc;
+    if ((rc = sgemm(1, s.dup, w->w_up, s.da, s.da, M, d, F, st))) return rc;
+    hipLaunchKernelGGL(rms_dgain_kernel, dim3((d + 255) / 256), dim3(256), 0, st, s.da, s.h1, s.inv2, g->norm_ffn, M, d);
+    hipLaunchKernelGGL(rms_bwd_kernel, dim3(M), dim3(256), 0, st, s.da, s.h1, w->norm_ffn, s.inv2, s.dh2, s.dh1, d);
+    if ((rc = sgemm(2, s.dh1, s.att, g->wo, nullptr, d, hq, M, st))) return rc;
+    if ((rc = sgemm(1, s.dh1, w->wo, s.datt, nullptr, M, hq, d, st))) return rc;
+    hipLaunchKernelGGL(train_attn_bwd_q_kernel, dim3(T, Hq, B), dim3(256), lds, st, s.qkv, s.P, s.datt, s.dS, s.dqkv, T, Hq, Hkv, hd,
+                       qkvd, scale);
+    hipLaunchKernelGGL(train_attn_bwd_kv_kernel, dim3(T, Hkv, B), dim3(hd <= 64 ? 64 : 128), 0, st, s.qkv, s.P, s.dS, s.datt, s.dqkv,
+                       T, Hq, Hkv, hd, qkvd);
+    hipLaunchKernelGGL(train_rope_kernel, dim3(M), dim3(256), 0, st, s.dqkv, T, Hq + Hkv, hd, qkvd, (double)c.rope_theta, -1);
+    if ((rc = sgemm(2, s.dqkv, s.a1, g->wqkv, nullptr, qkvd, d, M, st))) return rc;
+    if ((rc = sgemm(1, s.dqkv, w->wqkv, s.da, nullptr, M, d, qkvd, st))) return rc;
+    hipLaunchKernelGGL(rms_dgain_kernel, dim3((d + 255) / 256), dim3(256), 0, st, s.da, s.h0, s.inv1, g->norm_attn, M, d);
+    hipLaunchKernelGGL(rms_bwd_kernel, dim3(M), dim3(256), 0, st, s.da, s.h0, w->norm_attn, s.inv1, s.dh1, s.dx, d);
+    if ((rc = sgemm(2, s.dx, s.cat, g->fc, nullptr, d, 2 * d, M, st))) return rc;
+    FG_LAUNCH_CHECK("draft_train_grad");
+    return FG_OK;
+}
+
+int32_t launch_adamw(float *p, const float *g, float *m, float *v, int64_t n, float lr, float b1, float b2, float eps, float wd,
+                     int step, hipStream_t st)
+{
+    if (n <= 0) return FG_OK;
+    const float c1 = 1.f - powf(b1, (float)step), c2 = 1.f - powf(b2, (float)step);
+    hipLaunchKernelGGL(adamw_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, g, m, v, (size_t)n, lr, b1, b2, eps, wd, c1, c2);
+    FG_LAUNCH_CHECK("adamw");
+    return FG_OK;
+}
+
+}  // namespace fg
