@@ -447,6 +447,48 @@ def gemm_kernel_bench(args):
                       "mfma_frac": flops / ts[0] / PEAK_MFMA, "weight_stream_GBps": byts / ts[0] / 1e9}))
 
 
+def train_bench(args):
+    """--train: one step of online draft learning (Sec. 4.2) on the 7B-class draft head: loss + gradients of B chains of T
+    cached (token, feature) entries and the AdamW update, fp32.  Tokens/s of training entries and the fraction of the fp32
+    vector peak over the step's GEMM flops."""
+    import torch
+    import paper_2509_21792_amd as fg
+    from paper_2509_21792_amd import loop as gloop
+    from synth import configs, gen
+    model = configs.with_dtype(configs.Q7B, "fp32")
+    dcfg = configs.draft_of(model)
+    B, T = args.B or 8, args.T
+    d, F, V = model["d_model"], model["d_ffn"], model["vocab"]
+    g = torch.Generator(device="cuda").manual_seed(0)
+    tw = {"embed": torch.randn((V, d), generator=g, device="cuda") * 0.02, "lm_head": torch.randn((V, d), generator=g, device="cuda") * 0.02}
+    dw = gen.make_weights(dcfg, 0, device="cuda", draft=True)
+    compute = "fp32" if args.train == "fp32" else "bf16"
+    trainer = gloop.DraftTrainer(dcfg, dw, tw, compute=compute)
+    tokens = torch.randint(0, V, (B, T), generator=g, device="cuda", dtype=torch.int32)
+    fin = torch.randn((B, T, d), generator=g, device="cuda")
+    ftg = torch.randn((B, T, d), generator=g, device="cuda")
+    n_valid = torch.full((B,), T, dtype=torch.int32, device="cuda")
+    def f():
+        trainer.step(tokens, fin, ftg, n_valid)
+    ts = time_each(torch, f, max(3, args.steps // 3), 1)
+    qkvd = (model["n_q_heads"] + 2 * model["n_kv_heads"]) * model["head_dim"]
+    hq = model["n_q_heads"] * model["head_dim"]
+    p_fc, p_layer, p_lm = 2 * d * d, qkvd * d + hq * d + 3 * F * d, V * d
+    M = B * T
+    flops = 2.0 * M * (3 * (p_fc + p_layer) - p_fc + 3 * p_lm)
+    peak = 157.3e12 if compute == "fp32" else PEAK_MFMA
+    print(json.dumps({"metric": "draft training entries/s (online draft learning step: loss, gradients, AdamW)", "unit": "tokens/s",
+                      "value": M / ts[0], "n_gpus": 1, "dtype": "f32" if compute == "fp32" else "bf16", "data": "synthetic",
+                      "higher_is_better": True,
+                      "config": {"workload": f"7B-class draft head (1 layer, d={d}, F={F}, vocab {V}), {B} chains of {T} entries, "
+                                             f"matrix products in {compute}"},
+                      "step": spread(ts), "step_flops": flops,
+                      "roofline": {"bound": "alu" if compute == "fp32" else "mfma", "achieved": flops / ts[0] / 1e12, "peak": peak / 1e12,
+                                   "unit": "TFLOP/s", "frac": flops / ts[0] / peak, "traffic": None,
+                                   "kernel": "the step's GEMMs (whole-step flops over whole-step time: casts, packs, row-wise "
+                                             "kernels and the optimiser included)"}}))
+
+
 def ceilings(args):
     """--ceilings: what this GPU sustains for the two resources the path is bound by, next to the nominal peaks:
     a read-only stream and a plain copy over buffers far larger than the last-level cache, and a register-resident
@@ -541,6 +583,10 @@ def main():
     ap.add_argument("--variant", type=int, default=0, help="--gemm: 0 = the library's kernel choice, 1-5 force one (see fastgrpo.h)")
     ap.add_argument("--split", type=int, default=0, help="--gemm: k splits of the partial-sum epilogue (0 = the library's choice)")
     ap.add_argument("--cycle", type=int, default=8, help="--gemm: number of different weight matrices used in turn")
+    ap.add_argument("--train", default="", choices=["", "bf16", "fp32"],
+                    help="time one online draft learning step on the 7B-class draft head (matrix products on the matrix cores "
+                         "in bf16, or exact fp32) and exit")
+    ap.add_argument("--T", type=int, default=256, help="--train: entries per chain")
     ap.add_argument("--ceilings", action="store_true",
                     help="measure the achievable HBM stream rate and MFMA rate of this GPU (probe kernels) and exit")
     args = ap.parse_args()
@@ -554,6 +600,9 @@ def main():
     assert torch.cuda.is_available(), "no GPU: the HIP path has no CPU fallback"
     if args.gemm:
         gemm_kernel_bench(args)
+        return
+    if args.train:
+        train_bench(args)
         return
     if args.ceilings:
         ceilings(args)

@@ -328,8 +328,7 @@ int32_t fg_build_tree(const int32_t *cand_tok, const int32_t *cand_parent, const
  * averaged over the valid entries (the paper names no loss: this is the one of the draft-head pre-training it follows,
  * Sec. 5.1).  Outputs: loss (device, 2 floats: the regression and the cross-entropy term, unweighted) and the gradient
  * of the total in `grad`.  embed, lm_head: the target's, fp32 row-major [vocab, d], frozen.  tokens int32 [B, T],
- * feat_in / feat_tgt fp32 [B, T, d], n_valid int32 [B], all device.  cfg: the draft head's (n_layers must be 1; the dtype
- * field is ignored).  d, F, Hq hd, vocab multiples of 4; T * 4 bytes of LDS per block (T <= 8192).
+ * feat_in / feat_tgt fp32 [B, T, d], n_valid int32 [B], all device.  cfg: the draft head's (n_layers must be 1).  d, F, Hq hd, vocab multiples of 4; T * 4 bytes of LDS per block (T <= 8192).
  * workspace: fg_draft_train_workspace_bytes(cfg, B, T).  Deterministic: no atomics, fixed summation orders.
  *
  * fg_draft_adamw: one AdamW step on every parameter (decoupled weight decay, bias-corrected moments; step counts

@@ -519,12 +519,19 @@ def _params_struct(p):
     return DraftParamsC(*[p[n].data_ptr() for n in PARAM_NAMES])
 
 
-def fg_draft_train_grad(cfg, embed, lm_head, w, tokens, feat_in, feat_tgt, n_valid, w_ce=0.1, grad=None, workspace=None):
+def fg_draft_train_workspace_bytes(cfg, B, T, compute="fp32"):
+    c = model_cfg_struct(dict(cfg, dtype=compute))
+    return lib().fg_draft_train_workspace_bytes(C.byref(c), B, T)
+
+
+def fg_draft_train_grad(cfg, embed, lm_head, w, tokens, feat_in, feat_tgt, n_valid, w_ce=0.1, grad=None, workspace=None,
+                        compute="fp32"):
     """Loss terms (device tensor [2]) and gradients (dict of fp32 tensors shaped like `w`) of the draft head's training
-    loss; embed / lm_head: the target's, fp32 row-major on the device."""
+    loss; embed / lm_head: the target's, fp32 row-major on the device.  compute: "fp32" (exact) or "bf16" (the step's
+    matrix products on the matrix cores)."""
     dev = tokens.device
     B, T = tokens.shape
-    c = model_cfg_struct(dict(cfg, dtype="fp32"))
+    c = model_cfg_struct(dict(cfg, dtype=compute))
     if grad is None:
         grad = {n: torch.empty(s, dtype=torch.float32, device=dev) for n, s in draft_param_shapes(cfg).items()}
     if workspace is None:

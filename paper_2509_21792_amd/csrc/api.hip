@@ -809,7 +809,7 @@ static bool params_ok(const fg_draft_params *p)
 
 int64_t fg_draft_train_workspace_bytes(const fg_model_cfg *cfg, int32_t B, int32_t T)
 {
-    if (check_train_cfg(cfg) || B < 1 || T < 1) return 0;
+    if (check_train_cfg(cfg) || !dtype_ok(cfg->dtype) || B < 1 || T < 1) return 0;
     return draft_train_ws_bytes(*cfg, B, T);
 }
 
@@ -820,6 +820,10 @@ int32_t fg_draft_train_grad(const fg_model_cfg *cfg, const float *embed, const f
 {
     int32_t rc;
     if ((rc = check_train_cfg(cfg))) return rc;
+    if (cfg->dtype == FG_F16) return fail(FG_ERR_INVALID_ARG, "fg_draft_train_grad: FG_F32 (exact) or FG_BF16 (matrix cores); fp16 would flush the gradients");
+    if (cfg->dtype == FG_BF16 && (((int64_t)B * T) % 64 || cfg->d_model % 64 || cfg->d_ffn % 64 || cfg->vocab % 64 ||
+                                  (cfg->n_q_heads * cfg->head_dim) % 64 || ((cfg->n_q_heads + 2 * cfg->n_kv_heads) * cfg->head_dim) % 64))
+        return fail(FG_ERR_SHAPE, "fg_draft_train_grad: the matrix-core path needs B * T and every model width in multiples of 64");
     if (B < 0 || T < 0) return fail(FG_ERR_INVALID_ARG, "fg_draft_train_grad: negative B / T");
     if (B == 0 || T == 0) return FG_OK;
     if (T > 8192) return fail(FG_ERR_CAPACITY, "fg_draft_train_grad: chains of at most 8192 entries (got %d)", T);

@@ -1,9 +1,9 @@
 // Online draft learning (Sec. 4.2 "Draft Model Learning with Online Target Feedback"; Alg. 1, the draft training
 // phase): loss and gradients of the one-layer draft head on the tokens and hidden states the generation phase cached,
-// and the AdamW update.  Everything here computes in fp32 on fp32 master parameters; the generation path gets the
-// updated head by re-packing them (fg_pack_weight).  The phase is a few per cent of a training iteration (Sec. 4.2), so
-// these kernels are plain: a register-tiled fp32 GEMM in the three operand orders a backward pass needs, and row-wise
-// kernels for norm, RoPE, causal attention, SwiGLU and the loss, each with its backward.
+// and the AdamW update.  Parameters, gradients and activations are fp32; the generation path gets the updated head by
+// re-packing the parameters (fg_pack_weight).  The matrix products of a step run either in a register-tiled fp32 GEMM
+// (the parity mode) or, operands rounded to bf16, in the generation path's MFMA GEMM; norm, RoPE, causal attention,
+// SwiGLU and the loss are plain row-wise kernels, each with its backward.
 #include "fg_common.h"
 
 namespace fg {
@@ -98,6 +98,78 @@ static int32_t sgemm(int op, const float *A, const float *B, float *C, const flo
     else hipLaunchKernelGGL((sgemm_kernel<false, false>), grid, dim3(256), 0, st, A, B, C, add, M, N, K, M, N, N);
     FG_LAUNCH_CHECK("sgemm");
     return FG_OK;
+}
+
+// ---- the same three products on the matrix cores (bf16 operands, fp32 accumulate) --------------------------------------
+// The 16-bit GEMM of the generation path computes out = X . W^T for a packed W; each product is brought into that form
+// by casting (and, where the contraction runs over the other index, transposing) its fp32 operands into scratch and
+// packing the second one.  Gradients are tiny numbers: bf16 keeps fp32's exponent range, so nothing underflows.
+__global__ void cast_bf16_kernel(const float *__restrict__ src, bf16_t *__restrict__ dst, size_t n)
+{
+    const size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i + 3 < n) {
+        const float4 v = *reinterpret_cast<const float4 *>(src + i);
+        uint2 u;
+        u.x = (uint32_t)f2bf(v.x) | ((uint32_t)f2bf(v.y) << 16);
+        u.y = (uint32_t)f2bf(v.z) | ((uint32_t)f2bf(v.w) << 16);
+        *reinterpret_cast<uint2 *>(dst + i) = u;
+    } else {
+        for (size_t j = i; j < n; j++) dst[j] = f2bf(src[j]);
+    }
+}
+
+// dst [C, R] (bf16) = transpose of src [R, C] (fp32), 32 x 32 tiles through LDS
+__global__ __launch_bounds__(256) void transpose_cast_bf16_kernel(const float *__restrict__ src, bf16_t *__restrict__ dst, int R, int C)
+{
+    __shared__ float tile[32][33];
+    const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32, tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    for (int i = ty; i < 32; i += 8)
+        tile[i][tx] = (r0 + i < R && c0 + tx < C) ? src[(size_t)(r0 + i) * C + c0 + tx] : 0.f;
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8)
+        if (c0 + i < C && r0 + tx < R) dst[(size_t)(c0 + i) * R + r0 + tx] = f2bf(tile[tx][i]);
+}
+
+struct Mfma16 {          // scratch of the matrix-core path
+    bf16_t *x16;         // the first operand, cast (and transposed)
+    bf16_t *w16;         // the second operand, cast (and transposed), before packing
+    bf16_t *wp;          // ... packed
+    int64_t x_cap, w_cap;
+    // the packed form of the last second operand, so that the two LM-head products of the forward pass pack it once
+    const float *last_src = nullptr;
+    int last_op = -1;
+};
+
+static int32_t gemm16(Mfma16 &s, int op, const float *A, const float *B, float *C, const float *add, int M, int N, int K, hipStream_t st)
+{
+    if (M <= 0 || N <= 0 || K <= 0) return FG_OK;
+    if (N % 32 || K % 64) return fail(FG_ERR_SHAPE, "matrix-core training GEMM needs an output width in multiples of 32 and a contraction in multiples of 64 (%d, %d)", N, K);
+    if ((int64_t)M * K > s.x_cap || (int64_t)N * K > s.w_cap) return fail(FG_ERR_CAPACITY, "matrix-core training GEMM scratch too small");
+    auto cast = [&](const float *src, bf16_t *dst, size_t n) {
+        hipLaunchKernelGGL(cast_bf16_kernel, dim3((unsigned)((n / 4 + 255) / 256 + 1)), dim3(256), 0, st, src, dst, n);
+    };
+    auto tcast = [&](const float *src, bf16_t *dst, int R, int Cc) {
+        hipLaunchKernelGGL(transpose_cast_bf16_kernel, dim3((Cc + 31) / 32, (R + 31) / 32), dim3(256), 0, st, src, dst, R, Cc);
+    };
+    // first operand as [M, K] bf16
+    if (op == 2) tcast(A, s.x16, K, M);           // A is [K, M]
+    else cast(A, s.x16, (size_t)M * K);
+    // second operand as [N, K] bf16, packed
+    if (!(s.last_src == B && s.last_op == op)) {
+        if (op == 0) cast(B, s.w16, (size_t)N * K);          // B is [N, K]
+        else tcast(B, s.w16, K, N);                           // B is [K, N]
+        int32_t rc = launch_pack(FG_BF16, s.w16, nullptr, s.wp, N, K, st);
+        if (rc) return rc;
+        s.last_src = B;
+        s.last_op = op;
+    }
+    if (add) {
+        if (add != C) FG_HIP(hipMemcpyAsync(C, add, (size_t)M * N * 4, hipMemcpyDeviceToDevice, st));
+        GemmEpi ep;
+        ep.h = C;
+        return launch_gemm_mfma(FG_BF16, s.x16, s.wp, nullptr, M, N, K, EPI_RESIDUAL, 1, nullptr, st, &ep);
+    }
+    return launch_gemm_mfma(FG_BF16, s.x16, s.wp, C, M, N, K, EPI_SLABS, 1, nullptr, st);
 }
 
 // ---- row-wise kernels ------------------------------------------------------------------------------------------------
@@ -364,6 +436,7 @@ struct TrainWs {
     float *cat, *h0, *a1, *inv1, *qkv, *P, *dS, *att, *h1, *a2, *inv2, *gate, *up, *act, *h2, *z, *zt, *dh2, *dact, *dgate, *dup,
         *da, *dh1, *datt, *dqkv, *dx, *row_loss;
     int32_t *n_tot;
+    Mfma16 mm;
 };
 
 static int64_t carve_train(const fg_model_cfg &c, int B, int T, void *base, int64_t cap, TrainWs *w)
@@ -384,6 +457,15 @@ static int64_t carve_train(const fg_model_cfg &c, int B, int T, void *base, int6
     s.h2 = take(M * d); s.z = take(M * V); s.zt = take(M * V); s.dh2 = take(M * d); s.dact = take(M * F); s.dgate = take(M * F);
     s.dup = take(M * F); s.da = take(M * d); s.dh1 = take(M * d); s.datt = take(M * hq); s.dqkv = take(M * qkvd); s.dx = take(M * d);
     s.row_loss = take(M * 2); s.n_tot = (int32_t *)take(64);
+    if (is16(c.dtype)) {
+        // largest first operand: the logit gradients [M, V]; largest second operand: the LM head [V, d]
+        const int64_t big = V > F ? V : F, wide = F > 2 * d ? F : 2 * d, rows = M > d ? M : d;
+        s.mm.x_cap = M * (big > 2 * d ? big : 2 * d);
+        s.mm.w_cap = V * d > wide * rows ? V * d : wide * rows;
+        s.mm.x16 = (bf16_t *)take((s.mm.x_cap + 1) / 2);
+        s.mm.w16 = (bf16_t *)take((s.mm.w_cap + 1) / 2);
+        s.mm.wp = (bf16_t *)take((s.mm.w_cap + 1) / 2);
+    }
     if (w) *w = s;
     if (base && off > cap) return -1;
     return align_up(off, 256);
@@ -402,51 +484,56 @@ int32_t launch_draft_train_grad(const fg_model_cfg &c, const float *embed, const
     const float scale = 1.0f / sqrtf((float)hd);
     const size_t lds = (size_t)T * sizeof(float);
     int32_t rc;
+    // fp32 throughout, or the GEMMs on the matrix cores with bf16 operands (fp16 would flush the gradients to zero)
+    const bool mfma = c.dtype == FG_BF16;
+    auto gemm = [&](int op, const float *A, const float *Bm, float *C, const float *add, int Mo, int No, int Ko, hipStream_t) -> int32_t {
+        return mfma ? gemm16(s.mm, op, A, Bm, C, add, Mo, No, Ko, st) : sgemm(op, A, Bm, C, add, Mo, No, Ko, st);
+    };
     // forward
     hipLaunchKernelGGL(train_count_kernel, dim3(1), dim3(1), 0, st, n_valid, B, T, s.n_tot);
     hipLaunchKernelGGL(train_concat_kernel, dim3(M), dim3(256), 0, st, embed, tokens, V, feat_in, s.cat, d);
-    if ((rc = sgemm(0, s.cat, w->fc, s.h0, nullptr, M, d, 2 * d, st))) return rc;
+    if ((rc = gemm(0, s.cat, w->fc, s.h0, nullptr, M, d, 2 * d, st))) return rc;
     hipLaunchKernelGGL(rms_fwd_kernel, dim3(M), dim3(256), 0, st, s.h0, w->norm_attn, s.a1, s.inv1, d, c.rms_eps);
-    if ((rc = sgemm(0, s.a1, w->wqkv, s.qkv, nullptr, M, qkvd, d, st))) return rc;
+    if ((rc = gemm(0, s.a1, w->wqkv, s.qkv, nullptr, M, qkvd, d, st))) return rc;
     hipLaunchKernelGGL(train_rope_kernel, dim3(M), dim3(256), 0, st, s.qkv, T, Hq + Hkv, hd, qkvd, (double)c.rope_theta, 1);
     hipLaunchKernelGGL(train_attn_fwd_kernel, dim3(T, Hq, B), dim3(256), lds, st, s.qkv, s.P, s.att, T, Hq, Hkv, hd, qkvd, scale);
-    if ((rc = sgemm(0, s.att, w->wo, s.h1, s.h0, M, d, hq, st))) return rc;
+    if ((rc = gemm(0, s.att, w->wo, s.h1, s.h0, M, d, hq, st))) return rc;
     hipLaunchKernelGGL(rms_fwd_kernel, dim3(M), dim3(256), 0, st, s.h1, w->norm_ffn, s.a2, s.inv2, d, c.rms_eps);
-    if ((rc = sgemm(0, s.a2, w->w_gate, s.gate, nullptr, M, F, d, st))) return rc;
-    if ((rc = sgemm(0, s.a2, w->w_up, s.up, nullptr, M, F, d, st))) return rc;
+    if ((rc = gemm(0, s.a2, w->w_gate, s.gate, nullptr, M, F, d, st))) return rc;
+    if ((rc = gemm(0, s.a2, w->w_up, s.up, nullptr, M, F, d, st))) return rc;
     const size_t nf = (size_t)M * F;
     hipLaunchKernelGGL(train_swiglu_fwd_kernel, dim3((unsigned)((nf + 255) / 256)), dim3(256), 0, st, s.gate, s.up, s.act, nf);
-    if ((rc = sgemm(0, s.act, w->w_down, s.h2, s.h1, M, d, F, st))) return rc;
-    if ((rc = sgemm(0, s.h2, lm_head, s.z, nullptr, M, V, d, st))) return rc;
-    if ((rc = sgemm(0, feat_tgt, lm_head, s.zt, nullptr, M, V, d, st))) return rc;
+    if ((rc = gemm(0, s.act, w->w_down, s.h2, s.h1, M, d, F, st))) return rc;
+    if ((rc = gemm(0, s.h2, lm_head, s.z, nullptr, M, V, d, st))) return rc;
+    if ((rc = gemm(0, feat_tgt, lm_head, s.zt, nullptr, M, V, d, st))) return rc;
     // loss, d loss / d z (over z) and the regression part of d loss / d h2
     hipLaunchKernelGGL(train_loss_kernel, dim3(M), dim3(256), 0, st, s.h2, feat_tgt, s.z, s.zt, n_valid, s.n_tot, T, d, V, w_ce, s.dh2,
                        s.row_loss);
     hipLaunchKernelGGL(train_loss_reduce_kernel, dim3(1), dim3(256), 0, st, s.row_loss, M, s.n_tot, loss);
     // backward
-    if ((rc = sgemm(1, s.z, lm_head, s.dh2, s.dh2, M, d, V, st))) return rc;              // through the frozen LM head
-    if ((rc = sgemm(2, s.dh2, s.act, g->w_down, nullptr, d, F, M, st))) return rc;
-    if ((rc = sgemm(1, s.dh2, w->w_down, s.dact, nullptr, M, F, d, st))) return rc;
+    if ((rc = gemm(1, s.z, lm_head, s.dh2, s.dh2, M, d, V, st))) return rc;              // through the frozen LM head
+    if ((rc = gemm(2, s.dh2, s.act, g->w_down, nullptr, d, F, M, st))) return rc;
+    if ((rc = gemm(1, s.dh2, w->w_down, s.dact, nullptr, M, F, d, st))) return rc;
     hipLaunchKernelGGL(train_swiglu_bwd_kernel, dim3((unsigned)((nf + 255) / 256)), dim3(256), 0, st, s.dact, s.gate, s.up, s.dgate,
                        s.dup, nf);
-    if ((rc = sgemm(2, s.dgate, s.a2, g->w_gate, nullptr, F, d, M, st))) return rc;
-    if ((rc = sgemm(2, s.dup, s.a2, g->w_up, nullptr, F, d, M, st))) return rc;
-    if ((rc = sgemm(1, s.dgate, w->w_gate, s.da, nullptr, M, d, F, st))) return rc;
-    if ((rc = sgemm(1, s.dup, w->w_up, s.da, s.da, M, d, F, st))) return rc;
+    if ((rc = gemm(2, s.dgate, s.a2, g->w_gate, nullptr, F, d, M, st))) return rc;
+    if ((rc = gemm(2, s.dup, s.a2, g->w_up, nullptr, F, d, M, st))) return rc;
+    if ((rc = gemm(1, s.dgate, w->w_gate, s.da, nullptr, M, d, F, st))) return rc;
+    if ((rc = gemm(1, s.dup, w->w_up, s.da, s.da, M, d, F, st))) return rc;
     hipLaunchKernelGGL(rms_dgain_kernel, dim3((d + 255) / 256), dim3(256), 0, st, s.da, s.h1, s.inv2, g->norm_ffn, M, d);
     hipLaunchKernelGGL(rms_bwd_kernel, dim3(M), dim3(256), 0, st, s.da, s.h1, w->norm_ffn, s.inv2, s.dh2, s.dh1, d);
-    if ((rc = sgemm(2, s.dh1, s.att, g->wo, nullptr, d, hq, M, st))) return rc;
-    if ((rc = sgemm(1, s.dh1, w->wo, s.datt, nullptr, M, hq, d, st))) return rc;
+    if ((rc = gemm(2, s.dh1, s.att, g->wo, nullptr, d, hq, M, st))) return rc;
+    if ((rc = gemm(1, s.dh1, w->wo, s.datt, nullptr, M, hq, d, st))) return rc;
     hipLaunchKernelGGL(train_attn_bwd_q_kernel, dim3(T, Hq, B), dim3(256), lds, st, s.qkv, s.P, s.datt, s.dS, s.dqkv, T, Hq, Hkv, hd,
                        qkvd, scale);
     hipLaunchKernelGGL(train_attn_bwd_kv_kernel, dim3(T, Hkv, B), dim3(hd <= 64 ? 64 : 128), 0, st, s.qkv, s.P, s.dS, s.datt, s.dqkv,
                        T, Hq, Hkv, hd, qkvd);
     hipLaunchKernelGGL(train_rope_kernel, dim3(M), dim3(256), 0, st, s.dqkv, T, Hq + Hkv, hd, qkvd, (double)c.rope_theta, -1);
-    if ((rc = sgemm(2, s.dqkv, s.a1, g->wqkv, nullptr, qkvd, d, M, st))) return rc;
-    if ((rc = sgemm(1, s.dqkv, w->wqkv, s.da, nullptr, M, d, qkvd, st))) return rc;
+    if ((rc = gemm(2, s.dqkv, s.a1, g->wqkv, nullptr, qkvd, d, M, st))) return rc;
+    if ((rc = gemm(1, s.dqkv, w->wqkv, s.da, nullptr, M, d, qkvd, st))) return rc;
     hipLaunchKernelGGL(rms_dgain_kernel, dim3((d + 255) / 256), dim3(256), 0, st, s.da, s.h0, s.inv1, g->norm_attn, M, d);
     hipLaunchKernelGGL(rms_bwd_kernel, dim3(M), dim3(256), 0, st, s.da, s.h0, w->norm_attn, s.inv1, s.dh1, s.dx, d);
-    if ((rc = sgemm(2, s.dx, s.cat, g->fc, nullptr, d, 2 * d, M, st))) return rc;
+    if ((rc = gemm(2, s.dx, s.cat, g->fc, nullptr, d, 2 * d, M, st))) return rc;
     FG_LAUNCH_CHECK("draft_train_grad");
     return FG_OK;
 }

@@ -268,3 +268,59 @@ def prefill(target, draft, kv, dkv, slot, prompts, ws_t, ws_d, chunk=64, max_seq
             first = out["argmax"].view(B, n)[:, -1].contiguous()
     st = SpecState(first.view(B, 1).contiguous(), prev_feat, torch.zeros(B, dtype=torch.int32, device=dev))
     return first, st
+
+
+class DraftTrainer:
+    """Online draft learning (Sec. 4.2; Alg. 1, the draft training phase): fp32 master parameters of the draft head, their
+    AdamW state, and the two library calls of a step.  Host bookkeeping only -- the loss, the gradients and the update are
+    fg_draft_train_grad / fg_draft_adamw; `export` hands the updated head to the generation path by casting and re-packing
+    the matrices (binding.Model).
+
+    weights: dict fc, layers[0]{wqkv, wo, w_gate, w_up, w_down, norm_attn, norm_ffn} (tensors, any float type);
+    target_weights: dict with the target's embed and lm_head (row-major [vocab, d])."""
+
+    def __init__(self, draft_cfg, weights, target_weights, device="cuda", lr=1e-4, w_ce=0.1, betas=(0.9, 0.999), eps=1e-8,
+                 weight_decay=0.01, compute="fp32"):
+        self.cfg = dict(draft_cfg)
+        self.compute = compute          # "fp32": exact; "bf16": the step's matrix products on the matrix cores
+        f32 = lambda t: t.detach().to(device=device, dtype=torch.float32).contiguous().clone()
+        lay = weights["layers"][0]
+        self.w = {"fc": f32(weights["fc"])}
+        self.w.update({k: f32(lay[k]) for k in ("wqkv", "wo", "w_gate", "w_up", "w_down", "norm_attn", "norm_ffn")})
+        self.m = {k: torch.zeros_like(t) for k, t in self.w.items()}
+        self.v = {k: torch.zeros_like(t) for k, t in self.w.items()}
+        self.grad = {k: torch.empty_like(t) for k, t in self.w.items()}
+        self.embed, self.lm_head = f32(target_weights["embed"]), f32(target_weights["lm_head"])
+        self.lr, self.w_ce, self.betas, self.eps, self.weight_decay = lr, w_ce, betas, eps, weight_decay
+        self.steps = 0
+        self._ws = None
+
+    def step(self, tokens, feat_in, feat_tgt, n_valid):
+        """One update on a batch of chains: tokens int32 [B, T], feat_in / feat_tgt [B, T, d] (cast to fp32 here), n_valid
+        int32 [B].  Returns the device tensor [2] of the loss terms before the update (regression, cross-entropy)."""
+        B, T = tokens.shape
+        if self._ws is None or self._ws[0] != (B, T):      # one workspace per batch shape, kept between steps
+            self._ws = ((B, T), torch.empty(fg.fg_draft_train_workspace_bytes(self.cfg, B, T, self.compute), dtype=torch.uint8,
+                                            device=tokens.device))
+        loss, _ = fg.fg_draft_train_grad(self.cfg, self.embed, self.lm_head, self.w, tokens, feat_in.float().contiguous(),
+                                         feat_tgt.float().contiguous(), n_valid, self.w_ce, grad=self.grad, workspace=self._ws[1],
+                                         compute=self.compute)
+        self.steps += 1
+        fg.fg_draft_adamw(self.cfg, self.w, self.grad, self.m, self.v, lr=self.lr, step=self.steps, beta1=self.betas[0],
+                          beta2=self.betas[1], eps=self.eps, weight_decay=self.weight_decay)
+        return loss
+
+    def weights(self):
+        """The current parameters in the dict layout binding.Model takes for a draft head."""
+        return {"fc": self.w["fc"], "layers": [{k: self.w[k] for k in ("wqkv", "wo", "w_gate", "w_up", "w_down", "norm_attn", "norm_ffn")}]}
+
+    def export(self, target_model, max_pos=8192):
+        """A draft Model of the generation path from the current parameters (cast to its type, packed)."""
+        return fg.Model(self.cfg, self.weights(), target=target_model, max_pos=max_pos)
+
+
+def training_chains(feature, tokens):
+    """Training entries from what a pass of the target over whole sequences leaves behind: feature [B, P, d] (the target's
+    feature at every position) and tokens [B, P] give, per sequence, the chain of P - 1 entries (token t + 1, feature t)
+    with targets feature t + 1.  Returns (tokens [B, P-1], feat_in, feat_tgt)."""
+    return tokens[:, 1:].contiguous(), feature[:, :-1].contiguous(), feature[:, 1:].contiguous()

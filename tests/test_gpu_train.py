@@ -118,3 +118,85 @@ def test_training_steps_lower_the_loss_as_the_oracle_does(fg, orc):
         assert abs(total - o_total) <= 1e-4 * o_total, (step, total, o_total)
         first = first if first is not None else total
     assert total < first
+
+
+def test_online_learning_raises_the_accepted_length(fg):
+    """The synthetic analogue of the paper's accepted-length-versus-training-steps figure (Sec. 4.2): a randomly
+    initialised draft head is trained on the features and tokens the target's own greedy rollouts leave behind; the
+    accepted length of speculative decoding on those rollouts' prompts rises well above its untrained value, and the
+    emitted tokens stay those of plain decoding (speculation is lossless whatever the head predicts)."""
+    from paper_2509_21792_amd import loop as gloop
+    from synth import gen
+    model = configs.TINY
+    dcfg = configs.draft_of(model)
+    tw = gen.make_weights(model, 3, device="cuda")
+    dw = gen.make_weights(dcfg, 3, device="cuda", draft=True)
+    gm = fg.Model(model, tw)
+    B, P, n_new = 8, 24, 40
+    prompts = torch.as_tensor(gen.make_prompts(B, 1, P, model["vocab"], 5)).cuda()
+    prompts[1::2] = torch.as_tensor(np.random.default_rng(6).integers(0, model["vocab"], size=(B // 2, P)).astype(np.int32)).cuda()
+    cap = P + n_new + 80
+    slot = torch.arange(B, dtype=torch.int32, device="cuda")
+
+    def rollout(gd):
+        """(token lists, mean tokens emitted per verification over the speculative rounds) with draft head gd"""
+        table, n_pages = gen.make_page_table(np.zeros(B, np.int32), cap, 16, 1)
+        dtable, dn = gen.make_page_table(np.zeros(B, np.int32), cap, 16, 2)
+        kv, dkv = fg.KVCache(model, table, n_pages), fg.KVCache(dcfg, dtable, dn)
+        ws_t, ws_d = gm.workspace(B * 64, cap), gd.workspace(B * 64, cap)
+        first, st = gloop.prefill(gm, gd, kv, dkv, slot, prompts, ws_t, ws_d, max_seq_len=cap)
+        outs, hist = gloop.generate(gm, gd, kv, dkv, slot, st, first.cpu().numpy(), np.full(B, n_new, np.int32), 48.0, ws_t, ws_d,
+                                    max_seq_len=cap)
+        spec = [h for h in hist if h["N"] > 1]
+        return outs, sum(h["emitted"] for h in spec) / max(sum(h["B"] for h in spec), 1)
+
+    trainer = gloop.DraftTrainer(dcfg, dw, tw, lr=2e-3, w_ce=0.1)
+    outs0, tau0 = rollout(trainer.export(gm))
+    # the cached supervision: the target's features over prompt + its own continuation, one pass per sequence
+    seqs = torch.as_tensor(np.array([list(prompts[b].cpu().numpy()) + outs0[b] for b in range(B)], dtype=np.int32)).cuda()
+    S = seqs.shape[1]
+    table, n_pages = gen.make_page_table(np.zeros(B, np.int32), S + 16, 16, 3)
+    kv = fg.KVCache(model, table, n_pages)
+    ws = gm.workspace(B * 64, S + 16)
+    feats = []
+    for p0 in range(0, S, 64):
+        n = min(64, S - p0)
+        out = fg.fg_spec_verify(gm, kv, slot, seqs[:, p0:p0 + n].contiguous(), gloop.chain_parent(B, n, "cuda"), ws, max_seq_len=S + 16)
+        ident = torch.arange(n, dtype=torch.int32, device="cuda").repeat(B, 1)
+        fg.fg_kv_compact(kv, slot, torch.full((B,), n - 1, dtype=torch.int32, device="cuda"), ident)
+        feats.append(out["feature"].view(B, n, -1).float())
+    feature = torch.cat(feats, dim=1)
+    tok, fin, ftg = gloop.training_chains(feature, seqs)
+    n_valid = torch.full((B,), S - 1, dtype=torch.int32, device="cuda")
+    losses = []
+    for _ in range(60):
+        losses.append(trainer.step(tok, fin, ftg, n_valid).cpu().numpy())
+    # the regression term falls by far; the cross-entropy term falls towards its floor, the entropy of the target's own
+    # (near-uniform, with random weights) next-token distribution
+    assert losses[-1][0] < 0.2 * losses[0][0] and losses[-1][1] < losses[0][1]
+    outs1, tau1 = rollout(trainer.export(gm))
+    assert outs1 == outs0                      # lossless: the same tokens with either head
+    print(f"accepted tokens per verification: {tau0:.2f} untrained -> {tau1:.2f} after 60 steps; "
+          f"loss (reg, ce) {losses[0]} -> {losses[-1]}", flush=True)
+    assert tau1 > tau0 + 0.5
+
+
+def test_matrix_core_mode_follows_the_oracle_to_bf16_rounding(fg, orc):
+    """compute="bf16": the step's matrix products on the matrix cores, operands rounded to bf16.  Against the fp64 oracle
+    every gradient matrix agrees to about 1 % of its largest entry and points the same way (cosine above 0.999)."""
+    cfg = TINY1
+    B, T = 4, 64
+    w, embed, lm_head, tokens, feat_in, feat_tgt, n_valid = make_case(fg, cfg, B, T, [64, 50, 64, 7], 13)
+    w_ce = 0.3
+    o_loss, o_grad = orc.draft_train(oracle_draft(orc, cfg, w, embed, lm_head), tokens, feat_in, feat_tgt, n_valid, w_ce)
+    gw = {k: dev(v) for k, v in w.items()}
+    loss, grad = fg.fg_draft_train_grad(cfg, dev(embed), dev(lm_head), gw, dev(tokens), dev(feat_in), dev(feat_tgt), dev(n_valid), w_ce,
+                                        compute="bf16")
+    torch.cuda.synchronize()
+    assert np.abs(loss.cpu().numpy() - o_loss).max() <= 2e-2 * float(np.abs(o_loss).max())
+    for k in o_grad:
+        got, want = grad[k].cpu().numpy().astype(np.float64).ravel(), o_grad[k].ravel()
+        cos = float(got @ want / (np.linalg.norm(got) * np.linalg.norm(want)))
+        assert cos > 0.999 and np.abs(got - want).max() <= 3e-2 * np.abs(want).max(), (k, cos, np.abs(got - want).max(), np.abs(want).max())
+    with pytest.raises(fg.FgError):      # fp16 would flush the gradients
+        fg.fg_draft_train_grad(cfg, dev(embed), dev(lm_head), gw, dev(tokens), dev(feat_in), dev(feat_tgt), dev(n_valid), w_ce, compute="fp16")
