@@ -356,7 +356,8 @@ int32_t fg_draft_adamw(const fg_model_cfg *cfg, fg_draft_params *w, const fg_dra
  *   epilogue 3: out fp32 [M, n_out] += x . W^T in place (the residual add of the O and down projections; 16-bit
  *               dtypes, pipelined kernel only).
  *   variant: 0 = the kernel the library picks for the shape; 1 = weight-streaming kernel, 2 = few-row kernel (at most
- *               512 rows), 3 / 4 / 5 = pipelined kernel with 256- / 128- / 160-row blocks.  16-bit dtypes only.
+ *               512 rows), 3 / 4 / 5 = pipelined kernel with 256- / 128- / 160-row blocks, 6 = decode kernel (at most 16
+ *               rows, epilogues 0 and 1).  16-bit dtypes only.
  * fg_gemm_kernel_name: the kernel the library picks for a 16-bit GEMM of this shape and epilogue (a static string).
  * fg_attention: tree attention of already-rotated queries q [B*N, Hq*hd] (dtype) over the cache, which must
  *   already hold the in-round nodes' K/V; out [B*N, Hq*hd] (dtype).

@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libfastgrpo.so")
 OBJ = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "gemm_mfma.hip", "gemm_mfma_big.hip", "gemm_mfma_skinny.hip", "gemm_f32.hip", "elementwise.hip", "attention_simple.hip", "attention_mfma.hip",
+SOURCES = ["api.hip", "gemm_mfma.hip", "gemm_mfma_big.hip", "gemm_mfma_skinny.hip", "gemm_mfma_decode.hip", "gemm_f32.hip", "elementwise.hip", "attention_simple.hip", "attention_mfma.hip",
            "accept.hip", "kv_compact.hip", "draft.hip", "probes.hip", "train.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-result", "-I", INCLUDE, "-I", CSRC]

@@ -200,6 +200,10 @@ int gemm_mfma_big_unsplit_tiles(int M, int N, int K, int epilogue);
 int32_t launch_gemm_mfma_skinny(int32_t dtype, const void *x, const void *wp, void *out, int M, int N, int K, int epilogue,
                                 int split, hipStream_t st);
 int gemm_mfma_skinny_split_for(int M, int N, int K);
+int32_t launch_gemm_mfma_decode(int32_t dtype, const void *x, const void *wp, void *out, int M, int N, int K, int epilogue, int split,
+                                hipStream_t st);
+int gemm_mfma_decode_split_for(int M, int N, int K);
+bool gemm_mfma_decode_ok(int M, int N, int K, int epilogue);
 
 // Which kernel runs a shape.  All thresholds are measurements on the 7B-class and 1.5B-class matrices; "wide" means
 // at least 16384 output columns (gate/up, the LM head), "narrow" the QKV, O and down projections.
@@ -212,11 +216,15 @@ int gemm_mfma_skinny_split_for(int M, int N, int K);
 //     gate/up with its SwiGLU fused up to 64 rows (46.6 / 49.5 / 57.7 us at 8 / 32 / 64 rows against 48.8 / 56.8 / 53.0
 //       plus a 4.4 - 5.5 us SwiGLU pass), and up to 128 rows when at most 512 column blocks keep it to one round;
 //     the LM head up to 32 rows (167 against 177 us at 8 rows, level at 32, behind above);
+//   decode kernel (gemm_mfma_decode.hip, eight waves per block, no barrier in the main loop): gate/up with its SwiGLU
+//     fused up to 16 rows -- 43.6 / 45.6 us at 8 / 16 rows of the 7B-class model against 46.0 / 47.4 in the few-row kernel
+//     (kernel durations from a trace).  Its partial-sum epilogue loses to the few-row kernel on every narrow output (O 8.9
+//     against 6.9 us, QKV 12.0 against 7.8, down 25.9 against 22.0 at 8 rows) and on the LM head (186 against 168);
 //   pipelined kernel (gemm_mfma_big.hip): more than 256 rows; from 129 rows the wide outputs (a 256-row tile half
 //     full still beats streaming the weights through eight row tiles per wave) and the narrow ones with up to 16 k
 //     splits (the 7B down projection 42 - 47 us at 160 - 256 rows against 58 - 62 in the streaming kernel);
 //   streaming kernel (this file): the rest, i.e. 33 / 65 - 128 rows of the wide outputs.
-enum { KERNEL_STREAMING = 1, KERNEL_FEW = 2, KERNEL_BIG = 3 };
+enum { KERNEL_STREAMING = 1, KERNEL_FEW = 2, KERNEL_BIG = 3, KERNEL_DECODE = 4 };
 static int kernel_for(int M, int N, int K, int epilogue)
 {
     if (epilogue >= EPI_ROPE) return KERNEL_BIG;
@@ -225,10 +233,11 @@ static int kernel_for(int M, int N, int K, int epilogue)
         return KERNEL_BIG;
     }
     if (M > 128) return KERNEL_BIG;
+    if (epilogue == EPI_SWIGLU && M <= 16 && gemm_mfma_decode_ok(M, N, K, epilogue)) return KERNEL_DECODE;
     if (epilogue == EPI_SWIGLU) return (M <= 64 || (N + 63) / 64 <= 512) ? KERNEL_FEW : KERNEL_STREAMING;
     return M <= 32 ? KERNEL_FEW : KERNEL_STREAMING;
 }
-static int kernel_of_variant(int variant) { return variant == 1 ? KERNEL_STREAMING : (variant == 2 ? KERNEL_FEW : KERNEL_BIG); }
+static int kernel_of_variant(int variant) { return variant == 1 ? KERNEL_STREAMING : (variant == 2 ? KERNEL_FEW : (variant == 6 ? KERNEL_DECODE : KERNEL_BIG)); }
 
 // Whether the gate/up GEMM of M rows applies SwiGLU in its own epilogue (no slabs, no separate pass).
 bool gemm_mfma_fuses_swiglu(int M, int N, int K) { return kernel_for(M, N, K, EPI_SWIGLU) != KERNEL_STREAMING; }
@@ -252,11 +261,12 @@ int gemm_mfma_split_for(int M, int N, int K)
 {
     const int k = kernel_for(M, N, K, EPI_SLABS);
     if (k == KERNEL_FEW) return gemm_mfma_skinny_split_for(M, N, K);
+    if (k == KERNEL_DECODE) return gemm_mfma_decode_split_for(M, N, K);
     if (k == KERNEL_BIG) return gemm_mfma_big_split_for(M, N, K);
     return choose_split(M, N, K, 256, 256);
 }
 
-static const char *const KERNEL_NAMES[] = {"", "gemm_mfma_kernel", "gemm_mfma_skinny_kernel", "gemm_mfma_big_kernel"};
+static const char *const KERNEL_NAMES[] = {"", "gemm_mfma_kernel", "gemm_mfma_skinny_kernel", "gemm_mfma_big_kernel", "gemm_mfma_decode_kernel"};
 const char *gemm_mfma_kernel_name(int M, int N, int K, int epilogue) { return KERNEL_NAMES[kernel_for(M, N, K, epilogue)]; }
 
 template <typename T>
@@ -285,15 +295,17 @@ int32_t launch_gemm_mfma(int32_t dtype, const void *x, const void *wp, void *out
     if (N % 32 || K % 64) return fail(FG_ERR_SHAPE, "16-bit GEMM needs n_out %% 32 == 0 and n_in %% 64 == 0 (got %d, %d)", N, K);
     if (epilogue == EPI_SWIGLU && (N % 64)) return fail(FG_ERR_SHAPE, "gate/up GEMM needs n_out %% 64 == 0");
     if ((int64_t)M * N >= (1LL << 31)) return fail(FG_ERR_SHAPE, "GEMM output of %d x %d exceeds 2^31 elements", M, N);
-    if (variant < 0 || variant > 5) return fail(FG_ERR_INVALID_ARG, "unknown GEMM variant %d", variant);
+    if (variant < 0 || variant > 6) return fail(FG_ERR_INVALID_ARG, "unknown GEMM variant %d", variant);
     const int kernel = variant ? kernel_of_variant(variant) : kernel_for(M, N, K, epilogue);
     if (epilogue >= EPI_ROPE && kernel != KERNEL_BIG) return fail(FG_ERR_INVALID_ARG, "GEMM epilogue %d exists in the pipelined kernel only", epilogue);
     if (kernel == KERNEL_FEW && M > 512) return fail(FG_ERR_SHAPE, "the few-row kernel takes at most 512 rows (got %d)", M);
+    if (kernel == KERNEL_DECODE && !gemm_mfma_decode_ok(M, N, K, epilogue)) return fail(FG_ERR_SHAPE, "the decode kernel takes at most 16 rows and the partial-sum and SwiGLU epilogues (got %d rows, epilogue %d)", M, epilogue);
     if (kernel == KERNEL_STREAMING && M > 256 && epilogue != EPI_SLABS && epilogue != EPI_SWIGLU) return fail(FG_ERR_INVALID_ARG, "bad epilogue");
     int split = 1;
     if (epilogue == EPI_SLABS) {
         if (split_k > 0) split = split_k;
         else if (kernel == KERNEL_FEW) split = gemm_mfma_skinny_split_for(M, N, K);
+        else if (kernel == KERNEL_DECODE) split = gemm_mfma_decode_split_for(M, N, K);
         else if (kernel == KERNEL_BIG) split = gemm_mfma_big_split_for(M, N, K);
         else split = choose_split(M, N, K, 256, 256);
         if (split > K / 64) split = K / 64;
@@ -302,6 +314,7 @@ int32_t launch_gemm_mfma(int32_t dtype, const void *x, const void *wp, void *out
     }
     if (split_used) *split_used = split;
     if (kernel == KERNEL_FEW) return launch_gemm_mfma_skinny(dtype, x, wp, out, M, N, K, epilogue, split, st);
+    if (kernel == KERNEL_DECODE) return launch_gemm_mfma_decode(dtype, x, wp, out, M, N, K, epilogue, split, st);
     if (kernel == KERNEL_BIG) return launch_gemm_mfma_big(dtype, x, wp, out, M, N, K, epilogue, split, variant == 3 ? 8 : (variant == 4 ? 4 : (variant == 5 ? 5 : 0)), epi, st);
     return dtype == FG_BF16 ? launch_gemm_typed<bf16_t>(x, wp, out, M, N, K, epilogue, split, st)
                             : launch_gemm_typed<f16_t>(x, wp, out, M, N, K, epilogue, split, st);

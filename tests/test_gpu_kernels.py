@@ -283,3 +283,45 @@ def test_lm_head_with_the_selection_in_its_epilogue(fg, dtype, M, V, K):
     # the library's own one-pass kernel on the same logits agrees too
     t2, l2 = fg.fg_topk_logp(slabs[0], K)
     assert torch.equal(t2, tok)
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 32, 64), (5, 64, 192), (8, 3584, 3584), (13, 96, 640), (16, 3584, 18944), (9, 160, 384), (8, 37888, 3584),
+                                   (15, 16384 + 32, 256)])
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+def test_decode_gemm_partial_sums_and_swiglu(fg, M, N, K, dtype):
+    """The decode-shape kernel (at most 16 rows, forced through fg_gemm's variant 6) against a double-precision product
+    of the same operands: partial-sum slabs with the library's k split, none, and one that leaves empty splits; SwiGLU
+    (ragged band groups included); bitwise repeatable."""
+    print(f"decode gemm {dtype} M={M} N={N} K={K}", flush=True)
+    code, dt = CODES[dtype], TD[dtype]
+    g = torch.Generator().manual_seed(M * 11 + N + K)
+    x, w = bf16_randn((M, K), g, dt=dt), bf16_randn((N, K), g, 0.05, dt=dt)
+    ref = x.double() @ w.double().T
+    scale = ref.abs().max().item()
+    wp = fg.fg_pack_weight(code, w.cuda())
+    for split in (0, 1, 3, 16):
+        out, used = gemm_sum(fg, code, x.cuda(), wp, N, split_k=split, variant=6)
+        torch.cuda.synchronize()
+        assert (out.double().cpu() - ref).abs().max().item() <= 2e-5 * scale + 1e-4, (split, used)
+    a, _ = gemm_sum(fg, code, x.cuda(), wp, N, variant=6)
+    b, _ = gemm_sum(fg, code, x.cuda(), wp, N, variant=6)
+    assert torch.equal(a, b)
+    if N % 64 == 0:
+        F = N // 2
+        wg, wu = w[:F], w[F:]
+        wp2 = fg.fg_pack_weight(code, wg.cuda(), wu.cuda())
+        refs = torch.nn.functional.silu(x.double() @ wg.double().T) * (x.double() @ wu.double().T)
+        act, _ = fg.fg_gemm(code, x.cuda(), wp2, N, epilogue=1, variant=6)
+        torch.cuda.synchronize()
+        err = (act.double().cpu() - refs).abs()
+        assert (err <= 2 ** -8 * refs.abs() + 1e-3).all(), err.max().item()
+
+
+def test_decode_gemm_rejects_shapes_it_does_not_take(fg):
+    x = torch.zeros((17, 128), dtype=torch.bfloat16, device="cuda")
+    w = fg.fg_pack_weight(1, torch.zeros((32, 128), dtype=torch.bfloat16, device="cuda"))
+    with pytest.raises(fg.FgError):
+        fg.fg_gemm(1, x, w, 32, variant=6)                       # 17 rows
+    h = torch.zeros((8, 32), dtype=torch.float32, device="cuda")
+    with pytest.raises(fg.FgError):
+        fg.fg_gemm(1, x[:8], w, 32, epilogue=3, out=h, variant=6)  # no residual epilogue
