@@ -22,11 +22,11 @@ if ROOT not in sys.path:
 
 PEAK_HBM = 8.0e12          # B/s, MI355X HBM3E
 PEAK_MFMA = 2516.6e12      # flop/s, dense bf16 / fp16 MFMA
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this benchmark,
-# scaled by what the same counters read for a plain 1 GiB copy.
-# A recorded measurement, keyed by (workload, rows M); other workloads report null.
-MEASURED_TRAFFIC = {("cfg4", 2048): 815.4e6 + 77.6e6,      # profiles/bench_cfg4_b256_n8_hbm_traffic_pmc.txt
-                    ("b8", 8): 273.6e6 + 0.3e6}            # profiles/verify_b8_n1_memory_bound_regime.txt
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of that kernel at the
+# benchmark's shape (bench.py --gemm gate_up --rows M), scaled by what the same counters read for the library's copy probe
+# (FETCH_SIZE x 2.00, WRITE_SIZE x 1.00).  A recorded measurement, keyed by (workload, rows M); other workloads report null.
+MEASURED_TRAFFIC = {("cfg4", 2048): 1578.3e6 + 77.6e6,     # profiles/bench_cfg4_b256_n8_hbm_traffic_pmc.txt
+                    ("b8", 8): 277.3e6 + 0.3e6}            # same file, rows "M=8"
 
 
 def model_bytes_flops(model, M, lengths, N):
@@ -447,6 +447,30 @@ def gemm_kernel_bench(args):
                       "mfma_frac": flops / ts[0] / PEAK_MFMA, "weight_stream_GBps": byts / ts[0] / 1e9}))
 
 
+def attention_kernel_bench(args):
+    """--attention: the tree attention of one layer on the workload's paged cache (B, N, KV lengths of --workload),
+    launched --reps times through the kernel-level entry point, layers taken in turn so that K/V come from HBM.  The
+    in-round nodes' K/V cells hold whatever the cache fill left there: their values do not matter to the timing."""
+    import torch
+    import paper_2509_21792_amd as fg
+    wl = Workload(args.workload, args.dtype, B=args.B or None, N=args.N or None, verbose=True, with_draft=False)
+    m = wl.model
+    td = torch.bfloat16 if args.dtype == "bf16" else torch.float16
+    g = torch.Generator(device="cuda").manual_seed(0)
+    q = torch.randn((wl.B * wl.N, m["n_q_heads"] * m["head_dim"]), generator=g, device="cuda").to(td)
+    it = [0]
+
+    def f():
+        fg.fg_attention(wl.kv, it[0] % m["n_layers"], wl.slot, wl.parent_d, wl.B, wl.N, m["n_q_heads"], q, max_seq_len=wl.max_seq_len)
+        it[0] += 1
+    ts = time_each(torch, f, args.reps, 5)
+    kv_bytes = float(wl.lengths.sum()) * 2 * m["n_kv_heads"] * m["head_dim"] * 2
+    print(json.dumps({"metric": "tree attention of one layer (kernel-level entry point)", "n_gpus": 1, "dtype": args.dtype, "data": "synthetic",
+                      "config": {"workload": f"{wl.name}: B={wl.B} N={wl.N}, KV lengths U[{int(wl.lengths.min())},{int(wl.lengths.max())}]"},
+                      "us": spread(ts), "kv_bytes_per_layer": kv_bytes, "kv_GBps": kv_bytes / ts[0] / 1e9,
+                      "hbm_frac": kv_bytes / ts[0] / PEAK_HBM}))
+
+
 def train_bench(args):
     """--train: one step of online draft learning (Sec. 4.2) on the 7B-class draft head: loss + gradients of B chains of T
     cached (token, feature) entries and the AdamW update, fp32.  Tokens/s of training entries and the fraction of the fp32
@@ -578,6 +602,7 @@ def main():
                     help="the metric's range: B = 8 ... 256 on the 7B-class target, each with the shape Eq. 1-3 give")
     ap.add_argument("--gemm", default="", choices=["", "qkv", "o", "o_residual", "gate_up", "down", "down_residual", "lm_head", "lm_head_topk"],
                     help="time one GEMM of the 7B-class layer through the kernel-level entry point and exit")
+    ap.add_argument("--attention", action="store_true", help="time the tree attention of one layer on the workload's cache and exit")
     ap.add_argument("--rows", type=int, default=2048, help="--gemm: rows M")
     ap.add_argument("--reps", type=int, default=56, help="--gemm: timed launches")
     ap.add_argument("--variant", type=int, default=0, help="--gemm: 0 = the library's kernel choice, 1-5 force one (see fastgrpo.h)")
@@ -598,6 +623,9 @@ def main():
     import paper_2509_21792_amd as fg
     fg.lib()
     assert torch.cuda.is_available(), "no GPU: the HIP path has no CPU fallback"
+    if args.attention:
+        attention_kernel_bench(args)
+        return
     if args.gemm:
         gemm_kernel_bench(args)
         return
