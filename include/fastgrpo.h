@@ -313,8 +313,12 @@ int32_t fg_build_tree(const int32_t *cand_tok, const int32_t *cand_parent, const
 /*
  * Online draft learning (Sec. 4.2 "Draft Model Learning with Online Target Feedback"; Alg. 1, the draft training phase):
  * the draft head is trained on what the generation phase cached -- the tokens the target emitted and the target's
- * features.  Training computes in fp32 on fp32 master parameters, whatever type the generation path runs in; the
- * updated head reaches it by casting and re-packing the matrices (fg_pack_weight) into a new draft model.
+ * features.  Parameters, gradients, activations and the optimiser state are fp32, whatever type the generation path
+ * runs in; the updated head reaches it by casting and re-packing the matrices (fg_pack_weight) into a new draft model.
+ * cfg->dtype chooses how the step's matrix products are computed: FG_F32 exactly, in an fp32 GEMM (the parity mode);
+ * FG_BF16 on the matrix cores, both operands rounded to bf16 and accumulated in fp32 (6.4 times faster on the 7B-class
+ * head; gradients within a few per cent of the exact ones; B * T, d, F, Hq hd, (Hq + 2 Hkv) hd and vocab multiples of 64,
+ * FG_ERR_SHAPE otherwise); FG_F16 is refused: backward values underflow fp16.
  *
  * fg_draft_params: the head's parameters, row-major [out, in] fp32 device arrays the caller owns: fc [d, 2d],
  * wqkv [(Hq + 2 Hkv) hd, d] (q rows, k rows, v rows), wo [d, Hq hd], w_gate / w_up [F, d], w_down [d, F], the two norm
