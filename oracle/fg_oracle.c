@@ -43,6 +43,18 @@
  *   draft head internals (fc + one layer, no final norm): fixed by this
  *   build's reading of Sec. 2 only -- "parity unpinned" beyond the shared
  *   layer code.
+ *
+ * Rounding twin (cfg.act_round = 1: bf16, 2: fp16; 0 = the oracle proper, which
+ * every tolerance is quoted against).  The paper fixes no arithmetic; a 16-bit
+ * pipeline stores its activations in 16 bits between the steps of a layer, and
+ * the twin does the same with exact arithmetic in between: the outputs of both
+ * RMS norms, q / k / v after RoPE (hence the cached K and V), the attention
+ * output, the SwiGLU output and the vector handed to the LM head are rounded to
+ * nearest-even; the residual stream, scores, softmax weights and all sums are
+ * not.  It is a second reference for 16-bit implementations, tight where the
+ * first cannot be (bf16 rounding alone moves a 28-layer model's logits by 0.2).
+ * Pins: orc_round_act against torch's casts (ties, subnormals, range ends); the
+ * twin against the torch decoder of the chain pin with casts at the same places.
  */
 #include <math.h>
 #include <stdint.h>
@@ -56,7 +68,7 @@ typedef ORC_REAL real;
 
 typedef struct {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
-    int32_t pad_;
+    int32_t act_round;   /* 0: none (the oracle proper); 1 / 2: activations rounded to bf16 / fp16 between the layer's steps */
     double rms_eps, rope_theta;
 } orc_cfg;
 
@@ -78,6 +90,44 @@ typedef struct {
 enum { ORC_OK = 0, ORC_ERR_ARG = -1, ORC_ERR_TREE = -2, ORC_ERR_CAP = -3 };
 
 int orc_sizeof_real(void) { return (int)sizeof(real); }
+
+/* ------------------------------------------------------------------------ */
+/* Round to the nearest bf16 / fp16 value, ties to even (the rounding twin). */
+/* ------------------------------------------------------------------------ */
+static real round_act(real x, int mode)
+{
+    if (mode == 0) return x;
+    float f = (float)x;
+    if (!(f == f) || f == 0.0f) return (real)f;
+    if (mode == 1) {                       /* bf16: the top 16 bits of the fp32 pattern */
+        uint32_t u;
+        memcpy(&u, &f, 4);
+        u += 0x7fffu + ((u >> 16) & 1u);
+        u &= 0xffff0000u;
+        memcpy(&f, &u, 4);
+        return (real)f;
+    }
+    /* fp16 (from the fp32 value, as a cast does): 11 significant bits down to 2^-14, multiples of 2^-24 below,
+       infinity from 65504 + half an ulp on */
+    double a = fabs((double)f);
+    if (a >= 65520.0) return (real)(f > 0 ? INFINITY : -INFINITY);
+    int e;
+    frexp(a, &e);                          /* a = m 2^e, m in [0.5, 1) */
+    double ulp = ldexp(1.0, (e - 11 > -24) ? e - 11 : -24);
+    double r = nearbyint((double)f / ulp) * ulp;   /* default rounding mode: ties to even */
+    return (real)r;
+}
+int orc_round_act(real *x, int64_t n, int32_t mode)
+{
+    if (mode < 0 || mode > 2) return ORC_ERR_ARG;
+    for (int64_t i = 0; i < n; i++) x[i] = round_act(x[i], mode);
+    return ORC_OK;
+}
+static void round_all(real *x, size_t n, int mode)
+{
+    if (mode)
+        for (size_t i = 0; i < n; i++) x[i] = round_act(x[i], mode);
+}
 
 #ifdef _OPENMP
 #include <omp.h>
@@ -252,6 +302,7 @@ static int decoder_layers(const orc_cfg *c, const orc_weights *w, int B, int n_p
         real *kl = kc + (size_t)l * n_slots * cap * Hkv * hd;
         real *vl = vc + (size_t)l * n_slots * cap * Hkv * hd;
         rmsnorm(a, h, w->norm_attn[l], M, d, c->rms_eps);
+        round_all(a, (size_t)M * d, c->act_round);
         matmul_nt(qkv, a, w->wqkv[l], M, qkv_dim, d);
         /* RoPE on q and k heads; write k, v of each new node into its slot */
         for (int b = 0; b < B; b++)
@@ -260,6 +311,7 @@ static int decoder_layers(const orc_cfg *c, const orc_weights *w, int B, int n_p
                 int64_t pos = (int64_t)len[b] + depth[b * n_tot + i];
                 real *row = qkv + (size_t)(b * N_new + j) * qkv_dim;
                 for (int hh = 0; hh < Hq + Hkv; hh++) rope_head(row + (size_t)hh * hd, hd, pos, c->rope_theta);
+                round_all(row, (size_t)qkv_dim, c->act_round);
                 size_t at = ((size_t)sl[b] * cap + (size_t)len[b] + i) * Hkv * hd;
                 memcpy(kl + at, row + (size_t)Hq * hd, sizeof(real) * Hkv * hd);
                 memcpy(vl + at, row + (size_t)(Hq + Hkv) * hd, sizeof(real) * Hkv * hd);
@@ -301,6 +353,7 @@ static int decoder_layers(const orc_cfg *c, const orc_weights *w, int B, int n_p
                         real p = sc[t] / den;
                         for (int e = 0; e < hd; e++) o[e] += p * vv[e];
                     }
+                    round_all(o, (size_t)hd, c->act_round);
                 }
             }
             free(sc); free(key);
@@ -308,12 +361,13 @@ static int decoder_layers(const orc_cfg *c, const orc_weights *w, int B, int n_p
         matmul_nt(proj, att, w->wo[l], M, d, (int64_t)Hq * hd);
         for (size_t t = 0; t < (size_t)M * d; t++) h[t] += proj[t];
         rmsnorm(a, h, w->norm_ffn[l], M, d, c->rms_eps);
+        round_all(a, (size_t)M * d, c->act_round);
         matmul_nt(gate, a, w->w_gate[l], M, F, d);
         matmul_nt(up, a, w->w_up[l], M, F, d);
         for (size_t t = 0; t < (size_t)M * F; t++) {
             real g = gate[t];
             real silu = g / ((real)1 + (real)exp((double)-g));
-            gate[t] = silu * up[t];
+            gate[t] = round_act(silu * up[t], c->act_round);
         }
         matmul_nt(proj, gate, w->w_down[l], M, d, F);
         for (size_t t = 0; t < (size_t)M * d; t++) h[t] += proj[t];
@@ -363,6 +417,7 @@ int orc_tree_forward(const orc_cfg *c, const orc_weights *w, int32_t is_draft, i
     if (rc == ORC_OK) {
         if (!is_draft) rmsnorm(hidden, h, w->final_norm, M, d, c->rms_eps);
         else memcpy(hidden, h, sizeof(real) * (size_t)M * d);
+        round_all(hidden, (size_t)M * d, c->act_round);
         if (logits) matmul_nt(logits, hidden, w->lm_head, M, c->vocab, d);
     }
     free(h);

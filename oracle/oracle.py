@@ -16,7 +16,7 @@ _I32P = C.POINTER(C.c_int32)
 
 class _Cfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
-                ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab", "pad_")] + \
+                ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab", "act_round")] + \
                [("rms_eps", C.c_double), ("rope_theta", C.c_double)]
 
 
@@ -42,13 +42,16 @@ class OracleError(RuntimeError):
 class Model:
     """Weights of a target (or a draft head) held in the oracle's precision."""
 
-    def __init__(self, orc, cfg, weights, embed_from=None):
+    def __init__(self, orc, cfg, weights, embed_from=None, act_round=None):
+        """act_round: None for the oracle proper; "bf16" / "fp16" for its rounding twin (activations stored in 16 bits
+        between the steps of a layer, exact arithmetic in between)."""
         self.cfg = dict(cfg)
         self.real = orc.real
+        self.act_round = {None: 0, "bf16": 1, "fp16": 2}[act_round]
         conv = lambda a: np.ascontiguousarray(a, dtype=orc.real)
         self._keep = []
         self.c = _Cfg(cfg["n_layers"], cfg["d_model"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"],
-                      cfg["d_ffn"], cfg["vocab"], 0, cfg.get("rms_eps", 1e-6), cfg.get("rope_theta", 10000.0))
+                      cfg["d_ffn"], cfg["vocab"], self.act_round, cfg.get("rms_eps", 1e-6), cfg.get("rope_theta", 10000.0))
         w = _Weights()
         src = embed_from if embed_from is not None else None
         for name in ("embed", "lm_head", "final_norm", "fc"):
@@ -123,8 +126,14 @@ class Oracle:
         return k.value
 
     # -- forward ---------------------------------------------------------------------------------
-    def model(self, cfg, weights, embed_from=None):
-        return Model(self, cfg, weights, embed_from)
+    def model(self, cfg, weights, embed_from=None, act_round=None):
+        return Model(self, cfg, weights, embed_from, act_round)
+
+    def round_act(self, x, kind):
+        """x rounded to the nearest bf16 / fp16 value, ties to even (what the rounding twin applies)."""
+        x = np.array(x, dtype=self.real)
+        self._check(self.lib.orc_round_act(_ptr(x), C.c_int64(x.size), C.c_int32({"bf16": 1, "fp16": 2}[kind])), "orc_round_act")
+        return x
 
     def cache(self, cfg, B, cap):
         return KVCache(self, cfg, B, cap)

@@ -17,8 +17,11 @@ SMALL = dict(name="small", n_layers=2, d_model=64, n_q_heads=4, n_kv_heads=2, he
              rms_eps=1e-6, rope_theta=10000.0, dtype="fp32")
 
 
-def torch_chain_logits(cfg, w, tokens):
-    """A Llama-style decoder over full sequences with torch library ops in fp64: tokens [B, T] -> logits, feature."""
+def torch_chain_logits(cfg, w, tokens, store=None):
+    """A Llama-style decoder over full sequences with torch library ops in fp64: tokens [B, T] -> logits, feature.
+    store: None, or the 16-bit torch dtype the activations are stored in between the steps of a layer (a cast and back
+    at the outputs of both norms, q / k / v after RoPE, the attention output, the SwiGLU output, the LM head's input)."""
+    st = (lambda t: t) if store is None else (lambda t: t.to(store).to(torch.float64))
     d, Hq, Hkv, hd = cfg["d_model"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"]
     t64 = lambda a: torch.as_tensor(np.asarray(a), dtype=torch.float64)
     B, T = tokens.shape
@@ -33,19 +36,19 @@ def torch_chain_logits(cfg, w, tokens):
         return torch.cat([x1 * cos - x2 * sin, x2 * cos + x1 * sin], dim=-1)
 
     for lay in w["layers"]:
-        a = F.rms_norm(h, (d,), t64(lay["norm_attn"]), cfg["rms_eps"])
+        a = st(F.rms_norm(h, (d,), t64(lay["norm_attn"]), cfg["rms_eps"]))
         qkv = F.linear(a, t64(lay["wqkv"]))
         q, k, v = qkv.split([Hq * hd, Hkv * hd, Hkv * hd], dim=-1)
-        q = rope(q.view(B, T, Hq, hd).transpose(1, 2))
-        k = rope(k.view(B, T, Hkv, hd).transpose(1, 2))
-        v = v.view(B, T, Hkv, hd).transpose(1, 2)
+        q = st(rope(q.view(B, T, Hq, hd).transpose(1, 2)))
+        k = st(rope(k.view(B, T, Hkv, hd).transpose(1, 2)))
+        v = st(v.view(B, T, Hkv, hd).transpose(1, 2))
         k = k.repeat_interleave(Hq // Hkv, dim=1)
         v = v.repeat_interleave(Hq // Hkv, dim=1)
-        o = F.scaled_dot_product_attention(q, k, v, is_causal=True)
+        o = st(F.scaled_dot_product_attention(q, k, v, is_causal=True))
         h = h + F.linear(o.transpose(1, 2).reshape(B, T, Hq * hd), t64(lay["wo"]))
-        f = F.rms_norm(h, (d,), t64(lay["norm_ffn"]), cfg["rms_eps"])
-        h = h + F.linear(F.silu(F.linear(f, t64(lay["w_gate"]))) * F.linear(f, t64(lay["w_up"])), t64(lay["w_down"]))
-    feat = F.rms_norm(h, (d,), t64(w["final_norm"]), cfg["rms_eps"])
+        f = st(F.rms_norm(h, (d,), t64(lay["norm_ffn"]), cfg["rms_eps"]))
+        h = h + F.linear(st(F.silu(F.linear(f, t64(lay["w_gate"]))) * F.linear(f, t64(lay["w_up"]))), t64(lay["w_down"]))
+    feat = st(F.rms_norm(h, (d,), t64(w["final_norm"]), cfg["rms_eps"]))
     return F.linear(feat, t64(w["lm_head"])).numpy(), feat.numpy()
 
 
@@ -68,6 +71,43 @@ def test_chain_equals_torch_causal_decoder(orc64, small_w):
     assert np.abs(logits - ref_logits).max() < 1e-11
     assert np.abs(feat - ref_feat).max() < 1e-11
     assert (cache.len == T).all()
+
+
+@pytest.mark.parametrize("kind,store", [("bf16", torch.bfloat16), ("fp16", torch.float16)])
+def test_round_act_equals_torch_casts(orc32, orc64, kind, store):
+    """The rounding the twin applies is torch's cast: random values over the format's range, exact ties (which go to the
+    even neighbour), fp16 subnormals and the ends of its range."""
+    rng = np.random.default_rng(0)
+    x = (rng.standard_normal(20000) * np.exp(rng.uniform(-18, 11, 20000))).astype(np.float32)
+    ties = np.array([1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, 1 + 2.0 ** -11, 1 + 3 * 2.0 ** -11, 2.0 ** -25, 3 * 2.0 ** -25, 2.0 ** -24,
+                     65504.0, 65519.0, 65520.0, 70000.0, -65520.0, 0.0, -0.0, 1e-8, 6.1e-5, 5.96e-8], dtype=np.float32)
+    x = np.concatenate([x, ties, -ties])
+    want = torch.as_tensor(x).to(store).to(torch.float32).numpy()
+    for orc in (orc32, orc64):
+        got = orc.round_act(x, kind).astype(np.float32)
+        assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("kind,store", [("bf16", torch.bfloat16), ("fp16", torch.float16)])
+def test_rounding_twin_equals_torch_decoder_with_casts(orc64, small_w, kind, store):
+    """The twin rounds at exactly the places the torch decoder with casts does: same logits, same feature, to the fp64
+    noise of the arithmetic in between; it differs from the oracle proper by about what that many roundings predict; what
+    it hands to the LM head is representable in the format."""
+    B, T = 3, 11
+    tokens = gen.make_prompts(B, 1, T, SMALL["vocab"], seed=5)
+    model = orc64.model(SMALL, small_w, act_round=kind)
+    cache = orc64.cache(SMALL, B, T + 4)
+    feat, logits = loop.prefill(orc64, model, cache, tokens)
+    ref_logits, ref_feat = torch_chain_logits(SMALL, small_w, tokens, store=store)
+    assert np.abs(logits - ref_logits).max() < 1e-10
+    assert np.abs(feat - ref_feat).max() < 1e-10
+    assert np.array_equal(orc64.round_act(feat, kind), feat)
+    k = np.asarray(cache.k)[:, :, :T]
+    assert np.array_equal(orc64.round_act(k, kind), k)
+    plain_logits, _ = torch_chain_logits(SMALL, small_w, tokens)
+    rel = np.sqrt(np.mean((logits - plain_logits) ** 2)) / np.sqrt(np.mean(plain_logits ** 2))
+    u = (2.0 ** -8 if kind == "bf16" else 2.0 ** -11) / np.sqrt(3.0)
+    assert 0.3 * u < rel < 6 * u * np.sqrt(5 * SMALL["n_layers"] + 1), rel
 
 
 def test_incremental_decode_equals_torch(orc64, small_w):
