@@ -72,6 +72,20 @@ class Model:
         self.w = w
 
 
+def _twin(self, act_round):
+    """The same weights (shared, not copied) seen through the rounding twin (or, with None, the oracle proper)."""
+    import copy
+    t = copy.copy(self)
+    t.act_round = {None: 0, "bf16": 1, "fp16": 2}[act_round]
+    cfg = self.cfg
+    t.c = _Cfg(cfg["n_layers"], cfg["d_model"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["d_ffn"], cfg["vocab"],
+               t.act_round, cfg.get("rms_eps", 1e-6), cfg.get("rope_theta", 10000.0))
+    return t
+
+
+Model.twin = _twin
+
+
 class KVCache:
     """Contiguous per-sequence cache [n_layers][B][cap][Hkv][hd] and lengths [B]."""
 

@@ -120,10 +120,15 @@ def compare_rows(got_logits, want_logits, tol, got_argmax=None, margin=MARGIN):
     return stats
 
 
-def oracle_verify(state, tokens, parent, n_prev=0):
-    """The oracle's forward over the subset rows; returns (hidden [S*N, d], logits [S*N, V])."""
+TWIN_RMS_RATIO = 1.25    # rms logits error allowed, in units of the rounding twin's own rms error on the same rows
+
+
+def oracle_verify(state, tokens, parent, n_prev=0, twin=None):
+    """The oracle's forward over the subset rows; returns (hidden [S*N, d], logits [S*N, V]).  twin: "bf16" / "fp16" runs
+    the oracle's rounding twin instead (activations stored in 16 bits between the steps of a layer)."""
     sub = state.subset
-    return state.pair.orc.tree_forward(state.pair.om, state.ocache, tokens[sub], parent[sub], n_prev=n_prev)
+    om = state.pair.om.twin(twin) if twin else state.pair.om
+    return state.pair.orc.tree_forward(om, state.ocache, tokens[sub], parent[sub], n_prev=n_prev)
 
 
 def smoke_check():
