@@ -25,6 +25,7 @@ PEAK_MFMA = 2516.6e12      # flop/s, dense bf16 / fp16 MFMA
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of that kernel at the
 # benchmark's shape (bench.py --gemm gate_up --rows M), scaled by what the same counters read for the library's copy probe
 # (FETCH_SIZE x 2.00, WRITE_SIZE x 1.00).  A recorded measurement, keyed by (workload, rows M); other workloads report null.
+MEASURED_C_PEAK = 64       # knee of the 7B-class latency curve on the log2 batch axis (bench.py --sweep / --gen measure it afresh)
 MEASURED_TRAFFIC = {("cfg4", 2048): 1578.3e6 + 77.6e6,     # profiles/bench_cfg4_b256_n8_hbm_traffic_pmc.txt
                     ("b8", 8): 277.3e6 + 0.3e6}            # same file, rows "M=8"
 
@@ -605,7 +606,7 @@ def main():
     ap.add_argument("--attention", action="store_true", help="time the tree attention of one layer on the workload's cache and exit")
     ap.add_argument("--rows", type=int, default=2048, help="--gemm: rows M")
     ap.add_argument("--reps", type=int, default=56, help="--gemm: timed launches")
-    ap.add_argument("--variant", type=int, default=0, help="--gemm: 0 = the library's kernel choice, 1-5 force one (see fastgrpo.h)")
+    ap.add_argument("--variant", type=int, default=0, help="--gemm: 0 = the library's kernel choice, 1-6 force one (see fastgrpo.h)")
     ap.add_argument("--split", type=int, default=0, help="--gemm: k splits of the partial-sum epilogue (0 = the library's choice)")
     ap.add_argument("--cycle", type=int, default=8, help="--gemm: number of different weight matrices used in turn")
     ap.add_argument("--train", default="", choices=["", "bf16", "fp32"],
@@ -654,6 +655,8 @@ def main():
             t_step, emitted = time_steps(torch, wl.step, args.steps, args.warmup)
             return dict(ms_per_step=t_step * 1e3, value=emitted / t_step), wl
         acct = model_bytes_flops(model, M, wl.lengths.astype(np.float64), wl.N)
+        from synth import configs as cfgs_
+        pd_ = cfgs_.PLAN_DEFAULTS
         v_spread = time_each(torch, wl.verify_only, max(args.steps, 30), args.warmup)
         d_spread = time_each(torch, wl.draft, max(args.steps, 30), 2) if wl.draft_ready else None
         t_verify = v_spread[0]
@@ -727,6 +730,11 @@ def main():
             "attn_frac": (acct["kv_bytes"] + M * 2.0 * model["n_q_heads"] * model["head_dim"] * 2 * model["n_layers"]) / (attn_ms * 1e-3) / PEAK_HBM if attn_ms else None,
             "gemm_ms": gemm_ms, "attn_ms": attn_ms,
             "roofline": roof,
+            # the configuration pins N_verify (C_peak = B * N in Eq. 1); what Eq. 1-3 give this batch for the C_peak measured
+            # on this chip and model (bench.py --sweep, profiles/sweep_7b_b8_to_b256_rule_shapes.txt) stands beside it
+            "shape_for_measured_c_peak": dict(zip(("c_peak", "N_verify", "K_draft", "L_draft"),
+                                                  (MEASURED_C_PEAK,) + tuple(fg.fg_plan(wl.B, float(MEASURED_C_PEAK), pd_["alpha"], pd_["K_max"],
+                                                                                        pd_["L_max"], pd_["N_cap"])))),
         }
         if args.graph:
             t_graph, emitted_g = time_steps(torch, wl.step_graph, args.steps, args.warmup)
