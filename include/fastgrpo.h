@@ -393,6 +393,8 @@ int32_t fg_lm_head_topk(int32_t dtype, const void *x, const void *lm_head_packed
  * the stage the first announces, so the stages of a call add up to the call.  fg_model_profile_read waits for the last
  * event, fills ms[FG_STAGE_COUNT] and launches[FG_STAGE_COUNT] (host arrays) and starts a new collection.  A model is
  * driven from one thread (one stream) at a time, and so is its timing.  Not to be enabled under graph capture.
+ * enable: 0 off; 1 every stage; 2 + s only stage s (one event before its launches and one after: the cheapest way to time
+ * one kernel inside a timed region -- an event costs a microsecond or two of the stream's time).
  */
 enum { FG_STAGE_END = -1, FG_STAGE_PREP = 0, FG_STAGE_NORM, FG_STAGE_QKV, FG_STAGE_ROPE, FG_STAGE_ATTENTION, FG_STAGE_O,
        FG_STAGE_GATE_UP, FG_STAGE_SWIGLU, FG_STAGE_DOWN, FG_STAGE_LM_HEAD, FG_STAGE_SELECT, FG_STAGE_FC, FG_STAGE_COUNT };

@@ -557,8 +557,10 @@ def fg_draft_adamw(cfg, w, grad, m, v, lr, step, beta1=0.9, beta2=0.999, eps=1e-
 STAGES = ["prep", "norm", "qkv", "rope", "attention", "o", "gate_up", "swiglu", "down", "lm_head", "select", "fc"]
 
 
-def fg_model_profile(model, enable, max_marks=1 << 16):
-    _check(lib().fg_model_profile(model.handle, int(enable), max_marks))
+def fg_model_profile(model, enable, max_marks=1 << 16, only=None):
+    """enable: off / every stage; only="gate_up" (a name from STAGES): bracket that stage alone."""
+    code = int(bool(enable)) if only is None or not enable else 2 + STAGES.index(only)
+    _check(lib().fg_model_profile(model.handle, code, max_marks))
 
 
 def fg_model_profile_read(model):

@@ -77,6 +77,7 @@ using namespace fg;
 // first one announces.
 struct StageProf {
     bool on = false;
+    int only = -1;               // >= 0: only this stage is bracketed
     std::vector<hipEvent_t> ev;
     std::vector<int8_t> stage;   // stage[i]: what runs after event i (-1: nothing, the end of an entry point)
     size_t used = 0;
@@ -97,6 +98,7 @@ inline void mark(const fg_model *m, int stage, hipStream_t st)
 {
     StageProf &p = const_cast<fg_model *>(m)->prof;
     if (!p.on || p.used >= p.ev.size()) return;
+    if (p.only >= 0 && stage != p.only && !(p.used > 0 && p.stage[p.used - 1] == p.only)) return;
     (void)hipEventRecord(p.ev[p.used], st);
     p.stage[p.used++] = (int8_t)stage;
 }
@@ -881,7 +883,10 @@ int32_t fg_model_profile(fg_model *m, int32_t enable, int32_t max_marks)
     StageProf &p = m->prof;
     p.on = false;
     p.used = 0;
+    p.only = -1;
     if (!enable) return FG_OK;
+    if (enable < 0 || enable >= 2 + FG_STAGE_COUNT) return fail(FG_ERR_INVALID_ARG, "fg_model_profile: enable is 0, 1 or 2 + a stage");
+    if (enable >= 2) p.only = enable - 2;
     if (max_marks < 2 || max_marks > (1 << 22)) return fail(FG_ERR_INVALID_ARG, "fg_model_profile: bad max_marks");
     while ((int)p.ev.size() < max_marks) {
         hipEvent_t e;
@@ -901,7 +906,7 @@ int32_t fg_model_profile_read(fg_model *m, double *ms, int32_t *launches)
     if (p.used > 0) FG_HIP(hipEventSynchronize(p.ev[p.used - 1]));
     for (size_t i = 0; i + 1 < p.used; i++) {
         const int sg = p.stage[i];
-        if (sg < 0 || sg >= FG_STAGE_COUNT) continue;
+        if (sg < 0 || sg >= FG_STAGE_COUNT || (p.only >= 0 && sg != p.only)) continue;
         float t = 0.f;
         FG_HIP(hipEventElapsedTime(&t, p.ev[i], p.ev[i + 1]));
         ms[sg] += t;
