@@ -41,7 +41,7 @@ constexpr int waitcnt_imm(int vm, int lgkm) { return (vm & 15) | (7 << 4) | ((lg
 // rotate-half pair of its rows.  q and k rows leave through a 4 KiB transposing tile in LDS (one per wave, 32 rows at a
 // time): the accumulator layout has a lane on one column of 16 rows, the stores want 16 contiguous bytes of one row --
 // 8 consecutive head dims, which are contiguous in q rows and in both K page layouts.  LDS serves a wave's accesses in
-// order, so the tile needs no barrier.  v (pages transposed: consecutive dims 32 bytes apart) is stored directly.
+// order, so the tile needs no barrier.  v takes the same tile the other way round (see there).
 template <typename T, int MT>
 __device__ __forceinline__ void epilogue_rope(f32x16_t (&acc)[MT][2], const GemmEpi &ep, int M, int row0, int nt0, int n_tiles,
                                               int lane, T *tile)
@@ -53,20 +53,40 @@ __device__ __forceinline__ void epilogue_rope(f32x16_t (&acc)[MT][2], const Gemm
     const int c = lane & 31, rh = (lane >> 5) * 4;
     const size_t page_elems = (size_t)16 * hd;
     if (head >= Hq + Hkv) {
-        const int hk = head - Hq - Hkv, e0 = ebase + c, e1 = e0 + half;
-        T *vp = reinterpret_cast<T *>(ep.v_pool);
+        // v: the pages are transposed ([dim][token], a dim's 16 tokens = 32 bytes), so what is contiguous in memory is a
+        // run of rows (the consecutive cache slots of one sequence's new nodes) at one dim.  Stored from the accumulator
+        // layout, a wave instruction puts 64 two-byte values into 64 different sectors and a sector is written once per
+        // node (33 MB of write traffic for 2 MB of v at 2048 rows, 18 us of this kernel's 94).  Through the tile, with
+        // the lanes of a store running over eight consecutive rows first, a sector gets its new tokens in one write.
+        // A row's columns are rotated by two per row in the tile, so that the eight rows a group of lanes reads lie in
+        // eight different banks.
+        const int hk = head - Hq - Hkv;
+        T *vp = reinterpret_cast<T *>(ep.v_pool) + ((size_t)ep.layer * ep.n_pages * Hkv + hk) * page_elems;
+        const int lr = lane & 7, lc = lane >> 3;
 #pragma unroll
-        for (int i = 0; i < MT; i++)
+        for (int i = 0; i < MT; i++) {
+            if (row0 + i * 32 >= M) break;
+            T *dst[4];   // where this lane's four rows of the tile go: the row's page and slot (nullptr: not appended)
+#pragma unroll
+            for (int a = 0; a < 4; a++) {
+                const int m = row0 + i * 32 + lr + 8 * a;
+                const int cell = m < M ? ep.dest[m] : -1;
+                dst[a] = cell >= 0 ? vp + (size_t)(cell >> 4) * Hkv * page_elems + (cell & 15) : nullptr;
+            }
 #pragma unroll
             for (int r = 0; r < 16; r++) {
-                const int m = row0 + i * 32 + 8 * (r >> 2) + rh + (r & 3);
-                const int cell = m < M ? ep.dest[m] : -1, page = cell >> 4, t = cell & 15;
-                if (cell >= 0) {   // -1: beyond the page table, not appended
-                    T *o = vp + (((size_t)ep.layer * ep.n_pages + page) * Hkv + hk) * page_elems + t;
-                    o[e0 * 16] = from_f<T>(acc[i][0][r]);
-                    o[e1 * 16] = from_f<T>(acc[i][1][r]);
-                }
+                const int rr = 8 * (r >> 2) + rh + (r & 3);
+                tile[rr * 64 + ((c + 2 * rr) & 63)] = from_f<T>(acc[i][0][r]);
+                tile[rr * 64 + ((32 + c + 2 * rr) & 63)] = from_f<T>(acc[i][1][r]);
             }
+#pragma unroll
+            for (int it = 0; it < 32; it++) {
+                const int a = it & 3, rr = lr + 8 * a, cc = lc + 8 * (it >> 2);
+                const T v = tile[rr * 64 + ((cc + 2 * rr) & 63)];
+                const int e = cc < 32 ? ebase + cc : ebase + half + cc - 32;
+                if (dst[a]) dst[a][e * 16] = v;
+            }
+        }
         return;
     }
     const bool is_q = head < Hq;
