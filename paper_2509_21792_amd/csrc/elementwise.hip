@@ -311,8 +311,8 @@ __global__ void swiglu_partials_kernel(const float *gu, int S, T *act, int M, in
     const float *row = gu + (size_t)m * 2 * F + 64 * t + j;
     const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
     const float4 g = slab_sum4(row, slab, S, zero), u = slab_sum4(row + 32, slab, S, zero);
-    store4<T>(act + (size_t)m * F + f, make_float4(g.x / (1.f + __expf(-g.x)) * u.x, g.y / (1.f + __expf(-g.y)) * u.y,
-                                                   g.z / (1.f + __expf(-g.z)) * u.z, g.w / (1.f + __expf(-g.w)) * u.w));
+    store4<T>(act + (size_t)m * F + f, make_float4(swiglu_f(g.x, u.x), swiglu_f(g.y, u.y),
+                                                   swiglu_f(g.z, u.z), swiglu_f(g.w, u.w)));
 }
 
 int32_t launch_swiglu_partials(int32_t dtype, const float *gu, int S, void *act, int M, int F, hipStream_t st)

@@ -93,7 +93,7 @@ __device__ __forceinline__ void store_tiles(f32x16_t (&acc)[MT][NT], void *__res
                     const int m = mrow0 + i * 32 + 8 * (r >> 2) + (r & 3);
                     if (m < M) {
                         const float g = acc[i][j][r], u = acc[i][j + 1][r];
-                        o[m * F + f] = from_f<T>(g / (1.f + __expf(-g)) * u);
+                        o[m * F + f] = from_f<T>(swiglu_f(g, u));
                     }
                 }
         }

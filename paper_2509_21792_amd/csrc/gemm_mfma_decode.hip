@@ -162,7 +162,7 @@ __global__ __launch_bounds__(DC_WAVES * 64) void gemm_mfma_decode_kernel(const T
                 reinterpret_cast<float *>(out)[((size_t)z * M + m) * N + b0 * 32 + col] = s[0][k];
             } else {
                 const float g = s[0][k], u = s[NSUM - 1][k];
-                reinterpret_cast<T *>(out)[(size_t)m * (N >> 1) + (b0 >> 1) * 32 + col] = from_f<T>(g / (1.f + __expf(-g)) * u);
+                reinterpret_cast<T *>(out)[(size_t)m * (N >> 1) + (b0 >> 1) * 32 + col] = from_f<T>(swiglu_f(g, u));
             }
         }
     }

@@ -184,7 +184,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 1 ? 4
                     for (int j = 0; j + 1 < NT; j += 2) {
                         if (ntile0 + j + 1 >= n_tiles) continue;
                         const int f = ((ntile0 + j) >> 1) * 32 + (lane & 31);
-                        reinterpret_cast<T *>(out)[(size_t)m * F + f] = from_f<T>(s[j][k] / (1.f + __expf(-s[j][k])) * s[j + 1][k]);
+                        reinterpret_cast<T *>(out)[(size_t)m * F + f] = from_f<T>(swiglu_f(s[j][k], s[j + 1][k]));
                     }
                 }
             }
