@@ -443,9 +443,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 4 ? 2
 // proportion (+9 %) for shorter blocks; every extra split adds an fp32 slab the consumer has to read back.  Measured
 // on the 7B-class shapes (us, 2048 rows): QKV 99 in 256-row blocks (144 tiles), 103 in 128-row blocks (288), against
 // 61 predicted for 160-row blocks (234 tiles, one round); O 92 / 55 (256 / 128 rows); down 414 / 241, 236 with two
-// splits of 256-row blocks.  The wide outputs (gate/up, LM head) have thousands of tiles: 128-row blocks, two to a CU,
-// each one's prologue and epilogue under the other's main loop, are 4 - 8 % faster up to 2048 rows (gate/up 486 against
-// 506 us at 2048 rows, 248 against 269 at 1024) and 2 % slower at 4096.
+// splits of 256-row blocks.  The wide outputs (gate/up, LM head) have thousands of tiles.  128-row blocks, two to a CU,
+// put each one's prologue and epilogue under the other's main loop but draw half as much again from L2 per flop
+// (53.0 M against 35.5 M line requests for gate/up at 2048 rows); 256-row blocks leave their epilogue exposed, which
+// an exact-division SwiGLU made expensive.  With the reciprocal-instruction SwiGLU the 256-row blocks win from 1280
+// rows on (gate/up: 294 against 310 us at 1280 rows, 461 against 486 at 2048, 886 against 927 at 4096) and lose
+// below (262 against 256 at 1024).
 // The residual and top-k epilogues exist for 128- and 160-row blocks only: with 256 accumulator registers per lane the
 // extra live values of those epilogues (the tile of h, the selection's scratch) do not fit and the compiler spills.
 struct BigPlan { int split, mt; };
@@ -454,7 +457,7 @@ static BigPlan plan_big(int M, int N, int K, int fixed_split, int fixed_mt, int 
 {
     const int n_bands = (N / 32 + 7) / 8, chunks = K / 64;
     if (!tall_blocks_ok(epilogue) && fixed_mt == 8) fixed_mt = 0;
-    if (N >= 16384 && fixed_mt <= 0) fixed_mt = (M <= 2048 || !tall_blocks_ok(epilogue)) ? 4 : 8;
+    if (N >= 16384 && fixed_mt <= 0) fixed_mt = (M < 1280 || !tall_blocks_ok(epilogue)) ? 4 : 8;
     BigPlan best{fixed_split > 0 ? fixed_split : 1, fixed_mt > 0 ? fixed_mt : 8};
     double best_cost = 1e30;
     static const int heights[3] = {8, 5, 4};
