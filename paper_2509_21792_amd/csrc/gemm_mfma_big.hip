@@ -1,4 +1,4 @@
-// Compute-bound shape of the 16-bit MFMA GEMM (more than 256 rows): out = X . W^T on (32 MT) x 256 tiles, MT = 8 or 4.
+// Compute-bound shape of the 16-bit MFMA GEMM (more than 256 rows): out = X . W^T on (32 MT) x 256 tiles, MT = 8, 5 or 4.
 //
 // Block = 4 waves side by side, each owning 32 MT rows x 64 columns (MT x 2 tiles of v_mfma_f32_32x32x16).  MT = 8
 // fills the register file with one wave per SIMD, so nothing hides a stall and both operands are requested two
