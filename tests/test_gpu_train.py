@@ -11,6 +11,10 @@ pytestmark = pytest.mark.gpu
 ODD = dict(name="odd", n_layers=1, d_model=72, n_q_heads=6, n_kv_heads=2, head_dim=12, d_ffn=100, vocab=260, rms_eps=1e-6,
            rope_theta=10000.0, dtype="fp32")
 TINY1 = configs.draft_of(configs.TINY)
+# grouped-query heads of 128 dims: the tiled attention kernels' other shape (two query heads per kv head, chains that end
+# inside a 16-position tile and cross a 64-key tile)
+GQA128 = dict(name="gqa128", n_layers=1, d_model=512, n_q_heads=4, n_kv_heads=2, head_dim=128, d_ffn=192, vocab=300, rms_eps=1e-6,
+              rope_theta=10000.0, dtype="fp32")
 
 
 @pytest.fixture(scope="module")
@@ -52,7 +56,8 @@ def dev(a):
 
 
 @pytest.mark.parametrize("name,cfg,B,T,n_valid", [("tiny", TINY1, 3, 37, [37, 20, 1]), ("odd", ODD, 2, 9, [9, 4]),
-                                                  ("tiles", TINY1, 5, 130, [130, 129, 64, 2, 100])])
+                                                  ("tiles", TINY1, 5, 130, [130, 129, 64, 2, 100]),
+                                                  ("gqa128", GQA128, 2, 70, [70, 33])])
 def test_training_loss_and_gradients_follow_the_oracle(fg, orc, name, cfg, B, T, n_valid):
     print(f"draft training gradients: {name}", flush=True)
     w, embed, lm_head, tokens, feat_in, feat_tgt, n_valid = make_case(fg, cfg, B, T, n_valid, 7)
