@@ -140,6 +140,8 @@ int32_t launch_gemm_mfma(int32_t dtype, const void *x, const void *wp, void *out
 bool gemm_mfma_fusable(int M, int N, int K, int kind);
 int32_t launch_gemm_f32(const float *x, const float *w, float *out, int M, int N, int K, hipStream_t st);
 int32_t launch_pack(int32_t dtype, const void *src, const void *src2, void *dst, int64_t n_out, int64_t n_in, hipStream_t st);
+int32_t launch_pack_cast_bf16(const float *src, void *dst, int64_t n_out, int64_t n_in, hipStream_t st);   // fp32 source, bf16 fragments
+int32_t launch_pack_cast_t_bf16(const float *src, void *dst, int64_t n_out, int64_t n_in, hipStream_t st); // src is [n_in, n_out]
 
 int32_t launch_embed(int32_t dtype, const void *embed, const int32_t *tokens, int vocab, float *h, int M, int d, hipStream_t st);
 int32_t launch_concat_embed(int32_t dtype, const void *embed, const int32_t *tokens, int vocab, const void *feat,

@@ -345,6 +345,68 @@ __global__ void pack_bf16_kernel(const bf16_t *src, const bf16_t *src2, uint4 *d
     dst[idx] = *reinterpret_cast<const uint4 *>(logical_row(src, src2, n, K) + k);
 }
 
+// the same fragment order straight from an fp32 matrix, rounded to bf16 on the way (draft training packs fp32 operands
+// for every product: one pass instead of a cast pass and a pack pass)
+__global__ void pack_cast_bf16_kernel(const float *src, uint4 *dst, int64_t N, int64_t K)
+{
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t total = (N / 32) * (K / 16) * 64;
+    if (idx >= total) return;
+    int lane = idx & 63;
+    int64_t tile = idx >> 6;
+    int64_t kt = tile % (K / 16), nt = tile / (K / 16);
+    int64_t n = nt * 32 + (lane & 31), k = kt * 16 + (lane >> 5) * 8;
+    const float4 a = *reinterpret_cast<const float4 *>(src + n * K + k), b = *reinterpret_cast<const float4 *>(src + n * K + k + 4);
+    uint4 o;
+    o.x = (uint32_t)f2bf(a.x) | ((uint32_t)f2bf(a.y) << 16);
+    o.y = (uint32_t)f2bf(a.z) | ((uint32_t)f2bf(a.w) << 16);
+    o.z = (uint32_t)f2bf(b.x) | ((uint32_t)f2bf(b.y) << 16);
+    o.w = (uint32_t)f2bf(b.z) | ((uint32_t)f2bf(b.w) << 16);
+    dst[idx] = o;
+}
+
+// ... and from the transpose: src is [K, N] fp32, the packed matrix is its transpose [N, K].  The 32 lanes that share a
+// k read 128 contiguous bytes of a source row.
+__global__ void pack_cast_t_bf16_kernel(const float *src, uint4 *dst, int64_t N, int64_t K)
+{
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t total = (N / 32) * (K / 16) * 64;
+    if (idx >= total) return;
+    int lane = idx & 63;
+    int64_t tile = idx >> 6;
+    int64_t kt = tile % (K / 16), nt = tile / (K / 16);
+    int64_t n = nt * 32 + (lane & 31), k = kt * 16 + (lane >> 5) * 8;
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++) v[j] = src[(k + j) * N + n];
+    uint4 o;
+    o.x = (uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16);
+    o.y = (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16);
+    o.z = (uint32_t)f2bf(v[4]) | ((uint32_t)f2bf(v[5]) << 16);
+    o.w = (uint32_t)f2bf(v[6]) | ((uint32_t)f2bf(v[7]) << 16);
+    dst[idx] = o;
+}
+
+int32_t launch_pack_cast_t_bf16(const float *src, void *dst, int64_t n_out, int64_t n_in, hipStream_t st)
+{
+    if (n_out % 32 || n_in % 64) return fail(FG_ERR_SHAPE, "pack needs n_out %% 32 == 0 and n_in %% 64 == 0 (got %lld, %lld)",
+                                             (long long)n_out, (long long)n_in);
+    const int64_t total = (n_out / 32) * (n_in / 16) * 64;
+    hipLaunchKernelGGL(pack_cast_t_bf16_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, src, (uint4 *)dst, n_out, n_in);
+    FG_LAUNCH_CHECK("pack_cast_t");
+    return FG_OK;
+}
+
+int32_t launch_pack_cast_bf16(const float *src, void *dst, int64_t n_out, int64_t n_in, hipStream_t st)
+{
+    if (n_out % 32 || n_in % 64) return fail(FG_ERR_SHAPE, "pack needs n_out %% 32 == 0 and n_in %% 64 == 0 (got %lld, %lld)",
+                                             (long long)n_out, (long long)n_in);
+    const int64_t total = (n_out / 32) * (n_in / 16) * 64;
+    hipLaunchKernelGGL(pack_cast_bf16_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, src, (uint4 *)dst, n_out, n_in);
+    FG_LAUNCH_CHECK("pack_cast");
+    return FG_OK;
+}
+
 __global__ void pack_f32_kernel(const float *src, const float *src2, float *dst, int64_t N, int64_t K)
 {
     int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;

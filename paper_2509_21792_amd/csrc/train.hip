@@ -132,8 +132,7 @@ __global__ __launch_bounds__(256) void transpose_cast_bf16_kernel(const float *_
 
 struct Mfma16 {          // scratch of the matrix-core path
     bf16_t *x16;         // the first operand, cast (and transposed)
-    bf16_t *w16;         // the second operand, cast (and transposed), before packing
-    bf16_t *wp;          // ... packed
+    bf16_t *wp;          // the second operand, cast (and transposed) and packed
     int64_t x_cap, w_cap;
     // the packed form of the last second operand, so that the two LM-head products of the forward pass pack it once
     const float *last_src = nullptr;
@@ -156,9 +155,8 @@ static int32_t gemm16(Mfma16 &s, int op, const float *A, const float *B, float *
     else cast(A, s.x16, (size_t)M * K);
     // second operand as [N, K] bf16, packed
     if (!(s.last_src == B && s.last_op == op)) {
-        if (op == 0) cast(B, s.w16, (size_t)N * K);          // B is [N, K]
-        else tcast(B, s.w16, K, N);                           // B is [K, N]
-        int32_t rc = launch_pack(FG_BF16, s.w16, nullptr, s.wp, N, K, st);
+        // rounded (and transposed) and packed in one pass: B is [N, K], or [K, N] for the other two operand orders
+        const int32_t rc = op == 0 ? launch_pack_cast_bf16(B, s.wp, N, K, st) : launch_pack_cast_t_bf16(B, s.wp, N, K, st);
         if (rc) return rc;
         s.last_src = B;
         s.last_op = op;
@@ -673,7 +671,6 @@ static int64_t carve_train(const fg_model_cfg &c, int B, int T, void *base, int6
         s.mm.x_cap = M * (big > 2 * d ? big : 2 * d);
         s.mm.w_cap = V * d > wide * rows ? V * d : wide * rows;
         s.mm.x16 = (bf16_t *)take((s.mm.x_cap + 1) / 2);
-        s.mm.w16 = (bf16_t *)take((s.mm.w_cap + 1) / 2);
         s.mm.wp = (bf16_t *)take((s.mm.w_cap + 1) / 2);
     }
     if (w) *w = s;
