@@ -358,6 +358,7 @@ __global__ void train_attn_bwd_kv_kernel(const float *qkv, const float *P, const
 // below do the same sums -- over keys in ascending order, over head dims in ascending order, no atomics, so a step stays
 // bitwise repeatable -- with the operand rows staged through LDS 64 at a time and a tile of 16 positions per block.
 constexpr int TA_TQ = 16, TA_TK = 64;
+constexpr int TA_SS = 20;   // floats per key in the score array: the tile's 16 positions + 4 of padding (16-byte rows, fewer bank conflicts)
 
 // stage rows r0 .. r0 + 63 of a [*, hd] operand (row stride `stride` floats, rows clamped to n_rows - 1) into
 // tile [64][hd + 1] (the odd row stride keeps a column walk conflict-free)
@@ -374,14 +375,15 @@ __device__ __forceinline__ void ta_stage(float *tile, const float *src, size_t s
 
 // MODE 0, forward: S = (q . K^T) scale over the keys up to each position, P = softmax(S) (kept, [B, Hq, T, T]), att = P . V.
 // MODE 1, backward to q: dP = datt . V^T, dS = P (dP - sum_s dP P) scale (kept), dq = dS . K.
-// One block per (tile of 16 positions, query head, chain).  LDS: aT [hd][16], tile [64][hd + 1], sc [16][Tp].
+// One block per (tile of 16 positions, query head, chain).  LDS: aT [hd][16], tile [64][hd + 1], sc [Tp][20] (key-major, so
+// that the last phase reads the scores of four positions in one instruction).
 template <int MODE>
 __global__ __launch_bounds__(256) void train_attn_tile_kernel(const float *__restrict__ qkv, float *__restrict__ P, float *__restrict__ dS,
                                                               const float *__restrict__ datt, float *__restrict__ out, int T, int Tp, int Hq,
                                                               int Hkv, int hd, int qkvd, float scale)
 {
     extern __shared__ __align__(16) float ta_lds[];
-    float *aT = ta_lds, *tile = aT + hd * TA_TQ, *sc = tile + TA_TK * (hd + 1);
+    float *aT = ta_lds, *tile = aT + hd * TA_TQ, *sc = tile + (TA_TK * (hd + 1) + 3) / 4 * 4;
     const int t0 = blockIdx.x * TA_TQ, hq = blockIdx.y, b = blockIdx.z, hk = hq / (Hq / Hkv), tid = threadIdx.x;
     const int t_last = min(t0 + TA_TQ, T) - 1;
     const float *kbase = qkv + (size_t)b * T * qkvd + (size_t)(Hq + hk) * hd;
@@ -408,7 +410,7 @@ __global__ __launch_bounds__(256) void train_attn_tile_kernel(const float *__res
 #pragma unroll
         for (int i = 0; i < 4; i++) {
             const int s = k0 + kj, t = t0 + qg * 4 + i;
-            sc[(qg * 4 + i) * Tp + s] = (s <= t && t < T) ? acc[i] : (MODE == 0 ? -INFINITY : 0.f);
+            sc[s * TA_SS + qg * 4 + i] = (s <= t && t < T) ? acc[i] : (MODE == 0 ? -INFINITY : 0.f);
         }
     }
     __syncthreads();
@@ -416,31 +418,31 @@ __global__ __launch_bounds__(256) void train_attn_tile_kernel(const float *__res
     {
         const int i = tid >> 4, sub = tid & 15, t = t0 + i;
         const int n = t < T ? t + 1 : 0;                       // keys of this position
-        float *row = sc + i * Tp;
+        float *row = sc + i;                                   // element s of the position's row: row[s * TA_SS]
         const size_t grow = (((size_t)b * Hq + hq) * T + min(t, T - 1)) * T;
         if (MODE == 0) {
             float mx = -INFINITY;
-            for (int s2 = sub; s2 < n; s2 += 16) mx = fmaxf(mx, row[s2]);
+            for (int s2 = sub; s2 < n; s2 += 16) mx = fmaxf(mx, row[s2 * TA_SS]);
 #pragma unroll
             for (int o = 8; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 16));
             float den = 0.f;
-            for (int s2 = sub; s2 < n; s2 += 16) { const float e2 = expf(row[s2] - mx); row[s2] = e2; den += e2; }
+            for (int s2 = sub; s2 < n; s2 += 16) { const float e2 = expf(row[s2 * TA_SS] - mx); row[s2 * TA_SS] = e2; den += e2; }
 #pragma unroll
             for (int o = 8; o > 0; o >>= 1) den += __shfl_xor(den, o, 16);
             for (int s2 = sub; s2 < T; s2 += 16) {
-                const float pv = s2 < n ? row[s2] / den : 0.f;
+                const float pv = s2 < n ? row[s2 * TA_SS] / den : 0.f;
                 if (t < T) P[grow + s2] = pv;
-                if (s2 < Tp) row[s2] = pv;
+                row[s2 * TA_SS] = pv;
             }
         } else {
             float dot = 0.f;
-            for (int s2 = sub; s2 < n; s2 += 16) dot += row[s2] * P[grow + s2];
+            for (int s2 = sub; s2 < n; s2 += 16) dot += row[s2 * TA_SS] * P[grow + s2];
 #pragma unroll
             for (int o = 8; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 16);
             for (int s2 = sub; s2 < T; s2 += 16) {
-                const float g2 = s2 < n ? P[grow + s2] * (row[s2] - dot) * scale : 0.f;
+                const float g2 = s2 < n ? P[grow + s2] * (row[s2 * TA_SS] - dot) * scale : 0.f;
                 if (t < T) dS[grow + s2] = g2;
-                if (s2 < Tp) row[s2] = g2;
+                row[s2 * TA_SS] = g2;
             }
         }
     }
@@ -454,9 +456,13 @@ __global__ __launch_bounds__(256) void train_attn_tile_kernel(const float *__res
         const int cnt = min(TA_TK, t_last + 1 - k0);
         for (int s2 = 0; s2 < cnt; s2++) {
             const float bv = tile[s2 * (hd + 1) + e];
-#pragma unroll
-            for (int i = 0; i < 8; i++)
-                if (i < rpg) o8[i] += sc[(g * rpg + i) * Tp + k0 + s2] * bv;
+            const float *ps = sc + (k0 + s2) * TA_SS + g * rpg;
+            const float4 p0 = *reinterpret_cast<const float4 *>(ps);
+            o8[0] += p0.x * bv; o8[1] += p0.y * bv; o8[2] += p0.z * bv; o8[3] += p0.w * bv;
+            if (rpg == 8) {
+                const float4 p1 = *reinterpret_cast<const float4 *>(ps + 4);
+                o8[4] += p1.x * bv; o8[5] += p1.y * bv; o8[6] += p1.z * bv; o8[7] += p1.w * bv;
+            }
         }
     }
 #pragma unroll
@@ -477,7 +483,7 @@ __global__ __launch_bounds__(256) void train_attn_tile_kv_kernel(const float *__
                                                                  float *__restrict__ dqkv, int T, int Hq, int Hkv, int hd, int qkvd)
 {
     extern __shared__ __align__(16) float ta_lds[];
-    float *qt = ta_lds, *dt = qt + TA_TK * (hd + 1), *dsT = dt + TA_TK * (hd + 1), *pT = dsT + TA_TK * TA_TQ;
+    float *qt = ta_lds, *dt = qt + TA_TK * (hd + 1), *dsT = dt + TA_TK * (hd + 1), *pT = dsT + TA_TK * TA_TQ;   // 64 (hd + 1) is a multiple of 4
     const int s0 = blockIdx.x * TA_TQ, hk = blockIdx.y, b = blockIdx.z, G = Hq / Hkv, tid = threadIdx.x;
     const int groups = 256 / hd, rpg = TA_TQ / groups, e = tid % hd, g = tid / hd;
     float dk[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, dv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -498,12 +504,16 @@ __global__ __launch_bounds__(256) void train_attn_tile_kv_kernel(const float *__
             const int cnt = min(TA_TK, T - tt);
             for (int r = 0; r < cnt; r++) {
                 const float qv = qt[r * (hd + 1) + e], dov = dt[r * (hd + 1) + e];
-#pragma unroll
-                for (int i = 0; i < 8; i++)
-                    if (i < rpg) {
-                        dk[i] += dsT[r * TA_TQ + g * rpg + i] * qv;
-                        dv[i] += pT[r * TA_TQ + g * rpg + i] * dov;
-                    }
+                const float4 d0 = *reinterpret_cast<const float4 *>(dsT + r * TA_TQ + g * rpg);
+                const float4 p0 = *reinterpret_cast<const float4 *>(pT + r * TA_TQ + g * rpg);
+                dk[0] += d0.x * qv; dk[1] += d0.y * qv; dk[2] += d0.z * qv; dk[3] += d0.w * qv;
+                dv[0] += p0.x * dov; dv[1] += p0.y * dov; dv[2] += p0.z * dov; dv[3] += p0.w * dov;
+                if (rpg == 8) {
+                    const float4 d1 = *reinterpret_cast<const float4 *>(dsT + r * TA_TQ + g * rpg + 4);
+                    const float4 p1 = *reinterpret_cast<const float4 *>(pT + r * TA_TQ + g * rpg + 4);
+                    dk[4] += d1.x * qv; dk[5] += d1.y * qv; dk[6] += d1.z * qv; dk[7] += d1.w * qv;
+                    dv[4] += p1.x * dov; dv[5] += p1.y * dov; dv[6] += p1.z * dov; dv[7] += p1.w * dov;
+                }
             }
         }
     }
@@ -518,7 +528,11 @@ __global__ __launch_bounds__(256) void train_attn_tile_kv_kernel(const float *__
 }
 
 static bool train_attn_tiled_ok(int T, int hd) { return (hd == 64 || hd == 128) && T <= 1024; }
-static size_t train_attn_tile_lds(int T, int hd) { return sizeof(float) * ((size_t)hd * TA_TQ + (size_t)TA_TK * (hd + 1) + (size_t)TA_TQ * ((T + 63) / 64 * 64)); }
+static size_t train_attn_tile_lds(int T, int hd)
+{
+    // the tile is rounded up to whole 16-byte rows so that the score array behind it stays aligned
+    return sizeof(float) * ((size_t)hd * TA_TQ + (size_t)(TA_TK * (hd + 1) + 3) / 4 * 4 + (size_t)TA_SS * ((T + 63) / 64 * 64));
+}
 // more than 64 KiB of dynamic LDS has to be allowed per kernel
 static int32_t allow_lds(const void *kernel, size_t bytes)
 {
