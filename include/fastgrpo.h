@@ -334,6 +334,11 @@ int32_t fg_build_tree(const int32_t *cand_tok, const int32_t *cand_parent, const
  * of the total in `grad`.  embed, lm_head: the target's, fp32 row-major [vocab, d], frozen.  tokens int32 [B, T],
  * feat_in / feat_tgt fp32 [B, T, d], n_valid int32 [B], all device.  cfg: the draft head's (n_layers must be 1).  d, F, Hq hd, vocab multiples of 4; T * 4 bytes of LDS per block (T <= 8192).
  * workspace: fg_draft_train_workspace_bytes(cfg, B, T).  Deterministic: no atomics, fixed summation orders.
+ * head_packed (optional, NULL allowed; used in the FG_BF16 mode only): the frozen lm_head already rounded to bf16 and
+ * packed for the step's two kinds of product with it, written once by fg_draft_train_pack_head into a device buffer of
+ * fg_draft_train_head_bytes(cfg) bytes that the caller keeps for as long as lm_head does not change (vocab and d
+ * multiples of 64); without it every step packs the head again (1.3 of 16 ms on the 7B-class head).  The results are
+ * bitwise the same either way.
  *
  * fg_draft_adamw: one AdamW step on every parameter (decoupled weight decay, bias-corrected moments; step counts
  * from 1): m = b1 m + (1 - b1) g; v = b2 v + (1 - b2) g^2; p -= lr (m / (1 - b1^step) / (sqrt(v / (1 - b2^step)) + eps)
@@ -345,8 +350,10 @@ typedef struct {
 int64_t fg_draft_train_workspace_bytes(const fg_model_cfg *cfg, int32_t B, int32_t T);
 int32_t fg_draft_train_grad(const fg_model_cfg *cfg, const float *embed, const float *lm_head, const fg_draft_params *w,
                             const int32_t *tokens, const float *feat_in, const float *feat_tgt, const int32_t *n_valid,
-                            int32_t B, int32_t T, float w_ce, fg_draft_params *grad, float *loss, void *workspace,
-                            int64_t workspace_bytes, void *stream);
+                            int32_t B, int32_t T, float w_ce, fg_draft_params *grad, float *loss, const void *head_packed,
+                            void *workspace, int64_t workspace_bytes, void *stream);
+int64_t fg_draft_train_head_bytes(const fg_model_cfg *cfg);
+int32_t fg_draft_train_pack_head(const fg_model_cfg *cfg, const float *lm_head, void *packed, int64_t packed_bytes, void *stream);
 int32_t fg_draft_adamw(const fg_model_cfg *cfg, fg_draft_params *w, const fg_draft_params *grad, fg_draft_params *m,
                        fg_draft_params *v, float lr, float beta1, float beta2, float eps, float weight_decay, int32_t step,
                        void *stream);

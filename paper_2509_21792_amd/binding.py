@@ -21,7 +21,7 @@ EXPORTS = ["fg_last_error", "fg_plan", "fg_packed_bytes", "fg_pack_weight", "fg_
            "fg_workspace_bytes", "fg_workspace_bytes_for", "fg_step_workspace_bytes", "fg_spec_verify", "fg_spec_accept", "fg_kv_compact", "fg_draft_step",
            "fg_draft_frontier", "fg_build_tree", "fg_gemm", "fg_attention", "fg_attention_workspace_bytes",
            "fg_topk_logp", "fg_lm_head_topk", "fg_lm_head_topk_workspace_bytes", "fg_knee", "fg_select_rows", "fg_model_profile",
-           "fg_model_profile_read", "fg_gemm_kernel_name", "fg_spec_accept_static", "fg_draft_train_workspace_bytes", "fg_draft_train_grad", "fg_draft_adamw", "fg_probe_read", "fg_probe_copy", "fg_probe_mfma"]
+           "fg_model_profile_read", "fg_gemm_kernel_name", "fg_spec_accept_static", "fg_draft_train_workspace_bytes", "fg_draft_train_grad", "fg_draft_train_head_bytes", "fg_draft_train_pack_head", "fg_draft_adamw", "fg_probe_read", "fg_probe_copy", "fg_probe_mfma"]
 STATIC_SCRATCH_BYTES = 4 << 20
 
 
@@ -95,7 +95,10 @@ def lib():
         L.fg_draft_train_workspace_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int32, C.c_int32]
         L.fg_draft_train_grad.argtypes = [C.POINTER(ModelCfg), C.c_void_p, C.c_void_p, C.POINTER(DraftParamsC), C.c_void_p, C.c_void_p,
                                           C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.POINTER(DraftParamsC), C.c_void_p,
-                                          C.c_void_p, C.c_int64, C.c_void_p]
+                                          C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        L.fg_draft_train_head_bytes.restype = C.c_int64
+        L.fg_draft_train_head_bytes.argtypes = [C.POINTER(ModelCfg)]
+        L.fg_draft_train_pack_head.argtypes = [C.POINTER(ModelCfg), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         L.fg_draft_adamw.argtypes = [C.POINTER(ModelCfg), C.POINTER(DraftParamsC), C.POINTER(DraftParamsC), C.POINTER(DraftParamsC),
                                      C.POINTER(DraftParamsC)] + [C.c_float] * 5 + [C.c_int32, C.c_void_p]
         L.fg_kv_compact.argtypes = [C.POINTER(KvCacheC), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
@@ -524,11 +527,21 @@ def fg_draft_train_workspace_bytes(cfg, B, T, compute="fp32"):
     return lib().fg_draft_train_workspace_bytes(C.byref(c), B, T)
 
 
+def fg_draft_train_pack_head(cfg, lm_head):
+    """The frozen LM head (fp32 [vocab, d] on the device) rounded to bf16 and packed once for the matrix-core training
+    step; pass the returned buffer as head_packed to fg_draft_train_grad while lm_head stays the same."""
+    c = model_cfg_struct(dict(cfg, dtype="bf16"))
+    assert lm_head.dtype == torch.float32 and lm_head.is_contiguous()
+    buf = torch.empty(lib().fg_draft_train_head_bytes(C.byref(c)), dtype=torch.uint8, device=lm_head.device)
+    _check(lib().fg_draft_train_pack_head(C.byref(c), _p(lm_head), _p(buf), buf.numel(), _stream()))
+    return buf
+
+
 def fg_draft_train_grad(cfg, embed, lm_head, w, tokens, feat_in, feat_tgt, n_valid, w_ce=0.1, grad=None, workspace=None,
-                        compute="fp32"):
+                        compute="fp32", head_packed=None):
     """Loss terms (device tensor [2]) and gradients (dict of fp32 tensors shaped like `w`) of the draft head's training
     loss; embed / lm_head: the target's, fp32 row-major on the device.  compute: "fp32" (exact) or "bf16" (the step's
-    matrix products on the matrix cores)."""
+    matrix products on the matrix cores; head_packed: fg_draft_train_pack_head(cfg, lm_head), optional)."""
     dev = tokens.device
     B, T = tokens.shape
     c = model_cfg_struct(dict(cfg, dtype=compute))
@@ -541,8 +554,8 @@ def fg_draft_train_grad(cfg, embed, lm_head, w, tokens, feat_in, feat_tgt, n_val
     for t in (embed, lm_head, feat_in, feat_tgt):
         assert t.dtype == torch.float32 and t.is_contiguous()
     _check(lib().fg_draft_train_grad(C.byref(c), _p(embed), _p(lm_head), C.byref(ws), _p(_dev_i32(tokens, dev)), _p(feat_in), _p(feat_tgt),
-                                     _p(_dev_i32(n_valid, dev)), B, T, w_ce, C.byref(gs), _p(loss), _p(workspace), workspace.numel(),
-                                     _stream()))
+                                     _p(_dev_i32(n_valid, dev)), B, T, w_ce, C.byref(gs), _p(loss),
+                                     _p(head_packed) if head_packed is not None else None, _p(workspace), workspace.numel(), _stream()))
     return loss, grad
 
 

@@ -64,7 +64,10 @@ const char *gemm_mfma_kernel_name(int M, int N, int K, int epilogue);
 int64_t draft_train_ws_bytes(const fg_model_cfg &c, int B, int T);
 int32_t launch_draft_train_grad(const fg_model_cfg &c, const float *embed, const float *lm_head, const fg_draft_params *w,
                                 const int32_t *tokens, const float *feat_in, const float *feat_tgt, const int32_t *n_valid, int B,
-                                int T, float w_ce, fg_draft_params *g, float *loss, void *ws, int64_t ws_bytes, hipStream_t st);
+                                int T, float w_ce, fg_draft_params *g, float *loss, const void *head_packed, void *ws,
+                                int64_t ws_bytes, hipStream_t st);
+int64_t draft_train_head_bytes(const fg_model_cfg &c);
+int32_t launch_draft_train_pack_head(const fg_model_cfg &c, const float *lm_head, void *packed, hipStream_t st);
 int32_t launch_adamw(float *p, const float *g, float *m, float *v, int64_t n, float lr, float b1, float b2, float eps, float wd,
                      int step, hipStream_t st);
 
@@ -817,8 +820,8 @@ int64_t fg_draft_train_workspace_bytes(const fg_model_cfg *cfg, int32_t B, int32
 
 int32_t fg_draft_train_grad(const fg_model_cfg *cfg, const float *embed, const float *lm_head, const fg_draft_params *w,
                             const int32_t *tokens, const float *feat_in, const float *feat_tgt, const int32_t *n_valid, int32_t B,
-                            int32_t T, float w_ce, fg_draft_params *grad, float *loss, void *workspace, int64_t workspace_bytes,
-                            void *stream)
+                            int32_t T, float w_ce, fg_draft_params *grad, float *loss, const void *head_packed, void *workspace,
+                            int64_t workspace_bytes, void *stream)
 {
     int32_t rc;
     if ((rc = check_train_cfg(cfg))) return rc;
@@ -832,8 +835,24 @@ int32_t fg_draft_train_grad(const fg_model_cfg *cfg, const float *embed, const f
     if ((int64_t)B * T * (int64_t)cfg->vocab >= (1LL << 31) * 4) return fail(FG_ERR_CAPACITY, "fg_draft_train_grad: B * T * vocab too large");
     if (!embed || !lm_head || !params_ok(w) || !params_ok(grad) || !tokens || !feat_in || !feat_tgt || !n_valid || !loss || !workspace)
         return fail(FG_ERR_INVALID_ARG, "fg_draft_train_grad: NULL pointer");
-    return launch_draft_train_grad(*cfg, embed, lm_head, w, tokens, feat_in, feat_tgt, n_valid, B, T, w_ce, grad, loss, workspace,
-                                   workspace_bytes, (hipStream_t)stream);
+    return launch_draft_train_grad(*cfg, embed, lm_head, w, tokens, feat_in, feat_tgt, n_valid, B, T, w_ce, grad, loss, head_packed,
+                                   workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+int64_t fg_draft_train_head_bytes(const fg_model_cfg *cfg)
+{
+    if (check_train_cfg(cfg)) return 0;
+    return draft_train_head_bytes(*cfg);
+}
+
+int32_t fg_draft_train_pack_head(const fg_model_cfg *cfg, const float *lm_head, void *packed, int64_t packed_bytes, void *stream)
+{
+    int32_t rc;
+    if ((rc = check_train_cfg(cfg))) return rc;
+    if (!lm_head || !packed) return fail(FG_ERR_INVALID_ARG, "fg_draft_train_pack_head: NULL pointer");
+    if (cfg->vocab % 64 || cfg->d_model % 64) return fail(FG_ERR_SHAPE, "fg_draft_train_pack_head: vocab and d in multiples of 64");
+    if (packed_bytes < draft_train_head_bytes(*cfg)) return fail(FG_ERR_CAPACITY, "fg_draft_train_pack_head: buffer too small");
+    return launch_draft_train_pack_head(*cfg, lm_head, packed, (hipStream_t)stream);
 }
 
 int32_t fg_draft_adamw(const fg_model_cfg *cfg, fg_draft_params *w, const fg_draft_params *grad, fg_draft_params *m,

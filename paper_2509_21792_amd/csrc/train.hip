@@ -137,6 +137,9 @@ struct Mfma16 {          // scratch of the matrix-core path
     // the packed form of the last second operand, so that the two LM-head products of the forward pass pack it once
     const float *last_src = nullptr;
     int last_op = -1;
+    // the frozen LM head packed ahead of time by the caller (both operand orders), or nullptr
+    const float *head_src = nullptr;
+    const bf16_t *head_fwd = nullptr, *head_bwd = nullptr;
 };
 
 static int32_t gemm16(Mfma16 &s, int op, const float *A, const float *B, float *C, const float *add, int M, int N, int K, hipStream_t st)
@@ -154,7 +157,9 @@ static int32_t gemm16(Mfma16 &s, int op, const float *A, const float *B, float *
     if (op == 2) tcast(A, s.x16, K, M);           // A is [K, M]
     else cast(A, s.x16, (size_t)M * K);
     // second operand as [N, K] bf16, packed
-    if (!(s.last_src == B && s.last_op == op)) {
+    const bf16_t *wp = s.wp;
+    if (s.head_src && B == s.head_src && op != 2) wp = op == 0 ? s.head_fwd : s.head_bwd;
+    else if (!(s.last_src == B && s.last_op == op)) {
         // rounded (and transposed) and packed in one pass: B is [N, K], or [K, N] for the other two operand orders
         const int32_t rc = op == 0 ? launch_pack_cast_bf16(B, s.wp, N, K, st) : launch_pack_cast_t_bf16(B, s.wp, N, K, st);
         if (rc) return rc;
@@ -165,9 +170,9 @@ static int32_t gemm16(Mfma16 &s, int op, const float *A, const float *B, float *
         if (add != C) FG_HIP(hipMemcpyAsync(C, add, (size_t)M * N * 4, hipMemcpyDeviceToDevice, st));
         GemmEpi ep;
         ep.h = C;
-        return launch_gemm_mfma(FG_BF16, s.x16, s.wp, nullptr, M, N, K, EPI_RESIDUAL, 1, nullptr, st, &ep);
+        return launch_gemm_mfma(FG_BF16, s.x16, wp, nullptr, M, N, K, EPI_RESIDUAL, 1, nullptr, st, &ep);
     }
-    return launch_gemm_mfma(FG_BF16, s.x16, s.wp, C, M, N, K, EPI_SLABS, 1, nullptr, st);
+    return launch_gemm_mfma(FG_BF16, s.x16, wp, C, M, N, K, EPI_SLABS, 1, nullptr, st);
 }
 
 // ---- row-wise kernels ------------------------------------------------------------------------------------------------
@@ -694,12 +699,29 @@ static int64_t carve_train(const fg_model_cfg &c, int B, int T, void *base, int6
 
 int64_t draft_train_ws_bytes(const fg_model_cfg &c, int B, int T) { return carve_train(c, B, T, nullptr, 0, nullptr); }
 
+// The frozen LM head [V, d] in the two packed forms a matrix-core step multiplies with: as the second operand of
+// logits = x . head^T (n_out = V, n_in = d), and of dx = dlogits . head (n_out = d, n_in = V, i.e. the transpose).
+int64_t draft_train_head_bytes(const fg_model_cfg &c) { return 2 * align_up((int64_t)c.vocab * c.d_model * 2, 256); }
+int32_t launch_draft_train_pack_head(const fg_model_cfg &c, const float *lm_head, void *packed, hipStream_t st)
+{
+    char *p = (char *)packed;
+    int32_t rc = launch_pack_cast_bf16(lm_head, p, c.vocab, c.d_model, st);
+    if (rc) return rc;
+    return launch_pack_cast_t_bf16(lm_head, p + align_up((int64_t)c.vocab * c.d_model * 2, 256), c.d_model, c.vocab, st);
+}
+
 int32_t launch_draft_train_grad(const fg_model_cfg &c, const float *embed, const float *lm_head, const fg_draft_params *w,
                                 const int32_t *tokens, const float *feat_in, const float *feat_tgt, const int32_t *n_valid, int B,
-                                int T, float w_ce, fg_draft_params *g, float *loss, void *ws, int64_t ws_bytes, hipStream_t st)
+                                int T, float w_ce, fg_draft_params *g, float *loss, const void *head_packed, void *ws,
+                                int64_t ws_bytes, hipStream_t st)
 {
     TrainWs s;
     if (carve_train(c, B, T, ws, ws_bytes, &s) < 0) return fail(FG_ERR_CAPACITY, "fg_draft_train_grad: workspace too small");
+    if (head_packed && c.dtype == FG_BF16) {
+        s.mm.head_src = lm_head;
+        s.mm.head_fwd = (const bf16_t *)head_packed;
+        s.mm.head_bwd = (const bf16_t *)((const char *)head_packed + align_up((int64_t)c.vocab * c.d_model * 2, 256));
+    }
     const int M = B * T, d = c.d_model, F = c.d_ffn, V = c.vocab, Hq = c.n_q_heads, Hkv = c.n_kv_heads, hd = c.head_dim;
     const int hq = Hq * hd, qkvd = (Hq + 2 * Hkv) * hd;
     const float scale = 1.0f / sqrtf((float)hd);

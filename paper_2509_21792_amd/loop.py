@@ -294,6 +294,11 @@ class DraftTrainer:
         self.lr, self.w_ce, self.betas, self.eps, self.weight_decay = lr, w_ce, betas, eps, weight_decay
         self.steps = 0
         self._ws = None
+        # the head is frozen: in the matrix-core mode it is rounded and packed here, once, not in every step
+        self._head = fg.fg_draft_train_pack_head(self.cfg, self.lm_head) if compute == "bf16" and self._head_packable() else None
+
+    def _head_packable(self):
+        return self.cfg["vocab"] % 64 == 0 and self.cfg["d_model"] % 64 == 0
 
     def step(self, tokens, feat_in, feat_tgt, n_valid):
         """One update on a batch of chains: tokens int32 [B, T], feat_in / feat_tgt [B, T, d] (cast to fp32 here), n_valid
@@ -304,7 +309,7 @@ class DraftTrainer:
                                             device=tokens.device))
         loss, _ = fg.fg_draft_train_grad(self.cfg, self.embed, self.lm_head, self.w, tokens, feat_in.float().contiguous(),
                                          feat_tgt.float().contiguous(), n_valid, self.w_ce, grad=self.grad, workspace=self._ws[1],
-                                         compute=self.compute)
+                                         compute=self.compute, head_packed=self._head)
         self.steps += 1
         fg.fg_draft_adamw(self.cfg, self.w, self.grad, self.m, self.v, lr=self.lr, step=self.steps, beta1=self.betas[0],
                           beta2=self.betas[1], eps=self.eps, weight_decay=self.weight_decay)

@@ -203,5 +203,12 @@ def test_matrix_core_mode_follows_the_oracle_to_bf16_rounding(fg, orc):
         got, want = grad[k].cpu().numpy().astype(np.float64).ravel(), o_grad[k].ravel()
         cos = float(got @ want / (np.linalg.norm(got) * np.linalg.norm(want)))
         assert cos > 0.999 and np.abs(got - want).max() <= 3e-2 * np.abs(want).max(), (k, cos, np.abs(got - want).max(), np.abs(want).max())
+    # the frozen head packed ahead of time: bitwise the same step
+    head = dev(lm_head)
+    packed = fg.fg_draft_train_pack_head(cfg, head)
+    loss2, grad2 = fg.fg_draft_train_grad(cfg, dev(embed), head, gw, dev(tokens), dev(feat_in), dev(feat_tgt), dev(n_valid), w_ce,
+                                          compute="bf16", head_packed=packed)
+    torch.cuda.synchronize()
+    assert torch.equal(loss, loss2) and all(torch.equal(grad[k], grad2[k]) for k in grad)
     with pytest.raises(fg.FgError):      # fp16 would flush the gradients
         fg.fg_draft_train_grad(cfg, dev(embed), dev(lm_head), gw, dev(tokens), dev(feat_in), dev(feat_tgt), dev(n_valid), w_ce, compute="fp16")
