@@ -281,18 +281,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 4 ? 2
     // The accumulators start at zero -- or, for the residual epilogue, at the tile of h they are added to: those loads
     // fly with the prologue's, and the epilogue is then a plain store.
     f32x16_t acc[MT][NT];
+    if (EPI == EPI_RESIDUAL) {
+        // through a descriptor that ends with the matrix (or the block's rows): a row past it reads as zero, no branches
+        const int rows = min(M - row0, BM);
+        const __amdgpu_buffer_rsrc_t hrs = __builtin_amdgcn_make_buffer_rsrc(ep.h + (size_t)row0 * N, 0, rows * N * 4, 0x00020000);
 #pragma unroll
-    for (int i = 0; i < MT; i++)
+        for (int j = 0; j < NT; j++) {
+            const unsigned off0 = ntile[j] < n_tiles ? (unsigned)(((lane >> 5) * 4 * N + ntile[j] * 32 + (lane & 31)) * 4) : 0xc0000000u;
 #pragma unroll
-        for (int j = 0; j < NT; j++)
+            for (int i = 0; i < MT; i++)
 #pragma unroll
-            for (int r = 0; r < 16; r++) {
-                acc[i][j][r] = 0.f;
-                if (EPI == EPI_RESIDUAL) {
-                    const int m = row0 + i * 32 + 8 * (r >> 2) + (lane >> 5) * 4 + (r & 3);
-                    if (m < M && ntile[j] < n_tiles) acc[i][j][r] = ep.h[m * N + ntile[j] * 32 + (lane & 31)];
-                }
-            }
+                for (int r = 0; r < 16; r++)
+                    acc[i][j][r] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
+                        hrs, (int)(off0 + (unsigned)((i * 32 + 8 * (r >> 2) + (r & 3)) * N * 4)), 0, 0));
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < MT; i++)
+#pragma unroll
+            for (int j = 0; j < NT; j++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
+    }
 
     // W: lane pointer into each of the wave's two bands (clamped on a ragged last block; never stored)
     const uint4 *wband[NT];
