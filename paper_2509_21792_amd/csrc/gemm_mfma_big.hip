@@ -63,14 +63,22 @@ __device__ __forceinline__ void epilogue_rope(f32x16_t (&acc)[MT][2], const Gemm
         const int hk = head - Hq - Hkv;
         T *vp = reinterpret_cast<T *>(ep.v_pool) + ((size_t)ep.layer * ep.n_pages * Hkv + hk) * page_elems;
         const int lr = lane & 7, lc = lane >> 3;
+        // the cache cells of all the lane's rows in one batch of loads (every round trip of this epilogue is exposed)
+        int cellv[MT][4];
+#pragma unroll
+        for (int i = 0; i < MT; i++)
+#pragma unroll
+            for (int a = 0; a < 4; a++) {
+                const int m = row0 + i * 32 + lr + 8 * a;
+                cellv[i][a] = m < M ? ep.dest[m] : -1;
+            }
 #pragma unroll
         for (int i = 0; i < MT; i++) {
             if (row0 + i * 32 >= M) break;
             T *dst[4];   // where this lane's four rows of the tile go: the row's page and slot (nullptr: not appended)
 #pragma unroll
             for (int a = 0; a < 4; a++) {
-                const int m = row0 + i * 32 + lr + 8 * a;
-                const int cell = m < M ? ep.dest[m] : -1;
+                const int cell = cellv[i][a];
                 dst[a] = cell >= 0 ? vp + (size_t)(cell >> 4) * Hkv * page_elems + (cell & 15) : nullptr;
             }
 #pragma unroll
@@ -90,7 +98,6 @@ __device__ __forceinline__ void epilogue_rope(f32x16_t (&acc)[MT][2], const Gemm
         return;
     }
     const bool is_q = head < Hq;
-    T *qo = reinterpret_cast<T *>(ep.q_out) + head * hd;
     T *kp = reinterpret_cast<T *>(ep.k_pool);
     const int hk = head - Hq;
     // Every global round trip of this epilogue is exposed (one wave per SIMD, nothing else to run), so there are as few
@@ -105,6 +112,23 @@ __device__ __forceinline__ void epilogue_rope(f32x16_t (&acc)[MT][2], const Gemm
             const int m0 = row0 + i * 32 + 8 * q + rh;
             p4[i][q] = m0 < M ? *reinterpret_cast<const int4 *>(ep.pos + m0) : make_int4(0, 0, 0, 0);
         }
+    int cellk[MT][4];   // k rows: the cache cell of row (lane / 8) + 8 t of each row tile, fetched with the positions
+    if (!is_q) {
+#pragma unroll
+        for (int i = 0; i < MT; i++)
+#pragma unroll
+            for (int t = 0; t < 4; t++) {
+                const int m = row0 + i * 32 + (lane >> 3) + 8 * t;
+                cellk[i][t] = m < M ? ep.dest[m] : -1;
+            }
+    }
+    // table and q rows through buffer descriptors: 32-bit offsets, and a q row past the last one is dropped by the
+    // address check instead of by a branch
+    typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
+    typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+    const __amdgpu_buffer_rsrc_t trs =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float2 *>(ep.rope_tab), 0, ep.max_pos * half * 8, 0x00020000);
+    const __amdgpu_buffer_rsrc_t qrs = __builtin_amdgcn_make_buffer_rsrc(ep.q_out, 0, M * Hq * hd * 2, 0x00020000);
     float2 cs[2][16];
     auto load_table = [&](int i, float2 (&dst)[16]) {
 #pragma unroll
@@ -112,7 +136,8 @@ __device__ __forceinline__ void epilogue_rope(f32x16_t (&acc)[MT][2], const Gemm
             const int4 v = p4[i][r >> 2];
             const int pr = (r & 3) == 0 ? v.x : ((r & 3) == 1 ? v.y : ((r & 3) == 2 ? v.z : v.w));
             const int p = min(max(pr, 0), ep.max_pos - 1);
-            dst[r] = ep.rope_tab[(size_t)p * half + ebase + c];
+            const u32x2_t t = __builtin_amdgcn_raw_buffer_load_b64(trs, (p * half + ebase + c) * 8, 0, 0);
+            dst[r] = make_float2(__uint_as_float(t.x), __uint_as_float(t.y));
         }
     };
     load_table(0, cs[0]);
@@ -134,16 +159,14 @@ __device__ __forceinline__ void epilogue_rope(f32x16_t (&acc)[MT][2], const Gemm
                 const int piece = lane + 64 * t, rr = piece >> 3, seg = piece & 7;
                 const uint4 v = *reinterpret_cast<const uint4 *>(tile + rr * 64 + seg * 8);
                 const int m = row0 + i * 32 + rr;
-                if (m < M) {
-                    const int e = seg < 4 ? ebase + seg * 8 : ebase + half + (seg - 4) * 8;
-                    if (is_q) {
-                        *reinterpret_cast<uint4 *>(qo + (size_t)m * Hq * hd + e) = v;
-                    } else {
-                        const int cell = ep.dest[m], page = cell >> 4, tk = cell & 15;
-                        if (cell >= 0) {   // -1: beyond the page table, not appended
-                            T *o = kp + (((size_t)ep.layer * ep.n_pages + page) * Hkv + hk) * page_elems;
-                            *reinterpret_cast<uint4 *>(o + k_page_offset(ep.k_frag, hd, tk, e)) = v;
-                        }
+                const int e = seg < 4 ? ebase + seg * 8 : ebase + half + (seg - 4) * 8;
+                if (is_q) {
+                    __builtin_amdgcn_raw_buffer_store_b128((u32x4_t){v.x, v.y, v.z, v.w}, qrs, ((m * Hq + head) * hd + e) * 2, 0, 0);
+                } else {
+                    const int cell = cellk[i][t], page = cell >> 4, tk = cell & 15;
+                    if (cell >= 0) {   // -1: beyond the page table (or past the last row), not appended
+                        T *o = kp + (((size_t)ep.layer * ep.n_pages + page) * Hkv + hk) * page_elems;
+                        *reinterpret_cast<uint4 *>(o + k_page_offset(ep.k_frag, hd, tk, e)) = v;
                     }
                 }
             }
@@ -539,6 +562,8 @@ int32_t launch_gemm_mfma_big(int32_t dtype, const void *x, const void *wp, void 
         return fail(FG_ERR_INVALID_ARG, "top-k epilogue needs 1 <= k <= 8 and its partial buffers");
     if (epilogue >= EPI_ROPE && !epi) return fail(FG_ERR_INVALID_ARG, "GEMM epilogue %d needs its arguments", epilogue);
     if (epilogue == EPI_ROPE && (epi->hd != 64 && epi->hd != 128)) return fail(FG_ERR_SHAPE, "RoPE epilogue needs head_dim 64 or 128");
+    if (epilogue == EPI_ROPE && ((int64_t)M * epi->Hq * epi->hd >= (1LL << 30) || (int64_t)epi->max_pos * epi->hd >= (1LL << 28)))
+        return fail(FG_ERR_SHAPE, "RoPE epilogue: q output or rotation table beyond its 32-bit byte offsets");
     const BigPlan p = plan_big(M, N, K, split, fixed_mt, epilogue);
     const GemmEpi ep = epi ? *epi : GemmEpi();
 #define FG_BIG_MT(T)                                                                                   \
