@@ -182,7 +182,13 @@ __device__ __forceinline__ void epilogue_rope(f32x16_t (&acc)[MT][2], const Gemm
 // float4 reads of 16 lanes cover all 64 banks).  topk rounds follow: every lane offers its best entry that comes after
 // the previous winner in the order (value descending, column ascending), a 4-step exchange inside the 16 lanes picks
 // the round's winner.
-__device__ __forceinline__ bool topk_before(float va, int ia, float vb, int ib) { return va > vb || (va == vb && ia < ib); }
+// float bits -> unsigned whose order is the values' order (and back); no NaNs here
+__device__ __forceinline__ unsigned topk_ord(float x)
+{
+    const unsigned u = __float_as_uint(x);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float topk_unord(unsigned k) { return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k); }
 
 template <int MT>
 __device__ __forceinline__ void epilogue_topk(f32x16_t (&acc)[MT][2], const GemmEpi &ep, int M, int N, int row0, int bx, int n_bands,
@@ -206,8 +212,13 @@ __device__ __forceinline__ void epilogue_topk(f32x16_t (&acc)[MT][2], const Gemm
                     for (int j = 0; j < 2; j++)
                         tile[(8 * qq + 4 * hsel + k) * 256 + wn * 64 + j * 32 + c] = acc[i][j][4 * (2 * half + qq) + k];
             __syncthreads();
-            float v[16];
-            int col[16];
+            // An entry travels as one 64-bit key: the value's bits mapped so that unsigned order is value order, above the
+            // complemented column -- a larger key comes first in (value descending, column ascending).  A round is then
+            // "the largest key below the previous winner": two compares and four selects per entry and no branch (written
+            // with the pair comparison the compiler produced a compare-and-branch ladder per entry, ~20 instructions).
+            // Columns past the matrix get the key 0 | ~0x7fffffff, below every real entry; -0 is folded into +0 first so
+            // that the two still tie.
+            unsigned long long key[16];
 #pragma unroll
             for (int vv = 0; vv < 4; vv++) {
                 const float4 x = *reinterpret_cast<const float4 *>(tile + row16 * 256 + seg * 4 + 64 * vv);
@@ -215,39 +226,44 @@ __device__ __forceinline__ void epilogue_topk(f32x16_t (&acc)[MT][2], const Gemm
 #pragma unroll
                 for (int u = 0; u < 4; u++) {
                     const int cc = bx * 256 + seg * 4 + 64 * vv + u;
-                    col[4 * vv + u] = cc < N ? cc : 0x7fffffff;     // columns past the matrix never win a round
-                    v[4 * vv + u] = cc < N ? xs[u] : -INFINITY;
+                    key[4 * vv + u] = cc < N ? ((unsigned long long)topk_ord(xs[u] + 0.f) << 32) | (unsigned)~cc : 0x80000000ull;
                 }
             }
             const int m = row0 + i * 32 + half * 16 + row16;
-            float lv = INFINITY, bmax = -INFINITY;
-            int li = -1;
+            unsigned long long prev = ~0ull;
+            float bmax = -INFINITY;
             for (int k = 0; k < K; k++) {
-                float best = -INFINITY;
-                int bi = 0x7fffffff;
+                unsigned long long best = 0;
 #pragma unroll
                 for (int e = 0; e < 16; e++) {
-                    const bool after = topk_before(lv, li, v[e], col[e]);      // the previous winner comes before it
-                    if (after && topk_before(v[e], col[e], best, bi)) { best = v[e]; bi = col[e]; }
+                    const unsigned long long cand = key[e] < prev ? key[e] : 0ull;
+                    best = cand > best ? cand : best;
                 }
 #pragma unroll
                 for (int o = 1; o < 16; o <<= 1) {
-                    const float ob = __shfl_xor(best, o, 64);
-                    const int oi = __shfl_xor(bi, o, 64);
-                    if (topk_before(ob, oi, best, bi)) { best = ob; bi = oi; }
+                    const unsigned long long ob = ((unsigned long long)__shfl_xor((unsigned)(best >> 32), o, 64) << 32) |
+                                                  __shfl_xor((unsigned)best, o, 64);
+                    best = ob > best ? ob : best;
                 }
-                if (k == 0) bmax = best;
-                lv = best; li = bi;
+                const unsigned hi = (unsigned)(best >> 32);
+                const float bv = hi ? topk_unord(hi) : -INFINITY;          // nothing left in the block: (-inf, no column)
+                const int bi = hi ? (int)~(unsigned)best : 0x7fffffff;
+                if (k == 0) bmax = bv;
+                prev = best;
                 if (seg == 0 && m < M) {
                     const size_t at = ((size_t)m * n_bands + bx) * K + k;
-                    ep.part_val[at] = best;
+                    ep.part_val[at] = bv;
                     ep.part_idx[at] = bi;
                 }
             }
             if (ep.part_ms) {
                 float sum = 0.f;
 #pragma unroll
-                for (int e = 0; e < 16; e++) sum += v[e] > -INFINITY ? __expf(v[e] - bmax) : 0.f;
+                for (int e = 0; e < 16; e++) {
+                    const unsigned hi = (unsigned)(key[e] >> 32);
+                    const float ve = hi ? topk_unord(hi) : -INFINITY;
+                    sum += ve > -INFINITY ? __expf(ve - bmax) : 0.f;
+                }
 #pragma unroll
                 for (int o = 1; o < 16; o <<= 1) sum += __shfl_xor(sum, o, 64);
                 if (seg == 0 && m < M) {
