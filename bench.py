@@ -26,7 +26,7 @@ PEAK_MFMA = 2516.6e12      # flop/s, dense bf16 / fp16 MFMA
 # benchmark's shape (bench.py --gemm gate_up --rows M), scaled by what the same counters read for the library's copy probe
 # (FETCH_SIZE x 2.00, WRITE_SIZE x 1.00).  A recorded measurement, keyed by (workload, rows M); other workloads report null.
 MEASURED_C_PEAK = 64       # knee of the 7B-class latency curve on the log2 batch axis (bench.py --sweep / --gen measure it afresh)
-MEASURED_TRAFFIC = {("cfg4", 2048): 919.7e6 + 77.6e6,      # profiles/bench_cfg4_b256_n8_hbm_traffic_pmc.txt
+MEASURED_TRAFFIC = {("cfg4", 2048): 929.9e6 + 77.6e6,      # profiles/bench_cfg4_b256_n8_hbm_traffic_pmc.txt
                     ("b8", 8): 277.3e6 + 0.3e6}            # same file, rows "M=8"
 
 
