@@ -553,6 +553,15 @@ def ceilings(args):
         paged[f"{blocks}_blocks"] = nbytes / t / 1e9
     out["hbm_read_scattered_4KiB_pages_GBps"] = paged
     out["hbm_read_scattered_4KiB_pages_best_GBps"] = max(paged.values())
+    # L2 -> L1: every block streams one 1 MiB region 256 times (it stays in L2, no 32 KiB L1 holds it)
+    small = src[:1 << 20]
+    l2 = {}
+    for per_cu in (1, 2, 4):
+        blocks = 256 * per_cu
+        t = timed(lambda: fg.fg_probe_read(small, 3, blocks, sink), 3)
+        l2[f"{per_cu}_blocks_per_cu"] = dict(aggregate_GBps=blocks * 256 * (1 << 20) / t / 1e9, per_cu_GBps=blocks * (1 << 20) / t / 1e9)
+    out["l2_to_l1_stream"] = l2
+    out["l2_to_l1_best_per_cu_GBps"] = max(v["per_cu_GBps"] for v in l2.values())
     copies = {}
     half = src[:nbytes // 2]
     for blocks in (2048, 4096, 8192, 16384):

@@ -412,7 +412,9 @@ int32_t fg_model_profile_read(fg_model *m, double *ms, int32_t *launches);
  * Ceiling probes (measurement only): what the GPU sustains for the two resources the path is bound by.
  * fg_probe_read: `blocks` blocks of 256 threads stream `bytes` (a multiple of 16) from src with 16-byte loads, four in
  *   flight per lane; nontemporal 0: ordinary loads, 1: non-temporal loads, 2: non-temporal loads of 4 KiB pages visited
- *   in a hashed order, one page per wave at a time (the pattern of a paged KV cache; bytes a power of two);
+ *   in a hashed order, one page per wave at a time (the pattern of a paged KV cache; bytes a power of two); 3: EVERY
+ *   block streams the whole region 256 times (bytes a power of two from 32 KiB to 64 MiB: choose it to fit in L2 and
+ *   not in a 32 KiB L1), eight loads in flight per lane -- blocks * 256 * bytes are read in all, as L2 -> L1 fills;
  *   sink: device, blocks * 4 bytes (written only on a magic checksum).
  * fg_probe_copy: the same stream written to dst (the plain copy whose FETCH_SIZE / WRITE_SIZE counter readings scale
  *   the traffic figures of the other kernels).

@@ -5,6 +5,7 @@
 //           of what it read; nothing is written but one word per block
 //   copy    the same stream, written back: the plain copy whose FETCH_SIZE / WRITE_SIZE readings scale the HBM
 //           traffic counters of the other kernels
+//   read, L2-resident   every block streams one small region many times: the L2 -> L1 fill rate of a CU
 //   mfma    a register-resident loop of v_mfma_f32_32x32x16_{bf16,f16}: operands stay in registers, four independent
 //           accumulator tiles per wave, no memory traffic in the loop
 #include "fg_common.h"
@@ -118,9 +119,36 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, int random, 
     if (s == 1.2345f) sink[blockIdx.x * 256 + threadIdx.x] = s;   // keeps the loop alive; practically never true
 }
 
+// What a CU draws from L2: EVERY block streams the whole (small, power-of-two sized) region `passes` times, eight 16-byte
+// loads per lane in flight.  The region stays in L2 and in none of the 32 KiB L1s, so the bytes a block reads are L2 -> L1
+// fills: the path the operands of the large GEMMs take.
+__global__ __launch_bounds__(256) void probe_read_l2_kernel(const uint4 *__restrict__ src, int n_vec, int passes, uint32_t *sink)
+{
+    const int mask = n_vec - 1;
+    int idx = (blockIdx.x * 977 + threadIdx.x) & mask;
+    uint32_t acc = 0;
+    for (int it = 0; it < passes * (n_vec / 2048); it++) {
+        uint4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) v[u] = src[(idx + u * 256) & mask];
+#pragma unroll
+        for (int u = 0; u < 8; u++) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+        idx = (idx + 2048) & mask;
+    }
+    if (acc == 0x9e3779b9u && threadIdx.x == 0) sink[blockIdx.x] = acc;
+}
+
+constexpr int PROBE_L2_PASSES = 256;
+
 int32_t launch_probe_read(const void *src, int64_t bytes, int nontemporal, int blocks, void *sink, hipStream_t st)
 {
     const int64_t n_vec = bytes / 16;
+    if (nontemporal == 3) {   // L2-resident region, read PROBE_L2_PASSES times by every block
+        hipLaunchKernelGGL(probe_read_l2_kernel, dim3(blocks), dim3(256), 0, st, (const uint4 *)src, (int)n_vec, PROBE_L2_PASSES,
+                           (uint32_t *)sink);
+        FG_LAUNCH_CHECK("probe_read_l2");
+        return FG_OK;
+    }
     if (nontemporal == 2) {   // scattered 4 KiB pages; the caller checked that bytes is a power of two
         hipLaunchKernelGGL(probe_read_paged_kernel, dim3(blocks), dim3(256), 0, st, (const uint4 *)src, bytes / 4096, (uint32_t *)sink);
         FG_LAUNCH_CHECK("probe_read_paged");
