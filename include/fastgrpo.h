@@ -378,8 +378,8 @@ int32_t fg_draft_adamw(const fg_model_cfg *cfg, fg_draft_params *w, const fg_dra
  * fg_lm_head_topk: the same lists straight from the hidden states x [M, d_model] (dtype) and the packed LM head
  *   [vocab, d_model], the selection done in the GEMM's epilogue, so that no [M, vocab] tensor is written: per row and
  *   256-token block the K best (value, token) and (max, sum exp), then a merge.  What fg_spec_verify (K = 2, for the row
- *   arg-max and top-2) and fg_draft_step do when no logits are asked for; from 129 rows and 16384 tokens on
- *   (FG_ERR_SHAPE below).  workspace: fg_lm_head_topk_workspace_bytes(M, vocab, K) bytes, device.
+ *   arg-max and top-2) and fg_draft_step do when no logits are asked for; from 129 rows and 16384 tokens on,
+ *   and from 65 rows for vocabularies of at least 128 blocks of 256 tokens (FG_ERR_SHAPE below).  workspace: fg_lm_head_topk_workspace_bytes(M, vocab, K) bytes, device.
  */
 int32_t fg_gemm(int32_t dtype, const void *x, const void *w_packed, void *out, int32_t M, int32_t n_out,
                 int32_t n_in, int32_t epilogue, int32_t split_k, int32_t *split_k_used, int32_t variant, void *stream);

@@ -891,7 +891,7 @@ int32_t fg_lm_head_topk(int32_t dtype, const void *x, const void *lm_head_packed
     if (M == 0) return FG_OK;
     if (!is16(dtype) || vocab % 32 || d_model % 64) return fail(FG_ERR_SHAPE, "fg_lm_head_topk: 16-bit dtypes, vocab %% 32 == 0, d_model %% 64 == 0");
     if (!gemm_mfma_fusable(M, vocab, d_model, EPI_TOPK))
-        return fail(FG_ERR_SHAPE, "fg_lm_head_topk: the selecting epilogue runs from 129 rows and 16384 tokens on (got %d, %d)", M, vocab);
+        return fail(FG_ERR_SHAPE, "fg_lm_head_topk: the selecting epilogue runs from 129 rows and 16384 tokens on, from 65 rows and 32544 tokens on (got %d, %d)", M, vocab);
     if (workspace_bytes < lm_head_topk_bytes(M, vocab, K)) return fail(FG_ERR_CAPACITY, "fg_lm_head_topk: workspace too small");
     return lm_head_topk(dtype, x, lm_head_packed, M, vocab, d_model, K, true, workspace, tok, logp, nullptr, nullptr, (hipStream_t)stream);
 }

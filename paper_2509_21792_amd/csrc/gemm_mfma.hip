@@ -206,33 +206,32 @@ int gemm_mfma_decode_split_for(int M, int N, int K);
 bool gemm_mfma_decode_ok(int M, int N, int K, int epilogue);
 
 // Which kernel runs a shape.  All thresholds are measurements on the 7B-class and 1.5B-class matrices; "wide" means
-// at least 16384 output columns (gate/up, the LM head), "narrow" the QKV, O and down projections.
+// at least 16384 output columns (gate/up, the LM head), "narrow" the QKV, O and down projections.  Times in us.
 //   few-row kernel (gemm_mfma_skinny.hip, k split inside the block):
-//     narrow outputs up to 128 rows in one row block -- 22.0 / 26.1 / 33.2 / 38.7 us for the 7B down projection at
-//       8 / 48 / 96 / 128 rows with 4 slabs, against 22.4 / 33.7 / 41.8 / 45.1 with the streaming kernel's 16 -- and up
-//       to 256 rows (two row blocks) while the X traffic of the 64-column blocks (column blocks x M x K x 2 bytes, all
-//       from L2) stays small: the 7B O projection (103 MB) 14.8 / 17.7 us at 192 / 256 rows against 23 - 27 in the
-//       large-tile kernels, while the 7B down projection (543 MB) takes 65 against 47 - 62;
-//     gate/up with its SwiGLU fused up to 64 rows (46.6 / 49.5 / 57.7 us at 8 / 32 / 64 rows against 48.8 / 56.8 / 53.0
-//       plus a 4.4 - 5.5 us SwiGLU pass), and up to 128 rows when at most 512 column blocks keep it to one round;
-//     the LM head up to 32 rows (167 against 177 us at 8 rows, level at 32, behind above);
+//     narrow outputs up to 64 rows, and up to 128 rows of a short reduction (QKV 15.0 / O 16.7 at 96 rows, level with
+//       the pipelined kernel); the 7B down projection (18944 deep) takes 31.0 at 64 rows against 37 in the pipelined
+//       kernel, but 36.4 / 43.7 at 96 / 128 rows against 32.6 / 33.5;
+//     gate/up with its SwiGLU fused up to 64 rows (50.8 / 56.4 / 60.2 at 32 / 48 / 64 rows against 54.8 / 56.9 / 58.7 in
+//       128-row blocks of the pipelined kernel), and up to 128 rows when the pipelined kernel would have fewer than 128
+//       tiles to spread (the 1.5B-class gate/up has 70);
+//     the LM head up to 32 rows (167 against 177 at 8 rows, level at 32, behind above);
 //   decode kernel (gemm_mfma_decode.hip, eight waves per block, no barrier in the main loop): gate/up with its SwiGLU
-//     fused up to 16 rows -- 43.6 / 45.6 us at 8 / 16 rows of the 7B-class model against 46.0 / 47.4 in the few-row kernel
+//     fused up to 16 rows -- 43.6 / 45.6 at 8 / 16 rows of the 7B-class model against 46.0 / 47.4 in the few-row kernel
 //     (kernel durations from a trace).  Its partial-sum epilogue loses to the few-row kernel on every narrow output (O 8.9
-//     against 6.9 us, QKV 12.0 against 7.8, down 25.9 against 22.0 at 8 rows) and on the LM head (186 against 168);
-//   pipelined kernel (gemm_mfma_big.hip): more than 256 rows; from 129 rows the wide outputs (a 256-row tile half
-//     full still beats streaming the weights through eight row tiles per wave) and the narrow ones with up to 16 k
-//     splits (the 7B down projection 42 - 47 us at 160 - 256 rows against 58 - 62 in the streaming kernel);
-//   streaming kernel (this file): the rest, i.e. 33 / 65 - 128 rows of the wide outputs.
+//     against 6.9, QKV 12.0 against 7.8, down 25.9 against 22.0 at 8 rows) and on the LM head (186 against 168);
+//   pipelined kernel (gemm_mfma_big.hip): every shape above 128 rows -- QKV 17.1 / 17.7 / 19.9 at 144 / 160 / 192 rows
+//     against 24.5 in the few-row kernel, O 14.4 - 15.5 at 144 - 256 rows against 17 - 21 -- and from 65 rows the deep
+//     narrow reductions (above) and the wide outputs with at least 128 tiles: one row of 128-row blocks runs gate/up in
+//     61.4 / 64.2 at 96 / 128 rows against 71.3 / 83.0 in the few-row and 89.9 / 91.1 in the streaming kernel, the LM head
+//     in 248 / 249 against 261 / 271 streamed;
+//   streaming kernel (this file): the rest, i.e. the LM head at 33 - 64 rows (204 / 208 at 48 / 64 rows against 225 /
+//     235 in 128-row blocks) and wide outputs of few tiles at 65 - 128 rows.
 enum { KERNEL_STREAMING = 1, KERNEL_FEW = 2, KERNEL_BIG = 3, KERNEL_DECODE = 4 };
 static int kernel_for(int M, int N, int K, int epilogue)
 {
     if (epilogue >= EPI_ROPE) return KERNEL_BIG;
-    if (N < 16384) {
-        if (M <= 128 || (M <= 256 && (int64_t)((N + 63) / 64) * M * K <= (56LL << 20))) return KERNEL_FEW;
-        return KERNEL_BIG;
-    }
-    if (M > 128) return KERNEL_BIG;
+    if (N < 16384) return (M <= 64 || (M <= 128 && K < 8192)) ? KERNEL_FEW : KERNEL_BIG;
+    if (M > 128 || (M > 64 && (N / 32 + 7) / 8 >= 128)) return KERNEL_BIG;
     if (epilogue == EPI_SWIGLU && M <= 16 && gemm_mfma_decode_ok(M, N, K, epilogue)) return KERNEL_DECODE;
     if (epilogue == EPI_SWIGLU) return (M <= 64 || (N + 63) / 64 <= 512) ? KERNEL_FEW : KERNEL_STREAMING;
     return M <= 32 ? KERNEL_FEW : KERNEL_STREAMING;
@@ -253,7 +252,7 @@ bool gemm_mfma_fusable(int M, int N, int K, int kind)
     if (kind < EPI_ROPE) return true;
     if (kind > EPI_TOPK || (int64_t)M * K >= (1LL << 30)) return false;
     // the top-k epilogue is for LM heads: thousands of tiles, no k split at any row count the pipelined kernel takes
-    if (kind == EPI_TOPK) return N >= 16384 && M > 128;
+    if (kind == EPI_TOPK) return N >= 16384 && (M > 128 || (M > 64 && (N / 32 + 7) / 8 >= 128));
     return M > 256 && gemm_mfma_big_unsplit_tiles(M, N, K, kind) >= 192;
 }
 

@@ -495,18 +495,35 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 4 ? 2
 // splits of 256-row blocks.  The wide outputs (gate/up, LM head) have thousands of tiles.  128-row blocks, two to a CU,
 // put each one's prologue and epilogue under the other's main loop but draw half as much again from L2 per flop
 // (53.0 M against 35.5 M line requests for gate/up at 2048 rows); 256-row blocks leave their epilogue exposed, which
-// an exact-division SwiGLU made expensive.  With the reciprocal-instruction SwiGLU the 256-row blocks win from 1280
-// rows on (gate/up: 294 against 310 us at 1280 rows, 461 against 486 at 2048, 886 against 927 at 4096) and lose
-// below (262 against 256 at 1024).
+// an exact-division SwiGLU made expensive.  With the reciprocal-instruction SwiGLU a block's time is close to
+// proportional to its height, with 8 % more per row for 160-row blocks and 17 % more for 128-row ones, and the launch
+// takes as many of them as the busiest CU runs one after the other: ceil(tiles / 256) rounds.  That count decides the
+// height of the wide outputs (wide_height below); it reproduces every measured ordering of gate/up (us, 256- / 160- /
+// 128-row blocks): 64 at 128 rows in one 128-row block; 82 / 68 / 106 at 160 rows; 86 / 116 / 106 at 256; 160 / 132 /
+// 109 at 384; 152 in 128-row blocks at 512; 197 / - / 208 at 768; level at 1024; 294 / - / 310 at 1280; 461 / - / 486
+// at 2048; 886 / - / 927 at 4096.
 // The residual and top-k epilogues exist for 128- and 160-row blocks only: with 256 accumulator registers per lane the
 // extra live values of those epilogues (the tile of h, the selection's scratch) do not fit and the compiler spills.
 struct BigPlan { int split, mt; };
 static bool tall_blocks_ok(int epilogue) { return epilogue != EPI_RESIDUAL && epilogue != EPI_TOPK; }
+static int wide_height(int M, int n_bands)
+{
+    static const int heights[3] = {8, 5, 4};
+    static const double per_block[3] = {1.0, 1.08 * 5 / 8, 1.17 * 4 / 8};
+    int best = 8;
+    double best_cost = 1e30;
+    for (int i = 0; i < 3; i++) {
+        const long tiles = (long)n_bands * ((M + 32 * heights[i] - 1) / (32 * heights[i]));
+        const double cost = (double)((tiles + 255) / 256) * per_block[i];
+        if (cost < best_cost) { best_cost = cost; best = heights[i]; }   // ties go to the taller block: less L2 traffic
+    }
+    return best;
+}
 static BigPlan plan_big(int M, int N, int K, int fixed_split, int fixed_mt, int epilogue = EPI_SLABS)
 {
     const int n_bands = (N / 32 + 7) / 8, chunks = K / 64;
     if (!tall_blocks_ok(epilogue) && fixed_mt == 8) fixed_mt = 0;
-    if (N >= 16384 && fixed_mt <= 0) fixed_mt = (M < 1280 || !tall_blocks_ok(epilogue)) ? 4 : 8;
+    if (N >= 16384 && fixed_mt <= 0) fixed_mt = tall_blocks_ok(epilogue) ? wide_height(M, n_bands) : 4;
     BigPlan best{fixed_split > 0 ? fixed_split : 1, fixed_mt > 0 ? fixed_mt : 8};
     double best_cost = 1e30;
     static const int heights[3] = {8, 5, 4};

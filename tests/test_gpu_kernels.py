@@ -252,7 +252,7 @@ def test_tree_attention(fg, dtype, Hq, Hkv, hd, B, N, n_prev, lens):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp16"])
-@pytest.mark.parametrize("M,V,K", [(129, 16384, 4), (300, 16480, 1), (1030, 16640, 8), (520, 33024, 2)])
+@pytest.mark.parametrize("M,V,K", [(129, 16384, 4), (300, 16480, 1), (1030, 16640, 8), (520, 33024, 2), (70, 33024, 3)])
 def test_lm_head_with_the_selection_in_its_epilogue(fg, dtype, M, V, K):
     """fg_lm_head_topk (per-block top-K / log-sum-exp partials in the GEMM epilogue + merge, no [M, V] tensor) against the
     two-kernel path on the same accumulators (fg_gemm slabs, then the oracle's definition of top-K / log-softmax on
