@@ -276,13 +276,16 @@ __device__ __forceinline__ void epilogue_topk(f32x16_t (&acc)[MT][2], const Gemm
     }
 }
 
-template <typename T, int MT, int EPI>
+// WA = waves of the block that own columns: 4, or 3 for launches that are weight streams (see plan_big): the block is
+// then 192 columns wide, and its fourth wave only brings its share of X and keeps the block's barriers.
+template <typename T, int MT, int EPI, int WA = 4>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 4 ? 2 : 1))) void gemm_mfma_big_kernel(const T *__restrict__ X, const uint4 *__restrict__ Wp,
                                                              void *__restrict__ out, int M, int N, int K, int chunks_per_split,
                                                              int n_bands, int row_blocks, int per_xcd, int n_tile_total, GemmEpi ep)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the buffer-descriptor builtins exist in the device pass only
     constexpr int NT = 2, WN = 4, BM = MT * 32;
+    static_assert(WA == 4 || (WA == 3 && (EPI == EPI_SLABS || EPI == EPI_SWIGLU)), "the narrower block has the barrier-free epilogues");
     constexpr int STAGE_U4 = BM * 8;   // uint4 slots per stage: BM rows x 8 pieces
     // one variable per stage: the compiler orders LDS reads after direct-to-LDS loads per variable, so distinct
     // variables keep the reads of one stage from waiting on the loads in flight to the others
@@ -308,7 +311,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 4 ? 2
         ntile[0] = bx * 8 + (wn >> 1) * 4 + (wn & 1);
         ntile[1] = ntile[0] + 2;
     } else {
-        ntile[0] = (bx * WN + wn) * NT;
+        ntile[0] = (bx * WA + wn) * NT;
         ntile[1] = ntile[0] + 1;
     }
     const int total_chunks = k_tiles / KT;
@@ -386,6 +389,37 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 4 ? 2
 
     const int last = c_end - 1;
     auto clampc = [&](int c) { return min(c, last); };
+
+    if constexpr (WA < WN) {
+        if (wn >= WA) {
+            // A wave without columns: the same X loads and barriers as the others, nothing else.  At the barrier of chunk
+            // c its loads of chunk c + 1 must have landed; younger than them are those of chunk c + 2 alone.
+            FG_X_ISSUE(c_begin, xs0);
+            FG_X_ISSUE(clampc(c_begin + 1), xs1);
+            FG_X_ISSUE(clampc(c_begin + 2), xs2);
+            __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * MT, 0));
+            __builtin_amdgcn_s_barrier();
+#define FG_HELPER(c, st)                                        \
+    do {                                                        \
+        __builtin_amdgcn_s_waitcnt(waitcnt_imm(MT, 0));         \
+        __builtin_amdgcn_s_barrier();                           \
+        FG_FENCE();                                             \
+        FG_X_ISSUE(clampc((c) + 3), st);                        \
+        FG_FENCE();                                             \
+    } while (0)
+            int c = c_begin;
+            for (; c + 2 < c_end; c += 3) {
+                FG_HELPER(c, xs0);
+                FG_HELPER(c + 1, xs1);
+                FG_HELPER(c + 2, xs2);
+            }
+            if (c < c_end) FG_HELPER(c, xs0);
+            if (c + 1 < c_end) FG_HELPER(c + 1, xs1);
+#undef FG_HELPER
+            __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
+            return;
+        }
+    }
 
     // prologue: X(0), W(0) k tiles 0-2, X(1), W(0) k tile 3, W(1) k tiles 0-2, X(2), W(1) k tile 3
     FG_X_ISSUE(c_begin, xs0);
@@ -504,8 +538,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 4 ? 2
 // at 2048; 886 / - / 927 at 4096.
 // The residual and top-k epilogues exist for 128- and 160-row blocks only: with 256 accumulator registers per lane the
 // extra live values of those epilogues (the tile of h, the selection's scratch) do not fit and the compiler spills.
-struct BigPlan { int split, mt; };
+// A launch of at most 256 blocks with one block per CU is a weight stream, and a CU draws about 32 GB/s from HBM
+// whatever it keeps in flight (gate/up in one row of 148 blocks: 55 - 64 us from 32 to 128 rows, the same with operands
+// four chunks ahead instead of two; the decode kernel's 198 blocks: 43 us): what counts is the number of CUs that
+// stream.  Such launches of a wide output therefore use blocks of 192 columns (wa = 3 column waves) when that still
+// gives one round: 198 blocks for the 7B-class gate/up.
+struct BigPlan { int split, mt, wa; };
 static bool tall_blocks_ok(int epilogue) { return epilogue != EPI_RESIDUAL && epilogue != EPI_TOPK; }
+static int column_waves(int M, int N, int mt, int split, int epilogue)
+{
+    if (N < 16384 || split != 1 || (epilogue != EPI_SLABS && epilogue != EPI_SWIGLU) || M > 32 * mt) return 4;
+    return (N / 32 + 5) / 6 <= 256 ? 3 : 4;
+}
 static int wide_height(int M, int n_bands)
 {
     static const int heights[3] = {8, 5, 4};
@@ -524,7 +568,7 @@ static BigPlan plan_big(int M, int N, int K, int fixed_split, int fixed_mt, int 
     const int n_bands = (N / 32 + 7) / 8, chunks = K / 64;
     if (!tall_blocks_ok(epilogue) && fixed_mt == 8) fixed_mt = 0;
     if (N >= 16384 && fixed_mt <= 0) fixed_mt = tall_blocks_ok(epilogue) ? wide_height(M, n_bands) : 4;
-    BigPlan best{fixed_split > 0 ? fixed_split : 1, fixed_mt > 0 ? fixed_mt : 8};
+    BigPlan best{fixed_split > 0 ? fixed_split : 1, fixed_mt > 0 ? fixed_mt : 8, 4};
     double best_cost = 1e30;
     static const int heights[3] = {8, 5, 4};
     for (int mt : heights) {
@@ -541,9 +585,10 @@ static BigPlan plan_big(int M, int N, int K, int fixed_split, int fixed_mt, int 
             const int per_xcd = (n_bands * row_blocks * s + 7) / 8, per_cu = (per_xcd + 31) / 32;
             double cost = per_cu * (cps + (mt == 4 && per_cu >= 2 ? 2 : 8)) * chunk_us;
             cost += (s - 1) * (double)M * N * 4 * 1.3 / 4.5e6;
-            if (cost < best_cost) { best_cost = cost; best = BigPlan{s, mt}; }
+            if (cost < best_cost) { best_cost = cost; best = BigPlan{s, mt, 4}; }
         }
     }
+    best.wa = column_waves(M, N, best.mt, best.split, epilogue);
     return best;
 }
 
@@ -557,21 +602,28 @@ int gemm_mfma_big_unsplit_tiles(int M, int N, int K, int epilogue)
 }
 
 template <typename T, int MT>
-static void launch_big_typed(const void *x, const void *wp, void *out, int M, int N, int K, int epilogue, int split,
+static void launch_big_typed(const void *x, const void *wp, void *out, int M, int N, int K, int epilogue, int split, int wa,
                              const GemmEpi &ep, hipStream_t st)
 {
-    const int n_tiles = N / 32, per_block = 8;
+    const int n_tiles = N / 32, per_block = 2 * wa;
     const int total_chunks = K / 64;
     const int cps = (total_chunks + split - 1) / split;
     const int n_bands = (n_tiles + per_block - 1) / per_block, row_blocks = (M + 32 * MT - 1) / (32 * MT);
     const int total = n_bands * row_blocks * split, per_xcd = (total + 7) / 8;
     const dim3 grid((unsigned)(8 * per_xcd));
-#define FG_BIG_LAUNCH(E)                                                                                          \
-    hipLaunchKernelGGL((gemm_mfma_big_kernel<T, MT, E>), grid, dim3(256), 0, st, reinterpret_cast<const T *>(x),  \
+#define FG_BIG_LAUNCH_K(...)                                                                                        \
+    hipLaunchKernelGGL((gemm_mfma_big_kernel<__VA_ARGS__>), grid, dim3(256), 0, st, reinterpret_cast<const T *>(x), \
                        reinterpret_cast<const uint4 *>(wp), out, M, N, K, cps, n_bands, row_blocks, per_xcd, total, ep)
+#define FG_BIG_LAUNCH(E) FG_BIG_LAUNCH_K(T, MT, E)
     switch (epilogue) {
-    case EPI_SLABS: FG_BIG_LAUNCH(EPI_SLABS); break;
-    case EPI_SWIGLU: FG_BIG_LAUNCH(EPI_SWIGLU); break;
+    case EPI_SLABS:
+        if (wa == 3) FG_BIG_LAUNCH_K(T, MT, EPI_SLABS, 3);
+        else FG_BIG_LAUNCH(EPI_SLABS);
+        break;
+    case EPI_SWIGLU:
+        if (wa == 3) FG_BIG_LAUNCH_K(T, MT, EPI_SWIGLU, 3);
+        else FG_BIG_LAUNCH(EPI_SWIGLU);
+        break;
     case EPI_ROPE: FG_BIG_LAUNCH(EPI_ROPE); break;
     default:
         if constexpr (MT != 8) {   // the plan never pairs these epilogues with 256-row blocks
@@ -581,13 +633,19 @@ static void launch_big_typed(const void *x, const void *wp, void *out, int M, in
         break;
     }
 #undef FG_BIG_LAUNCH
+#undef FG_BIG_LAUNCH_K
 }
 
 // Shapes were validated by the caller (launch_gemm_mfma); M * K < 2^30 is needed by the 32-bit byte offsets.
-// fixed_mt: 0 = the plan's block height, else 8, 5 or 4 (row tiles of 32 per block).
+// fixed_mt: 0 = the plan's block height and width, else 8, 5 or 4 (row tiles of 32 per block) with 256-column blocks,
+// or 18, 15, 14 = the same heights with 192-column blocks (partial-sum and SwiGLU epilogues).
 int32_t launch_gemm_mfma_big(int32_t dtype, const void *x, const void *wp, void *out, int M, int N, int K, int epilogue,
                              int split, int fixed_mt, const GemmEpi *epi, hipStream_t st)
 {
+    const int fixed_wa = fixed_mt == 0 ? 0 : (fixed_mt > 10 ? 3 : 4);
+    if (fixed_mt > 10) fixed_mt -= 10;
+    if (fixed_wa == 3 && epilogue != EPI_SLABS && epilogue != EPI_SWIGLU)
+        return fail(FG_ERR_INVALID_ARG, "192-column blocks have the partial-sum and SwiGLU epilogues only (got %d)", epilogue);
     if ((int64_t)M * K >= (1LL << 30)) return fail(FG_ERR_SHAPE, "GEMM input of %d x %d exceeds 2^30 elements", M, K);
     if (epilogue >= EPI_ROPE && split != 1) return fail(FG_ERR_INVALID_ARG, "fused GEMM epilogue %d cannot run with a k split", epilogue);
     if (epilogue > EPI_TOPK) return fail(FG_ERR_UNIMPLEMENTED, "GEMM epilogue %d", epilogue);
@@ -597,13 +655,14 @@ int32_t launch_gemm_mfma_big(int32_t dtype, const void *x, const void *wp, void 
     if (epilogue == EPI_ROPE && (epi->hd != 64 && epi->hd != 128)) return fail(FG_ERR_SHAPE, "RoPE epilogue needs head_dim 64 or 128");
     if (epilogue == EPI_ROPE && ((int64_t)M * epi->Hq * epi->hd >= (1LL << 30) || (int64_t)epi->max_pos * epi->hd >= (1LL << 28)))
         return fail(FG_ERR_SHAPE, "RoPE epilogue: q output or rotation table beyond its 32-bit byte offsets");
-    const BigPlan p = plan_big(M, N, K, split, fixed_mt, epilogue);
+    BigPlan p = plan_big(M, N, K, split, fixed_mt, epilogue);
+    if (fixed_wa) p.wa = fixed_wa;
     const GemmEpi ep = epi ? *epi : GemmEpi();
 #define FG_BIG_MT(T)                                                                                   \
     do {                                                                                               \
-        if (p.mt == 8) launch_big_typed<T, 8>(x, wp, out, M, N, K, epilogue, split, ep, st);           \
-        else if (p.mt == 5) launch_big_typed<T, 5>(x, wp, out, M, N, K, epilogue, split, ep, st);      \
-        else launch_big_typed<T, 4>(x, wp, out, M, N, K, epilogue, split, ep, st);                     \
+        if (p.mt == 8) launch_big_typed<T, 8>(x, wp, out, M, N, K, epilogue, split, p.wa, ep, st);           \
+        else if (p.mt == 5) launch_big_typed<T, 5>(x, wp, out, M, N, K, epilogue, split, p.wa, ep, st);      \
+        else launch_big_typed<T, 4>(x, wp, out, M, N, K, epilogue, split, p.wa, ep, st);                     \
     } while (0)
     if (dtype == FG_BF16) FG_BIG_MT(bf16_t);
     else FG_BIG_MT(f16_t);
