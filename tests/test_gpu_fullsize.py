@@ -127,6 +127,13 @@ def test_config4_7b_high_concurrency_bf16(H, N):
     run_greedy_config(H, "cfg4", "bf16", n_sub=4, N=N)
 
 
+@pytest.mark.parametrize("N", [6, 20])
+def test_low_end_of_the_batch_range_7b(H, N):
+    """B = 8 of the metric's range at 48 and 160 rows per step: the row counts at which gate/up runs as one row of
+    192-column blocks of the pipelined kernel and the narrow projections change kernels."""
+    run_greedy_config(H, "b8", "fp16", n_sub=3, N=N)
+
+
 @pytest.mark.parametrize("name", ["cfg3", "cfg4"])
 def test_bf16_decisions_at_the_stated_margin_on_a_shallow_model(H, name):
     """Two layers of the 7B-class geometry, bf16 activations, whole batch: the rounding error is still small enough
