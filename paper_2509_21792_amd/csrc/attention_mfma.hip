@@ -109,7 +109,9 @@ static AttnPlan plan_attention(int B, int N, int Hq, int Hkv, int max_keys)
     long splits = (target + pairs - 1) / pairs;
     if (splits < 1) splits = 1;
     long ck = (max_keys + splits - 1) / splits;
-    long ck_min = 4L * p.QR;              // keeps the partial (m, l, O) traffic under ~1/4 of the K/V traffic
+    // keeps the partial (m, l, O) traffic under ~1/2 of the K/V traffic; binds for small batches only, where shorter
+    // chunks mean more waves at work (B = 8, N = 24: 0.94 ms of attention per step with 4 QR, 0.80 with 2 QR or QR)
+    long ck_min = 2L * p.QR;
     if (ck < ck_min) ck = ck_min;
     ck = (ck + 31) / 32 * 32;
     p.CK = (int)ck;
@@ -118,9 +120,16 @@ static AttnPlan plan_attention(int B, int N, int Hq, int Hkv, int max_keys)
     return p;
 }
 
-static int pick_qw(int N, int Hq, int Hkv)
+// Query tiles per wave.  Four make one wave carry all rows of an item up to N = 9 with 7 query heads per kv head, so that
+// K / V are streamed once, past L2: the choice when the batch alone fills the chip (B = 256, N = 8: 7.3 ms of attention
+// per step against 9.1 with two).  A small batch wants waves instead: with two tiles per wave an item's rows spread over
+// twice the waves, two to a SIMD, and the extra passes over K / V hit in L2 (B = 8, N = 8: 0.82 -> 0.59 ms per step;
+// B = 8, N = 24: 1.36 -> 0.80; B = 64, N = 24: 2.61 -> 2.47; B = 128, N = 32 with long caches: 6.71 -> 6.92, so the
+// switch sits at 1024 (sequence, kv head, wave) triples).
+static int pick_qw(int B, int N, int Hq, int Hkv)
 {
-    return ((Hq / Hkv) * N + 15) / 16 <= 2 ? 2 : 4;
+    const int QT = ((Hq / Hkv) * N + 15) / 16;
+    return (QT <= 2 || (long)B * Hkv * ((QT + 3) / 4) < 1024) ? 2 : 4;
 }
 
 // K / V loads.  Every cache line of K (pages in fragment order) and of V^T is touched by exactly one load
@@ -591,7 +600,7 @@ bool attention_mfma_supported(const fg_kv_cache *kv, int Hq, int N)
 int64_t attention_mfma_ws_bytes(int B, int N, int Hq, int Hkv, int hd, int max_keys)
 {
     if (B < 1 || N < 1 || Hkv < 1 || Hq % Hkv) return 0;
-    AttnPlan p = pick_qw(N, Hq, Hkv) == 2 ? plan_attention<2>(B, N, Hq, Hkv, max_keys) : plan_attention<4>(B, N, Hq, Hkv, max_keys);
+    AttnPlan p = pick_qw(B, N, Hq, Hkv) == 2 ? plan_attention<2>(B, N, Hq, Hkv, max_keys) : plan_attention<4>(B, N, Hq, Hkv, max_keys);
     int64_t rows = (int64_t)B * Hkv * p.n_chunks * p.QR;
     return align_up(rows * hd * 4, 256) + align_up(rows * 2 * 4, 256) + align_up((int64_t)B * Hkv * p.n_chunks * 16, 256);
 }
@@ -638,7 +647,7 @@ static int32_t launch_typed(const fg_kv_cache *kv, int layer, const fg_tree *t, 
 int32_t launch_attention_mfma(const fg_kv_cache *kv, int layer, const fg_tree *t, TreeDev td, int Hq, const void *q, void *out,
                               int max_keys, void *ws, int64_t ws_bytes, int reuse_order, hipStream_t st)
 {
-    const int qw = pick_qw(t->N, Hq, kv->n_kv_heads);
+    const int qw = pick_qw(t->B, t->N, Hq, kv->n_kv_heads);
 #define FG_ATTN(T, HD)                                                                                          \
     return qw == 2 ? launch_typed<T, HD, 2>(kv, layer, t, td, Hq, q, out, max_keys, ws, ws_bytes, reuse_order, st) \
                    : launch_typed<T, HD, 4>(kv, layer, t, td, Hq, q, out, max_keys, ws, ws_bytes, reuse_order, st)
