@@ -22,6 +22,9 @@
 // interleaving so that the count holds from the first chunk on, and chunks past the end are clamped (re-requested),
 // not skipped, so that it holds to the last.  Scheduling barriers pin the loads to their side of each wait.
 //
+// Launches of one row block of a wide output use blocks of 192 columns instead: three waves own columns, the fourth only
+// brings its share of X and keeps the barriers (see plan_big for why).
+//
 // Epilogues (no k split for the last three): fp32 slabs; SwiGLU of interleaved gate / up tiles; the QKV projection's
 // RoPE + KV append + q rows; residual add into the fp32 stream; per-block top-k / log-sum-exp partials of an LM head.
 #include "fg_common.h"

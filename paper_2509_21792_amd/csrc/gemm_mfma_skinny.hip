@@ -16,7 +16,8 @@
 //   EPI 0  fp32 partial slab of the block's k split (narrow outputs still want a few splits across blocks),
 //   EPI 1  W is the gate/up interleaved matrix: silu(gate) * up, stored as T.
 // Measured alternatives on the 7B-class gate/up at 8 rows (46.2 us as built): four bands per block 54.7 us (too few
-// blocks), a ring of eight chunks 47.3 us (no gain, and two row tiles then spill).  Three and four row tiles (65 - 128
+// blocks), a ring of eight chunks 47.3 us (no gain, and two row tiles then spill); four bands per block for the narrow
+// outputs at 64 rows (half the X staged per byte of W): QKV 11.8 against 11.0 us, O 10.7 against 9.8, down 29.4 against 28.8.  Three and four row tiles (65 - 128
 // rows) need 208 - 256 registers: two blocks per CU, which is enough for the narrow outputs' grids of at most 256
 // blocks.
 #include "fg_common.h"
