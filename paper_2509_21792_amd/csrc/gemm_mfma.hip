@@ -197,6 +197,7 @@ int32_t launch_gemm_mfma_big(int32_t dtype, const void *x, const void *wp, void 
                              int split, int fixed_mt, const GemmEpi *epi, hipStream_t st);
 int gemm_mfma_big_split_for(int M, int N, int K);
 int gemm_mfma_big_unsplit_tiles(int M, int N, int K, int epilogue);
+int gemm_mfma_big_stream_blocks(int N, int epilogue);
 int32_t launch_gemm_mfma_skinny(int32_t dtype, const void *x, const void *wp, void *out, int M, int N, int K, int epilogue,
                                 int split, hipStream_t st);
 int gemm_mfma_skinny_split_for(int M, int N, int K);
@@ -212,8 +213,9 @@ bool gemm_mfma_decode_ok(int M, int N, int K, int epilogue);
 //       the pipelined kernel); the 7B down projection (18944 deep) takes 31.0 at 64 rows against 37 in the pipelined
 //       kernel, but 36.4 / 43.7 at 96 / 128 rows against 32.6 / 33.5;
 //     gate/up with its SwiGLU fused up to 31 rows (49.5 at 24 rows, level with the pipelined kernel; 51.0 / 56.2 / 60.2
-//       at 32 / 48 / 64 rows against 49.7 / 50.8 / 52.2 there), and up to 128 rows when the pipelined kernel would have
-//       fewer than 128 tiles to spread (the 1.5B-class gate/up has 70);
+//       at 32 / 48 / 64 rows against 49.7 / 50.8 / 52.2 there), up to 64 rows when the pipelined kernel would stream
+//       through fewer than 192 blocks (the 1.5B-class gate/up, 140 blocks: level at 48 and 64 rows, 22 against 26 us per
+//       layer at 96 rows, 23 against 30 at 128), and up to 128 rows when through fewer than 128;
 //     the LM head up to 32 rows (167 against 177 at 8 rows, level at 32, behind above);
 //   decode kernel (gemm_mfma_decode.hip, eight waves per block, no barrier in the main loop): gate/up with its SwiGLU
 //     fused up to 16 rows -- 43.6 / 45.6 at 8 / 16 rows of the 7B-class model against 46.0 / 47.4 in the few-row kernel
@@ -221,18 +223,20 @@ bool gemm_mfma_decode_ok(int M, int N, int K, int epilogue);
 //     against 6.9, QKV 12.0 against 7.8, down 25.9 against 22.0 at 8 rows) and on the LM head (186 against 168);
 //   pipelined kernel (gemm_mfma_big.hip): every shape above 128 rows -- QKV 17.1 / 17.7 / 19.9 at 144 / 160 / 192 rows
 //     against 24.5 in the few-row kernel, O 14.4 - 15.5 at 144 - 256 rows against 17 - 21 -- and from 65 rows the deep
-//     narrow reductions (above) and the wide outputs with at least 128 tiles (gate/up from 32 rows): one row of 128-row
-//     blocks, 192 columns wide so that 198 CUs stream, runs gate/up in 53.6 / 55.9 at 96 / 128 rows (61.4 / 64.2 with
+//     narrow reductions (above) and the wide outputs that give at least 128 blocks (gate/up from 32 rows): one row of
+//     128-row blocks, 192 columns wide so that 198 CUs stream, runs gate/up in 53.6 / 55.9 at 96 / 128 rows (61.4 / 64.2 with
 //     256-column blocks) against 71.3 / 83.0 in the few-row and 89.9 / 91.1 in the streaming kernel, the LM head in 248 /
 //     249 against 261 / 271 streamed;
 //   streaming kernel (this file): the rest, i.e. the LM head at 33 - 64 rows (204 / 208 at 48 / 64 rows against 225 /
-//     235 in 128-row blocks) and wide outputs of few tiles at 65 - 128 rows.
+//     235 in 128-row blocks) and wide outputs of few blocks at 65 - 128 rows.
 enum { KERNEL_STREAMING = 1, KERNEL_FEW = 2, KERNEL_BIG = 3, KERNEL_DECODE = 4 };
 static int kernel_for(int M, int N, int K, int epilogue)
 {
     if (epilogue >= EPI_ROPE) return KERNEL_BIG;
     if (N < 16384) return (M <= 64 || (M <= 128 && K < 8192)) ? KERNEL_FEW : KERNEL_BIG;
-    if (M > 128 || (M > (epilogue == EPI_SWIGLU ? 31 : 64) && (N / 32 + 7) / 8 >= 128)) return KERNEL_BIG;
+    if (M > 128) return KERNEL_BIG;
+    const int stream_blocks = gemm_mfma_big_stream_blocks(N, epilogue == EPI_SWIGLU ? EPI_SWIGLU : EPI_SLABS);
+    if ((M > 64 && stream_blocks >= 128) || (M > 31 && epilogue == EPI_SWIGLU && stream_blocks >= 192)) return KERNEL_BIG;
     if (epilogue == EPI_SWIGLU && M <= 16 && gemm_mfma_decode_ok(M, N, K, epilogue)) return KERNEL_DECODE;
     if (epilogue == EPI_SWIGLU) return (M <= 64 || (N + 63) / 64 <= 512) ? KERNEL_FEW : KERNEL_STREAMING;
     return M <= 32 ? KERNEL_FEW : KERNEL_STREAMING;
@@ -295,7 +299,7 @@ int32_t launch_gemm_mfma(int32_t dtype, const void *x, const void *wp, void *out
     if (N % 32 || K % 64) return fail(FG_ERR_SHAPE, "16-bit GEMM needs n_out %% 32 == 0 and n_in %% 64 == 0 (got %d, %d)", N, K);
     if (epilogue == EPI_SWIGLU && (N % 64)) return fail(FG_ERR_SHAPE, "gate/up GEMM needs n_out %% 64 == 0");
     if ((int64_t)M * N >= (1LL << 31)) return fail(FG_ERR_SHAPE, "GEMM output of %d x %d exceeds 2^31 elements", M, N);
-    if (variant < 0 || variant > 9) return fail(FG_ERR_INVALID_ARG, "unknown GEMM variant %d", variant);
+    if (variant < 0 || variant > 10) return fail(FG_ERR_INVALID_ARG, "unknown GEMM variant %d", variant);
     const int kernel = variant ? kernel_of_variant(variant) : kernel_for(M, N, K, epilogue);
     if (epilogue >= EPI_ROPE && kernel != KERNEL_BIG) return fail(FG_ERR_INVALID_ARG, "GEMM epilogue %d exists in the pipelined kernel only", epilogue);
     if (kernel == KERNEL_FEW && M > 512) return fail(FG_ERR_SHAPE, "the few-row kernel takes at most 512 rows (got %d)", M);
@@ -315,7 +319,7 @@ int32_t launch_gemm_mfma(int32_t dtype, const void *x, const void *wp, void *out
     if (split_used) *split_used = split;
     if (kernel == KERNEL_FEW) return launch_gemm_mfma_skinny(dtype, x, wp, out, M, N, K, epilogue, split, st);
     if (kernel == KERNEL_DECODE) return launch_gemm_mfma_decode(dtype, x, wp, out, M, N, K, epilogue, split, st);
-    if (kernel == KERNEL_BIG) return launch_gemm_mfma_big(dtype, x, wp, out, M, N, K, epilogue, split, variant == 3 ? 8 : (variant == 4 ? 4 : (variant == 5 ? 5 : (variant == 7 ? 14 : (variant == 8 ? 15 : (variant == 9 ? 18 : 0))))), epi, st);
+    if (kernel == KERNEL_BIG) return launch_gemm_mfma_big(dtype, x, wp, out, M, N, K, epilogue, split, variant == 3 ? 8 : (variant == 4 ? 4 : (variant == 5 ? 5 : (variant == 7 ? 14 : (variant == 8 ? 15 : (variant == 9 ? 18 : (variant == 10 ? 24 : 0)))))), epi, st);
     return dtype == FG_BF16 ? launch_gemm_typed<bf16_t>(x, wp, out, M, N, K, epilogue, split, st)
                             : launch_gemm_typed<f16_t>(x, wp, out, M, N, K, epilogue, split, st);
 }

@@ -279,8 +279,8 @@ __device__ __forceinline__ void epilogue_topk(f32x16_t (&acc)[MT][2], const Gemm
     }
 }
 
-// WA = waves of the block that own columns: 4, or 3 for launches that are weight streams (see plan_big): the block is
-// then 192 columns wide, and its fourth wave only brings its share of X and keeps the block's barriers.
+// WA = waves of the block that own columns: 4, or 3 or 2 for launches that are weight streams (see plan_big): the block
+// is then 192 or 128 columns wide, and its other waves only bring their share of X and keep the block's barriers.
 template <typename T, int MT, int EPI, int WA = 4>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 4 ? 2 : 1))) void gemm_mfma_big_kernel(const T *__restrict__ X, const uint4 *__restrict__ Wp,
                                                              void *__restrict__ out, int M, int N, int K, int chunks_per_split,
@@ -288,7 +288,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 4 ? 2
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the buffer-descriptor builtins exist in the device pass only
     constexpr int NT = 2, WN = 4, BM = MT * 32;
-    static_assert(WA == 4 || (WA == 3 && (EPI == EPI_SLABS || EPI == EPI_SWIGLU)), "the narrower block has the barrier-free epilogues");
+    static_assert(WA == 4 || ((WA == 3 || WA == 2) && (EPI == EPI_SLABS || EPI == EPI_SWIGLU)), "the narrower blocks have the barrier-free epilogues");
     constexpr int STAGE_U4 = BM * 8;   // uint4 slots per stage: BM rows x 8 pieces
     // one variable per stage: the compiler orders LDS reads after direct-to-LDS loads per variable, so distinct
     // variables keep the reads of one stage from waiting on the loads in flight to the others
@@ -544,14 +544,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 4 ? 2
 // A launch of at most 256 blocks with one block per CU is a weight stream, and a CU draws about 32 GB/s from HBM
 // whatever it keeps in flight (gate/up in one row of 148 blocks: 55 - 64 us from 32 to 128 rows, the same with operands
 // four chunks ahead instead of two; the decode kernel's 198 blocks: 43 us): what counts is the number of CUs that
-// stream.  Such launches of a wide output therefore use blocks of 192 columns (wa = 3 column waves) when that still
-// gives one round: 198 blocks for the 7B-class gate/up.
+// stream.  Such launches of a wide output therefore use the narrowest blocks (128 or 192 columns: wa = 2 or 3 column
+// waves) that still give one round: 198 blocks for the 7B-class gate/up, 140 for the 1.5B-class one.
 struct BigPlan { int split, mt, wa; };
 static bool tall_blocks_ok(int epilogue) { return epilogue != EPI_RESIDUAL && epilogue != EPI_TOPK; }
 static int column_waves(int M, int N, int mt, int split, int epilogue)
 {
     if (N < 16384 || split != 1 || (epilogue != EPI_SLABS && epilogue != EPI_SWIGLU) || M > 32 * mt) return 4;
-    return (N / 32 + 5) / 6 <= 256 ? 3 : 4;
+    for (int wa = 2; wa < 4; wa++)   // the narrowest block that still gives one round
+        if ((N / 32 + 2 * wa - 1) / (2 * wa) <= 256) return wa;
+    return 4;
+}
+// Blocks of the launch for one row block of a wide output (what the kernel choice looks at).
+int gemm_mfma_big_stream_blocks(int N, int epilogue)
+{
+    const int wa = column_waves(1, N, 4, 1, epilogue);
+    return (N / 32 + 2 * wa - 1) / (2 * wa);
 }
 static int wide_height(int M, int n_bands)
 {
@@ -621,10 +629,12 @@ static void launch_big_typed(const void *x, const void *wp, void *out, int M, in
     switch (epilogue) {
     case EPI_SLABS:
         if (wa == 3) FG_BIG_LAUNCH_K(T, MT, EPI_SLABS, 3);
+        else if (wa == 2) FG_BIG_LAUNCH_K(T, MT, EPI_SLABS, 2);
         else FG_BIG_LAUNCH(EPI_SLABS);
         break;
     case EPI_SWIGLU:
         if (wa == 3) FG_BIG_LAUNCH_K(T, MT, EPI_SWIGLU, 3);
+        else if (wa == 2) FG_BIG_LAUNCH_K(T, MT, EPI_SWIGLU, 2);
         else FG_BIG_LAUNCH(EPI_SWIGLU);
         break;
     case EPI_ROPE: FG_BIG_LAUNCH(EPI_ROPE); break;
@@ -641,14 +651,14 @@ static void launch_big_typed(const void *x, const void *wp, void *out, int M, in
 
 // Shapes were validated by the caller (launch_gemm_mfma); M * K < 2^30 is needed by the 32-bit byte offsets.
 // fixed_mt: 0 = the plan's block height and width, else 8, 5 or 4 (row tiles of 32 per block) with 256-column blocks,
-// or 18, 15, 14 = the same heights with 192-column blocks (partial-sum and SwiGLU epilogues).
+// or 18, 15, 14 / 24 = the same heights with 192- / 128-column blocks (partial-sum and SwiGLU epilogues).
 int32_t launch_gemm_mfma_big(int32_t dtype, const void *x, const void *wp, void *out, int M, int N, int K, int epilogue,
                              int split, int fixed_mt, const GemmEpi *epi, hipStream_t st)
 {
-    const int fixed_wa = fixed_mt == 0 ? 0 : (fixed_mt > 10 ? 3 : 4);
-    if (fixed_mt > 10) fixed_mt -= 10;
-    if (fixed_wa == 3 && epilogue != EPI_SLABS && epilogue != EPI_SWIGLU)
-        return fail(FG_ERR_INVALID_ARG, "192-column blocks have the partial-sum and SwiGLU epilogues only (got %d)", epilogue);
+    const int fixed_wa = fixed_mt == 0 ? 0 : (fixed_mt > 20 ? 2 : (fixed_mt > 10 ? 3 : 4));
+    fixed_mt %= 10;
+    if (fixed_wa && fixed_wa < 4 && epilogue != EPI_SLABS && epilogue != EPI_SWIGLU)
+        return fail(FG_ERR_INVALID_ARG, "128- and 192-column blocks have the partial-sum and SwiGLU epilogues only (got %d)", epilogue);
     if ((int64_t)M * K >= (1LL << 30)) return fail(FG_ERR_SHAPE, "GEMM input of %d x %d exceeds 2^30 elements", M, K);
     if (epilogue >= EPI_ROPE && split != 1) return fail(FG_ERR_INVALID_ARG, "fused GEMM epilogue %d cannot run with a k split", epilogue);
     if (epilogue > EPI_TOPK) return fail(FG_ERR_UNIMPLEMENTED, "GEMM epilogue %d", epilogue);
