@@ -805,11 +805,14 @@ def sweep(args):
         wl = Workload("b8", args.dtype, B=B, N=N, verbose=True)
         t_verify, _ = time_steps(torch, wl.verify_only, max(3, args.steps // 2), args.warmup)
         t_step, emitted = time_steps(torch, wl.step, args.steps, args.warmup)
+        # the same round with its device side replayed as a HIP graph (small batches are launch-bound in the drafting steps)
+        t_graph, emitted_g = time_steps(torch, wl.step_graph, args.steps, args.warmup)
         acct = model_bytes_flops(wl.model, B * N, wl.lengths.astype(np.float64), N)
         points.append(dict(B=B, N=N, K_draft=K, L_draft=L, round_ms=t_step * 1e3, verify_ms=t_verify * 1e3,
                            accepted_tokens_per_s=emitted / t_step, tau=emitted / B,
+                           graph_round_ms=t_graph * 1e3, graph_accepted_tokens_per_s=emitted_g / t_graph,
                            step_hbm_frac=acct["bytes"] / t_verify / PEAK_HBM, step_mfma_frac=acct["flops"] / t_verify / PEAK_MFMA))
-        print(f"# B={B} N={N} K={K} L={L}: round {t_step * 1e3:.2f} ms, verify {t_verify * 1e3:.2f} ms, "
+        print(f"# B={B} N={N} K={K} L={L}: round {t_step * 1e3:.2f} ms ({t_graph * 1e3:.2f} replayed), verify {t_verify * 1e3:.2f} ms, "
               f"{emitted / t_step:.0f} tokens/s", file=sys.stderr, flush=True)
         del wl
         gc.collect()
