@@ -562,6 +562,15 @@ def ceilings(args):
         l2[f"{per_cu}_blocks_per_cu"] = dict(aggregate_GBps=blocks * 256 * (1 << 20) / t / 1e9, per_cu_GBps=blocks * (1 << 20) / t / 1e9)
     out["l2_to_l1_stream"] = l2
     out["l2_to_l1_best_per_cu_GBps"] = max(v["per_cu_GBps"] for v in l2.values())
+    # what one CU draws from HBM: at most one block per CU, each streaming its own slice with 4 ... 32 loads per lane in
+    # flight (4 ... 32 KiB per wave); a launch with fewer blocks than CUs is bound by this times its block count
+    one = {}
+    for blocks in (64, 128, 198, 256):
+        for mode, depth in ((4, 8), (5, 16), (6, 32)):
+            used = nbytes // blocks // (4096 * depth) * (4096 * depth) * blocks
+            t = timed(lambda: fg.fg_probe_read(src, mode, blocks, sink), 3)
+            one[f"{blocks}_blocks_{depth}_in_flight"] = dict(aggregate_GBps=used / t / 1e9, per_block_GBps=used / t / 1e9 / blocks)
+    out["hbm_read_one_block_per_cu"] = one
     copies = {}
     half = src[:nbytes // 2]
     for blocks in (2048, 4096, 8192, 16384):

@@ -418,6 +418,8 @@ int32_t fg_model_profile_read(fg_model *m, double *ms, int32_t *launches);
  *   in a hashed order, one page per wave at a time (the pattern of a paged KV cache; bytes a power of two); 3: EVERY
  *   block streams the whole region 256 times (bytes a power of two from 32 KiB to 64 MiB: choose it to fit in L2 and
  *   not in a 32 KiB L1), eight loads in flight per lane -- blocks * 256 * bytes are read in all, as L2 -> L1 fills;
+ *   4 / 5 / 6: every block streams its own contiguous slice (bytes / blocks, rounded down to whole rounds) with 8 / 16 /
+ *   32 non-temporal loads per lane in flight -- with at most one block per CU, what a single CU draws from HBM;
  *   sink: device, blocks * 4 bytes (written only on a magic checksum).
  * fg_probe_copy: the same stream written to dst (the plain copy whose FETCH_SIZE / WRITE_SIZE counter readings scale
  *   the traffic figures of the other kernels).

@@ -937,7 +937,7 @@ int32_t fg_model_profile_read(fg_model *m, double *ms, int32_t *launches)
 
 int32_t fg_probe_read(const void *src, int64_t bytes, int32_t nontemporal, int32_t blocks, void *sink, void *stream)
 {
-    if (!src || !sink || bytes < 16 || bytes % 16 || blocks < 1 || nontemporal < 0 || nontemporal > 3)
+    if (!src || !sink || bytes < 16 || bytes % 16 || blocks < 1 || nontemporal < 0 || nontemporal > 6)
         return fail(FG_ERR_INVALID_ARG, "fg_probe_read: bad argument");
     if (nontemporal == 3 && (bytes < 32768 || bytes > (64 << 20) || (bytes & (bytes - 1))))
         return fail(FG_ERR_INVALID_ARG, "fg_probe_read: the L2-resident pattern needs a power-of-two size of 32 KiB to 64 MiB");

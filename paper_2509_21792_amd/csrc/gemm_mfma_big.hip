@@ -542,8 +542,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MT == 4 ? 2
 // at 2048; 886 / - / 927 at 4096.
 // The residual and top-k epilogues exist for 128- and 160-row blocks only: with 256 accumulator registers per lane the
 // extra live values of those epilogues (the tile of h, the selection's scratch) do not fit and the compiler spills.
-// A launch of at most 256 blocks with one block per CU is a weight stream, and a CU draws about 32 GB/s from HBM
-// whatever it keeps in flight (gate/up in one row of 148 blocks: 55 - 64 us from 32 to 128 rows, the same with operands
+// A launch of at most 256 blocks with one block per CU is a weight stream, and a CU draws a bounded rate from HBM
+// whatever it keeps in flight -- 47 - 55 GB/s in a pure read stream with 32 KiB in flight as with 128, about 30 here (gate/up in one row of 148 blocks: 55 - 64 us from 32 to 128 rows, the same with operands
 // four chunks ahead instead of two; the decode kernel's 198 blocks: 43 us): what counts is the number of CUs that
 // stream.  Such launches of a wide output therefore use the narrowest blocks (128 or 192 columns: wa = 2 or 3 column
 // waves) that still give one round: 198 blocks for the 7B-class gate/up, 140 for the 1.5B-class one.

@@ -6,6 +6,7 @@
 //   copy    the same stream, written back: the plain copy whose FETCH_SIZE / WRITE_SIZE readings scale the HBM
 //           traffic counters of the other kernels
 //   read, L2-resident   every block streams one small region many times: the L2 -> L1 fill rate of a CU
+//   read, deep          one contiguous slice per block with 8 - 32 loads per lane in flight: what a single CU draws from HBM
 //   mfma    a register-resident loop of v_mfma_f32_32x32x16_{bf16,f16}: operands stay in registers, four independent
 //           accumulator tiles per wave, no memory traffic in the loop
 #include "fg_common.h"
@@ -140,6 +141,30 @@ __global__ __launch_bounds__(256) void probe_read_l2_kernel(const uint4 *__restr
 
 constexpr int PROBE_L2_PASSES = 256;
 
+// What one block draws from HBM when it keeps DEPTH 16-byte loads per lane in flight (DEPTH x 4 KiB per block): the
+// blocks take contiguous slices of the buffer, so with at most one block per CU the rate per block is the rate per CU.
+// It levels off far below the L2 -> L1 rate: a launch of fewer blocks than CUs is bound by how many CUs stream.
+template <int DEPTH>
+__global__ __launch_bounds__(256) void probe_read_deep_kernel(const uint4 *__restrict__ src, int64_t vec_per_block, uint32_t *sink)
+{
+    const uint4 *p = src + (int64_t)blockIdx.x * vec_per_block + threadIdx.x;
+    const int64_t steps = vec_per_block / 256;   // a multiple of DEPTH (the host rounds the slice down)
+    uint32_t acc = 0;
+    probe_u32x4_t v[DEPTH];
+#pragma unroll
+    for (int d = 0; d < DEPTH; d++) v[d] = __builtin_nontemporal_load(reinterpret_cast<const probe_u32x4_t *>(p + (int64_t)d * 256));
+    for (int64_t s0 = DEPTH; s0 < steps; s0 += DEPTH) {
+#pragma unroll
+        for (int d = 0; d < DEPTH; d++) {   // slot d is consumed and refilled: DEPTH - 1 loads stay in flight
+            acc ^= v[d].x ^ v[d].y ^ v[d].z ^ v[d].w;
+            v[d] = __builtin_nontemporal_load(reinterpret_cast<const probe_u32x4_t *>(p + (s0 + d) * 256));
+        }
+    }
+#pragma unroll
+    for (int d = 0; d < DEPTH; d++) acc ^= v[d].x ^ v[d].y ^ v[d].z ^ v[d].w;
+    if (acc == 0x9e3779b9u && threadIdx.x == 0) sink[blockIdx.x] = acc;
+}
+
 int32_t launch_probe_read(const void *src, int64_t bytes, int nontemporal, int blocks, void *sink, hipStream_t st)
 {
     const int64_t n_vec = bytes / 16;
@@ -147,6 +172,16 @@ int32_t launch_probe_read(const void *src, int64_t bytes, int nontemporal, int b
         hipLaunchKernelGGL(probe_read_l2_kernel, dim3(blocks), dim3(256), 0, st, (const uint4 *)src, (int)n_vec, PROBE_L2_PASSES,
                            (uint32_t *)sink);
         FG_LAUNCH_CHECK("probe_read_l2");
+        return FG_OK;
+    }
+    if (nontemporal >= 4) {   // contiguous slice per block, 8 / 16 / 32 loads per lane in flight
+        const int depth = nontemporal == 4 ? 8 : (nontemporal == 5 ? 16 : 32);
+        const int64_t per_block = n_vec / blocks / (256 * depth) * (256 * depth);
+        if (per_block < 256 * depth) return fail(FG_ERR_INVALID_ARG, "fg_probe_read: buffer too small for %d blocks of this depth", blocks);
+        if (depth == 8) hipLaunchKernelGGL(probe_read_deep_kernel<8>, dim3(blocks), dim3(256), 0, st, (const uint4 *)src, per_block, (uint32_t *)sink);
+        else if (depth == 16) hipLaunchKernelGGL(probe_read_deep_kernel<16>, dim3(blocks), dim3(256), 0, st, (const uint4 *)src, per_block, (uint32_t *)sink);
+        else hipLaunchKernelGGL(probe_read_deep_kernel<32>, dim3(blocks), dim3(256), 0, st, (const uint4 *)src, per_block, (uint32_t *)sink);
+        FG_LAUNCH_CHECK("probe_read_deep");
         return FG_OK;
     }
     if (nontemporal == 2) {   // scattered 4 KiB pages; the caller checked that bytes is a power of two

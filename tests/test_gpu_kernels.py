@@ -330,3 +330,23 @@ def test_decode_gemm_rejects_shapes_it_does_not_take(fg):
     h = torch.zeros((8, 32), dtype=torch.float32, device="cuda")
     with pytest.raises(fg.FgError):
         fg.fg_gemm(1, x[:8], w, 32, epilogue=3, out=h, variant=6)  # no residual epilogue
+
+
+def test_ceiling_probes_run_and_reject_bad_shapes(fg):
+    """The measurement probes of bench.py --ceilings (no part of the method): every read pattern, the copy and the MFMA loop
+    launch on small buffers, the copy copies, and shapes a pattern cannot take are errors, not launches."""
+    src = torch.randint(0, 255, (8 << 20,), dtype=torch.uint8, device="cuda")
+    dst = torch.zeros_like(src)
+    sink = torch.zeros(1 << 16, dtype=torch.float32, device="cuda")
+    for mode in range(7):
+        fg.fg_probe_read(src, mode, 64, sink)
+    fg.fg_probe_copy(src, dst, 64)
+    fg.fg_probe_mfma(fg.FG_BF16, 4, True, 8, sink)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    with pytest.raises(fg.FgError):
+        fg.fg_probe_read(src[:4096], 6, 64, sink)      # 64 slices of 32 loads per lane do not fit 4 KiB
+    with pytest.raises(fg.FgError):
+        fg.fg_probe_read(src[:3 << 20], 3, 64, sink)    # the L2-resident pattern wants a power-of-two size
+    with pytest.raises(fg.FgError):
+        fg.fg_probe_read(src, 7, 64, sink)
