@@ -224,6 +224,9 @@ def ref_attention(q, k, v, L, parent, n_prev, Hq, Hkv, hd):
     ("bf16", 28, 4, 128, 2, 4, 8, (77, 640)),
     ("bf16", 28, 4, 128, 9, 1, 0, (1, 16, 17, 255, 256, 257, 1023, 2000, 0)),
     ("bf16", 28, 4, 128, 2, 64, 0, (128, 50)),
+    # batches large enough for the four-tiles-per-wave plan (1024 (sequence, kv head, wave) triples): one wave and three
+    ("fp16", 28, 4, 128, 256, 8, 0, (40, 17, 64, 100) * 64),
+    ("bf16", 28, 4, 128, 96, 24, 0, (20, 50, 33) * 32),
 ])
 def test_tree_attention(fg, dtype, Hq, Hkv, hd, B, N, n_prev, lens):
     from synth import gen
