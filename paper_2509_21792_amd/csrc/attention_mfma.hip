@@ -14,7 +14,10 @@
 // and the cache keeps K pages in that fragment order, so that every K load of a wave is one contiguous KiB.
 // Measured and set aside: K / V of two steps in flight through LDS stages (direct-to-LDS buffer loads, query
 // fragments back in registers) instead of one step in a second register set: 305 against 291 us per layer at
-// B = 256, N = 8 -- the kernel is not short of bytes in flight.  Chunks write (m, l, O) partials; a merge kernel
+// B = 256, N = 8.  A later attempt kept V in two alternating register sets and sent only K two steps ahead through
+// two LDS stages (one variable each): parity-exact and slower again, 9.0 against 7.1 ms per verify step -- the compiler
+// orders every LDS read, the per-step reads of the parked Q fragments included, behind all direct-to-LDS loads still in
+// flight, so each step starts by waiting for the K loads it has just issued.  Chunks write (m, l, O) partials; a merge kernel
 // combines them.  Key positions >= committed length are in-round nodes and are masked per query row with the
 // node's 64-bit ancestor set.
 #include <stdlib.h>
