@@ -146,3 +146,30 @@ def test_workspace_bound_covers_every_call_shape(model_name, max_rows, cap):
     for B, N in ((32, 5), (16, 3), (32, 44), (64, 10)):
         if B * N <= max_rows:
             assert fg.binding.fg_step_workspace_bytes(cfg, False, B, N, cap) <= fg.binding.fg_workspace_bytes_for(cfg, False, B * N, cap)
+
+
+@pytest.mark.parametrize("M,n_out,n_in,epilogue,kernel", [
+    # 7B-class gate/up with SwiGLU: decode kernel, few-row kernel, then the pipelined kernel from 32 rows on
+    (8, 37888, 3584, 1, "gemm_mfma_decode_kernel"), (16, 37888, 3584, 1, "gemm_mfma_decode_kernel"),
+    (24, 37888, 3584, 1, "gemm_mfma_skinny_kernel"), (32, 37888, 3584, 1, "gemm_mfma_big_kernel"),
+    (128, 37888, 3584, 1, "gemm_mfma_big_kernel"), (2048, 37888, 3584, 1, "gemm_mfma_big_kernel"),
+    # 1.5B-class gate/up: too few blocks for the pipelined kernel up to 64 rows
+    (48, 17920, 1536, 1, "gemm_mfma_skinny_kernel"), (64, 17920, 1536, 1, "gemm_mfma_skinny_kernel"),
+    (96, 17920, 1536, 1, "gemm_mfma_big_kernel"),
+    # narrow outputs: few-row up to 64 rows, up to 128 for short contractions
+    (8, 3584, 18944, 0, "gemm_mfma_skinny_kernel"), (64, 3584, 18944, 0, "gemm_mfma_skinny_kernel"),
+    (96, 3584, 18944, 0, "gemm_mfma_big_kernel"), (96, 4608, 3584, 0, "gemm_mfma_skinny_kernel"),
+    (128, 3584, 3584, 0, "gemm_mfma_skinny_kernel"), (144, 4608, 3584, 0, "gemm_mfma_big_kernel"),
+    # LM head: few-row, streaming at 33 - 64 rows, pipelined above
+    (8, 152064, 3584, 0, "gemm_mfma_skinny_kernel"), (32, 152064, 3584, 0, "gemm_mfma_skinny_kernel"),
+    (48, 152064, 3584, 0, "gemm_mfma_kernel"), (64, 152064, 3584, 0, "gemm_mfma_kernel"),
+    (96, 152064, 3584, 0, "gemm_mfma_big_kernel"),
+    # fused epilogues exist in the pipelined kernel only
+    (2048, 3584, 18944, 3, "gemm_mfma_big_kernel"),
+])
+def test_gemm_kernel_choice_at_the_measured_shapes(L, M, n_out, n_in, epilogue, kernel):
+    """fg_gemm_kernel_name (host-only): the kernel the library picks at the row counts where its measurements put the
+    switch points, for the 7B-class and 1.5B-class matrices -- a guard against an edit of one threshold moving another."""
+    L.fg_gemm_kernel_name.restype = C.c_char_p
+    L.fg_gemm_kernel_name.argtypes = [C.c_int32] * 4
+    assert L.fg_gemm_kernel_name(M, n_out, n_in, epilogue).decode() == kernel
