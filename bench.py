@@ -624,7 +624,7 @@ def main():
     ap.add_argument("--attention", action="store_true", help="time the tree attention of one layer on the workload's cache and exit")
     ap.add_argument("--rows", type=int, default=2048, help="--gemm: rows M")
     ap.add_argument("--reps", type=int, default=56, help="--gemm: timed launches")
-    ap.add_argument("--variant", type=int, default=0, help="--gemm: 0 = the library's kernel choice, 1-12 force one (see fastgrpo.h)")
+    ap.add_argument("--variant", type=int, default=0, help="--gemm: 0 = the library's kernel choice, 1-14 force one (see fastgrpo.h)")
     ap.add_argument("--split", type=int, default=0, help="--gemm: k splits of the partial-sum epilogue (0 = the library's choice)")
     ap.add_argument("--cycle", type=int, default=8, help="--gemm: number of different weight matrices used in turn")
     ap.add_argument("--train", default="", choices=["", "bf16", "fp32"],

@@ -371,7 +371,7 @@ int32_t fg_draft_adamw(const fg_model_cfg *cfg, fg_draft_params *w, const fg_dra
  *               rows, epilogues 0 and 1), 7 / 8 / 9 = pipelined kernel with 128- / 160- / 256-row blocks of 192 columns instead of
  *               256, 10 = 128-row blocks of 128 columns (epilogues 0 and 1; variant 0 runs the narrowest of these that
  *               gives at most 256 blocks for one row block of a wide output), 11 / 12 = 192-row blocks of 256 / 192
- *               columns (epilogues 0 and 1).  16-bit dtypes only.
+ *               columns, 13 / 14 = 224-row blocks of 256 / 192 columns (epilogues 0 and 1).  16-bit dtypes only.
  * fg_gemm_kernel_name: the kernel the library picks for a 16-bit GEMM of this shape and epilogue (a static string).
  * fg_attention: tree attention of already-rotated queries q [B*N, Hq*hd] (dtype) over the cache, which must
  *   already hold the in-round nodes' K/V; out [B*N, Hq*hd] (dtype).

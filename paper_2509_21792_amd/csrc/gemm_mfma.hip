@@ -299,7 +299,7 @@ int32_t launch_gemm_mfma(int32_t dtype, const void *x, const void *wp, void *out
     if (N % 32 || K % 64) return fail(FG_ERR_SHAPE, "16-bit GEMM needs n_out %% 32 == 0 and n_in %% 64 == 0 (got %d, %d)", N, K);
     if (epilogue == EPI_SWIGLU && (N % 64)) return fail(FG_ERR_SHAPE, "gate/up GEMM needs n_out %% 64 == 0");
     if ((int64_t)M * N >= (1LL << 31)) return fail(FG_ERR_SHAPE, "GEMM output of %d x %d exceeds 2^31 elements", M, N);
-    if (variant < 0 || variant > 12) return fail(FG_ERR_INVALID_ARG, "unknown GEMM variant %d", variant);
+    if (variant < 0 || variant > 14) return fail(FG_ERR_INVALID_ARG, "unknown GEMM variant %d", variant);
     const int kernel = variant ? kernel_of_variant(variant) : kernel_for(M, N, K, epilogue);
     if (epilogue >= EPI_ROPE && kernel != KERNEL_BIG) return fail(FG_ERR_INVALID_ARG, "GEMM epilogue %d exists in the pipelined kernel only", epilogue);
     if (kernel == KERNEL_FEW && M > 512) return fail(FG_ERR_SHAPE, "the few-row kernel takes at most 512 rows (got %d)", M);
@@ -319,7 +319,7 @@ int32_t launch_gemm_mfma(int32_t dtype, const void *x, const void *wp, void *out
     if (split_used) *split_used = split;
     if (kernel == KERNEL_FEW) return launch_gemm_mfma_skinny(dtype, x, wp, out, M, N, K, epilogue, split, st);
     if (kernel == KERNEL_DECODE) return launch_gemm_mfma_decode(dtype, x, wp, out, M, N, K, epilogue, split, st);
-    if (kernel == KERNEL_BIG) return launch_gemm_mfma_big(dtype, x, wp, out, M, N, K, epilogue, split, variant == 3 ? 8 : (variant == 4 ? 4 : (variant == 5 ? 5 : (variant == 7 ? 14 : (variant == 8 ? 15 : (variant == 9 ? 18 : (variant == 10 ? 24 : (variant == 11 ? 6 : (variant == 12 ? 16 : 0)))))))), epi, st);
+    if (kernel == KERNEL_BIG) return launch_gemm_mfma_big(dtype, x, wp, out, M, N, K, epilogue, split, variant == 3 ? 8 : (variant == 4 ? 4 : (variant == 5 ? 5 : (variant == 7 ? 14 : (variant == 8 ? 15 : (variant == 9 ? 18 : (variant == 10 ? 24 : (variant == 11 ? 6 : (variant == 12 ? 16 : (variant == 13 ? 7 : (variant == 14 ? 17 : 0)))))))))), epi, st);
     return dtype == FG_BF16 ? launch_gemm_typed<bf16_t>(x, wp, out, M, N, K, epilogue, split, st)
                             : launch_gemm_typed<f16_t>(x, wp, out, M, N, K, epilogue, split, st);
 }

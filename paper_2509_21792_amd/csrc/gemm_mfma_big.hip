@@ -1,5 +1,6 @@
 // Compute-bound shape of the 16-bit MFMA GEMM (more than 256 rows): out = X . W^T on (32 MT) x 256 tiles, MT = 8, 5 or 4
-// (6 for one row block of 161 - 192 rows of a wide output: 67 against 80 us for the 7B-class gate/up at 192 rows).
+// (6 / 7 for one row block of 161 - 192 / 193 - 224 rows of a wide output: 67 against 80 us for the 7B-class gate/up at
+// 192 rows).
 //
 // Block = 4 waves side by side, each owning 32 MT rows x 64 columns (MT x 2 tiles of v_mfma_f32_32x32x16).  MT = 8
 // fills the register file with one wave per SIMD, so nothing hides a stall and both operands are requested two
@@ -564,12 +565,13 @@ int gemm_mfma_big_stream_blocks(int N, int epilogue)
 }
 static int wide_height(int M, int n_bands)
 {
-    static const int heights[4] = {8, 6, 5, 4};
-    static const double per_block[4] = {1.0, 1.05 * 6 / 8, 1.08 * 5 / 8, 1.17 * 4 / 8};
+    static const int heights[5] = {8, 7, 6, 5, 4};
+    static const double per_block[5] = {1.0, 1.03 * 7 / 8, 1.05 * 6 / 8, 1.08 * 5 / 8, 1.17 * 4 / 8};
     int best = 8;
     double best_cost = 1e30;
-    for (int i = 0; i < 4; i++) {
-        if (heights[i] == 6 && M > 192) continue;   // 192-row blocks: built for one row block of 161 - 192 rows only
+    for (int i = 0; i < 5; i++) {
+        // 224- and 192-row blocks: built for one row block of 193 - 224 / 161 - 192 rows only
+        if ((heights[i] == 7 && M > 224) || (heights[i] == 6 && M > 192)) continue;
         const long tiles = (long)n_bands * ((M + 32 * heights[i] - 1) / (32 * heights[i]));
         // over several rounds a 160-row block costs 19 % more per row than a 256-row one, not 8 (1792 rows: 450 us in
         // seven rounds of 160-row blocks against 432 in five of 256-row ones)
@@ -586,9 +588,9 @@ static BigPlan plan_big(int M, int N, int K, int fixed_split, int fixed_mt, int 
     if (N >= 16384 && fixed_mt <= 0) fixed_mt = tall_blocks_ok(epilogue) ? wide_height(M, n_bands) : 4;
     BigPlan best{fixed_split > 0 ? fixed_split : 1, fixed_mt > 0 ? fixed_mt : 8, 4};
     double best_cost = 1e30;
-    static const int heights[4] = {8, 6, 5, 4};
+    static const int heights[5] = {8, 7, 6, 5, 4};
     for (int mt : heights) {
-        if ((fixed_mt > 0 && mt != fixed_mt) || (mt == 6 && fixed_mt != 6)) continue;
+        if ((fixed_mt > 0 && mt != fixed_mt) || ((mt == 6 || mt == 7) && fixed_mt != mt)) continue;
         if (mt == 8 && !tall_blocks_ok(epilogue)) continue;
         const int row_blocks = (M + 32 * mt - 1) / (32 * mt);
         const int s_max = row_blocks == 1 ? 16 : 8;   // one row block: the slabs are small, the grid needs the splits
@@ -643,10 +645,10 @@ static void launch_big_typed(const void *x, const void *wp, void *out, int M, in
         else FG_BIG_LAUNCH(EPI_SWIGLU);
         break;
     case EPI_ROPE:
-        if constexpr (MT != 6) FG_BIG_LAUNCH(EPI_ROPE);
+        if constexpr (MT != 6 && MT != 7) FG_BIG_LAUNCH(EPI_ROPE);
         break;
     default:
-        if constexpr (MT != 8 && MT != 6) {   // the plan never pairs these epilogues with 256- or 192-row blocks
+        if constexpr (MT != 8 && MT != 7 && MT != 6) {   // the plan never pairs these epilogues with 256-, 224- or 192-row blocks
             if (epilogue == EPI_TOPK) FG_BIG_LAUNCH(EPI_TOPK);
             else FG_BIG_LAUNCH(EPI_RESIDUAL);
         }
@@ -657,8 +659,8 @@ static void launch_big_typed(const void *x, const void *wp, void *out, int M, in
 }
 
 // Shapes were validated by the caller (launch_gemm_mfma); M * K < 2^30 is needed by the 32-bit byte offsets.
-// fixed_mt: 0 = the plan's block height and width, else 8, 6, 5 or 4 (row tiles of 32 per block) with 256-column blocks,
-// or 18, 16, 15, 14 / 24 = the same heights with 192- / 128-column blocks (partial-sum and SwiGLU epilogues).
+// fixed_mt: 0 = the plan's block height and width, else 8, 7, 6, 5 or 4 (row tiles of 32 per block) with 256-column blocks,
+// or 18, 17, 16, 15, 14 / 24 = the same heights with 192- / 128-column blocks (partial-sum and SwiGLU epilogues).
 int32_t launch_gemm_mfma_big(int32_t dtype, const void *x, const void *wp, void *out, int M, int N, int K, int epilogue,
                              int split, int fixed_mt, const GemmEpi *epi, hipStream_t st)
 {
@@ -675,14 +677,15 @@ int32_t launch_gemm_mfma_big(int32_t dtype, const void *x, const void *wp, void 
     if (epilogue == EPI_ROPE && (epi->hd != 64 && epi->hd != 128)) return fail(FG_ERR_SHAPE, "RoPE epilogue needs head_dim 64 or 128");
     if (epilogue == EPI_ROPE && ((int64_t)M * epi->Hq * epi->hd >= (1LL << 30) || (int64_t)epi->max_pos * epi->hd >= (1LL << 28)))
         return fail(FG_ERR_SHAPE, "RoPE epilogue: q output or rotation table beyond its 32-bit byte offsets");
-    if (fixed_mt == 6 && epilogue != EPI_SLABS && epilogue != EPI_SWIGLU)
-        return fail(FG_ERR_INVALID_ARG, "192-row blocks have the partial-sum and SwiGLU epilogues only (got %d)", epilogue);
+    if ((fixed_mt == 6 || fixed_mt == 7) && epilogue != EPI_SLABS && epilogue != EPI_SWIGLU)
+        return fail(FG_ERR_INVALID_ARG, "192- and 224-row blocks have the partial-sum and SwiGLU epilogues only (got %d)", epilogue);
     BigPlan p = plan_big(M, N, K, split, fixed_mt, epilogue);
     if (fixed_wa) p.wa = fixed_wa;
     const GemmEpi ep = epi ? *epi : GemmEpi();
 #define FG_BIG_MT(T)                                                                                   \
     do {                                                                                               \
         if (p.mt == 8) launch_big_typed<T, 8>(x, wp, out, M, N, K, epilogue, split, p.wa, ep, st);           \
+        else if (p.mt == 7) launch_big_typed<T, 7>(x, wp, out, M, N, K, epilogue, split, p.wa, ep, st);      \
         else if (p.mt == 6) launch_big_typed<T, 6>(x, wp, out, M, N, K, epilogue, split, p.wa, ep, st);      \
         else if (p.mt == 5) launch_big_typed<T, 5>(x, wp, out, M, N, K, epilogue, split, p.wa, ep, st);      \
         else launch_big_typed<T, 4>(x, wp, out, M, N, K, epilogue, split, p.wa, ep, st);                     \

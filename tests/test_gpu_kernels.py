@@ -118,11 +118,11 @@ def test_gemm_16bit_swiglu_epilogue(fg, M, F, K, dtype):
     assert (err <= 2 ** -8 * ref.abs() + 1e-3).all(), err.max().item()
 
 
-@pytest.mark.parametrize("variant", [3, 4, 5, 7, 8, 9, 10, 11, 12])
+@pytest.mark.parametrize("variant", [3, 4, 5, 7, 8, 9, 10, 11, 12, 13, 14])
 @pytest.mark.parametrize("chunks", [1, 2, 3, 4, 5, 6, 7, 13, 27])
 def test_gemm_16bit_pipelined_block_heights_and_residual_epilogue(fg, variant, chunks):
     """The pipelined kernel with 256-, 128- and 160-row blocks of 256 columns (3, 4, 5), of 192 columns (9, 7, 8), 128-row blocks
-    of 128 columns (10) and 192-row blocks of 256 / 192 columns (11, 12), where the waves without columns only stage X, forced through fg_gemm's variant: partial-sum slabs with and without a k split,
+    of 128 columns (10) 192-row blocks of 256 / 192 columns (11, 12) and 224-row blocks (13, 14), where the waves without columns only stage X, forced through fg_gemm's variant: partial-sum slabs with and without a k split,
     SwiGLU, and (256-column blocks) the residual epilogue (out += x . W^T in place), on ragged row blocks and a ragged
     last column band; the chunk counts run through every tail length of the main loop and of the staging wave's."""
     print(f"pipelined variant {variant} chunks={chunks}", flush=True)
