@@ -127,10 +127,11 @@ def test_config4_7b_high_concurrency_bf16(H, N):
     run_greedy_config(H, "cfg4", "bf16", n_sub=4, N=N)
 
 
-@pytest.mark.parametrize("N", [6, 20, 24])
+@pytest.mark.parametrize("N", [6, 20, 24, 28])
 def test_low_end_of_the_batch_range_7b(H, N):
-    """B = 8 of the metric's range at 48, 160 and 192 rows per step: the row counts at which gate/up runs as one row of
-    192-column blocks of the pipelined kernel (128, 160 and 192 rows tall) and the narrow projections change kernels."""
+    """B = 8 of the metric's range at 48, 160, 192 and 224 rows per step: the row counts at which gate/up runs as one row
+    of 192-column blocks of the pipelined kernel (128, 160, 192 and 224 rows tall) and the narrow projections change
+    kernels."""
     run_greedy_config(H, "b8", "fp16", n_sub=3, N=N)
 
 
